@@ -1,0 +1,14 @@
+"""MI355X-native mixed-precision stacked-LSTM training step.
+
+The work is done by hand-written gfx950 HIP kernels behind a C ABI
+(include/lstm_mi355.h).  This package is the thin ctypes binding with the same
+entry-point names plus buffer plumbing on torch device tensors.  There is no
+CPU fallback: importing `binding` fails loudly when the library is missing.
+"""
+from .binding import (  # noqa: F401
+    LstmConfig, OptimizerConfig, TrainingStep, load_library, library_path,
+    lstm_abi_version, lstm_last_error, lstm_param_count, lstm_param_offset, lstm_workspace_bytes,
+    lstm_forward, lstm_backward, grad_average, master_update, lr_schedule,
+    DTYPE_FP32, DTYPE_FP16, DTYPE_BF16, HEAD_STEP_BCE, HEAD_LAST_BCE, HEAD_STEP_MSE, OPT_SGD_MOMENTUM, OPT_ADAM,
+    LstmError,
+)

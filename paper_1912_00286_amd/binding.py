@@ -1,0 +1,199 @@
+"""ctypes binding of liblstm_mi355.so: argument marshalling only.
+
+Every function mirrors the C entry point of the same name in
+include/lstm_mi355.h.  Tensors are passed as raw device addresses
+(`tensor.data_ptr()`), the stream as torch's current HIP stream handle.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "liblstm_mi355.so"
+
+DTYPE_FP32, DTYPE_FP16, DTYPE_BF16 = 0, 1, 2
+HEAD_STEP_BCE, HEAD_LAST_BCE, HEAD_STEP_MSE = 1, 2, 3
+OPT_SGD_MOMENTUM, OPT_ADAM = 0, 1
+P_EMBED, P_W, P_U, P_B, P_HEAD_W, P_HEAD_B = 0, 1, 2, 3, 4, 5
+
+
+class LstmError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"lstm_mi355 status {status}: {text}")
+        self.status = status
+
+
+class LstmConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("num_layers", "input_dim", "hidden", "seq_len", "batch", "dtype", "head",
+                                         "out_dim", "vocab", "embed_dim")]
+
+
+class OptimizerConfig(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("momentum", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
+                ("eps", C.c_float), ("weight_decay", C.c_float), ("dynamic_scale", C.c_int32),
+                ("scale_backoff", C.c_float), ("scale_growth", C.c_float), ("growth_interval", C.c_int32)]
+
+
+def library_path() -> str:
+    return os.path.join(HERE, _LIB_NAME)
+
+
+_lib = None
+
+
+def load_library():
+    """Load the HIP library built in-tree.  No fallback: raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(there is no CPU fallback for the HIP path)")
+    lib = C.CDLL(path)
+    vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+    cfgp, optp = C.POINTER(LstmConfig), C.POINTER(OptimizerConfig)
+    lib.lstm_abi_version.restype = C.c_int
+    lib.lstm_last_error.restype = C.c_char_p
+    lib.lstm_param_count.argtypes = [cfgp, C.POINTER(i64)]
+    lib.lstm_param_offset.argtypes = [cfgp, i32, i32, C.POINTER(i64), C.POINTER(i64)]
+    lib.lstm_workspace_bytes.argtypes = [cfgp, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+    lib.lstm_forward.argtypes = [cfgp] + [vp] * 11
+    lib.lstm_backward.argtypes = [cfgp] + [vp] * 8
+    lib.grad_average.argtypes = [i64, i32, vp, i32, vp, vp, vp, vp]
+    lib.master_update.argtypes = [i64, optp, f32, i64, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
+    lib.lr_schedule.argtypes = [f32, i32, f32, f32, i32, f32, i64]
+    lib.lr_schedule.restype = f32
+    for name in ("lstm_param_count", "lstm_param_offset", "lstm_workspace_bytes", "lstm_forward", "lstm_backward",
+                 "grad_average", "master_update"):
+        getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _check(status: int):
+    if status != 0:
+        raise LstmError(status, lstm_last_error())
+
+
+def _ptr(t) -> Optional[int]:
+    """Device address of a torch tensor (None passes NULL); ints pass through."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def lstm_abi_version() -> int:
+    return load_library().lstm_abi_version()
+
+
+def lstm_last_error() -> str:
+    return load_library().lstm_last_error().decode()
+
+
+def lstm_param_count(cfg: LstmConfig) -> int:
+    n = C.c_int64()
+    _check(load_library().lstm_param_count(C.byref(cfg), C.byref(n)))
+    return n.value
+
+
+def lstm_param_offset(cfg: LstmConfig, kind: int, layer: int = 0):
+    off, cnt = C.c_int64(), C.c_int64()
+    _check(load_library().lstm_param_offset(C.byref(cfg), kind, layer, C.byref(off), C.byref(cnt)))
+    return off.value, cnt.value
+
+
+def lstm_workspace_bytes(cfg: LstmConfig):
+    r, s = C.c_size_t(), C.c_size_t()
+    _check(load_library().lstm_workspace_bytes(C.byref(cfg), C.byref(r), C.byref(s)))
+    return r.value, s.value
+
+
+def lstm_forward(cfg, params_lp, x, targets, h0, c0, reserve, scratch, loss, hT=None, cT=None, stream=None):
+    _check(load_library().lstm_forward(C.byref(cfg), _ptr(params_lp), _ptr(x), _ptr(targets), _ptr(h0), _ptr(c0),
+                                       _ptr(reserve), _ptr(scratch), _ptr(loss), _ptr(hT), _ptr(cT), _stream(stream)))
+
+
+def lstm_backward(cfg, params_lp, x, targets, reserve, scratch, loss_scale, grads_lp, stream=None):
+    _check(load_library().lstm_backward(C.byref(cfg), _ptr(params_lp), _ptr(x), _ptr(targets), _ptr(reserve),
+                                        _ptr(scratch), _ptr(loss_scale), _ptr(grads_lp), _stream(stream)))
+
+
+def grad_average(n_params, n_workers, grads_lp, dtype, loss_scale, avg_grad, found_inf, stream=None):
+    _check(load_library().grad_average(n_params, n_workers, _ptr(grads_lp), dtype, _ptr(loss_scale), _ptr(avg_grad),
+                                       _ptr(found_inf), _stream(stream)))
+
+
+def master_update(n_params, opt, lr, step, master, state1, state2, avg_grad, found_inf, loss_scale, good_steps,
+                  params_lp_out, dtype, stream=None):
+    _check(load_library().master_update(n_params, C.byref(opt), lr, step, _ptr(master), _ptr(state1), _ptr(state2),
+                                        _ptr(avg_grad), _ptr(found_inf), _ptr(loss_scale), _ptr(good_steps),
+                                        _ptr(params_lp_out), dtype, _stream(stream)))
+
+
+def lr_schedule(lr0, n_workers, n_half, eff_lr_max, warmup_steps, gamma, index) -> float:
+    return float(load_library().lr_schedule(lr0, n_workers, n_half, eff_lr_max, warmup_steps, gamma, index))
+
+
+# --------------------------------------------------------------------------
+# buffer plumbing for a whole training step (no arithmetic here)
+# --------------------------------------------------------------------------
+class TrainingStep:
+    """Owns the device buffers of one model and enqueues the entry points in
+    the order of the paper's iteration: per worker fprop + bprop, then the
+    gradient average, the schedule and the master update."""
+
+    def __init__(self, cfg: LstmConfig, opt: OptimizerConfig, n_workers: int, master_fp32, loss_scale: float,
+                 device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.cfg, self.opt, self.N = cfg, opt, int(n_workers)
+        self.dev = torch.device(device)
+        self.lp_dtype = {DTYPE_FP32: torch.float32, DTYPE_FP16: torch.float16, DTYPE_BF16: torch.bfloat16}[cfg.dtype]
+        self.P = lstm_param_count(cfg)
+        rb, sb = lstm_workspace_bytes(cfg)
+        self.master = torch.as_tensor(master_fp32, dtype=torch.float32).to(self.dev).contiguous()
+        assert self.master.numel() == self.P
+        self.params_lp = self.master.to(self.lp_dtype)          # storage cast only
+        self.state1 = torch.zeros(self.P, dtype=torch.float32, device=self.dev)
+        self.state2 = torch.zeros(self.P, dtype=torch.float32, device=self.dev) if opt.kind == OPT_ADAM else None
+        self.grads = torch.zeros((self.N, self.P), dtype=self.lp_dtype, device=self.dev)
+        self.avg = torch.zeros(self.P, dtype=torch.float32, device=self.dev)
+        self.reserve = torch.empty(rb, dtype=torch.uint8, device=self.dev)
+        self.scratch = torch.empty(sb, dtype=torch.uint8, device=self.dev)
+        self.losses = torch.zeros(self.N, dtype=torch.float32, device=self.dev)
+        self.loss_scale = torch.tensor([loss_scale], dtype=torch.float32, device=self.dev)
+        self.found_inf = torch.zeros(1, dtype=torch.int32, device=self.dev)
+        self.good_steps = torch.zeros(1, dtype=torch.int32, device=self.dev)
+        self.step_index = 0
+
+    def forward_backward(self, xs, ys):
+        """xs, ys: per-worker device tensors (x lp [T,B,I] or int32 ids; targets fp32)."""
+        for w in range(self.N):
+            lstm_forward(self.cfg, self.params_lp, xs[w], ys[w], None, None, self.reserve, self.scratch,
+                         self.losses[w:w + 1])
+            lstm_backward(self.cfg, self.params_lp, xs[w], ys[w], self.reserve, self.scratch, self.loss_scale,
+                          self.grads[w])
+
+    def update(self, lr: float):
+        grad_average(self.P, self.N, self.grads, self.cfg.dtype, self.loss_scale, self.avg, self.found_inf)
+        self.step_index += 1
+        master_update(self.P, self.opt, lr, self.step_index, self.master, self.state1, self.state2, self.avg,
+                      self.found_inf, self.loss_scale, self.good_steps, self.params_lp, self.cfg.dtype)
+
+    def step(self, xs, ys, lr: float):
+        self.forward_backward(xs, ys)
+        self.update(lr)

@@ -1,0 +1,409 @@
+// C ABI entry points for the forward and backward halves of the training
+// step, plus the layout bookkeeping (parameter offsets, workspace plan).
+// Host code only orchestrates: every arithmetic step runs in a HIP kernel.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include <vector>
+
+#include "kernels.h"
+
+namespace lstm {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+namespace {
+
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+// Everything derived from a config: parameter offsets (elements) and the byte
+// offsets of each region inside the caller's reserve and scratch buffers.
+struct Plan {
+    int L, H, T, B, G, dtype, head, V, D;
+    size_t es;                           // bytes per lp element
+    std::vector<int> in_dim;             // I_l
+    int64_t off_E = -1, off_wh = 0, off_bh = 0, P = 0;
+    std::vector<int64_t> off_W, off_U, off_b;
+    int head_rows = 0;                   // rows the head acts on (T*B or B)
+    // reserve
+    std::vector<size_t> r_gates, r_c, r_h;
+    size_t r_xemb = 0, r_dzu = 0, reserve_bytes = 0;
+    // scratch
+    size_t s_ax = 0, s_cstate = 0, s_losspart = 0;
+    size_t s_wT = 0, s_dA = 0, s_dAT = 0, s_xT = 0, s_dh[2] = {0, 0}, s_dhrec = 0, s_dcstate = 0, s_splitk = 0,
+           s_colpart = 0, s_dE32 = 0, scratch_bytes = 0;
+    std::vector<size_t> wT_off, uT_off;  // byte offsets inside the s_wT region
+    std::vector<int> split_w, split_u;
+};
+
+int make_plan(const lstm_config *c, Plan &p) {
+    if (!c) {
+        set_error("config is null");
+        return LSTM_ERR_INVALID;
+    }
+    if (c->num_layers < 1 || c->hidden < 1 || c->seq_len < 1 || c->batch < 1) {
+        set_error("config: num_layers, hidden, seq_len and batch must be >= 1");
+        return LSTM_ERR_INVALID;
+    }
+    if (c->dtype < LSTM_DTYPE_FP32 || c->dtype > LSTM_DTYPE_BF16) {
+        set_error("config: bad dtype %d", c->dtype);
+        return LSTM_ERR_INVALID;
+    }
+    if (c->head < LSTM_HEAD_STEP_BCE || c->head > LSTM_HEAD_STEP_MSE) {
+        set_error("config: bad head %d", c->head);
+        return LSTM_ERR_INVALID;
+    }
+    if (c->out_dim != 1) {
+        set_error("config: out_dim must be 1 (got %d)", c->out_dim);
+        return LSTM_ERR_UNSUPPORTED;
+    }
+    if (c->vocab < 0 || (c->vocab > 0 && c->embed_dim < 1) || (c->vocab == 0 && c->input_dim < 1)) {
+        set_error("config: need input_dim >= 1, or vocab > 0 with embed_dim >= 1");
+        return LSTM_ERR_INVALID;
+    }
+    const int64_t rows = (int64_t)c->seq_len * c->batch;
+    if (rows > (int64_t)65535 * 64 || (int64_t)c->hidden * 4 > (1 << 24) || c->num_layers > 4096) {
+        set_error("config: shape too large for this build (T*B=%lld, H=%d, L=%d)", (long long)rows, c->hidden, c->num_layers);
+        return LSTM_ERR_UNSUPPORTED;
+    }
+    p.L = c->num_layers; p.H = c->hidden; p.T = c->seq_len; p.B = c->batch; p.G = 4 * c->hidden;
+    p.dtype = c->dtype; p.head = c->head; p.V = c->vocab; p.D = c->vocab > 0 ? c->embed_dim : 0;
+    p.es = dtype_size(c->dtype);
+    const int I0 = c->vocab > 0 ? c->embed_dim : c->input_dim;
+    p.in_dim.assign(p.L, p.H);
+    p.in_dim[0] = I0;
+    // ---- parameters
+    int64_t off = 0;
+    if (p.V > 0) { p.off_E = 0; off += (int64_t)p.V * p.D; }
+    p.off_W.resize(p.L); p.off_U.resize(p.L); p.off_b.resize(p.L);
+    for (int l = 0; l < p.L; ++l) {
+        p.off_W[l] = off; off += (int64_t)p.G * p.in_dim[l];
+        p.off_U[l] = off; off += (int64_t)p.G * p.H;
+        p.off_b[l] = off; off += p.G;
+    }
+    p.off_wh = off; off += p.H;
+    p.off_bh = off; off += 1;
+    p.P = off;
+    p.head_rows = p.head == LSTM_HEAD_LAST_BCE ? p.B : p.T * p.B;
+    // ---- reserve
+    const size_t TB = (size_t)p.T * p.B;
+    size_t r = 0;
+    p.r_gates.resize(p.L); p.r_c.resize(p.L); p.r_h.resize(p.L);
+    for (int l = 0; l < p.L; ++l) {
+        p.r_gates[l] = r; r += align_up(TB * p.G * p.es);
+        p.r_c[l] = r; r += align_up((TB + p.B) * p.H * p.es);
+        p.r_h[l] = r; r += align_up((TB + p.B) * p.H * p.es);
+    }
+    p.r_xemb = r; if (p.V > 0) r += align_up(TB * p.D * p.es);
+    p.r_dzu = r; r += align_up((size_t)p.head_rows * 4);
+    p.reserve_bytes = r;
+    // ---- scratch
+    size_t s = 0;
+    int max_in = 0;
+    for (int l = 0; l < p.L; ++l) max_in = p.in_dim[l] > max_in ? p.in_dim[l] : max_in;
+    const int max_dim = max_in > p.H ? max_in : p.H;
+    p.s_ax = s; s += align_up(TB * p.G * 4);
+    p.s_cstate = s; s += align_up((size_t)p.B * p.H * 4);
+    p.s_losspart = s; s += align_up((size_t)head_loss_blocks(p.head_rows) * 4);
+    p.s_wT = s;
+    p.wT_off.resize(p.L); p.uT_off.resize(p.L);
+    for (int l = 0; l < p.L; ++l) {
+        p.wT_off[l] = s - p.s_wT; s += align_up((size_t)p.G * p.in_dim[l] * p.es);
+        p.uT_off[l] = s - p.s_wT; s += align_up((size_t)p.G * p.H * p.es);
+    }
+    p.s_dA = s; s += align_up(TB * p.G * p.es);
+    p.s_dAT = s; s += align_up(TB * p.G * p.es);
+    p.s_xT = s; s += align_up(TB * max_dim * p.es);
+    p.s_dh[0] = s; s += align_up(TB * max_dim * p.es);
+    p.s_dh[1] = s; s += align_up(TB * max_dim * p.es);
+    p.s_dhrec = s; s += align_up((size_t)p.B * p.H * 4);
+    p.s_dcstate = s; s += align_up((size_t)p.B * p.H * 4);
+    size_t splitk = 0;
+    p.split_w.resize(p.L); p.split_u.resize(p.L);
+    for (int l = 0; l < p.L; ++l) {
+        p.split_w[l] = gemm_pick_splits(p.G, p.in_dim[l], (int)TB);
+        p.split_u[l] = gemm_pick_splits(p.G, p.H, (int)TB);
+        size_t a = p.split_w[l] > 1 ? (size_t)p.split_w[l] * p.G * p.in_dim[l] * 4 : 0;
+        size_t b = p.split_u[l] > 1 ? (size_t)p.split_u[l] * p.G * p.H * 4 : 0;
+        splitk = a > splitk ? a : splitk;
+        splitk = b > splitk ? b : splitk;
+    }
+    p.s_splitk = s; s += align_up(splitk);
+    const int colw = p.G > p.H ? p.G : p.H;
+    p.s_colpart = s; s += align_up((size_t)colsum_chunks((int)TB) * colw * 4);
+    p.s_dE32 = s; if (p.V > 0) s += align_up((size_t)p.V * p.D * 4);
+    p.scratch_bytes = s;
+    return LSTM_OK;
+}
+
+inline char *at(void *base, size_t off) { return reinterpret_cast<char *>(base) + off; }
+inline const char *at(const void *base, size_t off) { return reinterpret_cast<const char *>(base) + off; }
+
+int check_ptr(const void *p, const char *name, bool required = true) {
+    if (!p) {
+        if (!required) return LSTM_OK;
+        set_error("%s is null", name);
+        return LSTM_ERR_INVALID;
+    }
+    if ((uintptr_t)p % 16 != 0) {
+        set_error("%s is not 16-byte aligned", name);
+        return LSTM_ERR_INVALID;
+    }
+    return LSTM_OK;
+}
+
+}  // namespace
+}  // namespace lstm
+
+using namespace lstm;
+
+extern "C" int lstm_abi_version(void) { return LSTM_ABI_VERSION; }
+
+extern "C" const char *lstm_last_error(void) { return g_err; }
+
+extern "C" int lstm_param_count(const lstm_config *cfg, int64_t *n_params) {
+    Plan p;
+    LSTM_TRY(make_plan(cfg, p));
+    if (!n_params) {
+        set_error("n_params is null");
+        return LSTM_ERR_INVALID;
+    }
+    *n_params = p.P;
+    return LSTM_OK;
+}
+
+extern "C" int lstm_param_offset(const lstm_config *cfg, int32_t kind, int32_t layer, int64_t *offset, int64_t *count) {
+    Plan p;
+    LSTM_TRY(make_plan(cfg, p));
+    if (!offset || !count) {
+        set_error("offset/count is null");
+        return LSTM_ERR_INVALID;
+    }
+    const bool per_layer = kind == LSTM_P_W || kind == LSTM_P_U || kind == LSTM_P_B;
+    if (per_layer && (layer < 0 || layer >= p.L)) {
+        set_error("layer %d out of range", layer);
+        return LSTM_ERR_INVALID;
+    }
+    switch (kind) {
+        case LSTM_P_EMBED:
+            if (p.V == 0) {
+                set_error("config has no embedding");
+                return LSTM_ERR_INVALID;
+            }
+            *offset = p.off_E; *count = (int64_t)p.V * p.D; break;
+        case LSTM_P_W: *offset = p.off_W[layer]; *count = (int64_t)p.G * p.in_dim[layer]; break;
+        case LSTM_P_U: *offset = p.off_U[layer]; *count = (int64_t)p.G * p.H; break;
+        case LSTM_P_B: *offset = p.off_b[layer]; *count = p.G; break;
+        case LSTM_P_HEAD_W: *offset = p.off_wh; *count = p.H; break;
+        case LSTM_P_HEAD_B: *offset = p.off_bh; *count = 1; break;
+        default:
+            set_error("unknown tensor kind %d", kind);
+            return LSTM_ERR_INVALID;
+    }
+    return LSTM_OK;
+}
+
+extern "C" int lstm_workspace_bytes(const lstm_config *cfg, size_t *reserve_bytes, size_t *scratch_bytes) {
+    Plan p;
+    LSTM_TRY(make_plan(cfg, p));
+    if (!reserve_bytes || !scratch_bytes) {
+        set_error("reserve_bytes/scratch_bytes is null");
+        return LSTM_ERR_INVALID;
+    }
+    *reserve_bytes = p.reserve_bytes;
+    *scratch_bytes = p.scratch_bytes;
+    return LSTM_OK;
+}
+
+extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const void *x, const float *targets,
+                            const void *h0, const float *c0, void *reserve, void *scratch, float *loss, void *hT,
+                            float *cT, void *stream) {
+    Plan p;
+    LSTM_TRY(make_plan(cfg, p));
+    LSTM_TRY(check_ptr(params_lp, "params_lp"));
+    LSTM_TRY(check_ptr(x, "x"));
+    LSTM_TRY(check_ptr(targets, "targets"));
+    LSTM_TRY(check_ptr(reserve, "reserve"));
+    LSTM_TRY(check_ptr(scratch, "scratch"));
+    LSTM_TRY(check_ptr(h0, "h0", false));
+    LSTM_TRY(check_ptr(c0, "c0", false));
+    LSTM_TRY(check_ptr(hT, "hT", false));
+    LSTM_TRY(check_ptr(cT, "cT", false));
+    if (!loss) {
+        set_error("loss is null");
+        return LSTM_ERR_INVALID;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const size_t es = p.es;
+    const int TB = p.T * p.B;
+    const char *par = reinterpret_cast<const char *>(params_lp);
+    const int64_t BH = (int64_t)p.B * p.H;
+
+    const void *layer_in = x;
+    if (p.V > 0) {
+        void *xe = at(reserve, p.r_xemb);
+        LSTM_TRY(embed_gather(p.dtype, (const int32_t *)x, par + p.off_E * es, xe, TB, p.V, p.D, s));
+        layer_in = xe;
+    }
+    float *ax = (float *)at(scratch, p.s_ax);
+    float *c_state = (float *)at(scratch, p.s_cstate);
+    for (int l = 0; l < p.L; ++l) {
+        const void *W = par + p.off_W[l] * es, *U = par + p.off_U[l] * es, *b = par + p.off_b[l] * es;
+        char *gates = at(reserve, p.r_gates[l]);
+        char *cs = at(reserve, p.r_c[l]);
+        char *hs = at(reserve, p.r_h[l]);
+        // input projection of the whole sequence: Ax = X W^T + b
+        GemmArgs g{};
+        g.A = layer_in; g.B = W; g.C = ax; g.bias = b;
+        g.M = TB; g.N = p.G; g.K = p.in_dim[l];
+        g.lda = p.in_dim[l]; g.ldb = p.in_dim[l]; g.ldc = p.G;
+        LSTM_TRY(gemm_nt(p.dtype, g, s));
+        LSTM_TRY(init_state(p.dtype, h0 ? at(h0, (size_t)l * BH * es) : nullptr, c0 ? c0 + l * BH : nullptr, hs, cs,
+                            c_state, BH, s));
+        for (int t = 0; t < p.T; ++t) {
+            float *a_t = ax + (int64_t)t * p.B * p.G;
+            // recurrent projection added in place: A_t += h_{t-1} U^T
+            GemmArgs r{};
+            r.A = hs + (size_t)t * BH * es; r.B = U; r.C = a_t;
+            r.M = p.B; r.N = p.G; r.K = p.H;
+            r.lda = p.H; r.ldb = p.H; r.ldc = p.G;
+            r.accumulate = 1;
+            LSTM_TRY(gemm_nt(p.dtype, r, s));
+            LSTM_TRY(gates_forward(p.dtype, a_t, c_state, gates + (size_t)t * p.B * p.G * es,
+                                   cs + (size_t)(t + 1) * BH * es, hs + (size_t)(t + 1) * BH * es, p.B, p.H, s));
+        }
+        LSTM_TRY(copy_state(p.dtype, hs + (size_t)p.T * BH * es, c_state, hT ? at(hT, (size_t)l * BH * es) : nullptr,
+                            cT ? cT + l * BH : nullptr, BH, s));
+        layer_in = hs + (size_t)BH * es;   // h_1..h_T feed the next layer
+    }
+    // head + loss on the top layer's outputs
+    const char *top = at(reserve, p.r_h[p.L - 1]) + (size_t)BH * es;
+    if (p.head == LSTM_HEAD_LAST_BCE) top += (size_t)(p.T - 1) * BH * es;
+    LSTM_TRY(head_forward(p.dtype, p.head, top, par + p.off_wh * es, par + p.off_bh * es, targets, p.head_rows, p.H,
+                          p.head_rows, (float *)at(reserve, p.r_dzu), (float *)at(scratch, p.s_losspart), loss, s));
+    return LSTM_OK;
+}
+
+extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, const void *x, const float *targets,
+                             const void *reserve, void *scratch, const float *loss_scale, void *grads_lp, void *stream) {
+    Plan p;
+    LSTM_TRY(make_plan(cfg, p));
+    LSTM_TRY(check_ptr(params_lp, "params_lp"));
+    LSTM_TRY(check_ptr(x, "x"));
+    LSTM_TRY(check_ptr(reserve, "reserve"));
+    LSTM_TRY(check_ptr(scratch, "scratch"));
+    // one worker's row of an [N,P] gradient matrix: only element alignment can be asked for
+    if (!grads_lp || (uintptr_t)grads_lp % p.es != 0) {
+        set_error("grads_lp is null or not aligned to its element size");
+        return LSTM_ERR_INVALID;
+    }
+    if (!loss_scale) {
+        set_error("loss_scale is null");
+        return LSTM_ERR_INVALID;
+    }
+    (void)targets;  // the head's derivative was saved by lstm_forward
+    hipStream_t s = (hipStream_t)stream;
+    const size_t es = p.es;
+    const int TB = p.T * p.B;
+    const int64_t BH = (int64_t)p.B * p.H;
+    const char *par = reinterpret_cast<const char *>(params_lp);
+    char *grd = reinterpret_cast<char *>(grads_lp);
+    const float *dzu = (const float *)at(reserve, p.r_dzu);
+    float *colpart = (float *)at(scratch, p.s_colpart);
+    float *splitk = (float *)at(scratch, p.s_splitk);
+    char *wT = at(scratch, p.s_wT);
+
+    // transposed copies of the weights the data-gradient GEMMs contract over
+    for (int l = 0; l < p.L; ++l) {
+        if (l > 0 || p.V > 0)
+            LSTM_TRY(transpose_lp(p.dtype, par + p.off_W[l] * es, p.in_dim[l], wT + p.wT_off[l], p.G, p.G, p.in_dim[l], s));
+        LSTM_TRY(transpose_lp(p.dtype, par + p.off_U[l] * es, p.H, wT + p.uT_off[l], p.G, p.G, p.H, s));
+    }
+
+    // head: dz = S * dloss/dz; gradients of the head and the seed for the top layer
+    int cur = 0;
+    char *dh_above = at(scratch, p.s_dh[cur]);
+    const char *top = at(reserve, p.r_h[p.L - 1]) + (size_t)BH * es;
+    if (p.head == LSTM_HEAD_LAST_BCE) {
+        LSTM_TRY(fill_u32(dh_above, 0, (int64_t)(((size_t)TB * p.H * es + 3) / 4), s));
+        const char *top_last = top + (size_t)(p.T - 1) * BH * es;
+        LSTM_TRY(head_backward_dh(p.dtype, dzu, par + p.off_wh * es, loss_scale, dh_above + (size_t)(p.T - 1) * BH * es, p.B, p.H, s));
+        LSTM_TRY(colsum(p.dtype, top_last, p.H, p.B, p.H, dzu, loss_scale, colpart, grd + p.off_wh * es, s));
+    } else {
+        LSTM_TRY(head_backward_dh(p.dtype, dzu, par + p.off_wh * es, loss_scale, dh_above, TB, p.H, s));
+        LSTM_TRY(colsum(p.dtype, top, p.H, TB, p.H, dzu, loss_scale, colpart, grd + p.off_wh * es, s));
+    }
+    LSTM_TRY(head_backward_bias(p.dtype, dzu, loss_scale, p.head_rows, grd + p.off_bh * es, s));
+
+    char *dA = at(scratch, p.s_dA);
+    char *dAT = at(scratch, p.s_dAT);
+    char *xT = at(scratch, p.s_xT);
+    float *dh_rec = (float *)at(scratch, p.s_dhrec);
+    float *dc_state = (float *)at(scratch, p.s_dcstate);
+    for (int l = p.L - 1; l >= 0; --l) {
+        const char *gates = at(reserve, p.r_gates[l]);
+        const char *cs = at(reserve, p.r_c[l]);
+        const char *hs = at(reserve, p.r_h[l]);
+        const void *layer_in = l > 0 ? (const void *)(at(reserve, p.r_h[l - 1]) + (size_t)BH * es)
+                                     : (p.V > 0 ? (const void *)at(reserve, p.r_xemb) : x);
+        const int I = p.in_dim[l];
+        for (int t = p.T - 1; t >= 0; --t) {
+            const bool last = t == p.T - 1;
+            if (!last) {
+                // dh_rec = dA_{t+1} U   (contract over the 4H gate rows)
+                GemmArgs r{};
+                r.A = dA + (size_t)(t + 1) * p.B * p.G * es; r.B = wT + p.uT_off[l]; r.C = dh_rec;
+                r.M = p.B; r.N = p.H; r.K = p.G;
+                r.lda = p.G; r.ldb = p.G; r.ldc = p.H;
+                LSTM_TRY(gemm_nt(p.dtype, r, s));
+            }
+            LSTM_TRY(gates_backward(p.dtype, dh_above + (size_t)t * BH * es, last ? nullptr : dh_rec,
+                                    gates + (size_t)t * p.B * p.G * es, cs + (size_t)(t + 1) * BH * es,
+                                    cs + (size_t)t * BH * es, dc_state, dA + (size_t)t * p.B * p.G * es, p.B, p.H,
+                                    last ? 1 : 0, s));
+        }
+        char *d_below = at(scratch, p.s_dh[cur ^ 1]);
+        if (l > 0 || p.V > 0) {
+            // dX = dA W  for the layer below (or the embedding rows)
+            GemmArgs d{};
+            d.A = dA; d.B = wT + p.wT_off[l]; d.C = d_below;
+            d.M = TB; d.N = I; d.K = p.G;
+            d.lda = p.G; d.ldb = p.G; d.ldc = I;
+            d.out_lp = 1;
+            LSTM_TRY(gemm_nt(p.dtype, d, s));
+        }
+        // weight gradients, contracted over all T*B rows with fp32 accumulation
+        LSTM_TRY(transpose_lp(p.dtype, dA, p.G, dAT, TB, TB, p.G, s));
+        LSTM_TRY(transpose_lp(p.dtype, layer_in, I, xT, TB, TB, I, s));
+        GemmArgs w{};
+        w.A = dAT; w.B = xT; w.C = grd + p.off_W[l] * es;
+        w.M = p.G; w.N = I; w.K = TB;
+        w.lda = TB; w.ldb = TB; w.ldc = I;
+        w.out_lp = 1; w.splitk_ws = splitk; w.splits = p.split_w[l];
+        LSTM_TRY(gemm_nt(p.dtype, w, s));
+        LSTM_TRY(transpose_lp(p.dtype, hs, p.H, xT, TB, TB, p.H, s));   // h_0..h_{T-1}
+        GemmArgs u{};
+        u.A = dAT; u.B = xT; u.C = grd + p.off_U[l] * es;
+        u.M = p.G; u.N = p.H; u.K = TB;
+        u.lda = TB; u.ldb = TB; u.ldc = p.H;
+        u.out_lp = 1; u.splitk_ws = splitk; u.splits = p.split_u[l];
+        LSTM_TRY(gemm_nt(p.dtype, u, s));
+        LSTM_TRY(colsum(p.dtype, dA, p.G, TB, p.G, nullptr, nullptr, colpart, grd + p.off_b[l] * es, s));
+        cur ^= 1;
+        dh_above = d_below;
+    }
+    if (p.V > 0) {
+        float *dE32 = (float *)at(scratch, p.s_dE32);
+        LSTM_TRY(fill_u32(dE32, 0, (int64_t)p.V * p.D, s));
+        LSTM_TRY(embed_scatter_add(p.dtype, (const int32_t *)x, dh_above, dE32, TB, p.V, p.D, s));
+        LSTM_TRY(cast_f32_to_lp(p.dtype, dE32, grd + p.off_E * es, (int64_t)p.V * p.D, s));
+    }
+    return LSTM_OK;
+}

@@ -1,0 +1,120 @@
+// Shared declarations of the gfx950 LSTM training-step library (internal).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/lstm_mi355.h"
+
+namespace lstm {
+
+// ---------------------------------------------------------------- error plumbing
+void set_error(const char *fmt, ...);
+
+#define LSTM_HIP_TRY(expr)                                                                  \
+    do {                                                                                    \
+        hipError_t _e = (expr);                                                             \
+        if (_e != hipSuccess) {                                                             \
+            ::lstm::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(_e), __FILE__, __LINE__); \
+            return LSTM_ERR_HIP;                                                            \
+        }                                                                                   \
+    } while (0)
+
+#define LSTM_TRY(expr)                  \
+    do {                                \
+        int _s = (expr);                \
+        if (_s != LSTM_OK) return _s;   \
+    } while (0)
+
+#define LSTM_LAUNCH_CHECK() LSTM_HIP_TRY(hipGetLastError())
+
+// ---------------------------------------------------------------- storage types
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+typedef __bf16 v8b __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+struct bf16_t {
+    uint16_t bits;
+};
+
+__host__ __device__ inline float bf16_to_float(bf16_t v) {
+    union { uint32_t u; float f; } c;
+    c.u = ((uint32_t)v.bits) << 16;
+    return c.f;
+}
+// round to nearest even; NaN stays NaN
+__host__ __device__ inline bf16_t float_to_bf16(float f) {
+    union { uint32_t u; float f; } c;
+    c.f = f;
+    bf16_t r;
+    if ((c.u & 0x7fffffffu) > 0x7f800000u) {
+        r.bits = (uint16_t)((c.u >> 16) | 0x40u);
+    } else {
+        c.u += 0x7fffu + ((c.u >> 16) & 1u);
+        r.bits = (uint16_t)(c.u >> 16);
+    }
+    return r;
+}
+
+template <typename T> struct Lp;
+template <> struct Lp<float> {
+    static constexpr int code = LSTM_DTYPE_FP32;
+    __device__ static inline float to_f(float v) { return v; }
+    __device__ static inline float from_f(float v) { return v; }
+};
+template <> struct Lp<_Float16> {
+    static constexpr int code = LSTM_DTYPE_FP16;
+    __device__ static inline float to_f(_Float16 v) { return (float)v; }
+    __device__ static inline _Float16 from_f(float v) { return (_Float16)v; }  // RNE, overflow -> inf
+    __device__ static inline v16f mfma(const uint4 &a, const uint4 &b, v16f c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
+    }
+};
+template <> struct Lp<bf16_t> {
+    static constexpr int code = LSTM_DTYPE_BF16;
+    __device__ static inline float to_f(bf16_t v) { return bf16_to_float(v); }
+    __device__ static inline bf16_t from_f(float v) { return float_to_bf16(v); }
+    __device__ static inline v16f mfma(const uint4 &a, const uint4 &b, v16f c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8b, a), __builtin_bit_cast(v8b, b), c, 0, 0, 0);
+    }
+};
+
+inline size_t dtype_size(int dtype) { return dtype == LSTM_DTYPE_FP32 ? 4 : 2; }
+
+// ---------------------------------------------------------------- device math
+__device__ inline float sigmoidf_dev(float a) {
+    // 1/(1+e^-a); for large |a| the exponential saturates to 0 or inf and the
+    // quotient to 1 or 0, both correct limits.
+    return 1.0f / (1.0f + __expf(-a));
+}
+__device__ inline float tanhf_dev(float a) {
+    // tanh(a) = 1 - 2/(e^{2a}+1); exact limits at +-inf, no cancellation issue
+    // beyond fp32 rounding near 0 where the result is ~a.
+    float e = __expf(2.0f * a);
+    return 1.0f - 2.0f / (e + 1.0f);
+}
+
+// ---------------------------------------------------------------- GEMM interface
+// C[M,N] = A[M,K] * B[N,K]^T (+ bias[N]) ; both operands K-contiguous.
+struct GemmArgs {
+    const void *A;      // lp [M, lda]
+    const void *B;      // lp [N, ldb]
+    void *C;            // fp32 or lp [M, ldc]
+    const void *bias;   // lp [N] or null
+    int M, N, K;
+    int64_t lda, ldb, ldc;
+    int out_lp;         // 1: C is lp, 0: C is fp32
+    int accumulate;     // fp32 C only: C += result
+    float *splitk_ws;   // non-null with splits > 1: fp32 [splits, M, N] partials
+    int splits;
+};
+
+// Enqueue one GEMM. dtype = LSTM_DTYPE_*. Returns LSTM_OK or an error status.
+int gemm_nt(int dtype, const GemmArgs &g, hipStream_t stream);
+// number of K splits gemm_nt_auto would like for this shape (>= 1)
+int gemm_pick_splits(int M, int N, int K);
+
+}  // namespace lstm

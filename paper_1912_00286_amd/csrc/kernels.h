@@ -1,0 +1,58 @@
+// Launch wrappers of the pointwise / reduction / optimiser kernels (internal).
+#pragma once
+#include "common.h"
+
+namespace lstm {
+
+// fill n 32-bit words with `value`
+int fill_u32(void *dst, uint32_t value, int64_t n_words, hipStream_t s);
+
+// state set-up of one layer: h slot 0 / c slot 0 of the saved sequences and
+// the running fp32 cell state, from h0/c0 (null = zeros)
+int init_state(int dtype, const void *h0, const float *c0, void *h_slot0, void *c_slot0, float *c_state, int64_t n,
+               hipStream_t s);
+
+// one time step of the gate non-linearities and the cell/hidden update
+//   A       fp32 [B,4H] pre-activations (W x + U h + b)
+//   c_state fp32 [B,H]  in: c_{t-1}, out: c_t
+//   gates   lp   [B,4H] out: i,f,g,o
+//   c_out,h_out lp [B,H]
+int gates_forward(int dtype, const float *A, float *c_state, void *gates, void *c_out, void *h_out, int B, int H,
+                  hipStream_t s);
+
+// one time step of BPTT through the gates
+//   dh_above lp [B,H] (null = 0), dh_rec fp32 [B,H] (null = 0)
+//   gates lp [B,4H], c_t / c_prev lp [B,H]
+//   dc_state fp32 [B,H]: in dc carried from t+1 (ignored when first != 0), out dc for t-1
+//   dA lp [B,4H] out
+int gates_backward(int dtype, const void *dh_above, const float *dh_rec, const void *gates, const void *c_t,
+                   const void *c_prev, float *dc_state, void *dA, int B, int H, int first, hipStream_t s);
+
+// out[C,R] = in[R,C]^T for lp elements
+int transpose_lp(int dtype, const void *in, int64_t ld_in, void *out, int64_t ld_out, int R, int C, hipStream_t s);
+
+// out_lp[c] = scale * sum_r w[r] * in[r,c]   (w null = 1; scale_dev null = 1)
+// partial: fp32 [chunks, C] workspace with chunks = colsum_chunks(R)
+int colsum_chunks(int R);
+int colsum(int dtype, const void *in, int64_t ld, int R, int C, const float *row_w, const float *scale_dev,
+           float *partial, void *out_lp, hipStream_t s);
+
+// head forward: z = h.w + b per row; loss partial sums; dzu = dloss/dz (unscaled, already / M)
+int head_loss_blocks(int rows);
+int head_forward(int dtype, int head, const void *h_top, const void *w, const void *b, const float *targets, int rows,
+                 int H, int M_total, float *dzu, float *partial, float *loss, hipStream_t s);
+// dh[row,:] = scale * dzu[row] * w
+int head_backward_dh(int dtype, const float *dzu, const void *w, const float *scale_dev, void *dh, int rows, int H,
+                     hipStream_t s);
+// db_head = scale * sum dzu
+int head_backward_bias(int dtype, const float *dzu, const float *scale_dev, int rows, void *out_lp, hipStream_t s);
+
+// embedding: X[row,:] = E[clamp(ids[row]),:]
+int embed_gather(int dtype, const int32_t *ids, const void *E, void *X, int rows, int V, int D, hipStream_t s);
+// dE32[ids[row],:] += dX[row,:]  (fp32 atomics), then dE_lp = cast(dE32)
+int embed_scatter_add(int dtype, const int32_t *ids, const void *dX, float *dE32, int rows, int V, int D, hipStream_t s);
+int cast_f32_to_lp(int dtype, const float *in, void *out, int64_t n, hipStream_t s);
+// copy final states out
+int copy_state(int dtype, const void *h_src, const float *c_src, void *h_dst, float *c_dst, int64_t n, hipStream_t s);
+
+}  // namespace lstm

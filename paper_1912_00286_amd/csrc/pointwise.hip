@@ -1,0 +1,385 @@
+// Pointwise, layout and small reduction kernels of the LSTM training step:
+// gate non-linearities forward/backward, transposes, column sums, the output
+// head with its loss, embedding gather / scatter-add, casts and fills.
+#include "kernels.h"
+
+namespace lstm {
+
+#define LSTM_DISPATCH(dtype, T, ...)                               \
+    switch (dtype) {                                               \
+        case LSTM_DTYPE_FP32: { using T = float; __VA_ARGS__; } break;    \
+        case LSTM_DTYPE_FP16: { using T = _Float16; __VA_ARGS__; } break; \
+        case LSTM_DTYPE_BF16: { using T = bf16_t; __VA_ARGS__; } break;   \
+        default: set_error("bad dtype %d", dtype); return LSTM_ERR_INVALID; \
+    }
+
+namespace {
+
+// The fp32 baseline mode uses the accurate library functions; the
+// low-precision modes use the hardware exponential.
+template <typename T> struct Act {
+    __device__ static inline float sigmoid(float a) { return sigmoidf_dev(a); }
+    __device__ static inline float tanh(float a) { return tanhf_dev(a); }
+};
+template <> struct Act<float> {
+    __device__ static inline float sigmoid(float a) { return 1.0f / (1.0f + expf(-a)); }
+    __device__ static inline float tanh(float a) { return tanhf(a); }
+};
+
+inline int blocks_for(int64_t n, int threads, int cap = 65535 * 16) {
+    int64_t b = (n + threads - 1) / threads;
+    if (b > cap) b = cap;
+    if (b < 1) b = 1;
+    return (int)b;
+}
+
+__global__ void fill_u32_kernel(uint32_t *dst, uint32_t v, int64_t n) {
+    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) dst[i] = v;
+}
+
+template <typename T>
+__global__ void init_state_kernel(const T *h0, const float *c0, T *h_slot0, T *c_slot0, float *c_state, int64_t n) {
+    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        h_slot0[i] = h0 ? h0[i] : Lp<T>::from_f(0.0f);
+        const float c = c0 ? c0[i] : 0.0f;
+        c_slot0[i] = Lp<T>::from_f(c);
+        c_state[i] = c;
+    }
+}
+
+template <typename T>
+__global__ void gates_forward_kernel(const float *A, float *c_state, T *gates, T *c_out, T *h_out, int B, int H) {
+    const int64_t n = (int64_t)B * H;
+    const int G = 4 * H;
+    for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x) {
+        const int b = (int)(e / H), j = (int)(e % H);
+        const float *a = A + (int64_t)b * G;
+        const float i = Act<T>::sigmoid(a[j]);
+        const float f = Act<T>::sigmoid(a[H + j]);
+        const float g = Act<T>::tanh(a[2 * H + j]);
+        const float o = Act<T>::sigmoid(a[3 * H + j]);
+        const float c = f * c_state[e] + i * g;
+        const float h = o * Act<T>::tanh(c);
+        c_state[e] = c;
+        T *gr = gates + (int64_t)b * G;
+        gr[j] = Lp<T>::from_f(i);
+        gr[H + j] = Lp<T>::from_f(f);
+        gr[2 * H + j] = Lp<T>::from_f(g);
+        gr[3 * H + j] = Lp<T>::from_f(o);
+        c_out[e] = Lp<T>::from_f(c);
+        h_out[e] = Lp<T>::from_f(h);
+    }
+}
+
+template <typename T>
+__global__ void gates_backward_kernel(const T *dh_above, const float *dh_rec, const T *gates, const T *c_t,
+                                      const T *c_prev, float *dc_state, T *dA, int B, int H, int first) {
+    const int64_t n = (int64_t)B * H;
+    const int G = 4 * H;
+    for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x) {
+        const int b = (int)(e / H), j = (int)(e % H);
+        const T *gr = gates + (int64_t)b * G;
+        const float i = Lp<T>::to_f(gr[j]), f = Lp<T>::to_f(gr[H + j]);
+        const float g = Lp<T>::to_f(gr[2 * H + j]), o = Lp<T>::to_f(gr[3 * H + j]);
+        const float tc = Act<T>::tanh(Lp<T>::to_f(c_t[e]));
+        float dh = dh_above ? Lp<T>::to_f(dh_above[e]) : 0.0f;
+        if (dh_rec) dh += dh_rec[e];
+        const float dcr = first ? 0.0f : dc_state[e];
+        const float d_o = dh * tc;
+        const float dc = dcr + dh * o * (1.0f - tc * tc);
+        const float di = dc * g, dg = dc * i, df = dc * Lp<T>::to_f(c_prev[e]);
+        dc_state[e] = dc * f;
+        T *da = dA + (int64_t)b * G;
+        da[j] = Lp<T>::from_f(di * i * (1.0f - i));
+        da[H + j] = Lp<T>::from_f(df * f * (1.0f - f));
+        da[2 * H + j] = Lp<T>::from_f(dg * (1.0f - g * g));
+        da[3 * H + j] = Lp<T>::from_f(d_o * o * (1.0f - o));
+    }
+}
+
+// 64x64 tile transpose through LDS; 256 threads
+template <typename U>
+__global__ __launch_bounds__(256) void transpose_kernel(const U *in, int64_t ld_in, U *out, int64_t ld_out, int R, int C) {
+    __shared__ U tile[64][65];
+    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int rr = ty; rr < 64; rr += 4) {
+        const int r = r0 + rr, c = c0 + tx;
+        if (r < R && c < C) tile[rr][tx] = in[(int64_t)r * ld_in + c];
+    }
+    __syncthreads();
+    for (int cc = ty; cc < 64; cc += 4) {
+        const int c = c0 + cc, r = r0 + tx;
+        if (r < R && c < C) out[(int64_t)c * ld_out + r] = tile[tx][cc];
+    }
+}
+
+constexpr int CS_ROWS = 512;  // rows per column-sum chunk
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const T *in, int64_t ld, int R, int C, const float *row_w,
+                                                             float *partial) {
+    __shared__ float red[4][64];
+    const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int ry = threadIdx.x >> 6;
+    const int r_beg = blockIdx.y * CS_ROWS, r_end = min(R, r_beg + CS_ROWS);
+    float s = 0.0f;
+    if (c < C)
+        for (int r = r_beg + ry; r < r_end; r += 4) {
+            const float v = Lp<T>::to_f(in[(int64_t)r * ld + c]);
+            s += row_w ? row_w[r] * v : v;
+        }
+    red[ry][threadIdx.x & 63] = s;
+    __syncthreads();
+    if (ry == 0 && c < C) partial[(int64_t)blockIdx.y * C + c] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+}
+template <typename T>
+__global__ void colsum_final_kernel(const float *partial, int chunks, int C, const float *scale_dev, T *out) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    float s = 0.0f;
+    for (int k = 0; k < chunks; ++k) s += partial[(int64_t)k * C + c];
+    if (scale_dev) s *= *scale_dev;
+    out[c] = Lp<T>::from_f(s);
+}
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    return v;
+}
+
+// one wavefront per output row; 4 rows per workgroup
+template <typename T>
+__global__ __launch_bounds__(256) void head_forward_kernel(int head, const T *h_top, const T *w, const T *b,
+                                                           const float *targets, int rows, int H, float inv_M,
+                                                           float *dzu, float *partial) {
+    __shared__ float wl[4];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int row = blockIdx.x * 4 + wv;
+    float ell = 0.0f;
+    if (row < rows) {
+        const T *hr = h_top + (int64_t)row * H;
+        float s = 0.0f;
+        for (int j = lane; j < H; j += 64) s += Lp<T>::to_f(hr[j]) * Lp<T>::to_f(w[j]);
+        s = wave_sum(s);
+        if (lane == 0) {
+            const float z = s + Lp<T>::to_f(b[0]);
+            const float y = targets[row];
+            float d;
+            if (head == LSTM_HEAD_STEP_MSE) {
+                const float r = z - y;
+                ell = r * r;
+                d = 2.0f * r;
+            } else {
+                const float az = fabsf(z);
+                const float e = expf(-az);
+                ell = fmaxf(z, 0.0f) - z * y + log1pf(e);
+                const float sg = z >= 0.0f ? 1.0f / (1.0f + e) : e / (1.0f + e);
+                d = sg - y;
+            }
+            dzu[row] = d * inv_M;
+        }
+    }
+    if (lane == 0) wl[wv] = ell;
+    __syncthreads();
+    if (threadIdx.x == 0) partial[blockIdx.x] = (wl[0] + wl[1]) + (wl[2] + wl[3]);
+}
+__global__ __launch_bounds__(256) void loss_final_kernel(const float *partial, int n, float inv_M, float *loss) {
+    __shared__ double red[256];
+    double s = 0.0;
+    for (int i = threadIdx.x; i < n; i += 256) s += (double)partial[i];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *loss = (float)(red[0] * (double)inv_M);
+}
+
+template <typename T>
+__global__ void head_backward_dh_kernel(const float *dzu, const T *w, const float *scale_dev, T *dh, int rows, int H) {
+    const float S = *scale_dev;
+    const int64_t n = (int64_t)rows * H;
+    for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x) {
+        const int r = (int)(e / H), j = (int)(e % H);
+        dh[e] = Lp<T>::from_f(S * dzu[r] * Lp<T>::to_f(w[j]));
+    }
+}
+template <typename T>
+__global__ __launch_bounds__(256) void head_backward_bias_kernel(const float *dzu, const float *scale_dev, int rows, T *out) {
+    __shared__ double red[256];
+    double s = 0.0;
+    for (int i = threadIdx.x; i < rows; i += 256) s += (double)dzu[i];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[0] = Lp<T>::from_f((float)(red[0] * (double)(*scale_dev)));
+}
+
+template <typename T>
+__global__ void embed_gather_kernel(const int32_t *ids, const T *E, T *X, int rows, int V, int D) {
+    const int64_t n = (int64_t)rows * D;
+    for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x) {
+        const int r = (int)(e / D), d = (int)(e % D);
+        int id = ids[r];
+        id = id < 0 ? 0 : (id >= V ? V - 1 : id);
+        X[e] = E[(int64_t)id * D + d];
+    }
+}
+template <typename T>
+__global__ void embed_scatter_kernel(const int32_t *ids, const T *dX, float *dE, int rows, int V, int D) {
+    const int64_t n = (int64_t)rows * D;
+    for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x) {
+        const int r = (int)(e / D), d = (int)(e % D);
+        int id = ids[r];
+        id = id < 0 ? 0 : (id >= V ? V - 1 : id);
+        atomicAdd(&dE[(int64_t)id * D + d], Lp<T>::to_f(dX[e]));
+    }
+}
+template <typename T>
+__global__ void cast_kernel(const float *in, T *out, int64_t n) {
+    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) out[i] = Lp<T>::from_f(in[i]);
+}
+template <typename T>
+__global__ void copy_state_kernel(const T *h_src, const float *c_src, T *h_dst, float *c_dst, int64_t n) {
+    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        if (h_dst) h_dst[i] = h_src[i];
+        if (c_dst) c_dst[i] = c_src[i];
+    }
+}
+
+}  // namespace
+
+int fill_u32(void *dst, uint32_t value, int64_t n_words, hipStream_t s) {
+    if (n_words <= 0) return LSTM_OK;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks_for(n_words, 256, 8192)), dim3(256), 0, s, (uint32_t *)dst, value, n_words);
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+int init_state(int dtype, const void *h0, const float *c0, void *h_slot0, void *c_slot0, float *c_state, int64_t n,
+               hipStream_t s) {
+    LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(init_state_kernel<T>, dim3(blocks_for(n, 256, 4096)), dim3(256), 0, s,
+                                               (const T *)h0, c0, (T *)h_slot0, (T *)c_slot0, c_state, n));
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+int gates_forward(int dtype, const float *A, float *c_state, void *gates, void *c_out, void *h_out, int B, int H,
+                  hipStream_t s) {
+    const int64_t n = (int64_t)B * H;
+    LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(gates_forward_kernel<T>, dim3(blocks_for(n, 256, 8192)), dim3(256), 0, s, A,
+                                               c_state, (T *)gates, (T *)c_out, (T *)h_out, B, H));
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+int gates_backward(int dtype, const void *dh_above, const float *dh_rec, const void *gates, const void *c_t,
+                   const void *c_prev, float *dc_state, void *dA, int B, int H, int first, hipStream_t s) {
+    const int64_t n = (int64_t)B * H;
+    LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(gates_backward_kernel<T>, dim3(blocks_for(n, 256, 8192)), dim3(256), 0, s,
+                                               (const T *)dh_above, dh_rec, (const T *)gates, (const T *)c_t,
+                                               (const T *)c_prev, dc_state, (T *)dA, B, H, first));
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+int transpose_lp(int dtype, const void *in, int64_t ld_in, void *out, int64_t ld_out, int R, int C, hipStream_t s) {
+    if (R <= 0 || C <= 0) return LSTM_OK;
+    dim3 grid((C + 63) / 64, (R + 63) / 64);
+    if (grid.y > 65535u) {
+        set_error("transpose: too many rows %d", R);
+        return LSTM_ERR_UNSUPPORTED;
+    }
+    if (dtype == LSTM_DTYPE_FP32)
+        hipLaunchKernelGGL(transpose_kernel<uint32_t>, grid, dim3(256), 0, s, (const uint32_t *)in, ld_in, (uint32_t *)out, ld_out, R, C);
+    else
+        hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, dim3(256), 0, s, (const uint16_t *)in, ld_in, (uint16_t *)out, ld_out, R, C);
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+int colsum_chunks(int R) { return R <= 0 ? 1 : (R + CS_ROWS - 1) / CS_ROWS; }
+
+int colsum(int dtype, const void *in, int64_t ld, int R, int C, const float *row_w, const float *scale_dev,
+           float *partial, void *out_lp, hipStream_t s) {
+    if (C <= 0) return LSTM_OK;
+    const int chunks = colsum_chunks(R);
+    dim3 grid((C + 63) / 64, chunks);
+    if (grid.y > 65535u) {
+        set_error("colsum: too many rows %d", R);
+        return LSTM_ERR_UNSUPPORTED;
+    }
+    LSTM_DISPATCH(dtype, T, {
+        hipLaunchKernelGGL(colsum_partial_kernel<T>, grid, dim3(256), 0, s, (const T *)in, ld, R, C, row_w, partial);
+        hipLaunchKernelGGL(colsum_final_kernel<T>, dim3((C + 255) / 256), dim3(256), 0, s, partial, chunks, C, scale_dev, (T *)out_lp);
+    });
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+int head_loss_blocks(int rows) { return rows <= 0 ? 1 : (rows + 3) / 4; }
+
+int head_forward(int dtype, int head, const void *h_top, const void *w, const void *b, const float *targets, int rows,
+                 int H, int M_total, float *dzu, float *partial, float *loss, hipStream_t s) {
+    const int nb = head_loss_blocks(rows);
+    const float inv_M = 1.0f / (float)M_total;
+    LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(head_forward_kernel<T>, dim3(nb), dim3(256), 0, s, head, (const T *)h_top,
+                                               (const T *)w, (const T *)b, targets, rows, H, inv_M, dzu, partial));
+    LSTM_LAUNCH_CHECK();
+    hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(256), 0, s, partial, nb, inv_M, loss);
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+int head_backward_dh(int dtype, const float *dzu, const void *w, const float *scale_dev, void *dh, int rows, int H,
+                     hipStream_t s) {
+    const int64_t n = (int64_t)rows * H;
+    LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(head_backward_dh_kernel<T>, dim3(blocks_for(n, 256, 8192)), dim3(256), 0, s,
+                                               dzu, (const T *)w, scale_dev, (T *)dh, rows, H));
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+int head_backward_bias(int dtype, const float *dzu, const float *scale_dev, int rows, void *out_lp, hipStream_t s) {
+    LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(head_backward_bias_kernel<T>, dim3(1), dim3(256), 0, s, dzu, scale_dev, rows, (T *)out_lp));
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+int embed_gather(int dtype, const int32_t *ids, const void *E, void *X, int rows, int V, int D, hipStream_t s) {
+    const int64_t n = (int64_t)rows * D;
+    LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(embed_gather_kernel<T>, dim3(blocks_for(n, 256, 16384)), dim3(256), 0, s, ids,
+                                               (const T *)E, (T *)X, rows, V, D));
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+int embed_scatter_add(int dtype, const int32_t *ids, const void *dX, float *dE32, int rows, int V, int D, hipStream_t s) {
+    const int64_t n = (int64_t)rows * D;
+    LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(embed_scatter_kernel<T>, dim3(blocks_for(n, 256, 16384)), dim3(256), 0, s, ids,
+                                               (const T *)dX, dE32, rows, V, D));
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+int cast_f32_to_lp(int dtype, const float *in, void *out, int64_t n, hipStream_t s) {
+    if (n <= 0) return LSTM_OK;
+    LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(cast_kernel<T>, dim3(blocks_for(n, 256, 16384)), dim3(256), 0, s, in, (T *)out, n));
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+int copy_state(int dtype, const void *h_src, const float *c_src, void *h_dst, float *c_dst, int64_t n, hipStream_t s) {
+    if (!h_dst && !c_dst) return LSTM_OK;
+    LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(copy_state_kernel<T>, dim3(blocks_for(n, 256, 4096)), dim3(256), 0, s,
+                                               (const T *)h_src, c_src, (T *)h_dst, c_dst, n));
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+}  // namespace lstm

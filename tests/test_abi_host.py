@@ -1,0 +1,141 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, and its pure-host entry points (layout,
+workspace plan, schedule, argument validation) behave as documented."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import lstm_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "lstm_mi355.h")
+
+
+@pytest.fixture(scope="module")
+def hip():
+    import paper_1912_00286_amd as pkg
+    if not os.path.exists(pkg.library_path()):
+        import __graft_entry__ as g
+        g.build()
+    pkg.load_library()
+    return pkg
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"^\s*(?:const\s+)?(?:int|float|char)\s*\*?\s*(\w+)\s*\(", text, flags=re.M)
+    return sorted(set(names))
+
+
+def test_header_symbols_are_exported(hip):
+    names = _declared_functions()
+    for expected in ("lstm_forward", "lstm_backward", "grad_average", "master_update", "lr_schedule",
+                     "lstm_param_count", "lstm_param_offset", "lstm_workspace_bytes", "lstm_abi_version",
+                     "lstm_last_error"):
+        assert expected in names
+    lib = hip.load_library()
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in the header but not exported"
+    assert hip.lstm_abi_version() == 1
+
+
+def _cfg(hip, w):
+    from tests.parity_util import make_cfg
+    return make_cfg(w)
+
+
+@pytest.mark.parametrize("name", list(wl.CONFIGS))
+def test_param_layout_agrees_with_oracle_and_generator(hip, name):
+    w = wl.CONFIGS[name]
+    cfg = _cfg(hip, w)
+    P = hip.lstm_param_count(cfg)
+    assert P == wl.param_count(w) == orc.param_count(w.num_layers, w.input_dim, w.hidden, w.vocab, w.embed_dim)
+    kinds = {"E": 0, "W": 1, "U": 2, "b": 3, "w_head": 4, "b_head": 5}
+    off = 0
+    for nm, shape in orc.param_shapes(w.num_layers, w.input_dim, w.hidden, w.vocab, w.embed_dim):
+        if nm in ("E", "w_head", "b_head"):
+            o, c = hip.lstm_param_offset(cfg, kinds[nm], 0)
+        else:
+            o, c = hip.lstm_param_offset(cfg, kinds[nm[0]], int(nm[1:]))
+        assert (o, c) == (off, int(np.prod(shape))), nm
+        off += c
+    assert off == P
+
+
+def test_param_counts_of_the_benchmark_configs(hip):
+    want = {"tiny": 6049, "jet": 533001, "text": 2954497, "large": 88107009, "workers64": 533001}
+    for name, n in want.items():
+        assert hip.lstm_param_count(_cfg(hip, wl.CONFIGS[name])) == n
+
+
+def test_workspace_plan(hip):
+    w = wl.CONFIGS["large"]
+    r, s = hip.lstm_workspace_bytes(_cfg(hip, w))
+    saved = 6 * w.hidden * 2 * w.seq_len * w.batch * w.num_layers     # 4 gates + c + h in fp16
+    assert saved <= r <= 1.1 * saved + (1 << 20)
+    assert 0 < s < 8 << 30
+    r1, s1 = hip.lstm_workspace_bytes(_cfg(hip, wl.CONFIGS["tiny"]))
+    assert r1 % 256 == 0 and s1 % 256 == 0 and r1 < r and s1 < s
+
+
+def test_invalid_arguments_are_rejected_on_the_host(hip):
+    w = wl.CONFIGS["tiny"]
+    for field, val, status in (("batch", 0, -1), ("seq_len", 0, -1), ("hidden", 0, -1), ("num_layers", 0, -1),
+                               ("dtype", 7, -1), ("head", 0, -1), ("out_dim", 2, -2), ("input_dim", 0, -1)):
+        cfg = _cfg(hip, w)
+        setattr(cfg, field, val)
+        with pytest.raises(hip.LstmError) as e:
+            hip.lstm_param_count(cfg)
+        assert e.value.status == status and hip.lstm_last_error()
+    cfg = _cfg(hip, w)
+    with pytest.raises(hip.LstmError):
+        hip.lstm_param_offset(cfg, 1, 5)
+    with pytest.raises(hip.LstmError):
+        hip.lstm_param_offset(cfg, 0, 0)         # no embedding in this config
+    # null / misaligned device pointers are refused before anything is enqueued
+    with pytest.raises(hip.LstmError):
+        hip.lstm_forward(cfg, 0, 0, 0, None, None, 0, 0, 0, stream=0)
+    with pytest.raises(hip.LstmError) as e:
+        hip.lstm_forward(cfg, 4096 + 2, 4096, 4096, None, None, 4096, 4096, 4096, stream=0)
+    assert "aligned" in str(e.value)
+    with pytest.raises(hip.LstmError):
+        hip.grad_average(10, 0, 4096, 1, 4096, 4096, 4096, stream=0)
+    opt = hip.OptimizerConfig(kind=9)
+    with pytest.raises(hip.LstmError):
+        hip.master_update(10, opt, 0.1, 1, 4096, 4096, None, 4096, 4096, 4096, 4096, 4096, 1, stream=0)
+    opt = hip.OptimizerConfig(kind=1)
+    with pytest.raises(hip.LstmError):          # Adam without its second state
+        hip.master_update(10, opt, 0.1, 1, 4096, 4096, None, 4096, 4096, 4096, 4096, 4096, 1, stream=0)
+
+
+def test_lr_schedule_matches_oracle_and_paper(hip):
+    rng = np.random.default_rng(0)
+    for _ in range(200):
+        lr0 = float(10 ** rng.uniform(-4, -1)); N = int(rng.integers(1, 200)); n = float(rng.integers(1, 128))
+        W = int(rng.integers(0, 8)); gamma = float(rng.uniform(0.8, 1.0)); k = int(rng.integers(0, 30))
+        got = hip.lr_schedule(lr0, N, n, 0.1, W, gamma, k)
+        want = orc.lr_schedule(np.float32(lr0), N, np.float32(n), np.float32(0.1), W, np.float32(gamma), k)
+        assert got == pytest.approx(want, rel=2e-7)
+    assert hip.lr_schedule(0.001, 8, 8.0, 1e9, 0, 1.0, 0) == pytest.approx(0.0005, rel=1e-7)   # halved at N = n
+    assert hip.lr_schedule(0.05, 8, 8.0, 0.1, 0, 1.0, 0) == pytest.approx(0.0125, rel=1e-7)     # clipped
+    assert hip.lr_schedule(0.001, 0, 8.0, 0.1, 0, 1.0, 0) == 0.0                                 # invalid
+    w = wl.CONFIGS["workers64"]
+    vals = [hip.lr_schedule(w.lr0, 64, 64.0, 0.1, 5, 0.97, k) for k in range(8)]
+    assert vals[4] == pytest.approx(5e-4, rel=1e-6) and vals[0] == pytest.approx(1e-4, rel=1e-6)
+    assert vals[7] == pytest.approx(5e-4 * 0.97 ** 3, rel=1e-6)
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg_dir = os.path.join(ROOT, "paper_1912_00286_amd")
+    for dirpath, _, files in os.walk(pkg_dir):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f
+    otext = open(os.path.join(ROOT, "oracle", "lstm_oracle.py")).read()
+    assert "paper_1912_00286_amd" not in otext and "import workloads" not in otext

@@ -45,7 +45,7 @@ class Workload:
     momentum: float = 0.9
     lr0: float = 1e-3
     # worker-count schedule (Section "Learning rate schedule")
-    n_half: float = 64.0
+    n_half: float = 1e12            # single-worker configs: Eq. 4 leaves lr0 unchanged
     warmup_steps: int = 0
     gamma: float = 1.0
     target_kind: str = "bernoulli"   # "bernoulli" | "normal"
