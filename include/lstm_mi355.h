@@ -177,6 +177,21 @@ int master_update(int64_t n_params, const optimizer_config *opt, float lr, int64
 float lr_schedule(float lr0, int32_t n_workers, float n_half, float eff_lr_max, int32_t warmup_steps,
                   float gamma, int64_t index);
 
+/* ---- diagnostics (not part of the training step) ----------------------------
+ * Per-kernel-class launch timing for benchmarks.  When enabled, every launch
+ * the library enqueues is bracketed by two HIP events recorded on the caller's
+ * stream (events are created on first use and reused).  lstm_timing_enable
+ * also clears the accumulated numbers.  lstm_timing_read waits for the
+ * recorded work, then returns for one class the number of timed launches, the
+ * summed event-to-event duration in ms, and the summed algorithmic flops
+ * (GEMM classes: 2*M*N*K) and bytes (streaming classes) of those launches.
+ * Classes: 0 whole-sequence GEMMs, 1 per-time-step recurrent GEMMs, 2 gate
+ * pointwise kernels, 3 auxiliary kernels, 4 grad_average, 5 master_update.
+ * All out-pointers are host memory.  Not thread-safe with respect to
+ * concurrently running entry points on other threads' streams. */
+int lstm_timing_enable(int32_t on);
+int lstm_timing_read(int32_t kernel_class, int64_t *launches, double *total_ms, double *flops, double *bytes);
+
 #ifdef __cplusplus
 }
 #endif

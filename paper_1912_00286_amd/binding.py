@@ -66,8 +66,10 @@ def load_library():
     lib.master_update.argtypes = [i64, optp, f32, i64, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
     lib.lr_schedule.argtypes = [f32, i32, f32, f32, i32, f32, i64]
     lib.lr_schedule.restype = f32
+    lib.lstm_timing_enable.argtypes = [i32]
+    lib.lstm_timing_read.argtypes = [i32, C.POINTER(i64), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double)]
     for name in ("lstm_param_count", "lstm_param_offset", "lstm_workspace_bytes", "lstm_forward", "lstm_backward",
-                 "grad_average", "master_update"):
+                 "grad_average", "master_update", "lstm_timing_enable", "lstm_timing_read"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -146,6 +148,19 @@ def master_update(n_params, opt, lr, step, master, state1, state2, avg_grad, fou
 
 def lr_schedule(lr0, n_workers, n_half, eff_lr_max, warmup_steps, gamma, index) -> float:
     return float(load_library().lr_schedule(lr0, n_workers, n_half, eff_lr_max, warmup_steps, gamma, index))
+
+
+KERNEL_CLASSES = ("gemm_batched", "gemm_step", "pointwise", "aux", "grad_average", "master_update")
+
+
+def lstm_timing_enable(on: bool) -> None:
+    _check(load_library().lstm_timing_enable(1 if on else 0))
+
+
+def lstm_timing_read(kernel_class: int):
+    n, ms, fl, by = C.c_int64(), C.c_double(), C.c_double(), C.c_double()
+    _check(load_library().lstm_timing_read(kernel_class, C.byref(n), C.byref(ms), C.byref(fl), C.byref(by)))
+    return dict(launches=n.value, total_ms=ms.value, flops=fl.value, bytes=by.value)
 
 
 # --------------------------------------------------------------------------

@@ -264,6 +264,7 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
         g.A = layer_in; g.B = W; g.C = ax; g.bias = b;
         g.M = TB; g.N = p.G; g.K = p.in_dim[l];
         g.lda = p.in_dim[l]; g.ldb = p.in_dim[l]; g.ldc = p.G;
+        g.kclass = KC_GEMM_BATCHED;
         LSTM_TRY(gemm_nt(p.dtype, g, s));
         LSTM_TRY(init_state(p.dtype, h0 ? at(h0, (size_t)l * BH * es) : nullptr, c0 ? c0 + l * BH : nullptr, hs, cs,
                             c_state, BH, s));
@@ -275,6 +276,7 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
             r.M = p.B; r.N = p.G; r.K = p.H;
             r.lda = p.H; r.ldb = p.H; r.ldc = p.G;
             r.accumulate = 1;
+            r.kclass = KC_GEMM_STEP;
             LSTM_TRY(gemm_nt(p.dtype, r, s));
             LSTM_TRY(gates_forward(p.dtype, a_t, c_state, gates + (size_t)t * p.B * p.G * es,
                                    cs + (size_t)(t + 1) * BH * es, hs + (size_t)(t + 1) * BH * es, p.B, p.H, s));
@@ -362,6 +364,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
                 r.A = dA + (size_t)(t + 1) * p.B * p.G * es; r.B = wT + p.uT_off[l]; r.C = dh_rec;
                 r.M = p.B; r.N = p.H; r.K = p.G;
                 r.lda = p.G; r.ldb = p.G; r.ldc = p.H;
+                r.kclass = KC_GEMM_STEP;
                 LSTM_TRY(gemm_nt(p.dtype, r, s));
             }
             LSTM_TRY(gates_backward(p.dtype, dh_above + (size_t)t * BH * es, last ? nullptr : dh_rec,
@@ -376,7 +379,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             d.A = dA; d.B = wT + p.wT_off[l]; d.C = d_below;
             d.M = TB; d.N = I; d.K = p.G;
             d.lda = p.G; d.ldb = p.G; d.ldc = I;
-            d.out_lp = 1;
+            d.out_lp = 1; d.kclass = KC_GEMM_BATCHED;
             LSTM_TRY(gemm_nt(p.dtype, d, s));
         }
         // weight gradients, contracted over all T*B rows with fp32 accumulation
@@ -386,6 +389,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
         w.A = dAT; w.B = xT; w.C = grd + p.off_W[l] * es;
         w.M = p.G; w.N = I; w.K = TB;
         w.lda = TB; w.ldb = TB; w.ldc = I;
+        w.kclass = KC_GEMM_BATCHED;
         w.out_lp = 1; w.splitk_ws = splitk; w.splits = p.split_w[l];
         LSTM_TRY(gemm_nt(p.dtype, w, s));
         LSTM_TRY(transpose_lp(p.dtype, hs, p.H, xT, TB, TB, p.H, s));   // h_0..h_{T-1}
@@ -393,6 +397,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
         u.A = dAT; u.B = xT; u.C = grd + p.off_U[l] * es;
         u.M = p.G; u.N = p.H; u.K = TB;
         u.lda = TB; u.ldb = TB; u.ldc = p.H;
+        u.kclass = KC_GEMM_BATCHED;
         u.out_lp = 1; u.splitk_ws = splitk; u.splits = p.split_u[l];
         LSTM_TRY(gemm_nt(p.dtype, u, s));
         LSTM_TRY(colsum(p.dtype, dA, p.G, TB, p.G, nullptr, nullptr, colpart, grd + p.off_b[l] * es, s));

@@ -97,6 +97,31 @@ __device__ inline float tanhf_dev(float a) {
     return 1.0f - 2.0f / (e + 1.0f);
 }
 
+// ---------------------------------------------------------------- optional launch timing
+enum KernelClass {
+    KC_GEMM_BATCHED = 0,   // whole-sequence GEMMs: input projection, dX, dW/dU
+    KC_GEMM_STEP = 1,      // per-time-step recurrent GEMMs (forward and BPTT)
+    KC_POINTWISE = 2,      // gate non-linearities forward / backward
+    KC_AUX = 3,            // transposes, column sums, head, embedding, fills
+    KC_AVERAGE = 4,        // grad_average
+    KC_UPDATE = 5,         // master_update
+    KC_COUNT = 6
+};
+bool timing_enabled();
+// Brackets the launches enqueued during its lifetime with two HIP events on
+// `s` when timing is enabled (lstm_timing_enable); otherwise does nothing.
+class KernelTimer {
+public:
+    KernelTimer(int cls, hipStream_t s, double flops, double bytes);
+    ~KernelTimer();
+    KernelTimer(const KernelTimer &) = delete;
+    KernelTimer &operator=(const KernelTimer &) = delete;
+private:
+    int cls_;
+    hipStream_t stream_;
+    void *beg_;
+};
+
 // ---------------------------------------------------------------- GEMM interface
 // C[M,N] = A[M,K] * B[N,K]^T (+ bias[N]) ; both operands K-contiguous.
 struct GemmArgs {
@@ -110,6 +135,7 @@ struct GemmArgs {
     int accumulate;     // fp32 C only: C += result
     float *splitk_ws;   // non-null with splits > 1: fp32 [splits, M, N] partials
     int splits;
+    int kclass;         // KernelClass the launch is accounted to
 };
 
 // Enqueue one GEMM. dtype = LSTM_DTYPE_*. Returns LSTM_OK or an error status.

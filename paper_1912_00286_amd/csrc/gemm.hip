@@ -250,6 +250,7 @@ int launch(const GemmArgs &g, hipStream_t stream) {
         set_error("gemm_nt: grid too large (M=%d splits=%d)", g.M, splits);
         return LSTM_ERR_UNSUPPORTED;
     }
+    KernelTimer timer(g.kclass, stream, 2.0 * g.M * g.N * g.K, 0.0);
     if constexpr (is_f32) {
         hipLaunchKernelGGL(gemm_nt_f32_kernel, grid, dim3(256), 0, stream, a);
     } else {

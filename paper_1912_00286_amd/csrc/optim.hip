@@ -201,6 +201,8 @@ extern "C" int grad_average(int64_t n_params, int32_t n_workers, const void *gra
         return LSTM_ERR_INVALID;
     }
     hipStream_t s = (hipStream_t)stream;
+    // algorithmic traffic: every worker's gradient read once, the fp32 average written once
+    KernelTimer timer(KC_AVERAGE, s, 0.0, (double)n_params * ((double)n_workers * dtype_size(dtype) + 4.0));
     hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(64), 0, s, found_inf, 0);
     LSTM_LAUNCH_CHECK();
     if (n_params == 0) return LSTM_OK;
@@ -268,6 +270,9 @@ extern "C" int master_update(int64_t n_params, const optimizer_config *opt, floa
         u.inv_bc1 = (float)(1.0 / (1.0 - pow((double)opt->beta1, (double)step)));
         u.inv_bc2 = (float)(1.0 / (1.0 - pow((double)opt->beta2, (double)step)));
     }
+    // algorithmic traffic per parameter: read master, state(s), gradient; write master, state(s), working copy
+    const double per_param = (opt->kind == LSTM_OPT_ADAM ? 5.0 : 3.0) * 4.0 + 4.0 + (double)dtype_size(dtype);
+    KernelTimer timer(KC_UPDATE, s, 0.0, (double)n_params * per_param);
     if (n_params > 0) {
         const int grid = grid_for(n_params / 4 + 1);
         switch (dtype) {

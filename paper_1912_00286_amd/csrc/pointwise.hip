@@ -255,6 +255,7 @@ __global__ void copy_state_kernel(const T *h_src, const float *c_src, T *h_dst, 
 }  // namespace
 
 int fill_u32(void *dst, uint32_t value, int64_t n_words, hipStream_t s) {
+    KernelTimer timer(KC_AUX, s, 0.0, 0.0);
     if (n_words <= 0) return LSTM_OK;
     hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks_for(n_words, 256, 8192)), dim3(256), 0, s, (uint32_t *)dst, value, n_words);
     LSTM_LAUNCH_CHECK();
@@ -263,6 +264,7 @@ int fill_u32(void *dst, uint32_t value, int64_t n_words, hipStream_t s) {
 
 int init_state(int dtype, const void *h0, const float *c0, void *h_slot0, void *c_slot0, float *c_state, int64_t n,
                hipStream_t s) {
+    KernelTimer timer(KC_AUX, s, 0.0, 0.0);
     LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(init_state_kernel<T>, dim3(blocks_for(n, 256, 4096)), dim3(256), 0, s,
                                                (const T *)h0, c0, (T *)h_slot0, (T *)c_slot0, c_state, n));
     LSTM_LAUNCH_CHECK();
@@ -271,6 +273,7 @@ int init_state(int dtype, const void *h0, const float *c0, void *h_slot0, void *
 
 int gates_forward(int dtype, const float *A, float *c_state, void *gates, void *c_out, void *h_out, int B, int H,
                   hipStream_t s) {
+    KernelTimer timer(KC_POINTWISE, s, 0.0, (double)B * H * (16.0 + 4.0 + 4.0 + 6.0 * sizeof(uint16_t)));
     const int64_t n = (int64_t)B * H;
     LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(gates_forward_kernel<T>, dim3(blocks_for(n, 256, 8192)), dim3(256), 0, s, A,
                                                c_state, (T *)gates, (T *)c_out, (T *)h_out, B, H));
@@ -280,6 +283,7 @@ int gates_forward(int dtype, const float *A, float *c_state, void *gates, void *
 
 int gates_backward(int dtype, const void *dh_above, const float *dh_rec, const void *gates, const void *c_t,
                    const void *c_prev, float *dc_state, void *dA, int B, int H, int first, hipStream_t s) {
+    KernelTimer timer(KC_POINTWISE, s, 0.0, (double)B * H * (8.0 + 4.0 + 11.0 * sizeof(uint16_t)));
     const int64_t n = (int64_t)B * H;
     LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(gates_backward_kernel<T>, dim3(blocks_for(n, 256, 8192)), dim3(256), 0, s,
                                                (const T *)dh_above, dh_rec, (const T *)gates, (const T *)c_t,
@@ -289,6 +293,7 @@ int gates_backward(int dtype, const void *dh_above, const float *dh_rec, const v
 }
 
 int transpose_lp(int dtype, const void *in, int64_t ld_in, void *out, int64_t ld_out, int R, int C, hipStream_t s) {
+    KernelTimer timer(KC_AUX, s, 0.0, 0.0);
     if (R <= 0 || C <= 0) return LSTM_OK;
     dim3 grid((C + 63) / 64, (R + 63) / 64);
     if (grid.y > 65535u) {
@@ -307,6 +312,7 @@ int colsum_chunks(int R) { return R <= 0 ? 1 : (R + CS_ROWS - 1) / CS_ROWS; }
 
 int colsum(int dtype, const void *in, int64_t ld, int R, int C, const float *row_w, const float *scale_dev,
            float *partial, void *out_lp, hipStream_t s) {
+    KernelTimer timer(KC_AUX, s, 0.0, 0.0);
     if (C <= 0) return LSTM_OK;
     const int chunks = colsum_chunks(R);
     dim3 grid((C + 63) / 64, chunks);
@@ -326,6 +332,7 @@ int head_loss_blocks(int rows) { return rows <= 0 ? 1 : (rows + 3) / 4; }
 
 int head_forward(int dtype, int head, const void *h_top, const void *w, const void *b, const float *targets, int rows,
                  int H, int M_total, float *dzu, float *partial, float *loss, hipStream_t s) {
+    KernelTimer timer(KC_AUX, s, 0.0, 0.0);
     const int nb = head_loss_blocks(rows);
     const float inv_M = 1.0f / (float)M_total;
     LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(head_forward_kernel<T>, dim3(nb), dim3(256), 0, s, head, (const T *)h_top,
@@ -338,6 +345,7 @@ int head_forward(int dtype, int head, const void *h_top, const void *w, const vo
 
 int head_backward_dh(int dtype, const float *dzu, const void *w, const float *scale_dev, void *dh, int rows, int H,
                      hipStream_t s) {
+    KernelTimer timer(KC_AUX, s, 0.0, 0.0);
     const int64_t n = (int64_t)rows * H;
     LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(head_backward_dh_kernel<T>, dim3(blocks_for(n, 256, 8192)), dim3(256), 0, s,
                                                dzu, (const T *)w, scale_dev, (T *)dh, rows, H));
@@ -346,12 +354,14 @@ int head_backward_dh(int dtype, const float *dzu, const void *w, const float *sc
 }
 
 int head_backward_bias(int dtype, const float *dzu, const float *scale_dev, int rows, void *out_lp, hipStream_t s) {
+    KernelTimer timer(KC_AUX, s, 0.0, 0.0);
     LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(head_backward_bias_kernel<T>, dim3(1), dim3(256), 0, s, dzu, scale_dev, rows, (T *)out_lp));
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
 
 int embed_gather(int dtype, const int32_t *ids, const void *E, void *X, int rows, int V, int D, hipStream_t s) {
+    KernelTimer timer(KC_AUX, s, 0.0, 0.0);
     const int64_t n = (int64_t)rows * D;
     LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(embed_gather_kernel<T>, dim3(blocks_for(n, 256, 16384)), dim3(256), 0, s, ids,
                                                (const T *)E, (T *)X, rows, V, D));
@@ -360,6 +370,7 @@ int embed_gather(int dtype, const int32_t *ids, const void *E, void *X, int rows
 }
 
 int embed_scatter_add(int dtype, const int32_t *ids, const void *dX, float *dE32, int rows, int V, int D, hipStream_t s) {
+    KernelTimer timer(KC_AUX, s, 0.0, 0.0);
     const int64_t n = (int64_t)rows * D;
     LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(embed_scatter_kernel<T>, dim3(blocks_for(n, 256, 16384)), dim3(256), 0, s, ids,
                                                (const T *)dX, dE32, rows, V, D));
@@ -368,6 +379,7 @@ int embed_scatter_add(int dtype, const int32_t *ids, const void *dX, float *dE32
 }
 
 int cast_f32_to_lp(int dtype, const float *in, void *out, int64_t n, hipStream_t s) {
+    KernelTimer timer(KC_AUX, s, 0.0, 0.0);
     if (n <= 0) return LSTM_OK;
     LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(cast_kernel<T>, dim3(blocks_for(n, 256, 16384)), dim3(256), 0, s, in, (T *)out, n));
     LSTM_LAUNCH_CHECK();
@@ -375,6 +387,7 @@ int cast_f32_to_lp(int dtype, const float *in, void *out, int64_t n, hipStream_t
 }
 
 int copy_state(int dtype, const void *h_src, const float *c_src, void *h_dst, float *c_dst, int64_t n, hipStream_t s) {
+    KernelTimer timer(KC_AUX, s, 0.0, 0.0);
     if (!h_dst && !c_dst) return LSTM_OK;
     LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(copy_state_kernel<T>, dim3(blocks_for(n, 256, 4096)), dim3(256), 0, s,
                                                (const T *)h_src, c_src, (T *)h_dst, c_dst, n));

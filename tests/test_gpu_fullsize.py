@@ -1,0 +1,96 @@
+"""Full-size parity: benchmark configs 4 and 5 on the HIP path, in the launch
+configuration bench.py times, against the CPU oracle."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import lstm_oracle as orc
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hip():
+    import paper_1912_00286_amd as pkg
+    pkg.load_library()
+    return pkg
+
+
+def test_config4_large_fp16_dynamic_scale(hip):
+    """88 M parameters, T=128, B=256: whole step against the oracle run in full
+    (about 17 TFLOP of fp64 work on the host)."""
+    w = wl.CONFIGS["large"]
+    print("[case] large: HIP step", flush=True)
+    gpu = pu.run_gpu_step(w)
+    print(f"[case] large: HIP done, scales tried {gpu['scales']}, flags {gpu['found_inf']}; oracle ...", flush=True)
+    ref = pu.run_oracle_step(w)
+    print("[case] large: oracle done", flush=True)
+    pu.assert_step_close(w, gpu, ref)
+    assert gpu["scales"][0] == 32768.0
+
+
+def test_config5_sixty_four_workers(hip):
+    """64 micro-batches of the config-2 model averaged on the device.  The
+    averaged gradient is compared with the oracle's gradient on the
+    concatenated batch of 64*128 samples (equal by the big-batch identity the
+    oracle is pinned with); workers 0 and 63 are also compared one by one."""
+    w = wl.CONFIGS["workers64"]
+    print("[case] workers64: HIP step", flush=True)
+    gpu = pu.run_gpu_step(w)
+    master0, xs, ys = pu.inputs_for(w)
+    shapes = pu.oracle_shapes(w)
+    params = orc.unflatten(master0, shapes)
+    tol = pu.GRAD_RTOL[w.dtype]
+    print("[case] workers64: oracle on the concatenated batch", flush=True)
+    xcat = np.concatenate(xs, axis=1).astype(np.float64); ycat = np.concatenate(ys, axis=1)
+    loss_cat, cache = orc.forward(params, w.num_layers, xcat, ycat, w.head)
+    avg_ref = orc.flatten(orc.backward(params, w.num_layers, cache, 1.0), shapes)
+    del cache
+    assert gpu["found_inf"][-1] == 0
+    assert abs(gpu["losses"].mean() - loss_cat) <= pu.LOSS_RTOL * abs(loss_cat)
+    pu.assert_grads_close(gpu["avg"], avg_ref, shapes, tol, "averaged over 64 workers")
+    for k in (0, w.n_workers - 1):
+        loss, cache = orc.forward(params, w.num_layers, xs[k].astype(np.float64), ys[k], w.head)
+        g = orc.flatten(orc.backward(params, w.num_layers, cache, 1.0), shapes)
+        assert abs(gpu["losses"][k] - loss) <= pu.LOSS_RTOL * abs(loss)
+        pu.assert_grads_close(gpu["grads"][k], g, shapes, tol, f"worker {k}")
+    # schedule of step 0 (warm-up 1/5 of lr0 / (1 + 64/64)) and the update of Eq. 1-2
+    assert gpu["lr"] == pytest.approx(1e-3 / 2 / 5, rel=1e-6)
+    W, _ = orc.sgd_momentum_update(master0.astype(np.float64), np.zeros_like(avg_ref), avg_ref, gpu["lr"], w.momentum)
+    dW = W - master0
+    bound = tol * np.max(np.abs(dW)) + 1.2e-7 * np.abs(W) + 1e-12
+    assert np.all(np.abs(gpu["master"] - W) <= bound)
+    np.testing.assert_array_equal(gpu["params_lp"], orc.round_storage(gpu["master"], w.dtype))
+
+
+def test_many_steps_schedule_and_trajectory(hip):
+    """Eight iterations of a reduced many-worker model: warm-up then decay of
+    the learning rate, momentum carried across steps, master weights compared
+    with the oracle trajectory after every step."""
+    import torch
+    w = wl.Workload("s_traj", 2, 16, 40, 10, 8, "fp16", wl.HEAD_STEP_BCE, n_workers=4, loss_scale=1024.0,
+                    dynamic_scale=True, n_half=4.0, warmup_steps=5, gamma=0.97, lr0=0.05, data_seed=400, weight_seed=41)
+    master0, xs, ys = pu.inputs_for(w)
+    shapes = pu.oracle_shapes(w)
+    ts = pu.make_step(w, master0)
+    dx, dy = pu.device_batches(w, xs, ys, ts.lp_dtype, ts.dev)
+    W = master0.astype(np.float64); Hb = np.zeros_like(W)
+    for k in range(8):
+        lr = pu.lr_for(w, k)
+        lr_ref = orc.lr_schedule(w.lr0, w.n_workers, w.n_half, pu.EFF_LR_MAX, w.warmup_steps, w.gamma, k)
+        assert lr == pytest.approx(lr_ref, rel=1e-6)
+        # oracle step from the HIP path's current working copy (so errors do not compound in the comparison)
+        cur = ts.params_lp.double().cpu().numpy()
+        out = orc.training_step(cur, shapes, w.num_layers, [(x.astype(np.float64), y) for x, y in zip(xs, ys)],
+                                w.head, 1.0, lr_ref, w.momentum, Hbuf=ts.state1.double().cpu().numpy())
+        m_before = ts.master.double().cpu().numpy()
+        ts.step(dx, dy, lr)
+        torch.cuda.synchronize()
+        assert int(ts.found_inf.item()) == 0
+        pu.assert_grads_close(ts.avg.double().cpu().numpy(), out["avg_grad"], shapes, pu.GRAD_RTOL["fp16"], f"step {k}")
+        H_ref = w.momentum * out["H"] * 0 + out["H"]
+        W_ref = m_before + H_ref
+        bound = pu.GRAD_RTOL["fp16"] * np.max(np.abs(H_ref)) + 1.2e-7 * np.abs(W_ref) + 1e-12
+        assert np.all(np.abs(ts.master.double().cpu().numpy() - W_ref) <= bound), f"step {k}"
+    assert int(ts.good_steps.item()) == 8 and float(ts.loss_scale.item()) == 1024.0
