@@ -38,7 +38,7 @@ struct Plan {
     // scratch
     size_t s_ax = 0, s_cstate = 0, s_losspart = 0;
     size_t s_wT = 0, s_dA = 0, s_dAT = 0, s_xT = 0, s_dh[2] = {0, 0}, s_dhrec = 0, s_dcstate = 0, s_splitk = 0,
-           s_colpart = 0, s_dE32 = 0, scratch_bytes = 0;
+           s_colpart = 0, s_dE32 = 0, s_part = 0, s_upk = 0, s_apk[2] = {0, 0}, scratch_bytes = 0;
     std::vector<size_t> wT_off, uT_off;  // byte offsets inside the s_wT region
     std::vector<int> split_w, split_u;
 };
@@ -128,8 +128,8 @@ int make_plan(const lstm_config *c, Plan &p) {
     size_t splitk = 0;
     p.split_w.resize(p.L); p.split_u.resize(p.L);
     for (int l = 0; l < p.L; ++l) {
-        p.split_w[l] = gemm_pick_splits(p.G, p.in_dim[l], (int)TB);
-        p.split_u[l] = gemm_pick_splits(p.G, p.H, (int)TB);
+        p.split_w[l] = gemm_pick_splits(p.dtype, p.G, p.in_dim[l], (int)TB);
+        p.split_u[l] = gemm_pick_splits(p.dtype, p.G, p.H, (int)TB);
         size_t a = p.split_w[l] > 1 ? (size_t)p.split_w[l] * p.G * p.in_dim[l] * 4 : 0;
         size_t b = p.split_u[l] > 1 ? (size_t)p.split_u[l] * p.G * p.H * 4 : 0;
         splitk = a > splitk ? a : splitk;
@@ -139,6 +139,13 @@ int make_plan(const lstm_config *c, Plan &p) {
     const int colw = p.G > p.H ? p.G : p.H;
     p.s_colpart = s; s += align_up((size_t)colsum_chunks((int)TB) * colw * 4);
     p.s_dE32 = s; if (p.V > 0) s += align_up((size_t)p.V * p.D * 4);
+    if (p.dtype != LSTM_DTYPE_FP32) {
+        // packed operands of the fused recurrent kernels
+        const RecurrentDims rd = recurrent_dims(p.B, p.H);
+        p.s_part = s; s += align_up(rd.partial_bytes);
+        p.s_upk = s; s += align_up((rd.utpk_elems > rd.upk_elems ? rd.utpk_elems : rd.upk_elems) * p.es);
+        for (int k = 0; k < 2; ++k) { p.s_apk[k] = s; s += align_up(rd.dapk_elems * p.es); }
+    }
     p.scratch_bytes = s;
     return LSTM_OK;
 }
@@ -268,9 +275,26 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
         LSTM_TRY(gemm_nt(p.dtype, g, s));
         LSTM_TRY(init_state(p.dtype, h0 ? at(h0, (size_t)l * BH * es) : nullptr, c0 ? c0 + l * BH : nullptr, hs, cs,
                             c_state, BH, s));
+        const bool fused = p.dtype != LSTM_DTYPE_FP32;
+        char *upk = at(scratch, p.s_upk);
+        char *hpk[2] = {at(scratch, p.s_apk[0]), at(scratch, p.s_apk[1])};
+        if (fused) {
+            // recurrent weights and the initial hidden state in packed tile order; the second
+            // packed-h buffer only needs its zero padding
+            LSTM_TRY(pack_u_forward(p.dtype, U, upk, p.H, s));
+            LSTM_TRY(pack_rows(p.dtype, h0 ? at(h0, (size_t)l * BH * es) : nullptr, hpk[0], p.B, p.H, s));
+            LSTM_TRY(pack_rows(p.dtype, nullptr, hpk[1], p.B, p.H, s));
+        }
         for (int t = 0; t < p.T; ++t) {
             float *a_t = ax + (int64_t)t * p.B * p.G;
-            // recurrent projection added in place: A_t += h_{t-1} U^T
+            if (fused) {
+                // recurrent projection, gates, cell and hidden update in one launch
+                LSTM_TRY(step_forward_fused(p.dtype, hpk[t & 1], upk, a_t, c_state, gates + (size_t)t * p.B * p.G * es,
+                                            cs + (size_t)(t + 1) * BH * es, hs + (size_t)(t + 1) * BH * es,
+                                            hpk[(t + 1) & 1], p.B, p.H, s));
+                continue;
+            }
+            // fp32 baseline mode: recurrent projection added in place (A_t += h_{t-1} U^T), then the gates
             GemmArgs r{};
             r.A = hs + (size_t)t * BH * es; r.B = U; r.C = a_t;
             r.M = p.B; r.N = p.G; r.K = p.H;
@@ -326,7 +350,8 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
     for (int l = 0; l < p.L; ++l) {
         if (l > 0 || p.V > 0)
             LSTM_TRY(transpose_lp(p.dtype, par + p.off_W[l] * es, p.in_dim[l], wT + p.wT_off[l], p.G, p.G, p.in_dim[l], s));
-        LSTM_TRY(transpose_lp(p.dtype, par + p.off_U[l] * es, p.H, wT + p.uT_off[l], p.G, p.G, p.H, s));
+        if (p.dtype == LSTM_DTYPE_FP32)   // the 16-bit path packs U^T per layer instead
+            LSTM_TRY(transpose_lp(p.dtype, par + p.off_U[l] * es, p.H, wT + p.uT_off[l], p.G, p.G, p.H, s));
     }
 
     // head: dz = S * dloss/dz; gradients of the head and the seed for the top layer
@@ -356,8 +381,25 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
         const void *layer_in = l > 0 ? (const void *)(at(reserve, p.r_h[l - 1]) + (size_t)BH * es)
                                      : (p.V > 0 ? (const void *)at(reserve, p.r_xemb) : x);
         const int I = p.in_dim[l];
+        const bool fused = p.dtype != LSTM_DTYPE_FP32;
+        char *utpk = at(scratch, p.s_upk);
+        char *dapk[2] = {at(scratch, p.s_apk[0]), at(scratch, p.s_apk[1])};
+        if (fused) {
+            const RecurrentDims rd = recurrent_dims(p.B, p.H);
+            LSTM_TRY(pack_u_backward(p.dtype, par + p.off_U[l] * es, utpk, p.H, s));
+            for (int k = 0; k < 2; ++k) LSTM_TRY(fill_u32(dapk[k], 0, (int64_t)((rd.dapk_elems * es + 3) / 4), s));
+        }
         for (int t = p.T - 1; t >= 0; --t) {
             const bool last = t == p.T - 1;
+            if (fused) {
+                // dA_{t+1} U as four per-gate K-slices, summed by the gate kernel
+                float *part = (float *)at(scratch, p.s_part);
+                if (!last) LSTM_TRY(step_backward_gemm(p.dtype, dapk[(t + 1) & 1], utpk, part, p.B, p.H, s));
+                LSTM_TRY(gates_backward_packed(p.dtype, dh_above + (size_t)t * BH * es, part, gates + (size_t)t * p.B * p.G * es,
+                                               cs + (size_t)(t + 1) * BH * es, cs + (size_t)t * BH * es, dc_state,
+                                               dA + (size_t)t * p.B * p.G * es, dapk[t & 1], p.B, p.H, last ? 1 : 0, s));
+                continue;
+            }
             if (!last) {
                 // dh_rec = dA_{t+1} U   (contract over the 4H gate rows)
                 GemmArgs r{};
@@ -370,7 +412,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             LSTM_TRY(gates_backward(p.dtype, dh_above + (size_t)t * BH * es, last ? nullptr : dh_rec,
                                     gates + (size_t)t * p.B * p.G * es, cs + (size_t)(t + 1) * BH * es,
                                     cs + (size_t)t * BH * es, dc_state, dA + (size_t)t * p.B * p.G * es, p.B, p.H,
-                                    last ? 1 : 0, s));
+                                    last ? 1 : 0, 1, s));
         }
         char *d_below = at(scratch, p.s_dh[cur ^ 1]);
         if (l > 0 || p.V > 0) {

@@ -35,6 +35,9 @@ typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 typedef __bf16 v8b __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+// 16 bytes of packed 16-bit elements as a native vector (HIP's uint4 is a struct
+// wrapping a union, which keeps register arrays of it from being scalarised)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 struct bf16_t {
     uint16_t bits;
@@ -69,7 +72,7 @@ template <> struct Lp<_Float16> {
     static constexpr int code = LSTM_DTYPE_FP16;
     __device__ static inline float to_f(_Float16 v) { return (float)v; }
     __device__ static inline _Float16 from_f(float v) { return (_Float16)v; }  // RNE, overflow -> inf
-    __device__ static inline v16f mfma(const uint4 &a, const uint4 &b, v16f c) {
+    __device__ static inline v16f mfma(const u32x4 &a, const u32x4 &b, v16f c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
     }
 };
@@ -77,7 +80,7 @@ template <> struct Lp<bf16_t> {
     static constexpr int code = LSTM_DTYPE_BF16;
     __device__ static inline float to_f(bf16_t v) { return bf16_to_float(v); }
     __device__ static inline bf16_t from_f(float v) { return float_to_bf16(v); }
-    __device__ static inline v16f mfma(const uint4 &a, const uint4 &b, v16f c) {
+    __device__ static inline v16f mfma(const u32x4 &a, const u32x4 &b, v16f c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8b, a), __builtin_bit_cast(v8b, b), c, 0, 0, 0);
     }
 };
@@ -141,6 +144,6 @@ struct GemmArgs {
 // Enqueue one GEMM. dtype = LSTM_DTYPE_*. Returns LSTM_OK or an error status.
 int gemm_nt(int dtype, const GemmArgs &g, hipStream_t stream);
 // number of K splits gemm_nt_auto would like for this shape (>= 1)
-int gemm_pick_splits(int M, int N, int K);
+int gemm_pick_splits(int dtype, int M, int N, int K);
 
 }  // namespace lstm

@@ -32,27 +32,35 @@ struct KernArgs {
     int vec_ok;         // rows 16-byte aligned and K % 8 == 0: 16-byte global loads allowed
 };
 
-// 16-byte global load of 8 lp elements of row `row` at column k; zero outside.
-template <typename T>
-__device__ inline uint4 load8(const T *base, int64_t ld, int row, int nrows, int k, int kend, int vec_ok) {
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (row >= nrows || k >= kend) return v;
-    const T *p = base + (int64_t)row * ld + k;
-    if (vec_ok && k + 8 <= kend) {
-        v = *reinterpret_cast<const uint4 *>(p);
+// 8 consecutive lp elements of row `row` at column k; zero outside the operand.
+// VEC: aligned rows and K bounds that are multiples of 8 -> one unconditional
+// 16-byte load from a clamped address, masked afterwards, so that the loads of
+// a tile issue back to back.  Otherwise element-wise guarded loads.
+template <typename T, bool VEC>
+__device__ inline u32x4 load8(const T *base, int64_t ld, int row, int nrows, int k, int ksafe, int kend) {
+    if constexpr (VEC) {
+        const bool ok = row < nrows && k < kend;
+        const int rr = row < nrows ? row : 0;
+        const int kk = k < kend ? k : ksafe;
+        u32x4 v = *reinterpret_cast<const u32x4 *>(base + (int64_t)rr * ld + kk);
+        if (!ok) v = u32x4{0u, 0u, 0u, 0u};
+        return v;
     } else {
+        u32x4 v = u32x4{0u, 0u, 0u, 0u};
+        if (row >= nrows || k >= kend) return v;
+        const uint16_t *p = reinterpret_cast<const uint16_t *>(base + (int64_t)row * ld + k);
         uint16_t tmp[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) tmp[j] = (k + j < kend) ? reinterpret_cast<const uint16_t *>(p)[j] : (uint16_t)0;
+        for (int j = 0; j < 8; ++j) tmp[j] = (k + j < kend) ? p[j] : (uint16_t)0;
         v.x = tmp[0] | ((uint32_t)tmp[1] << 16);
         v.y = tmp[2] | ((uint32_t)tmp[3] << 16);
         v.z = tmp[4] | ((uint32_t)tmp[5] << 16);
         v.w = tmp[6] | ((uint32_t)tmp[7] << 16);
+        return v;
     }
-    return v;
 }
 
-template <typename T>
+template <typename T, bool VEC>
 __global__ __launch_bounds__(THREADS) void gemm_nt_mfma_kernel(KernArgs a) {
     __shared__ __attribute__((aligned(16))) uint16_t As[2][BM * LDS_LD];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN * LDS_LD];
@@ -76,14 +84,14 @@ __global__ __launch_bounds__(THREADS) void gemm_nt_mfma_kernel(KernArgs a) {
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
     // each thread moves 4 + 4 vectors of 8 elements per K tile
-    uint4 ra[4], rb[4];
+    u32x4 ra[4], rb[4];
     auto gload = [&](int k0) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             int v = tid + THREADS * i;
             int row = v >> 3, kv = (v & 7) * 8;
-            ra[i] = load8<T>(A, a.lda, m0 + row, a.M, k0 + kv, kend, a.vec_ok);
-            rb[i] = load8<T>(B, a.ldb, n0 + row, a.N, k0 + kv, kend, a.vec_ok);
+            ra[i] = load8<T, VEC>(A, a.lda, m0 + row, a.M, k0 + kv, kbeg, kend);
+            rb[i] = load8<T, VEC>(B, a.ldb, n0 + row, a.N, k0 + kv, kbeg, kend);
         }
     };
     auto sstore = [&](int buf) {
@@ -91,8 +99,8 @@ __global__ __launch_bounds__(THREADS) void gemm_nt_mfma_kernel(KernArgs a) {
         for (int i = 0; i < 4; ++i) {
             int v = tid + THREADS * i;
             int row = v >> 3, kv = (v & 7) * 8;
-            *reinterpret_cast<uint4 *>(&As[buf][row * LDS_LD + kv]) = ra[i];
-            *reinterpret_cast<uint4 *>(&Bs[buf][row * LDS_LD + kv]) = rb[i];
+            *reinterpret_cast<u32x4 *>(&As[buf][row * LDS_LD + kv]) = ra[i];
+            *reinterpret_cast<u32x4 *>(&Bs[buf][row * LDS_LD + kv]) = rb[i];
         }
     };
 
@@ -108,11 +116,11 @@ __global__ __launch_bounds__(THREADS) void gemm_nt_mfma_kernel(KernArgs a) {
         const int lrow = lane & 31, lk = (lane >> 5) * 8;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
-            uint4 fa[2], fb[2];
+            u32x4 fa[2], fb[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                fa[i] = *reinterpret_cast<const uint4 *>(&As[buf][(wm * 64 + i * 32 + lrow) * LDS_LD + ks * 16 + lk]);
-                fb[i] = *reinterpret_cast<const uint4 *>(&Bs[buf][(wn * 64 + i * 32 + lrow) * LDS_LD + ks * 16 + lk]);
+                fa[i] = *reinterpret_cast<const u32x4 *>(&As[buf][(wm * 64 + i * 32 + lrow) * LDS_LD + ks * 16 + lk]);
+                fb[i] = *reinterpret_cast<const u32x4 *>(&Bs[buf][(wn * 64 + i * 32 + lrow) * LDS_LD + ks * 16 + lk]);
             }
 #pragma unroll
             for (int i = 0; i < 2; ++i)
@@ -149,6 +157,177 @@ __global__ __launch_bounds__(THREADS) void gemm_nt_mfma_kernel(KernArgs a) {
                 }
             }
         }
+}
+
+// Large-tile variant for the whole-sequence GEMMs: 256x256 workgroup tile, eight
+// wavefronts (two per SIMD, so one can issue MFMAs while the other waits on LDS
+// or the barrier) in a 4x2 arrangement, each owning 64x128 (2x4 MFMA blocks,
+// 128 accumulator registers).  K tile 64, two LDS buffers (2 x 72 KB with
+// padding) and two register sets: while tile t is multiplied out of LDS, tile
+// t+1 sits in (or is arriving into) one register set and tile t+2 is in flight
+// into the other, which covers the L2/HBM latency of about two tile times.
+// The steady-state loop body is branch-free so that the wait before each
+// register->LDS copy covers only that set's loads.  Aligned operands only
+// (K, lda, ldb multiples of 8).
+constexpr int GBM = 256, GBN = 256, GBK = 64;
+constexpr int GTHREADS = 512;
+constexpr int GLD = GBK + LDS_PAD;
+constexpr int GNV = GBM * GBK / 8 / GTHREADS;   // 16-byte vectors per thread, operand and K tile (4)
+constexpr int GVPR = GBK / 8;                    // 16-byte vectors per row of a K tile
+
+struct BigSmem {
+    uint16_t a[2][GBM * GLD];
+    uint16_t b[2][GBN * GLD];
+};
+
+template <typename T>
+__global__ __launch_bounds__(GTHREADS) void gemm_nt_mfma_big_kernel(KernArgs a, int tiles_m, int tiles_n) {
+    __shared__ __attribute__((aligned(16))) BigSmem sm;
+    const T *A = reinterpret_cast<const T *>(a.A);
+    const T *B = reinterpret_cast<const T *>(a.B);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;       // 4 x 2 wavefronts of 64 x 128
+    // tile order: workgroups of one XCD (id % 8) take neighbouring tiles, and tiles
+    // are walked in bands of 8 tile rows so that a band's A and B panels stay in L2
+    const int total = tiles_m * tiles_n;
+    int lin = blockIdx.x;
+    if (total % 8 == 0) lin = (lin % 8) * (total / 8) + lin / 8;
+    const int band = 8 * tiles_n;
+    const int b0 = (lin / band) * 8;
+    const int bh = min(8, tiles_m - b0);
+    const int tm = b0 + (lin % band) % bh, tn = (lin % band) / bh;
+    const int m0 = tm * GBM, n0 = tn * GBN;
+    const int kbeg = blockIdx.z * a.k_chunk;
+    const int kend = min(a.K, kbeg + a.k_chunk);
+
+    v16f acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    // Per-thread element offsets of the rows this thread copies (32-bit: the host checks
+    // that both operands span less than 2^31 elements).  Rows outside the operand are
+    // clamped to row 0: what they contribute only reaches accumulator rows/columns that
+    // are never stored.
+    uint32_t oa[GNV], ob[GNV];
+#pragma unroll
+    for (int i = 0; i < GNV; ++i) {
+        const int v = tid + GTHREADS * i;
+        const int row = v / GVPR, kv = (v % GVPR) * 8;
+        oa[i] = (uint32_t)((m0 + row < a.M ? m0 + row : 0) * a.lda + kv + kbeg);
+        ob[i] = (uint32_t)((n0 + row < a.N ? n0 + row : 0) * a.ldb + kv + kbeg);
+    }
+    const int klen = kend > kbeg ? kend - kbeg : 0;
+    const int ntiles = (klen + GBK - 1) / GBK;
+    const int nfull = klen / GBK;                  // tiles that lie wholly inside the K range
+
+    u32x4 a0[GNV], b0r[GNV], a1[GNV], b1r[GNV];    // register set 0 and 1
+    auto gload_full = [&](u32x4 (&ra)[GNV], u32x4 (&rb)[GNV], int tile) {
+#pragma unroll
+        for (int i = 0; i < GNV; ++i) {
+            ra[i] = *reinterpret_cast<const u32x4 *>(A + (oa[i] + (uint32_t)(tile * GBK)));
+            rb[i] = *reinterpret_cast<const u32x4 *>(B + (ob[i] + (uint32_t)(tile * GBK)));
+        }
+    };
+    auto gload_any = [&](u32x4 (&ra)[GNV], u32x4 (&rb)[GNV], int tile) {   // also the last, partial tile
+#pragma unroll
+        for (int i = 0; i < GNV; ++i) {
+            const int kv = ((tid + GTHREADS * i) % GVPR) * 8;
+            const bool ok = tile * GBK + kv < klen;
+            ra[i] = ok ? *reinterpret_cast<const u32x4 *>(A + (oa[i] + (uint32_t)(tile * GBK))) : u32x4{0u, 0u, 0u, 0u};
+            rb[i] = ok ? *reinterpret_cast<const u32x4 *>(B + (ob[i] + (uint32_t)(tile * GBK))) : u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+    auto sstore = [&](const u32x4 (&ra)[GNV], const u32x4 (&rb)[GNV], int buf) {
+#pragma unroll
+        for (int i = 0; i < GNV; ++i) {
+            const int v = tid + GTHREADS * i;
+            const int row = v / GVPR, kv = (v % GVPR) * 8;
+            *reinterpret_cast<u32x4 *>(&sm.a[buf][row * GLD + kv]) = ra[i];
+            *reinterpret_cast<u32x4 *>(&sm.b[buf][row * GLD + kv]) = rb[i];
+        }
+    };
+    const int lrow = lane & 31, lk = (lane >> 5) * 8;
+    auto compute = [&](int buf) {
+        const uint16_t *as = &sm.a[buf][(wm * 64 + lrow) * GLD + lk];
+        const uint16_t *bs = &sm.b[buf][(wn * 128 + lrow) * GLD + lk];
+#pragma unroll
+        for (int ks = 0; ks < GBK / 16; ++ks) {
+            u32x4 fa[2], fb[4];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const u32x4 *>(as + i * 32 * GLD + ks * 16);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const u32x4 *>(bs + j * 32 * GLD + ks * 16);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = Lp<T>::mfma(fa[i], fb[j], acc[i][j]);
+        }
+    };
+
+    if (ntiles > 0) {
+        // prologue: tile 0 -> LDS buffer 0, tile 1 -> set 1, tile 2 -> set 0
+        gload_any(a0, b0r, 0);
+        if (ntiles > 1) gload_any(a1, b1r, 1);
+        sstore(a0, b0r, 0);
+        if (ntiles > 2) gload_any(a0, b0r, 2);
+        __syncthreads();
+        int t = 0;
+        // steady state: tiles t+3 and t+4 are full tiles, no branches in the body
+        for (; t + 4 < nfull; t += 2) {
+            compute(0);                 // tile t
+            sstore(a1, b1r, 1);         // tile t+1
+            gload_full(a1, b1r, t + 3);
+            __syncthreads();
+            compute(1);                 // tile t+1
+            sstore(a0, b0r, 0);         // tile t+2
+            gload_full(a0, b0r, t + 4);
+            __syncthreads();
+        }
+        // drain: same schedule with range checks
+        for (; t < ntiles; t += 2) {
+            compute(0);
+            if (t + 1 < ntiles) sstore(a1, b1r, 1);
+            if (t + 3 < ntiles) gload_any(a1, b1r, t + 3);
+            __syncthreads();
+            if (t + 1 < ntiles) {
+                compute(1);
+                if (t + 2 < ntiles) sstore(a0, b0r, 0);
+                if (t + 4 < ntiles) gload_any(a0, b0r, t + 4);
+                __syncthreads();
+            }
+        }
+    }
+
+    const int col_l = lane & 31, rgrp = (lane >> 5) * 4;
+    const T *bias = reinterpret_cast<const T *>(a.bias);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int col = n0 + wn * 128 + j * 32 + col_l;
+        if (col >= a.N) continue;
+        const float bv = (bias && blockIdx.z == 0) ? Lp<T>::to_f(bias[col]) : 0.0f;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + rgrp + (r & 3);
+                if (row >= a.M) continue;
+                const float v = acc[i][j][r] + bv;
+                if (a.ws) {
+                    a.ws[((int64_t)blockIdx.z * a.M + row) * a.N + col] = v;
+                } else if (a.out_lp) {
+                    reinterpret_cast<T *>(a.C)[(int64_t)row * a.ldc + col] = Lp<T>::from_f(v);
+                } else {
+                    float *c = reinterpret_cast<float *>(a.C) + (int64_t)row * a.ldc + col;
+                    *c = a.accumulate ? (*c + v) : v;
+                }
+            }
+    }
 }
 
 // fp32 baseline-mode GEMM: 64x64 tile, 16-deep K slices, 4x4 outputs per thread.
@@ -226,10 +405,18 @@ __global__ void splitk_reduce_kernel(const float *ws, int splits, int M, int N, 
     }
 }
 
+inline bool use_big_tiles(int dtype, int M, int N) { return dtype != LSTM_DTYPE_FP32 && M >= 192 && N >= 192; }
+inline bool fits_32bit(const GemmArgs &g) {
+    return (int64_t)g.M * g.lda < (int64_t)1 << 31 && (int64_t)g.N * g.ldb < (int64_t)1 << 31;
+}
+
 template <typename T>
 int launch(const GemmArgs &g, hipStream_t stream) {
     constexpr bool is_f32 = sizeof(T) == 4;
-    const int bm = is_f32 ? SBM : BM, bn = is_f32 ? SBN : BN, bk = is_f32 ? SBK : BK;
+    const bool aligned = !is_f32 && g.K % 8 == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 && ((uintptr_t)g.A % 16 == 0) &&
+                         ((uintptr_t)g.B % 16 == 0);
+    const bool big = aligned && fits_32bit(g) && use_big_tiles(is_f32 ? LSTM_DTYPE_FP32 : LSTM_DTYPE_FP16, g.M, g.N);
+    const int bm = is_f32 ? SBM : (big ? GBM : BM), bn = is_f32 ? SBN : (big ? GBN : BN), bk = is_f32 ? SBK : BK;
     KernArgs a;
     a.A = g.A; a.B = g.B; a.C = g.C; a.bias = g.bias;
     a.M = g.M; a.N = g.N; a.K = g.K;
@@ -243,18 +430,24 @@ int launch(const GemmArgs &g, hipStream_t stream) {
     }
     a.ws = splits > 1 ? g.splitk_ws : nullptr;
     a.k_chunk = k_chunk;
-    a.vec_ok = (!is_f32 && g.K % 8 == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 &&
-                ((uintptr_t)g.A % 16 == 0) && ((uintptr_t)g.B % 16 == 0)) ? 1 : 0;
-    dim3 grid((g.N + bn - 1) / bn, (g.M + bm - 1) / bm, splits);
-    if (grid.y > 65535u || grid.z > 65535u) {
-        set_error("gemm_nt: grid too large (M=%d splits=%d)", g.M, splits);
+    a.vec_ok = aligned ? 1 : 0;
+    const int tiles_m = (g.M + bm - 1) / bm, tiles_n = (g.N + bn - 1) / bn;
+    if (tiles_m > 65535 || splits > 65535 || (int64_t)tiles_m * tiles_n > 0x7fffffff) {
+        set_error("gemm_nt: grid too large (M=%d N=%d splits=%d)", g.M, g.N, splits);
         return LSTM_ERR_UNSUPPORTED;
     }
     KernelTimer timer(g.kclass, stream, 2.0 * g.M * g.N * g.K, 0.0);
     if constexpr (is_f32) {
-        hipLaunchKernelGGL(gemm_nt_f32_kernel, grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL(gemm_nt_f32_kernel, dim3(tiles_n, tiles_m, splits), dim3(256), 0, stream, a);
     } else {
-        hipLaunchKernelGGL(gemm_nt_mfma_kernel<T>, grid, dim3(THREADS), 0, stream, a);
+        if (big) {
+            hipLaunchKernelGGL(gemm_nt_mfma_big_kernel<T>, dim3(tiles_m * tiles_n, 1, splits), dim3(GTHREADS), 0, stream, a,
+                               tiles_m, tiles_n);
+        } else if (a.vec_ok) {
+            hipLaunchKernelGGL((gemm_nt_mfma_kernel<T, true>), dim3(tiles_n, tiles_m, splits), dim3(THREADS), 0, stream, a);
+        } else {
+            hipLaunchKernelGGL((gemm_nt_mfma_kernel<T, false>), dim3(tiles_n, tiles_m, splits), dim3(THREADS), 0, stream, a);
+        }
     }
     LSTM_LAUNCH_CHECK();
     if (splits > 1) {
@@ -270,12 +463,15 @@ int launch(const GemmArgs &g, hipStream_t stream) {
 
 }  // namespace
 
-int gemm_pick_splits(int M, int N, int K) {
-    // enough workgroups to cover the 256 compute units a few times over
-    const long tiles = (long)((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-    if (tiles >= 512 || K < 4 * BK) return 1;
-    long want = (1024 + tiles - 1) / tiles;
-    long maxs = K / (2 * BK);
+int gemm_pick_splits(int dtype, int M, int N, int K) {
+    // enough workgroups to cover the 256 compute units, each with a K range worth pipelining
+    const bool big = use_big_tiles(dtype, M, N);
+    const int bm = big ? GBM : BM, bn = big ? GBN : BN;
+    const long tiles = (long)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+    const long enough = big ? 256 : 512;
+    if (tiles >= enough || K < 8 * BK) return 1;
+    long want = (enough + tiles - 1) / tiles;
+    long maxs = K / (4 * BK);
     if (want > maxs) want = maxs;
     if (want > 256) want = 256;
     return want < 1 ? 1 : (int)want;

@@ -21,12 +21,12 @@ int gates_forward(int dtype, const float *A, float *c_state, void *gates, void *
                   hipStream_t s);
 
 // one time step of BPTT through the gates
-//   dh_above lp [B,H] (null = 0), dh_rec fp32 [B,H] (null = 0)
+//   dh_above lp [B,H] (null = 0), dh_rec fp32 [n_rec][B,H] partial sums (null = 0)
 //   gates lp [B,4H], c_t / c_prev lp [B,H]
 //   dc_state fp32 [B,H]: in dc carried from t+1 (ignored when first != 0), out dc for t-1
 //   dA lp [B,4H] out
 int gates_backward(int dtype, const void *dh_above, const float *dh_rec, const void *gates, const void *c_t,
-                   const void *c_prev, float *dc_state, void *dA, int B, int H, int first, hipStream_t s);
+                   const void *c_prev, float *dc_state, void *dA, int B, int H, int first, int n_rec, hipStream_t s);
 
 // out[C,R] = in[R,C]^T for lp elements
 int transpose_lp(int dtype, const void *in, int64_t ld_in, void *out, int64_t ld_out, int R, int C, hipStream_t s);
@@ -54,5 +54,26 @@ int embed_scatter_add(int dtype, const int32_t *ids, const void *dX, float *dE32
 int cast_f32_to_lp(int dtype, const float *in, void *out, int64_t n, hipStream_t s);
 // copy final states out
 int copy_state(int dtype, const void *h_src, const float *c_src, void *h_dst, float *c_dst, int64_t n, hipStream_t s);
+
+// ---- fused per-time-step kernels (half / bfloat16 only), operands in packed tile order
+struct RecurrentDims {
+    int n_mt, n_hb, n_nt, nkc;          // batch tiles of 64, hidden blocks of 32, unit tiles of 128, K chunks of 64
+    size_t upk_elems, utpk_elems;        // packed U for the forward / backward kernels
+    size_t hpk_elems, dapk_elems;        // packed h (one step) / packed dA (one step)
+    size_t partial_bytes;                // fp32 [4][B,H] recurrent partial sums
+};
+RecurrentDims recurrent_dims(int B, int H);
+int pack_u_forward(int dtype, const void *U, void *Upk, int H, hipStream_t s);
+int pack_u_backward(int dtype, const void *U, void *UTpk, int H, hipStream_t s);
+// hpk = packed copy of row-major h [B,H] (h null = zeros); also clears the padding
+int pack_rows(int dtype, const void *h, void *hpk, int B, int H, hipStream_t s);
+// forward: gates, c, h of one step from packed h_prev, packed U and the step's input projection Ax (fp32, bias included)
+int step_forward_fused(int dtype, const void *hpk_prev, const void *Upk, const float *Ax, float *c_state, void *gates,
+                       void *c_out, void *h_out, void *hpk_next, int B, int H, hipStream_t s);
+// backward: partials[q][B,H] = dA_next[:, gate q rows] * U[gate q rows, :] for q = 0..3
+int step_backward_gemm(int dtype, const void *dApk, const void *UTpk, float *partials, int B, int H, hipStream_t s);
+// BPTT through the gates; dA written row-major and packed
+int gates_backward_packed(int dtype, const void *dh_above, const float *partials, const void *gates, const void *c_t,
+                          const void *c_prev, float *dc_state, void *dA, void *dApk, int B, int H, int first, hipStream_t s);
 
 }  // namespace lstm

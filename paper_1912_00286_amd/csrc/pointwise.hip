@@ -73,7 +73,7 @@ __global__ void gates_forward_kernel(const float *A, float *c_state, T *gates, T
 
 template <typename T>
 __global__ void gates_backward_kernel(const T *dh_above, const float *dh_rec, const T *gates, const T *c_t,
-                                      const T *c_prev, float *dc_state, T *dA, int B, int H, int first) {
+                                      const T *c_prev, float *dc_state, T *dA, int B, int H, int first, int n_rec) {
     const int64_t n = (int64_t)B * H;
     const int G = 4 * H;
     for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x) {
@@ -83,7 +83,8 @@ __global__ void gates_backward_kernel(const T *dh_above, const float *dh_rec, co
         const float g = Lp<T>::to_f(gr[2 * H + j]), o = Lp<T>::to_f(gr[3 * H + j]);
         const float tc = Act<T>::tanh(Lp<T>::to_f(c_t[e]));
         float dh = dh_above ? Lp<T>::to_f(dh_above[e]) : 0.0f;
-        if (dh_rec) dh += dh_rec[e];
+        if (dh_rec)
+            for (int q = 0; q < n_rec; ++q) dh += dh_rec[(int64_t)q * n + e];
         const float dcr = first ? 0.0f : dc_state[e];
         const float d_o = dh * tc;
         const float dc = dcr + dh * o * (1.0f - tc * tc);
@@ -282,12 +283,12 @@ int gates_forward(int dtype, const float *A, float *c_state, void *gates, void *
 }
 
 int gates_backward(int dtype, const void *dh_above, const float *dh_rec, const void *gates, const void *c_t,
-                   const void *c_prev, float *dc_state, void *dA, int B, int H, int first, hipStream_t s) {
+                   const void *c_prev, float *dc_state, void *dA, int B, int H, int first, int n_rec, hipStream_t s) {
     KernelTimer timer(KC_POINTWISE, s, 0.0, (double)B * H * (8.0 + 4.0 + 11.0 * sizeof(uint16_t)));
     const int64_t n = (int64_t)B * H;
     LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(gates_backward_kernel<T>, dim3(blocks_for(n, 256, 8192)), dim3(256), 0, s,
                                                (const T *)dh_above, dh_rec, (const T *)gates, (const T *)c_t,
-                                               (const T *)c_prev, dc_state, (T *)dA, B, H, first));
+                                               (const T *)c_prev, dc_state, (T *)dA, B, H, first, n_rec));
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
