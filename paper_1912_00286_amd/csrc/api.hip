@@ -424,24 +424,37 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             d.out_lp = 1; d.kclass = KC_GEMM_BATCHED;
             LSTM_TRY(gemm_nt(p.dtype, d, s));
         }
-        // weight gradients, contracted over all T*B rows with fp32 accumulation
-        LSTM_TRY(transpose_lp(p.dtype, dA, p.G, dAT, TB, TB, p.G, s));
-        LSTM_TRY(transpose_lp(p.dtype, layer_in, I, xT, TB, TB, I, s));
+        // weight gradients dW = dA^T X and dU = dA^T H_prev, contracted over all T*B rows with
+        // fp32 accumulation.  Preferred: the kernel that reads both operands as they lie in
+        // memory; otherwise explicit transposes feed the K-contiguous kernel.
         GemmArgs w{};
-        w.A = dAT; w.B = xT; w.C = grd + p.off_W[l] * es;
-        w.M = p.G; w.N = I; w.K = TB;
-        w.lda = TB; w.ldb = TB; w.ldc = I;
+        w.M = p.G; w.N = I; w.K = TB; w.ldc = I;
+        w.C = grd + p.off_W[l] * es;
         w.kclass = KC_GEMM_BATCHED;
         w.out_lp = 1; w.splitk_ws = splitk; w.splits = p.split_w[l];
-        LSTM_TRY(gemm_nt(p.dtype, w, s));
-        LSTM_TRY(transpose_lp(p.dtype, hs, p.H, xT, TB, TB, p.H, s));   // h_0..h_{T-1}
-        GemmArgs u{};
-        u.A = dAT; u.B = xT; u.C = grd + p.off_U[l] * es;
-        u.M = p.G; u.N = p.H; u.K = TB;
-        u.lda = TB; u.ldb = TB; u.ldc = p.H;
-        u.kclass = KC_GEMM_BATCHED;
-        u.out_lp = 1; u.splitk_ws = splitk; u.splits = p.split_u[l];
-        LSTM_TRY(gemm_nt(p.dtype, u, s));
+        GemmArgs u = w;
+        u.N = p.H; u.ldc = p.H;
+        u.C = grd + p.off_U[l] * es;
+        u.splits = p.split_u[l];
+        GemmArgs wt = w, ut = u;
+        wt.A = dA; wt.lda = p.G; wt.B = layer_in; wt.ldb = I;
+        ut.A = dA; ut.lda = p.G; ut.B = hs; ut.ldb = p.H;                 // h_0..h_{T-1}
+        const bool w_tn = gemm_tn_supported(p.dtype, wt), u_tn = gemm_tn_supported(p.dtype, ut);
+        if (!w_tn || !u_tn) LSTM_TRY(transpose_lp(p.dtype, dA, p.G, dAT, TB, TB, p.G, s));
+        if (w_tn) {
+            LSTM_TRY(gemm_tn(p.dtype, wt, s));
+        } else {
+            LSTM_TRY(transpose_lp(p.dtype, layer_in, I, xT, TB, TB, I, s));
+            w.A = dAT; w.B = xT; w.lda = TB; w.ldb = TB;
+            LSTM_TRY(gemm_nt(p.dtype, w, s));
+        }
+        if (u_tn) {
+            LSTM_TRY(gemm_tn(p.dtype, ut, s));
+        } else {
+            LSTM_TRY(transpose_lp(p.dtype, hs, p.H, xT, TB, TB, p.H, s));
+            u.A = dAT; u.B = xT; u.lda = TB; u.ldb = TB;
+            LSTM_TRY(gemm_nt(p.dtype, u, s));
+        }
         LSTM_TRY(colsum(p.dtype, dA, p.G, TB, p.G, nullptr, nullptr, colpart, grd + p.off_b[l] * es, s));
         cur ^= 1;
         dh_above = d_below;

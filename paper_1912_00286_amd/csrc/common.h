@@ -143,7 +143,11 @@ struct GemmArgs {
 
 // Enqueue one GEMM. dtype = LSTM_DTYPE_*. Returns LSTM_OK or an error status.
 int gemm_nt(int dtype, const GemmArgs &g, hipStream_t stream);
-// number of K splits gemm_nt_auto would like for this shape (>= 1)
+// C[M,N] = A^T B with A[K,M] (lda) and B[K,N] (ldb): contraction over the rows of both
+// operands, no transposed copies.  16-bit types, aligned shapes with M, N >= 192 only.
+bool gemm_tn_supported(int dtype, const GemmArgs &g);
+int gemm_tn(int dtype, const GemmArgs &g, hipStream_t stream);
+// number of K splits gemm_nt / gemm_tn would like for this shape (>= 1)
 int gemm_pick_splits(int dtype, int M, int N, int K);
 
 }  // namespace lstm

@@ -167,21 +167,49 @@ __global__ __launch_bounds__(THREADS) void gemm_nt_mfma_kernel(KernArgs a) {
 // t+1 sits in (or is arriving into) one register set and tile t+2 is in flight
 // into the other, which covers the L2/HBM latency of about two tile times.
 // The steady-state loop body is branch-free so that the wait before each
-// register->LDS copy covers only that set's loads.  Aligned operands only
-// (K, lda, ldb multiples of 8).
+// register->LDS copy covers only that set's loads.
+//
+// Two operand layouts:
+//   TRANS = false: C = A B^T with A[M,K], B[N,K], K contiguous (forward
+//                  projection, data gradient).  LDS rows are operand rows; one
+//                  16-byte LDS read is one MFMA fragment.
+//   TRANS = true : C = A^T B with A[K,M], B[K,N], M / N contiguous (weight
+//                  gradients dA^T X, contraction over all T*B rows).  The tile
+//                  is kept as it lies in memory ([k][m]) and the fragments are
+//                  read with the LDS transpose read, which hands lane i of a
+//                  16-lane group the 4 k-values of column i: no transposed copy
+//                  of the activations is ever made.
+// Aligned operands only (every leading dimension, and K resp. M/N, a multiple of 8).
 constexpr int GBM = 256, GBN = 256, GBK = 64;
 constexpr int GTHREADS = 512;
-constexpr int GLD = GBK + LDS_PAD;
+constexpr int GLD = GBK + LDS_PAD;               // row pitch, rows = operand rows
+constexpr int GLDT = GBM + 32;                   // row pitch, rows = k (transposed form)
 constexpr int GNV = GBM * GBK / 8 / GTHREADS;   // 16-byte vectors per thread, operand and K tile (4)
-constexpr int GVPR = GBK / 8;                    // 16-byte vectors per row of a K tile
+constexpr int GVPR = GBK / 8;                    // 16-byte vectors per operand row of a K tile
+constexpr int GVPK = GBM / 8;                    // 16-byte vectors per k row (transposed form)
+static_assert(GBM * GLD == GBK * GLDT, "both layouts use the same LDS footprint");
 
 struct BigSmem {
     uint16_t a[2][GBM * GLD];
     uint16_t b[2][GBN * GLD];
 };
 
-template <typename T>
-__global__ __launch_bounds__(GTHREADS) void gemm_nt_mfma_big_kernel(KernArgs a, int tiles_m, int tiles_n) {
+typedef short v4s __attribute__((ext_vector_type(4)));
+
+// MFMA fragment (row = lane % 32 of the 32-row block starting at column m0 of the
+// [k][m] tile, k = 8 * (lane / 32) + 0..7 of k-step ks) via two transpose reads.
+__device__ __forceinline__ u32x4 read_frag_tr(const uint16_t *tile, int m0, int ks, int lane) {
+    const int g = lane >> 4, i = lane & 15;
+    const uint16_t *p = tile + (ks * 16 + 8 * (g >> 1) + (i >> 2)) * GLDT + m0 + 16 * (g & 1) + 4 * (i & 3);
+    typedef __attribute__((address_space(3))) v4s *lds_v4s;
+    const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)p);
+    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(p + 4 * GLDT));
+    struct { v4s l, h; } both = {lo, hi};
+    return __builtin_bit_cast(u32x4, both);
+}
+
+template <typename T, bool TRANS>
+__global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a, int tiles_m, int tiles_n) {
     __shared__ __attribute__((aligned(16))) BigSmem sm;
     const T *A = reinterpret_cast<const T *>(a.A);
     const T *B = reinterpret_cast<const T *>(a.B);
@@ -210,17 +238,25 @@ __global__ __launch_bounds__(GTHREADS) void gemm_nt_mfma_big_kernel(KernArgs a, 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // Per-thread element offsets of the rows this thread copies (32-bit: the host checks
-    // that both operands span less than 2^31 elements).  Rows outside the operand are
-    // clamped to row 0: what they contribute only reaches accumulator rows/columns that
-    // are never stored.
+    // Per-thread element offsets of the vectors this thread copies (32-bit: the host checks
+    // that both operands span less than 2^31 elements).  Rows (columns, in the transposed
+    // form) outside the operand are clamped to the first one: what they contribute only
+    // reaches accumulator rows/columns that are never stored.
     uint32_t oa[GNV], ob[GNV];
+    const uint32_t tile_step_a = TRANS ? (uint32_t)(GBK * a.lda) : (uint32_t)GBK;
+    const uint32_t tile_step_b = TRANS ? (uint32_t)(GBK * a.ldb) : (uint32_t)GBK;
 #pragma unroll
     for (int i = 0; i < GNV; ++i) {
         const int v = tid + GTHREADS * i;
-        const int row = v / GVPR, kv = (v % GVPR) * 8;
-        oa[i] = (uint32_t)((m0 + row < a.M ? m0 + row : 0) * a.lda + kv + kbeg);
-        ob[i] = (uint32_t)((n0 + row < a.N ? n0 + row : 0) * a.ldb + kv + kbeg);
+        if constexpr (TRANS) {
+            const int krow = v / GVPK, mv = (v % GVPK) * 8;
+            oa[i] = (uint32_t)((kbeg + krow) * a.lda + (m0 + mv < a.M ? m0 + mv : 0));
+            ob[i] = (uint32_t)((kbeg + krow) * a.ldb + (n0 + mv < a.N ? n0 + mv : 0));
+        } else {
+            const int row = v / GVPR, kv = (v % GVPR) * 8;
+            oa[i] = (uint32_t)((m0 + row < a.M ? m0 + row : 0) * a.lda + kv + kbeg);
+            ob[i] = (uint32_t)((n0 + row < a.N ? n0 + row : 0) * a.ldb + kv + kbeg);
+        }
     }
     const int klen = kend > kbeg ? kend - kbeg : 0;
     const int ntiles = (klen + GBK - 1) / GBK;
@@ -230,39 +266,50 @@ __global__ __launch_bounds__(GTHREADS) void gemm_nt_mfma_big_kernel(KernArgs a, 
     auto gload_full = [&](u32x4 (&ra)[GNV], u32x4 (&rb)[GNV], int tile) {
 #pragma unroll
         for (int i = 0; i < GNV; ++i) {
-            ra[i] = *reinterpret_cast<const u32x4 *>(A + (oa[i] + (uint32_t)(tile * GBK)));
-            rb[i] = *reinterpret_cast<const u32x4 *>(B + (ob[i] + (uint32_t)(tile * GBK)));
+            ra[i] = *reinterpret_cast<const u32x4 *>(A + (oa[i] + (uint32_t)tile * tile_step_a));
+            rb[i] = *reinterpret_cast<const u32x4 *>(B + (ob[i] + (uint32_t)tile * tile_step_b));
         }
     };
     auto gload_any = [&](u32x4 (&ra)[GNV], u32x4 (&rb)[GNV], int tile) {   // also the last, partial tile
 #pragma unroll
         for (int i = 0; i < GNV; ++i) {
-            const int kv = ((tid + GTHREADS * i) % GVPR) * 8;
-            const bool ok = tile * GBK + kv < klen;
-            ra[i] = ok ? *reinterpret_cast<const u32x4 *>(A + (oa[i] + (uint32_t)(tile * GBK))) : u32x4{0u, 0u, 0u, 0u};
-            rb[i] = ok ? *reinterpret_cast<const u32x4 *>(B + (ob[i] + (uint32_t)(tile * GBK))) : u32x4{0u, 0u, 0u, 0u};
+            const int v = tid + GTHREADS * i;
+            const int kk = TRANS ? v / GVPK : (v % GVPR) * 8;                // first k of this vector inside the tile
+            const bool ok = tile * GBK + kk < klen;
+            ra[i] = ok ? *reinterpret_cast<const u32x4 *>(A + (oa[i] + (uint32_t)tile * tile_step_a)) : u32x4{0u, 0u, 0u, 0u};
+            rb[i] = ok ? *reinterpret_cast<const u32x4 *>(B + (ob[i] + (uint32_t)tile * tile_step_b)) : u32x4{0u, 0u, 0u, 0u};
         }
     };
     auto sstore = [&](const u32x4 (&ra)[GNV], const u32x4 (&rb)[GNV], int buf) {
 #pragma unroll
         for (int i = 0; i < GNV; ++i) {
             const int v = tid + GTHREADS * i;
-            const int row = v / GVPR, kv = (v % GVPR) * 8;
-            *reinterpret_cast<u32x4 *>(&sm.a[buf][row * GLD + kv]) = ra[i];
-            *reinterpret_cast<u32x4 *>(&sm.b[buf][row * GLD + kv]) = rb[i];
+            const int off = TRANS ? (v / GVPK) * GLDT + (v % GVPK) * 8 : (v / GVPR) * GLD + (v % GVPR) * 8;
+            *reinterpret_cast<u32x4 *>(&sm.a[buf][off]) = ra[i];
+            *reinterpret_cast<u32x4 *>(&sm.b[buf][off]) = rb[i];
         }
     };
     const int lrow = lane & 31, lk = (lane >> 5) * 8;
-    auto compute = [&](int buf) {
-        const uint16_t *as = &sm.a[buf][(wm * 64 + lrow) * GLD + lk];
-        const uint16_t *bs = &sm.b[buf][(wn * 128 + lrow) * GLD + lk];
+    auto read_frags = [&](u32x4 (&fa)[2], u32x4 (&fb)[4], int buf, int ks) {
+        if constexpr (TRANS) {
 #pragma unroll
-        for (int ks = 0; ks < GBK / 16; ++ks) {
-            u32x4 fa[2], fb[4];
+            for (int i = 0; i < 2; ++i) fa[i] = read_frag_tr(sm.a[buf], wm * 64 + i * 32, ks, lane);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) fb[j] = read_frag_tr(sm.b[buf], wn * 128 + j * 32, ks, lane);
+        } else {
+            const uint16_t *as = &sm.a[buf][(wm * 64 + lrow) * GLD + lk];
+            const uint16_t *bs = &sm.b[buf][(wn * 128 + lrow) * GLD + lk];
 #pragma unroll
             for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const u32x4 *>(as + i * 32 * GLD + ks * 16);
 #pragma unroll
             for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const u32x4 *>(bs + j * 32 * GLD + ks * 16);
+        }
+    };
+    auto compute = [&](int buf) {
+#pragma unroll
+        for (int ks = 0; ks < GBK / 16; ++ks) {
+            u32x4 fa[2], fb[4];
+            read_frags(fa, fb, buf, ks);
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -406,8 +453,20 @@ __global__ void splitk_reduce_kernel(const float *ws, int splits, int M, int N, 
 }
 
 inline bool use_big_tiles(int dtype, int M, int N) { return dtype != LSTM_DTYPE_FP32 && M >= 192 && N >= 192; }
-inline bool fits_32bit(const GemmArgs &g) {
-    return (int64_t)g.M * g.lda < (int64_t)1 << 31 && (int64_t)g.N * g.ldb < (int64_t)1 << 31;
+inline bool fits_32bit(int64_t rows_a, int64_t lda, int64_t rows_b, int64_t ldb) {
+    return rows_a * lda < (int64_t)1 << 31 && rows_b * ldb < (int64_t)1 << 31;
+}
+
+template <typename T>
+int finish_splitk(const GemmArgs &g, int splits, hipStream_t stream) {
+    if (splits <= 1) return LSTM_OK;
+    const int64_t total = (int64_t)g.M * g.N;
+    int blocks = (int)((total + 255) / 256);
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(splitk_reduce_kernel<T>, dim3(blocks), dim3(256), 0, stream, g.splitk_ws, splits, g.M, g.N, g.C,
+                       g.ldc, g.out_lp, g.accumulate);
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
 }
 
 template <typename T>
@@ -415,7 +474,8 @@ int launch(const GemmArgs &g, hipStream_t stream) {
     constexpr bool is_f32 = sizeof(T) == 4;
     const bool aligned = !is_f32 && g.K % 8 == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 && ((uintptr_t)g.A % 16 == 0) &&
                          ((uintptr_t)g.B % 16 == 0);
-    const bool big = aligned && fits_32bit(g) && use_big_tiles(is_f32 ? LSTM_DTYPE_FP32 : LSTM_DTYPE_FP16, g.M, g.N);
+    const bool big = aligned && fits_32bit(g.M, g.lda, g.N, g.ldb) &&
+                     use_big_tiles(is_f32 ? LSTM_DTYPE_FP32 : LSTM_DTYPE_FP16, g.M, g.N);
     const int bm = is_f32 ? SBM : (big ? GBM : BM), bn = is_f32 ? SBN : (big ? GBN : BN), bk = is_f32 ? SBK : BK;
     KernArgs a;
     a.A = g.A; a.B = g.B; a.C = g.C; a.bias = g.bias;
@@ -441,8 +501,8 @@ int launch(const GemmArgs &g, hipStream_t stream) {
         hipLaunchKernelGGL(gemm_nt_f32_kernel, dim3(tiles_n, tiles_m, splits), dim3(256), 0, stream, a);
     } else {
         if (big) {
-            hipLaunchKernelGGL(gemm_nt_mfma_big_kernel<T>, dim3(tiles_m * tiles_n, 1, splits), dim3(GTHREADS), 0, stream, a,
-                               tiles_m, tiles_n);
+            hipLaunchKernelGGL((gemm_mfma_big_kernel<T, false>), dim3(tiles_m * tiles_n, 1, splits), dim3(GTHREADS), 0, stream,
+                               a, tiles_m, tiles_n);
         } else if (a.vec_ok) {
             hipLaunchKernelGGL((gemm_nt_mfma_kernel<T, true>), dim3(tiles_n, tiles_m, splits), dim3(THREADS), 0, stream, a);
         } else {
@@ -450,15 +510,32 @@ int launch(const GemmArgs &g, hipStream_t stream) {
         }
     }
     LSTM_LAUNCH_CHECK();
+    return finish_splitk<T>(g, splits, stream);
+}
+
+// C[M,N] = A^T B with A[K,M] (lda), B[K,N] (ldb); only the large-tile kernel implements it
+template <typename T>
+int launch_tn(const GemmArgs &g, hipStream_t stream) {
+    KernArgs a;
+    a.A = g.A; a.B = g.B; a.C = g.C; a.bias = nullptr;
+    a.M = g.M; a.N = g.N; a.K = g.K;
+    a.lda = g.lda; a.ldb = g.ldb; a.ldc = g.ldc;
+    a.out_lp = g.out_lp; a.accumulate = g.accumulate;
+    int splits = (g.splitk_ws && g.splits > 1) ? g.splits : 1;
+    int k_chunk = g.K;
     if (splits > 1) {
-        const int64_t total = (int64_t)g.M * g.N;
-        int blocks = (int)((total + 255) / 256);
-        if (blocks > 4096) blocks = 4096;
-        hipLaunchKernelGGL(splitk_reduce_kernel<T>, dim3(blocks), dim3(256), 0, stream, g.splitk_ws, splits, g.M, g.N,
-                           g.C, g.ldc, g.out_lp, g.accumulate);
-        LSTM_LAUNCH_CHECK();
+        k_chunk = ((g.K + splits - 1) / splits + GBK - 1) / GBK * GBK;
+        splits = (g.K + k_chunk - 1) / k_chunk;
     }
-    return LSTM_OK;
+    a.ws = splits > 1 ? g.splitk_ws : nullptr;
+    a.k_chunk = k_chunk;
+    a.vec_ok = 1;
+    const int tiles_m = (g.M + GBM - 1) / GBM, tiles_n = (g.N + GBN - 1) / GBN;
+    KernelTimer timer(g.kclass, stream, 2.0 * g.M * g.N * g.K, 0.0);
+    hipLaunchKernelGGL((gemm_mfma_big_kernel<T, true>), dim3(tiles_m * tiles_n, 1, splits), dim3(GTHREADS), 0, stream, a,
+                       tiles_m, tiles_n);
+    LSTM_LAUNCH_CHECK();
+    return finish_splitk<T>(g, splits, stream);
 }
 
 }  // namespace
@@ -490,6 +567,24 @@ int gemm_nt(int dtype, const GemmArgs &g, hipStream_t stream) {
     }
     set_error("gemm_nt: bad dtype %d", dtype);
     return LSTM_ERR_INVALID;
+}
+
+bool gemm_tn_supported(int dtype, const GemmArgs &g) {
+    return dtype != LSTM_DTYPE_FP32 && g.M % 8 == 0 && g.N % 8 == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 &&
+           (uintptr_t)g.A % 16 == 0 && (uintptr_t)g.B % 16 == 0 && g.M >= 192 && g.N >= 192 && g.K >= 1 &&
+           fits_32bit(g.K, g.lda, g.K, g.ldb);
+}
+
+int gemm_tn(int dtype, const GemmArgs &g, hipStream_t stream) {
+    if (!gemm_tn_supported(dtype, g)) {
+        set_error("gemm_tn: unsupported shape or alignment (M=%d N=%d K=%d)", g.M, g.N, g.K);
+        return LSTM_ERR_UNSUPPORTED;
+    }
+    if (!g.A || !g.B || !g.C) {
+        set_error("gemm_tn: null operand");
+        return LSTM_ERR_INVALID;
+    }
+    return dtype == LSTM_DTYPE_FP16 ? launch_tn<_Float16>(g, stream) : launch_tn<bf16_t>(g, stream);
 }
 
 }  // namespace lstm

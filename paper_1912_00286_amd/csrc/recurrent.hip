@@ -168,11 +168,24 @@ __global__ __launch_bounds__(256) void lstm_step_forward_kernel(FwdArgs a) {
     packed_mainloop<T>(reinterpret_cast<const uint16_t *>(a.hpk_prev) + (int64_t)mt * a.nkc * A_CHUNK,
                        reinterpret_cast<const uint16_t *>(a.Upk) + (int64_t)hb * a.nkc * B_CHUNK, c0, c1, (int)blockIdx.x,
                        lane, acc);
-    float pre[8][NBLK];
-    reduce_waves(smem, wave, lane, acc, pre);
-
+    // The step's input projection and the previous cell state do not depend on the GEMM:
+    // request them before the cross-wavefront reduction so that their latency hides behind
+    // it.  Addresses are clamped into the tensors; out-of-range lanes never store.
     const int mb = wave >> 1, rh = (wave & 1) * 8;
     const int j = j0 + (lane & 31);
+    const int jc = min(j, H - 1);
+    float axv[8][4], cprev[8];
+#pragma unroll
+    for (int rr = 0; rr < 8; ++rr) {
+        const int r = rh + rr;
+        const int row = min(m0 + mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), a.B - 1);
+        const float *ax = a.Ax + (int64_t)row * G + jc;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) axv[rr][g] = ax[g * H];
+        cprev[rr] = a.c_state[(int64_t)row * H + jc];
+    }
+    float pre[8][NBLK];
+    reduce_waves(smem, wave, lane, acc, pre);
     if (j >= H) return;
     T *gates = reinterpret_cast<T *>(a.gates);
     T *c_out = reinterpret_cast<T *>(a.c_out);
@@ -183,15 +196,14 @@ __global__ __launch_bounds__(256) void lstm_step_forward_kernel(FwdArgs a) {
         const int r = rh + rr;
         const int rl = mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
         const int row = m0 + rl;
-        if (row >= a.B) continue;
-        const float *ax = a.Ax + (int64_t)row * G + j;
-        const float gi = sigmoidf_dev(pre[rr][0] + ax[0]);
-        const float gf = sigmoidf_dev(pre[rr][1] + ax[H]);
-        const float gg = tanhf_dev(pre[rr][2] + ax[2 * H]);
-        const float go = sigmoidf_dev(pre[rr][3] + ax[3 * H]);
-        const int64_t e = (int64_t)row * H + j;
-        const float c = gf * a.c_state[e] + gi * gg;
+        const float gi = sigmoidf_dev(pre[rr][0] + axv[rr][0]);
+        const float gf = sigmoidf_dev(pre[rr][1] + axv[rr][1]);
+        const float gg = tanhf_dev(pre[rr][2] + axv[rr][2]);
+        const float go = sigmoidf_dev(pre[rr][3] + axv[rr][3]);
+        const float c = gf * cprev[rr] + gi * gg;
         const T h = Lp<T>::from_f(go * tanhf_dev(c));
+        if (row >= a.B) continue;
+        const int64_t e = (int64_t)row * H + j;
         a.c_state[e] = c;
         T *gr = gates + (int64_t)row * G + j;
         gr[0] = Lp<T>::from_f(gi);
@@ -248,39 +260,88 @@ __global__ __launch_bounds__(256) void lstm_step_backward_gemm_kernel(BwdArgs a)
 
 // BPTT through the gates of one step; sums the four recurrent partials, writes
 // dA row-major (for the whole-sequence GEMMs) and packed (A operand of the next
-// recurrent GEMM).
-template <typename T>
+// recurrent GEMM).  VEC: H % 8 == 0 and 16-byte aligned tensors; one thread
+// owns 8 consecutive hidden units of one batch row (16-byte loads and stores,
+// and its 8 packed outputs are one 16-byte fragment slot).
+template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void gates_backward_packed_kernel(const T *dh_above, const float *partials, const T *gates,
                                                                     const T *c_t, const T *c_prev, float *dc_state, T *dA,
                                                                     T *dApk, int B, int H, int nkc, int first) {
+    constexpr int W = VEC ? 8 : 1;
     const int64_t n = (int64_t)B * H;
     const int G = 4 * H;
-    for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x) {
-        const int b = (int)(e / H), j = (int)(e % H);
-        const T *gr = gates + (int64_t)b * G + j;
-        const float i = Lp<T>::to_f(gr[0]), f = Lp<T>::to_f(gr[H]);
-        const float g = Lp<T>::to_f(gr[2 * H]), o = Lp<T>::to_f(gr[3 * H]);
-        const float tc = tanhf_dev(Lp<T>::to_f(c_t[e]));
-        float dh = Lp<T>::to_f(dh_above[e]);
-        float dcr = 0.0f;
-        if (!first) {
-            dh += (partials[e] + partials[n + e]) + (partials[2 * n + e] + partials[3 * n + e]);
-            dcr = dc_state[e];
+    const int64_t gs = (int64_t)nkc * A_CHUNK;
+    for (int64_t e0 = (blockIdx.x * (int64_t)blockDim.x + threadIdx.x) * W; e0 < n; e0 += (int64_t)gridDim.x * blockDim.x * W) {
+        const int b = (int)(e0 / H), j0 = (int)(e0 % H);
+        __attribute__((aligned(16))) T vi[W], vf[W], vg[W], vo[W], vct[W], vcp[W], vdh[W];
+        __attribute__((aligned(16))) float p0[W], p1[W], p2[W], p3[W], dcs[W];
+        const T *gr = gates + (int64_t)b * G + j0;
+        if constexpr (VEC) {
+            *reinterpret_cast<u32x4 *>(vi) = *reinterpret_cast<const u32x4 *>(gr);
+            *reinterpret_cast<u32x4 *>(vf) = *reinterpret_cast<const u32x4 *>(gr + H);
+            *reinterpret_cast<u32x4 *>(vg) = *reinterpret_cast<const u32x4 *>(gr + 2 * H);
+            *reinterpret_cast<u32x4 *>(vo) = *reinterpret_cast<const u32x4 *>(gr + 3 * H);
+            *reinterpret_cast<u32x4 *>(vct) = *reinterpret_cast<const u32x4 *>(c_t + e0);
+            *reinterpret_cast<u32x4 *>(vcp) = *reinterpret_cast<const u32x4 *>(c_prev + e0);
+            *reinterpret_cast<u32x4 *>(vdh) = *reinterpret_cast<const u32x4 *>(dh_above + e0);
+            if (!first) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    *reinterpret_cast<u32x4 *>(p0 + 4 * h) = *reinterpret_cast<const u32x4 *>(partials + e0 + 4 * h);
+                    *reinterpret_cast<u32x4 *>(p1 + 4 * h) = *reinterpret_cast<const u32x4 *>(partials + n + e0 + 4 * h);
+                    *reinterpret_cast<u32x4 *>(p2 + 4 * h) = *reinterpret_cast<const u32x4 *>(partials + 2 * n + e0 + 4 * h);
+                    *reinterpret_cast<u32x4 *>(p3 + 4 * h) = *reinterpret_cast<const u32x4 *>(partials + 3 * n + e0 + 4 * h);
+                    *reinterpret_cast<u32x4 *>(dcs + 4 * h) = *reinterpret_cast<const u32x4 *>(dc_state + e0 + 4 * h);
+                }
+            }
+        } else {
+            vi[0] = gr[0]; vf[0] = gr[H]; vg[0] = gr[2 * H]; vo[0] = gr[3 * H];
+            vct[0] = c_t[e0]; vcp[0] = c_prev[e0]; vdh[0] = dh_above[e0];
+            if (!first) {
+                p0[0] = partials[e0]; p1[0] = partials[n + e0]; p2[0] = partials[2 * n + e0]; p3[0] = partials[3 * n + e0];
+                dcs[0] = dc_state[e0];
+            }
         }
-        const float d_o = dh * tc;
-        const float dc = dcr + dh * o * (1.0f - tc * tc);
-        const float di = dc * g, dg = dc * i, df = dc * Lp<T>::to_f(c_prev[e]);
-        dc_state[e] = dc * f;
-        const T v0 = Lp<T>::from_f(di * i * (1.0f - i));
-        const T v1 = Lp<T>::from_f(df * f * (1.0f - f));
-        const T v2 = Lp<T>::from_f(dg * (1.0f - g * g));
-        const T v3 = Lp<T>::from_f(d_o * o * (1.0f - o));
-        T *da = dA + (int64_t)b * G + j;
-        da[0] = v0; da[H] = v1; da[2 * H] = v2; da[3 * H] = v3;
-        // packed: [b / 64][gate][j / 64] chunk, fragment order inside
-        T *pk = dApk + (((int64_t)(b >> 6) * 4) * nkc + (j >> 6)) * A_CHUNK + frag_offset(b & 63, j & 63, 2);
-        const int64_t gs = (int64_t)nkc * A_CHUNK;
-        pk[0] = v0; pk[gs] = v1; pk[2 * gs] = v2; pk[3 * gs] = v3;
+        __attribute__((aligned(16))) T o0[W], o1[W], o2[W], o3[W];
+        __attribute__((aligned(16))) float dcn[W];
+#pragma unroll
+        for (int k = 0; k < W; ++k) {
+            const float i = Lp<T>::to_f(vi[k]), f = Lp<T>::to_f(vf[k]), g = Lp<T>::to_f(vg[k]), o = Lp<T>::to_f(vo[k]);
+            const float tc = tanhf_dev(Lp<T>::to_f(vct[k]));
+            float dh = Lp<T>::to_f(vdh[k]);
+            float dcr = 0.0f;
+            if (!first) {
+                dh += (p0[k] + p1[k]) + (p2[k] + p3[k]);
+                dcr = dcs[k];
+            }
+            const float d_o = dh * tc;
+            const float dc = dcr + dh * o * (1.0f - tc * tc);
+            const float di = dc * g, dg = dc * i, df = dc * Lp<T>::to_f(vcp[k]);
+            dcn[k] = dc * f;
+            o0[k] = Lp<T>::from_f(di * i * (1.0f - i));
+            o1[k] = Lp<T>::from_f(df * f * (1.0f - f));
+            o2[k] = Lp<T>::from_f(dg * (1.0f - g * g));
+            o3[k] = Lp<T>::from_f(d_o * o * (1.0f - o));
+        }
+        T *da = dA + (int64_t)b * G + j0;
+        // packed: [b / 64][gate][j / 64] chunk, fragment order inside; 8 aligned units are one slot
+        T *pk = dApk + (((int64_t)(b >> 6) * 4) * nkc + (j0 >> 6)) * A_CHUNK + frag_offset(b & 63, j0 & 63, 2);
+        if constexpr (VEC) {
+            *reinterpret_cast<u32x4 *>(da) = *reinterpret_cast<const u32x4 *>(o0);
+            *reinterpret_cast<u32x4 *>(da + H) = *reinterpret_cast<const u32x4 *>(o1);
+            *reinterpret_cast<u32x4 *>(da + 2 * H) = *reinterpret_cast<const u32x4 *>(o2);
+            *reinterpret_cast<u32x4 *>(da + 3 * H) = *reinterpret_cast<const u32x4 *>(o3);
+            *reinterpret_cast<u32x4 *>(pk) = *reinterpret_cast<const u32x4 *>(o0);
+            *reinterpret_cast<u32x4 *>(pk + gs) = *reinterpret_cast<const u32x4 *>(o1);
+            *reinterpret_cast<u32x4 *>(pk + 2 * gs) = *reinterpret_cast<const u32x4 *>(o2);
+            *reinterpret_cast<u32x4 *>(pk + 3 * gs) = *reinterpret_cast<const u32x4 *>(o3);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(dc_state + e0 + 4 * h) = *reinterpret_cast<const u32x4 *>(dcn + 4 * h);
+        } else {
+            da[0] = o0[0]; da[H] = o1[0]; da[2 * H] = o2[0]; da[3 * H] = o3[0];
+            pk[0] = o0[0]; pk[gs] = o1[0]; pk[2 * gs] = o2[0]; pk[3 * gs] = o3[0];
+            dc_state[e0] = dcn[0];
+        }
     }
 }
 
@@ -399,12 +460,23 @@ int gates_backward_packed(int dtype, const void *dh_above, const float *partials
                           const void *c_prev, float *dc_state, void *dA, void *dApk, int B, int H, int first, hipStream_t s) {
     const RecurrentDims d = recurrent_dims(B, H);
     const int64_t n = (int64_t)B * H;
-    int blocks = (int)((n + 255) / 256);
+    const uintptr_t all = (uintptr_t)dh_above | (uintptr_t)partials | (uintptr_t)gates | (uintptr_t)c_t | (uintptr_t)c_prev |
+                          (uintptr_t)dc_state | (uintptr_t)dA | (uintptr_t)dApk;
+    const bool vec = H % 8 == 0 && all % 16 == 0;
+    const int64_t items = vec ? n / 8 : n;
+    int blocks = (int)((items + 255) / 256);
     if (blocks > 8192) blocks = 8192;
+    if (blocks < 1) blocks = 1;
     KernelTimer timer(KC_POINTWISE, s, 0.0, (double)n * (16.0 + 8.0 + 15.0 * 2.0));
-    LP_ONLY(dtype, T, hipLaunchKernelGGL(gates_backward_packed_kernel<T>, dim3(blocks), dim3(256), 0, s, (const T *)dh_above,
-                                         partials, (const T *)gates, (const T *)c_t, (const T *)c_prev, dc_state, (T *)dA,
-                                         (T *)dApk, B, H, d.nkc, first));
+    if (vec) {
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((gates_backward_packed_kernel<T, true>), dim3(blocks), dim3(256), 0, s,
+                                             (const T *)dh_above, partials, (const T *)gates, (const T *)c_t, (const T *)c_prev,
+                                             dc_state, (T *)dA, (T *)dApk, B, H, d.nkc, first));
+    } else {
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((gates_backward_packed_kernel<T, false>), dim3(blocks), dim3(256), 0, s,
+                                             (const T *)dh_above, partials, (const T *)gates, (const T *)c_t, (const T *)c_prev,
+                                             dc_state, (T *)dA, (T *)dApk, B, H, d.nkc, first));
+    }
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
