@@ -192,6 +192,19 @@ float lr_schedule(float lr0, int32_t n_workers, float n_half, float eff_lr_max, 
 int lstm_timing_enable(int32_t on);
 int lstm_timing_read(int32_t kernel_class, int64_t *launches, double *total_ms, double *flops, double *bytes);
 
+/* One whole-sequence GEMM through the dispatch the training step uses, for kernel tests and
+ * micro-benchmarks.  All pointers device.  C: lp [M,N] row-major, out.
+ *   layout 0: C = A B^T, row-major A[M,K], B[N,K]
+ *   layout 1: C = A^T B, row-major A[K,M], B[K,N]   (16-bit types, M, N >= 192, multiples of 8)
+ *   layout 2/3/4: operands in 64x64 blocks as written by lstm_debug_pack_blocked, with
+ *                 (A rows, B rows) indexing (M, N) / (M, K) / (K, K)   (16-bit types, M, N >= 192)
+ * splitk_ws: fp32 [splits, M, N] or NULL with splits <= 1. */
+int lstm_debug_gemm(int32_t dtype, int32_t layout, int32_t M, int32_t N, int32_t K, const void *A, const void *B, void *C,
+                    float *splitk_ws, int32_t splits, void *stream);
+/* dst (64x64 blocks, zero padded to whole blocks: ceil(rows/64)*ceil(cols/64)*4096 elements) =
+ * src (row-major [rows, cols]).  Both device. */
+int lstm_debug_pack_blocked(int32_t dtype, const void *src, int32_t rows, int32_t cols, void *dst, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

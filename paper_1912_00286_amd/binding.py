@@ -66,10 +66,13 @@ def load_library():
     lib.master_update.argtypes = [i64, optp, f32, i64, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
     lib.lr_schedule.argtypes = [f32, i32, f32, f32, i32, f32, i64]
     lib.lr_schedule.restype = f32
+    lib.lstm_debug_gemm.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, i32, vp]
+    lib.lstm_debug_pack_blocked.argtypes = [i32, vp, i32, i32, vp, vp]
     lib.lstm_timing_enable.argtypes = [i32]
     lib.lstm_timing_read.argtypes = [i32, C.POINTER(i64), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double)]
     for name in ("lstm_param_count", "lstm_param_offset", "lstm_workspace_bytes", "lstm_forward", "lstm_backward",
-                 "grad_average", "master_update", "lstm_timing_enable", "lstm_timing_read"):
+                 "grad_average", "master_update", "lstm_timing_enable", "lstm_timing_read", "lstm_debug_gemm",
+                 "lstm_debug_pack_blocked"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -161,6 +164,15 @@ def lstm_timing_read(kernel_class: int):
     n, ms, fl, by = C.c_int64(), C.c_double(), C.c_double(), C.c_double()
     _check(load_library().lstm_timing_read(kernel_class, C.byref(n), C.byref(ms), C.byref(fl), C.byref(by)))
     return dict(launches=n.value, total_ms=ms.value, flops=fl.value, bytes=by.value)
+
+
+def lstm_debug_gemm(dtype, layout, M, N, K, A, B, Cout, splitk_ws=None, splits=1, stream=None):
+    _check(load_library().lstm_debug_gemm(dtype, layout, M, N, K, _ptr(A), _ptr(B), _ptr(Cout), _ptr(splitk_ws), splits,
+                                          _stream(stream)))
+
+
+def lstm_debug_pack_blocked(dtype, src, rows, cols, dst, stream=None):
+    _check(load_library().lstm_debug_pack_blocked(dtype, _ptr(src), rows, cols, _ptr(dst), _stream(stream)))
 
 
 # --------------------------------------------------------------------------

@@ -33,8 +33,11 @@ struct Plan {
     std::vector<int64_t> off_W, off_U, off_b;
     int head_rows = 0;                   // rows the head acts on (T*B or B)
     // reserve
-    std::vector<size_t> r_gates, r_c, r_h;
-    size_t r_xemb = 0, r_dzu = 0, reserve_bytes = 0;
+    std::vector<size_t> r_gates, r_c, r_h, r_hblk;
+    size_t r_xemb = 0, r_dzu = 0, r_xblk = 0, reserve_bytes = 0;
+    bool blk = false;                    // whole-sequence GEMM operands are also kept in 64x64 blocks
+    int h_ncb = 0, g_ncb = 0;            // column blocks of the blocked hidden sequence / dA
+    size_t s_wblk = 0, s_dablk = 0;
     // scratch
     size_t s_ax = 0, s_cstate = 0, s_losspart = 0;
     size_t s_wT = 0, s_dA = 0, s_dAT = 0, s_xT = 0, s_dh[2] = {0, 0}, s_dhrec = 0, s_dcstate = 0, s_splitk = 0,
@@ -103,6 +106,15 @@ int make_plan(const lstm_config *c, Plan &p) {
     }
     p.r_xemb = r; if (p.V > 0) r += align_up(TB * p.D * p.es);
     p.r_dzu = r; r += align_up((size_t)p.head_rows * 4);
+    // 64x64-blocked copies for the large-tile GEMMs: time slots must start on a block row
+    p.blk = p.dtype != LSTM_DTYPE_FP32 && p.B % 64 == 0 && gemm_blocked_supported(p.dtype, (int)TB, p.G);
+    p.r_hblk.assign(p.L, 0);
+    if (p.blk) {
+        p.h_ncb = (p.H + 63) / 64;
+        p.g_ncb = (p.G + 63) / 64;
+        for (int l = 0; l < p.L; ++l) { p.r_hblk[l] = r; r += align_up(blocked_elems((int)(TB + p.B), p.H) * p.es); }
+        p.r_xblk = r; r += align_up(blocked_elems((int)TB, p.in_dim[0]) * p.es);
+    }
     p.reserve_bytes = r;
     // ---- scratch
     size_t s = 0;
@@ -145,6 +157,10 @@ int make_plan(const lstm_config *c, Plan &p) {
         p.s_part = s; s += align_up(rd.partial_bytes);
         p.s_upk = s; s += align_up((rd.utpk_elems > rd.upk_elems ? rd.utpk_elems : rd.upk_elems) * p.es);
         for (int k = 0; k < 2; ++k) { p.s_apk[k] = s; s += align_up(rd.dapk_elems * p.es); }
+    }
+    if (p.blk) {
+        p.s_wblk = s; s += align_up(blocked_elems(p.G, max_dim) * p.es);
+        p.s_dablk = s; s += align_up(blocked_elems((int)TB, p.G) * p.es);
     }
     p.scratch_bytes = s;
     return LSTM_OK;
@@ -259,7 +275,11 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
         LSTM_TRY(embed_gather(p.dtype, (const int32_t *)x, par + p.off_E * es, xe, TB, p.V, p.D, s));
         layer_in = xe;
     }
-    float *ax = (float *)at(scratch, p.s_ax);
+    // input projection of a whole layer: fp32 in the fp32 baseline mode (the recurrent GEMM
+    // accumulates into it), otherwise stored in the 16-bit type like every other activation
+    char *ax = at(scratch, p.s_ax);
+    const bool fused = p.dtype != LSTM_DTYPE_FP32;
+    const size_t axs = fused ? es : 4;
     float *c_state = (float *)at(scratch, p.s_cstate);
     for (int l = 0; l < p.L; ++l) {
         const void *W = par + p.off_W[l] * es, *U = par + p.off_U[l] * es, *b = par + p.off_b[l] * es;
@@ -267,15 +287,34 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
         char *cs = at(reserve, p.r_c[l]);
         char *hs = at(reserve, p.r_h[l]);
         // input projection of the whole sequence: Ax = X W^T + b
-        GemmArgs g{};
-        g.A = layer_in; g.B = W; g.C = ax; g.bias = b;
-        g.M = TB; g.N = p.G; g.K = p.in_dim[l];
-        g.lda = p.in_dim[l]; g.ldb = p.in_dim[l]; g.ldc = p.G;
-        g.kclass = KC_GEMM_BATCHED;
-        LSTM_TRY(gemm_nt(p.dtype, g, s));
+        if (p.blk) {
+            // operands in 64x64 blocks: layer 0 packs the input once, upper layers read the blocked
+            // hidden sequence the step kernels of the layer below wrote
+            char *wblk = at(scratch, p.s_wblk);
+            LSTM_TRY(pack_blocked(p.dtype, W, p.in_dim[l], p.G, p.in_dim[l], wblk, s));
+            BlockedGemmArgs g{};
+            if (l == 0) {
+                LSTM_TRY(pack_blocked(p.dtype, layer_in, p.in_dim[0], TB, p.in_dim[0], at(reserve, p.r_xblk), s));
+                g.A = BlockedOperand{at(reserve, p.r_xblk), (p.in_dim[0] + 63) / 64, 0};
+            } else {
+                g.A = BlockedOperand{at(reserve, p.r_hblk[l - 1]) + (size_t)(p.B / 64) * p.h_ncb * 4096 * es, p.h_ncb, 0};
+            }
+            g.B = BlockedOperand{wblk, (p.in_dim[l] + 63) / 64, 0};
+            g.C = ax; g.bias = b; g.ldc = p.G; g.out_lp = 1;
+            g.M = TB; g.N = p.G; g.K = p.in_dim[l];
+            g.kclass = KC_GEMM_BATCHED;
+            LSTM_TRY(gemm_blocked(p.dtype, g, s));
+        } else {
+            GemmArgs g{};
+            g.A = layer_in; g.B = W; g.C = ax; g.bias = b;
+            g.M = TB; g.N = p.G; g.K = p.in_dim[l];
+            g.lda = p.in_dim[l]; g.ldb = p.in_dim[l]; g.ldc = p.G;
+            g.out_lp = fused ? 1 : 0;
+            g.kclass = KC_GEMM_BATCHED;
+            LSTM_TRY(gemm_nt(p.dtype, g, s));
+        }
         LSTM_TRY(init_state(p.dtype, h0 ? at(h0, (size_t)l * BH * es) : nullptr, c0 ? c0 + l * BH : nullptr, hs, cs,
                             c_state, BH, s));
-        const bool fused = p.dtype != LSTM_DTYPE_FP32;
         char *upk = at(scratch, p.s_upk);
         char *hpk[2] = {at(scratch, p.s_apk[0]), at(scratch, p.s_apk[1])};
         if (fused) {
@@ -285,24 +324,33 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
             LSTM_TRY(pack_rows(p.dtype, h0 ? at(h0, (size_t)l * BH * es) : nullptr, hpk[0], p.B, p.H, s));
             LSTM_TRY(pack_rows(p.dtype, nullptr, hpk[1], p.B, p.H, s));
         }
+        char *hblk = p.blk ? at(reserve, p.r_hblk[l]) : nullptr;
+        const size_t slot = (size_t)(p.B / 64) * p.h_ncb * 4096 * es;      // bytes of one time slot of the blocked sequence
+        if (p.blk) {
+            // zero padding columns (H not a multiple of 64) once, then slot 0 = initial hidden state
+            if (p.H % 64 != 0) LSTM_TRY(fill_u32(hblk, 0, (int64_t)(blocked_elems((int)(TB + p.B), p.H) * es / 4), s));
+            if (h0) LSTM_TRY(pack_blocked(p.dtype, at(h0, (size_t)l * BH * es), p.H, p.B, p.H, hblk, s));
+            else if (p.H % 64 == 0) LSTM_TRY(fill_u32(hblk, 0, (int64_t)(slot / 4), s));
+        }
         for (int t = 0; t < p.T; ++t) {
-            float *a_t = ax + (int64_t)t * p.B * p.G;
+            char *a_t = ax + (size_t)t * p.B * p.G * axs;
             if (fused) {
                 // recurrent projection, gates, cell and hidden update in one launch
                 LSTM_TRY(step_forward_fused(p.dtype, hpk[t & 1], upk, a_t, c_state, gates + (size_t)t * p.B * p.G * es,
                                             cs + (size_t)(t + 1) * BH * es, hs + (size_t)(t + 1) * BH * es,
-                                            hpk[(t + 1) & 1], p.B, p.H, s));
+                                            hpk[(t + 1) & 1], hblk ? hblk + (size_t)(t + 1) * slot : nullptr, p.h_ncb, p.B,
+                                            p.H, s));
                 continue;
             }
             // fp32 baseline mode: recurrent projection added in place (A_t += h_{t-1} U^T), then the gates
             GemmArgs r{};
-            r.A = hs + (size_t)t * BH * es; r.B = U; r.C = a_t;
+            r.A = hs + (size_t)t * BH * es; r.B = U; r.C = a_t;   // fp32 here
             r.M = p.B; r.N = p.G; r.K = p.H;
             r.lda = p.H; r.ldb = p.H; r.ldc = p.G;
             r.accumulate = 1;
             r.kclass = KC_GEMM_STEP;
             LSTM_TRY(gemm_nt(p.dtype, r, s));
-            LSTM_TRY(gates_forward(p.dtype, a_t, c_state, gates + (size_t)t * p.B * p.G * es,
+            LSTM_TRY(gates_forward(p.dtype, (const float *)a_t, c_state, gates + (size_t)t * p.B * p.G * es,
                                    cs + (size_t)(t + 1) * BH * es, hs + (size_t)(t + 1) * BH * es, p.B, p.H, s));
         }
         LSTM_TRY(copy_state(p.dtype, hs + (size_t)p.T * BH * es, c_state, hT ? at(hT, (size_t)l * BH * es) : nullptr,
@@ -348,7 +396,8 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
 
     // transposed copies of the weights the data-gradient GEMMs contract over
     for (int l = 0; l < p.L; ++l) {
-        if (l > 0 || p.V > 0)
+        const bool dx_blocked = p.blk && gemm_blocked_supported(p.dtype, TB, p.in_dim[l]);   // reads W in place
+        if ((l > 0 || p.V > 0) && !dx_blocked)
             LSTM_TRY(transpose_lp(p.dtype, par + p.off_W[l] * es, p.in_dim[l], wT + p.wT_off[l], p.G, p.G, p.in_dim[l], s));
         if (p.dtype == LSTM_DTYPE_FP32)   // the 16-bit path packs U^T per layer instead
             LSTM_TRY(transpose_lp(p.dtype, par + p.off_U[l] * es, p.H, wT + p.uT_off[l], p.G, p.G, p.H, s));
@@ -389,6 +438,8 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             LSTM_TRY(pack_u_backward(p.dtype, par + p.off_U[l] * es, utpk, p.H, s));
             for (int k = 0; k < 2; ++k) LSTM_TRY(fill_u32(dapk[k], 0, (int64_t)((rd.dapk_elems * es + 3) / 4), s));
         }
+        char *dablk = p.blk ? at(scratch, p.s_dablk) : nullptr;
+        if (p.blk && p.G % 64 != 0) LSTM_TRY(fill_u32(dablk, 0, (int64_t)(blocked_elems(TB, p.G) * es / 4), s));
         for (int t = p.T - 1; t >= 0; --t) {
             const bool last = t == p.T - 1;
             if (fused) {
@@ -397,7 +448,9 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
                 if (!last) LSTM_TRY(step_backward_gemm(p.dtype, dapk[(t + 1) & 1], utpk, part, p.B, p.H, s));
                 LSTM_TRY(gates_backward_packed(p.dtype, dh_above + (size_t)t * BH * es, part, gates + (size_t)t * p.B * p.G * es,
                                                cs + (size_t)(t + 1) * BH * es, cs + (size_t)t * BH * es, dc_state,
-                                               dA + (size_t)t * p.B * p.G * es, dapk[t & 1], p.B, p.H, last ? 1 : 0, s));
+                                               dA + (size_t)t * p.B * p.G * es, dapk[t & 1],
+                                               dablk ? dablk + (size_t)t * (p.B / 64) * p.g_ncb * 4096 * es : nullptr, p.g_ncb,
+                                               p.B, p.H, last ? 1 : 0, s));
                 continue;
             }
             if (!last) {
@@ -415,18 +468,37 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
                                     last ? 1 : 0, 1, s));
         }
         char *d_below = at(scratch, p.s_dh[cur ^ 1]);
+        // blocked operands of this layer: dA (written by the gate kernel), its input sequence and W
+        BlockedOperand in_blk{nullptr, 0, 0};
+        char *wblk = p.blk ? at(scratch, p.s_wblk) : nullptr;
+        if (p.blk) {
+            if (l == 0) in_blk = BlockedOperand{at(reserve, p.r_xblk), (p.in_dim[0] + 63) / 64, 0};
+            else in_blk = BlockedOperand{at(reserve, p.r_hblk[l - 1]) + (size_t)(p.B / 64) * p.h_ncb * 4096 * es, p.h_ncb, 0};
+        }
         if (l > 0 || p.V > 0) {
             // dX = dA W  for the layer below (or the embedding rows)
-            GemmArgs d{};
-            d.A = dA; d.B = wT + p.wT_off[l]; d.C = d_below;
-            d.M = TB; d.N = I; d.K = p.G;
-            d.lda = p.G; d.ldb = p.G; d.ldc = I;
-            d.out_lp = 1; d.kclass = KC_GEMM_BATCHED;
-            LSTM_TRY(gemm_nt(p.dtype, d, s));
+            if (p.blk && gemm_blocked_supported(p.dtype, TB, I)) {
+                LSTM_TRY(pack_blocked(p.dtype, par + p.off_W[l] * es, I, p.G, I, wblk, s));
+                BlockedGemmArgs d{};
+                d.A = BlockedOperand{dablk, p.g_ncb, 0};
+                d.B = BlockedOperand{wblk, (I + 63) / 64, 1};        // rows of W are the contraction index
+                d.C = d_below; d.ldc = I; d.out_lp = 1;
+                d.M = TB; d.N = I; d.K = p.G;
+                d.kclass = KC_GEMM_BATCHED;
+                LSTM_TRY(gemm_blocked(p.dtype, d, s));
+            } else {
+                GemmArgs d{};
+                d.A = dA; d.B = wT + p.wT_off[l]; d.C = d_below;
+                d.M = TB; d.N = I; d.K = p.G;
+                d.lda = p.G; d.ldb = p.G; d.ldc = I;
+                d.out_lp = 1; d.kclass = KC_GEMM_BATCHED;
+                LSTM_TRY(gemm_nt(p.dtype, d, s));
+            }
         }
         // weight gradients dW = dA^T X and dU = dA^T H_prev, contracted over all T*B rows with
-        // fp32 accumulation.  Preferred: the kernel that reads both operands as they lie in
-        // memory; otherwise explicit transposes feed the K-contiguous kernel.
+        // fp32 accumulation.  Preferred: blocked operands read as they lie in memory (rows are
+        // the contraction index); then the row-major form of the same kernel; otherwise explicit
+        // transposes feed the K-contiguous kernel.
         GemmArgs w{};
         w.M = p.G; w.N = I; w.K = TB; w.ldc = I;
         w.C = grd + p.off_W[l] * es;
@@ -439,16 +511,31 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
         GemmArgs wt = w, ut = u;
         wt.A = dA; wt.lda = p.G; wt.B = layer_in; wt.ldb = I;
         ut.A = dA; ut.lda = p.G; ut.B = hs; ut.ldb = p.H;                 // h_0..h_{T-1}
-        const bool w_tn = gemm_tn_supported(p.dtype, wt), u_tn = gemm_tn_supported(p.dtype, ut);
-        if (!w_tn || !u_tn) LSTM_TRY(transpose_lp(p.dtype, dA, p.G, dAT, TB, TB, p.G, s));
-        if (w_tn) {
+        const bool w_blk = p.blk && gemm_blocked_supported(p.dtype, p.G, I);
+        const bool u_blk = p.blk && gemm_blocked_supported(p.dtype, p.G, p.H);
+        const bool w_tn = !w_blk && gemm_tn_supported(p.dtype, wt), u_tn = !u_blk && gemm_tn_supported(p.dtype, ut);
+        if ((!w_blk && !w_tn) || (!u_blk && !u_tn)) LSTM_TRY(transpose_lp(p.dtype, dA, p.G, dAT, TB, TB, p.G, s));
+        auto blocked_wgrad = [&](const GemmArgs &r, const BlockedOperand &bop) {
+            BlockedGemmArgs g{};
+            g.A = BlockedOperand{dablk, p.g_ncb, 1};
+            g.B = BlockedOperand{bop.ptr, bop.ncb, 1};
+            g.C = r.C; g.ldc = r.ldc; g.out_lp = 1;
+            g.M = r.M; g.N = r.N; g.K = r.K;
+            g.splitk_ws = r.splitk_ws; g.splits = r.splits; g.kclass = r.kclass;
+            return gemm_blocked(p.dtype, g, s);
+        };
+        if (w_blk) {
+            LSTM_TRY(blocked_wgrad(w, in_blk));
+        } else if (w_tn) {
             LSTM_TRY(gemm_tn(p.dtype, wt, s));
         } else {
             LSTM_TRY(transpose_lp(p.dtype, layer_in, I, xT, TB, TB, I, s));
             w.A = dAT; w.B = xT; w.lda = TB; w.ldb = TB;
             LSTM_TRY(gemm_nt(p.dtype, w, s));
         }
-        if (u_tn) {
+        if (u_blk) {
+            LSTM_TRY(blocked_wgrad(u, BlockedOperand{at(reserve, p.r_hblk[l]), p.h_ncb, 1}));
+        } else if (u_tn) {
             LSTM_TRY(gemm_tn(p.dtype, ut, s));
         } else {
             LSTM_TRY(transpose_lp(p.dtype, hs, p.H, xT, TB, TB, p.H, s));
@@ -467,3 +554,32 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
     }
     return LSTM_OK;
 }
+
+// Diagnostic: one whole-sequence GEMM through the same dispatch the training step uses.
+// layout 0: C = A B^T, row-major A[M,K], B[N,K];  1: C = A^T B, row-major A[K,M], B[K,N];
+// 2/3/4: operands in 64x64 blocks (see pack_blocked), roles (A,B) = (rows M, rows N) /
+// (rows M, rows K) / (rows K, rows K).  C is row-major lp [M,N].
+extern "C" int lstm_debug_gemm(int32_t dtype, int32_t layout, int32_t M, int32_t N, int32_t K, const void *A, const void *B,
+                               void *C, float *splitk_ws, int32_t splits, void *stream) {
+    hipStream_t s = (hipStream_t)stream;
+    if (layout <= 1) {
+        GemmArgs g{};
+        g.A = A; g.B = B; g.C = C; g.M = M; g.N = N; g.K = K;
+        g.lda = layout == 0 ? K : M; g.ldb = layout == 0 ? K : N; g.ldc = N;
+        g.out_lp = 1; g.splitk_ws = splitk_ws; g.splits = splits; g.kclass = KC_GEMM_BATCHED;
+        return layout == 0 ? gemm_nt(dtype, g, s) : gemm_tn(dtype, g, s);
+    }
+    BlockedGemmArgs g{};
+    const int ta = layout == 4, tb = layout >= 3;
+    g.A = BlockedOperand{A, ((ta ? M : K) + 63) / 64, ta};
+    g.B = BlockedOperand{B, ((tb ? N : K) + 63) / 64, tb};
+    g.C = C; g.ldc = N; g.out_lp = 1; g.M = M; g.N = N; g.K = K;
+    g.splitk_ws = splitk_ws; g.splits = splits; g.kclass = KC_GEMM_BATCHED;
+    return gemm_blocked(dtype, g, s);
+}
+
+// Diagnostic: row-major [rows, cols] -> 64x64 blocks.
+extern "C" int lstm_debug_pack_blocked(int32_t dtype, const void *src, int32_t rows, int32_t cols, void *dst, void *stream) {
+    return pack_blocked(dtype, src, cols, rows, cols, dst, (hipStream_t)stream);
+}
+

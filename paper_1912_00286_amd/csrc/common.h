@@ -147,6 +147,31 @@ int gemm_nt(int dtype, const GemmArgs &g, hipStream_t stream);
 // operands, no transposed copies.  16-bit types, aligned shapes with M, N >= 192 only.
 bool gemm_tn_supported(int dtype, const GemmArgs &g);
 int gemm_tn(int dtype, const GemmArgs &g, hipStream_t stream);
+// ---- operands in 64x64 blocks: tensor [R, C] stored as [ceil(R/64)][ncb][64][64], zero padded.
+// A view may start at any row block (ptr points at that block row).
+struct BlockedOperand {
+    const void *ptr;
+    int ncb;      // column blocks per row block (>= ceil(C/64))
+    int trans;    // 0: rows index M (resp. N), columns index K; 1: rows index K, columns index M (resp. N)
+};
+struct BlockedGemmArgs {
+    BlockedOperand A, B;
+    void *C;             // row-major fp32 or lp [M, ldc]
+    const void *bias;    // lp [N] or null
+    int M, N, K;
+    int64_t ldc;
+    int out_lp, accumulate;
+    float *splitk_ws;
+    int splits;
+    int kclass;
+};
+size_t blocked_elems(int rows, int cols);
+// dst (blocked, zero padded) = src (row-major [rows, cols], leading dimension ld)
+int pack_blocked(int dtype, const void *src, int64_t ld, int rows, int cols, void *dst, hipStream_t stream);
+bool gemm_blocked_supported(int dtype, int M, int N);
+// C = op(A) op(B)^T-style product of blocked operands (roles per BlockedOperand::trans);
+// supported role pairs: (0,0), (0,1), (1,1).
+int gemm_blocked(int dtype, const BlockedGemmArgs &g, hipStream_t stream);
 // number of K splits gemm_nt / gemm_tn would like for this shape (>= 1)
 int gemm_pick_splits(int dtype, int M, int N, int K);
 

@@ -208,7 +208,12 @@ __device__ __forceinline__ u32x4 read_frag_tr(const uint16_t *tile, int m0, int 
     return __builtin_bit_cast(u32x4, both);
 }
 
-template <typename T, bool TRANS>
+// TA / TB_: operand A / B is in the transposed role (its rows are the contraction index).
+// BLK: operands are stored in 64x64 blocks ([row block][column block][64][64], zero padded to
+//      whole blocks; lda / ldb then hold the number of column blocks per row block and K is a
+//      multiple of 64).  A K tile of an operand is then four contiguous 8 KB blocks instead of 256
+//      row segments of 128 bytes, which is what the L2 -> CU path streams at full rate.
+template <typename T, bool TA, bool TB_, bool BLK>
 __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a, int tiles_m, int tiles_n) {
     __shared__ __attribute__((aligned(16))) BigSmem sm;
     const T *A = reinterpret_cast<const T *>(a.A);
@@ -238,26 +243,36 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a, int
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // Per-thread element offsets of the vectors this thread copies (32-bit: the host checks
-    // that both operands span less than 2^31 elements).  Rows (columns, in the transposed
-    // form) outside the operand are clamped to the first one: what they contribute only
-    // reaches accumulator rows/columns that are never stored.
+    // Per-thread element offsets of the vectors this thread copies for K tile 0 (32-bit: the
+    // host checks that both operands span less than 2^31 elements) and the step to the next
+    // tile.  Rows / columns / blocks outside the operand are clamped to the first one: what
+    // they contribute only reaches accumulator rows/columns that are never stored.
     uint32_t oa[GNV], ob[GNV];
-    const uint32_t tile_step_a = TRANS ? (uint32_t)(GBK * a.lda) : (uint32_t)GBK;
-    const uint32_t tile_step_b = TRANS ? (uint32_t)(GBK * a.ldb) : (uint32_t)GBK;
+    uint32_t step_a, step_b;
+    auto setup = [&](bool trans, int x0, int extent, int64_t ld, uint32_t (&o)[GNV], uint32_t &step) {
 #pragma unroll
-    for (int i = 0; i < GNV; ++i) {
-        const int v = tid + GTHREADS * i;
-        if constexpr (TRANS) {
-            const int krow = v / GVPK, mv = (v % GVPK) * 8;
-            oa[i] = (uint32_t)((kbeg + krow) * a.lda + (m0 + mv < a.M ? m0 + mv : 0));
-            ob[i] = (uint32_t)((kbeg + krow) * a.ldb + (n0 + mv < a.N ? n0 + mv : 0));
-        } else {
-            const int row = v / GVPR, kv = (v % GVPR) * 8;
-            oa[i] = (uint32_t)((m0 + row < a.M ? m0 + row : 0) * a.lda + kv + kbeg);
-            ob[i] = (uint32_t)((n0 + row < a.N ? n0 + row : 0) * a.ldb + kv + kbeg);
+        for (int i = 0; i < GNV; ++i) {
+            const int v = tid + GTHREADS * i;
+            if constexpr (BLK) {
+                // chunk i of the tile is one 64x64 block; thread tid copies its vector tid
+                const int xb = x0 / 64 + i, nxb = (extent + 63) / 64;
+                const int xbc = xb < nxb ? xb : 0;
+                const int ncb = (int)ld;
+                o[i] = trans ? (uint32_t)(((kbeg / 64) * ncb + xbc) * 4096 + tid * 8)
+                             : (uint32_t)((xbc * ncb + kbeg / 64) * 4096 + tid * 8);
+            } else if (trans) {
+                const int krow = v / GVPK, xv = (v % GVPK) * 8;
+                o[i] = (uint32_t)((kbeg + krow) * ld + (x0 + xv < extent ? x0 + xv : 0));
+            } else {
+                const int row = v / GVPR, kv = (v % GVPR) * 8;
+                o[i] = (uint32_t)((x0 + row < extent ? x0 + row : 0) * ld + kv + kbeg);
+            }
         }
-    }
+        if constexpr (BLK) step = trans ? (uint32_t)ld * 4096u : 4096u;
+        else step = trans ? (uint32_t)(GBK * ld) : (uint32_t)GBK;
+    };
+    setup(TA, m0, a.M, a.lda, oa, step_a);
+    setup(TB_, n0, a.N, a.ldb, ob, step_b);
     const int klen = kend > kbeg ? kend - kbeg : 0;
     const int ntiles = (klen + GBK - 1) / GBK;
     const int nfull = klen / GBK;                  // tiles that lie wholly inside the K range
@@ -266,56 +281,58 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a, int
     auto gload_full = [&](u32x4 (&ra)[GNV], u32x4 (&rb)[GNV], int tile) {
 #pragma unroll
         for (int i = 0; i < GNV; ++i) {
-            ra[i] = *reinterpret_cast<const u32x4 *>(A + (oa[i] + (uint32_t)tile * tile_step_a));
-            rb[i] = *reinterpret_cast<const u32x4 *>(B + (ob[i] + (uint32_t)tile * tile_step_b));
+            ra[i] = *reinterpret_cast<const u32x4 *>(A + (oa[i] + (uint32_t)tile * step_a));
+            rb[i] = *reinterpret_cast<const u32x4 *>(B + (ob[i] + (uint32_t)tile * step_b));
         }
     };
     auto gload_any = [&](u32x4 (&ra)[GNV], u32x4 (&rb)[GNV], int tile) {   // also the last, partial tile
 #pragma unroll
         for (int i = 0; i < GNV; ++i) {
             const int v = tid + GTHREADS * i;
-            const int kk = TRANS ? v / GVPK : (v % GVPR) * 8;                // first k of this vector inside the tile
-            const bool ok = tile * GBK + kk < klen;
-            ra[i] = ok ? *reinterpret_cast<const u32x4 *>(A + (oa[i] + (uint32_t)tile * tile_step_a)) : u32x4{0u, 0u, 0u, 0u};
-            rb[i] = ok ? *reinterpret_cast<const u32x4 *>(B + (ob[i] + (uint32_t)tile * tile_step_b)) : u32x4{0u, 0u, 0u, 0u};
+            // first k of this vector inside the tile (blocked operands are padded: always inside)
+            const int ka = BLK ? 0 : (TA ? v / GVPK : (v % GVPR) * 8);
+            const int kb = BLK ? 0 : (TB_ ? v / GVPK : (v % GVPR) * 8);
+            ra[i] = tile * GBK + ka < klen ? *reinterpret_cast<const u32x4 *>(A + (oa[i] + (uint32_t)tile * step_a))
+                                           : u32x4{0u, 0u, 0u, 0u};
+            rb[i] = tile * GBK + kb < klen ? *reinterpret_cast<const u32x4 *>(B + (ob[i] + (uint32_t)tile * step_b))
+                                           : u32x4{0u, 0u, 0u, 0u};
         }
+    };
+    auto lds_off = [&](bool trans, int i) {
+        const int v = tid + GTHREADS * i;
+        if constexpr (BLK) return trans ? (tid >> 3) * GLDT + i * 64 + (tid & 7) * 8 : (i * 64 + (tid >> 3)) * GLD + (tid & 7) * 8;
+        else return trans ? (v / GVPK) * GLDT + (v % GVPK) * 8 : (v / GVPR) * GLD + (v % GVPR) * 8;
     };
     auto sstore = [&](const u32x4 (&ra)[GNV], const u32x4 (&rb)[GNV], int buf) {
 #pragma unroll
         for (int i = 0; i < GNV; ++i) {
-            const int v = tid + GTHREADS * i;
-            const int off = TRANS ? (v / GVPK) * GLDT + (v % GVPK) * 8 : (v / GVPR) * GLD + (v % GVPR) * 8;
-            *reinterpret_cast<u32x4 *>(&sm.a[buf][off]) = ra[i];
-            *reinterpret_cast<u32x4 *>(&sm.b[buf][off]) = rb[i];
+            *reinterpret_cast<u32x4 *>(&sm.a[buf][lds_off(TA, i)]) = ra[i];
+            *reinterpret_cast<u32x4 *>(&sm.b[buf][lds_off(TB_, i)]) = rb[i];
         }
     };
     const int lrow = lane & 31, lk = (lane >> 5) * 8;
-    auto read_frags = [&](u32x4 (&fa)[2], u32x4 (&fb)[4], int buf, int ks) {
-        if constexpr (TRANS) {
+    // k-steps [ks0, ks1) of the tile in LDS buffer `buf`
+    auto compute = [&](int buf, int ks0, int ks1) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i) fa[i] = read_frag_tr(sm.a[buf], wm * 64 + i * 32, ks, lane);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) fb[j] = read_frag_tr(sm.b[buf], wn * 128 + j * 32, ks, lane);
-        } else {
-            const uint16_t *as = &sm.a[buf][(wm * 64 + lrow) * GLD + lk];
-            const uint16_t *bs = &sm.b[buf][(wn * 128 + lrow) * GLD + lk];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const u32x4 *>(as + i * 32 * GLD + ks * 16);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const u32x4 *>(bs + j * 32 * GLD + ks * 16);
-        }
-    };
-    auto compute = [&](int buf) {
-#pragma unroll
-        for (int ks = 0; ks < GBK / 16; ++ks) {
+        for (int ks = ks0; ks < ks1; ++ks) {
             u32x4 fa[2], fb[4];
-            read_frags(fa, fb, buf, ks);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                if constexpr (TA) fa[i] = read_frag_tr(sm.a[buf], wm * 64 + i * 32, ks, lane);
+                else fa[i] = *reinterpret_cast<const u32x4 *>(&sm.a[buf][(wm * 64 + i * 32 + lrow) * GLD + lk + ks * 16]);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if constexpr (TB_) fb[j] = read_frag_tr(sm.b[buf], wn * 128 + j * 32, ks, lane);
+                else fb[j] = *reinterpret_cast<const u32x4 *>(&sm.b[buf][(wn * 128 + j * 32 + lrow) * GLD + lk + ks * 16]);
+            }
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) acc[i][j] = Lp<T>::mfma(fa[i], fb[j], acc[i][j]);
         }
     };
+    constexpr int KS = GBK / 16;
 
     if (ntiles > 0) {
         // prologue: tile 0 -> LDS buffer 0, tile 1 -> set 1, tile 2 -> set 0
@@ -325,25 +342,29 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a, int
         if (ntiles > 2) gload_any(a0, b0r, 2);
         __syncthreads();
         int t = 0;
-        // steady state: tiles t+3 and t+4 are full tiles, no branches in the body
+        // steady state: tiles t+3 and t+4 are full tiles, no branches in the body.  The copy of
+        // the next tile into the other LDS buffer sits between the two halves of the MFMA work so
+        // that it overlaps with them instead of delaying the barrier.
         for (; t + 4 < nfull; t += 2) {
-            compute(0);                 // tile t
+            compute(0, 0, KS / 2);      // tile t
             sstore(a1, b1r, 1);         // tile t+1
             gload_full(a1, b1r, t + 3);
+            compute(0, KS / 2, KS);
             __syncthreads();
-            compute(1);                 // tile t+1
+            compute(1, 0, KS / 2);      // tile t+1
             sstore(a0, b0r, 0);         // tile t+2
             gload_full(a0, b0r, t + 4);
+            compute(1, KS / 2, KS);
             __syncthreads();
         }
         // drain: same schedule with range checks
         for (; t < ntiles; t += 2) {
-            compute(0);
+            compute(0, 0, KS);
             if (t + 1 < ntiles) sstore(a1, b1r, 1);
             if (t + 3 < ntiles) gload_any(a1, b1r, t + 3);
             __syncthreads();
             if (t + 1 < ntiles) {
-                compute(1);
+                compute(1, 0, KS);
                 if (t + 2 < ntiles) sstore(a0, b0r, 0);
                 if (t + 4 < ntiles) gload_any(a0, b0r, t + 4);
                 __syncthreads();
@@ -374,6 +395,17 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a, int
                     *c = a.accumulate ? (*c + v) : v;
                 }
             }
+    }
+}
+
+// row-major [R, C] (leading dimension ld) -> 64x64 blocks, zero padded
+template <typename U>
+__global__ __launch_bounds__(256) void pack_blocked_kernel(const U *src, int64_t ld, int R, int C, U *dst, int ncb) {
+    const int rb = blockIdx.y, cb = blockIdx.x;
+    U *d = dst + ((int64_t)rb * ncb + cb) * 4096;
+    for (int v = threadIdx.x; v < 4096; v += 256) {
+        const int r = rb * 64 + (v >> 6), c = cb * 64 + (v & 63);
+        d[v] = (r < R && c < C) ? src[(int64_t)r * ld + c] : (U)0;
     }
 }
 
@@ -501,8 +533,8 @@ int launch(const GemmArgs &g, hipStream_t stream) {
         hipLaunchKernelGGL(gemm_nt_f32_kernel, dim3(tiles_n, tiles_m, splits), dim3(256), 0, stream, a);
     } else {
         if (big) {
-            hipLaunchKernelGGL((gemm_mfma_big_kernel<T, false>), dim3(tiles_m * tiles_n, 1, splits), dim3(GTHREADS), 0, stream,
-                               a, tiles_m, tiles_n);
+            hipLaunchKernelGGL((gemm_mfma_big_kernel<T, false, false, false>), dim3(tiles_m * tiles_n, 1, splits), dim3(GTHREADS), 0,
+                               stream, a, tiles_m, tiles_n);
         } else if (a.vec_ok) {
             hipLaunchKernelGGL((gemm_nt_mfma_kernel<T, true>), dim3(tiles_n, tiles_m, splits), dim3(THREADS), 0, stream, a);
         } else {
@@ -532,8 +564,8 @@ int launch_tn(const GemmArgs &g, hipStream_t stream) {
     a.vec_ok = 1;
     const int tiles_m = (g.M + GBM - 1) / GBM, tiles_n = (g.N + GBN - 1) / GBN;
     KernelTimer timer(g.kclass, stream, 2.0 * g.M * g.N * g.K, 0.0);
-    hipLaunchKernelGGL((gemm_mfma_big_kernel<T, true>), dim3(tiles_m * tiles_n, 1, splits), dim3(GTHREADS), 0, stream, a,
-                       tiles_m, tiles_n);
+    hipLaunchKernelGGL((gemm_mfma_big_kernel<T, true, true, false>), dim3(tiles_m * tiles_n, 1, splits), dim3(GTHREADS), 0, stream,
+                       a, tiles_m, tiles_n);
     LSTM_LAUNCH_CHECK();
     return finish_splitk<T>(g, splits, stream);
 }
@@ -567,6 +599,80 @@ int gemm_nt(int dtype, const GemmArgs &g, hipStream_t stream) {
     }
     set_error("gemm_nt: bad dtype %d", dtype);
     return LSTM_ERR_INVALID;
+}
+
+namespace {
+template <typename T>
+int launch_blocked(const BlockedGemmArgs &g, hipStream_t stream) {
+    KernArgs a;
+    a.A = g.A.ptr; a.B = g.B.ptr; a.C = g.C; a.bias = g.bias;
+    a.M = g.M; a.N = g.N;
+    a.K = (g.K + 63) / 64 * 64;                  // operands are zero padded to whole blocks
+    a.lda = g.A.ncb; a.ldb = g.B.ncb; a.ldc = g.ldc;
+    a.out_lp = g.out_lp; a.accumulate = g.accumulate;
+    int splits = (g.splitk_ws && g.splits > 1) ? g.splits : 1;
+    int k_chunk = a.K;
+    if (splits > 1) {
+        k_chunk = ((a.K + splits - 1) / splits + GBK - 1) / GBK * GBK;
+        splits = (a.K + k_chunk - 1) / k_chunk;
+    }
+    a.ws = splits > 1 ? g.splitk_ws : nullptr;
+    a.k_chunk = k_chunk;
+    a.vec_ok = 1;
+    const int tiles_m = (g.M + GBM - 1) / GBM, tiles_n = (g.N + GBN - 1) / GBN;
+    const dim3 grid(tiles_m * tiles_n, 1, splits);
+    KernelTimer timer(g.kclass, stream, 2.0 * g.M * g.N * g.K, 0.0);
+    if (!g.A.trans && !g.B.trans)
+        hipLaunchKernelGGL((gemm_mfma_big_kernel<T, false, false, true>), grid, dim3(GTHREADS), 0, stream, a, tiles_m, tiles_n);
+    else if (!g.A.trans && g.B.trans)
+        hipLaunchKernelGGL((gemm_mfma_big_kernel<T, false, true, true>), grid, dim3(GTHREADS), 0, stream, a, tiles_m, tiles_n);
+    else if (g.A.trans && g.B.trans)
+        hipLaunchKernelGGL((gemm_mfma_big_kernel<T, true, true, true>), grid, dim3(GTHREADS), 0, stream, a, tiles_m, tiles_n);
+    else {
+        set_error("gemm_blocked: operand roles (A transposed, B not) have no kernel");
+        return LSTM_ERR_UNSUPPORTED;
+    }
+    LSTM_LAUNCH_CHECK();
+    GemmArgs r{};
+    r.M = g.M; r.N = g.N; r.C = g.C; r.ldc = g.ldc; r.out_lp = g.out_lp; r.accumulate = g.accumulate; r.splitk_ws = g.splitk_ws;
+    return finish_splitk<T>(r, splits, stream);
+}
+}  // namespace
+
+size_t blocked_elems(int rows, int cols) { return (size_t)((rows + 63) / 64) * ((cols + 63) / 64) * 4096; }
+
+int pack_blocked(int dtype, const void *src, int64_t ld, int rows, int cols, void *dst, hipStream_t stream) {
+    if (rows <= 0 || cols <= 0) return LSTM_OK;
+    const int nrb = (rows + 63) / 64, ncb = (cols + 63) / 64;
+    if (nrb > 65535) {
+        set_error("pack_blocked: too many rows %d", rows);
+        return LSTM_ERR_UNSUPPORTED;
+    }
+    KernelTimer timer(KC_AUX, stream, 0.0, 0.0);
+    if (dtype == LSTM_DTYPE_FP32)
+        hipLaunchKernelGGL(pack_blocked_kernel<uint32_t>, dim3(ncb, nrb), dim3(256), 0, stream, (const uint32_t *)src, ld, rows, cols, (uint32_t *)dst, ncb);
+    else
+        hipLaunchKernelGGL(pack_blocked_kernel<uint16_t>, dim3(ncb, nrb), dim3(256), 0, stream, (const uint16_t *)src, ld, rows, cols, (uint16_t *)dst, ncb);
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+bool gemm_blocked_supported(int dtype, int M, int N) { return dtype != LSTM_DTYPE_FP32 && M >= 192 && N >= 192; }
+
+int gemm_blocked(int dtype, const BlockedGemmArgs &g, hipStream_t stream) {
+    if (!g.A.ptr || !g.B.ptr || !g.C || g.M < 1 || g.N < 1 || g.K < 1 || dtype == LSTM_DTYPE_FP32) {
+        set_error("gemm_blocked: invalid argument");
+        return LSTM_ERR_INVALID;
+    }
+    // operand extents in elements must fit the kernel's 32-bit offsets
+    const int64_t kb = (g.K + 63) / 64;
+    const int64_t ea = (g.A.trans ? kb : (int64_t)(g.M + 63) / 64) * g.A.ncb * 4096;
+    const int64_t eb = (g.B.trans ? kb : (int64_t)(g.N + 63) / 64) * g.B.ncb * 4096;
+    if (ea >= (int64_t)1 << 31 || eb >= (int64_t)1 << 31) {
+        set_error("gemm_blocked: operand too large for 32-bit offsets");
+        return LSTM_ERR_UNSUPPORTED;
+    }
+    return dtype == LSTM_DTYPE_FP16 ? launch_blocked<_Float16>(g, stream) : launch_blocked<bf16_t>(g, stream);
 }
 
 bool gemm_tn_supported(int dtype, const GemmArgs &g) {

@@ -67,13 +67,15 @@ int pack_u_forward(int dtype, const void *U, void *Upk, int H, hipStream_t s);
 int pack_u_backward(int dtype, const void *U, void *UTpk, int H, hipStream_t s);
 // hpk = packed copy of row-major h [B,H] (h null = zeros); also clears the padding
 int pack_rows(int dtype, const void *h, void *hpk, int B, int H, hipStream_t s);
-// forward: gates, c, h of one step from packed h_prev, packed U and the step's input projection Ax (fp32, bias included)
-int step_forward_fused(int dtype, const void *hpk_prev, const void *Upk, const float *Ax, float *c_state, void *gates,
-                       void *c_out, void *h_out, void *hpk_next, int B, int H, hipStream_t s);
+// forward: gates, c, h of one step from packed h_prev, packed U and the step's input projection Ax (lp, bias included);
+// h_blk (nullable): first block row of this time slot in a 64x64-blocked copy of the hidden sequence
+int step_forward_fused(int dtype, const void *hpk_prev, const void *Upk, const void *Ax, float *c_state, void *gates,
+                       void *c_out, void *h_out, void *hpk_next, void *h_blk, int blk_ncb, int B, int H, hipStream_t s);
 // backward: partials[q][B,H] = dA_next[:, gate q rows] * U[gate q rows, :] for q = 0..3
 int step_backward_gemm(int dtype, const void *dApk, const void *UTpk, float *partials, int B, int H, hipStream_t s);
-// BPTT through the gates; dA written row-major and packed
+// BPTT through the gates; dA written row-major, packed, and (dAblk non-null: first block row of the time slot) 64x64-blocked
 int gates_backward_packed(int dtype, const void *dh_above, const float *partials, const void *gates, const void *c_t,
-                          const void *c_prev, float *dc_state, void *dA, void *dApk, int B, int H, int first, hipStream_t s);
+                          const void *c_prev, float *dc_state, void *dA, void *dApk, void *dAblk, int blk_ncb, int B, int H,
+                          int first, hipStream_t s);
 
 }  // namespace lstm

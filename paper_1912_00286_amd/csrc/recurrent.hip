@@ -144,12 +144,14 @@ __device__ __forceinline__ void zero_acc(v16f (&acc)[2][NBLK]) {
 struct FwdArgs {
     const void *hpk_prev;  // packed h_{t-1}: [n_mt][nkc][64][64]
     const void *Upk;       // packed U: [n_hb][nkc][128][64]
-    const float *Ax;       // fp32 [B,4H], input projection + bias of this step
+    const void *Ax;        // lp [B,4H], input projection + bias of this step
     float *c_state;        // fp32 [B,H] in/out
     void *gates;           // lp [B,4H] out
     void *c_out;           // lp [B,H] out
     void *h_out;           // lp [B,H] out (row-major)
     void *hpk_next;        // packed h_t out
+    void *h_blk;           // h_t out in 64x64 blocks (first block row of this time slot), or null
+    int blk_ncb;           // column blocks per row block of h_blk
     int B, H, n_mt, nkc;
 };
 
@@ -179,9 +181,9 @@ __global__ __launch_bounds__(256) void lstm_step_forward_kernel(FwdArgs a) {
     for (int rr = 0; rr < 8; ++rr) {
         const int r = rh + rr;
         const int row = min(m0 + mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), a.B - 1);
-        const float *ax = a.Ax + (int64_t)row * G + jc;
+        const T *ax = reinterpret_cast<const T *>(a.Ax) + (int64_t)row * G + jc;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) axv[rr][g] = ax[g * H];
+        for (int g = 0; g < 4; ++g) axv[rr][g] = Lp<T>::to_f(ax[g * H]);
         cprev[rr] = a.c_state[(int64_t)row * H + jc];
     }
     float pre[8][NBLK];
@@ -213,6 +215,8 @@ __global__ __launch_bounds__(256) void lstm_step_forward_kernel(FwdArgs a) {
         c_out[e] = Lp<T>::from_f(c);
         h_out[e] = h;
         hpk[frag_offset(rl, j & 63, 2)] = h;
+        if (a.h_blk)
+            reinterpret_cast<T *>(a.h_blk)[((int64_t)(row >> 6) * a.blk_ncb + (j >> 6)) * 4096 + (row & 63) * 64 + (j & 63)] = h;
     }
 }
 
@@ -266,7 +270,8 @@ __global__ __launch_bounds__(256) void lstm_step_backward_gemm_kernel(BwdArgs a)
 template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void gates_backward_packed_kernel(const T *dh_above, const float *partials, const T *gates,
                                                                     const T *c_t, const T *c_prev, float *dc_state, T *dA,
-                                                                    T *dApk, int B, int H, int nkc, int first) {
+                                                                    T *dApk, T *dAblk, int blk_ncb, int B, int H, int nkc,
+                                                                    int first) {
     constexpr int W = VEC ? 8 : 1;
     const int64_t n = (int64_t)B * H;
     const int G = 4 * H;
@@ -341,6 +346,18 @@ __global__ __launch_bounds__(256) void gates_backward_packed_kernel(const T *dh_
             da[0] = o0[0]; da[H] = o1[0]; da[2 * H] = o2[0]; da[3 * H] = o3[0];
             pk[0] = o0[0]; pk[gs] = o1[0]; pk[2 * gs] = o2[0]; pk[3 * gs] = o3[0];
             dc_state[e0] = dcn[0];
+        }
+        if (dAblk) {
+            // 64x64-blocked copy for the whole-sequence GEMMs: row b of this time slot, column gate*H + j
+            T *rowp = dAblk + (int64_t)(b >> 6) * blk_ncb * 4096 + (b & 63) * 64;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int col = g * H + j0;
+                T *d = rowp + (int64_t)(col >> 6) * 4096 + (col & 63);
+                const T *src = g == 0 ? o0 : (g == 1 ? o1 : (g == 2 ? o2 : o3));
+                if constexpr (VEC) *reinterpret_cast<u32x4 *>(d) = *reinterpret_cast<const u32x4 *>(src);
+                else d[0] = src[0];
+            }
         }
     }
 }
@@ -430,12 +447,12 @@ int pack_rows(int dtype, const void *h, void *hpk, int B, int H, hipStream_t s) 
     return LSTM_OK;
 }
 
-int step_forward_fused(int dtype, const void *hpk_prev, const void *Upk, const float *Ax, float *c_state, void *gates,
-                       void *c_out, void *h_out, void *hpk_next, int B, int H, hipStream_t s) {
+int step_forward_fused(int dtype, const void *hpk_prev, const void *Upk, const void *Ax, float *c_state, void *gates,
+                       void *c_out, void *h_out, void *hpk_next, void *h_blk, int blk_ncb, int B, int H, hipStream_t s) {
     const RecurrentDims d = recurrent_dims(B, H);
     FwdArgs a;
     a.hpk_prev = hpk_prev; a.Upk = Upk; a.Ax = Ax; a.c_state = c_state; a.gates = gates; a.c_out = c_out; a.h_out = h_out;
-    a.hpk_next = hpk_next;
+    a.hpk_next = hpk_next; a.h_blk = h_blk; a.blk_ncb = blk_ncb;
     a.B = B; a.H = H; a.n_mt = d.n_mt; a.nkc = d.nkc;
     const int grid = d.n_mt * d.n_hb;
     KernelTimer timer(KC_GEMM_STEP, s, 2.0 * B * 4.0 * H * H, 0.0);
@@ -457,11 +474,12 @@ int step_backward_gemm(int dtype, const void *dApk, const void *UTpk, float *par
 }
 
 int gates_backward_packed(int dtype, const void *dh_above, const float *partials, const void *gates, const void *c_t,
-                          const void *c_prev, float *dc_state, void *dA, void *dApk, int B, int H, int first, hipStream_t s) {
+                          const void *c_prev, float *dc_state, void *dA, void *dApk, void *dAblk, int blk_ncb, int B, int H,
+                          int first, hipStream_t s) {
     const RecurrentDims d = recurrent_dims(B, H);
     const int64_t n = (int64_t)B * H;
     const uintptr_t all = (uintptr_t)dh_above | (uintptr_t)partials | (uintptr_t)gates | (uintptr_t)c_t | (uintptr_t)c_prev |
-                          (uintptr_t)dc_state | (uintptr_t)dA | (uintptr_t)dApk;
+                          (uintptr_t)dc_state | (uintptr_t)dA | (uintptr_t)dApk | (uintptr_t)dAblk;
     const bool vec = H % 8 == 0 && all % 16 == 0;
     const int64_t items = vec ? n / 8 : n;
     int blocks = (int)((items + 255) / 256);
@@ -471,11 +489,11 @@ int gates_backward_packed(int dtype, const void *dh_above, const float *partials
     if (vec) {
         LP_ONLY(dtype, T, hipLaunchKernelGGL((gates_backward_packed_kernel<T, true>), dim3(blocks), dim3(256), 0, s,
                                              (const T *)dh_above, partials, (const T *)gates, (const T *)c_t, (const T *)c_prev,
-                                             dc_state, (T *)dA, (T *)dApk, B, H, d.nkc, first));
+                                             dc_state, (T *)dA, (T *)dApk, (T *)dAblk, blk_ncb, B, H, d.nkc, first));
     } else {
         LP_ONLY(dtype, T, hipLaunchKernelGGL((gates_backward_packed_kernel<T, false>), dim3(blocks), dim3(256), 0, s,
                                              (const T *)dh_above, partials, (const T *)gates, (const T *)c_t, (const T *)c_prev,
-                                             dc_state, (T *)dA, (T *)dApk, B, H, d.nkc, first));
+                                             dc_state, (T *)dA, (T *)dApk, (T *)dAblk, blk_ncb, B, H, d.nkc, first));
     }
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;

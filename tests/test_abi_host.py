@@ -77,7 +77,7 @@ def test_workspace_plan(hip):
     w = wl.CONFIGS["large"]
     r, s = hip.lstm_workspace_bytes(_cfg(hip, w))
     saved = 6 * w.hidden * 2 * w.seq_len * w.batch * w.num_layers     # 4 gates + c + h in fp16
-    assert saved <= r <= 1.1 * saved + (1 << 20)
+    assert saved <= r <= 1.25 * saved + (1 << 20)                     # + a blocked copy of h and of the input
     assert 0 < s < 8 << 30
     r1, s1 = hip.lstm_workspace_bytes(_cfg(hip, wl.CONFIGS["tiny"]))
     assert r1 % 256 == 0 and s1 % 256 == 0 and r1 < r and s1 < s
