@@ -41,7 +41,24 @@ def gemm_flops_per_step(w) -> float:
     return tot * w.batch * w.seq_len * w.n_workers
 
 
-def cpu_baseline(w, budget_flops=2.0e12):
+def measured_traffic(workload: str, kernel_class: str):
+    """HBM bytes per launch of one kernel class as measured with rocprofv3's
+    FETCH_SIZE and WRITE_SIZE counters (scaled by the copy-kernel calibration);
+    read from the committed counter summary of this workload, None if there is
+    no summary for it.  Counters cannot be collected from inside this process."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                p = line.split()
+                if len(p) == 3 and p[0] == "class" and p[1] == kernel_class:
+                    return float(p[2])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(w, budget_flops=6.0e12):
     """Time the CPU oracle (as it stands) on a bounded sample of the workload:
     same model and batch, sequence shortened so the fp64 work stays near
     budget_flops; the cost is linear in the number of time steps."""
@@ -75,6 +92,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="large")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run 5 plain device copies of 1 GiB and exit (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU only (no collectives are part of it); "
@@ -89,6 +108,15 @@ def main():
 
     hip.load_library()                      # no fallback: fails loudly if the HIP library is absent
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.calibrate_copy:
+        n = 1 << 29                         # 2^29 fp16 elements = 1 GiB read + 1 GiB written per copy
+        src = torch.ones(n, dtype=torch.float16, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "5 device copies", "bytes_read_each": 2 * n, "bytes_written_each": 2 * n}))
+        return
     w = wl.CONFIGS[args.workload]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -145,7 +173,8 @@ def main():
         achieved = c["bytes"] / (c["total_ms"] * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": achieved / PEAK_HBM_GBS, "traffic": None}
-    roof.update({"kernel_class": dom, "launches_per_step": c["launches"] / args.steps, "avg_launch_us": c["avg_us"]})
+    roof["traffic"] = measured_traffic(w.name, dom)
+    roof.update({"kernel_class": dom, "algorithmic_bytes_per_launch": c["bytes"] / max(c["launches"], 1), "launches_per_step": c["launches"] / args.steps, "avg_launch_us": c["avg_us"]})
     gemm_ms = classes["gemm_batched"]["total_ms"] + classes["gemm_step"]["total_ms"]
     gemm_fl = classes["gemm_batched"]["flops"] + classes["gemm_step"]["flops"]
 

@@ -501,6 +501,14 @@ int finish_splitk(const GemmArgs &g, int splits, hipStream_t stream) {
     return LSTM_OK;
 }
 
+// Bytes a GEMM moves if every operand is read once and the result written once
+// (read too when accumulating): what the event timer accounts the launch with.
+template <typename T, typename Args>
+static double gemm_algorithmic_bytes(const Args &g) {
+    const double out = (double)g.M * g.N * (g.out_lp ? sizeof(T) : 4.0);
+    return ((double)g.M + g.N) * g.K * sizeof(T) + out * (g.accumulate ? 2.0 : 1.0);
+}
+
 template <typename T>
 int launch(const GemmArgs &g, hipStream_t stream) {
     constexpr bool is_f32 = sizeof(T) == 4;
@@ -528,7 +536,7 @@ int launch(const GemmArgs &g, hipStream_t stream) {
         set_error("gemm_nt: grid too large (M=%d N=%d splits=%d)", g.M, g.N, splits);
         return LSTM_ERR_UNSUPPORTED;
     }
-    KernelTimer timer(g.kclass, stream, 2.0 * g.M * g.N * g.K, 0.0);
+    KernelTimer timer(g.kclass, stream, 2.0 * g.M * g.N * g.K, gemm_algorithmic_bytes<T>(g));
     if constexpr (is_f32) {
         hipLaunchKernelGGL(gemm_nt_f32_kernel, dim3(tiles_n, tiles_m, splits), dim3(256), 0, stream, a);
     } else {
@@ -563,7 +571,7 @@ int launch_tn(const GemmArgs &g, hipStream_t stream) {
     a.k_chunk = k_chunk;
     a.vec_ok = 1;
     const int tiles_m = (g.M + GBM - 1) / GBM, tiles_n = (g.N + GBN - 1) / GBN;
-    KernelTimer timer(g.kclass, stream, 2.0 * g.M * g.N * g.K, 0.0);
+    KernelTimer timer(g.kclass, stream, 2.0 * g.M * g.N * g.K, gemm_algorithmic_bytes<T>(g));
     hipLaunchKernelGGL((gemm_mfma_big_kernel<T, true, true, false>), dim3(tiles_m * tiles_n, 1, splits), dim3(GTHREADS), 0, stream,
                        a, tiles_m, tiles_n);
     LSTM_LAUNCH_CHECK();
@@ -621,7 +629,7 @@ int launch_blocked(const BlockedGemmArgs &g, hipStream_t stream) {
     a.vec_ok = 1;
     const int tiles_m = (g.M + GBM - 1) / GBM, tiles_n = (g.N + GBN - 1) / GBN;
     const dim3 grid(tiles_m * tiles_n, 1, splits);
-    KernelTimer timer(g.kclass, stream, 2.0 * g.M * g.N * g.K, 0.0);
+    KernelTimer timer(g.kclass, stream, 2.0 * g.M * g.N * g.K, gemm_algorithmic_bytes<T>(g));
     if (!g.A.trans && !g.B.trans)
         hipLaunchKernelGGL((gemm_mfma_big_kernel<T, false, false, true>), grid, dim3(GTHREADS), 0, stream, a, tiles_m, tiles_n);
     else if (!g.A.trans && g.B.trans)

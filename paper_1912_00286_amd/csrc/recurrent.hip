@@ -455,7 +455,10 @@ int step_forward_fused(int dtype, const void *hpk_prev, const void *Upk, const v
     a.hpk_next = hpk_next; a.h_blk = h_blk; a.blk_ncb = blk_ncb;
     a.B = B; a.H = H; a.n_mt = d.n_mt; a.nkc = d.nkc;
     const int grid = d.n_mt * d.n_hb;
-    KernelTimer timer(KC_GEMM_STEP, s, 2.0 * B * 4.0 * H * H, 0.0);
+    // operands once: U, h, Ax read, gates, c, h (row-major + packed [+ blocked]) written in storage, cell state fp32 both ways
+    const double bh = (double)B * H;
+    KernelTimer timer(KC_GEMM_STEP, s, 2.0 * B * 4.0 * H * H,
+                      2.0 * (4.0 * H * H + bh + 4.0 * bh) + 4.0 * bh + 2.0 * (4.0 * bh + bh + (h_blk ? 3.0 : 2.0) * bh) + 4.0 * bh);
     LP_ONLY(dtype, T, hipLaunchKernelGGL(lstm_step_forward_kernel<T>, dim3(grid), dim3(256), 0, s, a));
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
@@ -467,7 +470,8 @@ int step_backward_gemm(int dtype, const void *dApk, const void *UTpk, float *par
     a.dApk = dApk; a.UTpk = UTpk; a.partials = partials;
     a.B = B; a.H = H; a.n_mt = d.n_mt; a.nkc = d.nkc;
     const int grid = d.n_mt * d.n_nt * 4;
-    KernelTimer timer(KC_GEMM_STEP, s, 2.0 * B * 4.0 * H * H, 0.0);
+    // operands once: U^T and dA read in storage, four fp32 partial sums [B,H] written
+    KernelTimer timer(KC_GEMM_STEP, s, 2.0 * B * 4.0 * H * H, 2.0 * (4.0 * H * H + 4.0 * (double)B * H) + 16.0 * (double)B * H);
     LP_ONLY(dtype, T, hipLaunchKernelGGL(lstm_step_backward_gemm_kernel<T>, dim3(grid), dim3(256), 0, s, a));
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
