@@ -30,6 +30,7 @@ struct KernArgs {
     float *ws;          // split-K partials or null
     int k_chunk;        // K range handled by one blockIdx.z
     int vec_ok;         // rows 16-byte aligned and K % 8 == 0: 16-byte global loads allowed
+    int vec_out;        // 16-bit C with 16-byte aligned rows: 16-byte global stores allowed
 };
 
 // 8 consecutive lp elements of row `row` at column k; zero outside the operand.
@@ -181,10 +182,9 @@ __global__ __launch_bounds__(THREADS) void gemm_nt_mfma_kernel(KernArgs a) {
 //                  of the activations is ever made.
 // Aligned operands only (every leading dimension, and K resp. M/N, a multiple of 8).
 constexpr int GBM = 256, GBN = 256, GBK = 64;
-constexpr int GTHREADS = 512;
+constexpr int GTHREADS = 512;                    // the eight-wavefront form
 constexpr int GLD = GBK + LDS_PAD;               // row pitch, rows = operand rows
 constexpr int GLDT = GBM + 32;                   // row pitch, rows = k (transposed form)
-constexpr int GNV = GBM * GBK / 8 / GTHREADS;   // 16-byte vectors per thread, operand and K tile (4)
 constexpr int GVPR = GBK / 8;                    // 16-byte vectors per operand row of a K tile
 constexpr int GVPK = GBM / 8;                    // 16-byte vectors per k row (transposed form)
 static_assert(GBM * GLD == GBK * GLDT, "both layouts use the same LDS footprint");
@@ -213,15 +213,21 @@ __device__ __forceinline__ u32x4 read_frag_tr(const uint16_t *tile, int m0, int 
 //      whole blocks; lda / ldb then hold the number of column blocks per row block and K is a
 //      multiple of 64).  A K tile of an operand is then four contiguous 8 KB blocks instead of 256
 //      row segments of 128 bytes, which is what the L2 -> CU path streams at full rate.
-template <typename T, bool TA, bool TB_, bool BLK>
-__global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a, int tiles_m, int tiles_n) {
+// NW: wavefronts per workgroup.  8: 4 x 2 wavefronts of 64 x 128 (two per SIMD).  4: 2 x 2
+//     wavefronts of 128 x 128 (one per SIMD, 256 accumulator registers each), which reads a
+//     third less from LDS per MFMA.
+template <typename T, bool TA, bool TB_, bool BLK, int NW, bool PP = false>
+__global__ __launch_bounds__(NW * 64) void gemm_mfma_big_kernel(KernArgs a, int tiles_m, int tiles_n) {
+    constexpr int GTHREADS = NW * 64;
+    constexpr int GNV = GBM * GBK / 8 / GTHREADS;  // 16-byte vectors per thread, operand and K tile
+    constexpr int MI = 8 / NW * 2;                 // 32-row MFMA blocks per wavefront (2 or 4)
     __shared__ __attribute__((aligned(16))) BigSmem sm;
     const T *A = reinterpret_cast<const T *>(a.A);
     const T *B = reinterpret_cast<const T *>(a.B);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;       // 4 x 2 wavefronts of 64 x 128
+    const int wm = wave >> 1, wn = wave & 1;       // (NW / 2) x 2 wavefronts of (32 MI) x 128
     // tile order: workgroups of one XCD (id % 8) take neighbouring tiles, and tiles
     // are walked in bands of 8 tile rows so that a band's A and B panels stay in L2
     const int total = tiles_m * tiles_n;
@@ -235,9 +241,9 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a, int
     const int kbeg = blockIdx.z * a.k_chunk;
     const int kend = min(a.K, kbeg + a.k_chunk);
 
-    v16f acc[2][4];
+    v16f acc[MI][4];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -254,12 +260,12 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a, int
         for (int i = 0; i < GNV; ++i) {
             const int v = tid + GTHREADS * i;
             if constexpr (BLK) {
-                // chunk i of the tile is one 64x64 block; thread tid copies its vector tid
-                const int xb = x0 / 64 + i, nxb = (extent + 63) / 64;
+                // the tile is four 64x64 blocks of 512 vectors each
+                const int xb = x0 / 64 + v / 512, nxb = (extent + 63) / 64;
                 const int xbc = xb < nxb ? xb : 0;
                 const int ncb = (int)ld;
-                o[i] = trans ? (uint32_t)(((kbeg / 64) * ncb + xbc) * 4096 + tid * 8)
-                             : (uint32_t)((xbc * ncb + kbeg / 64) * 4096 + tid * 8);
+                o[i] = trans ? (uint32_t)(((kbeg / 64) * ncb + xbc) * 4096 + (v % 512) * 8)
+                             : (uint32_t)((xbc * ncb + kbeg / 64) * 4096 + (v % 512) * 8);
             } else if (trans) {
                 const int krow = v / GVPK, xv = (v % GVPK) * 8;
                 o[i] = (uint32_t)((kbeg + krow) * ld + (x0 + xv < extent ? x0 + xv : 0));
@@ -300,7 +306,10 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a, int
     };
     auto lds_off = [&](bool trans, int i) {
         const int v = tid + GTHREADS * i;
-        if constexpr (BLK) return trans ? (tid >> 3) * GLDT + i * 64 + (tid & 7) * 8 : (i * 64 + (tid >> 3)) * GLD + (tid & 7) * 8;
+        if constexpr (BLK) {
+            const int blk = v / 512, w = v % 512;
+            return trans ? (w >> 3) * GLDT + blk * 64 + (w & 7) * 8 : (blk * 64 + (w >> 3)) * GLD + (w & 7) * 8;
+        }
         else return trans ? (v / GVPK) * GLDT + (v % GVPK) * 8 : (v / GVPR) * GLD + (v % GVPR) * 8;
     };
     auto sstore = [&](const u32x4 (&ra)[GNV], const u32x4 (&rb)[GNV], int buf) {
@@ -315,11 +324,11 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a, int
     auto compute = [&](int buf, int ks0, int ks1) {
 #pragma unroll
         for (int ks = ks0; ks < ks1; ++ks) {
-            u32x4 fa[2], fb[4];
+            u32x4 fa[MI], fb[4];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                if constexpr (TA) fa[i] = read_frag_tr(sm.a[buf], wm * 64 + i * 32, ks, lane);
-                else fa[i] = *reinterpret_cast<const u32x4 *>(&sm.a[buf][(wm * 64 + i * 32 + lrow) * GLD + lk + ks * 16]);
+            for (int i = 0; i < MI; ++i) {
+                if constexpr (TA) fa[i] = read_frag_tr(sm.a[buf], (wm * MI + i) * 32, ks, lane);
+                else fa[i] = *reinterpret_cast<const u32x4 *>(&sm.a[buf][((wm * MI + i) * 32 + lrow) * GLD + lk + ks * 16]);
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -327,7 +336,7 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a, int
                 else fb[j] = *reinterpret_cast<const u32x4 *>(&sm.b[buf][(wn * 128 + j * 32 + lrow) * GLD + lk + ks * 16]);
             }
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) acc[i][j] = Lp<T>::mfma(fa[i], fb[j], acc[i][j]);
         }
@@ -342,6 +351,58 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a, int
         if (ntiles > 2) gload_any(a0, b0r, 2);
         __syncthreads();
         int t = 0;
+        if constexpr (PP && NW == 8) {
+            // Ping-pong schedule.  The first four wavefronts sit on the four SIMDs, the second four
+            // share them.  Every k-step is split into a slot that reads its fragments from LDS (and
+            // moves a quarter of the next tile: registers -> LDS, global -> registers) and a slot
+            // that issues its MFMAs, with a workgroup barrier after every slot.  The second group
+            // runs one slot behind the first, so while one wavefront of a SIMD keeps the matrix
+            // pipe busy the other one uses the LDS, instead of all eight doing the same thing at
+            // the same time.  Buffer safety: a tile's last fragment read (second group, k-step 3)
+            // lies one slot before the first store into that buffer, its first read one slot
+            // after the last store, and there is a barrier between any two slots.
+            const int grp = wave >> 2;
+            auto slot_barrier = [&]() {
+                __builtin_amdgcn_sched_barrier(0);
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            auto pp_tile = [&](int buf, u32x4 (&ra)[GNV], u32x4 (&rb)[GNV], int tile_next) {
+#pragma unroll
+                for (int ks = 0; ks < GBK / 16; ++ks) {
+                    u32x4 fa[MI], fb[4];
+#pragma unroll
+                    for (int i = 0; i < MI; ++i) {
+                        if constexpr (TA) fa[i] = read_frag_tr(sm.a[buf], (wm * MI + i) * 32, ks, lane);
+                        else fa[i] = *reinterpret_cast<const u32x4 *>(&sm.a[buf][((wm * MI + i) * 32 + lrow) * GLD + lk + ks * 16]);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        if constexpr (TB_) fb[j] = read_frag_tr(sm.b[buf], wn * 128 + j * 32, ks, lane);
+                        else fb[j] = *reinterpret_cast<const u32x4 *>(&sm.b[buf][(wn * 128 + j * 32 + lrow) * GLD + lk + ks * 16]);
+                    }
+                    *reinterpret_cast<u32x4 *>(&sm.a[buf ^ 1][lds_off(TA, ks)]) = ra[ks];
+                    *reinterpret_cast<u32x4 *>(&sm.b[buf ^ 1][lds_off(TB_, ks)]) = rb[ks];
+                    ra[ks] = *reinterpret_cast<const u32x4 *>(A + (oa[ks] + (uint32_t)tile_next * step_a));
+                    rb[ks] = *reinterpret_cast<const u32x4 *>(B + (ob[ks] + (uint32_t)tile_next * step_b));
+                    slot_barrier();
+#pragma unroll
+                    for (int i = 0; i < MI; ++i)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) acc[i][j] = Lp<T>::mfma(fa[i], fb[j], acc[i][j]);
+                    slot_barrier();
+                }
+            };
+            static_assert(GNV == GBK / 16, "one A and one B vector per thread and k-step");
+            if (t + 4 < nfull) {
+                if (grp == 1) slot_barrier();
+                for (; t + 4 < nfull; t += 2) {
+                    pp_tile(0, a1, b1r, t + 3);     // multiply tile t, move tile t+1, fetch tile t+3
+                    pp_tile(1, a0, b0r, t + 4);     // multiply tile t+1, move tile t+2, fetch tile t+4
+                }
+                if (grp == 0) slot_barrier();
+            }
+        }
         // steady state: tiles t+3 and t+4 are full tiles, no branches in the body.  The copy of
         // the next tile into the other LDS buffer sits between the two halves of the MFMA work so
         // that it overlaps with them instead of delaying the barrier.
@@ -374,16 +435,54 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a, int
 
     const int col_l = lane & 31, rgrp = (lane >> 5) * 4;
     const T *bias = reinterpret_cast<const T *>(a.bias);
+    if (a.out_lp && !a.ws && a.vec_out) {
+        // 16-bit result: the accumulators hold one column per lane, which would go out as 2-byte
+        // stores.  Stage the tile in LDS (free once the last K tile has been multiplied) and
+        // write it as whole 512-byte row segments instead.
+        constexpr int OLD = GBN + 8;                       // staging row pitch (elements)
+        static_assert(GBM * OLD * 2 <= (int)sizeof(BigSmem), "staged tile must fit the operand buffers");
+        T *stage = reinterpret_cast<T *>(&sm);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int cl = wn * 128 + j * 32 + col_l;
+            const int col = n0 + cl;
+            const float bv = (bias && col < a.N) ? Lp<T>::to_f(bias[col]) : 0.0f;
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int rl = (wm * MI + i) * 32 + (r >> 2) * 8 + rgrp + (r & 3);
+                    stage[rl * OLD + cl] = Lp<T>::from_f(acc[i][j][r] + bv);
+                }
+        }
+        __syncthreads();
+        T *C = reinterpret_cast<T *>(a.C);
+#pragma unroll 4
+        for (int v = tid; v < GBM * (GBN / 8); v += GTHREADS) {
+            const int rl = v / (GBN / 8), cl = (v % (GBN / 8)) * 8;
+            const int row = m0 + rl, col = n0 + cl;
+            if (row >= a.M || col >= a.N) continue;
+            const u32x4 val = *reinterpret_cast<const u32x4 *>(&stage[rl * OLD + cl]);
+            if (col + 8 <= a.N) {
+                *reinterpret_cast<u32x4 *>(&C[(int64_t)row * a.ldc + col]) = val;
+            } else {
+                T e[8];
+                __builtin_memcpy(e, &val, 16);
+                for (int q = 0; q < a.N - col; ++q) C[(int64_t)row * a.ldc + col + q] = e[q];
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int col = n0 + wn * 128 + j * 32 + col_l;
         if (col >= a.N) continue;
         const float bv = (bias && blockIdx.z == 0) ? Lp<T>::to_f(bias[col]) : 0.0f;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + rgrp + (r & 3);
+                const int row = m0 + (wm * MI + i) * 32 + (r >> 2) * 8 + rgrp + (r & 3);
                 if (row >= a.M) continue;
                 const float v = acc[i][j][r] + bv;
                 if (a.ws) {
@@ -531,6 +630,7 @@ int launch(const GemmArgs &g, hipStream_t stream) {
     a.ws = splits > 1 ? g.splitk_ws : nullptr;
     a.k_chunk = k_chunk;
     a.vec_ok = aligned ? 1 : 0;
+    a.vec_out = (g.out_lp && g.ldc % 8 == 0 && (uintptr_t)g.C % 16 == 0) ? 1 : 0;
     const int tiles_m = (g.M + bm - 1) / bm, tiles_n = (g.N + bn - 1) / bn;
     if (tiles_m > 65535 || splits > 65535 || (int64_t)tiles_m * tiles_n > 0x7fffffff) {
         set_error("gemm_nt: grid too large (M=%d N=%d splits=%d)", g.M, g.N, splits);
@@ -541,7 +641,7 @@ int launch(const GemmArgs &g, hipStream_t stream) {
         hipLaunchKernelGGL(gemm_nt_f32_kernel, dim3(tiles_n, tiles_m, splits), dim3(256), 0, stream, a);
     } else {
         if (big) {
-            hipLaunchKernelGGL((gemm_mfma_big_kernel<T, false, false, false>), dim3(tiles_m * tiles_n, 1, splits), dim3(GTHREADS), 0,
+            hipLaunchKernelGGL((gemm_mfma_big_kernel<T, false, false, false, 8>), dim3(tiles_m * tiles_n, 1, splits), dim3(GTHREADS), 0,
                                stream, a, tiles_m, tiles_n);
         } else if (a.vec_ok) {
             hipLaunchKernelGGL((gemm_nt_mfma_kernel<T, true>), dim3(tiles_n, tiles_m, splits), dim3(THREADS), 0, stream, a);
@@ -570,9 +670,10 @@ int launch_tn(const GemmArgs &g, hipStream_t stream) {
     a.ws = splits > 1 ? g.splitk_ws : nullptr;
     a.k_chunk = k_chunk;
     a.vec_ok = 1;
+    a.vec_out = (g.out_lp && g.ldc % 8 == 0 && (uintptr_t)g.C % 16 == 0) ? 1 : 0;
     const int tiles_m = (g.M + GBM - 1) / GBM, tiles_n = (g.N + GBN - 1) / GBN;
     KernelTimer timer(g.kclass, stream, 2.0 * g.M * g.N * g.K, gemm_algorithmic_bytes<T>(g));
-    hipLaunchKernelGGL((gemm_mfma_big_kernel<T, true, true, false>), dim3(tiles_m * tiles_n, 1, splits), dim3(GTHREADS), 0, stream,
+    hipLaunchKernelGGL((gemm_mfma_big_kernel<T, true, true, false, 8>), dim3(tiles_m * tiles_n, 1, splits), dim3(GTHREADS), 0, stream,
                        a, tiles_m, tiles_n);
     LSTM_LAUNCH_CHECK();
     return finish_splitk<T>(g, splits, stream);
@@ -627,15 +728,23 @@ int launch_blocked(const BlockedGemmArgs &g, hipStream_t stream) {
     a.ws = splits > 1 ? g.splitk_ws : nullptr;
     a.k_chunk = k_chunk;
     a.vec_ok = 1;
+    a.vec_out = (g.out_lp && g.ldc % 8 == 0 && (uintptr_t)g.C % 16 == 0) ? 1 : 0;
     const int tiles_m = (g.M + GBM - 1) / GBM, tiles_n = (g.N + GBN - 1) / GBN;
     const dim3 grid(tiles_m * tiles_n, 1, splits);
     KernelTimer timer(g.kclass, stream, 2.0 * g.M * g.N * g.K, gemm_algorithmic_bytes<T>(g));
-    if (!g.A.trans && !g.B.trans)
-        hipLaunchKernelGGL((gemm_mfma_big_kernel<T, false, false, true>), grid, dim3(GTHREADS), 0, stream, a, tiles_m, tiles_n);
-    else if (!g.A.trans && g.B.trans)
-        hipLaunchKernelGGL((gemm_mfma_big_kernel<T, false, true, true>), grid, dim3(GTHREADS), 0, stream, a, tiles_m, tiles_n);
-    else if (g.A.trans && g.B.trans)
-        hipLaunchKernelGGL((gemm_mfma_big_kernel<T, true, true, true>), grid, dim3(GTHREADS), 0, stream, a, tiles_m, tiles_n);
+    static const int nw = getenv("LSTM_GEMM_WAVES") ? atoi(getenv("LSTM_GEMM_WAVES")) : 9;
+#define BIG_LAUNCH(TA_, TB2_)                                                                                              \
+    do {                                                                                                                   \
+        if (nw == 4)                                                                                                       \
+            hipLaunchKernelGGL((gemm_mfma_big_kernel<T, TA_, TB2_, true, 4>), grid, dim3(256), 0, stream, a, tiles_m, tiles_n); \
+        else if (nw == 9)                                                                                                  \
+            hipLaunchKernelGGL((gemm_mfma_big_kernel<T, TA_, TB2_, true, 8, true>), grid, dim3(512), 0, stream, a, tiles_m, tiles_n); \
+        else                                                                                                               \
+            hipLaunchKernelGGL((gemm_mfma_big_kernel<T, TA_, TB2_, true, 8>), grid, dim3(512), 0, stream, a, tiles_m, tiles_n); \
+    } while (0)
+    if (!g.A.trans && !g.B.trans) BIG_LAUNCH(false, false);
+    else if (!g.A.trans && g.B.trans) BIG_LAUNCH(false, true);
+    else if (g.A.trans && g.B.trans) BIG_LAUNCH(true, true);
     else {
         set_error("gemm_blocked: operand roles (A transposed, B not) have no kernel");
         return LSTM_ERR_UNSUPPORTED;

@@ -133,6 +133,34 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T *in, int64_
     __syncthreads();
     if (ry == 0 && c < C) partial[(int64_t)blockIdx.y * C + c] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
 }
+// 16-bit types, 8 columns (one 16-byte load) per thread: a wavefront reads 1 KB of a row at once
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_partial_vec_kernel(const T *in, int64_t ld, int R, int C, const float *row_w,
+                                                                 float *partial) {
+    __shared__ float red[4][64][9];
+    const int lane = threadIdx.x & 63, ry = threadIdx.x >> 6;
+    const int c = blockIdx.x * 512 + lane * 8;
+    const int r_beg = blockIdx.y * CS_ROWS, r_end = min(R, r_beg + CS_ROWS);
+    float s[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+    if (c < C)
+#pragma unroll 4
+        for (int r = r_beg + ry; r < r_end; r += 4) {
+            const u32x4 raw = *reinterpret_cast<const u32x4 *>(in + (int64_t)r * ld + c);
+            T v[8];
+            __builtin_memcpy(v, &raw, 16);
+            const float w = row_w ? row_w[r] : 1.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s[e] += row_w ? w * Lp<T>::to_f(v[e]) : Lp<T>::to_f(v[e]);
+        }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[ry][lane][e] = s[e];
+    __syncthreads();
+    for (int i = threadIdx.x; i < 512; i += 256) {
+        const int l = i >> 3, e = i & 7;
+        if (blockIdx.x * 512 + i < C)
+            partial[(int64_t)blockIdx.y * C + blockIdx.x * 512 + i] = (red[0][l][e] + red[1][l][e]) + (red[2][l][e] + red[3][l][e]);
+    }
+}
 template <typename T>
 __global__ void colsum_final_kernel(const float *partial, int chunks, int C, const float *scale_dev, T *out) {
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
@@ -321,8 +349,14 @@ int colsum(int dtype, const void *in, int64_t ld, int R, int C, const float *row
         set_error("colsum: too many rows %d", R);
         return LSTM_ERR_UNSUPPORTED;
     }
+    const bool vec = dtype != LSTM_DTYPE_FP32 && C % 8 == 0 && ld % 8 == 0 && (uintptr_t)in % 16 == 0;
     LSTM_DISPATCH(dtype, T, {
-        hipLaunchKernelGGL(colsum_partial_kernel<T>, grid, dim3(256), 0, s, (const T *)in, ld, R, C, row_w, partial);
+        if constexpr (sizeof(T) == 2) {
+            if (vec)
+                hipLaunchKernelGGL(colsum_partial_vec_kernel<T>, dim3((C + 511) / 512, chunks), dim3(256), 0, s, (const T *)in, ld,
+                                   R, C, row_w, partial);
+        }
+        if (!vec) hipLaunchKernelGGL(colsum_partial_kernel<T>, grid, dim3(256), 0, s, (const T *)in, ld, R, C, row_w, partial);
         hipLaunchKernelGGL(colsum_final_kernel<T>, dim3((C + 255) / 256), dim3(256), 0, s, partial, chunks, C, scale_dev, (T *)out_lp);
     });
     LSTM_LAUNCH_CHECK();

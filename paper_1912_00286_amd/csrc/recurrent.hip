@@ -234,7 +234,10 @@ __global__ __launch_bounds__(256) void lstm_step_backward_gemm_kernel(BwdArgs a)
     __shared__ __attribute__((aligned(16))) float smem[4 * RED_FLOATS];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lin = xcd_swizzle(blockIdx.x, gridDim.x);
-    const int q = lin & 3, tile = lin >> 2;
+    // gate-slice major: the workgroups of one XCD share one K slice, so that XCD's L2 pulls
+    // only that quarter of dA over the fabric (all of it would be fetched by all eight otherwise)
+    const int per_q = (int)gridDim.x >> 2;
+    const int q = lin / per_q, tile = lin - q * per_q;
     const int mt = tile % a.n_mt, nt = tile / a.n_mt;
     const int m0 = mt * TM, n0 = nt * TN;
     const int H = a.H;
