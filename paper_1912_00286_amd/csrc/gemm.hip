@@ -182,7 +182,7 @@ __global__ __launch_bounds__(THREADS) void gemm_nt_mfma_kernel(KernArgs a) {
 //                  of the activations is ever made.
 // Aligned operands only (every leading dimension, and K resp. M/N, a multiple of 8).
 constexpr int GBM = 256, GBN = 256, GBK = 64;
-constexpr int GTHREADS = 512;                    // the eight-wavefront form
+constexpr int GTHREADS = 512;
 constexpr int GLD = GBK + LDS_PAD;               // row pitch, rows = operand rows
 constexpr int GLDT = GBM + 32;                   // row pitch, rows = k (transposed form)
 constexpr int GVPR = GBK / 8;                    // 16-byte vectors per operand row of a K tile
@@ -208,26 +208,92 @@ __device__ __forceinline__ u32x4 read_frag_tr(const uint16_t *tile, int m0, int 
     return __builtin_bit_cast(u32x4, both);
 }
 
+// Result tile of the large-tile kernels: bias, then split-K partials, 16-bit or fp32 result.
+// MI: 32-row MFMA blocks per wavefront; wavefront (wm, wn) owns rows (wm MI + i) 32.., columns wn 128...
+template <typename T, int MI, int GTHREADS>
+__device__ __forceinline__ void big_epilogue(const KernArgs &a, BigSmem &sm, v16f (&acc)[MI][4], int m0, int n0, int wm, int wn,
+                                             int lane, int tid) {
+    const int col_l = lane & 31, rgrp = (lane >> 5) * 4;
+    const T *bias = reinterpret_cast<const T *>(a.bias);
+    if (a.out_lp && !a.ws && a.vec_out) {
+        // 16-bit result: the accumulators hold one column per lane, which would go out as 2-byte
+        // stores.  Stage the tile in LDS (free once the last K tile has been multiplied) and
+        // write it as whole 512-byte row segments instead.
+        constexpr int OLD = GBN + 8;                       // staging row pitch (elements)
+        static_assert(GBM * OLD * 2 <= (int)sizeof(BigSmem), "staged tile must fit the operand buffers");
+        T *stage = reinterpret_cast<T *>(&sm);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int cl = wn * 128 + j * 32 + col_l;
+            const int col = n0 + cl;
+            const float bv = (bias && col < a.N) ? Lp<T>::to_f(bias[col]) : 0.0f;
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int rl = (wm * MI + i) * 32 + (r >> 2) * 8 + rgrp + (r & 3);
+                    stage[rl * OLD + cl] = Lp<T>::from_f(acc[i][j][r] + bv);
+                }
+        }
+        __syncthreads();
+        T *C = reinterpret_cast<T *>(a.C);
+#pragma unroll 4
+        for (int v = tid; v < GBM * (GBN / 8); v += GTHREADS) {
+            const int rl = v / (GBN / 8), cl = (v % (GBN / 8)) * 8;
+            const int row = m0 + rl, col = n0 + cl;
+            if (row >= a.M || col >= a.N) continue;
+            const u32x4 val = *reinterpret_cast<const u32x4 *>(&stage[rl * OLD + cl]);
+            if (col + 8 <= a.N) {
+                *reinterpret_cast<u32x4 *>(&C[(int64_t)row * a.ldc + col]) = val;
+            } else {
+                T e[8];
+                __builtin_memcpy(e, &val, 16);
+                for (int q = 0; q < a.N - col; ++q) C[(int64_t)row * a.ldc + col + q] = e[q];
+            }
+        }
+        return;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int col = n0 + wn * 128 + j * 32 + col_l;
+        if (col >= a.N) continue;
+        const float bv = (bias && blockIdx.z == 0) ? Lp<T>::to_f(bias[col]) : 0.0f;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + (wm * MI + i) * 32 + (r >> 2) * 8 + rgrp + (r & 3);
+                if (row >= a.M) continue;
+                const float v = acc[i][j][r] + bv;
+                if (a.ws) {
+                    a.ws[((int64_t)blockIdx.z * a.M + row) * a.N + col] = v;
+                } else if (a.out_lp) {
+                    reinterpret_cast<T *>(a.C)[(int64_t)row * a.ldc + col] = Lp<T>::from_f(v);
+                } else {
+                    float *c = reinterpret_cast<float *>(a.C) + (int64_t)row * a.ldc + col;
+                    *c = a.accumulate ? (*c + v) : v;
+                }
+            }
+    }
+}
+
 // TA / TB_: operand A / B is in the transposed role (its rows are the contraction index).
 // BLK: operands are stored in 64x64 blocks ([row block][column block][64][64], zero padded to
 //      whole blocks; lda / ldb then hold the number of column blocks per row block and K is a
 //      multiple of 64).  A K tile of an operand is then four contiguous 8 KB blocks instead of 256
 //      row segments of 128 bytes, which is what the L2 -> CU path streams at full rate.
-// NW: wavefronts per workgroup.  8: 4 x 2 wavefronts of 64 x 128 (two per SIMD).  4: 2 x 2
-//     wavefronts of 128 x 128 (one per SIMD, 256 accumulator registers each), which reads a
-//     third less from LDS per MFMA.
-template <typename T, bool TA, bool TB_, bool BLK, int NW, bool PP = false>
-__global__ __launch_bounds__(NW * 64) void gemm_mfma_big_kernel(KernArgs a, int tiles_m, int tiles_n) {
-    constexpr int GTHREADS = NW * 64;
-    constexpr int GNV = GBM * GBK / 8 / GTHREADS;  // 16-byte vectors per thread, operand and K tile
-    constexpr int MI = 8 / NW * 2;                 // 32-row MFMA blocks per wavefront (2 or 4)
+// PP:  steady state in the ping-pong slot schedule (below) instead of the plain two-stage loop.
+template <typename T, bool TA, bool TB_, bool BLK, bool PP>
+__global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a, int tiles_m, int tiles_n) {
+    constexpr int GNV = GBM * GBK / 8 / GTHREADS;  // 16-byte vectors per thread, operand and K tile (4)
+    constexpr int MI = 2;                          // 32-row MFMA blocks per wavefront
     __shared__ __attribute__((aligned(16))) BigSmem sm;
     const T *A = reinterpret_cast<const T *>(a.A);
     const T *B = reinterpret_cast<const T *>(a.B);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;       // (NW / 2) x 2 wavefronts of (32 MI) x 128
+    const int wm = wave >> 1, wn = wave & 1;       // 4 x 2 wavefronts of 64 x 128
     // tile order: workgroups of one XCD (id % 8) take neighbouring tiles, and tiles
     // are walked in bands of 8 tile rows so that a band's A and B panels stay in L2
     const int total = tiles_m * tiles_n;
@@ -351,7 +417,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_big_kernel(KernArgs a, int 
         if (ntiles > 2) gload_any(a0, b0r, 2);
         __syncthreads();
         int t = 0;
-        if constexpr (PP && NW == 8) {
+        if constexpr (PP) {
             // Ping-pong schedule.  The first four wavefronts sit on the four SIMDs, the second four
             // share them.  Every k-step is split into a slot that reads its fragments from LDS (and
             // moves a quarter of the next tile: registers -> LDS, global -> registers) and a slot
@@ -433,68 +499,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_big_kernel(KernArgs a, int 
         }
     }
 
-    const int col_l = lane & 31, rgrp = (lane >> 5) * 4;
-    const T *bias = reinterpret_cast<const T *>(a.bias);
-    if (a.out_lp && !a.ws && a.vec_out) {
-        // 16-bit result: the accumulators hold one column per lane, which would go out as 2-byte
-        // stores.  Stage the tile in LDS (free once the last K tile has been multiplied) and
-        // write it as whole 512-byte row segments instead.
-        constexpr int OLD = GBN + 8;                       // staging row pitch (elements)
-        static_assert(GBM * OLD * 2 <= (int)sizeof(BigSmem), "staged tile must fit the operand buffers");
-        T *stage = reinterpret_cast<T *>(&sm);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int cl = wn * 128 + j * 32 + col_l;
-            const int col = n0 + cl;
-            const float bv = (bias && col < a.N) ? Lp<T>::to_f(bias[col]) : 0.0f;
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int rl = (wm * MI + i) * 32 + (r >> 2) * 8 + rgrp + (r & 3);
-                    stage[rl * OLD + cl] = Lp<T>::from_f(acc[i][j][r] + bv);
-                }
-        }
-        __syncthreads();
-        T *C = reinterpret_cast<T *>(a.C);
-#pragma unroll 4
-        for (int v = tid; v < GBM * (GBN / 8); v += GTHREADS) {
-            const int rl = v / (GBN / 8), cl = (v % (GBN / 8)) * 8;
-            const int row = m0 + rl, col = n0 + cl;
-            if (row >= a.M || col >= a.N) continue;
-            const u32x4 val = *reinterpret_cast<const u32x4 *>(&stage[rl * OLD + cl]);
-            if (col + 8 <= a.N) {
-                *reinterpret_cast<u32x4 *>(&C[(int64_t)row * a.ldc + col]) = val;
-            } else {
-                T e[8];
-                __builtin_memcpy(e, &val, 16);
-                for (int q = 0; q < a.N - col; ++q) C[(int64_t)row * a.ldc + col + q] = e[q];
-            }
-        }
-        return;
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int col = n0 + wn * 128 + j * 32 + col_l;
-        if (col >= a.N) continue;
-        const float bv = (bias && blockIdx.z == 0) ? Lp<T>::to_f(bias[col]) : 0.0f;
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + (wm * MI + i) * 32 + (r >> 2) * 8 + rgrp + (r & 3);
-                if (row >= a.M) continue;
-                const float v = acc[i][j][r] + bv;
-                if (a.ws) {
-                    a.ws[((int64_t)blockIdx.z * a.M + row) * a.N + col] = v;
-                } else if (a.out_lp) {
-                    reinterpret_cast<T *>(a.C)[(int64_t)row * a.ldc + col] = Lp<T>::from_f(v);
-                } else {
-                    float *c = reinterpret_cast<float *>(a.C) + (int64_t)row * a.ldc + col;
-                    *c = a.accumulate ? (*c + v) : v;
-                }
-            }
-    }
+    big_epilogue<T, MI, GTHREADS>(a, sm, acc, m0, n0, wm, wn, lane, tid);
 }
 
 // row-major [R, C] (leading dimension ld) -> 64x64 blocks, zero padded
@@ -641,7 +646,7 @@ int launch(const GemmArgs &g, hipStream_t stream) {
         hipLaunchKernelGGL(gemm_nt_f32_kernel, dim3(tiles_n, tiles_m, splits), dim3(256), 0, stream, a);
     } else {
         if (big) {
-            hipLaunchKernelGGL((gemm_mfma_big_kernel<T, false, false, false, 8>), dim3(tiles_m * tiles_n, 1, splits), dim3(GTHREADS), 0,
+            hipLaunchKernelGGL((gemm_mfma_big_kernel<T, false, false, false, false>), dim3(tiles_m * tiles_n, 1, splits), dim3(GTHREADS), 0,
                                stream, a, tiles_m, tiles_n);
         } else if (a.vec_ok) {
             hipLaunchKernelGGL((gemm_nt_mfma_kernel<T, true>), dim3(tiles_n, tiles_m, splits), dim3(THREADS), 0, stream, a);
@@ -673,7 +678,7 @@ int launch_tn(const GemmArgs &g, hipStream_t stream) {
     a.vec_out = (g.out_lp && g.ldc % 8 == 0 && (uintptr_t)g.C % 16 == 0) ? 1 : 0;
     const int tiles_m = (g.M + GBM - 1) / GBM, tiles_n = (g.N + GBN - 1) / GBN;
     KernelTimer timer(g.kclass, stream, 2.0 * g.M * g.N * g.K, gemm_algorithmic_bytes<T>(g));
-    hipLaunchKernelGGL((gemm_mfma_big_kernel<T, true, true, false, 8>), dim3(tiles_m * tiles_n, 1, splits), dim3(GTHREADS), 0, stream,
+    hipLaunchKernelGGL((gemm_mfma_big_kernel<T, true, true, false, false>), dim3(tiles_m * tiles_n, 1, splits), dim3(GTHREADS), 0, stream,
                        a, tiles_m, tiles_n);
     LSTM_LAUNCH_CHECK();
     return finish_splitk<T>(g, splits, stream);
@@ -732,19 +737,12 @@ int launch_blocked(const BlockedGemmArgs &g, hipStream_t stream) {
     const int tiles_m = (g.M + GBM - 1) / GBM, tiles_n = (g.N + GBN - 1) / GBN;
     const dim3 grid(tiles_m * tiles_n, 1, splits);
     KernelTimer timer(g.kclass, stream, 2.0 * g.M * g.N * g.K, gemm_algorithmic_bytes<T>(g));
-    static const int nw = getenv("LSTM_GEMM_WAVES") ? atoi(getenv("LSTM_GEMM_WAVES")) : 9;
-#define BIG_LAUNCH(TA_, TB2_)                                                                                              \
-    do {                                                                                                                   \
-        if (nw == 4)                                                                                                       \
-            hipLaunchKernelGGL((gemm_mfma_big_kernel<T, TA_, TB2_, true, 4>), grid, dim3(256), 0, stream, a, tiles_m, tiles_n); \
-        else if (nw == 9)                                                                                                  \
-            hipLaunchKernelGGL((gemm_mfma_big_kernel<T, TA_, TB2_, true, 8, true>), grid, dim3(512), 0, stream, a, tiles_m, tiles_n); \
-        else                                                                                                               \
-            hipLaunchKernelGGL((gemm_mfma_big_kernel<T, TA_, TB2_, true, 8>), grid, dim3(512), 0, stream, a, tiles_m, tiles_n); \
-    } while (0)
-    if (!g.A.trans && !g.B.trans) BIG_LAUNCH(false, false);
-    else if (!g.A.trans && g.B.trans) BIG_LAUNCH(false, true);
-    else if (g.A.trans && g.B.trans) BIG_LAUNCH(true, true);
+    if (!g.A.trans && !g.B.trans)
+        hipLaunchKernelGGL((gemm_mfma_big_kernel<T, false, false, true, true>), grid, dim3(GTHREADS), 0, stream, a, tiles_m, tiles_n);
+    else if (!g.A.trans && g.B.trans)
+        hipLaunchKernelGGL((gemm_mfma_big_kernel<T, false, true, true, true>), grid, dim3(GTHREADS), 0, stream, a, tiles_m, tiles_n);
+    else if (g.A.trans && g.B.trans)
+        hipLaunchKernelGGL((gemm_mfma_big_kernel<T, true, true, true, true>), grid, dim3(GTHREADS), 0, stream, a, tiles_m, tiles_n);
     else {
         set_error("gemm_blocked: operand roles (A transposed, B not) have no kernel");
         return LSTM_ERR_UNSUPPORTED;
