@@ -240,6 +240,31 @@ def grad_average(worker_grads, loss_scale):
     return total / N / float(loss_scale), found_inf
 
 
+def grad_average_partial(worker_grads, loss_scale, participating):
+    """Fault-tolerant variant of step 4 (Section "Distributed computing
+    framework", closing paragraph): the master averages once a fraction of the
+    workers has delivered, so only the gradients that arrived are summed and
+    the divisor is their number.  worker_grads: [N,P]; participating: N flags.
+    Rows of absent workers are never looked at.  Returns (avg[P], found_inf,
+    n_present); with nobody present the average is zero."""
+    g = np.asarray(worker_grads, dtype=np.float64)
+    N, P = g.shape
+    total = np.zeros(P, dtype=np.float64)
+    n_present = 0
+    found_inf = False
+    for w in range(N):
+        if not participating[w]:
+            continue
+        n_present += 1
+        if not np.all(np.isfinite(g[w])):
+            found_inf = True
+        with np.errstate(invalid="ignore"):
+            total = total + g[w]
+    if n_present == 0:
+        return total, False, 0
+    return total / n_present / float(loss_scale), found_inf, n_present
+
+
 def lr_schedule(lr0, n_workers, n_half, eff_lr_max, warmup_steps, gamma, index):
     """Learning rate for iteration/epoch `index` with N workers.
 

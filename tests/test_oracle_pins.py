@@ -409,3 +409,51 @@ def test_training_step_matches_pieces():
     assert not out["found_inf"]
     np.testing.assert_allclose(out["W"], flat - 0.01 * out["avg_grad"], rtol=1e-14)
     np.testing.assert_allclose(out["avg_grad"], out["worker_grads"].mean(0) / 128.0, rtol=1e-13)
+
+
+# ---------------------------------------------------------------- fault-tolerant average
+def test_partial_average_by_hand_and_invariants():
+    """Averaging only the workers that reported (Section "Distributed computing
+    framework", closing paragraph)."""
+    # worked by hand: workers 0 and 1 present, scale 2 -> ((2+6)/2/2, (4+8)/2/2)
+    g = np.array([[2.0, 4.0], [6.0, 8.0], [100.0, -100.0]])
+    avg, bad, n = orc.grad_average_partial(g, 2.0, [1, 1, 0])
+    assert n == 2 and not bad
+    np.testing.assert_array_equal(avg, [2.0, 3.0])
+    # one participant: its own gradient over the scale
+    avg, bad, n = orc.grad_average_partial(g, 4.0, [0, 0, 1])
+    assert n == 1 and not bad
+    np.testing.assert_array_equal(avg, [25.0, -25.0])
+    # nobody: zero, no overflow flag
+    avg, bad, n = orc.grad_average_partial(g, 4.0, [0, 0, 0])
+    assert n == 0 and not bad and not avg.any()
+
+    rng = np.random.default_rng(11)
+    N, P, S = 9, 37, 128.0
+    g = rng.normal(size=(N, P))
+    mask = np.array([1, 0, 1, 1, 0, 1, 1, 1, 0])
+    avg, bad, n = orc.grad_average_partial(g, S, mask)
+    # library mean over the selected rows
+    np.testing.assert_allclose(avg, g[mask.astype(bool)].mean(axis=0) / S, rtol=1e-14, atol=0)
+    assert n == 6 and not bad
+    # everybody present: the lock-step average
+    full, bad_full = orc.grad_average(g, S)
+    part, bad_part, n_all = orc.grad_average_partial(g, S, np.ones(N, dtype=int))
+    np.testing.assert_allclose(part, full, rtol=1e-15, atol=0)
+    assert n_all == N and bad_part == bad_full
+    # what an absent worker holds is irrelevant, Inf and NaN included
+    g2 = g.copy()
+    g2[1] = np.inf
+    g2[4] = np.nan
+    g2[8] = -1e30
+    avg2, bad2, _ = orc.grad_average_partial(g2, S, mask)
+    np.testing.assert_array_equal(avg2, avg)
+    assert not bad2
+    # ... and an Inf in a present worker is reported
+    g3 = g.copy()
+    g3[3, 5] = np.inf
+    assert orc.grad_average_partial(g3, S, mask)[1]
+    # order of the workers does not matter beyond rounding
+    perm = rng.permutation(N)
+    avg_p, _, _ = orc.grad_average_partial(g[perm], S, mask[perm])
+    np.testing.assert_allclose(avg_p, avg, rtol=1e-13, atol=1e-18)
