@@ -58,6 +58,39 @@ def measured_traffic(workload: str, kernel_class: str):
     return None
 
 
+def measured_peaks(hip, torch, dtype: str):
+    """What this GPU sustains on the two plain patterns the rooflines are named after, measured here:
+    a register-resident MFMA loop (on constant operands and on N(0,1) operands: power management
+    makes the rate depend on the operand values) and a plain 1 GiB device copy."""
+    dev = torch.device("cuda:0")
+    res = {}
+    if dtype in ("fp16", "bf16"):
+        tdt, code = (torch.float16, hip.DTYPE_FP16) if dtype == "fp16" else (torch.bfloat16, hip.DTYPE_BF16)
+        n = 256 * 512 * 2 * 8
+        sink = torch.zeros(1, dtype=torch.float32, device=dev)
+        gen = torch.Generator(device="cpu").manual_seed(0)
+        for label, ops in (("constant", torch.full((n,), 0.5, dtype=tdt, device=dev)),
+                           ("normal", torch.randn(n, generator=gen).to(tdt).to(dev))):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            hip.lstm_debug_mfma_rate(code, ops, 2000, sink)            # warm-up
+            e0.record()
+            flops = hip.lstm_debug_mfma_rate(code, ops, 40000, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            res[f"mfma_{label}_operands_tflops"] = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    res["device_copy_gbs"] = 5 * 2.0 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    return res
+
+
 def cpu_baseline(w, budget_flops=6.0e12):
     """Time the CPU oracle (as it stands) on a bounded sample of the workload:
     same model and batch, sequence shortened so the fp64 work stays near
@@ -88,10 +121,12 @@ def cpu_baseline(w, budget_flops=6.0e12):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="large")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--eager", action="store_true",
+                    help="enqueue every launch from the host in the timed region instead of replaying a HIP graph")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run 5 plain device copies of 1 GiB and exit (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -127,9 +162,14 @@ def main():
     dx, dy = pu.device_batches(w, xs, ys, ts.lp_dtype, dev)
     del xs, ys
 
+    # fprop + BPTT of every worker and the gradient average are recorded once as a HIP graph (this
+    # runs nothing); a step is then one graph launch plus master_update with that step's rate
+    if not args.eager:
+        ts.capture(dx, dy)
+    run_step = (lambda lr: ts.step(dx, dy, lr)) if args.eager else ts.step_captured
     k = 0
     for _ in range(args.warmup):
-        ts.step(dx, dy, pu.lr_for(w, k)); k += 1
+        run_step(pu.lr_for(w, k)); k += 1
     torch.cuda.synchronize()
     good0, scale0 = int(ts.good_steps.item()), float(ts.loss_scale.item())
     log(f"[bench] warm-up done, loss {ts.losses[0].item():.5f}, loss scale {scale0}")
@@ -138,7 +178,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        ts.step(dx, dy, pu.lr_for(w, k)); k += 1
+        run_step(pu.lr_for(w, k)); k += 1
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     overflow_steps = None
@@ -200,6 +240,7 @@ def main():
         "sequential_steps_per_s": w.seq_len * w.num_layers * w.n_workers * args.steps / dt,
         "step_mfma_frac": gemm_flops_per_step(w) / (ms_per_step * 1e-3) / 1e12 / PEAK_TFLOPS[w.dtype],
         "gate_gemm_mfma_frac": (gemm_fl / (gemm_ms * 1e-3) / 1e12 / PEAK_TFLOPS[w.dtype]) if gemm_ms > 0 else None,
+        "launch": "eager" if args.eager else "hip_graph (fprop+BPTT+grad_average) + master_update",
         "overflow_steps": overflow_steps, "loss_scale": float(ts.loss_scale.item()), "loss": loss_after,
         "roofline": roof,
         "kernel_classes": {n: {"ms_per_step": round(v["ms_per_step"], 4), "launches_per_step": v["launches"] / args.steps,
@@ -210,6 +251,7 @@ def main():
     }
     del ts, dx, dy
     torch.cuda.empty_cache()
+    out["measured_peaks"] = measured_peaks(hip, torch, w.dtype)
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(w)

@@ -148,6 +148,20 @@ int lstm_backward(const lstm_config *cfg, const void *params_lp, const void *x, 
 int grad_average(int64_t n_params, int32_t n_workers, const void *grads_lp, int32_t dtype,
                  const float *loss_scale, float *avg_grad, int32_t *found_inf, void *stream);
 
+/* Fault-tolerant form of step 4 (Section "Distributed computing framework", last paragraph:
+ * the master proceeds once a fraction of the workers, normally 90-95 %, has delivered).
+ * Only the gradients of the workers that reported enter the average and the Inf/NaN test;
+ * the rows of the others are never read.  Whether enough workers have reported is the
+ * caller's decision, taken before the call.
+ *   participating   : device, int32[n_workers], non-zero = this worker's gradient is present.
+ *   avg_grad        : device, out, fp32[n_params] = sum over present w of g_w / (n_present * scale);
+ *                     all zero when nobody is present.
+ *   n_participating : device, out, one int32 = n_present (may be NULL).
+ * Everything else as grad_average. */
+int grad_average_masked(int64_t n_params, int32_t n_workers, const void *grads_lp, int32_t dtype,
+                        const float *loss_scale, const int32_t *participating, float *avg_grad,
+                        int32_t *found_inf, int32_t *n_participating, void *stream);
+
 /* Step 5: optimiser state and global weights (Eq. 1-2:  H <- m H - lr g,
  * W <- W + H) on fp32 master weights, then round to the lp working copy.
  *   lr         : learning rate for this iteration (see lr_schedule).
@@ -203,6 +217,15 @@ int lstm_debug_gemm(int32_t dtype, int32_t layout, int32_t M, int32_t N, int32_t
                     float *splitk_ws, int32_t splits, void *stream);
 /* dst (64x64 blocks, zero padded to whole blocks: ceil(rows/64)*ceil(cols/64)*4096 elements) =
  * src (row-major [rows, cols]).  Both device. */
+/* Enqueues a loop of `iters` x 8 independent 32x32x16 MFMAs per wavefront (256 workgroups of 8
+ * wavefronts) whose operands stay in registers: the rate the matrix pipes sustain on the given
+ * operand values, which depends on the values through the chip's power management.
+ *   operands: device, 256*512*2 fragments of 16 bytes (8 lp values each), read once
+ *   sink:     device, 1 float (never written in practice)
+ *   flops:    host, out (may be NULL): floating-point operations the launch performs
+ * 16-bit types only; 1 <= iters <= 2^22.  The caller times the launch. */
+int lstm_debug_mfma_rate(int32_t dtype, const void *operands, int32_t iters, float *sink, double *flops, void *stream);
+
 int lstm_debug_pack_blocked(int32_t dtype, const void *src, int32_t rows, int32_t cols, void *dst, void *stream);
 
 #ifdef __cplusplus

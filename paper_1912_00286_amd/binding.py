@@ -63,16 +63,18 @@ def load_library():
     lib.lstm_forward.argtypes = [cfgp] + [vp] * 11
     lib.lstm_backward.argtypes = [cfgp] + [vp] * 8
     lib.grad_average.argtypes = [i64, i32, vp, i32, vp, vp, vp, vp]
+    lib.grad_average_masked.argtypes = [i64, i32, vp, i32, vp, vp, vp, vp, vp, vp]
     lib.master_update.argtypes = [i64, optp, f32, i64, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
     lib.lr_schedule.argtypes = [f32, i32, f32, f32, i32, f32, i64]
     lib.lr_schedule.restype = f32
     lib.lstm_debug_gemm.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, i32, vp]
     lib.lstm_debug_pack_blocked.argtypes = [i32, vp, i32, i32, vp, vp]
+    lib.lstm_debug_mfma_rate.argtypes = [i32, vp, i32, vp, C.POINTER(C.c_double), vp]
     lib.lstm_timing_enable.argtypes = [i32]
     lib.lstm_timing_read.argtypes = [i32, C.POINTER(i64), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double)]
     for name in ("lstm_param_count", "lstm_param_offset", "lstm_workspace_bytes", "lstm_forward", "lstm_backward",
-                 "grad_average", "master_update", "lstm_timing_enable", "lstm_timing_read", "lstm_debug_gemm",
-                 "lstm_debug_pack_blocked"):
+                 "grad_average", "grad_average_masked", "master_update", "lstm_timing_enable", "lstm_timing_read", "lstm_debug_gemm",
+                 "lstm_debug_pack_blocked", "lstm_debug_mfma_rate"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -142,6 +144,13 @@ def grad_average(n_params, n_workers, grads_lp, dtype, loss_scale, avg_grad, fou
                                        _ptr(found_inf), _stream(stream)))
 
 
+def grad_average_masked(n_params, n_workers, grads_lp, dtype, loss_scale, participating, avg_grad, found_inf,
+                        n_participating=None, stream=None):
+    _check(load_library().grad_average_masked(n_params, n_workers, _ptr(grads_lp), dtype, _ptr(loss_scale),
+                                              _ptr(participating), _ptr(avg_grad), _ptr(found_inf),
+                                              _ptr(n_participating), _stream(stream)))
+
+
 def master_update(n_params, opt, lr, step, master, state1, state2, avg_grad, found_inf, loss_scale, good_steps,
                   params_lp_out, dtype, stream=None):
     _check(load_library().master_update(n_params, C.byref(opt), lr, step, _ptr(master), _ptr(state1), _ptr(state2),
@@ -169,6 +178,13 @@ def lstm_timing_read(kernel_class: int):
 def lstm_debug_gemm(dtype, layout, M, N, K, A, B, Cout, splitk_ws=None, splits=1, stream=None):
     _check(load_library().lstm_debug_gemm(dtype, layout, M, N, K, _ptr(A), _ptr(B), _ptr(Cout), _ptr(splitk_ws), splits,
                                           _stream(stream)))
+
+
+def lstm_debug_mfma_rate(dtype, operands, iters, sink, stream=None) -> float:
+    """Enqueue the register-resident MFMA loop; returns the flops it performs."""
+    fl = C.c_double()
+    _check(load_library().lstm_debug_mfma_rate(dtype, _ptr(operands), iters, _ptr(sink), C.byref(fl), _stream(stream)))
+    return fl.value
 
 
 def lstm_debug_pack_blocked(dtype, src, rows, cols, dst, stream=None):
@@ -224,3 +240,27 @@ class TrainingStep:
     def step(self, xs, ys, lr: float):
         self.forward_backward(xs, ys)
         self.update(lr)
+
+    # ---- the same step as one HIP graph launch plus the master update -----------------
+    # Small models are bound by the host's launch rate (three launches per layer and time
+    # step); replaying a recorded graph removes the per-launch host work.  The library
+    # allocates nothing, never synchronises and records no memset, so its launches can be
+    # captured as they are.  The graph holds the addresses of xs / ys: later batches are
+    # copied into those same tensors.  The learning rate and the step count change from step
+    # to step and are passed by value, so master_update stays outside the graph.
+    def capture(self, xs, ys):
+        torch = self.torch
+        self._captured_inputs = (xs, ys)             # the graph reads these buffers on every replay
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.forward_backward(xs, ys)
+            grad_average(self.P, self.N, self.grads, self.cfg.dtype, self.loss_scale, self.avg, self.found_inf)
+        self.graph = graph
+
+    def step_captured(self, lr: float):
+        if getattr(self, "graph", None) is None:
+            raise RuntimeError("step_captured: call capture(xs, ys) first")
+        self.graph.replay()
+        self.step_index += 1
+        master_update(self.P, self.opt, lr, self.step_index, self.master, self.state1, self.state2, self.avg,
+                      self.found_inf, self.loss_scale, self.good_steps, self.params_lp, self.cfg.dtype)

@@ -578,6 +578,12 @@ extern "C" int lstm_debug_gemm(int32_t dtype, int32_t layout, int32_t M, int32_t
     return gemm_blocked(dtype, g, s);
 }
 
+// Diagnostic: register-resident MFMA loop on caller-provided operand values.
+extern "C" int lstm_debug_mfma_rate(int32_t dtype, const void *operands, int32_t iters, float *sink, double *flops,
+                                    void *stream) {
+    return mfma_rate(dtype, operands, iters, sink, flops, (hipStream_t)stream);
+}
+
 // Diagnostic: row-major [rows, cols] -> 64x64 blocks.
 extern "C" int lstm_debug_pack_blocked(int32_t dtype, const void *src, int32_t rows, int32_t cols, void *dst, void *stream) {
     return pack_blocked(dtype, src, cols, rows, cols, dst, (hipStream_t)stream);

@@ -173,6 +173,8 @@ bool gemm_blocked_supported(int dtype, int M, int N);
 // supported role pairs: (0,0), (0,1), (1,1).
 int gemm_blocked(int dtype, const BlockedGemmArgs &g, hipStream_t stream);
 // number of K splits gemm_nt / gemm_tn would like for this shape (>= 1)
+// Diagnostic MFMA loop: operands = 256*512*2 16-byte fragments (device), sink = 1 float (device).
+int mfma_rate(int dtype, const void *operands, int iters, float *sink, double *flops, hipStream_t stream);
 int gemm_pick_splits(int dtype, int M, int N, int K);
 
 }  // namespace lstm

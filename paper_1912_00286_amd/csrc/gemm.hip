@@ -808,4 +808,44 @@ int gemm_tn(int dtype, const GemmArgs &g, hipStream_t stream) {
     return dtype == LSTM_DTYPE_FP16 ? launch_tn<_Float16>(g, stream) : launch_tn<bf16_t>(g, stream);
 }
 
+// Diagnostic: register-resident MFMA loop (no memory traffic inside the loop), the rate the matrix
+// pipes sustain on the given operand values.  256 workgroups x 8 wavefronts, 8 independent 32x32
+// accumulators per wavefront; every lane takes its two fragments from `operands`.
+namespace {
+template <typename T>
+__global__ __launch_bounds__(512) void mfma_rate_kernel(const u32x4 *operands, int iters, float *sink) {
+    const u32x4 fa = operands[(blockIdx.x * 512 + threadIdx.x) * 2];
+    const u32x4 fb = operands[(blockIdx.x * 512 + threadIdx.x) * 2 + 1];
+    v16f acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = Lp<T>::mfma(fa, fb, acc[j]);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[j][r];
+    if (s == 12345.678f) sink[0] = s;              // keeps the loop alive; practically never taken
+}
+}  // namespace
+
+int mfma_rate(int dtype, const void *operands, int iters, float *sink, double *flops, hipStream_t stream) {
+    if (dtype == LSTM_DTYPE_FP32 || !operands || !sink || iters < 1 || iters > (1 << 22)) {
+        set_error("mfma_rate: 16-bit type, operands, sink and 1 <= iters <= 2^22 required");
+        return LSTM_ERR_INVALID;
+    }
+    if (dtype == LSTM_DTYPE_FP16)
+        hipLaunchKernelGGL(mfma_rate_kernel<_Float16>, dim3(256), dim3(512), 0, stream, (const u32x4 *)operands, iters, sink);
+    else
+        hipLaunchKernelGGL(mfma_rate_kernel<bf16_t>, dim3(256), dim3(512), 0, stream, (const u32x4 *)operands, iters, sink);
+    LSTM_LAUNCH_CHECK();
+    if (flops) *flops = 256.0 * 8.0 * 8.0 * (double)iters * 2.0 * 32.0 * 32.0 * 16.0;
+    return LSTM_OK;
+}
+
 }  // namespace lstm

@@ -28,16 +28,29 @@ struct __attribute__((aligned(16))) A16x8 {
     uint16_t v[8];
 };
 
+// 1 / (participating workers * loss scale); every worker participates without a mask.  With no
+// participant at all the factor is 0, so the average comes out as zero.
+__device__ inline float average_factor(int N, const int *mask, float scale, int *n_present) {
+    int cnt = N;
+    if (mask) {
+        cnt = 0;
+        for (int w = 0; w < N; ++w) cnt += mask[w] != 0;
+    }
+    if (n_present && blockIdx.x == 0 && threadIdx.x == 0) *n_present = cnt;
+    return cnt > 0 ? 1.0f / ((float)cnt * scale) : 0.0f;
+}
+
 // 16-bit inputs: one thread owns 8 consecutive parameters and walks the workers.
 template <typename T, typename Vec>
 __global__ __launch_bounds__(256) void grad_average_lp_kernel(const uint16_t *g, int64_t P, int N, const float *loss_scale,
-                                                              float *avg, int *found_inf) {
-    const float inv = 1.0f / ((float)N * (*loss_scale));
+                                                              const int *mask, int *n_present, float *avg, int *found_inf) {
+    const float inv = average_factor(N, mask, *loss_scale, n_present);
     const int64_t nvec = P / 8;
     bool bad = false;
     for (int64_t v = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; v < nvec; v += (int64_t)gridDim.x * blockDim.x) {
         float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         for (int w = 0; w < N; ++w) {
+            if (mask && !mask[w]) continue;
             const Vec x = *reinterpret_cast<const Vec *>(g + (int64_t)w * P + v * 8);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
@@ -56,6 +69,7 @@ __global__ __launch_bounds__(256) void grad_average_lp_kernel(const uint16_t *g,
         if (e < P) {
             float s = 0.0f;
             for (int w = 0; w < N; ++w) {
+                if (mask && !mask[w]) continue;
                 const uint16_t x = g[(int64_t)w * P + e];
                 bad |= Bits<T>::nonfinite(x);
                 s += Bits<T>::to_f(x);
@@ -67,12 +81,13 @@ __global__ __launch_bounds__(256) void grad_average_lp_kernel(const uint16_t *g,
 }
 
 __global__ __launch_bounds__(256) void grad_average_f32_kernel(const float *g, int64_t P, int N, const float *loss_scale,
-                                                               float *avg, int *found_inf) {
-    const float inv = 1.0f / ((float)N * (*loss_scale));
+                                                               const int *mask, int *n_present, float *avg, int *found_inf) {
+    const float inv = average_factor(N, mask, *loss_scale, n_present);
     bool bad = false;
     for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < P; e += (int64_t)gridDim.x * blockDim.x) {
         float s = 0.0f;
         for (int w = 0; w < N; ++w) {
+            if (mask && !mask[w]) continue;
             const float x = g[(int64_t)w * P + e];
             bad |= (__float_as_uint(x) & 0x7f800000u) == 0x7f800000u;
             s += x;
@@ -186,18 +201,20 @@ int grid_for(int64_t work_items) {
 
 using namespace lstm;
 
-extern "C" int grad_average(int64_t n_params, int32_t n_workers, const void *grads_lp, int32_t dtype,
-                            const float *loss_scale, float *avg_grad, int32_t *found_inf, void *stream) {
+namespace {
+int grad_average_impl(const char *who, int64_t n_params, int32_t n_workers, const void *grads_lp, int32_t dtype,
+                      const float *loss_scale, const int32_t *mask, float *avg_grad, int32_t *found_inf,
+                      int32_t *n_present, void *stream) {
     if (n_params < 0 || n_workers < 1 || !loss_scale || !found_inf || (n_params > 0 && (!grads_lp || !avg_grad))) {
-        set_error("grad_average: invalid argument (n_params=%lld n_workers=%d)", (long long)n_params, n_workers);
+        set_error("%s: invalid argument (n_params=%lld n_workers=%d)", who, (long long)n_params, n_workers);
         return LSTM_ERR_INVALID;
     }
     if (dtype < LSTM_DTYPE_FP32 || dtype > LSTM_DTYPE_BF16) {
-        set_error("grad_average: bad dtype %d", dtype);
+        set_error("%s: bad dtype %d", who, dtype);
         return LSTM_ERR_INVALID;
     }
     if (((uintptr_t)grads_lp | (uintptr_t)avg_grad) % 16 != 0) {
-        set_error("grad_average: buffers must be 16-byte aligned");
+        set_error("%s: buffers must be 16-byte aligned", who);
         return LSTM_ERR_INVALID;
     }
     hipStream_t s = (hipStream_t)stream;
@@ -208,25 +225,43 @@ extern "C" int grad_average(int64_t n_params, int32_t n_workers, const void *gra
     if (n_params == 0) return LSTM_OK;
     if (dtype == LSTM_DTYPE_FP32) {
         hipLaunchKernelGGL(grad_average_f32_kernel, dim3(grid_for(n_params)), dim3(256), 0, s, (const float *)grads_lp,
-                           n_params, n_workers, loss_scale, avg_grad, found_inf);
+                           n_params, n_workers, loss_scale, mask, n_present, avg_grad, found_inf);
     } else {
         const uint16_t *g = (const uint16_t *)grads_lp;
         const bool aligned = (n_params % 8 == 0) || n_workers == 1;
         const int grid = grid_for(n_params / 8 + 1);
+#define GA_LAUNCH(T, V)                                                                                                  \
+    hipLaunchKernelGGL((grad_average_lp_kernel<T, V>), dim3(grid), dim3(256), 0, s, g, n_params, n_workers, loss_scale, \
+                       mask, n_present, avg_grad, found_inf)
         if (dtype == LSTM_DTYPE_FP16) {
-            if (aligned)
-                hipLaunchKernelGGL((grad_average_lp_kernel<_Float16, A16x8>), dim3(grid), dim3(256), 0, s, g, n_params, n_workers, loss_scale, avg_grad, found_inf);
-            else
-                hipLaunchKernelGGL((grad_average_lp_kernel<_Float16, U16x8>), dim3(grid), dim3(256), 0, s, g, n_params, n_workers, loss_scale, avg_grad, found_inf);
+            if (aligned) GA_LAUNCH(_Float16, A16x8);
+            else GA_LAUNCH(_Float16, U16x8);
         } else {
-            if (aligned)
-                hipLaunchKernelGGL((grad_average_lp_kernel<bf16_t, A16x8>), dim3(grid), dim3(256), 0, s, g, n_params, n_workers, loss_scale, avg_grad, found_inf);
-            else
-                hipLaunchKernelGGL((grad_average_lp_kernel<bf16_t, U16x8>), dim3(grid), dim3(256), 0, s, g, n_params, n_workers, loss_scale, avg_grad, found_inf);
+            if (aligned) GA_LAUNCH(bf16_t, A16x8);
+            else GA_LAUNCH(bf16_t, U16x8);
         }
+#undef GA_LAUNCH
     }
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
+}
+}  // namespace
+
+extern "C" int grad_average(int64_t n_params, int32_t n_workers, const void *grads_lp, int32_t dtype,
+                            const float *loss_scale, float *avg_grad, int32_t *found_inf, void *stream) {
+    return grad_average_impl("grad_average", n_params, n_workers, grads_lp, dtype, loss_scale, nullptr, avg_grad, found_inf,
+                             nullptr, stream);
+}
+
+extern "C" int grad_average_masked(int64_t n_params, int32_t n_workers, const void *grads_lp, int32_t dtype,
+                                   const float *loss_scale, const int32_t *participating, float *avg_grad,
+                                   int32_t *found_inf, int32_t *n_participating, void *stream) {
+    if (!participating) {
+        set_error("grad_average_masked: participating is NULL (use grad_average when every worker reports)");
+        return LSTM_ERR_INVALID;
+    }
+    return grad_average_impl("grad_average_masked", n_params, n_workers, grads_lp, dtype, loss_scale, participating, avg_grad,
+                             found_inf, n_participating, stream);
 }
 
 extern "C" int master_update(int64_t n_params, const optimizer_config *opt, float lr, int64_t step, float *master,

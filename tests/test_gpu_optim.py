@@ -142,3 +142,53 @@ def test_adam_update_matches_oracle(hip, P, dtype):
     np.testing.assert_allclose(m.double().cpu().numpy(), mr, rtol=1e-5, atol=2e-9)   # |g| ~ 1e-2: a few fp32 ulps of the addends
     np.testing.assert_allclose(v.double().cpu().numpy(), vr, rtol=1e-5, atol=1e-12)
     np.testing.assert_array_equal(out.double().cpu().numpy(), orc.round_storage(W.double().cpu().numpy(), dtype))
+
+
+@pytest.mark.parametrize("P,N,dtype,present", [(7, 3, "fp16", [1, 0, 1]), (4099, 5, "bf16", [0, 1, 1, 1, 0]), (4096, 4, "fp32", [1, 1, 1, 1]),
+                                               (533001, 64, "fp16", None), (64, 4, "fp16", [0, 0, 0, 0]), (1, 2, "fp16", [0, 1])])
+def test_grad_average_masked_matches_oracle(hip, P, N, dtype, present):
+    """Fault-tolerant average: only the workers that reported count; what the absent rows
+    hold (Inf and NaN included) is never read."""
+    import torch
+    print(f"[case] grad_average_masked P={P} N={N} {dtype}", flush=True)
+    gen = torch.Generator(device="cuda").manual_seed(P % 1000 + 7 * N)
+    S = 512.0
+    if present is None:                                    # 60 of 64 workers: a 94 % quorum
+        rng = np.random.default_rng(5)
+        present = np.ones(N, dtype=np.int32)
+        present[rng.choice(N, 4, replace=False)] = 0
+    present = np.asarray(present, dtype=np.int32)
+    g = (torch.randn((N, P), device="cuda", generator=gen) * 3.0).to(_tdtype(torch, dtype))
+    for w in range(N):                                     # poison the absent rows
+        if not present[w]:
+            g[w] = float("nan") if w % 2 else float("inf")
+    mask = torch.tensor(present, dtype=torch.int32, device="cuda") * 5     # any non-zero value means present
+    scale = torch.tensor([S], device="cuda"); avg = torch.full((P,), -7.0, device="cuda")
+    flag = torch.full((1,), 7, dtype=torch.int32, device="cuda"); cnt = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    hip.grad_average_masked(P, N, g, CODE[dtype], scale, mask, avg, flag, cnt)
+    torch.cuda.synchronize()
+    want, inf, n = orc.grad_average_partial(g.double().cpu().numpy(), S, present)
+    assert int(cnt.item()) == n == int(present.sum())
+    assert int(flag.item()) == 0 and not inf
+    np.testing.assert_allclose(avg.double().cpu().numpy(), want, rtol=2e-6, atol=1e-9)
+    if n:
+        w = int(np.flatnonzero(present)[-1])
+        g[w, P - 1] = float("inf")                          # an overflow in a present worker is reported
+        hip.grad_average_masked(P, N, g, CODE[dtype], scale, mask, avg, flag, None)
+        torch.cuda.synchronize()
+        assert int(flag.item()) == 1
+        assert orc.grad_average_partial(g.double().cpu().numpy(), S, present)[1]
+
+
+def test_grad_average_masked_all_present_equals_lockstep(hip):
+    import torch
+    P, N = 20011, 6
+    g = (torch.randn((N, P), device="cuda") * 2.0).half()
+    scale = torch.tensor([64.0], device="cuda")
+    a0 = torch.empty(P, device="cuda"); a1 = torch.empty(P, device="cuda"); flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    hip.grad_average(P, N, g, 1, scale, a0, flag)
+    hip.grad_average_masked(P, N, g, 1, scale, torch.ones(N, dtype=torch.int32, device="cuda"), a1, flag)
+    torch.cuda.synchronize()
+    assert torch.equal(a0, a1)
+    with pytest.raises(hip.LstmError):
+        hip.grad_average_masked(P, N, g, 1, scale, None, a1, flag)
