@@ -83,6 +83,26 @@ def test_workspace_plan(hip):
     assert r1 % 256 == 0 and s1 % 256 == 0 and r1 < r and s1 < s
 
 
+def test_capacity_trends_of_table1(hip):
+    """Table 1: at 200 units and 128 steps, halving the element size or quartering the batch
+    lets a deeper stack fit the device memory.  The workspace plan must show the same trends
+    (bytes per added layer: fp16 well below fp32, batch 64 well below batch 256)."""
+    def per_layer(dtype, batch):
+        def total(L):
+            w = wl.Workload("cap", L, 9, 200, 128, batch, dtype, wl.HEAD_STEP_BCE)
+            cfg = _cfg(hip, w)
+            r, s = hip.lstm_workspace_bytes(cfg)
+            es = 4 if dtype == "fp32" else 2
+            return r + s + hip.lstm_param_count(cfg) * (2 * es + 12)     # + weights, gradient, master, momentum, average
+        return (total(40) - total(20)) / 20.0
+    f32, f16 = per_layer("fp32", 256), per_layer("fp16", 256)
+    f32s, f16s = per_layer("fp32", 64), per_layer("fp16", 64)
+    assert 1.5 < f32 / f16 <= 2.0 and 1.5 < f32s / f16s <= 2.0
+    assert 3.0 < f32 / f32s <= 4.0 and 3.0 < f16 / f16s <= 4.0
+    # the paper's P100 held 58 fp16 layers at batch 256 in 16 GB; this plan needs less per layer
+    assert 16e9 / f16 > 58
+
+
 def test_invalid_arguments_are_rejected_on_the_host(hip):
     w = wl.CONFIGS["tiny"]
     for field, val, status in (("batch", 0, -1), ("seq_len", 0, -1), ("hidden", 0, -1), ("num_layers", 0, -1),

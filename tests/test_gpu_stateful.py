@@ -1,0 +1,86 @@
+"""Stateful truncated BPTT over a long shot and deep stacks (the paper trains on
+shots of thousands of steps cut into chunks of 128 with the recurrent state
+carried over, and grows capacity by stacking layers: Section "Neural Network
+architecture", Table 1)."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import lstm_oracle as orc
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hip():
+    import paper_1912_00286_amd as pkg
+    pkg.load_library()
+    return pkg
+
+
+def test_long_shot_in_chunks_with_updates(hip):
+    """Three chunks of one shot: chunk k starts from the state chunk k-1 ended in, gets
+    its own forward + BPTT + SGD-momentum update (gradients do not cross the cut).  The
+    oracle does the same with its own carried state; losses, every chunk's gradient and
+    the weights after the last update are compared."""
+    import torch
+    chunk, n_chunks = 16, 3
+    w = wl.Workload("shot", 2, 12, 48, chunk * n_chunks, 16, "fp16", wl.HEAD_STEP_BCE, loss_scale=256.0,
+                    momentum=0.9, lr0=0.05, data_seed=21, weight_seed=22)
+    master0, xs, ys = pu.inputs_for(w)
+    wc = w.with_(seq_len=chunk)
+    dev = torch.device("cuda:0")
+    ts = pu.make_step(wc, master0, dev)
+    L, B, H = w.num_layers, w.batch, w.hidden
+    x = torch.from_numpy(xs[0]).to(ts.lp_dtype).to(dev)
+    y = torch.from_numpy(ys[0]).to(dev)
+    h_in = torch.zeros(L, B, H, dtype=ts.lp_dtype, device=dev); c_in = torch.zeros(L, B, H, device=dev)
+    h_out = torch.zeros_like(h_in); c_out = torch.zeros_like(c_in)
+
+    shapes = pu.oracle_shapes(wc)
+    W_ref = master0.astype(np.float64)
+    V_ref = np.zeros_like(W_ref)
+    h_ref = np.zeros((L, B, H)); c_ref = np.zeros((L, B, H))
+    lr = w.lr0
+    for k in range(n_chunks):
+        print(f"[case] shot chunk {k}", flush=True)
+        xk = x[k * chunk:(k + 1) * chunk].contiguous(); yk = y[k * chunk:(k + 1) * chunk].contiguous()
+        hip.lstm_forward(ts.cfg, ts.params_lp, xk, yk, h_in, c_in, ts.reserve, ts.scratch, ts.losses[0:1], h_out, c_out)
+        hip.lstm_backward(ts.cfg, ts.params_lp, xk, yk, ts.reserve, ts.scratch, ts.loss_scale, ts.grads[0])
+        ts.update(lr)
+        torch.cuda.synchronize()
+        assert int(ts.found_inf.item()) == 0
+        # oracle: same chunk, its own carried state, weights rounded to storage like the working copy
+        params = orc.unflatten(orc.round_storage(W_ref, "fp16"), shapes)
+        xo = xs[0][k * chunk:(k + 1) * chunk].astype(np.float64); yo = ys[0][k * chunk:(k + 1) * chunk]
+        loss, cache = orc.forward(params, L, xo, yo, w.head, h_ref, c_ref)
+        g = orc.flatten(orc.backward(params, L, cache, 1.0), shapes)
+        assert abs(float(ts.losses[0].item()) - loss) <= pu.LOSS_RTOL * abs(loss)
+        got = ts.grads[0].double().cpu().numpy() / w.loss_scale
+        pu.assert_grads_close(got, g, shapes, pu.GRAD_RTOL["fp16"], f"chunk {k}")
+        W_ref, V_ref = orc.sgd_momentum_update(W_ref, V_ref, g, lr, w.momentum)
+        h_ref = np.stack([cache["layers"][l]["h"][-1] for l in range(L)])
+        c_ref = np.stack([cache["layers"][l]["c"][-1] for l in range(L)])
+        np.testing.assert_allclose(h_out.double().cpu().numpy(), h_ref, atol=6e-3)
+        np.testing.assert_allclose(c_out.double().cpu().numpy(), c_ref, atol=6e-3)
+        h_in, h_out = h_out, h_in
+        c_in, c_out = c_out, c_in
+    dW = np.abs(W_ref - master0).max()
+    np.testing.assert_allclose(ts.master.double().cpu().numpy(), W_ref, atol=pu.GRAD_RTOL["fp16"] * dW + 2e-7)
+
+
+@pytest.mark.parametrize("dtype,L", [("fp16", 4), ("bf16", 12), ("fp32", 6)])
+def test_deep_stack(hip, dtype, L):
+    """Capacity grows by stacking layers of 200 units (Table 1): a deep stack at the
+    paper's width, short sequence so that the fp64 oracle stays within seconds.
+    With freshly initialised weights the gradient shrinks by about a factor of ten per
+    layer; at twelve layers the bottom gradients (1e-12) and the top ones (0.4) no longer
+    fit the half-precision range under any single loss scale, so the fp16 case stops at
+    four layers with the scale at 2^15, and the twelve-layer case runs in bf16."""
+    w = wl.Workload(f"deep_{dtype}", L, 9, 200, 12, 64, dtype, wl.HEAD_STEP_BCE,
+                    loss_scale=1.0 if dtype != "fp16" else 32768.0, data_seed=31, weight_seed=32)
+    print(f"[case] deep stack {dtype} L={L}", flush=True)
+    got = pu.run_gpu_step(w)
+    want = pu.run_oracle_step(w)
+    pu.assert_step_close(w, got, want)
