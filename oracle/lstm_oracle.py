@@ -42,6 +42,7 @@ import numpy as np
 HEAD_STEP_BCE = 1
 HEAD_LAST_BCE = 2
 HEAD_STEP_MSE = 3
+HEAD_FC_HINGE = 4           # the paper's own head: see forward()
 
 FP16_MAX = 65504.0          # Section "Half-precision training modes"
 
@@ -49,10 +50,12 @@ FP16_MAX = 65504.0          # Section "Half-precision training modes"
 # --------------------------------------------------------------------------
 # parameter bookkeeping
 # --------------------------------------------------------------------------
-def param_shapes(num_layers, input_dim, hidden, vocab=0, embed_dim=0):
+def param_shapes(num_layers, input_dim, hidden, vocab=0, embed_dim=0, fc_units=0):
     """Ordered (name, shape) list of the flat parameter vector:
     [E[V,D]] then per layer W[4H,I_l], U[4H,H], b[4H], then w_head[H], b_head[1].
-    Rows of W, U, b are grouped by gate in the order i, f, g, o."""
+    Rows of W, U, b are grouped by gate in the order i, f, g, o.
+    With fc_units = F > 0 (the head of Fig. 2) the tail is W_fc[F,H], b_fc[F],
+    w_head[F], b_head[1]."""
     shapes = []
     first = input_dim
     if vocab > 0:
@@ -63,13 +66,18 @@ def param_shapes(num_layers, input_dim, hidden, vocab=0, embed_dim=0):
         shapes.append((f"W{l}", (G, first if l == 0 else hidden)))
         shapes.append((f"U{l}", (G, hidden)))
         shapes.append((f"b{l}", (G,)))
-    shapes.append(("w_head", (hidden,)))
+    if fc_units > 0:
+        shapes.append(("W_fc", (fc_units, hidden)))
+        shapes.append(("b_fc", (fc_units,)))
+        shapes.append(("w_head", (fc_units,)))
+    else:
+        shapes.append(("w_head", (hidden,)))
     shapes.append(("b_head", (1,)))
     return shapes
 
 
-def param_count(num_layers, input_dim, hidden, vocab=0, embed_dim=0):
-    return sum(int(np.prod(s)) for _, s in param_shapes(num_layers, input_dim, hidden, vocab, embed_dim))
+def param_count(num_layers, input_dim, hidden, vocab=0, embed_dim=0, fc_units=0):
+    return sum(int(np.prod(s)) for _, s in param_shapes(num_layers, input_dim, hidden, vocab, embed_dim, fc_units))
 
 
 def unflatten(flat, shapes):
@@ -141,7 +149,19 @@ def forward(params, num_layers, x, targets, head, h0=None, c0=None):
     top = inp                                      # [T,B,H]
     w_head, b_head = params["w_head"], params["b_head"]
     y = np.asarray(targets, dtype=np.float64)
-    if head == HEAD_LAST_BCE:
+    fc_pre = fc_act = None
+    if head == HEAD_FC_HINGE:
+        # Fig. 2: a fully connected ReLU layer applied to every temporal slice, then one
+        # output per slice; hinge loss max(0, 1 - t*y) with labels t = +-1 (Eq. 6 without
+        # its multiplier, which backward() applies).  Subgradient 0 at the kink.
+        fc_pre = top @ params["W_fc"].T + params["b_fc"]      # [T,B,F]
+        fc_act = np.maximum(fc_pre, 0.0)
+        z = fc_act @ w_head + b_head[0]                        # [T,B]
+        yy = y.reshape(T, B)
+        margin = 1.0 - yy * z
+        ell = np.maximum(margin, 0.0)
+        dldz = np.where(margin > 0.0, -yy, 0.0)
+    elif head == HEAD_LAST_BCE:
         z = top[T - 1] @ w_head + b_head[0]        # [B]
         yy = y.reshape(B)
     else:
@@ -155,10 +175,10 @@ def forward(params, num_layers, x, targets, head, h0=None, c0=None):
     elif head == HEAD_STEP_MSE:
         ell = (z - yy) ** 2
         dldz = 2.0 * (z - yy)
-    else:
+    elif head != HEAD_FC_HINGE:
         raise ValueError(f"unknown head {head}")
     loss = float(ell.sum() / M)
-    cache = dict(layers=layers, ids=ids, z=z, dldz=dldz / M, head=head, T=T, B=B)
+    cache = dict(layers=layers, ids=ids, z=z, dldz=dldz / M, head=head, T=T, B=B, fc_pre=fc_pre, fc_act=fc_act)
     return loss, cache
 
 
@@ -175,11 +195,20 @@ def backward(params, num_layers, cache, loss_scale=1.0):
     S = float(loss_scale)
     grads = {k: np.zeros_like(v) for k, v in params.items()}
     w_head = params["w_head"]
-    H = w_head.shape[0]
     top = cache["layers"][-1]["h"][1:]             # [T,B,H]
+    H = top.shape[2]
     dz = S * cache["dldz"]                         # seed: d(S*loss)/dz
     d_above = np.zeros((T, B, H))
-    if cache["head"] == HEAD_LAST_BCE:
+    if cache["head"] == HEAD_FC_HINGE:
+        a = cache["fc_act"]                                     # [T,B,F]
+        grads["w_head"] = np.einsum("tb,tbf->f", dz, a)
+        grads["b_head"] = np.array([dz.sum()])
+        d_pre = dz[:, :, None] * w_head[None, None, :] * (cache["fc_pre"] > 0.0)   # through the ReLU
+        grads["W_fc"] = np.einsum("tbf,tbh->fh", d_pre, top)
+        grads["b_fc"] = d_pre.sum(axis=(0, 1))
+        H = top.shape[2]
+        d_above = d_pre @ params["W_fc"]                         # [T,B,H]
+    elif cache["head"] == HEAD_LAST_BCE:
         grads["w_head"] = dz @ top[T - 1]
         grads["b_head"] = np.array([dz.sum()])
         d_above[T - 1] = np.outer(dz, w_head)

@@ -457,3 +457,111 @@ def test_partial_average_by_hand_and_invariants():
     perm = rng.permutation(N)
     avg_p, _, _ = orc.grad_average_partial(g[perm], S, mask[perm])
     np.testing.assert_allclose(avg_p, avg, rtol=1e-13, atol=1e-18)
+
+
+# ---------------------------------------------------------------- the paper's own head (Fig. 2, Eq. 6)
+def _fc_params(rng, L, I, H, F, scale=0.5):
+    shapes = orc.param_shapes(L, I, H, 0, 0, F)
+    return {n: rng.uniform(-scale, scale, s) for n, s in shapes}, shapes
+
+
+def _pm_targets(rng, T, B):
+    return np.where(rng.random((T, B, 1)) < 0.4, 1.0, -1.0)
+
+
+def test_fc_hinge_head_matches_central_differences():
+    """ReLU layer per temporal slice + one output + hinge loss (Fig. 2, Eq. 6).  The loss is
+    piecewise linear in the head's output; the seed avoids samples within the difference
+    step of a kink, which the test checks before differencing."""
+    rng = np.random.default_rng(404)
+    L, T, B, I, H, F = 2, 4, 3, 5, 4, 6
+    p, shapes = _fc_params(rng, L, I, H, F)
+    x = rng.standard_normal((T, B, I)); y = _pm_targets(rng, T, B)
+    S = 10.0                                                 # the paper's static multiplier
+    loss, cache = orc.forward(p, L, x, y, orc.HEAD_FC_HINGE)
+    assert np.abs(cache["fc_pre"]).min() > 1e-4 and np.abs(1.0 - y[..., 0] * cache["z"]).min() > 1e-4
+    assert (cache["fc_pre"] > 0).any() and (cache["fc_pre"] < 0).any()
+    assert ((1.0 - y[..., 0] * cache["z"]) > 0).any()
+    g = orc.backward(p, L, cache, S)
+    eps = 1e-6
+    for name, _ in shapes:
+        flat = p[name].reshape(-1)
+        for k in rng.choice(flat.size, size=min(flat.size, 10), replace=False):
+            old = flat[k]
+            flat[k] = old + eps; lp, _ = orc.forward(p, L, x, y, orc.HEAD_FC_HINGE)
+            flat[k] = old - eps; lm, _ = orc.forward(p, L, x, y, orc.HEAD_FC_HINGE)
+            flat[k] = old
+            fd = S * (lp - lm) / (2 * eps)
+            an = g[name].reshape(-1)[k]
+            assert abs(fd - an) <= 1e-6 * max(1.0, abs(fd)) + 2e-8, (name, k, fd, an)
+
+
+def test_fc_hinge_head_matches_torch_autograd():
+    rng = np.random.default_rng(405)
+    L, T, B, I, H, F = 1, 6, 4, 3, 5, 7
+    p, shapes = _fc_params(rng, L, I, H, F, scale=0.6)
+    x = rng.standard_normal((T, B, I)); y = _pm_targets(rng, T, B)
+    loss, cache = orc.forward(p, L, x, y, orc.HEAD_FC_HINGE)
+    g = orc.backward(p, L, cache, 1.0)
+    lstm = torch.nn.LSTM(I, H, num_layers=1, bias=True).double()
+    fc = torch.nn.Linear(H, F).double(); out = torch.nn.Linear(F, 1).double()
+    with torch.no_grad():
+        lstm.weight_ih_l0.copy_(torch.from_numpy(p["W0"])); lstm.weight_hh_l0.copy_(torch.from_numpy(p["U0"]))
+        lstm.bias_ih_l0.copy_(torch.from_numpy(p["b0"])); lstm.bias_hh_l0.zero_()
+        fc.weight.copy_(torch.from_numpy(p["W_fc"])); fc.bias.copy_(torch.from_numpy(p["b_fc"]))
+        out.weight.copy_(torch.from_numpy(p["w_head"][None, :])); out.bias.copy_(torch.from_numpy(p["b_head"]))
+    hseq, _ = lstm(torch.from_numpy(x))
+    z = out(torch.relu(fc(hseq)))[..., 0]
+    tl = torch.clamp(1.0 - torch.from_numpy(y[..., 0]) * z, min=0.0).mean()
+    tl.backward()
+    assert abs(loss - tl.item()) < 1e-13
+    np.testing.assert_allclose(g["W_fc"], fc.weight.grad.numpy(), atol=1e-14)
+    np.testing.assert_allclose(g["b_fc"], fc.bias.grad.numpy(), atol=1e-14)
+    np.testing.assert_allclose(g["w_head"], out.weight.grad.numpy()[0], atol=1e-14)
+    np.testing.assert_allclose(g["b_head"], out.bias.grad.numpy(), atol=1e-14)
+    np.testing.assert_allclose(g["W0"], lstm.weight_ih_l0.grad.numpy(), atol=1e-14)
+    np.testing.assert_allclose(g["U0"], lstm.weight_hh_l0.grad.numpy(), atol=1e-14)
+    np.testing.assert_allclose(g["b0"], lstm.bias_ih_l0.grad.numpy(), atol=1e-14)
+
+
+def test_fc_hinge_head_closed_forms():
+    rng = np.random.default_rng(406)
+    L, T, B, I, H, F = 1, 3, 2, 2, 3, 4
+    p, shapes = _fc_params(rng, L, I, H, F)
+    x = rng.standard_normal((T, B, I)); y = _pm_targets(rng, T, B)
+    # zero output weights: y = 0 everywhere, loss = max(0, 1 - 0) = 1, and d loss / d b_head = -mean(t)
+    p0 = {k: v.copy() for k, v in p.items()}
+    p0["w_head"][:] = 0.0; p0["b_head"][:] = 0.0
+    loss, cache = orc.forward(p0, L, x, y, orc.HEAD_FC_HINGE)
+    assert loss == 1.0
+    g = orc.backward(p0, L, cache, 1.0)
+    np.testing.assert_allclose(g["b_head"][0], -y.mean(), rtol=1e-15)
+    assert not g["W_fc"].any() and not g["W0"].any()      # nothing flows below a zero output weight
+    # large correct margin: every sample satisfied, loss and every gradient exactly zero
+    p1 = {k: v.copy() for k, v in p.items()}
+    p1["w_head"][:] = 0.0
+    yc = np.ones((T, B, 1)); p1["b_head"][:] = 5.0
+    loss, cache = orc.forward(p1, L, x, yc, orc.HEAD_FC_HINGE)
+    assert loss == 0.0
+    assert all(not v.any() for v in orc.backward(p1, L, cache, 10.0).values())
+    # one unit, one sample, by hand: h = o*tanh(c); a = relu(w h + b); y = v a + c0
+    pp = {"W0": np.array([[0.5], [0.0], [1.0], [2.0]]), "U0": np.zeros((4, 1)), "b0": np.zeros(4),
+          "W_fc": np.array([[2.0], [-1.0]]), "b_fc": np.array([0.1, 0.0]), "w_head": np.array([3.0, 7.0]), "b_head": np.array([-0.2])}
+    xx = np.array([[[1.0]]]); tt = np.array([[[-1.0]]])  # wrong side: margin 1 + y > 0
+    i = 1 / (1 + math.exp(-0.5)); gg = math.tanh(1.0); o = 1 / (1 + math.exp(-2.0))
+    h = o * math.tanh(i * gg)
+    a1 = 2.0 * h + 0.1                                    # positive; the second unit (-h) is cut by the ReLU
+    yv = 3.0 * a1 - 0.2
+    loss, cache = orc.forward(pp, 1, xx, tt, orc.HEAD_FC_HINGE)
+    assert abs(loss - (1.0 + yv)) < 1e-15 and yv > 0
+    g = orc.backward(pp, 1, cache, 10.0)
+    np.testing.assert_allclose(g["w_head"], [10.0 * a1, 0.0], rtol=1e-14)
+    np.testing.assert_allclose(g["b_head"], [10.0], rtol=1e-14)
+    np.testing.assert_allclose(g["b_fc"], [30.0, 0.0], rtol=1e-14)
+    np.testing.assert_allclose(g["W_fc"][:, 0], [30.0 * h, 0.0], rtol=1e-14)
+
+
+def test_fc_head_parameter_count():
+    # Fig. 2: 2 x LSTM(200) on 9 features, FC(200) + ReLU, 1 output
+    n = orc.param_count(2, 9, 200, 0, 0, 200)
+    assert n == 4 * 200 * (9 + 200) + 800 + 4 * 200 * 400 + 800 + 200 * 200 + 200 + 200 + 1
