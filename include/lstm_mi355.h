@@ -38,7 +38,7 @@
 extern "C" {
 #endif
 
-#define LSTM_ABI_VERSION 1
+#define LSTM_ABI_VERSION 2
 
 enum {
     LSTM_OK = 0,
@@ -53,13 +53,18 @@ enum { LSTM_DTYPE_FP32 = 0, LSTM_DTYPE_FP16 = 1, LSTM_DTYPE_BF16 = 2 };
 enum {
     LSTM_HEAD_STEP_BCE = 1,  /* z[t,b] = w.h_top[t,b] + b0, sigmoid + binary cross-entropy, every step */
     LSTM_HEAD_LAST_BCE = 2,  /* same, last time step only (targets [B,1])                            */
-    LSTM_HEAD_STEP_MSE = 3   /* z[t,b] linear, squared error, every step                             */
+    LSTM_HEAD_STEP_MSE = 3,  /* z[t,b] linear, squared error, every step                             */
+    LSTM_HEAD_FC_HINGE = 4   /* the head of Fig. 2: a[t,b] = relu(W_fc h_top[t,b] + b_fc) (head_hidden units),
+                                z[t,b] = w.a[t,b] + b0, hinge loss max(0, 1 - y z) with targets y = +-1 (Eq. 6
+                                without its multiplier, which is lstm_backward's loss scale), every step;
+                                derivative 0 at the kink */
 };
 
 enum { LSTM_OPT_SGD_MOMENTUM = 0, LSTM_OPT_ADAM = 1 };
 
 /* tensor kinds for lstm_param_offset */
-enum { LSTM_P_EMBED = 0, LSTM_P_W = 1, LSTM_P_U = 2, LSTM_P_B = 3, LSTM_P_HEAD_W = 4, LSTM_P_HEAD_B = 5 };
+enum { LSTM_P_EMBED = 0, LSTM_P_W = 1, LSTM_P_U = 2, LSTM_P_B = 3, LSTM_P_HEAD_W = 4, LSTM_P_HEAD_B = 5,
+       LSTM_P_FC_W = 6, LSTM_P_FC_B = 7 };
 
 /* Model shape.  Fig. 2 of the paper: stacked LSTM layers of `hidden` units over
  * (batch, sequence length, feature) inputs with one output per time slice. */
@@ -74,6 +79,7 @@ typedef struct {
     int32_t out_dim;     /* must be 1                                           */
     int32_t vocab;       /* > 0: x holds int32 token ids, looked up in E[V,D]   */
     int32_t embed_dim;   /* D (input dim of layer 0 when vocab > 0)             */
+    int32_t head_hidden; /* F >= 1 with LSTM_HEAD_FC_HINGE, ignored otherwise   */
 } lstm_config;
 
 /* Optimiser and loss-scale policy for master_update. */
@@ -97,6 +103,7 @@ const char *lstm_last_error(void);
 /* Number of elements of the flat parameter vector.  Layout (all row-major):
  *   [E[V,D]]  then for l = 0..L-1: W_l[4H,I_l], U_l[4H,H], b_l[4H]  then
  *   w_head[H], b_head[1];  I_0 = input_dim (or D), I_l = H above.
+ *   With LSTM_HEAD_FC_HINGE the tail is W_fc[F,H], b_fc[F], w_head[F], b_head[1].
  * The 4H rows are grouped by gate in the order input, forget, cell candidate,
  * output.  Gradient buffers use the same layout.  n_params: host, out. */
 int lstm_param_count(const lstm_config *cfg, int64_t *n_params);

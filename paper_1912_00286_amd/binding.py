@@ -14,9 +14,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "liblstm_mi355.so"
 
 DTYPE_FP32, DTYPE_FP16, DTYPE_BF16 = 0, 1, 2
-HEAD_STEP_BCE, HEAD_LAST_BCE, HEAD_STEP_MSE = 1, 2, 3
+HEAD_STEP_BCE, HEAD_LAST_BCE, HEAD_STEP_MSE, HEAD_FC_HINGE = 1, 2, 3, 4
 OPT_SGD_MOMENTUM, OPT_ADAM = 0, 1
-P_EMBED, P_W, P_U, P_B, P_HEAD_W, P_HEAD_B = 0, 1, 2, 3, 4, 5
+P_EMBED, P_W, P_U, P_B, P_HEAD_W, P_HEAD_B, P_FC_W, P_FC_B = 0, 1, 2, 3, 4, 5, 6, 7
 
 
 class LstmError(RuntimeError):
@@ -27,7 +27,7 @@ class LstmError(RuntimeError):
 
 class LstmConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("num_layers", "input_dim", "hidden", "seq_len", "batch", "dtype", "head",
-                                         "out_dim", "vocab", "embed_dim")]
+                                         "out_dim", "vocab", "embed_dim", "head_hidden")]
 
 
 class OptimizerConfig(C.Structure):

@@ -29,7 +29,11 @@ struct Plan {
     int L, H, T, B, G, dtype, head, V, D;
     size_t es;                           // bytes per lp element
     std::vector<int> in_dim;             // I_l
-    int64_t off_E = -1, off_wh = 0, off_bh = 0, P = 0;
+    int F = 0;                           // units of the fully connected head layer (0: none)
+    int64_t off_E = -1, off_wh = 0, off_bh = 0, off_Wfc = -1, off_bfc = -1, P = 0;
+    size_t r_fc = 0;                     // reserve: relu(W_fc h + b_fc), lp [T*B, F]
+    size_t s_fcd = 0, s_fcdT = 0, s_fcwT = 0;   // scratch: its gradient, the gradient transposed, W_fc^T
+    int split_fc = 1;
     std::vector<int64_t> off_W, off_U, off_b;
     int head_rows = 0;                   // rows the head acts on (T*B or B)
     // reserve
@@ -59,8 +63,12 @@ int make_plan(const lstm_config *c, Plan &p) {
         set_error("config: bad dtype %d", c->dtype);
         return LSTM_ERR_INVALID;
     }
-    if (c->head < LSTM_HEAD_STEP_BCE || c->head > LSTM_HEAD_STEP_MSE) {
+    if (c->head < LSTM_HEAD_STEP_BCE || c->head > LSTM_HEAD_FC_HINGE) {
         set_error("config: bad head %d", c->head);
+        return LSTM_ERR_INVALID;
+    }
+    if (c->head == LSTM_HEAD_FC_HINGE && (c->head_hidden < 1 || c->head_hidden > (1 << 20))) {
+        set_error("config: head_hidden must be in [1, 2^20] with the fully connected head (got %d)", c->head_hidden);
         return LSTM_ERR_INVALID;
     }
     if (c->out_dim != 1) {
@@ -78,6 +86,7 @@ int make_plan(const lstm_config *c, Plan &p) {
     }
     p.L = c->num_layers; p.H = c->hidden; p.T = c->seq_len; p.B = c->batch; p.G = 4 * c->hidden;
     p.dtype = c->dtype; p.head = c->head; p.V = c->vocab; p.D = c->vocab > 0 ? c->embed_dim : 0;
+    p.F = c->head == LSTM_HEAD_FC_HINGE ? c->head_hidden : 0;
     p.es = dtype_size(c->dtype);
     const int I0 = c->vocab > 0 ? c->embed_dim : c->input_dim;
     p.in_dim.assign(p.L, p.H);
@@ -91,7 +100,11 @@ int make_plan(const lstm_config *c, Plan &p) {
         p.off_U[l] = off; off += (int64_t)p.G * p.H;
         p.off_b[l] = off; off += p.G;
     }
-    p.off_wh = off; off += p.H;
+    if (p.F > 0) {
+        p.off_Wfc = off; off += (int64_t)p.F * p.H;
+        p.off_bfc = off; off += p.F;
+    }
+    p.off_wh = off; off += p.F > 0 ? p.F : p.H;
     p.off_bh = off; off += 1;
     p.P = off;
     p.head_rows = p.head == LSTM_HEAD_LAST_BCE ? p.B : p.T * p.B;
@@ -106,6 +119,7 @@ int make_plan(const lstm_config *c, Plan &p) {
     }
     p.r_xemb = r; if (p.V > 0) r += align_up(TB * p.D * p.es);
     p.r_dzu = r; r += align_up((size_t)p.head_rows * 4);
+    p.r_fc = r; if (p.F > 0) r += align_up(TB * p.F * p.es);
     // 64x64-blocked copies for the large-tile GEMMs: time slots must start on a block row
     p.blk = p.dtype != LSTM_DTYPE_FP32 && p.B % 64 == 0 && gemm_blocked_supported(p.dtype, (int)TB, p.G);
     p.r_hblk.assign(p.L, 0);
@@ -147,8 +161,18 @@ int make_plan(const lstm_config *c, Plan &p) {
         splitk = a > splitk ? a : splitk;
         splitk = b > splitk ? b : splitk;
     }
+    if (p.F > 0) {
+        p.split_fc = gemm_pick_splits(p.dtype, p.F, p.H, (int)TB);
+        const size_t a = p.split_fc > 1 ? (size_t)p.split_fc * p.F * p.H * 4 : 0;
+        splitk = a > splitk ? a : splitk;
+    }
     p.s_splitk = s; s += align_up(splitk);
-    const int colw = p.G > p.H ? p.G : p.H;
+    if (p.F > 0) {
+        p.s_fcd = s; s += align_up(TB * p.F * p.es);
+        p.s_fcdT = s; s += align_up(TB * p.F * p.es);
+        p.s_fcwT = s; s += align_up((size_t)p.F * p.H * p.es);
+    }
+    const int colw = (p.G > p.H ? p.G : p.H) > p.F ? (p.G > p.H ? p.G : p.H) : p.F;
     p.s_colpart = s; s += align_up((size_t)colsum_chunks((int)TB) * colw * 4);
     p.s_dE32 = s; if (p.V > 0) s += align_up((size_t)p.V * p.D * 4);
     if (p.dtype != LSTM_DTYPE_FP32) {
@@ -224,7 +248,16 @@ extern "C" int lstm_param_offset(const lstm_config *cfg, int32_t kind, int32_t l
         case LSTM_P_W: *offset = p.off_W[layer]; *count = (int64_t)p.G * p.in_dim[layer]; break;
         case LSTM_P_U: *offset = p.off_U[layer]; *count = (int64_t)p.G * p.H; break;
         case LSTM_P_B: *offset = p.off_b[layer]; *count = p.G; break;
-        case LSTM_P_HEAD_W: *offset = p.off_wh; *count = p.H; break;
+        case LSTM_P_HEAD_W: *offset = p.off_wh; *count = p.F > 0 ? p.F : p.H; break;
+        case LSTM_P_FC_W:
+        case LSTM_P_FC_B:
+            if (p.F == 0) {
+                set_error("config has no fully connected head layer");
+                return LSTM_ERR_INVALID;
+            }
+            *offset = kind == LSTM_P_FC_W ? p.off_Wfc : p.off_bfc;
+            *count = kind == LSTM_P_FC_W ? (int64_t)p.F * p.H : p.F;
+            break;
         case LSTM_P_HEAD_B: *offset = p.off_bh; *count = 1; break;
         default:
             set_error("unknown tensor kind %d", kind);
@@ -360,7 +393,21 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
     // head + loss on the top layer's outputs
     const char *top = at(reserve, p.r_h[p.L - 1]) + (size_t)BH * es;
     if (p.head == LSTM_HEAD_LAST_BCE) top += (size_t)(p.T - 1) * BH * es;
-    LSTM_TRY(head_forward(p.dtype, p.head, top, par + p.off_wh * es, par + p.off_bh * es, targets, p.head_rows, p.H,
+    int head_width = p.H;
+    if (p.F > 0) {
+        // Fig. 2: fully connected ReLU layer on every temporal slice, a = relu(h W_fc^T + b_fc)
+        char *act = at(reserve, p.r_fc);
+        GemmArgs g{};
+        g.A = top; g.B = par + p.off_Wfc * es; g.C = act; g.bias = par + p.off_bfc * es;
+        g.M = TB; g.N = p.F; g.K = p.H;
+        g.lda = p.H; g.ldb = p.H; g.ldc = p.F;
+        g.out_lp = 1; g.kclass = KC_GEMM_BATCHED;
+        LSTM_TRY(gemm_nt(p.dtype, g, s));
+        LSTM_TRY(relu_inplace(p.dtype, act, (int64_t)TB * p.F, s));
+        top = act;
+        head_width = p.F;
+    }
+    LSTM_TRY(head_forward(p.dtype, p.head, top, par + p.off_wh * es, par + p.off_bh * es, targets, p.head_rows, head_width,
                           p.head_rows, (float *)at(reserve, p.r_dzu), (float *)at(scratch, p.s_losspart), loss, s));
     return LSTM_OK;
 }
@@ -407,13 +454,46 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
     int cur = 0;
     char *dh_above = at(scratch, p.s_dh[cur]);
     const char *top = at(reserve, p.r_h[p.L - 1]) + (size_t)BH * es;
-    if (p.head == LSTM_HEAD_LAST_BCE) {
+    if (p.head == LSTM_HEAD_FC_HINGE) {
+        const char *act = at(reserve, p.r_fc);                 // relu(h W_fc^T + b_fc), [TB, F]
+        char *dpre = at(scratch, p.s_fcd);                     // gradient before the ReLU, [TB, F]
+        const char *Wfc = par + p.off_Wfc * es;
+        LSTM_TRY(colsum(p.dtype, act, p.F, TB, p.F, dzu, loss_scale, colpart, grd + p.off_wh * es, s));
+        LSTM_TRY(head_backward_dh(p.dtype, dzu, par + p.off_wh * es, loss_scale, act, dpre, TB, p.F, s));
+        LSTM_TRY(colsum(p.dtype, dpre, p.F, TB, p.F, nullptr, nullptr, colpart, grd + p.off_bfc * es, s));
+        // dW_fc = dpre^T h_top, contracted over all T*B rows
+        GemmArgs w{};
+        w.M = p.F; w.N = p.H; w.K = TB; w.ldc = p.H;
+        w.C = grd + p.off_Wfc * es; w.out_lp = 1;
+        w.splitk_ws = splitk; w.splits = p.split_fc; w.kclass = KC_GEMM_BATCHED;
+        GemmArgs wt = w;
+        wt.A = dpre; wt.lda = p.F; wt.B = top; wt.ldb = p.H;
+        if (gemm_tn_supported(p.dtype, wt)) {
+            LSTM_TRY(gemm_tn(p.dtype, wt, s));
+        } else {
+            char *dpreT = at(scratch, p.s_fcdT);
+            char *topT = at(scratch, p.s_xT);
+            LSTM_TRY(transpose_lp(p.dtype, dpre, p.F, dpreT, TB, TB, p.F, s));
+            LSTM_TRY(transpose_lp(p.dtype, top, p.H, topT, TB, TB, p.H, s));
+            w.A = dpreT; w.B = topT; w.lda = TB; w.ldb = TB;
+            LSTM_TRY(gemm_nt(p.dtype, w, s));
+        }
+        // seed of the top LSTM layer: dh = dpre W_fc
+        char *wfcT = at(scratch, p.s_fcwT);
+        LSTM_TRY(transpose_lp(p.dtype, Wfc, p.H, wfcT, p.F, p.F, p.H, s));
+        GemmArgs d{};
+        d.A = dpre; d.B = wfcT; d.C = dh_above;
+        d.M = TB; d.N = p.H; d.K = p.F;
+        d.lda = p.F; d.ldb = p.F; d.ldc = p.H;
+        d.out_lp = 1; d.kclass = KC_GEMM_BATCHED;
+        LSTM_TRY(gemm_nt(p.dtype, d, s));
+    } else if (p.head == LSTM_HEAD_LAST_BCE) {
         LSTM_TRY(fill_u32(dh_above, 0, (int64_t)(((size_t)TB * p.H * es + 3) / 4), s));
         const char *top_last = top + (size_t)(p.T - 1) * BH * es;
-        LSTM_TRY(head_backward_dh(p.dtype, dzu, par + p.off_wh * es, loss_scale, dh_above + (size_t)(p.T - 1) * BH * es, p.B, p.H, s));
+        LSTM_TRY(head_backward_dh(p.dtype, dzu, par + p.off_wh * es, loss_scale, nullptr, dh_above + (size_t)(p.T - 1) * BH * es, p.B, p.H, s));
         LSTM_TRY(colsum(p.dtype, top_last, p.H, p.B, p.H, dzu, loss_scale, colpart, grd + p.off_wh * es, s));
     } else {
-        LSTM_TRY(head_backward_dh(p.dtype, dzu, par + p.off_wh * es, loss_scale, dh_above, TB, p.H, s));
+        LSTM_TRY(head_backward_dh(p.dtype, dzu, par + p.off_wh * es, loss_scale, nullptr, dh_above, TB, p.H, s));
         LSTM_TRY(colsum(p.dtype, top, p.H, TB, p.H, dzu, loss_scale, colpart, grd + p.off_wh * es, s));
     }
     LSTM_TRY(head_backward_bias(p.dtype, dzu, loss_scale, p.head_rows, grd + p.off_bh * es, s));

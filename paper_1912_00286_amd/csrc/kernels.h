@@ -41,9 +41,11 @@ int colsum(int dtype, const void *in, int64_t ld, int R, int C, const float *row
 int head_loss_blocks(int rows);
 int head_forward(int dtype, int head, const void *h_top, const void *w, const void *b, const float *targets, int rows,
                  int H, int M_total, float *dzu, float *partial, float *loss, hipStream_t s);
-// dh[row,:] = scale * dzu[row] * w
-int head_backward_dh(int dtype, const float *dzu, const void *w, const float *scale_dev, void *dh, int rows, int H,
-                     hipStream_t s);
+// dh[row,:] = scale * dzu[row] * w, zeroed where relu_of (same shape, may be null) is not positive
+int head_backward_dh(int dtype, const float *dzu, const void *w, const float *scale_dev, const void *relu_of, void *dh,
+                     int rows, int H, hipStream_t s);
+// a = max(a, 0) element-wise
+int relu_inplace(int dtype, void *a, int64_t n, hipStream_t s);
 // db_head = scale * sum dzu
 int head_backward_bias(int dtype, const float *dzu, const float *scale_dev, int rows, void *out_lp, hipStream_t s);
 

@@ -199,6 +199,10 @@ __global__ __launch_bounds__(256) void head_forward_kernel(int head, const T *h_
                 const float r = z - y;
                 ell = r * r;
                 d = 2.0f * r;
+            } else if (head == LSTM_HEAD_FC_HINGE) {
+                const float m = 1.0f - y * z;            // Eq. 6 without the multiplier; labels +-1
+                ell = fmaxf(m, 0.0f);
+                d = m > 0.0f ? -y : 0.0f;
             } else {
                 const float az = fabsf(z);
                 const float e = expf(-az);
@@ -226,13 +230,25 @@ __global__ __launch_bounds__(256) void loss_final_kernel(const float *partial, i
     if (threadIdx.x == 0) *loss = (float)(red[0] * (double)inv_M);
 }
 
+// relu_of: when given, the output is the derivative through a ReLU whose result relu_of holds
+// (zero wherever that result is zero)
 template <typename T>
-__global__ void head_backward_dh_kernel(const float *dzu, const T *w, const float *scale_dev, T *dh, int rows, int H) {
+__global__ void head_backward_dh_kernel(const float *dzu, const T *w, const float *scale_dev, const T *relu_of, T *dh,
+                                        int rows, int H) {
     const float S = *scale_dev;
     const int64_t n = (int64_t)rows * H;
     for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x) {
         const int r = (int)(e / H), j = (int)(e % H);
-        dh[e] = Lp<T>::from_f(S * dzu[r] * Lp<T>::to_f(w[j]));
+        float v = S * dzu[r] * Lp<T>::to_f(w[j]);
+        if (relu_of && !(Lp<T>::to_f(relu_of[e]) > 0.0f)) v = 0.0f;
+        dh[e] = Lp<T>::from_f(v);
+    }
+}
+template <typename T>
+__global__ void relu_inplace_kernel(T *a, int64_t n) {
+    for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x) {
+        const float v = Lp<T>::to_f(a[e]);
+        if (!(v > 0.0f)) a[e] = Lp<T>::from_f(0.0f);
     }
 }
 template <typename T>
@@ -378,12 +394,20 @@ int head_forward(int dtype, int head, const void *h_top, const void *w, const vo
     return LSTM_OK;
 }
 
-int head_backward_dh(int dtype, const float *dzu, const void *w, const float *scale_dev, void *dh, int rows, int H,
-                     hipStream_t s) {
+int head_backward_dh(int dtype, const float *dzu, const void *w, const float *scale_dev, const void *relu_of, void *dh,
+                     int rows, int H, hipStream_t s) {
     KernelTimer timer(KC_AUX, s, 0.0, 0.0);
     const int64_t n = (int64_t)rows * H;
     LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(head_backward_dh_kernel<T>, dim3(blocks_for(n, 256, 8192)), dim3(256), 0, s,
-                                               dzu, (const T *)w, scale_dev, (T *)dh, rows, H));
+                                               dzu, (const T *)w, scale_dev, (const T *)relu_of, (T *)dh, rows, H));
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+int relu_inplace(int dtype, void *a, int64_t n, hipStream_t s) {
+    KernelTimer timer(KC_AUX, s, 0.0, 0.0);
+    if (n <= 0) return LSTM_OK;
+    LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(relu_inplace_kernel<T>, dim3(blocks_for(n, 256, 8192)), dim3(256), 0, s, (T *)a, n));
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }

@@ -21,7 +21,7 @@ EFF_LR_MAX = 0.1
 
 
 def oracle_shapes(w: wl.Workload):
-    return orc.param_shapes(w.num_layers, w.input_dim, w.hidden, w.vocab, w.embed_dim)
+    return orc.param_shapes(w.num_layers, w.input_dim, w.hidden, w.vocab, w.embed_dim, w.fc_units)
 
 
 def inputs_for(w: wl.Workload):
@@ -42,7 +42,7 @@ def make_cfg(w: wl.Workload):
     import paper_1912_00286_amd as hip
     return hip.LstmConfig(num_layers=w.num_layers, input_dim=max(w.input_dim, 0), hidden=w.hidden, seq_len=w.seq_len,
                           batch=w.batch, dtype=wl.DTYPE_CODE[w.dtype], head=w.head, out_dim=1, vocab=w.vocab,
-                          embed_dim=w.embed_dim)
+                          embed_dim=w.embed_dim, head_hidden=w.fc_units)
 
 
 def make_opt(w: wl.Workload, kind=0):

@@ -41,7 +41,7 @@ def test_header_symbols_are_exported(hip):
     lib = hip.load_library()
     for n in names:
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
-    assert hip.lstm_abi_version() == 1
+    assert hip.lstm_abi_version() == 2
 
 
 def _cfg(hip, w):
@@ -49,22 +49,27 @@ def _cfg(hip, w):
     return make_cfg(w)
 
 
-@pytest.mark.parametrize("name", list(wl.CONFIGS))
+PAPER_HEAD = wl.Workload("paper_head", 2, 9, 200, 128, 256, "fp16", wl.HEAD_FC_HINGE, fc_units=200, target_kind="sign")
+
+
+@pytest.mark.parametrize("name", list(wl.CONFIGS) + ["paper_head"])
 def test_param_layout_agrees_with_oracle_and_generator(hip, name):
-    w = wl.CONFIGS[name]
+    w = PAPER_HEAD if name == "paper_head" else wl.CONFIGS[name]
     cfg = _cfg(hip, w)
     P = hip.lstm_param_count(cfg)
-    assert P == wl.param_count(w) == orc.param_count(w.num_layers, w.input_dim, w.hidden, w.vocab, w.embed_dim)
-    kinds = {"E": 0, "W": 1, "U": 2, "b": 3, "w_head": 4, "b_head": 5}
+    assert P == wl.param_count(w) == orc.param_count(w.num_layers, w.input_dim, w.hidden, w.vocab, w.embed_dim, w.fc_units)
+    kinds = {"E": 0, "W": 1, "U": 2, "b": 3, "w_head": 4, "b_head": 5, "W_fc": 6, "b_fc": 7}
     off = 0
-    for nm, shape in orc.param_shapes(w.num_layers, w.input_dim, w.hidden, w.vocab, w.embed_dim):
-        if nm in ("E", "w_head", "b_head"):
+    for nm, shape in orc.param_shapes(w.num_layers, w.input_dim, w.hidden, w.vocab, w.embed_dim, w.fc_units):
+        if nm in ("E", "w_head", "b_head", "W_fc", "b_fc"):
             o, c = hip.lstm_param_offset(cfg, kinds[nm], 0)
         else:
             o, c = hip.lstm_param_offset(cfg, kinds[nm[0]], int(nm[1:]))
         assert (o, c) == (off, int(np.prod(shape))), nm
         off += c
     assert off == P
+    assert [n for n, _ in wl.param_segments(w)] == [n for n, _ in orc.param_shapes(w.num_layers, w.input_dim, w.hidden, w.vocab,
+                                                                                   w.embed_dim, w.fc_units)]
 
 
 def test_param_counts_of_the_benchmark_configs(hip):
@@ -106,7 +111,7 @@ def test_capacity_trends_of_table1(hip):
 def test_invalid_arguments_are_rejected_on_the_host(hip):
     w = wl.CONFIGS["tiny"]
     for field, val, status in (("batch", 0, -1), ("seq_len", 0, -1), ("hidden", 0, -1), ("num_layers", 0, -1),
-                               ("dtype", 7, -1), ("head", 0, -1), ("out_dim", 2, -2), ("input_dim", 0, -1)):
+                               ("dtype", 7, -1), ("head", 0, -1), ("head", 5, -1), ("out_dim", 2, -2), ("input_dim", 0, -1)):
         cfg = _cfg(hip, w)
         setattr(cfg, field, val)
         with pytest.raises(hip.LstmError) as e:

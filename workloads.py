@@ -23,6 +23,7 @@ import numpy as np
 HEAD_STEP_BCE = 1   # per-timestep sigmoid + binary cross-entropy
 HEAD_LAST_BCE = 2   # last-timestep sigmoid + binary cross-entropy
 HEAD_STEP_MSE = 3   # per-timestep linear + mean squared error
+HEAD_FC_HINGE = 4   # the paper's head: fully connected ReLU layer per time slice, one output, hinge loss, labels +-1
 
 DTYPE_CODE = {"fp32": 0, "fp16": 1, "bf16": 2}
 
@@ -48,7 +49,8 @@ class Workload:
     n_half: float = 1e12            # single-worker configs: Eq. 4 leaves lr0 unchanged
     warmup_steps: int = 0
     gamma: float = 1.0
-    target_kind: str = "bernoulli"   # "bernoulli" | "normal"
+    fc_units: int = 0               # units of the fully connected head layer (HEAD_FC_HINGE)
+    target_kind: str = "bernoulli"   # "bernoulli" | "normal" | "sign" (+1 with probability target_p, else -1)
     target_p: float = 0.1
     data_seed: int = 0
     weight_seed: int = 7
@@ -89,7 +91,8 @@ def param_segments(w: Workload) -> List[Tuple[str, Tuple[int, ...]]]:
     """Names and shapes of the parameter tensors in flat-buffer order.
 
     Order: [embedding] {W_l[4H,I_l], U_l[4H,H], b_l[4H]} for each layer,
-    then head weight [H] and head bias [1].  Pure bookkeeping.
+    then head weight [H] and head bias [1] (with a fully connected head layer:
+    W_fc[F,H], b_fc[F], head weight [F], head bias [1]).  Pure bookkeeping.
     """
     segs: List[Tuple[str, Tuple[int, ...]]] = []
     if w.vocab > 0:
@@ -99,7 +102,12 @@ def param_segments(w: Workload) -> List[Tuple[str, Tuple[int, ...]]]:
         segs.append((f"W{l}", (G, i_l)))
         segs.append((f"U{l}", (G, w.hidden)))
         segs.append((f"b{l}", (G,)))
-    segs.append(("w_head", (w.hidden,)))
+    if w.fc_units > 0:
+        segs.append(("W_fc", (w.fc_units, w.hidden)))
+        segs.append(("b_fc", (w.fc_units,)))
+        segs.append(("w_head", (w.fc_units,)))
+    else:
+        segs.append(("w_head", (w.hidden,)))
     segs.append(("b_head", (1,)))
     return segs
 
@@ -147,6 +155,8 @@ def make_batch(w: Workload, worker: int = 0) -> Tuple[np.ndarray, np.ndarray]:
     tshape = (B, 1) if w.head == HEAD_LAST_BCE else (T, B, 1)
     if w.target_kind == "normal":
         y = rng.standard_normal(tshape).astype(np.float32)
+    elif w.target_kind == "sign":
+        y = np.where(rng.random(tshape) < w.target_p, 1.0, -1.0).astype(np.float32)
     else:
         y = (rng.random(tshape) < w.target_p).astype(np.float32)
     return x, y
