@@ -125,6 +125,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="large")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--streams", type=int, default=0,
+                    help="streams the simulated workers are spread over (0: 4 when there are several workers, else 1)")
+    ap.add_argument("--one-by-one", action="store_true",
+                    help="run the simulated workers' fprop/BPTT one after another instead of stacked into one call")
     ap.add_argument("--eager", action="store_true",
                     help="enqueue every launch from the host in the timed region instead of replaying a HIP graph")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -158,8 +162,18 @@ def main():
     log(f"[bench] workload {w.name}: L={w.num_layers} H={w.hidden} T={w.seq_len} B={w.batch} N={w.n_workers} {w.dtype}")
 
     master0, xs, ys = pu.inputs_for(w)
-    ts = pu.make_step(w, master0, dev)
+    n_streams = args.streams if args.streams > 0 else (4 if w.n_workers > 1 else 1)
+    ts = None
+    if w.n_workers > 1 and not args.one_by_one:
+        try:                                    # all workers' micro-batches stacked into one call per direction
+            ts = pu.make_step(w, master0, dev, batched=True)
+        except hip.LstmError as e:
+            log(f"[bench] stacked form not available for this shape ({e}); running the workers one by one")
+    if ts is None:
+        ts = pu.make_step(w, master0, dev, n_streams=n_streams)
     dx, dy = pu.device_batches(w, xs, ys, ts.lp_dtype, dev)
+    if ts.batched:
+        dx, dy = ts.stack_workers(dx, dy)
     del xs, ys
 
     # fprop + BPTT of every worker and the gradient average are recorded once as a HIP graph (this
@@ -240,6 +254,7 @@ def main():
         "sequential_steps_per_s": w.seq_len * w.num_layers * w.n_workers * args.steps / dt,
         "step_mfma_frac": gemm_flops_per_step(w) / (ms_per_step * 1e-3) / 1e12 / PEAK_TFLOPS[w.dtype],
         "gate_gemm_mfma_frac": (gemm_fl / (gemm_ms * 1e-3) / 1e12 / PEAK_TFLOPS[w.dtype]) if gemm_ms > 0 else None,
+        "worker_streams": ts.n_streams, "workers_stacked": ts.batched,
         "launch": "eager" if args.eager else "hip_graph (fprop+BPTT+grad_average) + master_update",
         "overflow_steps": overflow_steps, "loss_scale": float(ts.loss_scale.item()), "loss": loss_after,
         "roofline": roof,

@@ -38,7 +38,7 @@
 extern "C" {
 #endif
 
-#define LSTM_ABI_VERSION 2
+#define LSTM_ABI_VERSION 3
 
 enum {
     LSTM_OK = 0,
@@ -80,6 +80,18 @@ typedef struct {
     int32_t vocab;       /* > 0: x holds int32 token ids, looked up in E[V,D]   */
     int32_t embed_dim;   /* D (input dim of layer 0 when vocab > 0)             */
     int32_t head_hidden; /* F >= 1 with LSTM_HEAD_FC_HINGE, ignored otherwise   */
+    int32_t workers;     /* W: simulated workers processed together, each with
+                            its own micro-batch of `batch` samples (0 reads as
+                            1).  With W > 1: x is [T, W, B, I], targets
+                            [T, W, B, 1] (last-step head: [W, B, 1]), h0/c0/
+                            hT/cT [L, W*B, H], loss fp32[W] (one mean per
+                            worker), grads_lp lp[W, n_params] (one raw
+                            gradient per worker, as if each had run alone).
+                            All workers share params_lp.  Supported for the
+                            16-bit types, batch a multiple of 64, no
+                            embedding, the three single-layer heads;
+                            otherwise LSTM_ERR_UNSUPPORTED (call once per
+                            worker instead).                                   */
 } lstm_config;
 
 /* Optimiser and loss-scale policy for master_update. */

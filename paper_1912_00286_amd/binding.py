@@ -27,7 +27,7 @@ class LstmError(RuntimeError):
 
 class LstmConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("num_layers", "input_dim", "hidden", "seq_len", "batch", "dtype", "head",
-                                         "out_dim", "vocab", "embed_dim", "head_hidden")]
+                                         "out_dim", "vocab", "embed_dim", "head_hidden", "workers")]
 
 
 class OptimizerConfig(C.Structure):
@@ -200,14 +200,24 @@ class TrainingStep:
     gradient average, the schedule and the master update."""
 
     def __init__(self, cfg: LstmConfig, opt: OptimizerConfig, n_workers: int, master_fp32, loss_scale: float,
-                 device="cuda:0"):
+                 device="cuda:0", n_streams: int = 1, batched: bool = False):
+        import copy
         import torch
         self.torch = torch
         self.cfg, self.opt, self.N = cfg, opt, int(n_workers)
         self.dev = torch.device(device)
         self.lp_dtype = {DTYPE_FP32: torch.float32, DTYPE_FP16: torch.float16, DTYPE_BF16: torch.bfloat16}[cfg.dtype]
         self.P = lstm_param_count(cfg)
-        rb, sb = lstm_workspace_bytes(cfg)
+        # batched: all workers' micro-batches go through one forward and one backward call
+        # (lstm_config.workers); the per-worker losses and gradients come out as if each worker
+        # had run alone.  Raises LstmError where the library has no such path for the shape.
+        self.batched = bool(batched) and self.N > 1
+        self.call_cfg = cfg
+        if self.batched:
+            self.call_cfg = copy.copy(cfg)
+            self.call_cfg.workers = self.N
+            n_streams = 1
+        rb, sb = lstm_workspace_bytes(self.call_cfg)
         self.master = torch.as_tensor(master_fp32, dtype=torch.float32).to(self.dev).contiguous()
         assert self.master.numel() == self.P
         self.params_lp = self.master.to(self.lp_dtype)          # storage cast only
@@ -215,21 +225,55 @@ class TrainingStep:
         self.state2 = torch.zeros(self.P, dtype=torch.float32, device=self.dev) if opt.kind == OPT_ADAM else None
         self.grads = torch.zeros((self.N, self.P), dtype=self.lp_dtype, device=self.dev)
         self.avg = torch.zeros(self.P, dtype=torch.float32, device=self.dev)
-        self.reserve = torch.empty(rb, dtype=torch.uint8, device=self.dev)
-        self.scratch = torch.empty(sb, dtype=torch.uint8, device=self.dev)
+        # The simulated workers are independent until their gradients are averaged.  With
+        # n_streams > 1 they are spread over that many streams (default priority), each with a
+        # workspace of its own, so that the short dependent kernel chains of small models overlap.
+        self.n_streams = max(1, min(int(n_streams), self.N))
+        self.reserves = [torch.empty(rb, dtype=torch.uint8, device=self.dev) for _ in range(self.n_streams)]
+        self.scratches = [torch.empty(sb, dtype=torch.uint8, device=self.dev) for _ in range(self.n_streams)]
+        self.reserve, self.scratch = self.reserves[0], self.scratches[0]
+        self.side_streams = [torch.cuda.Stream(device=self.dev) for _ in range(self.n_streams - 1)]
         self.losses = torch.zeros(self.N, dtype=torch.float32, device=self.dev)
         self.loss_scale = torch.tensor([loss_scale], dtype=torch.float32, device=self.dev)
         self.found_inf = torch.zeros(1, dtype=torch.int32, device=self.dev)
         self.good_steps = torch.zeros(1, dtype=torch.int32, device=self.dev)
         self.step_index = 0
 
+    def _worker(self, w, xs, ys, k, stream=None):
+        lstm_forward(self.cfg, self.params_lp, xs[w], ys[w], None, None, self.reserves[k], self.scratches[k],
+                     self.losses[w:w + 1], stream=stream)
+        lstm_backward(self.cfg, self.params_lp, xs[w], ys[w], self.reserves[k], self.scratches[k], self.loss_scale,
+                      self.grads[w], stream=stream)
+
+    def stack_workers(self, xs, ys):
+        """Per-worker tensors -> the [T, W, B, ...] layout of the batched form (copies)."""
+        torch = self.torch
+        x_all = torch.stack(list(xs), dim=1).contiguous()
+        y_all = torch.stack(list(ys), dim=1 if ys[0].dim() == 3 else 0).contiguous()
+        return x_all, y_all
+
     def forward_backward(self, xs, ys):
-        """xs, ys: per-worker device tensors (x lp [T,B,I] or int32 ids; targets fp32)."""
+        """xs, ys: per-worker device tensors (x lp [T,B,I] or int32 ids; targets fp32).  In
+        the batched form also accepted already stacked (see stack_workers)."""
+        torch = self.torch
+        if self.batched:
+            if isinstance(xs, (list, tuple)):
+                xs, ys = self.stack_workers(xs, ys)
+            lstm_forward(self.call_cfg, self.params_lp, xs, ys, None, None, self.reserve, self.scratch, self.losses)
+            lstm_backward(self.call_cfg, self.params_lp, xs, ys, self.reserve, self.scratch, self.loss_scale, self.grads)
+            return
+        if self.n_streams == 1:
+            for w in range(self.N):
+                self._worker(w, xs, ys, 0)
+            return
+        main = torch.cuda.current_stream(self.dev)
+        for st in self.side_streams:                       # fork: the side streams see the current weights
+            st.wait_stream(main)
         for w in range(self.N):
-            lstm_forward(self.cfg, self.params_lp, xs[w], ys[w], None, None, self.reserve, self.scratch,
-                         self.losses[w:w + 1])
-            lstm_backward(self.cfg, self.params_lp, xs[w], ys[w], self.reserve, self.scratch, self.loss_scale,
-                          self.grads[w])
+            k = w % self.n_streams
+            self._worker(w, xs, ys, k, None if k == 0 else self.side_streams[k - 1])
+        for st in self.side_streams:                       # join before the gradients are averaged
+            main.wait_stream(st)
 
     def update(self, lr: float):
         grad_average(self.P, self.N, self.grads, self.cfg.dtype, self.loss_scale, self.avg, self.found_inf)
@@ -250,6 +294,8 @@ class TrainingStep:
     # to step and are passed by value, so master_update stays outside the graph.
     def capture(self, xs, ys):
         torch = self.torch
+        if self.batched and isinstance(xs, (list, tuple)):
+            xs, ys = self.stack_workers(xs, ys)
         self._captured_inputs = (xs, ys)             # the graph reads these buffers on every replay
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):

@@ -26,7 +26,8 @@ inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 // Everything derived from a config: parameter offsets (elements) and the byte
 // offsets of each region inside the caller's reserve and scratch buffers.
 struct Plan {
-    int L, H, T, B, G, dtype, head, V, D;
+    int L, H, T, B, G, dtype, head, V, D;   // B: rows per time step = workers * per-worker batch
+    int W = 1, Bw = 0;                       // simulated workers processed together, batch of each
     size_t es;                           // bytes per lp element
     std::vector<int> in_dim;             // I_l
     int F = 0;                           // units of the fully connected head layer (0: none)
@@ -84,7 +85,16 @@ int make_plan(const lstm_config *c, Plan &p) {
         set_error("config: shape too large for this build (T*B=%lld, H=%d, L=%d)", (long long)rows, c->hidden, c->num_layers);
         return LSTM_ERR_UNSUPPORTED;
     }
-    p.L = c->num_layers; p.H = c->hidden; p.T = c->seq_len; p.B = c->batch; p.G = 4 * c->hidden;
+    p.W = c->workers > 1 ? c->workers : 1;
+    p.Bw = c->batch;
+    if (p.W > 1) {
+        if (c->dtype == LSTM_DTYPE_FP32 || c->batch % 64 != 0 || c->vocab > 0 || c->head == LSTM_HEAD_FC_HINGE || p.W > 4096 ||
+            (int64_t)c->seq_len * c->batch * p.W > (int64_t)65535 * 64) {
+            set_error("config: workers=%d needs a 16-bit type, batch %% 64 == 0, no embedding and a single-layer head", p.W);
+            return LSTM_ERR_UNSUPPORTED;
+        }
+    }
+    p.L = c->num_layers; p.H = c->hidden; p.T = c->seq_len; p.B = c->batch * p.W; p.G = 4 * c->hidden;
     p.dtype = c->dtype; p.head = c->head; p.V = c->vocab; p.D = c->vocab > 0 ? c->embed_dim : 0;
     p.F = c->head == LSTM_HEAD_FC_HINGE ? c->head_hidden : 0;
     p.es = dtype_size(c->dtype);
@@ -173,7 +183,7 @@ int make_plan(const lstm_config *c, Plan &p) {
         p.s_fcwT = s; s += align_up((size_t)p.F * p.H * p.es);
     }
     const int colw = (p.G > p.H ? p.G : p.H) > p.F ? (p.G > p.H ? p.G : p.H) : p.F;
-    p.s_colpart = s; s += align_up((size_t)colsum_chunks((int)TB) * colw * 4);
+    p.s_colpart = s; s += align_up((size_t)colsum_chunks((int)(TB / p.W)) * p.W * colw * 4);
     p.s_dE32 = s; if (p.V > 0) s += align_up((size_t)p.V * p.D * 4);
     if (p.dtype != LSTM_DTYPE_FP32) {
         // packed operands of the fused recurrent kernels
@@ -187,6 +197,10 @@ int make_plan(const lstm_config *c, Plan &p) {
         p.s_dablk = s; s += align_up(blocked_elems((int)TB, p.G) * p.es);
     }
     p.scratch_bytes = s;
+    if (p.W > 1 && !p.blk) {
+        set_error("config: workers=%d needs shapes the blocked GEMM path handles (T*W*B >= 192, 4H >= 192)", p.W);
+        return LSTM_ERR_UNSUPPORTED;
+    }
     return LSTM_OK;
 }
 
@@ -408,7 +422,8 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
         head_width = p.F;
     }
     LSTM_TRY(head_forward(p.dtype, p.head, top, par + p.off_wh * es, par + p.off_bh * es, targets, p.head_rows, head_width,
-                          p.head_rows, (float *)at(reserve, p.r_dzu), (float *)at(scratch, p.s_losspart), loss, s));
+                          p.head_rows / p.W, (float *)at(reserve, p.r_dzu), (float *)at(scratch, p.s_losspart), loss, s, p.W,
+                          p.Bw));
     return LSTM_OK;
 }
 
@@ -491,12 +506,12 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
         LSTM_TRY(fill_u32(dh_above, 0, (int64_t)(((size_t)TB * p.H * es + 3) / 4), s));
         const char *top_last = top + (size_t)(p.T - 1) * BH * es;
         LSTM_TRY(head_backward_dh(p.dtype, dzu, par + p.off_wh * es, loss_scale, nullptr, dh_above + (size_t)(p.T - 1) * BH * es, p.B, p.H, s));
-        LSTM_TRY(colsum(p.dtype, top_last, p.H, p.B, p.H, dzu, loss_scale, colpart, grd + p.off_wh * es, s));
+        LSTM_TRY(colsum(p.dtype, top_last, p.H, p.Bw, p.H, dzu, loss_scale, colpart, grd + p.off_wh * es, s, p.W, p.Bw, p.P));
     } else {
         LSTM_TRY(head_backward_dh(p.dtype, dzu, par + p.off_wh * es, loss_scale, nullptr, dh_above, TB, p.H, s));
-        LSTM_TRY(colsum(p.dtype, top, p.H, TB, p.H, dzu, loss_scale, colpart, grd + p.off_wh * es, s));
+        LSTM_TRY(colsum(p.dtype, top, p.H, TB / p.W, p.H, dzu, loss_scale, colpart, grd + p.off_wh * es, s, p.W, p.Bw, p.P));
     }
-    LSTM_TRY(head_backward_bias(p.dtype, dzu, loss_scale, p.head_rows, grd + p.off_bh * es, s));
+    LSTM_TRY(head_backward_bias(p.dtype, dzu, loss_scale, p.head_rows / p.W, grd + p.off_bh * es, s, p.W, p.Bw, p.P));
 
     char *dA = at(scratch, p.s_dA);
     char *dAT = at(scratch, p.s_dAT);
@@ -591,8 +606,9 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
         GemmArgs wt = w, ut = u;
         wt.A = dA; wt.lda = p.G; wt.B = layer_in; wt.ldb = I;
         ut.A = dA; ut.lda = p.G; ut.B = hs; ut.ldb = p.H;                 // h_0..h_{T-1}
-        const bool w_blk = p.blk && gemm_blocked_supported(p.dtype, p.G, I);
-        const bool u_blk = p.blk && gemm_blocked_supported(p.dtype, p.G, p.H);
+        // several workers: always the blocked kernel (its per-worker K mapping), whatever the width
+        const bool w_blk = p.blk && (p.W > 1 || gemm_blocked_supported(p.dtype, p.G, I));
+        const bool u_blk = p.blk && (p.W > 1 || gemm_blocked_supported(p.dtype, p.G, p.H));
         const bool w_tn = !w_blk && gemm_tn_supported(p.dtype, wt), u_tn = !u_blk && gemm_tn_supported(p.dtype, ut);
         if ((!w_blk && !w_tn) || (!u_blk && !u_tn)) LSTM_TRY(transpose_lp(p.dtype, dA, p.G, dAT, TB, TB, p.G, s));
         auto blocked_wgrad = [&](const GemmArgs &r, const BlockedOperand &bop) {
@@ -602,6 +618,12 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             g.C = r.C; g.ldc = r.ldc; g.out_lp = 1;
             g.M = r.M; g.N = r.N; g.K = r.K;
             g.splitk_ws = r.splitk_ws; g.splits = r.splits; g.kclass = r.kclass;
+            if (p.W > 1) {
+                // one product per worker over that worker's rows of every time step
+                g.K = r.K / p.W;
+                g.batch = p.W; g.seg_len = p.Bw / 64; g.seg_stride = p.B / 64; g.batch_c = p.P;
+                g.splitk_ws = nullptr; g.splits = 1;
+            }
             return gemm_blocked(p.dtype, g, s);
         };
         if (w_blk) {
@@ -622,7 +644,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             u.A = dAT; u.B = xT; u.lda = TB; u.ldb = TB;
             LSTM_TRY(gemm_nt(p.dtype, u, s));
         }
-        LSTM_TRY(colsum(p.dtype, dA, p.G, TB, p.G, nullptr, nullptr, colpart, grd + p.off_b[l] * es, s));
+        LSTM_TRY(colsum(p.dtype, dA, p.G, TB / p.W, p.G, nullptr, nullptr, colpart, grd + p.off_b[l] * es, s, p.W, p.Bw, p.P));
         cur ^= 1;
         dh_above = d_below;
     }

@@ -164,6 +164,11 @@ struct BlockedGemmArgs {
     float *splitk_ws;
     int splits;
     int kclass;
+    // batch > 1 (both operands in the rows-are-K role): `batch` products whose K rows interleave in
+    // memory in segments of seg_len block rows: K tile t of product y is block row
+    // (t / seg_len) * seg_stride + t % seg_len + y * seg_len; results batch_c elements apart.
+    int batch = 1, seg_len = 0, seg_stride = 0;
+    int64_t batch_c = 0;
 };
 size_t blocked_elems(int rows, int cols);
 // dst (blocked, zero padded) = src (row-major [rows, cols], leading dimension ld)

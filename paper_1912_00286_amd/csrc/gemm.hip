@@ -31,6 +31,11 @@ struct KernArgs {
     int k_chunk;        // K range handled by one blockIdx.z
     int vec_ok;         // rows 16-byte aligned and K % 8 == 0: 16-byte global loads allowed
     int vec_out;        // 16-bit C with 16-byte aligned rows: 16-byte global stores allowed
+    // blocked operands in the "rows are K" role only: batch of GEMMs (blockIdx.y) whose K rows are
+    // interleaved in memory.  K tile t of batch entry y is block row
+    //   (t / seg_len) * seg_stride + t % seg_len + y * seg_len      (seg_len = 0: plain, one GEMM)
+    int seg_len, seg_stride;
+    int64_t batch_c;    // elements between the results of consecutive batch entries
 };
 
 // 8 consecutive lp elements of row `row` at column k; zero outside the operand.
@@ -284,12 +289,29 @@ __device__ __forceinline__ void big_epilogue(const KernArgs &a, BigSmem &sm, v16
 //      row segments of 128 bytes, which is what the L2 -> CU path streams at full rate.
 // PP:  steady state in the ping-pong slot schedule (below) instead of the plain two-stage loop.
 template <typename T, bool TA, bool TB_, bool BLK, bool PP>
-__global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a, int tiles_m, int tiles_n) {
+__global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a_in, int tiles_m, int tiles_n) {
     constexpr int GNV = GBM * GBK / 8 / GTHREADS;  // 16-byte vectors per thread, operand and K tile (4)
     constexpr int MI = 2;                          // 32-row MFMA blocks per wavefront
     __shared__ __attribute__((aligned(16))) BigSmem sm;
+    KernArgs a = a_in;
     const T *A = reinterpret_cast<const T *>(a.A);
     const T *B = reinterpret_cast<const T *>(a.B);
+    if constexpr (BLK && TA && TB_) {
+        // batch entry blockIdx.y: its K rows start seg_len block rows further on in both operands
+        if (a.seg_len > 0) {
+            const int64_t y = blockIdx.y;
+            A += y * a.seg_len * a.lda * 4096;
+            B += y * a.seg_len * a.ldb * 4096;
+            a.C = reinterpret_cast<char *>(a.C) + y * a.batch_c * (a.out_lp ? (int64_t)sizeof(T) : 4);
+        }
+    }
+    // K tile -> block row of a "rows are K" blocked operand
+    auto krow = [&](int tile) -> uint32_t {
+        if constexpr (BLK && TA && TB_) {
+            if (a.seg_len > 0) return (uint32_t)((tile / a.seg_len) * a.seg_stride + tile % a.seg_len);
+        }
+        return (uint32_t)tile;
+    };
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -353,8 +375,8 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a, int
     auto gload_full = [&](u32x4 (&ra)[GNV], u32x4 (&rb)[GNV], int tile) {
 #pragma unroll
         for (int i = 0; i < GNV; ++i) {
-            ra[i] = *reinterpret_cast<const u32x4 *>(A + (oa[i] + (uint32_t)tile * step_a));
-            rb[i] = *reinterpret_cast<const u32x4 *>(B + (ob[i] + (uint32_t)tile * step_b));
+            ra[i] = *reinterpret_cast<const u32x4 *>(A + (oa[i] + (TA ? krow(tile) : (uint32_t)tile) * step_a));
+            rb[i] = *reinterpret_cast<const u32x4 *>(B + (ob[i] + (TB_ ? krow(tile) : (uint32_t)tile) * step_b));
         }
     };
     auto gload_any = [&](u32x4 (&ra)[GNV], u32x4 (&rb)[GNV], int tile) {   // also the last, partial tile
@@ -364,9 +386,9 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a, int
             // first k of this vector inside the tile (blocked operands are padded: always inside)
             const int ka = BLK ? 0 : (TA ? v / GVPK : (v % GVPR) * 8);
             const int kb = BLK ? 0 : (TB_ ? v / GVPK : (v % GVPR) * 8);
-            ra[i] = tile * GBK + ka < klen ? *reinterpret_cast<const u32x4 *>(A + (oa[i] + (uint32_t)tile * step_a))
+            ra[i] = tile * GBK + ka < klen ? *reinterpret_cast<const u32x4 *>(A + (oa[i] + (TA ? krow(tile) : (uint32_t)tile) * step_a))
                                            : u32x4{0u, 0u, 0u, 0u};
-            rb[i] = tile * GBK + kb < klen ? *reinterpret_cast<const u32x4 *>(B + (ob[i] + (uint32_t)tile * step_b))
+            rb[i] = tile * GBK + kb < klen ? *reinterpret_cast<const u32x4 *>(B + (ob[i] + (TB_ ? krow(tile) : (uint32_t)tile) * step_b))
                                            : u32x4{0u, 0u, 0u, 0u};
         }
     };
@@ -434,6 +456,8 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a, int
                 __builtin_amdgcn_sched_barrier(0);
             };
             auto pp_tile = [&](int buf, u32x4 (&ra)[GNV], u32x4 (&rb)[GNV], int tile_next) {
+                const uint32_t next_a = (TA ? krow(tile_next) : (uint32_t)tile_next) * step_a;
+                const uint32_t next_b = (TB_ ? krow(tile_next) : (uint32_t)tile_next) * step_b;
 #pragma unroll
                 for (int ks = 0; ks < GBK / 16; ++ks) {
                     u32x4 fa[MI], fb[4];
@@ -449,8 +473,8 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a, int
                     }
                     *reinterpret_cast<u32x4 *>(&sm.a[buf ^ 1][lds_off(TA, ks)]) = ra[ks];
                     *reinterpret_cast<u32x4 *>(&sm.b[buf ^ 1][lds_off(TB_, ks)]) = rb[ks];
-                    ra[ks] = *reinterpret_cast<const u32x4 *>(A + (oa[ks] + (uint32_t)tile_next * step_a));
-                    rb[ks] = *reinterpret_cast<const u32x4 *>(B + (ob[ks] + (uint32_t)tile_next * step_b));
+                    ra[ks] = *reinterpret_cast<const u32x4 *>(A + (oa[ks] + next_a));
+                    rb[ks] = *reinterpret_cast<const u32x4 *>(B + (ob[ks] + next_b));
                     slot_barrier();
 #pragma unroll
                     for (int i = 0; i < MI; ++i)
@@ -621,7 +645,7 @@ int launch(const GemmArgs &g, hipStream_t stream) {
     const bool big = aligned && fits_32bit(g.M, g.lda, g.N, g.ldb) &&
                      use_big_tiles(is_f32 ? LSTM_DTYPE_FP32 : LSTM_DTYPE_FP16, g.M, g.N);
     const int bm = is_f32 ? SBM : (big ? GBM : BM), bn = is_f32 ? SBN : (big ? GBN : BN), bk = is_f32 ? SBK : BK;
-    KernArgs a;
+    KernArgs a{};
     a.A = g.A; a.B = g.B; a.C = g.C; a.bias = g.bias;
     a.M = g.M; a.N = g.N; a.K = g.K;
     a.lda = g.lda; a.ldb = g.ldb; a.ldc = g.ldc;
@@ -661,7 +685,7 @@ int launch(const GemmArgs &g, hipStream_t stream) {
 // C[M,N] = A^T B with A[K,M] (lda), B[K,N] (ldb); only the large-tile kernel implements it
 template <typename T>
 int launch_tn(const GemmArgs &g, hipStream_t stream) {
-    KernArgs a;
+    KernArgs a{};
     a.A = g.A; a.B = g.B; a.C = g.C; a.bias = nullptr;
     a.M = g.M; a.N = g.N; a.K = g.K;
     a.lda = g.lda; a.ldb = g.ldb; a.ldc = g.ldc;
@@ -718,7 +742,7 @@ int gemm_nt(int dtype, const GemmArgs &g, hipStream_t stream) {
 namespace {
 template <typename T>
 int launch_blocked(const BlockedGemmArgs &g, hipStream_t stream) {
-    KernArgs a;
+    KernArgs a{};
     a.A = g.A.ptr; a.B = g.B.ptr; a.C = g.C; a.bias = g.bias;
     a.M = g.M; a.N = g.N;
     a.K = (g.K + 63) / 64 * 64;                  // operands are zero padded to whole blocks
@@ -735,7 +759,10 @@ int launch_blocked(const BlockedGemmArgs &g, hipStream_t stream) {
     a.vec_ok = 1;
     a.vec_out = (g.out_lp && g.ldc % 8 == 0 && (uintptr_t)g.C % 16 == 0) ? 1 : 0;
     const int tiles_m = (g.M + GBM - 1) / GBM, tiles_n = (g.N + GBN - 1) / GBN;
-    const dim3 grid(tiles_m * tiles_n, 1, splits);
+    a.seg_len = g.batch > 1 ? g.seg_len : 0;
+    a.seg_stride = g.seg_stride;
+    a.batch_c = g.batch_c;
+    const dim3 grid(tiles_m * tiles_n, g.batch > 1 ? g.batch : 1, splits);
     KernelTimer timer(g.kclass, stream, 2.0 * g.M * g.N * g.K, gemm_algorithmic_bytes<T>(g));
     if (!g.A.trans && !g.B.trans)
         hipLaunchKernelGGL((gemm_mfma_big_kernel<T, false, false, true, true>), grid, dim3(GTHREADS), 0, stream, a, tiles_m, tiles_n);
@@ -779,8 +806,18 @@ int gemm_blocked(int dtype, const BlockedGemmArgs &g, hipStream_t stream) {
         set_error("gemm_blocked: invalid argument");
         return LSTM_ERR_INVALID;
     }
+    int64_t kb = (g.K + 63) / 64;
+    if (g.batch > 1) {
+        // a batch of products whose K rows interleave in memory: whole segments, rows-are-K roles, no split-K
+        if (!g.A.trans || !g.B.trans || g.seg_len < 1 || g.seg_stride < g.seg_len * g.batch || g.K % (64 * g.seg_len) != 0 ||
+            g.splits > 1 || g.batch > 65535) {
+            set_error("gemm_blocked: unsupported batched form (batch=%d seg_len=%d seg_stride=%d K=%d)", g.batch, g.seg_len,
+                      g.seg_stride, g.K);
+            return LSTM_ERR_UNSUPPORTED;
+        }
+        kb = kb / g.seg_len * g.seg_stride;            // block rows the batch spans in memory
+    }
     // operand extents in elements must fit the kernel's 32-bit offsets
-    const int64_t kb = (g.K + 63) / 64;
     const int64_t ea = (g.A.trans ? kb : (int64_t)(g.M + 63) / 64) * g.A.ncb * 4096;
     const int64_t eb = (g.B.trans ? kb : (int64_t)(g.N + 63) / 64) * g.B.ncb * 4096;
     if (ea >= (int64_t)1 << 31 || eb >= (int64_t)1 << 31) {

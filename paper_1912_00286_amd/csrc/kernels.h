@@ -34,20 +34,24 @@ int transpose_lp(int dtype, const void *in, int64_t ld_in, void *out, int64_t ld
 // out_lp[c] = scale * sum_r w[r] * in[r,c]   (w null = 1; scale_dev null = 1)
 // partial: fp32 [chunks, C] workspace with chunks = colsum_chunks(R)
 int colsum_chunks(int R);
+// Several workers (rows interleaved in segments of `seg` rows per time step, see RowSeg in
+// pointwise.hip): R rows per worker, one result per worker out_stride elements apart,
+// partial then holds workers * chunks * C floats.
 int colsum(int dtype, const void *in, int64_t ld, int R, int C, const float *row_w, const float *scale_dev,
-           float *partial, void *out_lp, hipStream_t s);
+           float *partial, void *out_lp, hipStream_t s, int workers = 1, int seg = 0, int64_t out_stride = 0);
 
 // head forward: z = h.w + b per row; loss partial sums; dzu = dloss/dz (unscaled, already / M)
 int head_loss_blocks(int rows);
 int head_forward(int dtype, int head, const void *h_top, const void *w, const void *b, const float *targets, int rows,
-                 int H, int M_total, float *dzu, float *partial, float *loss, hipStream_t s);
+                 int H, int M_total, float *dzu, float *partial, float *loss, hipStream_t s, int workers = 1, int seg = 0);
 // dh[row,:] = scale * dzu[row] * w, zeroed where relu_of (same shape, may be null) is not positive
 int head_backward_dh(int dtype, const float *dzu, const void *w, const float *scale_dev, const void *relu_of, void *dh,
                      int rows, int H, hipStream_t s);
 // a = max(a, 0) element-wise
 int relu_inplace(int dtype, void *a, int64_t n, hipStream_t s);
 // db_head = scale * sum dzu
-int head_backward_bias(int dtype, const float *dzu, const float *scale_dev, int rows, void *out_lp, hipStream_t s);
+int head_backward_bias(int dtype, const float *dzu, const float *scale_dev, int rows, void *out_lp, hipStream_t s,
+                       int workers = 1, int seg = 0, int64_t out_stride = 0);
 
 // embedding: X[row,:] = E[clamp(ids[row]),:]
 int embed_gather(int dtype, const int32_t *ids, const void *E, void *X, int rows, int V, int D, hipStream_t s);

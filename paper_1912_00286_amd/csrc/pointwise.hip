@@ -15,6 +15,14 @@ namespace lstm {
 
 namespace {
 
+// Rows of several simulated workers interleave in the time-major activations: logical row r of
+// worker w (its own [T, seg] rows) lies at (r / seg) * (workers * seg) + w * seg + r % seg.
+// One worker: the identity.
+struct RowSeg {
+    int workers, seg;
+    __device__ inline int64_t row(int r, int w) const { return (int64_t)(r / seg) * workers * seg + (int64_t)w * seg + r % seg; }
+};
+
 // The fp32 baseline mode uses the accurate library functions; the
 // low-precision modes use the hardware exponential.
 template <typename T> struct Act {
@@ -118,7 +126,7 @@ __global__ __launch_bounds__(256) void transpose_kernel(const U *in, int64_t ld_
 constexpr int CS_ROWS = 512;  // rows per column-sum chunk
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_partial_kernel(const T *in, int64_t ld, int R, int C, const float *row_w,
-                                                             float *partial) {
+                                                             float *partial, RowSeg rs) {
     __shared__ float red[4][64];
     const int c = blockIdx.x * 64 + (threadIdx.x & 63);
     const int ry = threadIdx.x >> 6;
@@ -126,17 +134,19 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T *in, int64_
     float s = 0.0f;
     if (c < C)
         for (int r = r_beg + ry; r < r_end; r += 4) {
-            const float v = Lp<T>::to_f(in[(int64_t)r * ld + c]);
-            s += row_w ? row_w[r] * v : v;
+            const int64_t pr = rs.row(r, blockIdx.z);
+            const float v = Lp<T>::to_f(in[pr * ld + c]);
+            s += row_w ? row_w[pr] * v : v;
         }
     red[ry][threadIdx.x & 63] = s;
     __syncthreads();
-    if (ry == 0 && c < C) partial[(int64_t)blockIdx.y * C + c] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+    if (ry == 0 && c < C)
+        partial[((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * C + c] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
 }
 // 16-bit types, 8 columns (one 16-byte load) per thread: a wavefront reads 1 KB of a row at once
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_partial_vec_kernel(const T *in, int64_t ld, int R, int C, const float *row_w,
-                                                                 float *partial) {
+                                                                 float *partial, RowSeg rs) {
     __shared__ float red[4][64][9];
     const int lane = threadIdx.x & 63, ry = threadIdx.x >> 6;
     const int c = blockIdx.x * 512 + lane * 8;
@@ -145,10 +155,11 @@ __global__ __launch_bounds__(256) void colsum_partial_vec_kernel(const T *in, in
     if (c < C)
 #pragma unroll 4
         for (int r = r_beg + ry; r < r_end; r += 4) {
-            const u32x4 raw = *reinterpret_cast<const u32x4 *>(in + (int64_t)r * ld + c);
+            const int64_t pr = rs.row(r, blockIdx.z);
+            const u32x4 raw = *reinterpret_cast<const u32x4 *>(in + pr * ld + c);
             T v[8];
             __builtin_memcpy(v, &raw, 16);
-            const float w = row_w ? row_w[r] : 1.0f;
+            const float w = row_w ? row_w[pr] : 1.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) s[e] += row_w ? w * Lp<T>::to_f(v[e]) : Lp<T>::to_f(v[e]);
         }
@@ -158,17 +169,18 @@ __global__ __launch_bounds__(256) void colsum_partial_vec_kernel(const T *in, in
     for (int i = threadIdx.x; i < 512; i += 256) {
         const int l = i >> 3, e = i & 7;
         if (blockIdx.x * 512 + i < C)
-            partial[(int64_t)blockIdx.y * C + blockIdx.x * 512 + i] = (red[0][l][e] + red[1][l][e]) + (red[2][l][e] + red[3][l][e]);
+            partial[((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * C + blockIdx.x * 512 + i] =
+                (red[0][l][e] + red[1][l][e]) + (red[2][l][e] + red[3][l][e]);
     }
 }
 template <typename T>
-__global__ void colsum_final_kernel(const float *partial, int chunks, int C, const float *scale_dev, T *out) {
+__global__ void colsum_final_kernel(const float *partial, int chunks, int C, const float *scale_dev, T *out, int64_t out_stride) {
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= C) return;
     float s = 0.0f;
-    for (int k = 0; k < chunks; ++k) s += partial[(int64_t)k * C + c];
+    for (int k = 0; k < chunks; ++k) s += partial[((int64_t)blockIdx.y * chunks + k) * C + c];
     if (scale_dev) s *= *scale_dev;
-    out[c] = Lp<T>::from_f(s);
+    out[blockIdx.y * out_stride + c] = Lp<T>::from_f(s);
 }
 
 __device__ inline float wave_sum(float v) {
@@ -217,17 +229,20 @@ __global__ __launch_bounds__(256) void head_forward_kernel(int head, const T *h_
     __syncthreads();
     if (threadIdx.x == 0) partial[blockIdx.x] = (wl[0] + wl[1]) + (wl[2] + wl[3]);
 }
-__global__ __launch_bounds__(256) void loss_final_kernel(const float *partial, int n, float inv_M, float *loss) {
+// one workgroup per worker: partial sum i covers rows 4i..4i+3, all of one worker (seg % 4 == 0
+// whenever there are several)
+__global__ __launch_bounds__(256) void loss_final_kernel(const float *partial, int n, float inv_M, float *loss, RowSeg rs) {
     __shared__ double red[256];
     double s = 0.0;
-    for (int i = threadIdx.x; i < n; i += 256) s += (double)partial[i];
+    for (int i = threadIdx.x; i < n; i += 256)
+        if (rs.workers == 1 || (4 * i % (rs.workers * rs.seg)) / rs.seg == (int)blockIdx.x) s += (double)partial[i];
     red[threadIdx.x] = s;
     __syncthreads();
     for (int o = 128; o > 0; o >>= 1) {
         if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
         __syncthreads();
     }
-    if (threadIdx.x == 0) *loss = (float)(red[0] * (double)inv_M);
+    if (threadIdx.x == 0) loss[blockIdx.x] = (float)(red[0] * (double)inv_M);
 }
 
 // relu_of: when given, the output is the derivative through a ReLU whose result relu_of holds
@@ -252,17 +267,18 @@ __global__ void relu_inplace_kernel(T *a, int64_t n) {
     }
 }
 template <typename T>
-__global__ __launch_bounds__(256) void head_backward_bias_kernel(const float *dzu, const float *scale_dev, int rows, T *out) {
+__global__ __launch_bounds__(256) void head_backward_bias_kernel(const float *dzu, const float *scale_dev, int rows, T *out,
+                                                                 RowSeg rs, int64_t out_stride) {
     __shared__ double red[256];
     double s = 0.0;
-    for (int i = threadIdx.x; i < rows; i += 256) s += (double)dzu[i];
+    for (int i = threadIdx.x; i < rows; i += 256) s += (double)dzu[rs.row(i, blockIdx.x)];
     red[threadIdx.x] = s;
     __syncthreads();
     for (int o = 128; o > 0; o >>= 1) {
         if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
         __syncthreads();
     }
-    if (threadIdx.x == 0) out[0] = Lp<T>::from_f((float)(red[0] * (double)(*scale_dev)));
+    if (threadIdx.x == 0) out[blockIdx.x * out_stride] = Lp<T>::from_f((float)(red[0] * (double)(*scale_dev)));
 }
 
 template <typename T>
@@ -356,12 +372,13 @@ int transpose_lp(int dtype, const void *in, int64_t ld_in, void *out, int64_t ld
 int colsum_chunks(int R) { return R <= 0 ? 1 : (R + CS_ROWS - 1) / CS_ROWS; }
 
 int colsum(int dtype, const void *in, int64_t ld, int R, int C, const float *row_w, const float *scale_dev,
-           float *partial, void *out_lp, hipStream_t s) {
+           float *partial, void *out_lp, hipStream_t s, int workers, int seg, int64_t out_stride) {
     KernelTimer timer(KC_AUX, s, 0.0, 0.0);
     if (C <= 0) return LSTM_OK;
     const int chunks = colsum_chunks(R);
-    dim3 grid((C + 63) / 64, chunks);
-    if (grid.y > 65535u) {
+    const RowSeg rs{workers, workers > 1 ? seg : (R > 0 ? R : 1)};
+    dim3 grid((C + 63) / 64, chunks, workers);
+    if (grid.y > 65535u || workers > 65535 || workers < 1 || rs.seg < 1) {
         set_error("colsum: too many rows %d", R);
         return LSTM_ERR_UNSUPPORTED;
     }
@@ -369,11 +386,12 @@ int colsum(int dtype, const void *in, int64_t ld, int R, int C, const float *row
     LSTM_DISPATCH(dtype, T, {
         if constexpr (sizeof(T) == 2) {
             if (vec)
-                hipLaunchKernelGGL(colsum_partial_vec_kernel<T>, dim3((C + 511) / 512, chunks), dim3(256), 0, s, (const T *)in, ld,
-                                   R, C, row_w, partial);
+                hipLaunchKernelGGL(colsum_partial_vec_kernel<T>, dim3((C + 511) / 512, chunks, workers), dim3(256), 0, s,
+                                   (const T *)in, ld, R, C, row_w, partial, rs);
         }
-        if (!vec) hipLaunchKernelGGL(colsum_partial_kernel<T>, grid, dim3(256), 0, s, (const T *)in, ld, R, C, row_w, partial);
-        hipLaunchKernelGGL(colsum_final_kernel<T>, dim3((C + 255) / 256), dim3(256), 0, s, partial, chunks, C, scale_dev, (T *)out_lp);
+        if (!vec) hipLaunchKernelGGL(colsum_partial_kernel<T>, grid, dim3(256), 0, s, (const T *)in, ld, R, C, row_w, partial, rs);
+        hipLaunchKernelGGL(colsum_final_kernel<T>, dim3((C + 255) / 256, workers), dim3(256), 0, s, partial, chunks, C, scale_dev,
+                           (T *)out_lp, out_stride);
     });
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
@@ -382,14 +400,15 @@ int colsum(int dtype, const void *in, int64_t ld, int R, int C, const float *row
 int head_loss_blocks(int rows) { return rows <= 0 ? 1 : (rows + 3) / 4; }
 
 int head_forward(int dtype, int head, const void *h_top, const void *w, const void *b, const float *targets, int rows,
-                 int H, int M_total, float *dzu, float *partial, float *loss, hipStream_t s) {
+                 int H, int M_total, float *dzu, float *partial, float *loss, hipStream_t s, int workers, int seg) {
     KernelTimer timer(KC_AUX, s, 0.0, 0.0);
     const int nb = head_loss_blocks(rows);
     const float inv_M = 1.0f / (float)M_total;
+    const RowSeg rs{workers, workers > 1 ? seg : 1};
     LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(head_forward_kernel<T>, dim3(nb), dim3(256), 0, s, head, (const T *)h_top,
                                                (const T *)w, (const T *)b, targets, rows, H, inv_M, dzu, partial));
     LSTM_LAUNCH_CHECK();
-    hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(256), 0, s, partial, nb, inv_M, loss);
+    hipLaunchKernelGGL(loss_final_kernel, dim3(workers), dim3(256), 0, s, partial, nb, inv_M, loss, rs);
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
@@ -412,9 +431,12 @@ int relu_inplace(int dtype, void *a, int64_t n, hipStream_t s) {
     return LSTM_OK;
 }
 
-int head_backward_bias(int dtype, const float *dzu, const float *scale_dev, int rows, void *out_lp, hipStream_t s) {
+int head_backward_bias(int dtype, const float *dzu, const float *scale_dev, int rows, void *out_lp, hipStream_t s, int workers,
+                       int seg, int64_t out_stride) {
     KernelTimer timer(KC_AUX, s, 0.0, 0.0);
-    LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(head_backward_bias_kernel<T>, dim3(1), dim3(256), 0, s, dzu, scale_dev, rows, (T *)out_lp));
+    const RowSeg rs{workers, workers > 1 ? seg : (rows > 0 ? rows : 1)};
+    LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(head_backward_bias_kernel<T>, dim3(workers), dim3(256), 0, s, dzu, scale_dev, rows,
+                                               (T *)out_lp, rs, out_stride));
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }

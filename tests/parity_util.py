@@ -69,17 +69,18 @@ def device_batches(w: wl.Workload, xs, ys, lp_dtype, dev):
     return dx, dy
 
 
-def make_step(w: wl.Workload, master0, dev="cuda:0"):
+def make_step(w: wl.Workload, master0, dev="cuda:0", n_streams=1, batched=False):
     import paper_1912_00286_amd as hip
-    return hip.TrainingStep(make_cfg(w), make_opt(w), w.n_workers, master0, w.loss_scale, dev)
+    return hip.TrainingStep(make_cfg(w), make_opt(w), w.n_workers, master0, w.loss_scale, dev, n_streams=n_streams,
+                            batched=batched)
 
 
-def run_gpu_step(w: wl.Workload, max_retries: int = 20):
+def run_gpu_step(w: wl.Workload, max_retries: int = 20, batched: bool = False):
     """One training iteration on the HIP path (retrying after overflow when the
     loss scale is dynamic).  Returns host copies of everything comparable."""
     import torch
     master0, xs, ys = inputs_for(w)
-    ts = make_step(w, master0)
+    ts = make_step(w, master0, batched=batched)
     dx, dy = device_batches(w, xs, ys, ts.lp_dtype, ts.dev)
     lr = lr_for(w, 0)
     scales, flags = [], []

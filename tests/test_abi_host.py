@@ -41,7 +41,7 @@ def test_header_symbols_are_exported(hip):
     lib = hip.load_library()
     for n in names:
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
-    assert hip.lstm_abi_version() == 2
+    assert hip.lstm_abi_version() == 3
 
 
 def _cfg(hip, w):

@@ -59,6 +59,29 @@ def test_graph_replay_matches_eager(name):
     assert graph.step_index == n_steps
 
 
+@pytest.mark.parametrize("captured", [False, True])
+def test_workers_on_several_streams_match_one_stream(captured):
+    """Five simulated workers spread over three streams (each with its own workspace) give
+    bit for bit what one stream gives, eagerly and as a captured fork-join graph."""
+    import torch
+    w = wl.CONFIGS["jet"].with_(seq_len=12, n_workers=5, dynamic_scale=True, loss_scale=2048.0)
+    master0, xs, ys = pu.inputs_for(w)
+    one = pu.make_step(w, master0)
+    dx, dy = pu.device_batches(w, xs, ys, one.lp_dtype, one.dev)
+    many = pu.make_step(w, master0, n_streams=3)
+    assert many.n_streams == 3 and len(many.side_streams) == 2
+    if captured:
+        many.capture(dx, dy)
+    for k in range(3):
+        lr = pu.lr_for(w, k)
+        one.step(dx, dy, lr)
+        if captured:
+            many.step_captured(lr)
+        else:
+            many.step(dx, dy, lr)
+        _assert_same(_snapshot(one), _snapshot(many), f"step {k}")
+
+
 def test_step_captured_requires_capture():
     w = wl.CONFIGS["tiny"]
     master0, xs, ys = pu.inputs_for(w)
