@@ -288,7 +288,8 @@ __device__ __forceinline__ void big_epilogue(const KernArgs &a, BigSmem &sm, v16
 //      multiple of 64).  A K tile of an operand is then four contiguous 8 KB blocks instead of 256
 //      row segments of 128 bytes, which is what the L2 -> CU path streams at full rate.
 // PP:  steady state in the ping-pong slot schedule (below) instead of the plain two-stage loop.
-template <typename T, bool TA, bool TB_, bool BLK, bool PP>
+// SEG: a batch of products (blockIdx.y) whose K rows interleave in memory (see KernArgs::seg_len).
+template <typename T, bool TA, bool TB_, bool BLK, bool PP, bool SEG = false>
 __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a_in, int tiles_m, int tiles_n) {
     constexpr int GNV = GBM * GBK / 8 / GTHREADS;  // 16-byte vectors per thread, operand and K tile (4)
     constexpr int MI = 2;                          // 32-row MFMA blocks per wavefront
@@ -296,20 +297,17 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a_in, 
     KernArgs a = a_in;
     const T *A = reinterpret_cast<const T *>(a.A);
     const T *B = reinterpret_cast<const T *>(a.B);
-    if constexpr (BLK && TA && TB_) {
+    if constexpr (SEG) {
         // batch entry blockIdx.y: its K rows start seg_len block rows further on in both operands
-        if (a.seg_len > 0) {
-            const int64_t y = blockIdx.y;
-            A += y * a.seg_len * a.lda * 4096;
-            B += y * a.seg_len * a.ldb * 4096;
-            a.C = reinterpret_cast<char *>(a.C) + y * a.batch_c * (a.out_lp ? (int64_t)sizeof(T) : 4);
-        }
+        static_assert(!SEG || (BLK && TA && TB_), "segmented K only for blocked operands in the rows-are-K role");
+        const int64_t y = blockIdx.y;
+        A += y * a.seg_len * a.lda * 4096;
+        B += y * a.seg_len * a.ldb * 4096;
+        a.C = reinterpret_cast<char *>(a.C) + y * a.batch_c * (a.out_lp ? (int64_t)sizeof(T) : 4);
     }
     // K tile -> block row of a "rows are K" blocked operand
     auto krow = [&](int tile) -> uint32_t {
-        if constexpr (BLK && TA && TB_) {
-            if (a.seg_len > 0) return (uint32_t)((tile / a.seg_len) * a.seg_stride + tile % a.seg_len);
-        }
+        if constexpr (SEG) return (uint32_t)((tile / a.seg_len) * a.seg_stride + tile % a.seg_len);
         return (uint32_t)tile;
     };
     const int tid = threadIdx.x;
@@ -768,6 +766,8 @@ int launch_blocked(const BlockedGemmArgs &g, hipStream_t stream) {
         hipLaunchKernelGGL((gemm_mfma_big_kernel<T, false, false, true, true>), grid, dim3(GTHREADS), 0, stream, a, tiles_m, tiles_n);
     else if (!g.A.trans && g.B.trans)
         hipLaunchKernelGGL((gemm_mfma_big_kernel<T, false, true, true, true>), grid, dim3(GTHREADS), 0, stream, a, tiles_m, tiles_n);
+    else if (g.A.trans && g.B.trans && a.seg_len > 0)
+        hipLaunchKernelGGL((gemm_mfma_big_kernel<T, true, true, true, true, true>), grid, dim3(GTHREADS), 0, stream, a, tiles_m, tiles_n);
     else if (g.A.trans && g.B.trans)
         hipLaunchKernelGGL((gemm_mfma_big_kernel<T, true, true, true, true>), grid, dim3(GTHREADS), 0, stream, a, tiles_m, tiles_n);
     else {

@@ -155,68 +155,97 @@ struct FwdArgs {
     int B, H, n_mt, nkc;
 };
 
-template <typename T>
+// WIDE = false: the four wavefronts split the K range of one 64-row tile and their partial
+//                accumulators are summed through LDS (large H: operand bytes per CU are what counts).
+// WIDE = true : workgroups of one wavefront, each with a 64-row tile of its own over the whole K
+//                range; no LDS, no reduction (small H with many batch rows, where the reduction
+//                would cost more than the product); several such wavefronts share a SIMD and
+//                hide each other's latencies.
+template <typename T, bool WIDE>
 __global__ __launch_bounds__(256) void lstm_step_forward_kernel(FwdArgs a) {
-    __shared__ __attribute__((aligned(16))) float smem[4 * RED_FLOATS];   // 128 KB: cross-wavefront reduction
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tile = xcd_swizzle(blockIdx.x, gridDim.x);
     const int mt = tile % a.n_mt, hb = tile / a.n_mt;
     const int m0 = mt * TM, j0 = hb * 32;
     const int H = a.H, G = 4 * a.H;
     const int cpw = (a.nkc + 3) / 4;                       // chunks per wavefront
-    const int c0 = min(a.nkc, wave * cpw), c1 = min(a.nkc, c0 + cpw);
+    const int c0 = WIDE ? 0 : min(a.nkc, wave * cpw), c1 = WIDE ? a.nkc : min(a.nkc, c0 + cpw);
     v16f acc[2][NBLK];
     zero_acc(acc);
     packed_mainloop<T>(reinterpret_cast<const uint16_t *>(a.hpk_prev) + (int64_t)mt * a.nkc * A_CHUNK,
                        reinterpret_cast<const uint16_t *>(a.Upk) + (int64_t)hb * a.nkc * B_CHUNK, c0, c1, (int)blockIdx.x,
                        lane, acc);
-    // The step's input projection and the previous cell state do not depend on the GEMM:
-    // request them before the cross-wavefront reduction so that their latency hides behind
-    // it.  Addresses are clamped into the tensors; out-of-range lanes never store.
-    const int mb = wave >> 1, rh = (wave & 1) * 8;
     const int j = j0 + (lane & 31);
     const int jc = min(j, H - 1);
-    float axv[8][4], cprev[8];
-#pragma unroll
-    for (int rr = 0; rr < 8; ++rr) {
-        const int r = rh + rr;
-        const int row = min(m0 + mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), a.B - 1);
-        const T *ax = reinterpret_cast<const T *>(a.Ax) + (int64_t)row * G + jc;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) axv[rr][g] = Lp<T>::to_f(ax[g * H]);
-        cprev[rr] = a.c_state[(int64_t)row * H + jc];
-    }
-    float pre[8][NBLK];
-    reduce_waves(smem, wave, lane, acc, pre);
-    if (j >= H) return;
     T *gates = reinterpret_cast<T *>(a.gates);
     T *c_out = reinterpret_cast<T *>(a.c_out);
     T *h_out = reinterpret_cast<T *>(a.h_out);
-    T *hpk = reinterpret_cast<T *>(a.hpk_next) + ((int64_t)mt * a.nkc + (j >> 6)) * A_CHUNK;
+    T *hpk = reinterpret_cast<T *>(a.hpk_next) + ((int64_t)mt * a.nkc + (min(j, H - 1) >> 6)) * A_CHUNK;
+    // The step's input projection and the previous cell state do not depend on the GEMM: a
+    // group of 8 accumulator rows requests them first (addresses clamped into the tensors;
+    // out-of-range lanes never store) and consumes them after the pre-activations are ready.
+    auto load_group = [&](int mb, int rh, float (&axv)[8][4], float (&cprev)[8]) {
 #pragma unroll
-    for (int rr = 0; rr < 8; ++rr) {
-        const int r = rh + rr;
-        const int rl = mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        const int row = m0 + rl;
-        const float gi = sigmoidf_dev(pre[rr][0] + axv[rr][0]);
-        const float gf = sigmoidf_dev(pre[rr][1] + axv[rr][1]);
-        const float gg = tanhf_dev(pre[rr][2] + axv[rr][2]);
-        const float go = sigmoidf_dev(pre[rr][3] + axv[rr][3]);
-        const float c = gf * cprev[rr] + gi * gg;
-        const T h = Lp<T>::from_f(go * tanhf_dev(c));
-        if (row >= a.B) continue;
-        const int64_t e = (int64_t)row * H + j;
-        a.c_state[e] = c;
-        T *gr = gates + (int64_t)row * G + j;
-        gr[0] = Lp<T>::from_f(gi);
-        gr[H] = Lp<T>::from_f(gf);
-        gr[2 * H] = Lp<T>::from_f(gg);
-        gr[3 * H] = Lp<T>::from_f(go);
-        c_out[e] = Lp<T>::from_f(c);
-        h_out[e] = h;
-        hpk[frag_offset(rl, j & 63, 2)] = h;
-        if (a.h_blk)
-            reinterpret_cast<T *>(a.h_blk)[((int64_t)(row >> 6) * a.blk_ncb + (j >> 6)) * 4096 + (row & 63) * 64 + (j & 63)] = h;
+        for (int rr = 0; rr < 8; ++rr) {
+            const int r = rh + rr;
+            const int row = min(m0 + mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), a.B - 1);
+            const T *ax = reinterpret_cast<const T *>(a.Ax) + (int64_t)row * G + jc;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) axv[rr][g] = Lp<T>::to_f(ax[g * H]);
+            cprev[rr] = a.c_state[(int64_t)row * H + jc];
+        }
+    };
+    auto finish_group = [&](int mb, int rh, const float (&pre)[8][NBLK], const float (&axv)[8][4], const float (&cprev)[8]) {
+        if (j >= H) return;
+#pragma unroll
+        for (int rr = 0; rr < 8; ++rr) {
+            const int r = rh + rr;
+            const int rl = mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+            const int row = m0 + rl;
+            const float gi = sigmoidf_dev(pre[rr][0] + axv[rr][0]);
+            const float gf = sigmoidf_dev(pre[rr][1] + axv[rr][1]);
+            const float gg = tanhf_dev(pre[rr][2] + axv[rr][2]);
+            const float go = sigmoidf_dev(pre[rr][3] + axv[rr][3]);
+            const float c = gf * cprev[rr] + gi * gg;
+            const T h = Lp<T>::from_f(go * tanhf_dev(c));
+            if (row >= a.B) continue;
+            const int64_t e = (int64_t)row * H + j;
+            a.c_state[e] = c;
+            T *gr = gates + (int64_t)row * G + j;
+            gr[0] = Lp<T>::from_f(gi);
+            gr[H] = Lp<T>::from_f(gf);
+            gr[2 * H] = Lp<T>::from_f(gg);
+            gr[3 * H] = Lp<T>::from_f(go);
+            c_out[e] = Lp<T>::from_f(c);
+            h_out[e] = h;
+            hpk[frag_offset(rl, j & 63, 2)] = h;
+            if (a.h_blk)
+                reinterpret_cast<T *>(a.h_blk)[((int64_t)(row >> 6) * a.blk_ncb + (j >> 6)) * 4096 + (row & 63) * 64 + (j & 63)] = h;
+        }
+    };
+    if constexpr (WIDE) {
+        // four groups of 8 accumulator rows; the loads of the next group are in flight while
+        // the current one is finished
+        float axv[2][8][4], cprev[2][8];
+        load_group(0, 0, axv[0], cprev[0]);
+#pragma unroll
+        for (int grp = 0; grp < 4; ++grp) {
+            const int mb = grp >> 1, rh = (grp & 1) * 8;
+            if (grp < 3) load_group((grp + 1) >> 1, ((grp + 1) & 1) * 8, axv[(grp + 1) & 1], cprev[(grp + 1) & 1]);
+            float pre[8][NBLK];
+#pragma unroll
+            for (int rr = 0; rr < 8; ++rr)
+#pragma unroll
+                for (int nb = 0; nb < NBLK; ++nb) pre[rr][nb] = acc[mb][nb][rh + rr];
+            finish_group(mb, rh, pre, axv[grp & 1], cprev[grp & 1]);
+        }
+    } else {
+        __shared__ __attribute__((aligned(16))) float smem[4 * RED_FLOATS];   // 128 KB: cross-wavefront reduction
+        const int mb = wave >> 1, rh = (wave & 1) * 8;
+        float axv[8][4], cprev[8], pre[8][NBLK];
+        load_group(mb, rh, axv, cprev);                    // in flight during the reduction
+        reduce_waves(smem, wave, lane, acc, pre);
+        finish_group(mb, rh, pre, axv, cprev);
     }
 }
 
@@ -229,9 +258,8 @@ struct BwdArgs {
 };
 
 // partial[q][b, j] = sum over the rows k of gate q of dA_next[b, k] * U[k, j]
-template <typename T>
+template <typename T, bool WIDE>
 __global__ __launch_bounds__(256) void lstm_step_backward_gemm_kernel(BwdArgs a) {
-    __shared__ __attribute__((aligned(16))) float smem[4 * RED_FLOATS];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lin = xcd_swizzle(blockIdx.x, gridDim.x);
     // gate-slice major: the workgroups of one XCD share one K slice, so that XCD's L2 pulls
@@ -242,26 +270,42 @@ __global__ __launch_bounds__(256) void lstm_step_backward_gemm_kernel(BwdArgs a)
     const int m0 = mt * TM, n0 = nt * TN;
     const int H = a.H;
     const int cpw = (a.nkc + 3) / 4;
-    const int c0 = min(a.nkc, wave * cpw), c1 = min(a.nkc, c0 + cpw);
+    const int c0 = WIDE ? 0 : min(a.nkc, wave * cpw), c1 = WIDE ? a.nkc : min(a.nkc, c0 + cpw);
     v16f acc[2][NBLK];
     zero_acc(acc);
     packed_mainloop<T>(reinterpret_cast<const uint16_t *>(a.dApk) + ((int64_t)mt * 4 + q) * a.nkc * A_CHUNK,
                        reinterpret_cast<const uint16_t *>(a.UTpk) + ((int64_t)nt * 4 + q) * a.nkc * B_CHUNK, c0, c1,
                        (int)blockIdx.x, lane, acc);
-    float sum[8][NBLK];
-    reduce_waves(smem, wave, lane, acc, sum);
-    const int mb = wave >> 1, rh = (wave & 1) * 8;
     float *part = a.partials + (int64_t)q * a.B * H;
+    auto store_group = [&](int mb, int rh, const float (&sum)[8][NBLK]) {
 #pragma unroll
-    for (int rr = 0; rr < 8; ++rr) {
-        const int r = rh + rr;
-        const int row = m0 + mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        if (row >= a.B) continue;
+        for (int rr = 0; rr < 8; ++rr) {
+            const int r = rh + rr;
+            const int row = m0 + mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+            if (row >= a.B) continue;
 #pragma unroll
-        for (int nb = 0; nb < NBLK; ++nb) {
-            const int j = n0 + nb * 32 + (lane & 31);
-            if (j < H) part[(int64_t)row * H + j] = sum[rr][nb];
+            for (int nb = 0; nb < NBLK; ++nb) {
+                const int j = n0 + nb * 32 + (lane & 31);
+                if (j < H) part[(int64_t)row * H + j] = sum[rr][nb];
+            }
         }
+    };
+    if constexpr (WIDE) {
+#pragma unroll
+        for (int grp = 0; grp < 4; ++grp) {
+            const int mb = grp >> 1, rh = (grp & 1) * 8;
+            float sum[8][NBLK];
+#pragma unroll
+            for (int rr = 0; rr < 8; ++rr)
+#pragma unroll
+                for (int nb = 0; nb < NBLK; ++nb) sum[rr][nb] = acc[mb][nb][rh + rr];
+            store_group(mb, rh, sum);
+        }
+    } else {
+        __shared__ __attribute__((aligned(16))) float smem[4 * RED_FLOATS];
+        float sum[8][NBLK];
+        reduce_waves(smem, wave, lane, acc, sum);
+        store_group(wave >> 1, (wave & 1) * 8, sum);
     }
 }
 
@@ -421,6 +465,10 @@ RecurrentDims recurrent_dims(int B, int H) {
     return d;
 }
 
+// Few K chunks and many batch tiles: one-wavefront workgroups, one 64-row tile each over the
+// whole K range, instead of a four-way K split with an LDS reduction.
+static bool recurrent_wide(const RecurrentDims &d) { return d.nkc <= 8 && d.n_mt >= 16; }   // H <= 512, B >= 961
+
 #define LP_ONLY(dtype, T, ...)                                                       \
     if (dtype == LSTM_DTYPE_FP16) { using T = _Float16; __VA_ARGS__; }               \
     else if (dtype == LSTM_DTYPE_BF16) { using T = bf16_t; __VA_ARGS__; }            \
@@ -457,12 +505,17 @@ int step_forward_fused(int dtype, const void *hpk_prev, const void *Upk, const v
     a.hpk_prev = hpk_prev; a.Upk = Upk; a.Ax = Ax; a.c_state = c_state; a.gates = gates; a.c_out = c_out; a.h_out = h_out;
     a.hpk_next = hpk_next; a.h_blk = h_blk; a.blk_ncb = blk_ncb;
     a.B = B; a.H = H; a.n_mt = d.n_mt; a.nkc = d.nkc;
+    const bool wide = recurrent_wide(d);
     const int grid = d.n_mt * d.n_hb;
     // operands once: U, h, Ax read, gates, c, h (row-major + packed [+ blocked]) written in storage, cell state fp32 both ways
     const double bh = (double)B * H;
     KernelTimer timer(KC_GEMM_STEP, s, 2.0 * B * 4.0 * H * H,
                       2.0 * (4.0 * H * H + bh + 4.0 * bh) + 4.0 * bh + 2.0 * (4.0 * bh + bh + (h_blk ? 3.0 : 2.0) * bh) + 4.0 * bh);
-    LP_ONLY(dtype, T, hipLaunchKernelGGL(lstm_step_forward_kernel<T>, dim3(grid), dim3(256), 0, s, a));
+    if (wide) {
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_step_forward_kernel<T, true>), dim3(grid), dim3(64), 0, s, a));
+    } else {
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_step_forward_kernel<T, false>), dim3(grid), dim3(256), 0, s, a));
+    }
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
@@ -472,10 +525,15 @@ int step_backward_gemm(int dtype, const void *dApk, const void *UTpk, float *par
     BwdArgs a;
     a.dApk = dApk; a.UTpk = UTpk; a.partials = partials;
     a.B = B; a.H = H; a.n_mt = d.n_mt; a.nkc = d.nkc;
+    const bool wide = recurrent_wide(d);
     const int grid = d.n_mt * d.n_nt * 4;
     // operands once: U^T and dA read in storage, four fp32 partial sums [B,H] written
     KernelTimer timer(KC_GEMM_STEP, s, 2.0 * B * 4.0 * H * H, 2.0 * (4.0 * H * H + 4.0 * (double)B * H) + 16.0 * (double)B * H);
-    LP_ONLY(dtype, T, hipLaunchKernelGGL(lstm_step_backward_gemm_kernel<T>, dim3(grid), dim3(256), 0, s, a));
+    if (wide) {
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_step_backward_gemm_kernel<T, true>), dim3(grid), dim3(64), 0, s, a));
+    } else {
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_step_backward_gemm_kernel<T, false>), dim3(grid), dim3(256), 0, s, a));
+    }
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
