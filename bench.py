@@ -124,6 +124,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="large")
+    ap.add_argument("--dtype", default=None, choices=["fp16", "bf16"],
+                    help="storage type override (bf16: no loss scaling needed, static scale 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streams", type=int, default=0,
                     help="streams the simulated workers are spread over (0: 4 when there are several workers, else 1)")
@@ -157,6 +159,8 @@ def main():
         print(json.dumps({"calibration": "5 device copies", "bytes_read_each": 2 * n, "bytes_written_each": 2 * n}))
         return
     w = wl.CONFIGS[args.workload]
+    if args.dtype and args.dtype != w.dtype:
+        w = w.with_(dtype=args.dtype, **({"loss_scale": 1.0, "dynamic_scale": False} if args.dtype == "bf16" else {}))
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     log(f"[bench] workload {w.name}: L={w.num_layers} H={w.hidden} T={w.seq_len} B={w.batch} N={w.n_workers} {w.dtype}")
