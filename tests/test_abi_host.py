@@ -164,3 +164,20 @@ def test_product_package_does_not_import_the_oracle():
                 assert "oracle" not in text.lower(), f
     otext = open(os.path.join(ROOT, "oracle", "lstm_oracle.py")).read()
     assert "paper_1912_00286_amd" not in otext and "import workloads" not in otext
+
+
+def test_bench_helpers_do_not_load_the_oracle():
+    """bench.py drives the HIP path through tests/parity_util.py; only its CPU-baseline leg may
+    touch the oracle.  Importing the helpers and building a config must not load it."""
+    import subprocess
+    import sys
+    code = ("import sys; sys.path.insert(0, %r); import workloads as wl; from tests import parity_util as pu; "
+            "pu.make_cfg(wl.CONFIGS['jet']); pu.make_opt(wl.CONFIGS['jet']); pu.inputs_for(wl.CONFIGS['tiny']); "
+            "print(any(m == 'oracle' or m.startswith('oracle.') for m in sys.modules))" % ROOT)
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert out.returncode == 0, out.stderr
+    assert out.stdout.strip().splitlines()[-1] == "False"
+    bench = open(os.path.join(ROOT, "bench.py")).read()
+    _, _, tail = bench.partition("def cpu_baseline")
+    # the only import of the oracle in bench.py sits inside cpu_baseline()
+    assert bench.count("from oracle import") == 1 and "from oracle import" in tail.split("\ndef ")[0]
