@@ -47,6 +47,9 @@ struct Plan {
     size_t s_ax = 0, s_cstate = 0, s_losspart = 0;
     size_t s_wT = 0, s_dA = 0, s_dAT = 0, s_xT = 0, s_dh[2] = {0, 0}, s_dhrec = 0, s_dcstate = 0, s_splitk = 0,
            s_colpart = 0, s_dE32 = 0, s_part = 0, s_upk = 0, s_apk[2] = {0, 0}, scratch_bytes = 0;
+    // forward along anti-diagonals (cells of several layers per launch): per-layer operands and state
+    bool wf = false;
+    std::vector<size_t> s_wf_upk, s_wf_wpk, s_wf_c, s_wf_hpk0, s_wf_hpk1;
     std::vector<size_t> wT_off, uT_off;  // byte offsets inside the s_wT region
     std::vector<int> split_w, split_u;
 };
@@ -196,6 +199,22 @@ int make_plan(const lstm_config *c, Plan &p) {
         p.s_wblk = s; s += align_up(blocked_elems(p.G, max_dim) * p.es);
         p.s_dablk = s; s += align_up(blocked_elems((int)TB, p.G) * p.es);
     }
+    if (p.dtype != LSTM_DTYPE_FP32 && p.L >= 2) {
+        // Stacks of narrow layers: a time step of one layer is a handful of workgroups, so the
+        // forward pass runs along anti-diagonals (all layers' ready cells in one launch).
+        const RecurrentDims rd = recurrent_dims(p.B, p.H);
+        p.wf = rd.n_mt * rd.n_hb <= 128;
+        if (p.wf) {
+            p.s_wf_upk.resize(p.L); p.s_wf_wpk.assign(p.L, 0); p.s_wf_c.resize(p.L); p.s_wf_hpk0.resize(p.L); p.s_wf_hpk1.resize(p.L);
+            for (int l = 0; l < p.L; ++l) {
+                p.s_wf_upk[l] = s; s += align_up(rd.upk_elems * p.es);
+                if (l > 0) { p.s_wf_wpk[l] = s; s += align_up(rd.upk_elems * p.es); }
+                p.s_wf_hpk0[l] = s; s += align_up(rd.hpk_elems * p.es);
+                p.s_wf_hpk1[l] = s; s += align_up(rd.hpk_elems * p.es);
+                p.s_wf_c[l] = s; s += align_up((size_t)p.B * p.H * 4);
+            }
+        }
+    }
     p.scratch_bytes = s;
     if (p.W > 1 && !p.blk) {
         set_error("config: workers=%d needs shapes the blocked GEMM path handles (T*W*B >= 192, 4H >= 192)", p.W);
@@ -327,14 +346,17 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
     char *ax = at(scratch, p.s_ax);
     const bool fused = p.dtype != LSTM_DTYPE_FP32;
     const size_t axs = fused ? es : 4;
-    float *c_state = (float *)at(scratch, p.s_cstate);
     for (int l = 0; l < p.L; ++l) {
         const void *W = par + p.off_W[l] * es, *U = par + p.off_U[l] * es, *b = par + p.off_b[l] * es;
         char *gates = at(reserve, p.r_gates[l]);
         char *cs = at(reserve, p.r_c[l]);
         char *hs = at(reserve, p.r_h[l]);
-        // input projection of the whole sequence: Ax = X W^T + b
-        if (p.blk) {
+        float *c_state = (float *)at(scratch, p.wf ? p.s_wf_c[l] : p.s_cstate);
+        // input projection of the whole sequence: Ax = X W^T + b  (along the anti-diagonals only
+        // layer 0 has its input ahead of time; the layers above project inside their step kernels)
+        if (p.wf && l > 0) {
+            LSTM_TRY(pack_u_forward(p.dtype, W, at(scratch, p.s_wf_wpk[l]), p.H, s));
+        } else if (p.blk) {
             // operands in 64x64 blocks: layer 0 packs the input once, upper layers read the blocked
             // hidden sequence the step kernels of the layer below wrote
             char *wblk = at(scratch, p.s_wblk);
@@ -362,8 +384,8 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
         }
         LSTM_TRY(init_state(p.dtype, h0 ? at(h0, (size_t)l * BH * es) : nullptr, c0 ? c0 + l * BH : nullptr, hs, cs,
                             c_state, BH, s));
-        char *upk = at(scratch, p.s_upk);
-        char *hpk[2] = {at(scratch, p.s_apk[0]), at(scratch, p.s_apk[1])};
+        char *upk = at(scratch, p.wf ? p.s_wf_upk[l] : p.s_upk);
+        char *hpk[2] = {at(scratch, p.wf ? p.s_wf_hpk0[l] : p.s_apk[0]), at(scratch, p.wf ? p.s_wf_hpk1[l] : p.s_apk[1])};
         if (fused) {
             // recurrent weights and the initial hidden state in packed tile order; the second
             // packed-h buffer only needs its zero padding
@@ -379,6 +401,7 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
             if (h0) LSTM_TRY(pack_blocked(p.dtype, at(h0, (size_t)l * BH * es), p.H, p.B, p.H, hblk, s));
             else if (p.H % 64 == 0) LSTM_TRY(fill_u32(hblk, 0, (int64_t)(slot / 4), s));
         }
+        if (p.wf) continue;                                   // the time steps follow below, diagonal by diagonal
         for (int t = 0; t < p.T; ++t) {
             char *a_t = ax + (size_t)t * p.B * p.G * axs;
             if (fused) {
@@ -403,6 +426,45 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
         LSTM_TRY(copy_state(p.dtype, hs + (size_t)p.T * BH * es, c_state, hT ? at(hT, (size_t)l * BH * es) : nullptr,
                             cT ? cT + l * BH : nullptr, BH, s));
         layer_in = hs + (size_t)BH * es;   // h_1..h_T feed the next layer
+    }
+    if (p.wf) {
+        // cell (l, t) needs (l, t-1) and (l-1, t): all cells with l + t = d are independent
+        const int max_cells = wave_forward_max_cells();
+        const size_t slot = p.blk ? (size_t)(p.B / 64) * p.h_ncb * 4096 * es : 0;
+        std::vector<WaveCell> cells;
+        for (int d = 0; d < p.T + p.L - 1; ++d) {
+            cells.clear();
+            for (int l = 0; l < p.L; ++l) {
+                const int t = d - l;
+                if (t < 0 || t >= p.T) continue;
+                char *hpk[2] = {at(scratch, p.s_wf_hpk0[l]), at(scratch, p.s_wf_hpk1[l])};
+                WaveCell c{};
+                c.hpk_prev = hpk[t & 1]; c.hpk_next = hpk[(t + 1) & 1];
+                c.Upk = at(scratch, p.s_wf_upk[l]);
+                if (l == 0) {
+                    c.Ax = ax + (size_t)t * p.B * p.G * axs;
+                } else {
+                    // packed h_t of the layer below: written one launch ago into its buffer (t + 1) % 2
+                    c.xpk = at(scratch, ((t + 1) & 1) ? p.s_wf_hpk1[l - 1] : p.s_wf_hpk0[l - 1]);
+                    c.Wpk = at(scratch, p.s_wf_wpk[l]);
+                    c.bias = par + p.off_b[l] * es;
+                }
+                c.c_state = (float *)at(scratch, p.s_wf_c[l]);
+                c.gates = at(reserve, p.r_gates[l]) + (size_t)t * p.B * p.G * es;
+                c.c_out = at(reserve, p.r_c[l]) + (size_t)(t + 1) * BH * es;
+                c.h_out = at(reserve, p.r_h[l]) + (size_t)(t + 1) * BH * es;
+                c.h_blk = p.blk ? at(reserve, p.r_hblk[l]) + (size_t)(t + 1) * slot : nullptr;
+                cells.push_back(c);
+                if ((int)cells.size() == max_cells) {
+                    LSTM_TRY(step_forward_wave(p.dtype, cells.data(), (int)cells.size(), p.h_ncb, p.B, p.H, s));
+                    cells.clear();
+                }
+            }
+            if (!cells.empty()) LSTM_TRY(step_forward_wave(p.dtype, cells.data(), (int)cells.size(), p.h_ncb, p.B, p.H, s));
+        }
+        for (int l = 0; l < p.L; ++l)
+            LSTM_TRY(copy_state(p.dtype, at(reserve, p.r_h[l]) + (size_t)p.T * BH * es, (const float *)at(scratch, p.s_wf_c[l]),
+                                hT ? at(hT, (size_t)l * BH * es) : nullptr, cT ? cT + l * BH : nullptr, BH, s));
     }
     // head + loss on the top layer's outputs
     const char *top = at(reserve, p.r_h[p.L - 1]) + (size_t)BH * es;

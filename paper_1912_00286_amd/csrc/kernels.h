@@ -84,4 +84,15 @@ int gates_backward_packed(int dtype, const void *dh_above, const float *partials
                           const void *c_prev, float *dc_state, void *dA, void *dApk, void *dAblk, int blk_ncb, int B, int H,
                           int first, hipStream_t s);
 
+// Up to wave_forward_max_cells() independent (layer, time) cells in one launch.  A cell either
+// takes its input projection ready-made (Ax) or computes it from the packed h_t of the layer
+// below (xpk), W packed like U (Wpk) and the bias.
+struct WaveCell {
+    const void *hpk_prev, *Upk, *Ax, *xpk, *Wpk, *bias;
+    float *c_state;
+    void *gates, *c_out, *h_out, *hpk_next, *h_blk;
+};
+int wave_forward_max_cells();
+int step_forward_wave(int dtype, const WaveCell *cells, int n_cells, int blk_ncb, int B, int H, hipStream_t s);
+
 }  // namespace lstm

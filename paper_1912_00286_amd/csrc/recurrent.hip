@@ -144,7 +144,10 @@ __device__ __forceinline__ void zero_acc(v16f (&acc)[2][NBLK]) {
 struct FwdArgs {
     const void *hpk_prev;  // packed h_{t-1}: [n_mt][nkc][64][64]
     const void *Upk;       // packed U: [n_hb][nkc][128][64]
-    const void *Ax;        // lp [B,4H], input projection + bias of this step
+    const void *Ax;        // lp [B,4H], input projection + bias of this step; null: computed here from xpk, Wpk, bias
+    const void *xpk;       // packed input of this step (the layer below's h_t), same layout as hpk_prev
+    const void *Wpk;       // packed W, same layout as Upk (input width = H)
+    const void *bias;      // lp [4H]
     float *c_state;        // fp32 [B,H] in/out
     void *gates;           // lp [B,4H] out
     void *c_out;           // lp [B,H] out
@@ -162,9 +165,8 @@ struct FwdArgs {
 //                would cost more than the product); several such wavefronts share a SIMD and
 //                hide each other's latencies.
 template <typename T, bool WIDE>
-__global__ __launch_bounds__(256) void lstm_step_forward_kernel(FwdArgs a) {
+__device__ __forceinline__ void forward_cell(const FwdArgs &a, int tile, int rot) {
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int tile = xcd_swizzle(blockIdx.x, gridDim.x);
     const int mt = tile % a.n_mt, hb = tile / a.n_mt;
     const int m0 = mt * TM, j0 = hb * 32;
     const int H = a.H, G = 4 * a.H;
@@ -173,8 +175,10 @@ __global__ __launch_bounds__(256) void lstm_step_forward_kernel(FwdArgs a) {
     v16f acc[2][NBLK];
     zero_acc(acc);
     packed_mainloop<T>(reinterpret_cast<const uint16_t *>(a.hpk_prev) + (int64_t)mt * a.nkc * A_CHUNK,
-                       reinterpret_cast<const uint16_t *>(a.Upk) + (int64_t)hb * a.nkc * B_CHUNK, c0, c1, (int)blockIdx.x,
-                       lane, acc);
+                       reinterpret_cast<const uint16_t *>(a.Upk) + (int64_t)hb * a.nkc * B_CHUNK, c0, c1, rot, lane, acc);
+    if (!a.Ax)   // the input projection of this step: the layer below's h_t times W^T, same tiling
+        packed_mainloop<T>(reinterpret_cast<const uint16_t *>(a.xpk) + (int64_t)mt * a.nkc * A_CHUNK,
+                           reinterpret_cast<const uint16_t *>(a.Wpk) + (int64_t)hb * a.nkc * B_CHUNK, c0, c1, rot, lane, acc);
     const int j = j0 + (lane & 31);
     const int jc = min(j, H - 1);
     T *gates = reinterpret_cast<T *>(a.gates);
@@ -189,7 +193,8 @@ __global__ __launch_bounds__(256) void lstm_step_forward_kernel(FwdArgs a) {
         for (int rr = 0; rr < 8; ++rr) {
             const int r = rh + rr;
             const int row = min(m0 + mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), a.B - 1);
-            const T *ax = reinterpret_cast<const T *>(a.Ax) + (int64_t)row * G + jc;
+            // with the projection done above only the bias is left to add
+            const T *ax = a.Ax ? reinterpret_cast<const T *>(a.Ax) + (int64_t)row * G + jc : reinterpret_cast<const T *>(a.bias) + jc;
 #pragma unroll
             for (int g = 0; g < 4; ++g) axv[rr][g] = Lp<T>::to_f(ax[g * H]);
             cprev[rr] = a.c_state[(int64_t)row * H + jc];
@@ -247,6 +252,26 @@ __global__ __launch_bounds__(256) void lstm_step_forward_kernel(FwdArgs a) {
         reduce_waves(smem, wave, lane, acc, pre);
         finish_group(mb, rh, pre, axv, cprev);
     }
+}
+
+template <typename T, bool WIDE>
+__global__ __launch_bounds__(256) void lstm_step_forward_kernel(FwdArgs a) {
+    forward_cell<T, WIDE>(a, xcd_swizzle(blockIdx.x, gridDim.x), (int)blockIdx.x);
+}
+
+// Several independent cells in one launch: layer l at time t depends on (l, t-1) and (l-1, t),
+// so the cells of one anti-diagonal l + t = d can run together.  Stacks of narrow layers are
+// bound by the chain of dependent launches (T * L of them layer by layer); along the diagonals
+// the chain is T + L - 1 long and each launch carries up to L cells' workgroups.
+constexpr int WAVE_MAX_CELLS = 8;
+struct WaveFwdArgs {
+    FwdArgs cell[WAVE_MAX_CELLS];
+    int wgs_per_cell;
+};
+template <typename T>
+__global__ __launch_bounds__(256) void lstm_wave_forward_kernel(WaveFwdArgs w) {
+    const int c = blockIdx.x / w.wgs_per_cell;             // uniform: selects the cell's argument block
+    forward_cell<T, false>(w.cell[c], (int)blockIdx.x - c * w.wgs_per_cell, (int)blockIdx.x);
 }
 
 // ---------------------------------------------------------------- backward
@@ -503,6 +528,7 @@ int step_forward_fused(int dtype, const void *hpk_prev, const void *Upk, const v
     const RecurrentDims d = recurrent_dims(B, H);
     FwdArgs a;
     a.hpk_prev = hpk_prev; a.Upk = Upk; a.Ax = Ax; a.c_state = c_state; a.gates = gates; a.c_out = c_out; a.h_out = h_out;
+    a.xpk = nullptr; a.Wpk = nullptr; a.bias = nullptr;
     a.hpk_next = hpk_next; a.h_blk = h_blk; a.blk_ncb = blk_ncb;
     a.B = B; a.H = H; a.n_mt = d.n_mt; a.nkc = d.nkc;
     const bool wide = recurrent_wide(d);
@@ -560,6 +586,35 @@ int gates_backward_packed(int dtype, const void *dh_above, const float *partials
                                              (const T *)dh_above, partials, (const T *)gates, (const T *)c_t, (const T *)c_prev,
                                              dc_state, (T *)dA, (T *)dApk, (T *)dAblk, blk_ncb, B, H, d.nkc, first));
     }
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+int wave_forward_max_cells() { return WAVE_MAX_CELLS; }
+
+int step_forward_wave(int dtype, const WaveCell *cells, int n_cells, int blk_ncb, int B, int H, hipStream_t s) {
+    const RecurrentDims d = recurrent_dims(B, H);
+    if (n_cells < 1 || n_cells > WAVE_MAX_CELLS) {
+        set_error("step_forward_wave: %d cells (1..%d)", n_cells, WAVE_MAX_CELLS);
+        return LSTM_ERR_INVALID;
+    }
+    WaveFwdArgs w;
+    w.wgs_per_cell = d.n_mt * d.n_hb;
+    for (int i = 0; i < WAVE_MAX_CELLS; ++i) {
+        const WaveCell &c = cells[i < n_cells ? i : 0];
+        if (!c.hpk_prev || !c.Upk || !c.c_state || !c.gates || !c.c_out || !c.h_out || !c.hpk_next || (!c.Ax && (!c.xpk || !c.Wpk || !c.bias))) {
+            set_error("step_forward_wave: null operand in cell %d", i);
+            return LSTM_ERR_INVALID;
+        }
+        FwdArgs &a = w.cell[i];
+        a.hpk_prev = c.hpk_prev; a.Upk = c.Upk; a.Ax = c.Ax; a.xpk = c.xpk; a.Wpk = c.Wpk; a.bias = c.bias;
+        a.c_state = c.c_state; a.gates = c.gates; a.c_out = c.c_out; a.h_out = c.h_out; a.hpk_next = c.hpk_next; a.h_blk = c.h_blk;
+        a.blk_ncb = blk_ncb; a.B = B; a.H = H; a.n_mt = d.n_mt; a.nkc = d.nkc;
+    }
+    double flops = 0.0;
+    for (int i = 0; i < n_cells; ++i) flops += 2.0 * B * 4.0 * H * H * (cells[i].Ax ? 1.0 : 2.0);
+    KernelTimer timer(KC_GEMM_STEP, s, flops, 0.0);
+    LP_ONLY(dtype, T, hipLaunchKernelGGL(lstm_wave_forward_kernel<T>, dim3(w.wgs_per_cell * n_cells), dim3(256), 0, s, w));
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
