@@ -4,6 +4,7 @@
 #include <stdarg.h>
 #include <stdio.h>
 
+#include <algorithm>
 #include <vector>
 
 #include "kernels.h"
@@ -48,8 +49,11 @@ struct Plan {
     size_t s_wT = 0, s_dA = 0, s_dAT = 0, s_xT = 0, s_dh[2] = {0, 0}, s_dhrec = 0, s_dcstate = 0, s_splitk = 0,
            s_colpart = 0, s_dE32 = 0, s_part = 0, s_upk = 0, s_apk[2] = {0, 0}, scratch_bytes = 0;
     // forward along anti-diagonals (cells of several layers per launch): per-layer operands and state
-    bool wf = false;
+    bool wf = false, wb = false;   // wb: the backward pass too (costs one dA per layer, see make_plan)
     std::vector<size_t> s_wf_upk, s_wf_wpk, s_wf_c, s_wf_hpk0, s_wf_hpk1;
+    // backward along anti-diagonals: per-layer dA (row-major and blocked), packed U^T / W^T, packed dA_t,
+    // the two sets of K-slice partials (dA U for the step before, dA W for the layer below), cell gradient
+    std::vector<size_t> s_wb_dA, s_wb_dablk, s_wb_utpk, s_wb_wtpk, s_wb_dapk, s_wb_partU, s_wb_partW, s_wb_dc;
     std::vector<size_t> wT_off, uT_off;  // byte offsets inside the s_wT region
     std::vector<int> split_w, split_u;
 };
@@ -212,6 +216,29 @@ int make_plan(const lstm_config *c, Plan &p) {
                 p.s_wf_hpk0[l] = s; s += align_up(rd.hpk_elems * p.es);
                 p.s_wf_hpk1[l] = s; s += align_up(rd.hpk_elems * p.es);
                 p.s_wf_c[l] = s; s += align_up((size_t)p.B * p.H * 4);
+            }
+            // The backward pass along the diagonals keeps every layer's dA (row-major and blocked) until
+            // the weight-gradient GEMMs at the end, instead of one layer's at a time.  It is used while
+            // that extra storage stays within a fixed budget; stacks deep enough to be bound by device
+            // memory (the capacity experiment of Table 1) keep the layer-by-layer backward pass.
+            constexpr size_t kDiagonalBackwardBudget = (size_t)8 << 30;
+            const size_t per_layer = align_up(TB * p.G * p.es) + (p.blk ? align_up(blocked_elems((int)TB, p.G) * p.es) : 0) +
+                                     2 * align_up(rd.utpk_elems * p.es) + align_up(rd.dapk_elems * p.es) +
+                                     2 * align_up(rd.partial_bytes) + align_up((size_t)p.B * p.H * 4);
+            p.wb = per_layer * (size_t)p.L <= kDiagonalBackwardBudget;
+        }
+        if (p.wb) {
+            p.s_wb_dA.resize(p.L); p.s_wb_dablk.assign(p.L, 0); p.s_wb_utpk.resize(p.L); p.s_wb_wtpk.assign(p.L, 0);
+            p.s_wb_dapk.resize(p.L); p.s_wb_partU.resize(p.L); p.s_wb_partW.assign(p.L, 0); p.s_wb_dc.resize(p.L);
+            for (int l = 0; l < p.L; ++l) {
+                p.s_wb_dA[l] = s; s += align_up(TB * p.G * p.es);
+                if (p.blk) { p.s_wb_dablk[l] = s; s += align_up(blocked_elems((int)TB, p.G) * p.es); }
+                p.s_wb_utpk[l] = s; s += align_up(rd.utpk_elems * p.es);
+                if (l > 0) { p.s_wb_wtpk[l] = s; s += align_up(rd.utpk_elems * p.es); }
+                p.s_wb_dapk[l] = s; s += align_up(rd.dapk_elems * p.es);
+                p.s_wb_partU[l] = s; s += align_up(rd.partial_bytes);
+                if (l > 0) { p.s_wb_partW[l] = s; s += align_up(rd.partial_bytes); }
+                p.s_wb_dc[l] = s; s += align_up((size_t)p.B * p.H * 4);
             }
         }
     }
@@ -575,12 +602,55 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
     }
     LSTM_TRY(head_backward_bias(p.dtype, dzu, loss_scale, p.head_rows / p.W, grd + p.off_bh * es, s, p.W, p.Bw, p.P));
 
-    char *dA = at(scratch, p.s_dA);
+    if (p.wb) {
+        // BPTT along anti-diagonals: cell (l, t) needs dA_{l,t+1} U_l (its own layer, one step later) and
+        // dA_{l+1,t} W_{l+1} (the layer above, same step), both products of cells on the diagonal before.
+        // Per diagonal: one launch with the gate arithmetic of all its cells, one with their products.
+        const RecurrentDims rd = recurrent_dims(p.B, p.H);
+        for (int l = 0; l < p.L; ++l) {
+            LSTM_TRY(pack_u_backward(p.dtype, par + p.off_U[l] * es, at(scratch, p.s_wb_utpk[l]), p.H, s));
+            if (l > 0) LSTM_TRY(pack_u_backward(p.dtype, par + p.off_W[l] * es, at(scratch, p.s_wb_wtpk[l]), p.H, s));
+            LSTM_TRY(fill_u32(at(scratch, p.s_wb_dapk[l]), 0, (int64_t)((rd.dapk_elems * es + 3) / 4), s));
+            if (p.blk && p.G % 64 != 0)
+                LSTM_TRY(fill_u32(at(scratch, p.s_wb_dablk[l]), 0, (int64_t)(blocked_elems(TB, p.G) * es / 4), s));
+        }
+        const int max_gates = wave_backward_max_gates(), max_gemms = wave_backward_max_gemms();
+        std::vector<WaveGates> gc;
+        std::vector<WaveGemm> mm;
+        for (int d = 0; d < p.T + p.L - 1; ++d) {
+            gc.clear(); mm.clear();
+            for (int l = p.L - 1; l >= 0; --l) {
+                const int t = p.T - 1 - (d - (p.L - 1 - l));
+                if (t < 0 || t >= p.T) continue;
+                WaveGates c{};
+                c.dh_above = l == p.L - 1 ? dh_above + (size_t)t * BH * es : nullptr;
+                c.above4 = l < p.L - 1 ? (const float *)at(scratch, p.s_wb_partW[l + 1]) : nullptr;
+                c.partials = (const float *)at(scratch, p.s_wb_partU[l]);
+                c.gates = at(reserve, p.r_gates[l]) + (size_t)t * p.B * p.G * es;
+                c.c_t = at(reserve, p.r_c[l]) + (size_t)(t + 1) * BH * es;
+                c.c_prev = at(reserve, p.r_c[l]) + (size_t)t * BH * es;
+                c.dc_state = (float *)at(scratch, p.s_wb_dc[l]);
+                c.dA = at(scratch, p.s_wb_dA[l]) + (size_t)t * p.B * p.G * es;
+                c.dApk = at(scratch, p.s_wb_dapk[l]);
+                c.dAblk = p.blk ? at(scratch, p.s_wb_dablk[l]) + (size_t)t * (p.B / 64) * p.g_ncb * 4096 * es : nullptr;
+                c.first = t == p.T - 1 ? 1 : 0;
+                gc.push_back(c);
+                if (t > 0) mm.push_back(WaveGemm{c.dApk, at(scratch, p.s_wb_utpk[l]), (float *)at(scratch, p.s_wb_partU[l])});
+                if (l > 0) mm.push_back(WaveGemm{c.dApk, at(scratch, p.s_wb_wtpk[l]), (float *)at(scratch, p.s_wb_partW[l])});
+            }
+            for (size_t i = 0; i < gc.size(); i += max_gates)
+                LSTM_TRY(gates_backward_wave(p.dtype, gc.data() + i, (int)std::min<size_t>(max_gates, gc.size() - i), p.g_ncb, p.B,
+                                             p.H, s));
+            for (size_t i = 0; i < mm.size(); i += max_gemms)
+                LSTM_TRY(step_backward_gemm_wave(p.dtype, mm.data() + i, (int)std::min<size_t>(max_gemms, mm.size() - i), p.B, p.H, s));
+        }
+    }
     char *dAT = at(scratch, p.s_dAT);
     char *xT = at(scratch, p.s_xT);
     float *dh_rec = (float *)at(scratch, p.s_dhrec);
     float *dc_state = (float *)at(scratch, p.s_dcstate);
     for (int l = p.L - 1; l >= 0; --l) {
+        char *dA = at(scratch, p.wb ? p.s_wb_dA[l] : p.s_dA);
         const char *gates = at(reserve, p.r_gates[l]);
         const char *cs = at(reserve, p.r_c[l]);
         const char *hs = at(reserve, p.r_h[l]);
@@ -590,14 +660,14 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
         const bool fused = p.dtype != LSTM_DTYPE_FP32;
         char *utpk = at(scratch, p.s_upk);
         char *dapk[2] = {at(scratch, p.s_apk[0]), at(scratch, p.s_apk[1])};
-        if (fused) {
+        if (fused && !p.wb) {
             const RecurrentDims rd = recurrent_dims(p.B, p.H);
             LSTM_TRY(pack_u_backward(p.dtype, par + p.off_U[l] * es, utpk, p.H, s));
             for (int k = 0; k < 2; ++k) LSTM_TRY(fill_u32(dapk[k], 0, (int64_t)((rd.dapk_elems * es + 3) / 4), s));
         }
-        char *dablk = p.blk ? at(scratch, p.s_dablk) : nullptr;
-        if (p.blk && p.G % 64 != 0) LSTM_TRY(fill_u32(dablk, 0, (int64_t)(blocked_elems(TB, p.G) * es / 4), s));
-        for (int t = p.T - 1; t >= 0; --t) {
+        char *dablk = p.blk ? at(scratch, p.wb ? p.s_wb_dablk[l] : p.s_dablk) : nullptr;
+        if (!p.wb && p.blk && p.G % 64 != 0) LSTM_TRY(fill_u32(dablk, 0, (int64_t)(blocked_elems(TB, p.G) * es / 4), s));
+        for (int t = p.wb ? -1 : p.T - 1; t >= 0; --t) {      // along the diagonals the steps are already done
             const bool last = t == p.T - 1;
             if (fused) {
                 // dA_{t+1} U as four per-gate K-slices, summed by the gate kernel
@@ -632,8 +702,9 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             if (l == 0) in_blk = BlockedOperand{at(reserve, p.r_xblk), (p.in_dim[0] + 63) / 64, 0};
             else in_blk = BlockedOperand{at(reserve, p.r_hblk[l - 1]) + (size_t)(p.B / 64) * p.h_ncb * 4096 * es, p.h_ncb, 0};
         }
-        if (l > 0 || p.V > 0) {
-            // dX = dA W  for the layer below (or the embedding rows)
+        if ((l > 0 && !p.wb) || (l == 0 && p.V > 0)) {
+            // dX = dA W  for the layer below (or the embedding rows); along the diagonals the layers
+            // above the first got theirs step by step
             if (p.blk && gemm_blocked_supported(p.dtype, TB, I)) {
                 LSTM_TRY(pack_blocked(p.dtype, par + p.off_W[l] * es, I, p.G, I, wblk, s));
                 BlockedGemmArgs d{};

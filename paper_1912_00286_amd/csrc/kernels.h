@@ -92,6 +92,24 @@ struct WaveCell {
     float *c_state;
     void *gates, *c_out, *h_out, *hpk_next, *h_blk;
 };
+// backward along anti-diagonals: several per-step products / several cells' gate arithmetic per launch
+struct WaveGemm {
+    const void *dApk, *Bpk;   // packed dA_t and packed U^T (or W^T) of its layer
+    float *partials;          // fp32 [4][B,H] out
+};
+struct WaveGates {
+    const void *dh_above;     // lp [B,H] or null
+    const float *above4;      // fp32 [4][B,H] (dA_t W of the layer above) or null
+    const float *partials;    // fp32 [4][B,H] (dA_{t+1} U), unused when first
+    const void *gates, *c_t, *c_prev;
+    float *dc_state;
+    void *dA, *dApk, *dAblk;
+    int first;
+};
+int wave_backward_max_gemms();
+int wave_backward_max_gates();
+int step_backward_gemm_wave(int dtype, const WaveGemm *g, int n, int B, int H, hipStream_t s);
+int gates_backward_wave(int dtype, const WaveGates *c, int n_cells, int blk_ncb, int B, int H, hipStream_t s);
 int wave_forward_max_cells();
 int step_forward_wave(int dtype, const WaveCell *cells, int n_cells, int blk_ncb, int B, int H, hipStream_t s);
 

@@ -284,12 +284,11 @@ struct BwdArgs {
 
 // partial[q][b, j] = sum over the rows k of gate q of dA_next[b, k] * U[k, j]
 template <typename T, bool WIDE>
-__global__ __launch_bounds__(256) void lstm_step_backward_gemm_kernel(BwdArgs a) {
+__device__ __forceinline__ void backward_gemm_cell(const BwdArgs &a, int lin, int total, int rot) {
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int lin = xcd_swizzle(blockIdx.x, gridDim.x);
     // gate-slice major: the workgroups of one XCD share one K slice, so that XCD's L2 pulls
     // only that quarter of dA over the fabric (all of it would be fetched by all eight otherwise)
-    const int per_q = (int)gridDim.x >> 2;
+    const int per_q = total >> 2;
     const int q = lin / per_q, tile = lin - q * per_q;
     const int mt = tile % a.n_mt, nt = tile / a.n_mt;
     const int m0 = mt * TM, n0 = nt * TN;
@@ -299,8 +298,7 @@ __global__ __launch_bounds__(256) void lstm_step_backward_gemm_kernel(BwdArgs a)
     v16f acc[2][NBLK];
     zero_acc(acc);
     packed_mainloop<T>(reinterpret_cast<const uint16_t *>(a.dApk) + ((int64_t)mt * 4 + q) * a.nkc * A_CHUNK,
-                       reinterpret_cast<const uint16_t *>(a.UTpk) + ((int64_t)nt * 4 + q) * a.nkc * B_CHUNK, c0, c1,
-                       (int)blockIdx.x, lane, acc);
+                       reinterpret_cast<const uint16_t *>(a.UTpk) + ((int64_t)nt * 4 + q) * a.nkc * B_CHUNK, c0, c1, rot, lane, acc);
     float *part = a.partials + (int64_t)q * a.B * H;
     auto store_group = [&](int mb, int rh, const float (&sum)[8][NBLK]) {
 #pragma unroll
@@ -334,21 +332,47 @@ __global__ __launch_bounds__(256) void lstm_step_backward_gemm_kernel(BwdArgs a)
     }
 }
 
+template <typename T, bool WIDE>
+__global__ __launch_bounds__(256) void lstm_step_backward_gemm_kernel(BwdArgs a) {
+    backward_gemm_cell<T, WIDE>(a, xcd_swizzle(blockIdx.x, gridDim.x), (int)gridDim.x, (int)blockIdx.x);
+}
+
+// Several products in one launch (the backward anti-diagonal: dA_t U of every ready layer, and
+// dA_t W for the layer below it).
+constexpr int WAVE_MAX_GEMMS = 16;
+struct WaveBwdGemmArgs {
+    const void *dApk[WAVE_MAX_GEMMS];
+    const void *Bpk[WAVE_MAX_GEMMS];
+    float *partials[WAVE_MAX_GEMMS];
+    int B, H, n_mt, nkc, wgs_per_cell;
+};
+template <typename T>
+__global__ __launch_bounds__(256) void lstm_wave_backward_gemm_kernel(WaveBwdGemmArgs w) {
+    const int c = blockIdx.x / w.wgs_per_cell;
+    BwdArgs a;
+    a.dApk = w.dApk[c]; a.UTpk = w.Bpk[c]; a.partials = w.partials[c];
+    a.B = w.B; a.H = w.H; a.n_mt = w.n_mt; a.nkc = w.nkc;
+    backward_gemm_cell<T, false>(a, (int)blockIdx.x - c * w.wgs_per_cell, w.wgs_per_cell, (int)blockIdx.x);
+}
+
 // BPTT through the gates of one step; sums the four recurrent partials, writes
 // dA row-major (for the whole-sequence GEMMs) and packed (A operand of the next
 // recurrent GEMM).  VEC: H % 8 == 0 and 16-byte aligned tensors; one thread
 // owns 8 consecutive hidden units of one batch row (16-byte loads and stores,
 // and its 8 packed outputs are one 16-byte fragment slot).
+// The gradient arriving from above is dh_above (16-bit, row-major: the head or a whole-sequence
+// data-gradient GEMM) and/or above4 (four fp32 K-slice partials of the per-step product
+// dA_t W of the layer above, used when the backward pass runs along anti-diagonals).
 template <typename T, bool VEC>
-__global__ __launch_bounds__(256) void gates_backward_packed_kernel(const T *dh_above, const float *partials, const T *gates,
-                                                                    const T *c_t, const T *c_prev, float *dc_state, T *dA,
-                                                                    T *dApk, T *dAblk, int blk_ncb, int B, int H, int nkc,
-                                                                    int first) {
+__device__ __forceinline__ void gates_backward_cell(const T *dh_above, const float *above4, const float *partials, const T *gates,
+                                                    const T *c_t, const T *c_prev, float *dc_state, T *dA, T *dApk, T *dAblk,
+                                                    int blk_ncb, int B, int H, int nkc, int first, int64_t thread0,
+                                                    int64_t nthreads) {
     constexpr int W = VEC ? 8 : 1;
     const int64_t n = (int64_t)B * H;
     const int G = 4 * H;
     const int64_t gs = (int64_t)nkc * A_CHUNK;
-    for (int64_t e0 = (blockIdx.x * (int64_t)blockDim.x + threadIdx.x) * W; e0 < n; e0 += (int64_t)gridDim.x * blockDim.x * W) {
+    for (int64_t e0 = thread0 * W; e0 < n; e0 += nthreads * W) {
         const int b = (int)(e0 / H), j0 = (int)(e0 % H);
         __attribute__((aligned(16))) T vi[W], vf[W], vg[W], vo[W], vct[W], vcp[W], vdh[W];
         __attribute__((aligned(16))) float p0[W], p1[W], p2[W], p3[W], dcs[W];
@@ -360,7 +384,7 @@ __global__ __launch_bounds__(256) void gates_backward_packed_kernel(const T *dh_
             *reinterpret_cast<u32x4 *>(vo) = *reinterpret_cast<const u32x4 *>(gr + 3 * H);
             *reinterpret_cast<u32x4 *>(vct) = *reinterpret_cast<const u32x4 *>(c_t + e0);
             *reinterpret_cast<u32x4 *>(vcp) = *reinterpret_cast<const u32x4 *>(c_prev + e0);
-            *reinterpret_cast<u32x4 *>(vdh) = *reinterpret_cast<const u32x4 *>(dh_above + e0);
+            if (dh_above) *reinterpret_cast<u32x4 *>(vdh) = *reinterpret_cast<const u32x4 *>(dh_above + e0);
             if (!first) {
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
@@ -373,7 +397,8 @@ __global__ __launch_bounds__(256) void gates_backward_packed_kernel(const T *dh_
             }
         } else {
             vi[0] = gr[0]; vf[0] = gr[H]; vg[0] = gr[2 * H]; vo[0] = gr[3 * H];
-            vct[0] = c_t[e0]; vcp[0] = c_prev[e0]; vdh[0] = dh_above[e0];
+            vct[0] = c_t[e0]; vcp[0] = c_prev[e0];
+            if (dh_above) vdh[0] = dh_above[e0];
             if (!first) {
                 p0[0] = partials[e0]; p1[0] = partials[n + e0]; p2[0] = partials[2 * n + e0]; p3[0] = partials[3 * n + e0];
                 dcs[0] = dc_state[e0];
@@ -385,7 +410,8 @@ __global__ __launch_bounds__(256) void gates_backward_packed_kernel(const T *dh_
         for (int k = 0; k < W; ++k) {
             const float i = Lp<T>::to_f(vi[k]), f = Lp<T>::to_f(vf[k]), g = Lp<T>::to_f(vg[k]), o = Lp<T>::to_f(vo[k]);
             const float tc = tanhf_dev(Lp<T>::to_f(vct[k]));
-            float dh = Lp<T>::to_f(vdh[k]);
+            float dh = dh_above ? Lp<T>::to_f(vdh[k]) : 0.0f;
+            if (above4) dh += (above4[e0 + k] + above4[n + e0 + k]) + (above4[2 * n + e0 + k] + above4[3 * n + e0 + k]);
             float dcr = 0.0f;
             if (!first) {
                 dh += (p0[k] + p1[k]) + (p2[k] + p3[k]);
@@ -432,6 +458,40 @@ __global__ __launch_bounds__(256) void gates_backward_packed_kernel(const T *dh_
             }
         }
     }
+}
+
+template <typename T, bool VEC>
+__global__ __launch_bounds__(256) void gates_backward_packed_kernel(const T *dh_above, const float *partials, const T *gates,
+                                                                    const T *c_t, const T *c_prev, float *dc_state, T *dA,
+                                                                    T *dApk, T *dAblk, int blk_ncb, int B, int H, int nkc,
+                                                                    int first) {
+    gates_backward_cell<T, VEC>(dh_above, nullptr, partials, gates, c_t, c_prev, dc_state, dA, dApk, dAblk, blk_ncb, B, H, nkc, first,
+                                blockIdx.x * (int64_t)blockDim.x + threadIdx.x, (int64_t)gridDim.x * blockDim.x);
+}
+
+// The BPTT gate arithmetic of several independent (layer, time) cells in one launch.
+constexpr int WAVE_MAX_GATES = 8;
+struct WaveGateCell {
+    const void *dh_above;     // lp [B,H] or null
+    const float *above4;      // fp32 [4][B,H] or null
+    const float *partials;    // fp32 [4][B,H]: dA_{t+1} U of this layer (unused when first)
+    const void *gates, *c_t, *c_prev;
+    float *dc_state;
+    void *dA, *dApk, *dAblk;
+    int first;
+};
+struct WaveGateArgs {
+    WaveGateCell cell[WAVE_MAX_GATES];
+    int blk_ncb, B, H, nkc, blocks_per_cell;
+};
+template <typename T, bool VEC>
+__global__ __launch_bounds__(256) void wave_gates_backward_kernel(WaveGateArgs w) {
+    const int ci = blockIdx.x / w.blocks_per_cell;
+    const WaveGateCell &c = w.cell[ci];
+    const int blk = (int)blockIdx.x - ci * w.blocks_per_cell;
+    gates_backward_cell<T, VEC>((const T *)c.dh_above, c.above4, c.partials, (const T *)c.gates, (const T *)c.c_t, (const T *)c.c_prev,
+                                c.dc_state, (T *)c.dA, (T *)c.dApk, (T *)c.dAblk, w.blk_ncb, w.B, w.H, w.nkc, c.first,
+                                blk * (int64_t)blockDim.x + threadIdx.x, (int64_t)w.blocks_per_cell * blockDim.x);
 }
 
 // ---------------------------------------------------------------- packing
@@ -611,10 +671,80 @@ int step_forward_wave(int dtype, const WaveCell *cells, int n_cells, int blk_ncb
         a.c_state = c.c_state; a.gates = c.gates; a.c_out = c.c_out; a.h_out = c.h_out; a.hpk_next = c.hpk_next; a.h_blk = c.h_blk;
         a.blk_ncb = blk_ncb; a.B = B; a.H = H; a.n_mt = d.n_mt; a.nkc = d.nkc;
     }
-    double flops = 0.0;
-    for (int i = 0; i < n_cells; ++i) flops += 2.0 * B * 4.0 * H * H * (cells[i].Ax ? 1.0 : 2.0);
-    KernelTimer timer(KC_GEMM_STEP, s, flops, 0.0);
+    // per cell as in step_forward_fused; a cell that projects its input reads W and the packed
+    // input instead of a ready-made projection
+    double flops = 0.0, bytes = 0.0;
+    const double bh = (double)B * H;
+    for (int i = 0; i < n_cells; ++i) {
+        const bool proj = !cells[i].Ax;
+        flops += 2.0 * B * 4.0 * H * H * (proj ? 2.0 : 1.0);
+        bytes += 2.0 * (4.0 * H * H * (proj ? 2.0 : 1.0) + bh + (proj ? bh : 4.0 * bh)) + 4.0 * bh +
+                 2.0 * (4.0 * bh + bh + (cells[i].h_blk ? 3.0 : 2.0) * bh) + 4.0 * bh;
+    }
+    KernelTimer timer(KC_GEMM_STEP, s, flops, bytes);
     LP_ONLY(dtype, T, hipLaunchKernelGGL(lstm_wave_forward_kernel<T>, dim3(w.wgs_per_cell * n_cells), dim3(256), 0, s, w));
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+int wave_backward_max_gemms() { return WAVE_MAX_GEMMS; }
+int wave_backward_max_gates() { return WAVE_MAX_GATES; }
+
+int step_backward_gemm_wave(int dtype, const WaveGemm *g, int n, int B, int H, hipStream_t s) {
+    const RecurrentDims d = recurrent_dims(B, H);
+    if (n < 1 || n > WAVE_MAX_GEMMS) {
+        set_error("step_backward_gemm_wave: %d products (1..%d)", n, WAVE_MAX_GEMMS);
+        return LSTM_ERR_INVALID;
+    }
+    WaveBwdGemmArgs w;
+    for (int i = 0; i < WAVE_MAX_GEMMS; ++i) {
+        const WaveGemm &c = g[i < n ? i : 0];
+        if (!c.dApk || !c.Bpk || !c.partials) {
+            set_error("step_backward_gemm_wave: null operand in product %d", i);
+            return LSTM_ERR_INVALID;
+        }
+        w.dApk[i] = c.dApk; w.Bpk[i] = c.Bpk; w.partials[i] = c.partials;
+    }
+    w.B = B; w.H = H; w.n_mt = d.n_mt; w.nkc = d.nkc; w.wgs_per_cell = d.n_mt * d.n_nt * 4;
+    KernelTimer timer(KC_GEMM_STEP, s, n * 2.0 * B * 4.0 * H * H, n * (2.0 * (4.0 * H * H + 4.0 * (double)B * H) + 16.0 * (double)B * H));
+    LP_ONLY(dtype, T, hipLaunchKernelGGL(lstm_wave_backward_gemm_kernel<T>, dim3(w.wgs_per_cell * n), dim3(256), 0, s, w));
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+int gates_backward_wave(int dtype, const WaveGates *c, int n_cells, int blk_ncb, int B, int H, hipStream_t s) {
+    const RecurrentDims d = recurrent_dims(B, H);
+    if (n_cells < 1 || n_cells > WAVE_MAX_GATES) {
+        set_error("gates_backward_wave: %d cells (1..%d)", n_cells, WAVE_MAX_GATES);
+        return LSTM_ERR_INVALID;
+    }
+    const int64_t n = (int64_t)B * H;
+    uintptr_t all = 0;
+    WaveGateArgs w;
+    for (int i = 0; i < WAVE_MAX_GATES; ++i) {
+        const WaveGates &x = c[i < n_cells ? i : 0];
+        if (!x.gates || !x.c_t || !x.c_prev || !x.dc_state || !x.dA || !x.dApk || (!x.first && !x.partials) || (!x.dh_above && !x.above4)) {
+            set_error("gates_backward_wave: null operand in cell %d", i);
+            return LSTM_ERR_INVALID;
+        }
+        all |= (uintptr_t)x.dh_above | (uintptr_t)x.above4 | (uintptr_t)x.partials | (uintptr_t)x.gates | (uintptr_t)x.c_t |
+               (uintptr_t)x.c_prev | (uintptr_t)x.dc_state | (uintptr_t)x.dA | (uintptr_t)x.dApk | (uintptr_t)x.dAblk;
+        WaveGateCell &o = w.cell[i];
+        o.dh_above = x.dh_above; o.above4 = x.above4; o.partials = x.partials; o.gates = x.gates; o.c_t = x.c_t; o.c_prev = x.c_prev;
+        o.dc_state = x.dc_state; o.dA = x.dA; o.dApk = x.dApk; o.dAblk = x.dAblk; o.first = x.first;
+    }
+    const bool vec = H % 8 == 0 && all % 16 == 0;
+    const int64_t items = vec ? n / 8 : n;
+    int blocks = (int)((items + 255) / 256);
+    if (blocks > 2048) blocks = 2048;
+    if (blocks < 1) blocks = 1;
+    w.blk_ncb = blk_ncb; w.B = B; w.H = H; w.nkc = d.nkc; w.blocks_per_cell = blocks;
+    KernelTimer timer(KC_POINTWISE, s, 0.0, n_cells * (double)n * (16.0 + 8.0 + 15.0 * 2.0));
+    if (vec) {
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((wave_gates_backward_kernel<T, true>), dim3(blocks * n_cells), dim3(256), 0, s, w));
+    } else {
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((wave_gates_backward_kernel<T, false>), dim3(blocks * n_cells), dim3(256), 0, s, w));
+    }
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
