@@ -47,6 +47,9 @@ SMALL = [
     ("s_bf16_mse", 1, 40, 136, 5, 130, "bf16", wl.HEAD_STEP_MSE),
     ("s_T1_B1", 1, 16, 32, 1, 1, "fp16", wl.HEAD_STEP_BCE),            # degenerate: one step, one sample
     ("s_H1", 1, 3, 1, 4, 3, "fp32", wl.HEAD_STEP_BCE),                 # one hidden unit
+    ("s_fp16_L3_T1", 3, 8, 40, 1, 5, "fp16", wl.HEAD_STEP_BCE),        # anti-diagonal schedule, a single time step
+    ("s_bf16_L9_T3", 9, 8, 24, 3, 4, "bf16", wl.HEAD_STEP_MSE),        # more layers than cells per launch, L > T
+    ("s_fp16_L4_last", 4, 10, 72, 7, 9, "fp16", wl.HEAD_LAST_BCE),     # four layers, last-step head, ragged sizes
 ]
 
 
