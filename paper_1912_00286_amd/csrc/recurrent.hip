@@ -72,19 +72,24 @@ __device__ __forceinline__ void mfma_chunk(const u32x4 (&ra)[NLD_A], const u32x4
 // already loaded and the one after is in flight.
 template <typename T>
 __device__ __forceinline__ void packed_mainloop(const uint16_t *Apk, const uint16_t *Bpk, int c0, int c1, int rot, int lane,
-                                                v16f (&acc)[2][NBLK]) {
+                                                v16f (&acc)[2][NBLK], const uint16_t *Apk2 = nullptr,
+                                                const uint16_t *Bpk2 = nullptr, int nkc1 = 0) {
+    // With a second operand pair the chunk list is the concatenation [pair 1: nkc1 chunks][pair 2],
+    // so the load pipeline runs across the boundary between the two products.
     const int nst = c1 - c0;
     if (nst <= 0) return;
     rot %= nst;
     auto pa = [&](int s) {
         int ss = s + rot;
         if (ss >= nst) ss -= nst;
-        return reinterpret_cast<const u32x4 *>(Apk + (int64_t)(c0 + ss) * A_CHUNK);
+        const int c = c0 + ss;
+        return reinterpret_cast<const u32x4 *>(Apk2 && c >= nkc1 ? Apk2 + (int64_t)(c - nkc1) * A_CHUNK : Apk + (int64_t)c * A_CHUNK);
     };
     auto pb = [&](int s) {
         int ss = s + rot;
         if (ss >= nst) ss -= nst;
-        return reinterpret_cast<const u32x4 *>(Bpk + (int64_t)(c0 + ss) * B_CHUNK);
+        const int c = c0 + ss;
+        return reinterpret_cast<const u32x4 *>(Bpk2 && c >= nkc1 ? Bpk2 + (int64_t)(c - nkc1) * B_CHUNK : Bpk + (int64_t)c * B_CHUNK);
     };
     u32x4 ra0[NLD_A], rb0[NLD_B], ra1[NLD_A], rb1[NLD_B];
     load_chunk(ra0, rb0, pa(0), pb(0), lane);
@@ -170,15 +175,17 @@ __device__ __forceinline__ void forward_cell(const FwdArgs &a, int tile, int rot
     const int mt = tile % a.n_mt, hb = tile / a.n_mt;
     const int m0 = mt * TM, j0 = hb * 32;
     const int H = a.H, G = 4 * a.H;
-    const int cpw = (a.nkc + 3) / 4;                       // chunks per wavefront
-    const int c0 = WIDE ? 0 : min(a.nkc, wave * cpw), c1 = WIDE ? a.nkc : min(a.nkc, c0 + cpw);
+    // K chunks of this cell: the recurrent product, then (a cell that projects its own input) the
+    // layer below's h_t times W^T; the wavefronts split the whole list
+    const int nch = a.Ax ? a.nkc : 2 * a.nkc;
+    const int cpw = (nch + 3) / 4;                         // chunks per wavefront
+    const int c0 = WIDE ? 0 : min(nch, wave * cpw), c1 = WIDE ? nch : min(nch, c0 + cpw);
     v16f acc[2][NBLK];
     zero_acc(acc);
     packed_mainloop<T>(reinterpret_cast<const uint16_t *>(a.hpk_prev) + (int64_t)mt * a.nkc * A_CHUNK,
-                       reinterpret_cast<const uint16_t *>(a.Upk) + (int64_t)hb * a.nkc * B_CHUNK, c0, c1, rot, lane, acc);
-    if (!a.Ax)   // the input projection of this step: the layer below's h_t times W^T, same tiling
-        packed_mainloop<T>(reinterpret_cast<const uint16_t *>(a.xpk) + (int64_t)mt * a.nkc * A_CHUNK,
-                           reinterpret_cast<const uint16_t *>(a.Wpk) + (int64_t)hb * a.nkc * B_CHUNK, c0, c1, rot, lane, acc);
+                       reinterpret_cast<const uint16_t *>(a.Upk) + (int64_t)hb * a.nkc * B_CHUNK, c0, c1, rot, lane, acc,
+                       a.Ax ? nullptr : reinterpret_cast<const uint16_t *>(a.xpk) + (int64_t)mt * a.nkc * A_CHUNK,
+                       a.Ax ? nullptr : reinterpret_cast<const uint16_t *>(a.Wpk) + (int64_t)hb * a.nkc * B_CHUNK, a.nkc);
     const int j = j0 + (lane & 31);
     const int jc = min(j, H - 1);
     T *gates = reinterpret_cast<T *>(a.gates);
