@@ -69,6 +69,15 @@ def test_small_embedding_text_model(hip):
     _check(w.with_(dtype="fp32", loss_scale=1.0, name="s_text32"))
 
 
+def test_small_embedding_two_layers(hip):
+    """Embedding front-end under the anti-diagonal schedule: the data gradient of layer 0 (for the
+    embedding rows) is still a whole-sequence product, the one of layer 1 arrives step by step."""
+    w = wl.Workload("s_text2", 2, 0, 40, 9, 12, "fp16", wl.HEAD_LAST_BCE, vocab=37, embed_dim=16,
+                    loss_scale=1024.0, target_p=0.5, data_seed=79, weight_seed=80)
+    _check(w)
+    _check(w.with_(dtype="bf16", loss_scale=1.0, head=wl.HEAD_STEP_BCE, target_p=0.3, name="s_text2_bf16"))
+
+
 def test_small_many_workers(hip):
     w = wl.Workload("s_workers", 2, 16, 40, 6, 8, "fp16", wl.HEAD_STEP_BCE, n_workers=5, loss_scale=4096.0,
                     dynamic_scale=True, n_half=4.0, warmup_steps=3, gamma=0.9, data_seed=300, weight_seed=31)
