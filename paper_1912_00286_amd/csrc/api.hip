@@ -602,6 +602,15 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
     }
     LSTM_TRY(head_backward_bias(p.dtype, dzu, loss_scale, p.head_rows / p.W, grd + p.off_bh * es, s, p.W, p.Bw, p.P));
 
+    // The row-major copy of dA is only written where something reads it: with every consumer (dX,
+    // dW, dU, the bias gradient) on the blocked copy it is left out.
+    auto dA_rowmajor_needed = [&](int l) {
+        if (!p.blk || p.W > 1) return true;
+        const int I = p.in_dim[l];
+        const bool dx = (l > 0 && !p.wb) || (l == 0 && p.V > 0);
+        if (dx && !gemm_blocked_supported(p.dtype, TB, I)) return true;
+        return !gemm_blocked_supported(p.dtype, p.G, I) || !gemm_blocked_supported(p.dtype, p.G, p.H);
+    };
     if (p.wb) {
         // BPTT along anti-diagonals: cell (l, t) needs dA_{l,t+1} U_l (its own layer, one step later) and
         // dA_{l+1,t} W_{l+1} (the layer above, same step), both products of cells on the diagonal before.
@@ -630,7 +639,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
                 c.c_t = at(reserve, p.r_c[l]) + (size_t)(t + 1) * BH * es;
                 c.c_prev = at(reserve, p.r_c[l]) + (size_t)t * BH * es;
                 c.dc_state = (float *)at(scratch, p.s_wb_dc[l]);
-                c.dA = at(scratch, p.s_wb_dA[l]) + (size_t)t * p.B * p.G * es;
+                c.dA = dA_rowmajor_needed(l) ? at(scratch, p.s_wb_dA[l]) + (size_t)t * p.B * p.G * es : nullptr;
                 c.dApk = at(scratch, p.s_wb_dapk[l]);
                 c.dAblk = p.blk ? at(scratch, p.s_wb_dablk[l]) + (size_t)t * (p.B / 64) * p.g_ncb * 4096 * es : nullptr;
                 c.first = t == p.T - 1 ? 1 : 0;
@@ -650,6 +659,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
     float *dh_rec = (float *)at(scratch, p.s_dhrec);
     float *dc_state = (float *)at(scratch, p.s_dcstate);
     for (int l = p.L - 1; l >= 0; --l) {
+        const bool dA_rm = dA_rowmajor_needed(l);
         char *dA = at(scratch, p.wb ? p.s_wb_dA[l] : p.s_dA);
         const char *gates = at(reserve, p.r_gates[l]);
         const char *cs = at(reserve, p.r_c[l]);
@@ -675,7 +685,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
                 if (!last) LSTM_TRY(step_backward_gemm(p.dtype, dapk[(t + 1) & 1], utpk, part, p.B, p.H, s));
                 LSTM_TRY(gates_backward_packed(p.dtype, dh_above + (size_t)t * BH * es, part, gates + (size_t)t * p.B * p.G * es,
                                                cs + (size_t)(t + 1) * BH * es, cs + (size_t)t * BH * es, dc_state,
-                                               dA + (size_t)t * p.B * p.G * es, dapk[t & 1],
+                                               dA_rm ? dA + (size_t)t * p.B * p.G * es : nullptr, dapk[t & 1],
                                                dablk ? dablk + (size_t)t * (p.B / 64) * p.g_ncb * 4096 * es : nullptr, p.g_ncb,
                                                p.B, p.H, last ? 1 : 0, s));
                 continue;
@@ -777,7 +787,8 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             u.A = dAT; u.B = xT; u.lda = TB; u.ldb = TB;
             LSTM_TRY(gemm_nt(p.dtype, u, s));
         }
-        LSTM_TRY(colsum(p.dtype, dA, p.G, TB / p.W, p.G, nullptr, nullptr, colpart, grd + p.off_b[l] * es, s, p.W, p.Bw, p.P));
+        if (dA_rm) LSTM_TRY(colsum(p.dtype, dA, p.G, TB / p.W, p.G, nullptr, nullptr, colpart, grd + p.off_b[l] * es, s, p.W, p.Bw, p.P));
+        else LSTM_TRY(colsum_blocked(p.dtype, dablk, p.g_ncb, TB, p.G, colpart, grd + p.off_b[l] * es, s));
         cur ^= 1;
         dh_above = d_below;
     }

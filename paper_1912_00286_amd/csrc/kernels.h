@@ -40,6 +40,11 @@ int colsum_chunks(int R);
 int colsum(int dtype, const void *in, int64_t ld, int R, int C, const float *row_w, const float *scale_dev,
            float *partial, void *out_lp, hipStream_t s, int workers = 1, int seg = 0, int64_t out_stride = 0);
 
+// the same sums (no weights, no scale) of a 16-bit tensor stored in 64x64 blocks with ncb column
+// blocks per row block; partial holds colsum_blocked_chunks(R) * C floats
+int colsum_blocked_chunks(int R);
+int colsum_blocked(int dtype, const void *blk, int ncb, int R, int C, float *partial, void *out_lp, hipStream_t s);
+
 // head forward: z = h.w + b per row; loss partial sums; dzu = dloss/dz (unscaled, already / M)
 int head_loss_blocks(int rows);
 int head_forward(int dtype, int head, const void *h_top, const void *w, const void *b, const float *targets, int rows,

@@ -173,6 +173,38 @@ __global__ __launch_bounds__(256) void colsum_partial_vec_kernel(const T *in, in
                 (red[0][l][e] + red[1][l][e]) + (red[2][l][e] + red[3][l][e]);
     }
 }
+// Column sums of a tensor stored in 64x64 blocks ([row block][ncb][64][64], zero padded): a
+// workgroup owns one column block and up to CSB_BLOCKS row blocks, reads them as whole 8 KB
+// blocks (thread = 8 columns of one of 32 row slots) and writes one partial row.
+constexpr int CSB_BLOCKS = 8;
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_blocked_partial_kernel(const T *blk, int ncb, int nrb, int C, float *partial) {
+    __shared__ float red[32][65];
+    const int cb = blockIdx.x, c8 = (threadIdx.x & 7) * 8, rs = threadIdx.x >> 3;
+    const int rb0 = blockIdx.y * CSB_BLOCKS, rb1 = min(nrb, rb0 + CSB_BLOCKS);
+    float s[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+    for (int rb = rb0; rb < rb1; ++rb) {
+        const T *b = blk + ((int64_t)rb * ncb + cb) * 4096;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const u32x4 raw = *reinterpret_cast<const u32x4 *>(b + (rs + 32 * h) * 64 + c8);
+            T v[8];
+            __builtin_memcpy(v, &raw, 16);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s[e] += Lp<T>::to_f(v[e]);
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[rs][c8 + e] = s[e];
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        float t = 0.0f;
+#pragma unroll
+        for (int r = 0; r < 32; ++r) t += red[r][threadIdx.x];
+        const int c = cb * 64 + threadIdx.x;
+        if (c < C) partial[(int64_t)blockIdx.y * C + c] = t;
+    }
+}
 template <typename T>
 __global__ void colsum_final_kernel(const float *partial, int chunks, int C, const float *scale_dev, T *out, int64_t out_stride) {
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
@@ -392,6 +424,27 @@ int colsum(int dtype, const void *in, int64_t ld, int R, int C, const float *row
         if (!vec) hipLaunchKernelGGL(colsum_partial_kernel<T>, grid, dim3(256), 0, s, (const T *)in, ld, R, C, row_w, partial, rs);
         hipLaunchKernelGGL(colsum_final_kernel<T>, dim3((C + 255) / 256, workers), dim3(256), 0, s, partial, chunks, C, scale_dev,
                            (T *)out_lp, out_stride);
+    });
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+int colsum_blocked_chunks(int R) { return R <= 0 ? 1 : ((R + 63) / 64 + CSB_BLOCKS - 1) / CSB_BLOCKS; }
+
+int colsum_blocked(int dtype, const void *blk, int ncb, int R, int C, float *partial, void *out_lp, hipStream_t s) {
+    KernelTimer timer(KC_AUX, s, 0.0, 0.0);
+    if (C <= 0) return LSTM_OK;
+    const int nrb = (R + 63) / 64, chunks = colsum_blocked_chunks(R);
+    if (dtype == LSTM_DTYPE_FP32 || chunks > 65535 || (C + 63) / 64 > ncb) {
+        set_error("colsum_blocked: unsupported (dtype %d, R=%d, C=%d, ncb=%d)", dtype, R, C, ncb);
+        return LSTM_ERR_UNSUPPORTED;
+    }
+    LSTM_DISPATCH(dtype, T, {
+        if constexpr (sizeof(T) == 2)
+            hipLaunchKernelGGL(colsum_blocked_partial_kernel<T>, dim3((C + 63) / 64, chunks), dim3(256), 0, s, (const T *)blk, ncb, nrb,
+                               C, partial);
+        hipLaunchKernelGGL(colsum_final_kernel<T>, dim3((C + 255) / 256, 1), dim3(256), 0, s, partial, chunks, C, (const float *)nullptr,
+                           (T *)out_lp, (int64_t)0);
     });
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;

@@ -437,10 +437,12 @@ __device__ __forceinline__ void gates_backward_cell(const T *dh_above, const flo
         // packed: [b / 64][gate][j / 64] chunk, fragment order inside; 8 aligned units are one slot
         T *pk = dApk + (((int64_t)(b >> 6) * 4) * nkc + (j0 >> 6)) * A_CHUNK + frag_offset(b & 63, j0 & 63, 2);
         if constexpr (VEC) {
-            *reinterpret_cast<u32x4 *>(da) = *reinterpret_cast<const u32x4 *>(o0);
-            *reinterpret_cast<u32x4 *>(da + H) = *reinterpret_cast<const u32x4 *>(o1);
-            *reinterpret_cast<u32x4 *>(da + 2 * H) = *reinterpret_cast<const u32x4 *>(o2);
-            *reinterpret_cast<u32x4 *>(da + 3 * H) = *reinterpret_cast<const u32x4 *>(o3);
+            if (dA) {                                  // row-major copy only where somebody reads it
+                *reinterpret_cast<u32x4 *>(da) = *reinterpret_cast<const u32x4 *>(o0);
+                *reinterpret_cast<u32x4 *>(da + H) = *reinterpret_cast<const u32x4 *>(o1);
+                *reinterpret_cast<u32x4 *>(da + 2 * H) = *reinterpret_cast<const u32x4 *>(o2);
+                *reinterpret_cast<u32x4 *>(da + 3 * H) = *reinterpret_cast<const u32x4 *>(o3);
+            }
             *reinterpret_cast<u32x4 *>(pk) = *reinterpret_cast<const u32x4 *>(o0);
             *reinterpret_cast<u32x4 *>(pk + gs) = *reinterpret_cast<const u32x4 *>(o1);
             *reinterpret_cast<u32x4 *>(pk + 2 * gs) = *reinterpret_cast<const u32x4 *>(o2);
@@ -448,7 +450,7 @@ __device__ __forceinline__ void gates_backward_cell(const T *dh_above, const flo
 #pragma unroll
             for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(dc_state + e0 + 4 * h) = *reinterpret_cast<const u32x4 *>(dcn + 4 * h);
         } else {
-            da[0] = o0[0]; da[H] = o1[0]; da[2 * H] = o2[0]; da[3 * H] = o3[0];
+            if (dA) { da[0] = o0[0]; da[H] = o1[0]; da[2 * H] = o2[0]; da[3 * H] = o3[0]; }
             pk[0] = o0[0]; pk[gs] = o1[0]; pk[2 * gs] = o2[0]; pk[3 * gs] = o3[0];
             dc_state[e0] = dcn[0];
         }
@@ -643,7 +645,9 @@ int gates_backward_packed(int dtype, const void *dh_above, const float *partials
     int blocks = (int)((items + 255) / 256);
     if (blocks > 8192) blocks = 8192;
     if (blocks < 1) blocks = 1;
-    KernelTimer timer(KC_POINTWISE, s, 0.0, (double)n * (16.0 + 8.0 + 15.0 * 2.0));
+    // per unit: four fp32 partials and the cell gradient read, the cell gradient written, seven
+    // 16-bit values read, four gate gradients written once per copy (packed, row-major, blocked)
+    KernelTimer timer(KC_POINTWISE, s, 0.0, (double)n * (16.0 + 8.0 + 2.0 * (7.0 + 4.0 * (1 + (dA ? 1 : 0) + (dAblk ? 1 : 0)))));
     if (vec) {
         LP_ONLY(dtype, T, hipLaunchKernelGGL((gates_backward_packed_kernel<T, true>), dim3(blocks), dim3(256), 0, s,
                                              (const T *)dh_above, partials, (const T *)gates, (const T *)c_t, (const T *)c_prev,
@@ -730,7 +734,7 @@ int gates_backward_wave(int dtype, const WaveGates *c, int n_cells, int blk_ncb,
     WaveGateArgs w;
     for (int i = 0; i < WAVE_MAX_GATES; ++i) {
         const WaveGates &x = c[i < n_cells ? i : 0];
-        if (!x.gates || !x.c_t || !x.c_prev || !x.dc_state || !x.dA || !x.dApk || (!x.first && !x.partials) || (!x.dh_above && !x.above4)) {
+        if (!x.gates || !x.c_t || !x.c_prev || !x.dc_state || (!x.dA && !x.dAblk) || !x.dApk || (!x.first && !x.partials) || (!x.dh_above && !x.above4)) {
             set_error("gates_backward_wave: null operand in cell %d", i);
             return LSTM_ERR_INVALID;
         }
