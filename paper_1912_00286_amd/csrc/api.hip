@@ -55,6 +55,15 @@ struct Plan {
     // the two sets of K-slice partials (dA U for the step before, dA W for the layer below), cell gradient
     std::vector<size_t> s_wb_dA, s_wb_dablk, s_wb_utpk, s_wb_wtpk, s_wb_dapk, s_wb_partU, s_wb_partW, s_wb_dc;
     std::vector<size_t> wT_off, uT_off;  // byte offsets inside the s_wT region
+    // The row-major copy of dA is only kept where something reads it: with every consumer (dX, dW,
+    // dU, the bias gradient) on the blocked copy it is left out.
+    bool dA_rowmajor_needed(int l) const {
+        if (!blk || W > 1) return true;
+        const int TB = T * B, I = in_dim[l];
+        const bool dx = (l > 0 && !wb) || (l == 0 && V > 0);
+        if (dx && !gemm_blocked_supported(dtype, TB, I)) return true;
+        return !gemm_blocked_supported(dtype, G, I) || !gemm_blocked_supported(dtype, G, H);
+    }
     std::vector<int> split_w, split_u;
 };
 
@@ -222,16 +231,19 @@ int make_plan(const lstm_config *c, Plan &p) {
             // that extra storage stays within a fixed budget; stacks deep enough to be bound by device
             // memory (the capacity experiment of Table 1) keep the layer-by-layer backward pass.
             constexpr size_t kDiagonalBackwardBudget = (size_t)8 << 30;
-            const size_t per_layer = align_up(TB * p.G * p.es) + (p.blk ? align_up(blocked_elems((int)TB, p.G) * p.es) : 0) +
-                                     2 * align_up(rd.utpk_elems * p.es) + align_up(rd.dapk_elems * p.es) +
-                                     2 * align_up(rd.partial_bytes) + align_up((size_t)p.B * p.H * 4);
-            p.wb = per_layer * (size_t)p.L <= kDiagonalBackwardBudget;
+            p.wb = true;                                       // dA_rowmajor_needed() asks as if the form were on
+            size_t extra = 0;
+            for (int l = 0; l < p.L; ++l)
+                extra += (p.dA_rowmajor_needed(l) ? align_up(TB * p.G * p.es) : 0) +
+                         (p.blk ? align_up(blocked_elems((int)TB, p.G) * p.es) : 0) + 2 * align_up(rd.utpk_elems * p.es) +
+                         align_up(rd.dapk_elems * p.es) + 2 * align_up(rd.partial_bytes) + align_up((size_t)p.B * p.H * 4);
+            p.wb = extra <= kDiagonalBackwardBudget;
         }
         if (p.wb) {
             p.s_wb_dA.resize(p.L); p.s_wb_dablk.assign(p.L, 0); p.s_wb_utpk.resize(p.L); p.s_wb_wtpk.assign(p.L, 0);
             p.s_wb_dapk.resize(p.L); p.s_wb_partU.resize(p.L); p.s_wb_partW.assign(p.L, 0); p.s_wb_dc.resize(p.L);
             for (int l = 0; l < p.L; ++l) {
-                p.s_wb_dA[l] = s; s += align_up(TB * p.G * p.es);
+                p.s_wb_dA[l] = s; if (p.dA_rowmajor_needed(l)) s += align_up(TB * p.G * p.es);
                 if (p.blk) { p.s_wb_dablk[l] = s; s += align_up(blocked_elems((int)TB, p.G) * p.es); }
                 p.s_wb_utpk[l] = s; s += align_up(rd.utpk_elems * p.es);
                 if (l > 0) { p.s_wb_wtpk[l] = s; s += align_up(rd.utpk_elems * p.es); }
@@ -602,15 +614,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
     }
     LSTM_TRY(head_backward_bias(p.dtype, dzu, loss_scale, p.head_rows / p.W, grd + p.off_bh * es, s, p.W, p.Bw, p.P));
 
-    // The row-major copy of dA is only written where something reads it: with every consumer (dX,
-    // dW, dU, the bias gradient) on the blocked copy it is left out.
-    auto dA_rowmajor_needed = [&](int l) {
-        if (!p.blk || p.W > 1) return true;
-        const int I = p.in_dim[l];
-        const bool dx = (l > 0 && !p.wb) || (l == 0 && p.V > 0);
-        if (dx && !gemm_blocked_supported(p.dtype, TB, I)) return true;
-        return !gemm_blocked_supported(p.dtype, p.G, I) || !gemm_blocked_supported(p.dtype, p.G, p.H);
-    };
+    auto dA_rowmajor_needed = [&](int l) { return p.dA_rowmajor_needed(l); };
     if (p.wb) {
         // BPTT along anti-diagonals: cell (l, t) needs dA_{l,t+1} U_l (its own layer, one step later) and
         // dA_{l+1,t} W_{l+1} (the layer above, same step), both products of cells on the diagonal before.
