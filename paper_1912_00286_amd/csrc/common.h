@@ -90,14 +90,15 @@ inline size_t dtype_size(int dtype) { return dtype == LSTM_DTYPE_FP32 ? 4 : 2; }
 // ---------------------------------------------------------------- device math
 __device__ inline float sigmoidf_dev(float a) {
     // 1/(1+e^-a); for large |a| the exponential saturates to 0 or inf and the
-    // quotient to 1 or 0, both correct limits.
-    return 1.0f / (1.0f + __expf(-a));
+    // reciprocal to 1 or 0, both correct limits.  The hardware reciprocal (1 ulp)
+    // replaces the IEEE division sequence: the gate epilogues are issue-bound.
+    return __builtin_amdgcn_rcpf(1.0f + __expf(-a));
 }
 __device__ inline float tanhf_dev(float a) {
     // tanh(a) = 1 - 2/(e^{2a}+1); exact limits at +-inf, no cancellation issue
     // beyond fp32 rounding near 0 where the result is ~a.
     float e = __expf(2.0f * a);
-    return 1.0f - 2.0f / (e + 1.0f);
+    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f);
 }
 
 // ---------------------------------------------------------------- optional launch timing

@@ -370,12 +370,13 @@ __global__ __launch_bounds__(256) void lstm_wave_backward_gemm_kernel(WaveBwdGem
 // The gradient arriving from above is dh_above (16-bit, row-major: the head or a whole-sequence
 // data-gradient GEMM) and/or above4 (four fp32 K-slice partials of the per-step product
 // dA_t W of the layer above, used when the backward pass runs along anti-diagonals).
-template <typename T, bool VEC>
+template <typename T, int W>
 __device__ __forceinline__ void gates_backward_cell(const T *dh_above, const float *above4, const float *partials, const T *gates,
                                                     const T *c_t, const T *c_prev, float *dc_state, T *dA, T *dApk, T *dAblk,
                                                     int blk_ncb, int B, int H, int nkc, int first, int64_t thread0,
                                                     int64_t nthreads) {
-    constexpr int W = VEC ? 8 : 1;
+    constexpr bool VEC = W > 1;
+    typedef unsigned int lpvec __attribute__((ext_vector_type(W > 1 ? W / 2 : 1)));   // W 16-bit values
     const int64_t n = (int64_t)B * H;
     const int G = 4 * H;
     const int64_t gs = (int64_t)nkc * A_CHUNK;
@@ -385,16 +386,16 @@ __device__ __forceinline__ void gates_backward_cell(const T *dh_above, const flo
         __attribute__((aligned(16))) float p0[W], p1[W], p2[W], p3[W], dcs[W];
         const T *gr = gates + (int64_t)b * G + j0;
         if constexpr (VEC) {
-            *reinterpret_cast<u32x4 *>(vi) = *reinterpret_cast<const u32x4 *>(gr);
-            *reinterpret_cast<u32x4 *>(vf) = *reinterpret_cast<const u32x4 *>(gr + H);
-            *reinterpret_cast<u32x4 *>(vg) = *reinterpret_cast<const u32x4 *>(gr + 2 * H);
-            *reinterpret_cast<u32x4 *>(vo) = *reinterpret_cast<const u32x4 *>(gr + 3 * H);
-            *reinterpret_cast<u32x4 *>(vct) = *reinterpret_cast<const u32x4 *>(c_t + e0);
-            *reinterpret_cast<u32x4 *>(vcp) = *reinterpret_cast<const u32x4 *>(c_prev + e0);
-            if (dh_above) *reinterpret_cast<u32x4 *>(vdh) = *reinterpret_cast<const u32x4 *>(dh_above + e0);
+            *reinterpret_cast<lpvec *>(vi) = *reinterpret_cast<const lpvec *>(gr);
+            *reinterpret_cast<lpvec *>(vf) = *reinterpret_cast<const lpvec *>(gr + H);
+            *reinterpret_cast<lpvec *>(vg) = *reinterpret_cast<const lpvec *>(gr + 2 * H);
+            *reinterpret_cast<lpvec *>(vo) = *reinterpret_cast<const lpvec *>(gr + 3 * H);
+            *reinterpret_cast<lpvec *>(vct) = *reinterpret_cast<const lpvec *>(c_t + e0);
+            *reinterpret_cast<lpvec *>(vcp) = *reinterpret_cast<const lpvec *>(c_prev + e0);
+            if (dh_above) *reinterpret_cast<lpvec *>(vdh) = *reinterpret_cast<const lpvec *>(dh_above + e0);
             if (!first) {
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
+                for (int h = 0; h < W / 4; ++h) {
                     *reinterpret_cast<u32x4 *>(p0 + 4 * h) = *reinterpret_cast<const u32x4 *>(partials + e0 + 4 * h);
                     *reinterpret_cast<u32x4 *>(p1 + 4 * h) = *reinterpret_cast<const u32x4 *>(partials + n + e0 + 4 * h);
                     *reinterpret_cast<u32x4 *>(p2 + 4 * h) = *reinterpret_cast<const u32x4 *>(partials + 2 * n + e0 + 4 * h);
@@ -438,17 +439,17 @@ __device__ __forceinline__ void gates_backward_cell(const T *dh_above, const flo
         T *pk = dApk + (((int64_t)(b >> 6) * 4) * nkc + (j0 >> 6)) * A_CHUNK + frag_offset(b & 63, j0 & 63, 2);
         if constexpr (VEC) {
             if (dA) {                                  // row-major copy only where somebody reads it
-                *reinterpret_cast<u32x4 *>(da) = *reinterpret_cast<const u32x4 *>(o0);
-                *reinterpret_cast<u32x4 *>(da + H) = *reinterpret_cast<const u32x4 *>(o1);
-                *reinterpret_cast<u32x4 *>(da + 2 * H) = *reinterpret_cast<const u32x4 *>(o2);
-                *reinterpret_cast<u32x4 *>(da + 3 * H) = *reinterpret_cast<const u32x4 *>(o3);
+                *reinterpret_cast<lpvec *>(da) = *reinterpret_cast<const lpvec *>(o0);
+                *reinterpret_cast<lpvec *>(da + H) = *reinterpret_cast<const lpvec *>(o1);
+                *reinterpret_cast<lpvec *>(da + 2 * H) = *reinterpret_cast<const lpvec *>(o2);
+                *reinterpret_cast<lpvec *>(da + 3 * H) = *reinterpret_cast<const lpvec *>(o3);
             }
-            *reinterpret_cast<u32x4 *>(pk) = *reinterpret_cast<const u32x4 *>(o0);
-            *reinterpret_cast<u32x4 *>(pk + gs) = *reinterpret_cast<const u32x4 *>(o1);
-            *reinterpret_cast<u32x4 *>(pk + 2 * gs) = *reinterpret_cast<const u32x4 *>(o2);
-            *reinterpret_cast<u32x4 *>(pk + 3 * gs) = *reinterpret_cast<const u32x4 *>(o3);
+            *reinterpret_cast<lpvec *>(pk) = *reinterpret_cast<const lpvec *>(o0);
+            *reinterpret_cast<lpvec *>(pk + gs) = *reinterpret_cast<const lpvec *>(o1);
+            *reinterpret_cast<lpvec *>(pk + 2 * gs) = *reinterpret_cast<const lpvec *>(o2);
+            *reinterpret_cast<lpvec *>(pk + 3 * gs) = *reinterpret_cast<const lpvec *>(o3);
 #pragma unroll
-            for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(dc_state + e0 + 4 * h) = *reinterpret_cast<const u32x4 *>(dcn + 4 * h);
+            for (int h = 0; h < W / 4; ++h) *reinterpret_cast<u32x4 *>(dc_state + e0 + 4 * h) = *reinterpret_cast<const u32x4 *>(dcn + 4 * h);
         } else {
             if (dA) { da[0] = o0[0]; da[H] = o1[0]; da[2 * H] = o2[0]; da[3 * H] = o3[0]; }
             pk[0] = o0[0]; pk[gs] = o1[0]; pk[2 * gs] = o2[0]; pk[3 * gs] = o3[0];
@@ -462,19 +463,19 @@ __device__ __forceinline__ void gates_backward_cell(const T *dh_above, const flo
                 const int col = g * H + j0;
                 T *d = rowp + (int64_t)(col >> 6) * 4096 + (col & 63);
                 const T *src = g == 0 ? o0 : (g == 1 ? o1 : (g == 2 ? o2 : o3));
-                if constexpr (VEC) *reinterpret_cast<u32x4 *>(d) = *reinterpret_cast<const u32x4 *>(src);
+                if constexpr (VEC) *reinterpret_cast<lpvec *>(d) = *reinterpret_cast<const lpvec *>(src);
                 else d[0] = src[0];
             }
         }
     }
 }
 
-template <typename T, bool VEC>
+template <typename T, int W>
 __global__ __launch_bounds__(256) void gates_backward_packed_kernel(const T *dh_above, const float *partials, const T *gates,
                                                                     const T *c_t, const T *c_prev, float *dc_state, T *dA,
                                                                     T *dApk, T *dAblk, int blk_ncb, int B, int H, int nkc,
                                                                     int first) {
-    gates_backward_cell<T, VEC>(dh_above, nullptr, partials, gates, c_t, c_prev, dc_state, dA, dApk, dAblk, blk_ncb, B, H, nkc, first,
+    gates_backward_cell<T, W>(dh_above, nullptr, partials, gates, c_t, c_prev, dc_state, dA, dApk, dAblk, blk_ncb, B, H, nkc, first,
                                 blockIdx.x * (int64_t)blockDim.x + threadIdx.x, (int64_t)gridDim.x * blockDim.x);
 }
 
@@ -493,12 +494,12 @@ struct WaveGateArgs {
     WaveGateCell cell[WAVE_MAX_GATES];
     int blk_ncb, B, H, nkc, blocks_per_cell;
 };
-template <typename T, bool VEC>
+template <typename T, int W>
 __global__ __launch_bounds__(256) void wave_gates_backward_kernel(WaveGateArgs w) {
     const int ci = blockIdx.x / w.blocks_per_cell;
     const WaveGateCell &c = w.cell[ci];
     const int blk = (int)blockIdx.x - ci * w.blocks_per_cell;
-    gates_backward_cell<T, VEC>((const T *)c.dh_above, c.above4, c.partials, (const T *)c.gates, (const T *)c.c_t, (const T *)c.c_prev,
+    gates_backward_cell<T, W>((const T *)c.dh_above, c.above4, c.partials, (const T *)c.gates, (const T *)c.c_t, (const T *)c.c_prev,
                                 c.dc_state, (T *)c.dA, (T *)c.dApk, (T *)c.dAblk, w.blk_ncb, w.B, w.H, w.nkc, c.first,
                                 blk * (int64_t)blockDim.x + threadIdx.x, (int64_t)w.blocks_per_cell * blockDim.x);
 }
@@ -641,22 +642,24 @@ int gates_backward_packed(int dtype, const void *dh_above, const float *partials
     const uintptr_t all = (uintptr_t)dh_above | (uintptr_t)partials | (uintptr_t)gates | (uintptr_t)c_t | (uintptr_t)c_prev |
                           (uintptr_t)dc_state | (uintptr_t)dA | (uintptr_t)dApk | (uintptr_t)dAblk;
     const bool vec = H % 8 == 0 && all % 16 == 0;
-    const int64_t items = vec ? n / 8 : n;
+    // 8 units per thread (16-byte accesses everywhere); 4 while that would leave fewer than two
+    // wavefronts per SIMD on the chip (the kernel is latency-bound then)
+    const int per_thread = !vec ? 1 : (n / 8 <= 256 * 256 * 2 ? 4 : 8);
+    const int64_t items = n / per_thread;
     int blocks = (int)((items + 255) / 256);
     if (blocks > 8192) blocks = 8192;
     if (blocks < 1) blocks = 1;
     // per unit: four fp32 partials and the cell gradient read, the cell gradient written, seven
     // 16-bit values read, four gate gradients written once per copy (packed, row-major, blocked)
     KernelTimer timer(KC_POINTWISE, s, 0.0, (double)n * (16.0 + 8.0 + 2.0 * (7.0 + 4.0 * (1 + (dA ? 1 : 0) + (dAblk ? 1 : 0)))));
-    if (vec) {
-        LP_ONLY(dtype, T, hipLaunchKernelGGL((gates_backward_packed_kernel<T, true>), dim3(blocks), dim3(256), 0, s,
-                                             (const T *)dh_above, partials, (const T *)gates, (const T *)c_t, (const T *)c_prev,
-                                             dc_state, (T *)dA, (T *)dApk, (T *)dAblk, blk_ncb, B, H, d.nkc, first));
-    } else {
-        LP_ONLY(dtype, T, hipLaunchKernelGGL((gates_backward_packed_kernel<T, false>), dim3(blocks), dim3(256), 0, s,
-                                             (const T *)dh_above, partials, (const T *)gates, (const T *)c_t, (const T *)c_prev,
-                                             dc_state, (T *)dA, (T *)dApk, (T *)dAblk, blk_ncb, B, H, d.nkc, first));
-    }
+#define LSTM_GATES_LAUNCH(W)                                                                                                   \
+    LP_ONLY(dtype, T, hipLaunchKernelGGL((gates_backward_packed_kernel<T, W>), dim3(blocks), dim3(256), 0, s,                  \
+                                         (const T *)dh_above, partials, (const T *)gates, (const T *)c_t, (const T *)c_prev,   \
+                                         dc_state, (T *)dA, (T *)dApk, (T *)dAblk, blk_ncb, B, H, d.nkc, first))
+    if (per_thread == 8) { LSTM_GATES_LAUNCH(8); }
+    else if (per_thread == 4) { LSTM_GATES_LAUNCH(4); }
+    else { LSTM_GATES_LAUNCH(1); }
+#undef LSTM_GATES_LAUNCH
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
@@ -752,9 +755,9 @@ int gates_backward_wave(int dtype, const WaveGates *c, int n_cells, int blk_ncb,
     w.blk_ncb = blk_ncb; w.B = B; w.H = H; w.nkc = d.nkc; w.blocks_per_cell = blocks;
     KernelTimer timer(KC_POINTWISE, s, 0.0, n_cells * (double)n * (16.0 + 8.0 + 15.0 * 2.0));
     if (vec) {
-        LP_ONLY(dtype, T, hipLaunchKernelGGL((wave_gates_backward_kernel<T, true>), dim3(blocks * n_cells), dim3(256), 0, s, w));
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((wave_gates_backward_kernel<T, 8>), dim3(blocks * n_cells), dim3(256), 0, s, w));
     } else {
-        LP_ONLY(dtype, T, hipLaunchKernelGGL((wave_gates_backward_kernel<T, false>), dim3(blocks * n_cells), dim3(256), 0, s, w));
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((wave_gates_backward_kernel<T, 1>), dim3(blocks * n_cells), dim3(256), 0, s, w));
     }
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
