@@ -50,6 +50,8 @@ struct Plan {
            s_colpart = 0, s_dE32 = 0, s_part = 0, s_upk = 0, s_apk[2] = {0, 0}, scratch_bytes = 0;
     // forward along anti-diagonals (cells of several layers per launch): per-layer operands and state
     bool wf = false, wb = false;   // wb: the backward pass too (costs one dA per layer, see make_plan)
+    bool fb = false;               // wb with each cell's products and gate arithmetic in one launch (narrow layers)
+    std::vector<size_t> s_wb_dapk1; // second packed dA per layer (fb: a cell reads one step's while writing the next)
     std::vector<size_t> s_wf_upk, s_wf_wpk, s_wf_c, s_wf_hpk0, s_wf_hpk1;
     // backward along anti-diagonals: per-layer dA (row-major and blocked), packed U^T / W^T, packed dA_t,
     // the two sets of K-slice partials (dA U for the step before, dA W for the layer below), cell gradient
@@ -212,11 +214,11 @@ int make_plan(const lstm_config *c, Plan &p) {
         p.s_wblk = s; s += align_up(blocked_elems(p.G, max_dim) * p.es);
         p.s_dablk = s; s += align_up(blocked_elems((int)TB, p.G) * p.es);
     }
-    if (p.dtype != LSTM_DTYPE_FP32 && p.L >= 2) {
+    if (p.dtype != LSTM_DTYPE_FP32) {
+        const RecurrentDims rd = recurrent_dims(p.B, p.H);
         // Stacks of narrow layers: a time step of one layer is a handful of workgroups, so the
         // forward pass runs along anti-diagonals (all layers' ready cells in one launch).
-        const RecurrentDims rd = recurrent_dims(p.B, p.H);
-        p.wf = rd.n_mt * rd.n_hb <= 128;
+        p.wf = p.L >= 2 && rd.n_mt * rd.n_hb <= 128;
         if (p.wf) {
             p.s_wf_upk.resize(p.L); p.s_wf_wpk.assign(p.L, 0); p.s_wf_c.resize(p.L); p.s_wf_hpk0.resize(p.L); p.s_wf_hpk1.resize(p.L);
             for (int l = 0; l < p.L; ++l) {
@@ -226,6 +228,10 @@ int make_plan(const lstm_config *c, Plan &p) {
                 p.s_wf_hpk1[l] = s; s += align_up(rd.hpk_elems * p.es);
                 p.s_wf_c[l] = s; s += align_up((size_t)p.B * p.H * 4);
             }
+        }
+        // Narrow layers of any depth: each BPTT cell in one launch instead of two.
+        const bool fb_ok = p.W == 1 && fused_backward_supported(p.dtype, p.B, p.H);
+        if (p.wf || fb_ok) {
             // The backward pass along the diagonals keeps every layer's dA (row-major and blocked) until
             // the weight-gradient GEMMs at the end, instead of one layer's at a time.  It is used while
             // that extra storage stays within a fixed budget; stacks deep enough to be bound by device
@@ -236,20 +242,23 @@ int make_plan(const lstm_config *c, Plan &p) {
             for (int l = 0; l < p.L; ++l)
                 extra += (p.dA_rowmajor_needed(l) ? align_up(TB * p.G * p.es) : 0) +
                          (p.blk ? align_up(blocked_elems((int)TB, p.G) * p.es) : 0) + 2 * align_up(rd.utpk_elems * p.es) +
-                         align_up(rd.dapk_elems * p.es) + 2 * align_up(rd.partial_bytes) + align_up((size_t)p.B * p.H * 4);
+                         2 * align_up(rd.dapk_elems * p.es) + 2 * align_up(rd.partial_bytes) + align_up((size_t)p.B * p.H * 4);
             p.wb = extra <= kDiagonalBackwardBudget;
         }
+        p.fb = p.wb && fb_ok;
         if (p.wb) {
             p.s_wb_dA.resize(p.L); p.s_wb_dablk.assign(p.L, 0); p.s_wb_utpk.resize(p.L); p.s_wb_wtpk.assign(p.L, 0);
-            p.s_wb_dapk.resize(p.L); p.s_wb_partU.resize(p.L); p.s_wb_partW.assign(p.L, 0); p.s_wb_dc.resize(p.L);
+            p.s_wb_dapk.resize(p.L); p.s_wb_dapk1.assign(p.L, 0); p.s_wb_partU.resize(p.L); p.s_wb_partW.assign(p.L, 0);
+            p.s_wb_dc.resize(p.L);
             for (int l = 0; l < p.L; ++l) {
                 p.s_wb_dA[l] = s; if (p.dA_rowmajor_needed(l)) s += align_up(TB * p.G * p.es);
                 if (p.blk) { p.s_wb_dablk[l] = s; s += align_up(blocked_elems((int)TB, p.G) * p.es); }
                 p.s_wb_utpk[l] = s; s += align_up(rd.utpk_elems * p.es);
                 if (l > 0) { p.s_wb_wtpk[l] = s; s += align_up(rd.utpk_elems * p.es); }
                 p.s_wb_dapk[l] = s; s += align_up(rd.dapk_elems * p.es);
-                p.s_wb_partU[l] = s; s += align_up(rd.partial_bytes);
-                if (l > 0) { p.s_wb_partW[l] = s; s += align_up(rd.partial_bytes); }
+                if (p.fb) { p.s_wb_dapk1[l] = s; s += align_up(rd.dapk_elems * p.es); }
+                p.s_wb_partU[l] = s; if (!p.fb) s += align_up(rd.partial_bytes);
+                if (l > 0 && !p.fb) { p.s_wb_partW[l] = s; s += align_up(rd.partial_bytes); }
                 p.s_wb_dc[l] = s; s += align_up((size_t)p.B * p.H * 4);
             }
         }
@@ -627,10 +636,44 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             if (p.blk && p.G % 64 != 0)
                 LSTM_TRY(fill_u32(at(scratch, p.s_wb_dablk[l]), 0, (int64_t)(blocked_elems(TB, p.G) * es / 4), s));
         }
+        if (p.fb) {
+            for (int l = 0; l < p.L; ++l)
+                LSTM_TRY(fill_u32(at(scratch, p.s_wb_dapk1[l]), 0, (int64_t)((rd.dapk_elems * es + 3) / 4), s));
+            // one launch per diagonal: every cell contracts over all 4H gate rows itself
+            const int max_cells = fused_backward_max_cells();
+            std::vector<FusedBackwardCell> fc;
+            for (int d = 0; d < p.T + p.L - 1; ++d) {
+                fc.clear();
+                for (int l = p.L - 1; l >= 0; --l) {
+                    const int t = p.T - 1 - (d - (p.L - 1 - l));
+                    if (t < 0 || t >= p.T) continue;
+                    auto dapk = [&](int layer, int step) { return at(scratch, (step & 1) ? p.s_wb_dapk1[layer] : p.s_wb_dapk[layer]); };
+                    FusedBackwardCell c{};
+                    const bool top_layer = l == p.L - 1, last = t == p.T - 1;
+                    c.dApk_next = last ? nullptr : dapk(l, t + 1);
+                    c.UTpk = last ? nullptr : at(scratch, p.s_wb_utpk[l]);
+                    c.dApk_above = top_layer ? nullptr : dapk(l + 1, t);
+                    c.WTpk = top_layer ? nullptr : at(scratch, p.s_wb_wtpk[l + 1]);
+                    c.dh_above = top_layer ? dh_above + (size_t)t * BH * es : nullptr;
+                    c.gates = at(reserve, p.r_gates[l]) + (size_t)t * p.B * p.G * es;
+                    c.c_t = at(reserve, p.r_c[l]) + (size_t)(t + 1) * BH * es;
+                    c.c_prev = at(reserve, p.r_c[l]) + (size_t)t * BH * es;
+                    c.dc_state = (float *)at(scratch, p.s_wb_dc[l]);
+                    c.dA = dA_rowmajor_needed(l) ? at(scratch, p.s_wb_dA[l]) + (size_t)t * p.B * p.G * es : nullptr;
+                    c.dApk = dapk(l, t);
+                    c.dAblk = p.blk ? at(scratch, p.s_wb_dablk[l]) + (size_t)t * (p.B / 64) * p.g_ncb * 4096 * es : nullptr;
+                    c.first = last ? 1 : 0;
+                    fc.push_back(c);
+                }
+                for (size_t i = 0; i < fc.size(); i += max_cells)
+                    LSTM_TRY(backward_fused_wave(p.dtype, fc.data() + i, (int)std::min<size_t>(max_cells, fc.size() - i), p.g_ncb, p.B,
+                                                 p.H, s));
+            }
+        }
         const int max_gates = wave_backward_max_gates(), max_gemms = wave_backward_max_gemms();
         std::vector<WaveGates> gc;
         std::vector<WaveGemm> mm;
-        for (int d = 0; d < p.T + p.L - 1; ++d) {
+        for (int d = 0; d < (p.fb ? 0 : p.T + p.L - 1); ++d) {
             gc.clear(); mm.clear();
             for (int l = p.L - 1; l >= 0; --l) {
                 const int t = p.T - 1 - (d - (p.L - 1 - l));

@@ -115,6 +115,21 @@ int wave_backward_max_gemms();
 int wave_backward_max_gates();
 int step_backward_gemm_wave(int dtype, const WaveGemm *g, int n, int B, int H, hipStream_t s);
 int gates_backward_wave(int dtype, const WaveGates *c, int n_cells, int blk_ncb, int B, int H, hipStream_t s);
+// One BPTT cell done in a single launch (narrow layers): the recurrent products and the gate
+// arithmetic together.  dApk_next / UTpk: packed dA_{t+1} and U^T of the cell's layer (null at the
+// last time step); dApk_above / WTpk: packed dA_t and W^T of the layer above (null for the top
+// layer, whose gradient arrives in dh_above).
+struct FusedBackwardCell {
+    const void *dApk_next, *UTpk, *dApk_above, *WTpk;
+    const void *dh_above;     // lp [B,H] or null
+    const void *gates, *c_t, *c_prev;
+    float *dc_state;
+    void *dA, *dApk, *dAblk;  // dA row-major (nullable), packed (the next step's operand), blocked (nullable)
+    int first;
+};
+int fused_backward_max_cells();
+bool fused_backward_supported(int dtype, int B, int H);
+int backward_fused_wave(int dtype, const FusedBackwardCell *c, int n_cells, int blk_ncb, int B, int H, hipStream_t s);
 int wave_forward_max_cells();
 int step_forward_wave(int dtype, const WaveCell *cells, int n_cells, int blk_ncb, int B, int H, hipStream_t s);
 

@@ -504,6 +504,266 @@ __global__ __launch_bounds__(256) void wave_gates_backward_kernel(WaveGateArgs w
                                 blk * (int64_t)blockDim.x + threadIdx.x, (int64_t)w.blocks_per_cell * blockDim.x);
 }
 
+// ---------------------------------------------------------------- fused backward cell
+// Narrow layers: a BPTT step is a handful of workgroups, so what counts is the number of
+// dependent launches.  Here one launch does the whole cell.  A workgroup owns 64 batch rows
+// x 32 hidden units and contracts over ALL 4H gate rows of dA_{t+1} U (and of dA_t W of the
+// layer above) itself, its four wavefronts splitting that range: the gradient reaching its
+// units is then complete inside the workgroup, and the gate arithmetic of those units follows
+// in the epilogue (the two-launch form splits the contraction over workgroups and needs a
+// second kernel to sum the slices).  Operands and outputs are the packed ones of the other
+// kernels; of a 128-row B chunk only this workgroup's 32-row block is read.
+constexpr int FUSED_MAX_CELLS = 8;
+constexpr int TILE_LD = 36;               // floats per row of the summed 64x32 tile (16-byte aligned rows)
+struct FusedBwdCell {
+    const void *dApk_next, *UTpk, *dApk_above, *WTpk, *dh_above, *gates, *c_t, *c_prev;
+    float *dc_state;
+    void *dA, *dApk, *dAblk;
+    int first;
+};
+struct FusedBwdArgs {
+    FusedBwdCell cell[FUSED_MAX_CELLS];
+    int blk_ncb, B, H, n_mt, nkc, wgs_per_cell;
+};
+
+__device__ __forceinline__ void load_narrow(u32x4 (&ra)[NLD_A], u32x4 (&rb)[SK / 16], const u32x4 *a, const u32x4 *b, int lane) {
+#pragma unroll
+    for (int i = 0; i < NLD_A; ++i) ra[i] = a[lane + 64 * i];
+#pragma unroll
+    for (int ks = 0; ks < SK / 16; ++ks) rb[ks] = b[lane + 64 * NBLK * ks];     // one 32-row block of each k-step
+}
+template <typename T>
+__device__ __forceinline__ void mfma_narrow(const u32x4 (&ra)[NLD_A], const u32x4 (&rb)[SK / 16], v16f (&acc)[2]) {
+#pragma unroll
+    for (int ks = 0; ks < SK / 16; ++ks)
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) acc[mb] = Lp<T>::mfma(ra[ks * 2 + mb], rb[ks], acc[mb]);
+}
+// acc += sum over the chunks k in [c0, c1) of the list [pair 1: n1 chunks][pair 2] of (64-row A chunk)
+// x (one 32-row block of the B chunk)^T; B1 / B2 already point at the block.  These kernels are bound
+// by latency, not bandwidth: NS chunks are requested before the first one is used.
+template <typename T, int NS>
+__device__ __forceinline__ void narrow_mainloop(const uint16_t *A1, const uint16_t *B1, const uint16_t *A2, const uint16_t *B2,
+                                                int n1, int c0, int c1, int lane, v16f (&acc)[2]) {
+    if (c1 <= c0) return;
+    auto pa = [&](int k) { return reinterpret_cast<const u32x4 *>(k < n1 ? A1 + (int64_t)k * A_CHUNK : A2 + (int64_t)(k - n1) * A_CHUNK); };
+    auto pb = [&](int k) { return reinterpret_cast<const u32x4 *>(k < n1 ? B1 + (int64_t)k * B_CHUNK : B2 + (int64_t)(k - n1) * B_CHUNK); };
+    u32x4 ra[NS][NLD_A], rb[NS][SK / 16];
+#pragma unroll
+    for (int i = 0; i < NS; ++i)
+        if (c0 + i < c1) load_narrow(ra[i], rb[i], pa(c0 + i), pb(c0 + i), lane);
+    int k = c0;
+    for (; k + 2 * NS <= c1; k += NS) {        // branch-free body: every refill is in range
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+            mfma_narrow<T>(ra[i], rb[i], acc);
+            load_narrow(ra[i], rb[i], pa(k + NS + i), pb(k + NS + i), lane);
+        }
+    }
+    // fewer than 2 NS chunks left; set i holds chunk k + i
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+        if (k + i < c1) mfma_narrow<T>(ra[i], rb[i], acc);
+        if (k + NS + i < c1) load_narrow(ra[i], rb[i], pa(k + NS + i), pb(k + NS + i), lane);
+    }
+#pragma unroll
+    for (int i = 0; i < NS - 1; ++i)
+        if (k + NS + i < c1) mfma_narrow<T>(ra[i], rb[i], acc);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void lstm_fused_backward_kernel(FusedBwdArgs w) {
+    const int ci = blockIdx.x / w.wgs_per_cell;                  // uniform: the cell's argument block
+    const FusedBwdCell &c = w.cell[ci];
+    const int tile = (int)blockIdx.x - ci * w.wgs_per_cell;
+    const int mt = tile % w.n_mt, ub = tile / w.n_mt;            // batch tile of 64, unit block of 32
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nt = ub >> 2, nb = ub & 3;
+    const int H = w.H, G = 4 * w.H;
+    // the epilogue's operands do not depend on the products: one thread per batch row and 8
+    // consecutive units requests them first
+    const int row = tid >> 2, ug = tid & 3;
+    const int b = mt * TM + row, j0 = ub * 32 + ug * 8;
+    const bool valid = b < w.B && j0 < H;
+    const int64_t e0 = (int64_t)b * H + j0;
+    __attribute__((aligned(16))) T vi[8], vf[8], vg[8], vo[8], vct[8], vcp[8], vdh[8];
+    __attribute__((aligned(16))) float dcs[8];
+    if (valid) {
+        const T *gr = reinterpret_cast<const T *>(c.gates) + (int64_t)b * G + j0;
+        *reinterpret_cast<u32x4 *>(vi) = *reinterpret_cast<const u32x4 *>(gr);
+        *reinterpret_cast<u32x4 *>(vf) = *reinterpret_cast<const u32x4 *>(gr + H);
+        *reinterpret_cast<u32x4 *>(vg) = *reinterpret_cast<const u32x4 *>(gr + 2 * H);
+        *reinterpret_cast<u32x4 *>(vo) = *reinterpret_cast<const u32x4 *>(gr + 3 * H);
+        *reinterpret_cast<u32x4 *>(vct) = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(c.c_t) + e0);
+        *reinterpret_cast<u32x4 *>(vcp) = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(c.c_prev) + e0);
+        if (c.dh_above) *reinterpret_cast<u32x4 *>(vdh) = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(c.dh_above) + e0);
+        if (!c.first) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(dcs + 4 * h) = *reinterpret_cast<const u32x4 *>(c.dc_state + e0 + 4 * h);
+        }
+    }
+    // chunk list: [dA_{t+1} x U^T: 4 nkc chunks][dA_t(above) x W^T: 4 nkc chunks], either part may be absent
+    const int per = 4 * w.nkc;
+    const int n1 = c.dApk_next ? per : 0, nch = n1 + (c.dApk_above ? per : 0);
+    const int cpw = (nch + 3) / 4;
+    const int c0 = min(nch, wave * cpw), c1 = min(nch, c0 + cpw);
+    v16f acc[2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[mb][r] = 0.0f;
+    narrow_mainloop<T, 4>(reinterpret_cast<const uint16_t *>(c.dApk_next) + (int64_t)mt * per * A_CHUNK,
+                          reinterpret_cast<const uint16_t *>(c.UTpk) + (int64_t)nt * per * B_CHUNK + nb * 64 * 8,
+                          reinterpret_cast<const uint16_t *>(c.dApk_above) + (int64_t)mt * per * A_CHUNK,
+                          reinterpret_cast<const uint16_t *>(c.WTpk) + (int64_t)nt * per * B_CHUNK + nb * 64 * 8, n1, c0, c1, lane, acc);
+    // sum the four wavefronts' accumulators and lay the 64x32 tile out row by row
+    __shared__ __attribute__((aligned(16))) float red[4 * 32 * 64];
+    __shared__ __attribute__((aligned(16))) float sums[64 * TILE_LD];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) red[(wave * 32 + mb * 16 + r) * 64 + lane] = acc[mb][r];
+    __syncthreads();
+    {
+        const int mb = wave >> 1, rh = (wave & 1) * 8;
+#pragma unroll
+        for (int rr = 0; rr < 8; ++rr) {
+            const int r = rh + rr, idx = (mb * 16 + r) * 64 + lane;
+            const float v = (red[idx] + red[2048 + idx]) + (red[4096 + idx] + red[6144 + idx]);
+            sums[(mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * TILE_LD + (lane & 31)] = v;
+        }
+    }
+    __syncthreads();
+    // gate arithmetic of the thread's 8 units
+    if (!valid) return;
+    __attribute__((aligned(16))) float rec[8];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(rec + 4 * h) = *reinterpret_cast<const u32x4 *>(sums + row * TILE_LD + ug * 8 + 4 * h);
+    __attribute__((aligned(16))) T o0[8], o1[8], o2[8], o3[8];
+    __attribute__((aligned(16))) float dcn[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const float i = Lp<T>::to_f(vi[k]), f = Lp<T>::to_f(vf[k]), g = Lp<T>::to_f(vg[k]), o = Lp<T>::to_f(vo[k]);
+        const float tc = tanhf_dev(Lp<T>::to_f(vct[k]));
+        const float dh = (c.dh_above ? Lp<T>::to_f(vdh[k]) : 0.0f) + rec[k];
+        const float dcr = c.first ? 0.0f : dcs[k];
+        const float d_o = dh * tc;
+        const float dc = dcr + dh * o * (1.0f - tc * tc);
+        const float di = dc * g, dg = dc * i, df = dc * Lp<T>::to_f(vcp[k]);
+        dcn[k] = dc * f;
+        o0[k] = Lp<T>::from_f(di * i * (1.0f - i));
+        o1[k] = Lp<T>::from_f(df * f * (1.0f - f));
+        o2[k] = Lp<T>::from_f(dg * (1.0f - g * g));
+        o3[k] = Lp<T>::from_f(d_o * o * (1.0f - o));
+    }
+    const int64_t gs = (int64_t)w.nkc * A_CHUNK;
+    T *pk = reinterpret_cast<T *>(c.dApk) + (((int64_t)(b >> 6) * 4) * w.nkc + (j0 >> 6)) * A_CHUNK + frag_offset(b & 63, j0 & 63, 2);
+    *reinterpret_cast<u32x4 *>(pk) = *reinterpret_cast<const u32x4 *>(o0);
+    *reinterpret_cast<u32x4 *>(pk + gs) = *reinterpret_cast<const u32x4 *>(o1);
+    *reinterpret_cast<u32x4 *>(pk + 2 * gs) = *reinterpret_cast<const u32x4 *>(o2);
+    *reinterpret_cast<u32x4 *>(pk + 3 * gs) = *reinterpret_cast<const u32x4 *>(o3);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(c.dc_state + e0 + 4 * h) = *reinterpret_cast<const u32x4 *>(dcn + 4 * h);
+    if (c.dA) {
+        T *da = reinterpret_cast<T *>(c.dA) + (int64_t)b * G + j0;
+        *reinterpret_cast<u32x4 *>(da) = *reinterpret_cast<const u32x4 *>(o0);
+        *reinterpret_cast<u32x4 *>(da + H) = *reinterpret_cast<const u32x4 *>(o1);
+        *reinterpret_cast<u32x4 *>(da + 2 * H) = *reinterpret_cast<const u32x4 *>(o2);
+        *reinterpret_cast<u32x4 *>(da + 3 * H) = *reinterpret_cast<const u32x4 *>(o3);
+    }
+    if (c.dAblk) {
+        T *rowp = reinterpret_cast<T *>(c.dAblk) + (int64_t)(b >> 6) * w.blk_ncb * 4096 + (b & 63) * 64;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int col = g * H + j0;
+            const T *src = g == 0 ? o0 : (g == 1 ? o1 : (g == 2 ? o2 : o3));
+            *reinterpret_cast<u32x4 *>(rowp + (int64_t)(col >> 6) * 4096 + (col & 63)) = *reinterpret_cast<const u32x4 *>(src);
+        }
+    }
+}
+
+// ---------------------------------------------------------------- narrow forward cell
+// The forward counterpart for narrow layers (H % 8 == 0): a workgroup owns 64 batch rows x 32
+// hidden units, wavefront q computes gate q's pre-activations over the whole K range (no
+// partial sums to add up), the four gates meet through 36 KB of LDS, and one thread per batch
+// row and 8 units does the cell update with 16-byte accesses throughout; the operands of that
+// update are requested before the products start.
+template <typename T>
+__global__ __launch_bounds__(256) void lstm_narrow_forward_kernel(WaveFwdArgs w) {
+    const int ci = blockIdx.x / w.wgs_per_cell;
+    const FwdArgs &a = w.cell[ci];
+    const int tile = (int)blockIdx.x - ci * w.wgs_per_cell;
+    const int mt = tile % a.n_mt, hb = tile / a.n_mt;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int H = a.H, G = 4 * a.H;
+    const int row = tid >> 2, ug = tid & 3;
+    const int b = mt * TM + row, j0 = hb * 32 + ug * 8;
+    const bool valid = b < a.B && j0 < H;
+    const int64_t e0 = (int64_t)b * H + j0;
+    __attribute__((aligned(16))) T vax[4][8];
+    __attribute__((aligned(16))) float cprev[8];
+    if (valid) {
+        // input projection (bias included) of this step, or just the bias when the cell projects its own input
+        const T *ax = a.Ax ? reinterpret_cast<const T *>(a.Ax) + (int64_t)b * G + j0 : reinterpret_cast<const T *>(a.bias) + j0;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) *reinterpret_cast<u32x4 *>(vax[g]) = *reinterpret_cast<const u32x4 *>(ax + g * H);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(cprev + 4 * h) = *reinterpret_cast<const u32x4 *>(a.c_state + e0 + 4 * h);
+    }
+    const int nch = a.Ax ? a.nkc : 2 * a.nkc;
+    v16f acc[2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[mb][r] = 0.0f;
+    narrow_mainloop<T, 4>(reinterpret_cast<const uint16_t *>(a.hpk_prev) + (int64_t)mt * a.nkc * A_CHUNK,
+                          reinterpret_cast<const uint16_t *>(a.Upk) + (int64_t)hb * a.nkc * B_CHUNK + wave * 64 * 8,
+                          reinterpret_cast<const uint16_t *>(a.xpk) + (int64_t)mt * a.nkc * A_CHUNK,
+                          reinterpret_cast<const uint16_t *>(a.Wpk) + (int64_t)hb * a.nkc * B_CHUNK + wave * 64 * 8, a.nkc, 0, nch, lane, acc);
+    __shared__ __attribute__((aligned(16))) float pre[4 * 64 * TILE_LD];     // [gate][row][unit]
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            pre[(wave * 64 + mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * TILE_LD + (lane & 31)] = acc[mb][r];
+    __syncthreads();
+    if (!valid) return;
+    __attribute__((aligned(16))) float pz[4][8];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            *reinterpret_cast<u32x4 *>(pz[g] + 4 * h) = *reinterpret_cast<const u32x4 *>(pre + (g * 64 + row) * TILE_LD + ug * 8 + 4 * h);
+    __attribute__((aligned(16))) T oi[8], of[8], og[8], oo[8], oc[8], oh[8];
+    __attribute__((aligned(16))) float cn[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const float gi = sigmoidf_dev(pz[0][k] + Lp<T>::to_f(vax[0][k]));
+        const float gf = sigmoidf_dev(pz[1][k] + Lp<T>::to_f(vax[1][k]));
+        const float gg = tanhf_dev(pz[2][k] + Lp<T>::to_f(vax[2][k]));
+        const float go = sigmoidf_dev(pz[3][k] + Lp<T>::to_f(vax[3][k]));
+        const float cc = gf * cprev[k] + gi * gg;
+        cn[k] = cc;
+        oi[k] = Lp<T>::from_f(gi); of[k] = Lp<T>::from_f(gf); og[k] = Lp<T>::from_f(gg); oo[k] = Lp<T>::from_f(go);
+        oc[k] = Lp<T>::from_f(cc);
+        oh[k] = Lp<T>::from_f(go * tanhf_dev(cc));
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(a.c_state + e0 + 4 * h) = *reinterpret_cast<const u32x4 *>(cn + 4 * h);
+    T *gr = reinterpret_cast<T *>(a.gates) + (int64_t)b * G + j0;
+    *reinterpret_cast<u32x4 *>(gr) = *reinterpret_cast<const u32x4 *>(oi);
+    *reinterpret_cast<u32x4 *>(gr + H) = *reinterpret_cast<const u32x4 *>(of);
+    *reinterpret_cast<u32x4 *>(gr + 2 * H) = *reinterpret_cast<const u32x4 *>(og);
+    *reinterpret_cast<u32x4 *>(gr + 3 * H) = *reinterpret_cast<const u32x4 *>(oo);
+    *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.c_out) + e0) = *reinterpret_cast<const u32x4 *>(oc);
+    *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.h_out) + e0) = *reinterpret_cast<const u32x4 *>(oh);
+    *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.hpk_next) + ((int64_t)mt * a.nkc + (j0 >> 6)) * A_CHUNK + frag_offset(row, j0 & 63, 2)) =
+        *reinterpret_cast<const u32x4 *>(oh);
+    if (a.h_blk)
+        *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.h_blk) + ((int64_t)(b >> 6) * a.blk_ncb + (j0 >> 6)) * 4096 + (b & 63) * 64 + (j0 & 63)) =
+            *reinterpret_cast<const u32x4 *>(oh);
+}
+
 // ---------------------------------------------------------------- packing
 // chunk (hb, kc) of Upk, row g*32 + r, column kk = U[g*H + hb*32 + r][kc*64 + kk], zero outside
 template <typename T>
@@ -562,6 +822,8 @@ RecurrentDims recurrent_dims(int B, int H) {
 
 // Few K chunks and many batch tiles: one-wavefront workgroups, one 64-row tile each over the
 // whole K range, instead of a four-way K split with an LDS reduction.
+// Narrow layers (a cell is at most 128 workgroups of 64 rows x 32 units) with 16-byte-friendly width.
+static bool narrow_cells(const RecurrentDims &d, int H) { return H % 8 == 0 && d.n_mt * d.n_hb <= 128; }
 static bool recurrent_wide(const RecurrentDims &d) { return d.nkc <= 8 && d.n_mt >= 16; }   // H <= 512, B >= 961
 
 #define LP_ONLY(dtype, T, ...)                                                       \
@@ -601,6 +863,12 @@ int step_forward_fused(int dtype, const void *hpk_prev, const void *Upk, const v
     a.xpk = nullptr; a.Wpk = nullptr; a.bias = nullptr;
     a.hpk_next = hpk_next; a.h_blk = h_blk; a.blk_ncb = blk_ncb;
     a.B = B; a.H = H; a.n_mt = d.n_mt; a.nkc = d.nkc;
+    if (narrow_cells(d, H)) {                                  // a few dozen workgroups: the latency-lean kernel
+        WaveCell c{};
+        c.hpk_prev = hpk_prev; c.Upk = Upk; c.Ax = Ax; c.c_state = c_state; c.gates = gates; c.c_out = c_out; c.h_out = h_out;
+        c.hpk_next = hpk_next; c.h_blk = h_blk;
+        return step_forward_wave(dtype, &c, 1, blk_ncb, B, H, s);
+    }
     const bool wide = recurrent_wide(d);
     const int grid = d.n_mt * d.n_hb;
     // operands once: U, h, Ax read, gates, c, h (row-major + packed [+ blocked]) written in storage, cell state fp32 both ways
@@ -664,6 +932,52 @@ int gates_backward_packed(int dtype, const void *dh_above, const float *partials
     return LSTM_OK;
 }
 
+int fused_backward_max_cells() { return FUSED_MAX_CELLS; }
+
+// 16-byte accesses need H % 8 == 0; worth it while a cell is a few dozen workgroups
+bool fused_backward_supported(int dtype, int B, int H) {
+    if (dtype != LSTM_DTYPE_FP16 && dtype != LSTM_DTYPE_BF16) return false;
+    return narrow_cells(recurrent_dims(B, H), H);
+}
+
+int backward_fused_wave(int dtype, const FusedBackwardCell *c, int n_cells, int blk_ncb, int B, int H, hipStream_t s) {
+    const RecurrentDims d = recurrent_dims(B, H);
+    if (n_cells < 1 || n_cells > FUSED_MAX_CELLS || H % 8 != 0) {
+        set_error("backward_fused_wave: %d cells (1..%d), H = %d (multiple of 8)", n_cells, FUSED_MAX_CELLS, H);
+        return LSTM_ERR_INVALID;
+    }
+    FusedBwdArgs w;
+    uintptr_t all = 0;
+    double chunks = 0.0;
+    for (int i = 0; i < FUSED_MAX_CELLS; ++i) {
+        const FusedBackwardCell &x = c[i < n_cells ? i : 0];
+        if (!x.gates || !x.c_t || !x.c_prev || !x.dc_state || !x.dApk || (!x.dA && !x.dAblk) || (!x.dApk_next != !x.UTpk) ||
+            (!x.dApk_above != !x.WTpk) || (!x.dApk_above && !x.dh_above) || (!x.first && !x.dApk_next)) {
+            set_error("backward_fused_wave: inconsistent operands in cell %d", i);
+            return LSTM_ERR_INVALID;
+        }
+        all |= (uintptr_t)x.dApk_next | (uintptr_t)x.UTpk | (uintptr_t)x.dApk_above | (uintptr_t)x.WTpk | (uintptr_t)x.dh_above |
+               (uintptr_t)x.gates | (uintptr_t)x.c_t | (uintptr_t)x.c_prev | (uintptr_t)x.dc_state | (uintptr_t)x.dA |
+               (uintptr_t)x.dApk | (uintptr_t)x.dAblk;
+        FusedBwdCell &o = w.cell[i];
+        o.dApk_next = x.dApk_next; o.UTpk = x.UTpk; o.dApk_above = x.dApk_above; o.WTpk = x.WTpk; o.dh_above = x.dh_above;
+        o.gates = x.gates; o.c_t = x.c_t; o.c_prev = x.c_prev; o.dc_state = x.dc_state; o.dA = x.dA; o.dApk = x.dApk;
+        o.dAblk = x.dAblk; o.first = x.first;
+        if (i < n_cells) chunks += (x.dApk_next ? 1.0 : 0.0) + (x.dApk_above ? 1.0 : 0.0);
+    }
+    if (all % 16 != 0) {
+        set_error("backward_fused_wave: operands must be 16-byte aligned");
+        return LSTM_ERR_INVALID;
+    }
+    w.blk_ncb = blk_ncb; w.B = B; w.H = H; w.n_mt = d.n_mt; w.nkc = d.nkc; w.wgs_per_cell = d.n_mt * d.n_hb;
+    const double n = (double)B * H;
+    // products: 2 B H 4H flops, operands once; gate arithmetic: as in the stand-alone kernel without the partials
+    KernelTimer timer(KC_GEMM_STEP, s, chunks * 2.0 * n * 4.0 * H, chunks * 2.0 * (4.0 * H * H + 4.0 * n) + n_cells * n * (8.0 + 15.0 * 2.0));
+    LP_ONLY(dtype, T, hipLaunchKernelGGL(lstm_fused_backward_kernel<T>, dim3(w.wgs_per_cell * n_cells), dim3(256), 0, s, w));
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
 int wave_forward_max_cells() { return WAVE_MAX_CELLS; }
 
 int step_forward_wave(int dtype, const WaveCell *cells, int n_cells, int blk_ncb, int B, int H, hipStream_t s) {
@@ -674,12 +988,15 @@ int step_forward_wave(int dtype, const WaveCell *cells, int n_cells, int blk_ncb
     }
     WaveFwdArgs w;
     w.wgs_per_cell = d.n_mt * d.n_hb;
+    uintptr_t all = 0;
     for (int i = 0; i < WAVE_MAX_CELLS; ++i) {
         const WaveCell &c = cells[i < n_cells ? i : 0];
         if (!c.hpk_prev || !c.Upk || !c.c_state || !c.gates || !c.c_out || !c.h_out || !c.hpk_next || (!c.Ax && (!c.xpk || !c.Wpk || !c.bias))) {
             set_error("step_forward_wave: null operand in cell %d", i);
             return LSTM_ERR_INVALID;
         }
+        all |= (uintptr_t)c.hpk_prev | (uintptr_t)c.Upk | (uintptr_t)c.Ax | (uintptr_t)c.xpk | (uintptr_t)c.Wpk | (uintptr_t)c.bias |
+               (uintptr_t)c.c_state | (uintptr_t)c.gates | (uintptr_t)c.c_out | (uintptr_t)c.h_out | (uintptr_t)c.hpk_next | (uintptr_t)c.h_blk;
         FwdArgs &a = w.cell[i];
         a.hpk_prev = c.hpk_prev; a.Upk = c.Upk; a.Ax = c.Ax; a.xpk = c.xpk; a.Wpk = c.Wpk; a.bias = c.bias;
         a.c_state = c.c_state; a.gates = c.gates; a.c_out = c.c_out; a.h_out = c.h_out; a.hpk_next = c.hpk_next; a.h_blk = c.h_blk;
@@ -696,7 +1013,11 @@ int step_forward_wave(int dtype, const WaveCell *cells, int n_cells, int blk_ncb
                  2.0 * (4.0 * bh + bh + (cells[i].h_blk ? 3.0 : 2.0) * bh) + 4.0 * bh;
     }
     KernelTimer timer(KC_GEMM_STEP, s, flops, bytes);
-    LP_ONLY(dtype, T, hipLaunchKernelGGL(lstm_wave_forward_kernel<T>, dim3(w.wgs_per_cell * n_cells), dim3(256), 0, s, w));
+    if (narrow_cells(d, H) && all % 16 == 0) {
+        LP_ONLY(dtype, T, hipLaunchKernelGGL(lstm_narrow_forward_kernel<T>, dim3(w.wgs_per_cell * n_cells), dim3(256), 0, s, w));
+    } else {
+        LP_ONLY(dtype, T, hipLaunchKernelGGL(lstm_wave_forward_kernel<T>, dim3(w.wgs_per_cell * n_cells), dim3(256), 0, s, w));
+    }
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
