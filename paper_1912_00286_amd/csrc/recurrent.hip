@@ -523,68 +523,75 @@ struct FusedBwdCell {
 };
 struct FusedBwdArgs {
     FusedBwdCell cell[FUSED_MAX_CELLS];
-    int blk_ncb, B, H, n_mt, nkc, wgs_per_cell;
+    int blk_ncb, B, H, n_rt, nkc, wgs_per_cell;
 };
 
-__device__ __forceinline__ void load_narrow(u32x4 (&ra)[NLD_A], u32x4 (&rb)[SK / 16], const u32x4 *a, const u32x4 *b, int lane) {
-#pragma unroll
-    for (int i = 0; i < NLD_A; ++i) ra[i] = a[lane + 64 * i];
-#pragma unroll
-    for (int ks = 0; ks < SK / 16; ++ks) rb[ks] = b[lane + 64 * NBLK * ks];     // one 32-row block of each k-step
-}
-template <typename T>
-__device__ __forceinline__ void mfma_narrow(const u32x4 (&ra)[NLD_A], const u32x4 (&rb)[SK / 16], v16f (&acc)[2]) {
+// MB 32-row blocks of the 64-row A chunk (MB = 1: `a` already points at the block) and one 32-row
+// block of the B chunk
+template <int MB>
+__device__ __forceinline__ void load_narrow(u32x4 (&ra)[MB * SK / 16], u32x4 (&rb)[SK / 16], const u32x4 *a, const u32x4 *b, int lane) {
 #pragma unroll
     for (int ks = 0; ks < SK / 16; ++ks)
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) acc[mb] = Lp<T>::mfma(ra[ks * 2 + mb], rb[ks], acc[mb]);
+        for (int m = 0; m < MB; ++m) ra[ks * MB + m] = a[lane + 64 * (2 * ks + m)];
+#pragma unroll
+    for (int ks = 0; ks < SK / 16; ++ks) rb[ks] = b[lane + 64 * NBLK * ks];
 }
-// acc += sum over the chunks k in [c0, c1) of the list [pair 1: n1 chunks][pair 2] of (64-row A chunk)
-// x (one 32-row block of the B chunk)^T; B1 / B2 already point at the block.  These kernels are bound
-// by latency, not bandwidth: NS chunks are requested before the first one is used.
-template <typename T, int NS>
+template <typename T, int MB>
+__device__ __forceinline__ void mfma_narrow(const u32x4 (&ra)[MB * SK / 16], const u32x4 (&rb)[SK / 16], v16f (&acc)[MB]) {
+#pragma unroll
+    for (int ks = 0; ks < SK / 16; ++ks)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) acc[mb] = Lp<T>::mfma(ra[ks * MB + mb], rb[ks], acc[mb]);
+}
+// acc += sum over the chunks k in [c0, c1) of the list [pair 1: n1 chunks][pair 2] of (32 MB rows of
+// the A chunk) x (one 32-row block of the B chunk)^T; the pointers already address the blocks.  These
+// kernels are bound by latency, not bandwidth: NS chunks are requested before the first one is used.
+template <typename T, int MB, int NS>
 __device__ __forceinline__ void narrow_mainloop(const uint16_t *A1, const uint16_t *B1, const uint16_t *A2, const uint16_t *B2,
-                                                int n1, int c0, int c1, int lane, v16f (&acc)[2]) {
+                                                int n1, int c0, int c1, int lane, v16f (&acc)[MB]) {
     if (c1 <= c0) return;
     auto pa = [&](int k) { return reinterpret_cast<const u32x4 *>(k < n1 ? A1 + (int64_t)k * A_CHUNK : A2 + (int64_t)(k - n1) * A_CHUNK); };
     auto pb = [&](int k) { return reinterpret_cast<const u32x4 *>(k < n1 ? B1 + (int64_t)k * B_CHUNK : B2 + (int64_t)(k - n1) * B_CHUNK); };
-    u32x4 ra[NS][NLD_A], rb[NS][SK / 16];
+    u32x4 ra[NS][MB * SK / 16], rb[NS][SK / 16];
 #pragma unroll
     for (int i = 0; i < NS; ++i)
-        if (c0 + i < c1) load_narrow(ra[i], rb[i], pa(c0 + i), pb(c0 + i), lane);
+        if (c0 + i < c1) load_narrow<MB>(ra[i], rb[i], pa(c0 + i), pb(c0 + i), lane);
     int k = c0;
     for (; k + 2 * NS <= c1; k += NS) {        // branch-free body: every refill is in range
 #pragma unroll
         for (int i = 0; i < NS; ++i) {
-            mfma_narrow<T>(ra[i], rb[i], acc);
-            load_narrow(ra[i], rb[i], pa(k + NS + i), pb(k + NS + i), lane);
+            mfma_narrow<T, MB>(ra[i], rb[i], acc);
+            load_narrow<MB>(ra[i], rb[i], pa(k + NS + i), pb(k + NS + i), lane);
         }
     }
     // fewer than 2 NS chunks left; set i holds chunk k + i
 #pragma unroll
     for (int i = 0; i < NS; ++i) {
-        if (k + i < c1) mfma_narrow<T>(ra[i], rb[i], acc);
-        if (k + NS + i < c1) load_narrow(ra[i], rb[i], pa(k + NS + i), pb(k + NS + i), lane);
+        if (k + i < c1) mfma_narrow<T, MB>(ra[i], rb[i], acc);
+        if (k + NS + i < c1) load_narrow<MB>(ra[i], rb[i], pa(k + NS + i), pb(k + NS + i), lane);
     }
 #pragma unroll
     for (int i = 0; i < NS - 1; ++i)
-        if (k + NS + i < c1) mfma_narrow<T>(ra[i], rb[i], acc);
+        if (k + NS + i < c1) mfma_narrow<T, MB>(ra[i], rb[i], acc);
 }
 
-template <typename T>
+template <typename T, int MB>
 __global__ __launch_bounds__(256) void lstm_fused_backward_kernel(FusedBwdArgs w) {
+    constexpr int RT = 32 * MB;                                  // batch rows per workgroup
     const int ci = blockIdx.x / w.wgs_per_cell;                  // uniform: the cell's argument block
     const FusedBwdCell &c = w.cell[ci];
     const int tile = (int)blockIdx.x - ci * w.wgs_per_cell;
-    const int mt = tile % w.n_mt, ub = tile / w.n_mt;            // batch tile of 64, unit block of 32
+    const int rt = tile % w.n_rt, ub = tile / w.n_rt;            // batch tile of RT rows, unit block of 32
+    const int mt = rt * RT / TM, asel = MB == 1 ? (rt & 1) * 64 * 8 : 0;   // its 64-row chunk, its block in there
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nt = ub >> 2, nb = ub & 3;
     const int H = w.H, G = 4 * w.H;
     // the epilogue's operands do not depend on the products: one thread per batch row and 8
     // consecutive units requests them first
     const int row = tid >> 2, ug = tid & 3;
-    const int b = mt * TM + row, j0 = ub * 32 + ug * 8;
-    const bool valid = b < w.B && j0 < H;
+    const int b = rt * RT + row, j0 = ub * 32 + ug * 8;
+    const bool valid = row < RT && b < w.B && j0 < H;
     const int64_t e0 = (int64_t)b * H + j0;
     __attribute__((aligned(16))) T vi[8], vf[8], vg[8], vo[8], vct[8], vcp[8], vdh[8];
     __attribute__((aligned(16))) float dcs[8];
@@ -607,31 +614,30 @@ __global__ __launch_bounds__(256) void lstm_fused_backward_kernel(FusedBwdArgs w
     const int n1 = c.dApk_next ? per : 0, nch = n1 + (c.dApk_above ? per : 0);
     const int cpw = (nch + 3) / 4;
     const int c0 = min(nch, wave * cpw), c1 = min(nch, c0 + cpw);
-    v16f acc[2];
+    v16f acc[MB];
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[mb][r] = 0.0f;
-    narrow_mainloop<T, 4>(reinterpret_cast<const uint16_t *>(c.dApk_next) + (int64_t)mt * per * A_CHUNK,
-                          reinterpret_cast<const uint16_t *>(c.UTpk) + (int64_t)nt * per * B_CHUNK + nb * 64 * 8,
-                          reinterpret_cast<const uint16_t *>(c.dApk_above) + (int64_t)mt * per * A_CHUNK,
-                          reinterpret_cast<const uint16_t *>(c.WTpk) + (int64_t)nt * per * B_CHUNK + nb * 64 * 8, n1, c0, c1, lane, acc);
-    // sum the four wavefronts' accumulators and lay the 64x32 tile out row by row
-    __shared__ __attribute__((aligned(16))) float red[4 * 32 * 64];
-    __shared__ __attribute__((aligned(16))) float sums[64 * TILE_LD];
+    narrow_mainloop<T, MB, 4>(reinterpret_cast<const uint16_t *>(c.dApk_next) + (int64_t)mt * per * A_CHUNK + asel,
+                              reinterpret_cast<const uint16_t *>(c.UTpk) + (int64_t)nt * per * B_CHUNK + nb * 64 * 8,
+                              reinterpret_cast<const uint16_t *>(c.dApk_above) + (int64_t)mt * per * A_CHUNK + asel,
+                              reinterpret_cast<const uint16_t *>(c.WTpk) + (int64_t)nt * per * B_CHUNK + nb * 64 * 8, n1, c0, c1, lane, acc);
+    // sum the four wavefronts' accumulators and lay the RT x 32 tile out row by row: wavefront q
+    // adds up a quarter of the 16 MB accumulator registers
+    constexpr int RW = 16 * MB;                                  // accumulator registers per wavefront
+    __shared__ __attribute__((aligned(16))) float red[4 * RW * 64];
+    __shared__ __attribute__((aligned(16))) float sums[RT * TILE_LD];
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) red[(wave * 32 + mb * 16 + r) * 64 + lane] = acc[mb][r];
+        for (int r = 0; r < 16; ++r) red[(wave * RW + mb * 16 + r) * 64 + lane] = acc[mb][r];
     __syncthreads();
-    {
-        const int mb = wave >> 1, rh = (wave & 1) * 8;
 #pragma unroll
-        for (int rr = 0; rr < 8; ++rr) {
-            const int r = rh + rr, idx = (mb * 16 + r) * 64 + lane;
-            const float v = (red[idx] + red[2048 + idx]) + (red[4096 + idx] + red[6144 + idx]);
-            sums[(mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * TILE_LD + (lane & 31)] = v;
-        }
+    for (int rr = 0; rr < RW / 4; ++rr) {
+        const int x = wave * (RW / 4) + rr, mb = x >> 4, r = x & 15, idx = x * 64 + lane;
+        const float v = (red[idx] + red[RW * 64 + idx]) + (red[2 * RW * 64 + idx] + red[3 * RW * 64 + idx]);
+        sums[(mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * TILE_LD + (lane & 31)] = v;
     }
     __syncthreads();
     // gate arithmetic of the thread's 8 units
@@ -688,17 +694,20 @@ __global__ __launch_bounds__(256) void lstm_fused_backward_kernel(FusedBwdArgs w
 // partial sums to add up), the four gates meet through 36 KB of LDS, and one thread per batch
 // row and 8 units does the cell update with 16-byte accesses throughout; the operands of that
 // update are requested before the products start.
-template <typename T>
+template <typename T, int MB>
 __global__ __launch_bounds__(256) void lstm_narrow_forward_kernel(WaveFwdArgs w) {
+    constexpr int RT = 32 * MB;                                  // batch rows per workgroup
     const int ci = blockIdx.x / w.wgs_per_cell;
     const FwdArgs &a = w.cell[ci];
     const int tile = (int)blockIdx.x - ci * w.wgs_per_cell;
-    const int mt = tile % a.n_mt, hb = tile / a.n_mt;
+    const int n_rt = (a.B + RT - 1) / RT;
+    const int rt = tile % n_rt, hb = tile / n_rt;
+    const int mt = rt * RT / TM, asel = MB == 1 ? (rt & 1) * 64 * 8 : 0;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int H = a.H, G = 4 * a.H;
     const int row = tid >> 2, ug = tid & 3;
-    const int b = mt * TM + row, j0 = hb * 32 + ug * 8;
-    const bool valid = b < a.B && j0 < H;
+    const int b = rt * RT + row, j0 = hb * 32 + ug * 8;
+    const bool valid = row < RT && b < a.B && j0 < H;
     const int64_t e0 = (int64_t)b * H + j0;
     __attribute__((aligned(16))) T vax[4][8];
     __attribute__((aligned(16))) float cprev[8];
@@ -711,21 +720,21 @@ __global__ __launch_bounds__(256) void lstm_narrow_forward_kernel(WaveFwdArgs w)
         for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(cprev + 4 * h) = *reinterpret_cast<const u32x4 *>(a.c_state + e0 + 4 * h);
     }
     const int nch = a.Ax ? a.nkc : 2 * a.nkc;
-    v16f acc[2];
+    v16f acc[MB];
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[mb][r] = 0.0f;
-    narrow_mainloop<T, 4>(reinterpret_cast<const uint16_t *>(a.hpk_prev) + (int64_t)mt * a.nkc * A_CHUNK,
-                          reinterpret_cast<const uint16_t *>(a.Upk) + (int64_t)hb * a.nkc * B_CHUNK + wave * 64 * 8,
-                          reinterpret_cast<const uint16_t *>(a.xpk) + (int64_t)mt * a.nkc * A_CHUNK,
-                          reinterpret_cast<const uint16_t *>(a.Wpk) + (int64_t)hb * a.nkc * B_CHUNK + wave * 64 * 8, a.nkc, 0, nch, lane, acc);
-    __shared__ __attribute__((aligned(16))) float pre[4 * 64 * TILE_LD];     // [gate][row][unit]
+    narrow_mainloop<T, MB, 4>(reinterpret_cast<const uint16_t *>(a.hpk_prev) + (int64_t)mt * a.nkc * A_CHUNK + asel,
+                              reinterpret_cast<const uint16_t *>(a.Upk) + (int64_t)hb * a.nkc * B_CHUNK + wave * 64 * 8,
+                              reinterpret_cast<const uint16_t *>(a.xpk) + (int64_t)mt * a.nkc * A_CHUNK + asel,
+                              reinterpret_cast<const uint16_t *>(a.Wpk) + (int64_t)hb * a.nkc * B_CHUNK + wave * 64 * 8, a.nkc, 0, nch, lane, acc);
+    __shared__ __attribute__((aligned(16))) float pre[4 * RT * TILE_LD];     // [gate][row][unit]
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-            pre[(wave * 64 + mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * TILE_LD + (lane & 31)] = acc[mb][r];
+            pre[(wave * RT + mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * TILE_LD + (lane & 31)] = acc[mb][r];
     __syncthreads();
     if (!valid) return;
     __attribute__((aligned(16))) float pz[4][8];
@@ -733,7 +742,7 @@ __global__ __launch_bounds__(256) void lstm_narrow_forward_kernel(WaveFwdArgs w)
     for (int g = 0; g < 4; ++g)
 #pragma unroll
         for (int h = 0; h < 2; ++h)
-            *reinterpret_cast<u32x4 *>(pz[g] + 4 * h) = *reinterpret_cast<const u32x4 *>(pre + (g * 64 + row) * TILE_LD + ug * 8 + 4 * h);
+            *reinterpret_cast<u32x4 *>(pz[g] + 4 * h) = *reinterpret_cast<const u32x4 *>(pre + (g * RT + row) * TILE_LD + ug * 8 + 4 * h);
     __attribute__((aligned(16))) T oi[8], of[8], og[8], oo[8], oc[8], oh[8];
     __attribute__((aligned(16))) float cn[8];
 #pragma unroll
@@ -757,7 +766,7 @@ __global__ __launch_bounds__(256) void lstm_narrow_forward_kernel(WaveFwdArgs w)
     *reinterpret_cast<u32x4 *>(gr + 3 * H) = *reinterpret_cast<const u32x4 *>(oo);
     *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.c_out) + e0) = *reinterpret_cast<const u32x4 *>(oc);
     *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.h_out) + e0) = *reinterpret_cast<const u32x4 *>(oh);
-    *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.hpk_next) + ((int64_t)mt * a.nkc + (j0 >> 6)) * A_CHUNK + frag_offset(row, j0 & 63, 2)) =
+    *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.hpk_next) + ((int64_t)mt * a.nkc + (j0 >> 6)) * A_CHUNK + frag_offset(b & 63, j0 & 63, 2)) =
         *reinterpret_cast<const u32x4 *>(oh);
     if (a.h_blk)
         *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.h_blk) + ((int64_t)(b >> 6) * a.blk_ncb + (j0 >> 6)) * 4096 + (b & 63) * 64 + (j0 & 63)) =
@@ -969,11 +978,12 @@ int backward_fused_wave(int dtype, const FusedBackwardCell *c, int n_cells, int 
         set_error("backward_fused_wave: operands must be 16-byte aligned");
         return LSTM_ERR_INVALID;
     }
-    w.blk_ncb = blk_ncb; w.B = B; w.H = H; w.n_mt = d.n_mt; w.nkc = d.nkc; w.wgs_per_cell = d.n_mt * d.n_hb;
+    w.blk_ncb = blk_ncb; w.B = B; w.H = H; w.n_rt = (B + 31) / 32; w.nkc = d.nkc; w.wgs_per_cell = w.n_rt * d.n_hb;
     const double n = (double)B * H;
     // products: 2 B H 4H flops, operands once; gate arithmetic: as in the stand-alone kernel without the partials
     KernelTimer timer(KC_GEMM_STEP, s, chunks * 2.0 * n * 4.0 * H, chunks * 2.0 * (4.0 * H * H + 4.0 * n) + n_cells * n * (8.0 + 15.0 * 2.0));
-    LP_ONLY(dtype, T, hipLaunchKernelGGL(lstm_fused_backward_kernel<T>, dim3(w.wgs_per_cell * n_cells), dim3(256), 0, s, w));
+    // 32-row tiles: these cells are bound by the bytes each compute unit pulls in, so the more workgroups the better
+    LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_fused_backward_kernel<T, 1>), dim3(w.wgs_per_cell * n_cells), dim3(256), 0, s, w));
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
@@ -1014,7 +1024,8 @@ int step_forward_wave(int dtype, const WaveCell *cells, int n_cells, int blk_ncb
     }
     KernelTimer timer(KC_GEMM_STEP, s, flops, bytes);
     if (narrow_cells(d, H) && all % 16 == 0) {
-        LP_ONLY(dtype, T, hipLaunchKernelGGL(lstm_narrow_forward_kernel<T>, dim3(w.wgs_per_cell * n_cells), dim3(256), 0, s, w));
+        w.wgs_per_cell = ((B + 31) / 32) * d.n_hb;             // 32-row tiles
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_narrow_forward_kernel<T, 1>), dim3(w.wgs_per_cell * n_cells), dim3(256), 0, s, w));
     } else {
         LP_ONLY(dtype, T, hipLaunchKernelGGL(lstm_wave_forward_kernel<T>, dim3(w.wgs_per_cell * n_cells), dim3(256), 0, s, w));
     }
