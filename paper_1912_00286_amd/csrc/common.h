@@ -75,6 +75,10 @@ template <> struct Lp<_Float16> {
     __device__ static inline v16f mfma(const u32x4 &a, const u32x4 &b, v16f c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
     }
+    // 16x16 tile, 32 deep: lane = 16 * (k / 8) + row (A) or column (B); result rows 4 (lane / 16) + r, column lane % 16
+    __device__ static inline v4f mfma16(const u32x4 &a, const u32x4 &b, v4f c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
+    }
 };
 template <> struct Lp<bf16_t> {
     static constexpr int code = LSTM_DTYPE_BF16;
@@ -82,6 +86,9 @@ template <> struct Lp<bf16_t> {
     __device__ static inline bf16_t from_f(float v) { return float_to_bf16(v); }
     __device__ static inline v16f mfma(const u32x4 &a, const u32x4 &b, v16f c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8b, a), __builtin_bit_cast(v8b, b), c, 0, 0, 0);
+    }
+    __device__ static inline v4f mfma16(const u32x4 &a, const u32x4 &b, v4f c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8b, a), __builtin_bit_cast(v8b, b), c, 0, 0, 0);
     }
 };
 

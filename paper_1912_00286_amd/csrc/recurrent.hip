@@ -504,17 +504,23 @@ __global__ __launch_bounds__(256) void wave_gates_backward_kernel(WaveGateArgs w
                                 blk * (int64_t)blockDim.x + threadIdx.x, (int64_t)w.blocks_per_cell * blockDim.x);
 }
 
-// ---------------------------------------------------------------- fused backward cell
-// Narrow layers: a BPTT step is a handful of workgroups, so what counts is the number of
-// dependent launches.  Here one launch does the whole cell.  A workgroup owns 64 batch rows
-// x 32 hidden units and contracts over ALL 4H gate rows of dA_{t+1} U (and of dA_t W of the
-// layer above) itself, its four wavefronts splitting that range: the gradient reaching its
-// units is then complete inside the workgroup, and the gate arithmetic of those units follows
-// in the epilogue (the two-launch form splits the contraction over workgroups and needs a
-// second kernel to sum the slices).  Operands and outputs are the packed ones of the other
-// kernels; of a 128-row B chunk only this workgroup's 32-row block is read.
+// ---------------------------------------------------------------- narrow layers
+// Narrow layers: a time step is a few small tiles, the launches of one sequence form a long
+// dependent chain, and what a launch costs is its own latency: how many bytes each compute unit
+// has to pull in (measured: the duration follows bytes per compute unit, at ~45 GB/s each), how
+// many barriers and dependent memory round trips it has.  The two kernels below do a whole
+// cell per launch on R x R tiles (R = 32 or 16, one workgroup each, so a cell spreads over many
+// compute units), request the epilogue's operands before the products start, keep NS chunks
+// of operands in flight, and use 16-byte accesses throughout (H % 8 == 0).
+//   backward: the workgroup contracts over ALL 4H gate rows of dA_{t+1} U (and of dA_t W of
+//             the layer above) itself, its four wavefronts splitting that range, so the gradient
+//             reaching its units is complete inside the workgroup and the gate arithmetic follows
+//             in the epilogue: one launch per BPTT cell instead of two.
+//   forward : wavefront q computes gate q's pre-activations over the whole K range (nothing to
+//             add up), the four gates meet through LDS.
+// Operands are the packed ones of the other kernels; an R-row slice of a chunk is a few
+// contiguous pieces of it.
 constexpr int FUSED_MAX_CELLS = 8;
-constexpr int TILE_LD = 36;               // floats per row of the summed 64x32 tile (16-byte aligned rows)
 struct FusedBwdCell {
     const void *dApk_next, *UTpk, *dApk_above, *WTpk, *dh_above, *gates, *c_t, *c_prev;
     float *dc_state;
@@ -523,80 +529,88 @@ struct FusedBwdCell {
 };
 struct FusedBwdArgs {
     FusedBwdCell cell[FUSED_MAX_CELLS];
-    int blk_ncb, B, H, n_rt, nkc, wgs_per_cell;
+    int blk_ncb, B, H, nkc, wgs_per_cell;
 };
 
-// MB 32-row blocks of the 64-row A chunk (MB = 1: `a` already points at the block) and one 32-row
-// block of the B chunk
-template <int MB>
-__device__ __forceinline__ void load_narrow(u32x4 (&ra)[MB * SK / 16], u32x4 (&rb)[SK / 16], const u32x4 *a, const u32x4 *b, int lane) {
-#pragma unroll
-    for (int ks = 0; ks < SK / 16; ++ks)
-#pragma unroll
-        for (int m = 0; m < MB; ++m) ra[ks * MB + m] = a[lane + 64 * (2 * ks + m)];
-#pragma unroll
-    for (int ks = 0; ks < SK / 16; ++ks) rb[ks] = b[lane + 64 * NBLK * ks];
-}
-template <typename T, int MB>
-__device__ __forceinline__ void mfma_narrow(const u32x4 (&ra)[MB * SK / 16], const u32x4 (&rb)[SK / 16], v16f (&acc)[MB]) {
-#pragma unroll
-    for (int ks = 0; ks < SK / 16; ++ks)
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) acc[mb] = Lp<T>::mfma(ra[ks * MB + mb], rb[ks], acc[mb]);
-}
-// acc += sum over the chunks k in [c0, c1) of the list [pair 1: n1 chunks][pair 2] of (32 MB rows of
-// the A chunk) x (one 32-row block of the B chunk)^T; the pointers already address the blocks.  These
-// kernels are bound by latency, not bandwidth: NS chunks are requested before the first one is used.
-template <typename T, int MB, int NS>
-__device__ __forceinline__ void narrow_mainloop(const uint16_t *A1, const uint16_t *B1, const uint16_t *A2, const uint16_t *B2,
-                                                int n1, int c0, int c1, int lane, v16f (&acc)[MB]) {
+// How an R x R tile maps onto the packed chunks ([k-step of 16][32-row block][lane][8]) and onto the
+// MFMA that multiplies it: 32x32x16 (lane = 32 (k / 8) + row) or 16x16x32 (lane = 16 (k / 8) + row).
+template <typename T, int R> struct NarrowGeo;
+template <typename T> struct NarrowGeo<T, 32> {
+    typedef v16f acc_t;
+    static constexpr int NR = 16, STEPS = 4, A_STRIDE = 128, B_STRIDE = 256;   // strides in 16-byte units
+    __device__ static int lane_a(int lane) { return lane; }
+    __device__ static int lane_b(int lane) { return lane; }
+    // 16-byte offset of rows r0.. of a 64-row A chunk / 128-row B chunk
+    __device__ static int slice_a(int r0) { return ((r0 >> 5) & 1) * 64; }
+    __device__ static int slice_b(int r0) { return ((r0 >> 5) & 3) * 64; }
+    __device__ static int row(int r, int lane) { return (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3); }
+    __device__ static int col(int lane) { return lane & 31; }
+    __device__ static acc_t mfma(const u32x4 &a, const u32x4 &b, acc_t c) { return Lp<T>::mfma(a, b, c); }
+};
+template <typename T> struct NarrowGeo<T, 16> {
+    typedef v4f acc_t;
+    static constexpr int NR = 4, STEPS = 2, A_STRIDE = 256, B_STRIDE = 512;
+    // a 32-deep step spans two 16-deep k-steps of the chunk: lane / 32 picks the k-step, (lane / 16) % 2 its half
+    __device__ static int lane_a(int lane) { return (lane >> 5) * 128 + ((lane >> 4) & 1) * 32 + (lane & 15); }
+    __device__ static int lane_b(int lane) { return (lane >> 5) * 256 + ((lane >> 4) & 1) * 32 + (lane & 15); }
+    __device__ static int slice_a(int r0) { return ((r0 >> 5) & 1) * 64 + ((r0 >> 4) & 1) * 16; }
+    __device__ static int slice_b(int r0) { return ((r0 >> 5) & 3) * 64 + ((r0 >> 4) & 1) * 16; }
+    __device__ static int row(int r, int lane) { return (lane >> 4) * 4 + r; }
+    __device__ static int col(int lane) { return lane & 15; }
+    __device__ static acc_t mfma(const u32x4 &a, const u32x4 &b, acc_t c) { return Lp<T>::mfma16(a, b, c); }
+};
+
+// acc += sum over the chunks k in [c0, c1) of the list [pair 1: n1 chunks][pair 2] of (R rows of the A
+// chunk) x (R rows of the B chunk)^T; the pointers already address the slices and the lane.
+template <typename T, int R, int NS>
+__device__ __forceinline__ void narrow_mainloop(const u32x4 *A1, const u32x4 *B1, const u32x4 *A2, const u32x4 *B2, int n1, int c0,
+                                                int c1, typename NarrowGeo<T, R>::acc_t &acc) {
+    typedef NarrowGeo<T, R> Geo;
+    constexpr int STEPS = Geo::STEPS, AV = A_CHUNK / 8, BV = B_CHUNK / 8;   // chunk sizes in 16-byte units
     if (c1 <= c0) return;
-    auto pa = [&](int k) { return reinterpret_cast<const u32x4 *>(k < n1 ? A1 + (int64_t)k * A_CHUNK : A2 + (int64_t)(k - n1) * A_CHUNK); };
-    auto pb = [&](int k) { return reinterpret_cast<const u32x4 *>(k < n1 ? B1 + (int64_t)k * B_CHUNK : B2 + (int64_t)(k - n1) * B_CHUNK); };
-    u32x4 ra[NS][MB * SK / 16], rb[NS][SK / 16];
+    auto load = [&](u32x4 (&ra)[STEPS], u32x4 (&rb)[STEPS], int k) {
+        const u32x4 *a = k < n1 ? A1 + (int64_t)k * AV : A2 + (int64_t)(k - n1) * AV;
+        const u32x4 *b = k < n1 ? B1 + (int64_t)k * BV : B2 + (int64_t)(k - n1) * BV;
+#pragma unroll
+        for (int i = 0; i < STEPS; ++i) ra[i] = a[Geo::A_STRIDE * i];
+#pragma unroll
+        for (int i = 0; i < STEPS; ++i) rb[i] = b[Geo::B_STRIDE * i];
+    };
+    auto mul = [&](const u32x4 (&ra)[STEPS], const u32x4 (&rb)[STEPS]) {
+#pragma unroll
+        for (int i = 0; i < STEPS; ++i) acc = Geo::mfma(ra[i], rb[i], acc);
+    };
+    u32x4 ra[NS][STEPS], rb[NS][STEPS];
 #pragma unroll
     for (int i = 0; i < NS; ++i)
-        if (c0 + i < c1) load_narrow<MB>(ra[i], rb[i], pa(c0 + i), pb(c0 + i), lane);
+        if (c0 + i < c1) load(ra[i], rb[i], c0 + i);
     int k = c0;
     for (; k + 2 * NS <= c1; k += NS) {        // branch-free body: every refill is in range
 #pragma unroll
         for (int i = 0; i < NS; ++i) {
-            mfma_narrow<T, MB>(ra[i], rb[i], acc);
-            load_narrow<MB>(ra[i], rb[i], pa(k + NS + i), pb(k + NS + i), lane);
+            mul(ra[i], rb[i]);
+            load(ra[i], rb[i], k + NS + i);
         }
     }
     // fewer than 2 NS chunks left; set i holds chunk k + i
 #pragma unroll
     for (int i = 0; i < NS; ++i) {
-        if (k + i < c1) mfma_narrow<T, MB>(ra[i], rb[i], acc);
-        if (k + NS + i < c1) load_narrow<MB>(ra[i], rb[i], pa(k + NS + i), pb(k + NS + i), lane);
+        if (k + i < c1) mul(ra[i], rb[i]);
+        if (k + NS + i < c1) load(ra[i], rb[i], k + NS + i);
     }
 #pragma unroll
     for (int i = 0; i < NS - 1; ++i)
-        if (k + NS + i < c1) mfma_narrow<T, MB>(ra[i], rb[i], acc);
+        if (k + NS + i < c1) mul(ra[i], rb[i]);
 }
 
-template <typename T, int MB>
-__global__ __launch_bounds__(256) void lstm_fused_backward_kernel(FusedBwdArgs w) {
-    constexpr int RT = 32 * MB;                                  // batch rows per workgroup
-    const int ci = blockIdx.x / w.wgs_per_cell;                  // uniform: the cell's argument block
-    const FusedBwdCell &c = w.cell[ci];
-    const int tile = (int)blockIdx.x - ci * w.wgs_per_cell;
-    const int rt = tile % w.n_rt, ub = tile / w.n_rt;            // batch tile of RT rows, unit block of 32
-    const int mt = rt * RT / TM, asel = MB == 1 ? (rt & 1) * 64 * 8 : 0;   // its 64-row chunk, its block in there
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int nt = ub >> 2, nb = ub & 3;
-    const int H = w.H, G = 4 * w.H;
-    // the epilogue's operands do not depend on the products: one thread per batch row and 8
-    // consecutive units requests them first
-    const int row = tid >> 2, ug = tid & 3;
-    const int b = rt * RT + row, j0 = ub * 32 + ug * 8;
-    const bool valid = row < RT && b < w.B && j0 < H;
-    const int64_t e0 = (int64_t)b * H + j0;
+// One batch row x 8 consecutive units of a BPTT cell: operands requested early, finished once the
+// gradient reaching h_t of those units (rec, from the products) is known.
+template <typename T> struct BackwardItem {
     __attribute__((aligned(16))) T vi[8], vf[8], vg[8], vo[8], vct[8], vcp[8], vdh[8];
     __attribute__((aligned(16))) float dcs[8];
-    if (valid) {
-        const T *gr = reinterpret_cast<const T *>(c.gates) + (int64_t)b * G + j0;
+    __device__ __forceinline__ void request(const FusedBwdCell &c, int b, int j0, int H) {
+        const int64_t e0 = (int64_t)b * H + j0;
+        const T *gr = reinterpret_cast<const T *>(c.gates) + (int64_t)b * 4 * H + j0;
         *reinterpret_cast<u32x4 *>(vi) = *reinterpret_cast<const u32x4 *>(gr);
         *reinterpret_cast<u32x4 *>(vf) = *reinterpret_cast<const u32x4 *>(gr + H);
         *reinterpret_cast<u32x4 *>(vg) = *reinterpret_cast<const u32x4 *>(gr + 2 * H);
@@ -609,132 +623,175 @@ __global__ __launch_bounds__(256) void lstm_fused_backward_kernel(FusedBwdArgs w
             for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(dcs + 4 * h) = *reinterpret_cast<const u32x4 *>(c.dc_state + e0 + 4 * h);
         }
     }
+    __device__ __forceinline__ void finish(const FusedBwdCell &c, const float (&rec)[8], int b, int j0, int H, int nkc, int blk_ncb) {
+        const int64_t e0 = (int64_t)b * H + j0;
+        __attribute__((aligned(16))) T o0[8], o1[8], o2[8], o3[8];
+        __attribute__((aligned(16))) float dcn[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const float i = Lp<T>::to_f(vi[k]), f = Lp<T>::to_f(vf[k]), g = Lp<T>::to_f(vg[k]), o = Lp<T>::to_f(vo[k]);
+            const float tc = tanhf_dev(Lp<T>::to_f(vct[k]));
+            const float dh = (c.dh_above ? Lp<T>::to_f(vdh[k]) : 0.0f) + rec[k];
+            const float dcr = c.first ? 0.0f : dcs[k];
+            const float d_o = dh * tc;
+            const float dc = dcr + dh * o * (1.0f - tc * tc);
+            const float di = dc * g, dg = dc * i, df = dc * Lp<T>::to_f(vcp[k]);
+            dcn[k] = dc * f;
+            o0[k] = Lp<T>::from_f(di * i * (1.0f - i));
+            o1[k] = Lp<T>::from_f(df * f * (1.0f - f));
+            o2[k] = Lp<T>::from_f(dg * (1.0f - g * g));
+            o3[k] = Lp<T>::from_f(d_o * o * (1.0f - o));
+        }
+        // packed: [b / 64][gate][j / 64] chunk, fragment order inside; 8 aligned units are one slot
+        const int64_t gs = (int64_t)nkc * A_CHUNK;
+        T *pk = reinterpret_cast<T *>(c.dApk) + (((int64_t)(b >> 6) * 4) * nkc + (j0 >> 6)) * A_CHUNK + frag_offset(b & 63, j0 & 63, 2);
+        *reinterpret_cast<u32x4 *>(pk) = *reinterpret_cast<const u32x4 *>(o0);
+        *reinterpret_cast<u32x4 *>(pk + gs) = *reinterpret_cast<const u32x4 *>(o1);
+        *reinterpret_cast<u32x4 *>(pk + 2 * gs) = *reinterpret_cast<const u32x4 *>(o2);
+        *reinterpret_cast<u32x4 *>(pk + 3 * gs) = *reinterpret_cast<const u32x4 *>(o3);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(c.dc_state + e0 + 4 * h) = *reinterpret_cast<const u32x4 *>(dcn + 4 * h);
+        if (c.dA) {
+            T *da = reinterpret_cast<T *>(c.dA) + (int64_t)b * 4 * H + j0;
+            *reinterpret_cast<u32x4 *>(da) = *reinterpret_cast<const u32x4 *>(o0);
+            *reinterpret_cast<u32x4 *>(da + H) = *reinterpret_cast<const u32x4 *>(o1);
+            *reinterpret_cast<u32x4 *>(da + 2 * H) = *reinterpret_cast<const u32x4 *>(o2);
+            *reinterpret_cast<u32x4 *>(da + 3 * H) = *reinterpret_cast<const u32x4 *>(o3);
+        }
+        if (c.dAblk) {
+            T *rowp = reinterpret_cast<T *>(c.dAblk) + (int64_t)(b >> 6) * blk_ncb * 4096 + (b & 63) * 64;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int col = g * H + j0;
+                const T *src = g == 0 ? o0 : (g == 1 ? o1 : (g == 2 ? o2 : o3));
+                *reinterpret_cast<u32x4 *>(rowp + (int64_t)(col >> 6) * 4096 + (col & 63)) = *reinterpret_cast<const u32x4 *>(src);
+            }
+        }
+    }
+};
+
+template <typename T, int R>
+__global__ __launch_bounds__(256) void lstm_fused_backward_kernel(FusedBwdArgs w) {
+    typedef NarrowGeo<T, R> Geo;
+    constexpr int UG = R / 8, LD = R + 4, NR = Geo::NR;          // 8-unit groups per row, LDS row pitch, accumulator registers
+    const int ci = blockIdx.x / w.wgs_per_cell;                  // uniform: the cell's argument block
+    const FusedBwdCell &c = w.cell[ci];
+    const int tile = (int)blockIdx.x - ci * w.wgs_per_cell;
+    const int n_rt = (w.B + R - 1) / R;
+    const int b0 = (tile % n_rt) * R, u0 = (tile / n_rt) * R;    // first batch row, first hidden unit
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int H = w.H;
+    const int row = tid / UG, ug = tid % UG;
+    const int b = b0 + row, j0 = u0 + ug * 8;
+    const bool valid = row < R && b < w.B && j0 < H;
+    BackwardItem<T> item;
+    if (valid) item.request(c, b, j0, H);
     // chunk list: [dA_{t+1} x U^T: 4 nkc chunks][dA_t(above) x W^T: 4 nkc chunks], either part may be absent
     const int per = 4 * w.nkc;
     const int n1 = c.dApk_next ? per : 0, nch = n1 + (c.dApk_above ? per : 0);
     const int cpw = (nch + 3) / 4;
     const int c0 = min(nch, wave * cpw), c1 = min(nch, c0 + cpw);
-    v16f acc[MB];
+    const int64_t a_off = (int64_t)(b0 >> 6) * per * (A_CHUNK / 8) + Geo::slice_a(b0) + Geo::lane_a(lane);
+    const int64_t b_off = (int64_t)(u0 >> 7) * per * (B_CHUNK / 8) + Geo::slice_b(u0) + Geo::lane_b(lane);
+    typename Geo::acc_t acc;
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
+    for (int r = 0; r < NR; ++r) acc[r] = 0.0f;
+    narrow_mainloop<T, R, 4>(reinterpret_cast<const u32x4 *>(c.dApk_next) + a_off, reinterpret_cast<const u32x4 *>(c.UTpk) + b_off,
+                             reinterpret_cast<const u32x4 *>(c.dApk_above) + a_off, reinterpret_cast<const u32x4 *>(c.WTpk) + b_off, n1,
+                             c0, c1, acc);
+    // sum the four wavefronts' accumulators and lay the tile out row by row
+    __shared__ __attribute__((aligned(16))) float red[4 * NR * 64];
+    __shared__ __attribute__((aligned(16))) float sums[R * LD];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[mb][r] = 0.0f;
-    narrow_mainloop<T, MB, 4>(reinterpret_cast<const uint16_t *>(c.dApk_next) + (int64_t)mt * per * A_CHUNK + asel,
-                              reinterpret_cast<const uint16_t *>(c.UTpk) + (int64_t)nt * per * B_CHUNK + nb * 64 * 8,
-                              reinterpret_cast<const uint16_t *>(c.dApk_above) + (int64_t)mt * per * A_CHUNK + asel,
-                              reinterpret_cast<const uint16_t *>(c.WTpk) + (int64_t)nt * per * B_CHUNK + nb * 64 * 8, n1, c0, c1, lane, acc);
-    // sum the four wavefronts' accumulators and lay the RT x 32 tile out row by row: wavefront q
-    // adds up a quarter of the 16 MB accumulator registers
-    constexpr int RW = 16 * MB;                                  // accumulator registers per wavefront
-    __shared__ __attribute__((aligned(16))) float red[4 * RW * 64];
-    __shared__ __attribute__((aligned(16))) float sums[RT * TILE_LD];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) red[(wave * RW + mb * 16 + r) * 64 + lane] = acc[mb][r];
+    for (int r = 0; r < NR; ++r) red[(wave * NR + r) * 64 + lane] = acc[r];
     __syncthreads();
-#pragma unroll
-    for (int rr = 0; rr < RW / 4; ++rr) {
-        const int x = wave * (RW / 4) + rr, mb = x >> 4, r = x & 15, idx = x * 64 + lane;
-        const float v = (red[idx] + red[RW * 64 + idx]) + (red[2 * RW * 64 + idx] + red[3 * RW * 64 + idx]);
-        sums[(mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * TILE_LD + (lane & 31)] = v;
+    for (int e = tid; e < NR * 64; e += 256) {
+        const float v = (red[e] + red[NR * 64 + e]) + (red[2 * NR * 64 + e] + red[3 * NR * 64 + e]);
+        sums[Geo::row(e >> 6, e & 63) * LD + Geo::col(e & 63)] = v;
     }
     __syncthreads();
-    // gate arithmetic of the thread's 8 units
     if (!valid) return;
     __attribute__((aligned(16))) float rec[8];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(rec + 4 * h) = *reinterpret_cast<const u32x4 *>(sums + row * TILE_LD + ug * 8 + 4 * h);
-    __attribute__((aligned(16))) T o0[8], o1[8], o2[8], o3[8];
-    __attribute__((aligned(16))) float dcn[8];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const float i = Lp<T>::to_f(vi[k]), f = Lp<T>::to_f(vf[k]), g = Lp<T>::to_f(vg[k]), o = Lp<T>::to_f(vo[k]);
-        const float tc = tanhf_dev(Lp<T>::to_f(vct[k]));
-        const float dh = (c.dh_above ? Lp<T>::to_f(vdh[k]) : 0.0f) + rec[k];
-        const float dcr = c.first ? 0.0f : dcs[k];
-        const float d_o = dh * tc;
-        const float dc = dcr + dh * o * (1.0f - tc * tc);
-        const float di = dc * g, dg = dc * i, df = dc * Lp<T>::to_f(vcp[k]);
-        dcn[k] = dc * f;
-        o0[k] = Lp<T>::from_f(di * i * (1.0f - i));
-        o1[k] = Lp<T>::from_f(df * f * (1.0f - f));
-        o2[k] = Lp<T>::from_f(dg * (1.0f - g * g));
-        o3[k] = Lp<T>::from_f(d_o * o * (1.0f - o));
-    }
-    const int64_t gs = (int64_t)w.nkc * A_CHUNK;
-    T *pk = reinterpret_cast<T *>(c.dApk) + (((int64_t)(b >> 6) * 4) * w.nkc + (j0 >> 6)) * A_CHUNK + frag_offset(b & 63, j0 & 63, 2);
-    *reinterpret_cast<u32x4 *>(pk) = *reinterpret_cast<const u32x4 *>(o0);
-    *reinterpret_cast<u32x4 *>(pk + gs) = *reinterpret_cast<const u32x4 *>(o1);
-    *reinterpret_cast<u32x4 *>(pk + 2 * gs) = *reinterpret_cast<const u32x4 *>(o2);
-    *reinterpret_cast<u32x4 *>(pk + 3 * gs) = *reinterpret_cast<const u32x4 *>(o3);
-#pragma unroll
-    for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(c.dc_state + e0 + 4 * h) = *reinterpret_cast<const u32x4 *>(dcn + 4 * h);
-    if (c.dA) {
-        T *da = reinterpret_cast<T *>(c.dA) + (int64_t)b * G + j0;
-        *reinterpret_cast<u32x4 *>(da) = *reinterpret_cast<const u32x4 *>(o0);
-        *reinterpret_cast<u32x4 *>(da + H) = *reinterpret_cast<const u32x4 *>(o1);
-        *reinterpret_cast<u32x4 *>(da + 2 * H) = *reinterpret_cast<const u32x4 *>(o2);
-        *reinterpret_cast<u32x4 *>(da + 3 * H) = *reinterpret_cast<const u32x4 *>(o3);
-    }
-    if (c.dAblk) {
-        T *rowp = reinterpret_cast<T *>(c.dAblk) + (int64_t)(b >> 6) * w.blk_ncb * 4096 + (b & 63) * 64;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int col = g * H + j0;
-            const T *src = g == 0 ? o0 : (g == 1 ? o1 : (g == 2 ? o2 : o3));
-            *reinterpret_cast<u32x4 *>(rowp + (int64_t)(col >> 6) * 4096 + (col & 63)) = *reinterpret_cast<const u32x4 *>(src);
-        }
-    }
+    for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(rec + 4 * h) = *reinterpret_cast<const u32x4 *>(sums + row * LD + ug * 8 + 4 * h);
+    item.finish(c, rec, b, j0, H, w.nkc, w.blk_ncb);
 }
 
-// ---------------------------------------------------------------- narrow forward cell
-// The forward counterpart for narrow layers (H % 8 == 0): a workgroup owns 64 batch rows x 32
-// hidden units, wavefront q computes gate q's pre-activations over the whole K range (no
-// partial sums to add up), the four gates meet through 36 KB of LDS, and one thread per batch
-// row and 8 units does the cell update with 16-byte accesses throughout; the operands of that
-// update are requested before the products start.
-template <typename T, int MB>
-__global__ __launch_bounds__(256) void lstm_narrow_forward_kernel(WaveFwdArgs w) {
-    constexpr int RT = 32 * MB;                                  // batch rows per workgroup
-    const int ci = blockIdx.x / w.wgs_per_cell;
-    const FwdArgs &a = w.cell[ci];
-    const int tile = (int)blockIdx.x - ci * w.wgs_per_cell;
-    const int n_rt = (a.B + RT - 1) / RT;
-    const int rt = tile % n_rt, hb = tile / n_rt;
-    const int mt = rt * RT / TM, asel = MB == 1 ? (rt & 1) * 64 * 8 : 0;
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int H = a.H, G = 4 * a.H;
-    const int row = tid >> 2, ug = tid & 3;
-    const int b = rt * RT + row, j0 = hb * 32 + ug * 8;
-    const bool valid = row < RT && b < a.B && j0 < H;
-    const int64_t e0 = (int64_t)b * H + j0;
+// One batch row x 8 consecutive units of a forward cell.
+template <typename T> struct ForwardItem {
     __attribute__((aligned(16))) T vax[4][8];
     __attribute__((aligned(16))) float cprev[8];
-    if (valid) {
+    __device__ __forceinline__ void request(const FwdArgs &a, int b, int j0) {
+        const int H = a.H;
         // input projection (bias included) of this step, or just the bias when the cell projects its own input
-        const T *ax = a.Ax ? reinterpret_cast<const T *>(a.Ax) + (int64_t)b * G + j0 : reinterpret_cast<const T *>(a.bias) + j0;
+        const T *ax = a.Ax ? reinterpret_cast<const T *>(a.Ax) + (int64_t)b * 4 * H + j0 : reinterpret_cast<const T *>(a.bias) + j0;
 #pragma unroll
         for (int g = 0; g < 4; ++g) *reinterpret_cast<u32x4 *>(vax[g]) = *reinterpret_cast<const u32x4 *>(ax + g * H);
 #pragma unroll
-        for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(cprev + 4 * h) = *reinterpret_cast<const u32x4 *>(a.c_state + e0 + 4 * h);
+        for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(cprev + 4 * h) = *reinterpret_cast<const u32x4 *>(a.c_state + (int64_t)b * H + j0 + 4 * h);
     }
+    __device__ __forceinline__ void finish(const FwdArgs &a, const float (&pz)[4][8], int b, int j0) {
+        const int H = a.H;
+        const int64_t e0 = (int64_t)b * H + j0;
+        __attribute__((aligned(16))) T oi[8], of[8], og[8], oo[8], oc[8], oh[8];
+        __attribute__((aligned(16))) float cn[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const float gi = sigmoidf_dev(pz[0][k] + Lp<T>::to_f(vax[0][k]));
+            const float gf = sigmoidf_dev(pz[1][k] + Lp<T>::to_f(vax[1][k]));
+            const float gg = tanhf_dev(pz[2][k] + Lp<T>::to_f(vax[2][k]));
+            const float go = sigmoidf_dev(pz[3][k] + Lp<T>::to_f(vax[3][k]));
+            const float cc = gf * cprev[k] + gi * gg;
+            cn[k] = cc;
+            oi[k] = Lp<T>::from_f(gi); of[k] = Lp<T>::from_f(gf); og[k] = Lp<T>::from_f(gg); oo[k] = Lp<T>::from_f(go);
+            oc[k] = Lp<T>::from_f(cc);
+            oh[k] = Lp<T>::from_f(go * tanhf_dev(cc));
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(a.c_state + e0 + 4 * h) = *reinterpret_cast<const u32x4 *>(cn + 4 * h);
+        T *gr = reinterpret_cast<T *>(a.gates) + (int64_t)b * 4 * H + j0;
+        *reinterpret_cast<u32x4 *>(gr) = *reinterpret_cast<const u32x4 *>(oi);
+        *reinterpret_cast<u32x4 *>(gr + H) = *reinterpret_cast<const u32x4 *>(of);
+        *reinterpret_cast<u32x4 *>(gr + 2 * H) = *reinterpret_cast<const u32x4 *>(og);
+        *reinterpret_cast<u32x4 *>(gr + 3 * H) = *reinterpret_cast<const u32x4 *>(oo);
+        *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.c_out) + e0) = *reinterpret_cast<const u32x4 *>(oc);
+        *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.h_out) + e0) = *reinterpret_cast<const u32x4 *>(oh);
+        *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.hpk_next) + ((int64_t)(b >> 6) * a.nkc + (j0 >> 6)) * A_CHUNK +
+                                   frag_offset(b & 63, j0 & 63, 2)) = *reinterpret_cast<const u32x4 *>(oh);
+        if (a.h_blk)
+            *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.h_blk) + ((int64_t)(b >> 6) * a.blk_ncb + (j0 >> 6)) * 4096 + (b & 63) * 64 +
+                                       (j0 & 63)) = *reinterpret_cast<const u32x4 *>(oh);
+    }
+};
+
+template <typename T, int R>
+__global__ __launch_bounds__(256) void lstm_narrow_forward_kernel(WaveFwdArgs w) {
+    typedef NarrowGeo<T, R> Geo;
+    constexpr int UG = R / 8, LD = R + 4, NR = Geo::NR;
+    const int ci = blockIdx.x / w.wgs_per_cell;
+    const FwdArgs &a = w.cell[ci];
+    const int tile = (int)blockIdx.x - ci * w.wgs_per_cell;
+    const int n_rt = (a.B + R - 1) / R;
+    const int b0 = (tile % n_rt) * R, u0 = (tile / n_rt) * R;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int row = tid / UG, ug = tid % UG;
+    const int b = b0 + row, j0 = u0 + ug * 8;
+    const bool valid = row < R && b < a.B && j0 < a.H;
+    ForwardItem<T> item;
+    if (valid) item.request(a, b, j0);
     const int nch = a.Ax ? a.nkc : 2 * a.nkc;
-    v16f acc[MB];
+    // rows of U (and W): hidden block u0 / 32, inside it gate `wave`'s 32 rows, of those the tile's R
+    const int64_t a_off = (int64_t)(b0 >> 6) * a.nkc * (A_CHUNK / 8) + Geo::slice_a(b0) + Geo::lane_a(lane);
+    const int64_t b_off = (int64_t)(u0 >> 5) * a.nkc * (B_CHUNK / 8) + Geo::slice_b(wave * 32 + (u0 & 31)) + Geo::lane_b(lane);
+    typename Geo::acc_t acc;
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
+    for (int r = 0; r < NR; ++r) acc[r] = 0.0f;
+    narrow_mainloop<T, R, 4>(reinterpret_cast<const u32x4 *>(a.hpk_prev) + a_off, reinterpret_cast<const u32x4 *>(a.Upk) + b_off,
+                             reinterpret_cast<const u32x4 *>(a.xpk) + a_off, reinterpret_cast<const u32x4 *>(a.Wpk) + b_off, a.nkc, 0,
+                             nch, acc);
+    __shared__ __attribute__((aligned(16))) float pre[4 * R * LD];     // [gate][row][unit]
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[mb][r] = 0.0f;
-    narrow_mainloop<T, MB, 4>(reinterpret_cast<const uint16_t *>(a.hpk_prev) + (int64_t)mt * a.nkc * A_CHUNK + asel,
-                              reinterpret_cast<const uint16_t *>(a.Upk) + (int64_t)hb * a.nkc * B_CHUNK + wave * 64 * 8,
-                              reinterpret_cast<const uint16_t *>(a.xpk) + (int64_t)mt * a.nkc * A_CHUNK + asel,
-                              reinterpret_cast<const uint16_t *>(a.Wpk) + (int64_t)hb * a.nkc * B_CHUNK + wave * 64 * 8, a.nkc, 0, nch, lane, acc);
-    __shared__ __attribute__((aligned(16))) float pre[4 * RT * TILE_LD];     // [gate][row][unit]
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-            pre[(wave * RT + mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * TILE_LD + (lane & 31)] = acc[mb][r];
+    for (int r = 0; r < NR; ++r) pre[(wave * R + Geo::row(r, lane)) * LD + Geo::col(lane)] = acc[r];
     __syncthreads();
     if (!valid) return;
     __attribute__((aligned(16))) float pz[4][8];
@@ -742,35 +799,8 @@ __global__ __launch_bounds__(256) void lstm_narrow_forward_kernel(WaveFwdArgs w)
     for (int g = 0; g < 4; ++g)
 #pragma unroll
         for (int h = 0; h < 2; ++h)
-            *reinterpret_cast<u32x4 *>(pz[g] + 4 * h) = *reinterpret_cast<const u32x4 *>(pre + (g * RT + row) * TILE_LD + ug * 8 + 4 * h);
-    __attribute__((aligned(16))) T oi[8], of[8], og[8], oo[8], oc[8], oh[8];
-    __attribute__((aligned(16))) float cn[8];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const float gi = sigmoidf_dev(pz[0][k] + Lp<T>::to_f(vax[0][k]));
-        const float gf = sigmoidf_dev(pz[1][k] + Lp<T>::to_f(vax[1][k]));
-        const float gg = tanhf_dev(pz[2][k] + Lp<T>::to_f(vax[2][k]));
-        const float go = sigmoidf_dev(pz[3][k] + Lp<T>::to_f(vax[3][k]));
-        const float cc = gf * cprev[k] + gi * gg;
-        cn[k] = cc;
-        oi[k] = Lp<T>::from_f(gi); of[k] = Lp<T>::from_f(gf); og[k] = Lp<T>::from_f(gg); oo[k] = Lp<T>::from_f(go);
-        oc[k] = Lp<T>::from_f(cc);
-        oh[k] = Lp<T>::from_f(go * tanhf_dev(cc));
-    }
-#pragma unroll
-    for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(a.c_state + e0 + 4 * h) = *reinterpret_cast<const u32x4 *>(cn + 4 * h);
-    T *gr = reinterpret_cast<T *>(a.gates) + (int64_t)b * G + j0;
-    *reinterpret_cast<u32x4 *>(gr) = *reinterpret_cast<const u32x4 *>(oi);
-    *reinterpret_cast<u32x4 *>(gr + H) = *reinterpret_cast<const u32x4 *>(of);
-    *reinterpret_cast<u32x4 *>(gr + 2 * H) = *reinterpret_cast<const u32x4 *>(og);
-    *reinterpret_cast<u32x4 *>(gr + 3 * H) = *reinterpret_cast<const u32x4 *>(oo);
-    *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.c_out) + e0) = *reinterpret_cast<const u32x4 *>(oc);
-    *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.h_out) + e0) = *reinterpret_cast<const u32x4 *>(oh);
-    *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.hpk_next) + ((int64_t)mt * a.nkc + (j0 >> 6)) * A_CHUNK + frag_offset(b & 63, j0 & 63, 2)) =
-        *reinterpret_cast<const u32x4 *>(oh);
-    if (a.h_blk)
-        *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.h_blk) + ((int64_t)(b >> 6) * a.blk_ncb + (j0 >> 6)) * 4096 + (b & 63) * 64 + (j0 & 63)) =
-            *reinterpret_cast<const u32x4 *>(oh);
+            *reinterpret_cast<u32x4 *>(pz[g] + 4 * h) = *reinterpret_cast<const u32x4 *>(pre + (g * R + row) * LD + ug * 8 + 4 * h);
+    item.finish(a, pz, b, j0);
 }
 
 // ---------------------------------------------------------------- packing
@@ -833,6 +863,9 @@ RecurrentDims recurrent_dims(int B, int H) {
 // whole K range, instead of a four-way K split with an LDS reduction.
 // Narrow layers (a cell is at most 128 workgroups of 64 rows x 32 units) with 16-byte-friendly width.
 static bool narrow_cells(const RecurrentDims &d, int H) { return H % 8 == 0 && d.n_mt * d.n_hb <= 128; }
+// Tile edge of the narrow-layer kernels: 16 while that keeps a cell within a few hundred workgroups
+// (the smaller the tile, the fewer bytes each compute unit pulls in), else 32.
+static int narrow_tile(int B, int H) { return ((B + 15) / 16) * ((H + 15) / 16) <= 512 ? 16 : 32; }
 static bool recurrent_wide(const RecurrentDims &d) { return d.nkc <= 8 && d.n_mt >= 16; }   // H <= 512, B >= 961
 
 #define LP_ONLY(dtype, T, ...)                                                       \
@@ -978,12 +1011,16 @@ int backward_fused_wave(int dtype, const FusedBackwardCell *c, int n_cells, int 
         set_error("backward_fused_wave: operands must be 16-byte aligned");
         return LSTM_ERR_INVALID;
     }
-    w.blk_ncb = blk_ncb; w.B = B; w.H = H; w.n_rt = (B + 31) / 32; w.nkc = d.nkc; w.wgs_per_cell = w.n_rt * d.n_hb;
+    const int R = narrow_tile(B, H);
+    w.blk_ncb = blk_ncb; w.B = B; w.H = H; w.nkc = d.nkc; w.wgs_per_cell = ((B + R - 1) / R) * ((H + R - 1) / R);
     const double n = (double)B * H;
     // products: 2 B H 4H flops, operands once; gate arithmetic: as in the stand-alone kernel without the partials
     KernelTimer timer(KC_GEMM_STEP, s, chunks * 2.0 * n * 4.0 * H, chunks * 2.0 * (4.0 * H * H + 4.0 * n) + n_cells * n * (8.0 + 15.0 * 2.0));
-    // 32-row tiles: these cells are bound by the bytes each compute unit pulls in, so the more workgroups the better
-    LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_fused_backward_kernel<T, 1>), dim3(w.wgs_per_cell * n_cells), dim3(256), 0, s, w));
+    if (R == 16) {
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_fused_backward_kernel<T, 16>), dim3(w.wgs_per_cell * n_cells), dim3(256), 0, s, w));
+    } else {
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_fused_backward_kernel<T, 32>), dim3(w.wgs_per_cell * n_cells), dim3(256), 0, s, w));
+    }
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
@@ -1024,8 +1061,13 @@ int step_forward_wave(int dtype, const WaveCell *cells, int n_cells, int blk_ncb
     }
     KernelTimer timer(KC_GEMM_STEP, s, flops, bytes);
     if (narrow_cells(d, H) && all % 16 == 0) {
-        w.wgs_per_cell = ((B + 31) / 32) * d.n_hb;             // 32-row tiles
-        LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_narrow_forward_kernel<T, 1>), dim3(w.wgs_per_cell * n_cells), dim3(256), 0, s, w));
+        const int R = narrow_tile(B, H);
+        w.wgs_per_cell = ((B + R - 1) / R) * ((H + R - 1) / R);
+        if (R == 16) {
+            LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_narrow_forward_kernel<T, 16>), dim3(w.wgs_per_cell * n_cells), dim3(256), 0, s, w));
+        } else {
+            LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_narrow_forward_kernel<T, 32>), dim3(w.wgs_per_cell * n_cells), dim3(256), 0, s, w));
+        }
     } else {
         LP_ONLY(dtype, T, hipLaunchKernelGGL(lstm_wave_forward_kernel<T>, dim3(w.wgs_per_cell * n_cells), dim3(256), 0, s, w));
     }
