@@ -230,7 +230,7 @@ int make_plan(const lstm_config *c, Plan &p) {
             }
         }
         // Narrow layers of any depth: each BPTT cell in one launch instead of two.
-        const bool fb_ok = p.W == 1 && fused_backward_supported(p.dtype, p.B, p.H);
+        const bool fb_ok = fused_backward_supported(p.dtype, p.B, p.H);
         if (p.wf || fb_ok) {
             // The backward pass along the diagonals keeps every layer's dA (row-major and blocked) until
             // the weight-gradient GEMMs at the end, instead of one layer's at a time.  It is used while

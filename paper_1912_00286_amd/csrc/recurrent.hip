@@ -861,8 +861,12 @@ RecurrentDims recurrent_dims(int B, int H) {
 
 // Few K chunks and many batch tiles: one-wavefront workgroups, one 64-row tile each over the
 // whole K range, instead of a four-way K split with an LDS reduction.
-// Narrow layers (a cell is at most 128 workgroups of 64 rows x 32 units) with 16-byte-friendly width.
-static bool narrow_cells(const RecurrentDims &d, int H) { return H % 8 == 0 && d.n_mt * d.n_hb <= 128; }
+// Narrow layers with a 16-byte-friendly width: the kernels that keep a whole cell in one launch.  Their
+// backward form contracts over all 4H gate rows inside each workgroup, which stops paying above H = 768,
+// and their small tiles re-read the operands too often once the batch is in the thousands (measured
+// against the two-launch form: ahead or level for H <= 768 up to batch 4096 at H = 200..256, 1.6x behind
+// at H = 2048, 12 % behind at H = 200 with 8192 rows).
+static bool narrow_cells(const RecurrentDims &d, int H) { return H % 8 == 0 && H <= 768 && d.n_mt * d.n_hb <= 512; }
 // Tile edge of the narrow-layer kernels: 16 while that keeps a cell within a few hundred workgroups
 // (the smaller the tile, the fewer bytes each compute unit pulls in), else 32.
 static int narrow_tile(int B, int H) { return ((B + 15) / 16) * ((H + 15) / 16) <= 512 ? 16 : 32; }

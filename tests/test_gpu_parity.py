@@ -50,6 +50,8 @@ SMALL = [
     ("s_fp16_L3_T1", 3, 8, 40, 1, 5, "fp16", wl.HEAD_STEP_BCE),        # anti-diagonal schedule, a single time step
     ("s_bf16_L9_T3", 9, 8, 24, 3, 4, "bf16", wl.HEAD_STEP_MSE),        # more layers than cells per launch, L > T
     ("s_fp16_L4_last", 4, 10, 72, 7, 9, "fp16", wl.HEAD_LAST_BCE),     # four layers, last-step head, ragged sizes
+    ("s_fp16_tile32", 2, 24, 264, 3, 600, "fp16", wl.HEAD_STEP_MSE),   # narrow-layer kernels on 32x32 tiles, ragged both ways
+    ("s_bf16_tile32", 1, 40, 264, 2, 600, "bf16", wl.HEAD_STEP_BCE),
 ]
 
 
