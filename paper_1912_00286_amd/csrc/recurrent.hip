@@ -112,21 +112,28 @@ __device__ __forceinline__ void packed_mainloop(const uint16_t *Apk, const uint1
 // holds in out[rr][nb] (rr = 0..7) the totals for m-block (q >> 1), accumulator
 // registers r = 8 (q & 1) + rr, B block nb.
 __device__ __forceinline__ void reduce_waves(float *red, int wave, int lane, v16f (&acc)[2][NBLK], float (&out)[8][NBLK]) {
-    float *mine = red + wave * RED_FLOATS;
+    // four consecutive accumulator registers travel as one 16-byte LDS access
+    v4f *red4 = reinterpret_cast<v4f *>(red);
+    v4f *mine = red4 + wave * (RED_FLOATS / 4);
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int nb = 0; nb < NBLK; ++nb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) mine[((mb * NBLK + nb) * 16 + r) * 64 + lane] = acc[mb][nb][r];
+            for (int r4 = 0; r4 < 4; ++r4) {
+                v4f v = {acc[mb][nb][4 * r4], acc[mb][nb][4 * r4 + 1], acc[mb][nb][4 * r4 + 2], acc[mb][nb][4 * r4 + 3]};
+                mine[((mb * NBLK + nb) * 4 + r4) * 64 + lane] = v;
+            }
     __syncthreads();
-    const int mb = wave >> 1, rh = (wave & 1) * 8;
+    const int mb = wave >> 1, rq = (wave & 1) * 2;
 #pragma unroll
-    for (int rr = 0; rr < 8; ++rr)
+    for (int q = 0; q < 2; ++q)
 #pragma unroll
         for (int nb = 0; nb < NBLK; ++nb) {
-            const int idx = ((mb * NBLK + nb) * 16 + rh + rr) * 64 + lane;
-            out[rr][nb] = (red[idx] + red[RED_FLOATS + idx]) + (red[2 * RED_FLOATS + idx] + red[3 * RED_FLOATS + idx]);
+            const int idx = ((mb * NBLK + nb) * 4 + rq + q) * 64 + lane;
+            const v4f s = (red4[idx] + red4[RED_FLOATS / 4 + idx]) + (red4[2 * (RED_FLOATS / 4) + idx] + red4[3 * (RED_FLOATS / 4) + idx]);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) out[q * 4 + k][nb] = s[k];
         }
 }
 
