@@ -323,14 +323,32 @@ __global__ void embed_gather_kernel(const int32_t *ids, const T *E, T *X, int ro
         X[e] = E[(int64_t)id * D + d];
     }
 }
+// dE[id[r]] += dX[r].  Token frequencies are heavy-tailed (a bounded Zipf law here), so plain atomics
+// serialise on the few hottest rows of the table: thousands of additions to the same 128 addresses.  Each
+// workgroup therefore owns a contiguous slice of the tokens, sums the rows with id < hot_rows in LDS and
+// adds that table to memory once at the end; all other rows go to memory directly.  Correct for any ids
+// (the split is by value, not by frequency); the summation order is not fixed either way.
+constexpr int SCATTER_LDS_FLOATS = 8192;
 template <typename T>
-__global__ void embed_scatter_kernel(const int32_t *ids, const T *dX, float *dE, int rows, int V, int D) {
-    const int64_t n = (int64_t)rows * D;
-    for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x) {
+__global__ __launch_bounds__(256) void embed_scatter_kernel(const int32_t *ids, const T *dX, float *dE, int rows, int V, int D,
+                                                            int rows_per_wg, int hot_rows) {
+    __shared__ float hot[SCATTER_LDS_FLOATS];
+    const int hot_n = hot_rows * D;
+    for (int i = threadIdx.x; i < hot_n; i += 256) hot[i] = 0.0f;
+    __syncthreads();
+    const int r0 = blockIdx.x * rows_per_wg, r1 = min(rows, r0 + rows_per_wg);
+    for (int64_t e = (int64_t)r0 * D + threadIdx.x; e < (int64_t)r1 * D; e += 256) {
         const int r = (int)(e / D), d = (int)(e % D);
         int id = ids[r];
         id = id < 0 ? 0 : (id >= V ? V - 1 : id);
-        atomicAdd(&dE[(int64_t)id * D + d], Lp<T>::to_f(dX[e]));
+        const float v = Lp<T>::to_f(dX[e]);
+        if (id < hot_rows) atomicAdd(&hot[id * D + d], v);
+        else atomicAdd(&dE[(int64_t)id * D + d], v);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < hot_n; i += 256) {
+        const float v = hot[i];
+        if (v != 0.0f) atomicAdd(&dE[i], v);
     }
 }
 template <typename T>
@@ -505,9 +523,16 @@ int embed_gather(int dtype, const int32_t *ids, const void *E, void *X, int rows
 
 int embed_scatter_add(int dtype, const int32_t *ids, const void *dX, float *dE32, int rows, int V, int D, hipStream_t s) {
     KernelTimer timer(KC_AUX, s, 0.0, 0.0);
-    const int64_t n = (int64_t)rows * D;
-    LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(embed_scatter_kernel<T>, dim3(blocks_for(n, 256, 16384)), dim3(256), 0, s, ids,
-                                               (const T *)dX, dE32, rows, V, D));
+    if (rows <= 0 || D <= 0) return LSTM_OK;
+    int hot_rows = SCATTER_LDS_FLOATS / D;                     // rows of the table summed in LDS (0: D too wide, all direct)
+    if (hot_rows > 64) hot_rows = 64;
+    if (hot_rows > V) hot_rows = V;
+    // about two workgroups per four compute units: few enough that the hot rows see little contention
+    int rows_per_wg = (rows + 127) / 128;
+    if (rows_per_wg < 16) rows_per_wg = 16;
+    const int grid = (rows + rows_per_wg - 1) / rows_per_wg;
+    LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(embed_scatter_kernel<T>, dim3(grid), dim3(256), 0, s, ids, (const T *)dX, dE32, rows, V,
+                                               D, rows_per_wg, hot_rows));
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
