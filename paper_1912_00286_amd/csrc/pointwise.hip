@@ -13,6 +13,14 @@ namespace lstm {
         default: set_error("bad dtype %d", dtype); return LSTM_ERR_INVALID; \
     }
 
+// 16-bit storage types only (the 16-byte vector kernels)
+#define LP16_DISPATCH(dtype, T, ...)                               \
+    switch (dtype) {                                               \
+        case LSTM_DTYPE_FP16: { using T = _Float16; __VA_ARGS__; } break; \
+        case LSTM_DTYPE_BF16: { using T = bf16_t; __VA_ARGS__; } break;   \
+        default: set_error("bad dtype %d", dtype); return LSTM_ERR_INVALID; \
+    }
+
 namespace {
 
 // Rows of several simulated workers interleave in the time-major activations: logical row r of
@@ -261,6 +269,73 @@ __global__ __launch_bounds__(256) void head_forward_kernel(int head, const T *h_
     __syncthreads();
     if (threadIdx.x == 0) partial[blockIdx.x] = (wl[0] + wl[1]) + (wl[2] + wl[3]);
 }
+// The same with 16-byte loads (H % 8 == 0, aligned rows): LPR lanes (a power of two, at most 64) share a
+// row, each lane-group takes the four consecutive rows of one partial sum.
+template <typename T>
+__device__ __forceinline__ float dot8(const u32x4 &a, const u32x4 &b) {
+    __attribute__((aligned(16))) T x[8], y[8];
+    *reinterpret_cast<u32x4 *>(x) = a;
+    *reinterpret_cast<u32x4 *>(y) = b;
+    float s = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) s += Lp<T>::to_f(x[k]) * Lp<T>::to_f(y[k]);
+    return s;
+}
+template <typename T>
+__global__ __launch_bounds__(256) void head_forward_vec_kernel(int head, const T *h_top, const T *w, const T *b,
+                                                               const float *targets, int rows, int H, float inv_M,
+                                                               float *dzu, float *partial, int lpr) {
+    const int nvec = H / 8;
+    const int sub = threadIdx.x & (lpr - 1);
+    const int64_t group = ((int64_t)blockIdx.x * 256 + threadIdx.x) / lpr;      // rows 4 group .. 4 group + 3
+    const int64_t row0 = group * 4;
+    if (row0 >= rows) return;                          // whole lane-groups leave together; no barrier below
+    const u32x4 *wv = reinterpret_cast<const u32x4 *>(w);
+    float dot[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int v = sub; v < nvec; v += lpr) {
+        const u32x4 wq = wv[v];
+        u32x4 hq[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int64_t r = row0 + k < rows ? row0 + k : rows - 1;
+            hq[k] = reinterpret_cast<const u32x4 *>(h_top + r * H)[v];
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) dot[k] += dot8<T>(hq[k], wq);
+    }
+    for (int off = lpr >> 1; off > 0; off >>= 1) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) dot[k] += __shfl_xor(dot[k], off, 64);
+    }
+    if (sub != 0) return;
+    const float bias = Lp<T>::to_f(b[0]);
+    float ell_sum = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        if (row0 + k >= rows) break;
+        const float z = dot[k] + bias;
+        const float y = targets[row0 + k];
+        float d, ell;
+        if (head == LSTM_HEAD_STEP_MSE) {
+            const float r = z - y;
+            ell = r * r;
+            d = 2.0f * r;
+        } else if (head == LSTM_HEAD_FC_HINGE) {
+            const float m = 1.0f - y * z;
+            ell = fmaxf(m, 0.0f);
+            d = m > 0.0f ? -y : 0.0f;
+        } else {
+            const float az = fabsf(z);
+            const float e = expf(-az);
+            ell = fmaxf(z, 0.0f) - z * y + log1pf(e);
+            const float sg = z >= 0.0f ? 1.0f / (1.0f + e) : e / (1.0f + e);
+            d = sg - y;
+        }
+        dzu[row0 + k] = d * inv_M;
+        ell_sum += ell;
+    }
+    partial[group] = ell_sum;
+}
 // one workgroup per worker: partial sum i covers rows 4i..4i+3, all of one worker (seg % 4 == 0
 // whenever there are several)
 __global__ __launch_bounds__(256) void loss_final_kernel(const float *partial, int n, float inv_M, float *loss, RowSeg rs) {
@@ -289,6 +364,27 @@ __global__ void head_backward_dh_kernel(const float *dzu, const T *w, const floa
         float v = S * dzu[r] * Lp<T>::to_f(w[j]);
         if (relu_of && !(Lp<T>::to_f(relu_of[e]) > 0.0f)) v = 0.0f;
         dh[e] = Lp<T>::from_f(v);
+    }
+}
+template <typename T>
+__global__ void head_backward_dh_vec_kernel(const float *dzu, const T *w, const float *scale_dev, const T *relu_of, T *dh,
+                                            int rows, int H) {
+    const float S = *scale_dev;
+    const int nvec = H / 8;
+    const int64_t n = (int64_t)rows * nvec;
+    for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x) {
+        const int r = (int)(e / nvec), v = (int)(e % nvec);
+        __attribute__((aligned(16))) T wq[8], rq[8], out[8];
+        *reinterpret_cast<u32x4 *>(wq) = reinterpret_cast<const u32x4 *>(w)[v];
+        if (relu_of) *reinterpret_cast<u32x4 *>(rq) = reinterpret_cast<const u32x4 *>(relu_of)[e];
+        const float g = S * dzu[r];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            float x = g * Lp<T>::to_f(wq[k]);
+            if (relu_of && !(Lp<T>::to_f(rq[k]) > 0.0f)) x = 0.0f;
+            out[k] = Lp<T>::from_f(x);
+        }
+        reinterpret_cast<u32x4 *>(dh)[e] = *reinterpret_cast<const u32x4 *>(out);
     }
 }
 template <typename T>
@@ -476,8 +572,18 @@ int head_forward(int dtype, int head, const void *h_top, const void *w, const vo
     const int nb = head_loss_blocks(rows);
     const float inv_M = 1.0f / (float)M_total;
     const RowSeg rs{workers, workers > 1 ? seg : 1};
-    LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(head_forward_kernel<T>, dim3(nb), dim3(256), 0, s, head, (const T *)h_top,
-                                               (const T *)w, (const T *)b, targets, rows, H, inv_M, dzu, partial));
+    const bool vec = dtype != LSTM_DTYPE_FP32 && H % 8 == 0 && ((uintptr_t)h_top | (uintptr_t)w) % 16 == 0;
+    if (vec) {
+        int lpr = 1;
+        while (lpr < 64 && lpr < H / 8) lpr <<= 1;
+        const int groups_per_wg = 256 / lpr;
+        LP16_DISPATCH(dtype, T, hipLaunchKernelGGL(head_forward_vec_kernel<T>, dim3((nb + groups_per_wg - 1) / groups_per_wg), dim3(256),
+                                                   0, s, head, (const T *)h_top, (const T *)w, (const T *)b, targets, rows, H, inv_M,
+                                                   dzu, partial, lpr));
+    } else {
+        LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(head_forward_kernel<T>, dim3(nb), dim3(256), 0, s, head, (const T *)h_top,
+                                                   (const T *)w, (const T *)b, targets, rows, H, inv_M, dzu, partial));
+    }
     LSTM_LAUNCH_CHECK();
     hipLaunchKernelGGL(loss_final_kernel, dim3(workers), dim3(256), 0, s, partial, nb, inv_M, loss, rs);
     LSTM_LAUNCH_CHECK();
@@ -488,8 +594,14 @@ int head_backward_dh(int dtype, const float *dzu, const void *w, const float *sc
                      int rows, int H, hipStream_t s) {
     KernelTimer timer(KC_AUX, s, 0.0, 0.0);
     const int64_t n = (int64_t)rows * H;
-    LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(head_backward_dh_kernel<T>, dim3(blocks_for(n, 256, 8192)), dim3(256), 0, s,
-                                               dzu, (const T *)w, scale_dev, (const T *)relu_of, (T *)dh, rows, H));
+    const bool vec = dtype != LSTM_DTYPE_FP32 && H % 8 == 0 && ((uintptr_t)w | (uintptr_t)relu_of | (uintptr_t)dh) % 16 == 0;
+    if (vec) {
+        LP16_DISPATCH(dtype, T, hipLaunchKernelGGL(head_backward_dh_vec_kernel<T>, dim3(blocks_for(n / 8, 256, 8192)), dim3(256), 0, s,
+                                                   dzu, (const T *)w, scale_dev, (const T *)relu_of, (T *)dh, rows, H));
+    } else {
+        LSTM_DISPATCH(dtype, T, hipLaunchKernelGGL(head_backward_dh_kernel<T>, dim3(blocks_for(n, 256, 8192)), dim3(256), 0, s,
+                                                   dzu, (const T *)w, scale_dev, (const T *)relu_of, (T *)dh, rows, H));
+    }
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
