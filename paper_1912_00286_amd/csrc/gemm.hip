@@ -719,6 +719,13 @@ int gemm_pick_splits(int dtype, int M, int N, int K) {
     long maxs = K / (4 * BK);
     if (want > maxs) want = maxs;
     if (want > 256) want = 256;
+    // every split writes an fp32 copy of the result that the reduction reads back: keep that traffic
+    // (it, not the products, is what a small-output contraction costs) within a few megabytes
+    // ... but no split longer than 32 K tiles while workgroups are still to be had
+    long cap = (8L << 20) / ((long)M * N * 4);
+    const long by_length = (K + 32 * BK - 1) / (32 * BK);
+    if (cap < by_length) cap = by_length;
+    if (want > cap) want = cap;
     return want < 1 ? 1 : (int)want;
 }
 
