@@ -274,6 +274,22 @@ int make_plan(const lstm_config *c, Plan &p) {
 inline char *at(void *base, size_t off) { return reinterpret_cast<char *>(base) + off; }
 inline const char *at(const void *base, size_t off) { return reinterpret_cast<const char *>(base) + off; }
 
+// The packing jobs and zero fills a pass starts with, collected and sent as one launch (16-bit types;
+// the fp32 mode has no packed operands and keeps its plain fills).
+struct SetupBatch {
+    std::vector<SetupJob> jobs;
+    void pack_u_forward(const void *U, void *dst) { jobs.push_back(SetupJob{SETUP_PACK_U_FORWARD, U, dst, 0}); }
+    void pack_u_backward(const void *U, void *dst) { jobs.push_back(SetupJob{SETUP_PACK_U_BACKWARD, U, dst, 0}); }
+    void pack_rows(const void *h, void *dst) { jobs.push_back(SetupJob{SETUP_PACK_ROWS, h, dst, 0}); }
+    void zero(void *dst, int64_t n_words) { if (n_words > 0) jobs.push_back(SetupJob{SETUP_ZERO, nullptr, dst, n_words}); }
+    int flush(int dtype, int B, int H, hipStream_t s) {
+        if (jobs.empty()) return LSTM_OK;
+        const int rc = setup_jobs(dtype, jobs.data(), (int)jobs.size(), B, H, s);
+        jobs.clear();
+        return rc;
+    }
+};
+
 int check_ptr(const void *p, const char *name, bool required = true) {
     if (!p) {
         if (!required) return LSTM_OK;
@@ -394,6 +410,7 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
     char *ax = at(scratch, p.s_ax);
     const bool fused = p.dtype != LSTM_DTYPE_FP32;
     const size_t axs = fused ? es : 4;
+    SetupBatch setup;
     for (int l = 0; l < p.L; ++l) {
         const void *W = par + p.off_W[l] * es, *U = par + p.off_U[l] * es, *b = par + p.off_b[l] * es;
         char *gates = at(reserve, p.r_gates[l]);
@@ -403,7 +420,7 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
         // input projection of the whole sequence: Ax = X W^T + b  (along the anti-diagonals only
         // layer 0 has its input ahead of time; the layers above project inside their step kernels)
         if (p.wf && l > 0) {
-            LSTM_TRY(pack_u_forward(p.dtype, W, at(scratch, p.s_wf_wpk[l]), p.H, s));
+            setup.pack_u_forward(W, at(scratch, p.s_wf_wpk[l]));
         } else if (p.blk) {
             // operands in 64x64 blocks: layer 0 packs the input once, upper layers read the blocked
             // hidden sequence the step kernels of the layer below wrote
@@ -437,19 +454,23 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
         if (fused) {
             // recurrent weights and the initial hidden state in packed tile order; the second
             // packed-h buffer only needs its zero padding
-            LSTM_TRY(pack_u_forward(p.dtype, U, upk, p.H, s));
-            LSTM_TRY(pack_rows(p.dtype, h0 ? at(h0, (size_t)l * BH * es) : nullptr, hpk[0], p.B, p.H, s));
-            LSTM_TRY(pack_rows(p.dtype, nullptr, hpk[1], p.B, p.H, s));
+            setup.pack_u_forward(U, upk);
+            setup.pack_rows(h0 ? at(h0, (size_t)l * BH * es) : nullptr, hpk[0]);
+            setup.pack_rows(nullptr, hpk[1]);
         }
         char *hblk = p.blk ? at(reserve, p.r_hblk[l]) : nullptr;
         const size_t slot = (size_t)(p.B / 64) * p.h_ncb * 4096 * es;      // bytes of one time slot of the blocked sequence
         if (p.blk) {
             // zero padding columns (H not a multiple of 64) once, then slot 0 = initial hidden state
-            if (p.H % 64 != 0) LSTM_TRY(fill_u32(hblk, 0, (int64_t)(blocked_elems((int)(TB + p.B), p.H) * es / 4), s));
-            if (h0) LSTM_TRY(pack_blocked(p.dtype, at(h0, (size_t)l * BH * es), p.H, p.B, p.H, hblk, s));
-            else if (p.H % 64 == 0) LSTM_TRY(fill_u32(hblk, 0, (int64_t)(slot / 4), s));
+            if (p.H % 64 != 0) setup.zero(hblk, (int64_t)(blocked_elems((int)(TB + p.B), p.H) * es / 4));
+            else if (!h0) setup.zero(hblk, (int64_t)(slot / 4));
+            if (h0) {
+                LSTM_TRY(setup.flush(p.dtype, p.B, p.H, s));     // the padding is cleared before slot 0 is written
+                LSTM_TRY(pack_blocked(p.dtype, at(h0, (size_t)l * BH * es), p.H, p.B, p.H, hblk, s));
+            }
         }
         if (p.wf) continue;                                   // the time steps follow below, diagonal by diagonal
+        LSTM_TRY(setup.flush(p.dtype, p.B, p.H, s));
         for (int t = 0; t < p.T; ++t) {
             char *a_t = ax + (size_t)t * p.B * p.G * axs;
             if (fused) {
@@ -476,6 +497,7 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
         layer_in = hs + (size_t)BH * es;   // h_1..h_T feed the next layer
     }
     if (p.wf) {
+        LSTM_TRY(setup.flush(p.dtype, p.B, p.H, s));              // every layer's packing in one launch
         // cell (l, t) needs (l, t-1) and (l-1, t): all cells with l + t = d are independent
         const int max_cells = wave_forward_max_cells();
         const size_t slot = p.blk ? (size_t)(p.B / 64) * p.h_ncb * 4096 * es : 0;
@@ -629,16 +651,16 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
         // dA_{l+1,t} W_{l+1} (the layer above, same step), both products of cells on the diagonal before.
         // Per diagonal: one launch with the gate arithmetic of all its cells, one with their products.
         const RecurrentDims rd = recurrent_dims(p.B, p.H);
+        SetupBatch setup;
         for (int l = 0; l < p.L; ++l) {
-            LSTM_TRY(pack_u_backward(p.dtype, par + p.off_U[l] * es, at(scratch, p.s_wb_utpk[l]), p.H, s));
-            if (l > 0) LSTM_TRY(pack_u_backward(p.dtype, par + p.off_W[l] * es, at(scratch, p.s_wb_wtpk[l]), p.H, s));
-            LSTM_TRY(fill_u32(at(scratch, p.s_wb_dapk[l]), 0, (int64_t)((rd.dapk_elems * es + 3) / 4), s));
-            if (p.blk && p.G % 64 != 0)
-                LSTM_TRY(fill_u32(at(scratch, p.s_wb_dablk[l]), 0, (int64_t)(blocked_elems(TB, p.G) * es / 4), s));
+            setup.pack_u_backward(par + p.off_U[l] * es, at(scratch, p.s_wb_utpk[l]));
+            if (l > 0) setup.pack_u_backward(par + p.off_W[l] * es, at(scratch, p.s_wb_wtpk[l]));
+            setup.zero(at(scratch, p.s_wb_dapk[l]), (int64_t)((rd.dapk_elems * es + 3) / 4));
+            if (p.fb) setup.zero(at(scratch, p.s_wb_dapk1[l]), (int64_t)((rd.dapk_elems * es + 3) / 4));
+            if (p.blk && p.G % 64 != 0) setup.zero(at(scratch, p.s_wb_dablk[l]), (int64_t)(blocked_elems(TB, p.G) * es / 4));
         }
+        LSTM_TRY(setup.flush(p.dtype, p.B, p.H, s));
         if (p.fb) {
-            for (int l = 0; l < p.L; ++l)
-                LSTM_TRY(fill_u32(at(scratch, p.s_wb_dapk1[l]), 0, (int64_t)((rd.dapk_elems * es + 3) / 4), s));
             // one launch per diagonal: every cell contracts over all 4H gate rows itself
             const int max_cells = fused_backward_max_cells();
             std::vector<FusedBackwardCell> fc;
@@ -719,11 +741,13 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
         char *dapk[2] = {at(scratch, p.s_apk[0]), at(scratch, p.s_apk[1])};
         if (fused && !p.wb) {
             const RecurrentDims rd = recurrent_dims(p.B, p.H);
-            LSTM_TRY(pack_u_backward(p.dtype, par + p.off_U[l] * es, utpk, p.H, s));
-            for (int k = 0; k < 2; ++k) LSTM_TRY(fill_u32(dapk[k], 0, (int64_t)((rd.dapk_elems * es + 3) / 4), s));
+            SetupBatch setup;
+            setup.pack_u_backward(par + p.off_U[l] * es, utpk);
+            for (int k = 0; k < 2; ++k) setup.zero(dapk[k], (int64_t)((rd.dapk_elems * es + 3) / 4));
+            if (p.blk && p.G % 64 != 0) setup.zero(at(scratch, p.s_dablk), (int64_t)(blocked_elems(TB, p.G) * es / 4));
+            LSTM_TRY(setup.flush(p.dtype, p.B, p.H, s));
         }
         char *dablk = p.blk ? at(scratch, p.wb ? p.s_wb_dablk[l] : p.s_dablk) : nullptr;
-        if (!p.wb && p.blk && p.G % 64 != 0) LSTM_TRY(fill_u32(dablk, 0, (int64_t)(blocked_elems(TB, p.G) * es / 4), s));
         for (int t = p.wb ? -1 : p.T - 1; t >= 0; --t) {      // along the diagonals the steps are already done
             const bool last = t == p.T - 1;
             if (fused) {

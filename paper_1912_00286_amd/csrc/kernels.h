@@ -78,6 +78,15 @@ int pack_u_forward(int dtype, const void *U, void *Upk, int H, hipStream_t s);
 int pack_u_backward(int dtype, const void *U, void *UTpk, int H, hipStream_t s);
 // hpk = packed copy of row-major h [B,H] (h null = zeros); also clears the padding
 int pack_rows(int dtype, const void *h, void *hpk, int B, int H, hipStream_t s);
+// several packing jobs and zero fills in one launch (16-bit types)
+enum { SETUP_PACK_U_FORWARD = 0, SETUP_PACK_U_BACKWARD = 1, SETUP_PACK_ROWS = 2, SETUP_ZERO = 3 };
+struct SetupJob {
+    int kind;
+    const void *src;      // U / W [4H,H], or h [B,H] (null: zeros) for SETUP_PACK_ROWS; unused for SETUP_ZERO
+    void *dst;
+    int64_t n_words;      // SETUP_ZERO: 32-bit words to clear
+};
+int setup_jobs(int dtype, const SetupJob *jobs, int n_jobs, int B, int H, hipStream_t s);
 // forward: gates, c, h of one step from packed h_prev, packed U and the step's input projection Ax (lp, bias included);
 // h_blk (nullable): first block row of this time slot in a 64x64-blocked copy of the hidden sequence
 int step_forward_fused(int dtype, const void *hpk_prev, const void *Upk, const void *Ax, float *c_state, void *gates,

@@ -813,8 +813,7 @@ __global__ __launch_bounds__(256) void lstm_narrow_forward_kernel(WaveFwdArgs w)
 // ---------------------------------------------------------------- packing
 // chunk (hb, kc) of Upk, row g*32 + r, column kk = U[g*H + hb*32 + r][kc*64 + kk], zero outside
 template <typename T>
-__global__ __launch_bounds__(256) void pack_u_forward_kernel(const T *U, T *Upk, int H, int nkc) {
-    const int hb = blockIdx.y, kc = blockIdx.x;
+__device__ __forceinline__ void pack_u_forward_block(const T *U, T *Upk, int H, int nkc, int kc, int hb) {
     T *dst = Upk + ((int64_t)hb * nkc + kc) * B_CHUNK;
     for (int v = threadIdx.x; v < B_CHUNK; v += 256) {
         const int row = v >> 6, kk = v & 63;
@@ -825,9 +824,7 @@ __global__ __launch_bounds__(256) void pack_u_forward_kernel(const T *U, T *Upk,
 }
 // chunk (nt, q, kc) of UTpk, row r, column kk = U[q*H + kc*64 + kk][nt*128 + r], zero outside
 template <typename T>
-__global__ __launch_bounds__(256) void pack_u_backward_kernel(const T *U, T *UTpk, int H, int nkc) {
-    __shared__ T tile[64][TN + 2];
-    const int nt = blockIdx.z, q = blockIdx.y, kc = blockIdx.x;
+__device__ __forceinline__ void pack_u_backward_block(const T *U, T *UTpk, int H, int nkc, int kc, int q, int nt, T (*tile)[TN + 2]) {
     // read U rows (k) x columns (units) coalesced along units, write transposed
     for (int v = threadIdx.x; v < 64 * TN; v += 256) {
         const int kk = v / TN, r = v % TN;
@@ -840,12 +837,60 @@ __global__ __launch_bounds__(256) void pack_u_backward_kernel(const T *U, T *UTp
 }
 // chunk (mt, kc) of hpk, row, column kk = h[mt*64 + row][kc*64 + kk] (null h = 0), zero outside
 template <typename T>
-__global__ __launch_bounds__(256) void pack_rows_kernel(const T *h, T *hpk, int B, int H, int nkc) {
-    const int mt = blockIdx.y, kc = blockIdx.x;
+__device__ __forceinline__ void pack_rows_block(const T *h, T *hpk, int B, int H, int nkc, int kc, int mt) {
     T *dst = hpk + ((int64_t)mt * nkc + kc) * A_CHUNK;
     for (int v = threadIdx.x; v < A_CHUNK; v += 256) {
         const int row = mt * 64 + (v >> 6), k = kc * 64 + (v & 63);
         dst[frag_offset(v >> 6, v & 63, 2)] = (h && row < B && k < H) ? h[(int64_t)row * H + k] : Lp<T>::from_f(0.0f);
+    }
+}
+template <typename T>
+__global__ __launch_bounds__(256) void pack_u_forward_kernel(const T *U, T *Upk, int H, int nkc) {
+    pack_u_forward_block<T>(U, Upk, H, nkc, blockIdx.x, blockIdx.y);
+}
+template <typename T>
+__global__ __launch_bounds__(256) void pack_u_backward_kernel(const T *U, T *UTpk, int H, int nkc) {
+    __shared__ T tile[64][TN + 2];
+    pack_u_backward_block<T>(U, UTpk, H, nkc, blockIdx.x, blockIdx.y, blockIdx.z, tile);
+}
+template <typename T>
+__global__ __launch_bounds__(256) void pack_rows_kernel(const T *h, T *hpk, int B, int H, int nkc) {
+    pack_rows_block<T>(h, hpk, B, H, nkc, blockIdx.x, blockIdx.y);
+}
+
+// Several of the above (and plain fills) in one launch: blockIdx.y selects the job.  The set-up of a
+// pass is a dozen small independent kernels, and on narrow layers every launch counts.
+constexpr int SETUP_MAX_JOBS = 16;
+struct SetupJobArg {
+    const void *src;
+    void *dst;
+    int64_t n_words;
+    int kind;
+};
+struct SetupArgs {
+    SetupJobArg job[SETUP_MAX_JOBS];
+    int B, H, nkc, n_mt, n_hb, n_nt;
+};
+template <typename T>
+__global__ __launch_bounds__(256) void setup_jobs_kernel(SetupArgs a) {
+    __shared__ T tile[64][TN + 2];
+    const SetupJobArg &j = a.job[blockIdx.y];
+    const int x = blockIdx.x;
+    switch (j.kind) {                                    // uniform over the workgroup
+        case SETUP_PACK_U_FORWARD:
+            if (x < a.nkc * a.n_hb) pack_u_forward_block<T>((const T *)j.src, (T *)j.dst, a.H, a.nkc, x % a.nkc, x / a.nkc);
+            break;
+        case SETUP_PACK_U_BACKWARD:
+            if (x < a.nkc * 4 * a.n_nt)
+                pack_u_backward_block<T>((const T *)j.src, (T *)j.dst, a.H, a.nkc, x % a.nkc, (x / a.nkc) & 3, x / (4 * a.nkc), tile);
+            break;
+        case SETUP_PACK_ROWS:
+            if (x < a.nkc * a.n_mt) pack_rows_block<T>((const T *)j.src, (T *)j.dst, a.B, a.H, a.nkc, x % a.nkc, x / a.nkc);
+            break;
+        default: {                                       // SETUP_ZERO: n_words 32-bit words
+            uint32_t *d = (uint32_t *)j.dst;
+            for (int64_t i = (int64_t)x * 256 + threadIdx.x; i < j.n_words; i += (int64_t)gridDim.x * 256) d[i] = 0u;
+        }
     }
 }
 
@@ -897,6 +942,40 @@ int pack_u_backward(int dtype, const void *U, void *UTpk, int H, hipStream_t s) 
     KernelTimer timer(KC_AUX, s, 0.0, 0.0);
     LP_ONLY(dtype, T, hipLaunchKernelGGL(pack_u_backward_kernel<T>, dim3(d.nkc, 4, d.n_nt), dim3(256), 0, s, (const T *)U, (T *)UTpk, H, d.nkc));
     LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+int setup_jobs(int dtype, const SetupJob *jobs, int n_jobs, int B, int H, hipStream_t s) {
+    const RecurrentDims d = recurrent_dims(B, H);
+    for (int first = 0; first < n_jobs; first += SETUP_MAX_JOBS) {
+        const int n = n_jobs - first < SETUP_MAX_JOBS ? n_jobs - first : SETUP_MAX_JOBS;
+        SetupArgs a;
+        a.B = B; a.H = H; a.nkc = d.nkc; a.n_mt = d.n_mt; a.n_hb = d.n_hb; a.n_nt = d.n_nt;
+        int64_t grid_x = 1;
+        for (int i = 0; i < SETUP_MAX_JOBS; ++i) {
+            const SetupJob &j = jobs[first + (i < n ? i : 0)];
+            if (!j.dst || (j.kind != SETUP_ZERO && j.kind != SETUP_PACK_ROWS && !j.src) || j.kind < 0 || j.kind > SETUP_ZERO) {
+                set_error("setup_jobs: bad job %d (kind %d)", first + i, j.kind);
+                return LSTM_ERR_INVALID;
+            }
+            a.job[i].src = j.src; a.job[i].dst = j.dst; a.job[i].n_words = j.n_words; a.job[i].kind = j.kind;
+            int64_t need = 1;
+            switch (j.kind) {
+                case SETUP_PACK_U_FORWARD: need = (int64_t)d.nkc * d.n_hb; break;
+                case SETUP_PACK_U_BACKWARD: need = (int64_t)d.nkc * 4 * d.n_nt; break;
+                case SETUP_PACK_ROWS: need = (int64_t)d.nkc * d.n_mt; break;
+                default: need = (j.n_words + 2047) / 2048; if (need > 4096) need = 4096; break;   // 8 words per thread at least
+            }
+            if (need > grid_x) grid_x = need;
+        }
+        if (grid_x > 65535) {
+            set_error("setup_jobs: grid too large");
+            return LSTM_ERR_UNSUPPORTED;
+        }
+        KernelTimer timer(KC_AUX, s, 0.0, 0.0);
+        LP_ONLY(dtype, T, hipLaunchKernelGGL(setup_jobs_kernel<T>, dim3((unsigned)grid_x, n), dim3(256), 0, s, a));
+        LSTM_LAUNCH_CHECK();
+    }
     return LSTM_OK;
 }
 
