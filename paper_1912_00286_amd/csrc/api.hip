@@ -64,7 +64,7 @@ struct Plan {
         const int TB = T * B, I = in_dim[l];
         const bool dx = (l > 0 && !wb) || (l == 0 && V > 0);
         if (dx && !gemm_blocked_supported(dtype, TB, I)) return true;
-        return !gemm_blocked_supported(dtype, G, I) || !gemm_blocked_supported(dtype, G, H);
+        return !gemm_blocked_supported(dtype, G, H);          // dW takes the blocked kernel at any input width
     }
     std::vector<int> split_w, split_u;
 };
@@ -820,8 +820,10 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
         GemmArgs wt = w, ut = u;
         wt.A = dA; wt.lda = p.G; wt.B = layer_in; wt.ldb = I;
         ut.A = dA; ut.lda = p.G; ut.B = hs; ut.ldb = p.H;                 // h_0..h_{T-1}
-        // several workers: always the blocked kernel (its per-worker K mapping), whatever the width
-        const bool w_blk = p.blk && (p.W > 1 || gemm_blocked_supported(p.dtype, p.G, I));
+        // dW: always the blocked kernel when the blocked copies exist, whatever the input width (a narrow
+        // input wastes part of a tile, the alternative is two transposes); several workers need it anyway
+        // (its per-worker K mapping)
+        const bool w_blk = p.blk;
         const bool u_blk = p.blk && (p.W > 1 || gemm_blocked_supported(p.dtype, p.G, p.H));
         const bool w_tn = !w_blk && gemm_tn_supported(p.dtype, wt), u_tn = !u_blk && gemm_tn_supported(p.dtype, ut);
         if ((!w_blk && !w_tn) || (!u_blk && !u_tn)) LSTM_TRY(transpose_lp(p.dtype, dA, p.G, dAT, TB, TB, p.G, s));
