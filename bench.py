@@ -158,7 +158,7 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibration": "5 device copies", "bytes_read_each": 2 * n, "bytes_written_each": 2 * n}))
         return
-    w = wl.CONFIGS[args.workload]
+    w = wl.CONFIGS[args.workload] if args.workload in wl.CONFIGS else wl.EXTRA[args.workload]
     if args.dtype and args.dtype != w.dtype:
         w = w.with_(dtype=args.dtype, **({"loss_scale": 1.0, "dynamic_scale": False} if args.dtype == "bf16" else {}))
     dev = torch.device("cuda:0")

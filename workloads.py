@@ -87,6 +87,16 @@ CONFIGS: Dict[str, Workload] = {
 }
 
 
+# Not one of the five benchmark configurations: the paper's own network (Fig. 2: 9 signals, two LSTM
+# layers of 200 units, a fully connected ReLU layer of 200 units on every temporal slice, one output,
+# hinge loss) at its batch size 256, sequence length 128 and static loss multiplier 10, on synthetic
+# signals.  `bench.py --workload fig2` reports it.
+EXTRA: Dict[str, Workload] = {
+    "fig2": Workload("fig2", 2, 9, 200, 128, 256, "fp16", HEAD_FC_HINGE, fc_units=200, target_kind="sign",
+                     target_p=0.1, loss_scale=10.0, data_seed=43, weight_seed=44),
+}
+
+
 def param_segments(w: Workload) -> List[Tuple[str, Tuple[int, ...]]]:
     """Names and shapes of the parameter tensors in flat-buffer order.
 
