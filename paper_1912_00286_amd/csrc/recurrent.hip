@@ -27,7 +27,15 @@
 //   U packed for the backward : [unit tile of 128][gate][K chunk] blocks (transposed on the fly)
 //   h / dA packed             : [batch tile of 64]([gate])[K chunk] blocks
 // The epilogues write the next step's A operand directly in packed order (and
-// in plain row-major order for the whole-sequence GEMMs).
+// in row-major / 64x64-blocked order for the whole-sequence GEMMs).
+//
+// Three families share those operands:
+//   * the kernels above (any H; a second form, WIDE, for H <= 512 with >= 1024 rows);
+//   * their multi-cell forms (several independent (layer, time) cells per launch) for the
+//     anti-diagonal schedule of stacks of narrow layers;
+//   * the narrow-layer kernels (H <= 768, H % 8 == 0): a whole cell per launch on 16x16 or 32x32
+//     tiles, the BPTT cell with its products and gate arithmetic in ONE launch.
+// The host wrappers at the end of the file pick the family from the shape.
 #include "kernels.h"
 
 namespace lstm {
