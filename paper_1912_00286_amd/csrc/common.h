@@ -83,7 +83,12 @@ template <> struct Lp<_Float16> {
 template <> struct Lp<bf16_t> {
     static constexpr int code = LSTM_DTYPE_BF16;
     __device__ static inline float to_f(bf16_t v) { return bf16_to_float(v); }
-    __device__ static inline bf16_t from_f(float v) { return float_to_bf16(v); }
+    // the hardware conversion (round to nearest even, NaN stays NaN): one instruction instead of five
+    __device__ static inline bf16_t from_f(float v) {
+        bf16_t r;
+        r.bits = __builtin_bit_cast(unsigned short, (__bf16)v);
+        return r;
+    }
     __device__ static inline v16f mfma(const u32x4 &a, const u32x4 &b, v16f c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8b, a), __builtin_bit_cast(v8b, b), c, 0, 0, 0);
     }

@@ -133,8 +133,8 @@ template <> struct Pack4<_Float16> {
 template <> struct Pack4<bf16_t> {
     __device__ static inline void store(bf16_t *o, float a, float b, float c, float d) {
         uint2 v;
-        v.x = float_to_bf16(a).bits | ((uint32_t)float_to_bf16(b).bits << 16);
-        v.y = float_to_bf16(c).bits | ((uint32_t)float_to_bf16(d).bits << 16);
+        v.x = Lp<bf16_t>::from_f(a).bits | ((uint32_t)Lp<bf16_t>::from_f(b).bits << 16);
+        v.y = Lp<bf16_t>::from_f(c).bits | ((uint32_t)Lp<bf16_t>::from_f(d).bits << 16);
         *reinterpret_cast<uint2 *>(o) = v;
     }
 };
