@@ -51,6 +51,13 @@ constexpr int RED_FLOATS = 8 * 16 * 64;   // one wavefront's 8 accumulator block
 constexpr int A_CHUNK = TM * SK;       // elements of one packed A block
 constexpr int B_CHUNK = TN * SK;       // elements of one packed B block
 
+// A small kernel in a chain of dependent launches starts with dependent memory round trips (arguments,
+// then operands), and the compiler fetches kernel arguments lazily, next to their first use: up to nine
+// scalar loads one after the other were measured.  Naming a value as an input of an empty asm statement
+// makes its load issue there, together with its neighbours'.
+template <typename V>
+__device__ __forceinline__ void fetch_now(const V &v) { asm volatile("" ::"s"(v)); }
+
 // offset of element (row, kk) inside a packed chunk whose rows form `nblk` blocks of 32
 __host__ __device__ inline int frag_offset(int row, int kk, int nblk) {
     const int blk = row >> 5, r = row & 31, ks = kk >> 4, half = (kk >> 3) & 1, j = kk & 7;
@@ -490,6 +497,8 @@ __global__ __launch_bounds__(256) void gates_backward_packed_kernel(const T *dh_
                                                                     const T *c_t, const T *c_prev, float *dc_state, T *dA,
                                                                     T *dApk, T *dAblk, int blk_ncb, int B, int H, int nkc,
                                                                     int first) {
+    fetch_now(dh_above); fetch_now(partials); fetch_now(gates); fetch_now(c_t); fetch_now(c_prev); fetch_now(dc_state); fetch_now(dA);
+    fetch_now(dApk); fetch_now(dAblk); fetch_now(blk_ncb); fetch_now(B); fetch_now(H); fetch_now(nkc); fetch_now(first);
     gates_backward_cell<T, W>(dh_above, nullptr, partials, gates, c_t, c_prev, dc_state, dA, dApk, dAblk, blk_ncb, B, H, nkc, first,
                                 blockIdx.x * (int64_t)blockDim.x + threadIdx.x, (int64_t)gridDim.x * blockDim.x);
 }
@@ -547,13 +556,8 @@ struct FusedBwdArgs {
     int blk_ncb, B, H, nkc, wgs_per_cell;
 };
 
-// These kernels start with a chain of dependent memory round trips (arguments, then operands); the
-// compiler fetches kernel arguments lazily, next to their first use, which made that chain nine scalar
-// loads long.  The cell's argument block is therefore copied into registers in one go: cell = blockIdx.y
-// (no division by a loaded value first), every field named as an input of an empty asm statement so
-// that all its loads are issued together.
-template <typename V>
-__device__ __forceinline__ void fetch_now(const V &v) { asm volatile("" ::"s"(v)); }
+// The cell's argument block is copied into registers in one go: cell = blockIdx.y (no division by a
+// loaded value first), every field fetched at the top (fetch_now).
 
 // How an R x R tile maps onto the packed chunks ([k-step of 16][32-row block][lane][8]) and onto the
 // MFMA that multiplies it: 32x32x16 (lane = 32 (k / 8) + row) or 16x16x32 (lane = 16 (k / 8) + row).
