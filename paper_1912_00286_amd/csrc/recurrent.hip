@@ -556,8 +556,8 @@ struct FusedBwdArgs {
     int blk_ncb, B, H, nkc, wgs_per_cell;
 };
 
-// The cell's argument block is copied into registers in one go: cell = blockIdx.y (no division by a
-// loaded value first), every field fetched at the top (fetch_now).
+// The cell's argument block is copied into registers in one go: cell = blockIdx.z, tile = (blockIdx.x,
+// blockIdx.y): no division by a loaded value first, every field fetched at the top (fetch_now).
 
 // How an R x R tile maps onto the packed chunks ([k-step of 16][32-row block][lane][8]) and onto the
 // MFMA that multiplies it: 32x32x16 (lane = 32 (k / 8) + row) or 16x16x32 (lane = 16 (k / 8) + row).
@@ -701,13 +701,11 @@ template <typename T, int R>
 __global__ __launch_bounds__(256) void lstm_fused_backward_kernel(FusedBwdArgs w) {
     typedef NarrowGeo<T, R> Geo;
     constexpr int UG = R / 8, LD = R + 4, NR = Geo::NR;          // 8-unit groups per row, LDS row pitch, accumulator registers
-    const FusedBwdCell c = w.cell[blockIdx.y];                   // uniform: the cell's argument block
+    const FusedBwdCell c = w.cell[blockIdx.z];                   // uniform: the cell's argument block
     fetch_now(c.dApk_next); fetch_now(c.UTpk); fetch_now(c.dApk_above); fetch_now(c.WTpk); fetch_now(c.dh_above); fetch_now(c.gates);
     fetch_now(c.c_t); fetch_now(c.c_prev); fetch_now(c.dc_state); fetch_now(c.dA); fetch_now(c.dApk); fetch_now(c.dAblk);
     fetch_now(c.first); fetch_now(w.B); fetch_now(w.H); fetch_now(w.nkc); fetch_now(w.blk_ncb);
-    const int tile = (int)blockIdx.x;
-    const int n_rt = (w.B + R - 1) / R;
-    const int b0 = (tile % n_rt) * R, u0 = (tile / n_rt) * R;    // first batch row, first hidden unit
+    const int b0 = (int)blockIdx.x * R, u0 = (int)blockIdx.y * R;    // first batch row, first hidden unit
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int H = w.H;
     const int row = tid / UG, ug = tid % UG;
@@ -797,13 +795,11 @@ template <typename T, int R>
 __global__ __launch_bounds__(256) void lstm_narrow_forward_kernel(WaveFwdArgs w) {
     typedef NarrowGeo<T, R> Geo;
     constexpr int UG = R / 8, LD = R + 4, NR = Geo::NR;
-    const FwdArgs a = w.cell[blockIdx.y];
+    const FwdArgs a = w.cell[blockIdx.z];
     fetch_now(a.hpk_prev); fetch_now(a.Upk); fetch_now(a.Ax); fetch_now(a.xpk); fetch_now(a.Wpk); fetch_now(a.bias);
     fetch_now(a.c_state); fetch_now(a.gates); fetch_now(a.c_out); fetch_now(a.h_out); fetch_now(a.hpk_next); fetch_now(a.h_blk);
     fetch_now(a.blk_ncb); fetch_now(a.B); fetch_now(a.H); fetch_now(a.nkc);
-    const int tile = (int)blockIdx.x;
-    const int n_rt = (a.B + R - 1) / R;
-    const int b0 = (tile % n_rt) * R, u0 = (tile / n_rt) * R;
+    const int b0 = (int)blockIdx.x * R, u0 = (int)blockIdx.y * R;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int row = tid / UG, ug = tid % UG;
     const int b = b0 + row, j0 = u0 + ug * 8;
@@ -1126,14 +1122,15 @@ int backward_fused_wave(int dtype, const FusedBackwardCell *c, int n_cells, int 
         return LSTM_ERR_INVALID;
     }
     const int R = narrow_tile(B, H);
-    w.blk_ncb = blk_ncb; w.B = B; w.H = H; w.nkc = d.nkc; w.wgs_per_cell = ((B + R - 1) / R) * ((H + R - 1) / R);
+    const dim3 grid((B + R - 1) / R, (H + R - 1) / R, n_cells);
+    w.blk_ncb = blk_ncb; w.B = B; w.H = H; w.nkc = d.nkc; w.wgs_per_cell = (int)(grid.x * grid.y);
     const double n = (double)B * H;
     // products: 2 B H 4H flops, operands once; gate arithmetic: as in the stand-alone kernel without the partials
     KernelTimer timer(KC_GEMM_STEP, s, chunks * 2.0 * n * 4.0 * H, chunks * 2.0 * (4.0 * H * H + 4.0 * n) + n_cells * n * (8.0 + 15.0 * 2.0));
     if (R == 16) {
-        LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_fused_backward_kernel<T, 16>), dim3(w.wgs_per_cell, n_cells), dim3(256), 0, s, w));
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_fused_backward_kernel<T, 16>), grid, dim3(256), 0, s, w));
     } else {
-        LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_fused_backward_kernel<T, 32>), dim3(w.wgs_per_cell, n_cells), dim3(256), 0, s, w));
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_fused_backward_kernel<T, 32>), grid, dim3(256), 0, s, w));
     }
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
@@ -1176,11 +1173,11 @@ int step_forward_wave(int dtype, const WaveCell *cells, int n_cells, int blk_ncb
     KernelTimer timer(KC_GEMM_STEP, s, flops, bytes);
     if (narrow_cells(d, H) && all % 16 == 0) {
         const int R = narrow_tile(B, H);
-        w.wgs_per_cell = ((B + R - 1) / R) * ((H + R - 1) / R);
+        const dim3 grid((B + R - 1) / R, (H + R - 1) / R, n_cells);
         if (R == 16) {
-            LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_narrow_forward_kernel<T, 16>), dim3(w.wgs_per_cell, n_cells), dim3(256), 0, s, w));
+            LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_narrow_forward_kernel<T, 16>), grid, dim3(256), 0, s, w));
         } else {
-            LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_narrow_forward_kernel<T, 32>), dim3(w.wgs_per_cell, n_cells), dim3(256), 0, s, w));
+            LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_narrow_forward_kernel<T, 32>), grid, dim3(256), 0, s, w));
         }
     } else {
         LP_ONLY(dtype, T, hipLaunchKernelGGL(lstm_wave_forward_kernel<T>, dim3(w.wgs_per_cell * n_cells), dim3(256), 0, s, w));
