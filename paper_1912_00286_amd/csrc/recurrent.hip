@@ -630,32 +630,48 @@ __device__ __forceinline__ void narrow_mainloop(const u32x4 *A1, const u32x4 *B1
         if (k + NS + i < c1) mul(ra[i], rb[i]);
 }
 
-// One batch row x 8 consecutive units of a BPTT cell: operands requested early, finished once the
-// gradient reaching h_t of those units (rec, from the products) is known.
-template <typename T> struct BackwardItem {
-    __attribute__((aligned(16))) T vi[8], vf[8], vg[8], vo[8], vct[8], vcp[8], vdh[8];
-    __attribute__((aligned(16))) float dcs[8];
+// IW consecutive 16-bit values / floats as one access
+template <int BYTES> struct VecOfBytes;
+template <> struct VecOfBytes<16> { typedef u32x4 type; };
+template <> struct VecOfBytes<8> { typedef unsigned int type __attribute__((ext_vector_type(2))); };
+template <> struct VecOfBytes<4> { typedef unsigned int type; };
+template <> struct VecOfBytes<2> { typedef unsigned short type; };
+template <int BYTES, typename D, typename S>
+__device__ __forceinline__ void copy_bytes(D *dst, const S *src) {
+    if constexpr (BYTES == 32) {
+        reinterpret_cast<u32x4 *>(dst)[0] = reinterpret_cast<const u32x4 *>(src)[0];
+        reinterpret_cast<u32x4 *>(dst)[1] = reinterpret_cast<const u32x4 *>(src)[1];
+    } else {
+        typedef typename VecOfBytes<BYTES>::type V;
+        *reinterpret_cast<V *>(dst) = *reinterpret_cast<const V *>(src);
+    }
+}
+
+// One batch row x IW consecutive units of a BPTT cell (IW = 8, 4, 2 or 1; j0 a multiple of IW): operands
+// requested early, finished once the gradient reaching h_t of those units (rec, from the products) is
+// known.  These kernels are latency-bound, so IW is chosen to give every thread of the workgroup an item:
+// what counts is the length of one thread's instruction stream, not the width of its accesses.
+template <typename T, int IW> struct BackwardItem {
+    __attribute__((aligned(16))) T vi[IW], vf[IW], vg[IW], vo[IW], vct[IW], vcp[IW], vdh[IW];
+    __attribute__((aligned(16))) float dcs[IW];
     __device__ __forceinline__ void request(const FusedBwdCell &c, int b, int j0, int H) {
         const int64_t e0 = (int64_t)b * H + j0;
         const T *gr = reinterpret_cast<const T *>(c.gates) + (int64_t)b * 4 * H + j0;
-        *reinterpret_cast<u32x4 *>(vi) = *reinterpret_cast<const u32x4 *>(gr);
-        *reinterpret_cast<u32x4 *>(vf) = *reinterpret_cast<const u32x4 *>(gr + H);
-        *reinterpret_cast<u32x4 *>(vg) = *reinterpret_cast<const u32x4 *>(gr + 2 * H);
-        *reinterpret_cast<u32x4 *>(vo) = *reinterpret_cast<const u32x4 *>(gr + 3 * H);
-        *reinterpret_cast<u32x4 *>(vct) = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(c.c_t) + e0);
-        *reinterpret_cast<u32x4 *>(vcp) = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(c.c_prev) + e0);
-        if (c.dh_above) *reinterpret_cast<u32x4 *>(vdh) = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(c.dh_above) + e0);
-        if (!c.first) {
-#pragma unroll
-            for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(dcs + 4 * h) = *reinterpret_cast<const u32x4 *>(c.dc_state + e0 + 4 * h);
-        }
+        copy_bytes<2 * IW>(vi, gr);
+        copy_bytes<2 * IW>(vf, gr + H);
+        copy_bytes<2 * IW>(vg, gr + 2 * H);
+        copy_bytes<2 * IW>(vo, gr + 3 * H);
+        copy_bytes<2 * IW>(vct, reinterpret_cast<const T *>(c.c_t) + e0);
+        copy_bytes<2 * IW>(vcp, reinterpret_cast<const T *>(c.c_prev) + e0);
+        if (c.dh_above) copy_bytes<2 * IW>(vdh, reinterpret_cast<const T *>(c.dh_above) + e0);
+        if (!c.first) copy_bytes<4 * IW>(dcs, c.dc_state + e0);
     }
-    __device__ __forceinline__ void finish(const FusedBwdCell &c, const float (&rec)[8], int b, int j0, int H, int nkc, int blk_ncb) {
+    __device__ __forceinline__ void finish(const FusedBwdCell &c, const float (&rec)[IW], int b, int j0, int H, int nkc, int blk_ncb) {
         const int64_t e0 = (int64_t)b * H + j0;
-        __attribute__((aligned(16))) T o0[8], o1[8], o2[8], o3[8];
-        __attribute__((aligned(16))) float dcn[8];
+        __attribute__((aligned(16))) T o0[IW], o1[IW], o2[IW], o3[IW];
+        __attribute__((aligned(16))) float dcn[IW];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
+        for (int k = 0; k < IW; ++k) {
             const float i = Lp<T>::to_f(vi[k]), f = Lp<T>::to_f(vf[k]), g = Lp<T>::to_f(vg[k]), o = Lp<T>::to_f(vo[k]);
             const float tc = tanhf_dev(Lp<T>::to_f(vct[k]));
             const float dh = (c.dh_above ? Lp<T>::to_f(vdh[k]) : 0.0f) + rec[k];
@@ -669,21 +685,20 @@ template <typename T> struct BackwardItem {
             o2[k] = Lp<T>::from_f(dg * (1.0f - g * g));
             o3[k] = Lp<T>::from_f(d_o * o * (1.0f - o));
         }
-        // packed: [b / 64][gate][j / 64] chunk, fragment order inside; 8 aligned units are one slot
+        // packed: [b / 64][gate][j / 64] chunk, fragment order inside; 8 aligned units are one 16-byte slot
         const int64_t gs = (int64_t)nkc * A_CHUNK;
         T *pk = reinterpret_cast<T *>(c.dApk) + (((int64_t)(b >> 6) * 4) * nkc + (j0 >> 6)) * A_CHUNK + frag_offset(b & 63, j0 & 63, 2);
-        *reinterpret_cast<u32x4 *>(pk) = *reinterpret_cast<const u32x4 *>(o0);
-        *reinterpret_cast<u32x4 *>(pk + gs) = *reinterpret_cast<const u32x4 *>(o1);
-        *reinterpret_cast<u32x4 *>(pk + 2 * gs) = *reinterpret_cast<const u32x4 *>(o2);
-        *reinterpret_cast<u32x4 *>(pk + 3 * gs) = *reinterpret_cast<const u32x4 *>(o3);
-#pragma unroll
-        for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(c.dc_state + e0 + 4 * h) = *reinterpret_cast<const u32x4 *>(dcn + 4 * h);
+        copy_bytes<2 * IW>(pk, o0);
+        copy_bytes<2 * IW>(pk + gs, o1);
+        copy_bytes<2 * IW>(pk + 2 * gs, o2);
+        copy_bytes<2 * IW>(pk + 3 * gs, o3);
+        copy_bytes<4 * IW>(c.dc_state + e0, dcn);
         if (c.dA) {
             T *da = reinterpret_cast<T *>(c.dA) + (int64_t)b * 4 * H + j0;
-            *reinterpret_cast<u32x4 *>(da) = *reinterpret_cast<const u32x4 *>(o0);
-            *reinterpret_cast<u32x4 *>(da + H) = *reinterpret_cast<const u32x4 *>(o1);
-            *reinterpret_cast<u32x4 *>(da + 2 * H) = *reinterpret_cast<const u32x4 *>(o2);
-            *reinterpret_cast<u32x4 *>(da + 3 * H) = *reinterpret_cast<const u32x4 *>(o3);
+            copy_bytes<2 * IW>(da, o0);
+            copy_bytes<2 * IW>(da + H, o1);
+            copy_bytes<2 * IW>(da + 2 * H, o2);
+            copy_bytes<2 * IW>(da + 3 * H, o3);
         }
         if (c.dAblk) {
             T *rowp = reinterpret_cast<T *>(c.dAblk) + (int64_t)(b >> 6) * blk_ncb * 4096 + (b & 63) * 64;
@@ -691,7 +706,7 @@ template <typename T> struct BackwardItem {
             for (int g = 0; g < 4; ++g) {
                 const int col = g * H + j0;
                 const T *src = g == 0 ? o0 : (g == 1 ? o1 : (g == 2 ? o2 : o3));
-                *reinterpret_cast<u32x4 *>(rowp + (int64_t)(col >> 6) * 4096 + (col & 63)) = *reinterpret_cast<const u32x4 *>(src);
+                copy_bytes<2 * IW>(rowp + (int64_t)(col >> 6) * 4096 + (col & 63), src);
             }
         }
     }
@@ -700,7 +715,8 @@ template <typename T> struct BackwardItem {
 template <typename T, int R>
 __global__ __launch_bounds__(256) void lstm_fused_backward_kernel(FusedBwdArgs w) {
     typedef NarrowGeo<T, R> Geo;
-    constexpr int UG = R / 8, LD = R + 4, NR = Geo::NR;          // 8-unit groups per row, LDS row pitch, accumulator registers
+    constexpr int IW = R * R / 256;                              // units per thread: every thread gets an item
+    constexpr int UG = R / IW, LD = R + 4, NR = Geo::NR;         // items per row, LDS row pitch, accumulator registers
     const FusedBwdCell c = w.cell[blockIdx.z];                   // uniform: the cell's argument block
     fetch_now(c.dApk_next); fetch_now(c.UTpk); fetch_now(c.dApk_above); fetch_now(c.WTpk); fetch_now(c.dh_above); fetch_now(c.gates);
     fetch_now(c.c_t); fetch_now(c.c_prev); fetch_now(c.dc_state); fetch_now(c.dA); fetch_now(c.dApk); fetch_now(c.dAblk);
@@ -709,9 +725,9 @@ __global__ __launch_bounds__(256) void lstm_fused_backward_kernel(FusedBwdArgs w
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int H = w.H;
     const int row = tid / UG, ug = tid % UG;
-    const int b = b0 + row, j0 = u0 + ug * 8;
-    const bool valid = row < R && b < w.B && j0 < H;
-    BackwardItem<T> item;
+    const int b = b0 + row, j0 = u0 + ug * IW;
+    const bool valid = b < w.B && j0 < H;
+    BackwardItem<T, IW> item;
     if (valid) item.request(c, b, j0, H);
     // chunk list: [dA_{t+1} x U^T: 4 nkc chunks][dA_t(above) x W^T: 4 nkc chunks], either part may be absent
     const int per = 4 * w.nkc;
@@ -738,32 +754,30 @@ __global__ __launch_bounds__(256) void lstm_fused_backward_kernel(FusedBwdArgs w
     }
     __syncthreads();
     if (!valid) return;
-    __attribute__((aligned(16))) float rec[8];
-#pragma unroll
-    for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(rec + 4 * h) = *reinterpret_cast<const u32x4 *>(sums + row * LD + ug * 8 + 4 * h);
+    __attribute__((aligned(16))) float rec[IW];
+    copy_bytes<4 * IW>(rec, sums + row * LD + ug * IW);
     item.finish(c, rec, b, j0, H, w.nkc, w.blk_ncb);
 }
 
-// One batch row x 8 consecutive units of a forward cell.
-template <typename T> struct ForwardItem {
-    __attribute__((aligned(16))) T vax[4][8];
-    __attribute__((aligned(16))) float cprev[8];
+// One batch row x IW consecutive units of a forward cell.
+template <typename T, int IW> struct ForwardItem {
+    __attribute__((aligned(16))) T vax[4][IW];
+    __attribute__((aligned(16))) float cprev[IW];
     __device__ __forceinline__ void request(const FwdArgs &a, int b, int j0) {
         const int H = a.H;
         // input projection (bias included) of this step, or just the bias when the cell projects its own input
         const T *ax = a.Ax ? reinterpret_cast<const T *>(a.Ax) + (int64_t)b * 4 * H + j0 : reinterpret_cast<const T *>(a.bias) + j0;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) *reinterpret_cast<u32x4 *>(vax[g]) = *reinterpret_cast<const u32x4 *>(ax + g * H);
-#pragma unroll
-        for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(cprev + 4 * h) = *reinterpret_cast<const u32x4 *>(a.c_state + (int64_t)b * H + j0 + 4 * h);
+        for (int g = 0; g < 4; ++g) copy_bytes<2 * IW>(vax[g], ax + g * H);
+        copy_bytes<4 * IW>(cprev, a.c_state + (int64_t)b * H + j0);
     }
-    __device__ __forceinline__ void finish(const FwdArgs &a, const float (&pz)[4][8], int b, int j0) {
+    __device__ __forceinline__ void finish(const FwdArgs &a, const float (&pz)[4][IW], int b, int j0) {
         const int H = a.H;
         const int64_t e0 = (int64_t)b * H + j0;
-        __attribute__((aligned(16))) T oi[8], of[8], og[8], oo[8], oc[8], oh[8];
-        __attribute__((aligned(16))) float cn[8];
+        __attribute__((aligned(16))) T oi[IW], of[IW], og[IW], oo[IW], oc[IW], oh[IW];
+        __attribute__((aligned(16))) float cn[IW];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
+        for (int k = 0; k < IW; ++k) {
             const float gi = sigmoidf_dev(pz[0][k] + Lp<T>::to_f(vax[0][k]));
             const float gf = sigmoidf_dev(pz[1][k] + Lp<T>::to_f(vax[1][k]));
             const float gg = tanhf_dev(pz[2][k] + Lp<T>::to_f(vax[2][k]));
@@ -774,27 +788,25 @@ template <typename T> struct ForwardItem {
             oc[k] = Lp<T>::from_f(cc);
             oh[k] = Lp<T>::from_f(go * tanhf_dev(cc));
         }
-#pragma unroll
-        for (int h = 0; h < 2; ++h) *reinterpret_cast<u32x4 *>(a.c_state + e0 + 4 * h) = *reinterpret_cast<const u32x4 *>(cn + 4 * h);
+        copy_bytes<4 * IW>(a.c_state + e0, cn);
         T *gr = reinterpret_cast<T *>(a.gates) + (int64_t)b * 4 * H + j0;
-        *reinterpret_cast<u32x4 *>(gr) = *reinterpret_cast<const u32x4 *>(oi);
-        *reinterpret_cast<u32x4 *>(gr + H) = *reinterpret_cast<const u32x4 *>(of);
-        *reinterpret_cast<u32x4 *>(gr + 2 * H) = *reinterpret_cast<const u32x4 *>(og);
-        *reinterpret_cast<u32x4 *>(gr + 3 * H) = *reinterpret_cast<const u32x4 *>(oo);
-        *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.c_out) + e0) = *reinterpret_cast<const u32x4 *>(oc);
-        *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.h_out) + e0) = *reinterpret_cast<const u32x4 *>(oh);
-        *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.hpk_next) + ((int64_t)(b >> 6) * a.nkc + (j0 >> 6)) * A_CHUNK +
-                                   frag_offset(b & 63, j0 & 63, 2)) = *reinterpret_cast<const u32x4 *>(oh);
+        copy_bytes<2 * IW>(gr, oi);
+        copy_bytes<2 * IW>(gr + H, of);
+        copy_bytes<2 * IW>(gr + 2 * H, og);
+        copy_bytes<2 * IW>(gr + 3 * H, oo);
+        copy_bytes<2 * IW>(reinterpret_cast<T *>(a.c_out) + e0, oc);
+        copy_bytes<2 * IW>(reinterpret_cast<T *>(a.h_out) + e0, oh);
+        copy_bytes<2 * IW>(reinterpret_cast<T *>(a.hpk_next) + ((int64_t)(b >> 6) * a.nkc + (j0 >> 6)) * A_CHUNK + frag_offset(b & 63, j0 & 63, 2), oh);
         if (a.h_blk)
-            *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(a.h_blk) + ((int64_t)(b >> 6) * a.blk_ncb + (j0 >> 6)) * 4096 + (b & 63) * 64 +
-                                       (j0 & 63)) = *reinterpret_cast<const u32x4 *>(oh);
+            copy_bytes<2 * IW>(reinterpret_cast<T *>(a.h_blk) + ((int64_t)(b >> 6) * a.blk_ncb + (j0 >> 6)) * 4096 + (b & 63) * 64 + (j0 & 63), oh);
     }
 };
 
 template <typename T, int R>
 __global__ __launch_bounds__(256) void lstm_narrow_forward_kernel(WaveFwdArgs w) {
     typedef NarrowGeo<T, R> Geo;
-    constexpr int UG = R / 8, LD = R + 4, NR = Geo::NR;
+    constexpr int IW = R * R / 256;                              // units per thread: every thread gets an item
+    constexpr int UG = R / IW, LD = R + 4, NR = Geo::NR;
     const FwdArgs a = w.cell[blockIdx.z];
     fetch_now(a.hpk_prev); fetch_now(a.Upk); fetch_now(a.Ax); fetch_now(a.xpk); fetch_now(a.Wpk); fetch_now(a.bias);
     fetch_now(a.c_state); fetch_now(a.gates); fetch_now(a.c_out); fetch_now(a.h_out); fetch_now(a.hpk_next); fetch_now(a.h_blk);
@@ -802,9 +814,9 @@ __global__ __launch_bounds__(256) void lstm_narrow_forward_kernel(WaveFwdArgs w)
     const int b0 = (int)blockIdx.x * R, u0 = (int)blockIdx.y * R;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int row = tid / UG, ug = tid % UG;
-    const int b = b0 + row, j0 = u0 + ug * 8;
-    const bool valid = row < R && b < a.B && j0 < a.H;
-    ForwardItem<T> item;
+    const int b = b0 + row, j0 = u0 + ug * IW;
+    const bool valid = b < a.B && j0 < a.H;
+    ForwardItem<T, IW> item;
     if (valid) item.request(a, b, j0);
     const int nch = a.Ax ? a.nkc : 2 * a.nkc;
     // rows of U (and W): hidden block u0 / 32, inside it gate `wave`'s 32 rows, of those the tile's R
@@ -821,12 +833,9 @@ __global__ __launch_bounds__(256) void lstm_narrow_forward_kernel(WaveFwdArgs w)
     for (int r = 0; r < NR; ++r) pre[(wave * R + Geo::row(r, lane)) * LD + Geo::col(lane)] = acc[r];
     __syncthreads();
     if (!valid) return;
-    __attribute__((aligned(16))) float pz[4][8];
+    __attribute__((aligned(16))) float pz[4][IW];
 #pragma unroll
-    for (int g = 0; g < 4; ++g)
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-            *reinterpret_cast<u32x4 *>(pz[g] + 4 * h) = *reinterpret_cast<const u32x4 *>(pre + (g * R + row) * LD + ug * 8 + 4 * h);
+    for (int g = 0; g < 4; ++g) copy_bytes<4 * IW>(pz[g], pre + (g * R + row) * LD + ug * IW);
     item.finish(a, pz, b, j0);
 }
 
