@@ -161,7 +161,7 @@ __global__ __launch_bounds__(256) void colsum_partial_vec_kernel(const T *in, in
     const int r_beg = blockIdx.y * CS_ROWS, r_end = min(R, r_beg + CS_ROWS);
     float s[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
     if (c < C)
-#pragma unroll 4
+#pragma unroll 8
         for (int r = r_beg + ry; r < r_end; r += 4) {
             const int64_t pr = rs.row(r, blockIdx.z);
             const u32x4 raw = *reinterpret_cast<const u32x4 *>(in + pr * ld + c);
@@ -399,6 +399,7 @@ __global__ __launch_bounds__(256) void head_backward_bias_kernel(const float *dz
                                                                  RowSeg rs, int64_t out_stride) {
     __shared__ double red[256];
     double s = 0.0;
+#pragma unroll 8
     for (int i = threadIdx.x; i < rows; i += 256) s += (double)dzu[rs.row(i, blockIdx.x)];
     red[threadIdx.x] = s;
     __syncthreads();
