@@ -50,3 +50,33 @@ def test_random_configuration(seed):
     got = pu.run_gpu_step(w)
     want = pu.run_oracle_step(w)
     pu.assert_step_close(w, got, want)
+
+
+def _draw_narrow(seed):
+    """Shapes the one-launch-per-cell kernels take (16-bit storage, H a multiple of 8): tile edges that do
+    and do not divide the batch and the width, more layers than cells per launch, single steps."""
+    rng = np.random.default_rng(9500 + seed)
+    dtype = ["fp16", "bf16"][int(rng.integers(0, 2))]
+    L = int(rng.integers(1, 4))
+    H = int(rng.choice([8, 16, 40, 56, 104, 136, 200, 264]))
+    B = int(rng.choice([1, 15, 16, 33, 64, 100, 192, 256]))
+    T = int(rng.integers(1, 6))
+    I = int(rng.choice([3, 8, 24, 64]))
+    head = int(rng.choice([wl.HEAD_STEP_BCE, wl.HEAD_LAST_BCE, wl.HEAD_STEP_MSE]))
+    kw = dict(target_kind="normal") if head == wl.HEAD_STEP_MSE else dict(target_p=0.4)
+    if dtype == "bf16":
+        L = min(L, 2)
+        B = max(B, 64)
+        T = max(T, 3)
+        H = max(H, 40)
+    scale = 1.0 if dtype != "fp16" else float(rng.choice([64.0, 1024.0]))
+    return wl.Workload(f"nar{seed}", L, I, H, T, B, dtype, head, loss_scale=scale, data_seed=1700 + seed, weight_seed=1800 + seed, **kw)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_narrow_configuration(seed):
+    w = _draw_narrow(seed)
+    print(f"[case] nar{seed}: L={w.num_layers} I={w.input_dim} H={w.hidden} T={w.seq_len} B={w.batch} {w.dtype} head={w.head}", flush=True)
+    got = pu.run_gpu_step(w)
+    want = pu.run_oracle_step(w)
+    pu.assert_step_close(w, got, want)
