@@ -278,10 +278,14 @@ inline const char *at(const void *base, size_t off) { return reinterpret_cast<co
 // the fp32 mode has no packed operands and keeps its plain fills).
 struct SetupBatch {
     std::vector<SetupJob> jobs;
-    void pack_u_forward(const void *U, void *dst) { jobs.push_back(SetupJob{SETUP_PACK_U_FORWARD, U, dst, 0}); }
-    void pack_u_backward(const void *U, void *dst) { jobs.push_back(SetupJob{SETUP_PACK_U_BACKWARD, U, dst, 0}); }
-    void pack_rows(const void *h, void *dst) { jobs.push_back(SetupJob{SETUP_PACK_ROWS, h, dst, 0}); }
-    void zero(void *dst, int64_t n_words) { if (n_words > 0) jobs.push_back(SetupJob{SETUP_ZERO, nullptr, dst, n_words}); }
+    void pack_u_forward(const void *U, void *dst) { jobs.push_back(SetupJob{SETUP_PACK_U_FORWARD, U, dst, 0, 0, 0}); }
+    void pack_u_backward(const void *U, void *dst) { jobs.push_back(SetupJob{SETUP_PACK_U_BACKWARD, U, dst, 0, 0, 0}); }
+    void pack_rows(const void *h, void *dst) { jobs.push_back(SetupJob{SETUP_PACK_ROWS, h, dst, 0, 0, 0}); }
+    void zero(void *dst, int64_t n_words) { if (n_words > 0) jobs.push_back(SetupJob{SETUP_ZERO, nullptr, dst, n_words, 0, 0}); }
+    // padding columns of a 64x64-blocked [rows, cols] tensor (the kernels that fill it write valid columns only)
+    void zero_pad(void *dst, int64_t rows, int cols) {
+        if (cols % 64 != 0 && rows > 0) jobs.push_back(SetupJob{SETUP_ZERO_PAD, nullptr, dst, (rows + 63) / 64, (cols + 63) / 64, cols});
+    }
     int flush(int dtype, int B, int H, hipStream_t s) {
         if (jobs.empty()) return LSTM_OK;
         const int rc = setup_jobs(dtype, jobs.data(), (int)jobs.size(), B, H, s);
@@ -462,8 +466,8 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
         const size_t slot = (size_t)(p.B / 64) * p.h_ncb * 4096 * es;      // bytes of one time slot of the blocked sequence
         if (p.blk) {
             // zero padding columns (H not a multiple of 64) once, then slot 0 = initial hidden state
-            if (p.H % 64 != 0) setup.zero(hblk, (int64_t)(blocked_elems((int)(TB + p.B), p.H) * es / 4));
-            else if (!h0) setup.zero(hblk, (int64_t)(slot / 4));
+            setup.zero_pad(hblk, (int64_t)TB + p.B, p.H);
+            if (!h0) setup.zero(hblk, (int64_t)(slot / 4));
             if (h0) {
                 LSTM_TRY(setup.flush(p.dtype, p.B, p.H, s));     // the padding is cleared before slot 0 is written
                 LSTM_TRY(pack_blocked(p.dtype, at(h0, (size_t)l * BH * es), p.H, p.B, p.H, hblk, s));
@@ -657,7 +661,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             if (l > 0) setup.pack_u_backward(par + p.off_W[l] * es, at(scratch, p.s_wb_wtpk[l]));
             setup.zero(at(scratch, p.s_wb_dapk[l]), (int64_t)((rd.dapk_elems * es + 3) / 4));
             if (p.fb) setup.zero(at(scratch, p.s_wb_dapk1[l]), (int64_t)((rd.dapk_elems * es + 3) / 4));
-            if (p.blk && p.G % 64 != 0) setup.zero(at(scratch, p.s_wb_dablk[l]), (int64_t)(blocked_elems(TB, p.G) * es / 4));
+            if (p.blk) setup.zero_pad(at(scratch, p.s_wb_dablk[l]), TB, p.G);
         }
         LSTM_TRY(setup.flush(p.dtype, p.B, p.H, s));
         if (p.fb) {
@@ -744,7 +748,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             SetupBatch setup;
             setup.pack_u_backward(par + p.off_U[l] * es, utpk);
             for (int k = 0; k < 2; ++k) setup.zero(dapk[k], (int64_t)((rd.dapk_elems * es + 3) / 4));
-            if (p.blk && p.G % 64 != 0) setup.zero(at(scratch, p.s_dablk), (int64_t)(blocked_elems(TB, p.G) * es / 4));
+            if (p.blk) setup.zero_pad(at(scratch, p.s_dablk), TB, p.G);
             LSTM_TRY(setup.flush(p.dtype, p.B, p.H, s));
         }
         char *dablk = p.blk ? at(scratch, p.wb ? p.s_wb_dablk[l] : p.s_dablk) : nullptr;

@@ -79,12 +79,14 @@ int pack_u_backward(int dtype, const void *U, void *UTpk, int H, hipStream_t s);
 // hpk = packed copy of row-major h [B,H] (h null = zeros); also clears the padding
 int pack_rows(int dtype, const void *h, void *hpk, int B, int H, hipStream_t s);
 // several packing jobs and zero fills in one launch (16-bit types)
-enum { SETUP_PACK_U_FORWARD = 0, SETUP_PACK_U_BACKWARD = 1, SETUP_PACK_ROWS = 2, SETUP_ZERO = 3 };
+enum { SETUP_PACK_U_FORWARD = 0, SETUP_PACK_U_BACKWARD = 1, SETUP_PACK_ROWS = 2, SETUP_ZERO = 3, SETUP_ZERO_PAD = 4 };
 struct SetupJob {
     int kind;
-    const void *src;      // U / W [4H,H], or h [B,H] (null: zeros) for SETUP_PACK_ROWS; unused for SETUP_ZERO
+    const void *src;      // U / W [4H,H], or h [B,H] (null: zeros) for SETUP_PACK_ROWS; unused for the fills
     void *dst;
-    int64_t n_words;      // SETUP_ZERO: 32-bit words to clear
+    int64_t n_words;      // SETUP_ZERO: 32-bit words to clear; SETUP_ZERO_PAD: row blocks of the blocked tensor
+    int ncb, cols;        // SETUP_ZERO_PAD: column blocks per row block, valid columns C (C % 64 != 0): the columns
+                          // C % 64 .. 63 of the last column block of every row block are cleared (16-bit elements)
 };
 int setup_jobs(int dtype, const SetupJob *jobs, int n_jobs, int B, int H, hipStream_t s);
 // forward: gates, c, h of one step from packed h_prev, packed U and the step's input projection Ax (lp, bias included);

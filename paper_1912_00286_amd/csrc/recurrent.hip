@@ -894,7 +894,7 @@ struct SetupJobArg {
     const void *src;
     void *dst;
     int64_t n_words;
-    int kind;
+    int kind, ncb, cols;
 };
 struct SetupArgs {
     SetupJobArg job[SETUP_MAX_JOBS];
@@ -916,6 +916,17 @@ __global__ __launch_bounds__(256) void setup_jobs_kernel(SetupArgs a) {
         case SETUP_PACK_ROWS:
             if (x < a.nkc * a.n_mt) pack_rows_block<T>((const T *)j.src, (T *)j.dst, a.B, a.H, a.nkc, x % a.nkc, x / a.nkc);
             break;
+        case SETUP_ZERO_PAD: {                           // padding columns of a 64x64-blocked 16-bit tensor
+            const int c0 = j.cols & 63, npad = 64 - c0;
+            const int64_t n = j.n_words * 64 * npad;     // row blocks x 64 rows x padding columns
+            uint16_t *d = (uint16_t *)j.dst;
+            for (int64_t i = (int64_t)x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+                const int64_t r = i / npad;              // row index over all row blocks
+                const int c = c0 + (int)(i - r * npad);
+                d[((r >> 6) * j.ncb + (j.ncb - 1)) * 4096 + (r & 63) * 64 + c] = 0;
+            }
+            break;
+        }
         default: {                                       // SETUP_ZERO: n_words 32-bit words
             uint32_t *d = (uint32_t *)j.dst;
             for (int64_t i = (int64_t)x * 256 + threadIdx.x; i < j.n_words; i += (int64_t)gridDim.x * 256) d[i] = 0u;
@@ -983,16 +994,19 @@ int setup_jobs(int dtype, const SetupJob *jobs, int n_jobs, int B, int H, hipStr
         int64_t grid_x = 1;
         for (int i = 0; i < SETUP_MAX_JOBS; ++i) {
             const SetupJob &j = jobs[first + (i < n ? i : 0)];
-            if (!j.dst || (j.kind != SETUP_ZERO && j.kind != SETUP_PACK_ROWS && !j.src) || j.kind < 0 || j.kind > SETUP_ZERO) {
+            if (!j.dst || (j.kind < SETUP_PACK_ROWS && !j.src) || j.kind < 0 || j.kind > SETUP_ZERO_PAD ||
+                (j.kind == SETUP_ZERO_PAD && (j.ncb < 1 || (j.cols & 63) == 0 || (j.cols + 63) / 64 != j.ncb))) {
                 set_error("setup_jobs: bad job %d (kind %d)", first + i, j.kind);
                 return LSTM_ERR_INVALID;
             }
             a.job[i].src = j.src; a.job[i].dst = j.dst; a.job[i].n_words = j.n_words; a.job[i].kind = j.kind;
+            a.job[i].ncb = j.ncb; a.job[i].cols = j.cols;
             int64_t need = 1;
             switch (j.kind) {
                 case SETUP_PACK_U_FORWARD: need = (int64_t)d.nkc * d.n_hb; break;
                 case SETUP_PACK_U_BACKWARD: need = (int64_t)d.nkc * 4 * d.n_nt; break;
                 case SETUP_PACK_ROWS: need = (int64_t)d.nkc * d.n_mt; break;
+                case SETUP_ZERO_PAD: need = (j.n_words * 64 * (64 - (j.cols & 63)) + 2047) / 2048; if (need > 4096) need = 4096; break;
                 default: need = (j.n_words + 2047) / 2048; if (need > 4096) need = 4096; break;   // 8 words per thread at least
             }
             if (need > grid_x) grid_x = need;
