@@ -553,7 +553,7 @@ struct FusedBwdCell {
 };
 struct FusedBwdArgs {
     FusedBwdCell cell[FUSED_MAX_CELLS];
-    int blk_ncb, B, H, nkc, wgs_per_cell;
+    int blk_ncb, B, H, nkc;
 };
 
 // The cell's argument block is copied into registers in one go: cell = blockIdx.z, tile = (blockIdx.x,
@@ -1146,7 +1146,7 @@ int backward_fused_wave(int dtype, const FusedBackwardCell *c, int n_cells, int 
     }
     const int R = narrow_tile(B, H);
     const dim3 grid((B + R - 1) / R, (H + R - 1) / R, n_cells);
-    w.blk_ncb = blk_ncb; w.B = B; w.H = H; w.nkc = d.nkc; w.wgs_per_cell = (int)(grid.x * grid.y);
+    w.blk_ncb = blk_ncb; w.B = B; w.H = H; w.nkc = d.nkc;
     const double n = (double)B * H;
     // products: 2 B H 4H flops, operands once; gate arithmetic: as in the stand-alone kernel without the partials
     KernelTimer timer(KC_GEMM_STEP, s, chunks * 2.0 * n * 4.0 * H, chunks * 2.0 * (4.0 * H * H + 4.0 * n) + n_cells * n * (8.0 + 15.0 * 2.0));
