@@ -307,23 +307,28 @@ __global__ __launch_bounds__(256) void lstm_wave_forward_kernel(WaveFwdArgs w) {
 struct BwdArgs {
     const void *dApk;      // packed dA_{t+1}: [n_mt][4][nkc][64][64]
     const void *UTpk;      // packed U^T: [n_nt][4][nkc][128][64]
-    float *partials;       // fp32 [4][B,H] out: one K-slice (gate) each
+    float *partials;       // fp32 [slices][B,H] out: one K-slice (gate) each, or the whole sum
     int B, H, n_mt, nkc;
+    int slices;            // 4: the contraction over the 4H gate rows is split by gate over workgroups; 1: not split
 };
 
-// partial[q][b, j] = sum over the rows k of gate q of dA_next[b, k] * U[k, j]
+// partial[q][b, j] = sum over the rows k of gate q of dA_next[b, k] * U[k, j]   (slices = 4)
+// partial[0][b, j] = sum over all 4H rows                                        (slices = 1: enough tiles without the split)
 template <typename T, bool WIDE>
 __device__ __forceinline__ void backward_gemm_cell(const BwdArgs &a, int lin, int total, int rot) {
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // gate-slice major: the workgroups of one XCD share one K slice, so that XCD's L2 pulls
     // only that quarter of dA over the fabric (all of it would be fetched by all eight otherwise)
-    const int per_q = total >> 2;
+    const int per_q = total / a.slices;
     const int q = lin / per_q, tile = lin - q * per_q;
     const int mt = tile % a.n_mt, nt = tile / a.n_mt;
     const int m0 = mt * TM, n0 = nt * TN;
     const int H = a.H;
-    const int cpw = (a.nkc + 3) / 4;
-    const int c0 = WIDE ? 0 : min(a.nkc, wave * cpw), c1 = WIDE ? a.nkc : min(a.nkc, c0 + cpw);
+    // the chunks of the four gates follow each other in both packed operands, so the unsplit
+    // contraction is the same loop over four times as many chunks
+    const int nch = a.slices == 1 ? 4 * a.nkc : a.nkc;
+    const int cpw = (nch + 3) / 4;
+    const int c0 = WIDE ? 0 : min(nch, wave * cpw), c1 = WIDE ? nch : min(nch, c0 + cpw);
     v16f acc[2][NBLK];
     zero_acc(acc);
     packed_mainloop<T>(reinterpret_cast<const uint16_t *>(a.dApk) + ((int64_t)mt * 4 + q) * a.nkc * A_CHUNK,
@@ -380,7 +385,7 @@ __global__ __launch_bounds__(256) void lstm_wave_backward_gemm_kernel(WaveBwdGem
     const int c = blockIdx.x / w.wgs_per_cell;
     BwdArgs a;
     a.dApk = w.dApk[c]; a.UTpk = w.Bpk[c]; a.partials = w.partials[c];
-    a.B = w.B; a.H = w.H; a.n_mt = w.n_mt; a.nkc = w.nkc;
+    a.B = w.B; a.H = w.H; a.n_mt = w.n_mt; a.nkc = w.nkc; a.slices = 4;
     backward_gemm_cell<T, false>(a, (int)blockIdx.x - c * w.wgs_per_cell, w.wgs_per_cell, (int)blockIdx.x);
 }
 
@@ -396,7 +401,7 @@ template <typename T, int W>
 __device__ __forceinline__ void gates_backward_cell(const T *dh_above, const float *above4, const float *partials, const T *gates,
                                                     const T *c_t, const T *c_prev, float *dc_state, T *dA, T *dApk, T *dAblk,
                                                     int blk_ncb, int B, int H, int nkc, int first, int64_t thread0,
-                                                    int64_t nthreads) {
+                                                    int64_t nthreads, int n_part = 4) {
     constexpr bool VEC = W > 1;
     typedef unsigned int lpvec __attribute__((ext_vector_type(W > 1 ? W / 2 : 1)));   // W 16-bit values
     const int64_t n = (int64_t)B * H;
@@ -419,9 +424,11 @@ __device__ __forceinline__ void gates_backward_cell(const T *dh_above, const flo
 #pragma unroll
                 for (int h = 0; h < W / 4; ++h) {
                     *reinterpret_cast<u32x4 *>(p0 + 4 * h) = *reinterpret_cast<const u32x4 *>(partials + e0 + 4 * h);
-                    *reinterpret_cast<u32x4 *>(p1 + 4 * h) = *reinterpret_cast<const u32x4 *>(partials + n + e0 + 4 * h);
-                    *reinterpret_cast<u32x4 *>(p2 + 4 * h) = *reinterpret_cast<const u32x4 *>(partials + 2 * n + e0 + 4 * h);
-                    *reinterpret_cast<u32x4 *>(p3 + 4 * h) = *reinterpret_cast<const u32x4 *>(partials + 3 * n + e0 + 4 * h);
+                    if (n_part == 4) {
+                        *reinterpret_cast<u32x4 *>(p1 + 4 * h) = *reinterpret_cast<const u32x4 *>(partials + n + e0 + 4 * h);
+                        *reinterpret_cast<u32x4 *>(p2 + 4 * h) = *reinterpret_cast<const u32x4 *>(partials + 2 * n + e0 + 4 * h);
+                        *reinterpret_cast<u32x4 *>(p3 + 4 * h) = *reinterpret_cast<const u32x4 *>(partials + 3 * n + e0 + 4 * h);
+                    }
                     *reinterpret_cast<u32x4 *>(dcs + 4 * h) = *reinterpret_cast<const u32x4 *>(dc_state + e0 + 4 * h);
                 }
             }
@@ -430,7 +437,8 @@ __device__ __forceinline__ void gates_backward_cell(const T *dh_above, const flo
             vct[0] = c_t[e0]; vcp[0] = c_prev[e0];
             if (dh_above) vdh[0] = dh_above[e0];
             if (!first) {
-                p0[0] = partials[e0]; p1[0] = partials[n + e0]; p2[0] = partials[2 * n + e0]; p3[0] = partials[3 * n + e0];
+                p0[0] = partials[e0];
+                if (n_part == 4) { p1[0] = partials[n + e0]; p2[0] = partials[2 * n + e0]; p3[0] = partials[3 * n + e0]; }
                 dcs[0] = dc_state[e0];
             }
         }
@@ -444,7 +452,7 @@ __device__ __forceinline__ void gates_backward_cell(const T *dh_above, const flo
             if (above4) dh += (above4[e0 + k] + above4[n + e0 + k]) + (above4[2 * n + e0 + k] + above4[3 * n + e0 + k]);
             float dcr = 0.0f;
             if (!first) {
-                dh += (p0[k] + p1[k]) + (p2[k] + p3[k]);
+                dh += n_part == 4 ? (p0[k] + p1[k]) + (p2[k] + p3[k]) : p0[k];
                 dcr = dcs[k];
             }
             const float d_o = dh * tc;
@@ -496,11 +504,12 @@ template <typename T, int W>
 __global__ __launch_bounds__(256) void gates_backward_packed_kernel(const T *dh_above, const float *partials, const T *gates,
                                                                     const T *c_t, const T *c_prev, float *dc_state, T *dA,
                                                                     T *dApk, T *dAblk, int blk_ncb, int B, int H, int nkc,
-                                                                    int first) {
+                                                                    int first, int n_part) {
+    fetch_now(n_part);
     fetch_now(dh_above); fetch_now(partials); fetch_now(gates); fetch_now(c_t); fetch_now(c_prev); fetch_now(dc_state); fetch_now(dA);
     fetch_now(dApk); fetch_now(dAblk); fetch_now(blk_ncb); fetch_now(B); fetch_now(H); fetch_now(nkc); fetch_now(first);
     gates_backward_cell<T, W>(dh_above, nullptr, partials, gates, c_t, c_prev, dc_state, dA, dApk, dAblk, blk_ncb, B, H, nkc, first,
-                                blockIdx.x * (int64_t)blockDim.x + threadIdx.x, (int64_t)gridDim.x * blockDim.x);
+                                blockIdx.x * (int64_t)blockDim.x + threadIdx.x, (int64_t)gridDim.x * blockDim.x, n_part);
 }
 
 // The BPTT gate arithmetic of several independent (layer, time) cells in one launch.
@@ -962,6 +971,10 @@ static bool narrow_cells(const RecurrentDims &d, int H) { return H % 8 == 0 && H
 // Tile edge of the narrow-layer kernels: 16 while that keeps a cell within a few hundred workgroups
 // (the smaller the tile, the fewer bytes each compute unit pulls in), else 32.
 static int narrow_tile(int B, int H) { return ((B + 15) / 16) * ((H + 15) / 16) <= 512 ? 16 : 32; }
+// Slices of the backward contraction over the 4H gate rows: split by gate over four workgroups (four
+// fp32 partial results that the gate kernel adds) unless the tiles alone fill the chip: then one
+// workgroup contracts over all of it and 12 bytes per unit less are written and read back.
+static int backward_slices(const RecurrentDims &d) { return d.n_mt * d.n_nt >= 256 ? 1 : 4; }
 static bool recurrent_wide(const RecurrentDims &d) { return d.nkc <= 8 && d.n_mt >= 16; }   // H <= 512, B >= 961
 
 #define LP_ONLY(dtype, T, ...)                                                       \
@@ -1063,11 +1076,12 @@ int step_backward_gemm(int dtype, const void *dApk, const void *UTpk, float *par
     const RecurrentDims d = recurrent_dims(B, H);
     BwdArgs a;
     a.dApk = dApk; a.UTpk = UTpk; a.partials = partials;
-    a.B = B; a.H = H; a.n_mt = d.n_mt; a.nkc = d.nkc;
-    const bool wide = recurrent_wide(d);
-    const int grid = d.n_mt * d.n_nt * 4;
-    // operands once: U^T and dA read in storage, four fp32 partial sums [B,H] written
-    KernelTimer timer(KC_GEMM_STEP, s, 2.0 * B * 4.0 * H * H, 2.0 * (4.0 * H * H + 4.0 * (double)B * H) + 16.0 * (double)B * H);
+    a.B = B; a.H = H; a.n_mt = d.n_mt; a.nkc = d.nkc; a.slices = backward_slices(d);
+    const bool wide = recurrent_wide(d) && a.slices == 4;      // unsplit: the four wavefronts share the longer K range
+    const int grid = d.n_mt * d.n_nt * a.slices;
+    // operands once: U^T and dA read in storage, the fp32 partial sums [slices][B,H] written
+    KernelTimer timer(KC_GEMM_STEP, s, 2.0 * B * 4.0 * H * H,
+                      2.0 * (4.0 * H * H + 4.0 * (double)B * H) + 4.0 * a.slices * (double)B * H);
     if (wide) {
         LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_step_backward_gemm_kernel<T, true>), dim3(grid), dim3(64), 0, s, a));
     } else {
@@ -1094,11 +1108,12 @@ int gates_backward_packed(int dtype, const void *dh_above, const float *partials
     if (blocks < 1) blocks = 1;
     // per unit: four fp32 partials and the cell gradient read, the cell gradient written, seven
     // 16-bit values read, four gate gradients written once per copy (packed, row-major, blocked)
-    KernelTimer timer(KC_POINTWISE, s, 0.0, (double)n * (16.0 + 8.0 + 2.0 * (7.0 + 4.0 * (1 + (dA ? 1 : 0) + (dAblk ? 1 : 0)))));
+    const int n_part = backward_slices(d);                      // as step_backward_gemm wrote them
+    KernelTimer timer(KC_POINTWISE, s, 0.0, (double)n * (4.0 * n_part + 8.0 + 2.0 * (7.0 + 4.0 * (1 + (dA ? 1 : 0) + (dAblk ? 1 : 0)))));
 #define LSTM_GATES_LAUNCH(W)                                                                                                   \
     LP_ONLY(dtype, T, hipLaunchKernelGGL((gates_backward_packed_kernel<T, W>), dim3(blocks), dim3(256), 0, s,                  \
                                          (const T *)dh_above, partials, (const T *)gates, (const T *)c_t, (const T *)c_prev,   \
-                                         dc_state, (T *)dA, (T *)dApk, (T *)dAblk, blk_ncb, B, H, d.nkc, first))
+                                         dc_state, (T *)dA, (T *)dApk, (T *)dAblk, blk_ncb, B, H, d.nkc, first, n_part))
     if (per_thread == 8) { LSTM_GATES_LAUNCH(8); }
     else if (per_thread == 4) { LSTM_GATES_LAUNCH(4); }
     else { LSTM_GATES_LAUNCH(1); }
