@@ -60,11 +60,12 @@ struct Plan {
     // The row-major copy of dA is only kept where something reads it: with every consumer (dX, dW,
     // dU, the bias gradient) on the blocked copy it is left out.
     bool dA_rowmajor_needed(int l) const {
-        if (!blk || W > 1) return true;
+        if (!blk) return true;
         const int TB = T * B, I = in_dim[l];
         const bool dx = (l > 0 && !wb) || (l == 0 && V > 0);
         if (dx && !gemm_blocked_supported(dtype, TB, I)) return true;
-        return !gemm_blocked_supported(dtype, G, H);          // dW takes the blocked kernel at any input width
+        // dW takes the blocked kernel at any input width; dU too when there are several workers
+        return W == 1 && !gemm_blocked_supported(dtype, G, H);
     }
     std::vector<int> split_w, split_u;
 };
@@ -865,7 +866,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             LSTM_TRY(gemm_nt(p.dtype, u, s));
         }
         if (dA_rm) LSTM_TRY(colsum(p.dtype, dA, p.G, TB / p.W, p.G, nullptr, nullptr, colpart, grd + p.off_b[l] * es, s, p.W, p.Bw, p.P));
-        else LSTM_TRY(colsum_blocked(p.dtype, dablk, p.g_ncb, TB, p.G, colpart, grd + p.off_b[l] * es, s));
+        else LSTM_TRY(colsum_blocked(p.dtype, dablk, p.g_ncb, TB / p.W, p.G, colpart, grd + p.off_b[l] * es, s, p.W, p.Bw, p.P));
         cur ^= 1;
         dh_above = d_below;
     }

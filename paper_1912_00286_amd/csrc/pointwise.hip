@@ -186,13 +186,18 @@ __global__ __launch_bounds__(256) void colsum_partial_vec_kernel(const T *in, in
 // blocks (thread = 8 columns of one of 32 row slots) and writes one partial row.
 constexpr int CSB_BLOCKS = 8;
 template <typename T>
-__global__ __launch_bounds__(256) void colsum_blocked_partial_kernel(const T *blk, int ncb, int nrb, int C, float *partial) {
+__global__ __launch_bounds__(256) void colsum_blocked_partial_kernel(const T *blk, int ncb, int nrb, int C, float *partial, int seg,
+                                                                     int stride) {
+    // Several workers (blockIdx.z): worker z owns `seg` consecutive row blocks out of every `stride`
+    // (its rows of one time step); its i-th row block is (i / seg) * stride + z * seg + i % seg.
+    // One worker: seg = stride, which makes that i.
     __shared__ float red[32][65];
     const int cb = blockIdx.x, c8 = (threadIdx.x & 7) * 8, rs = threadIdx.x >> 3;
     const int rb0 = blockIdx.y * CSB_BLOCKS, rb1 = min(nrb, rb0 + CSB_BLOCKS);
     float s[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
-    for (int rb = rb0; rb < rb1; ++rb) {
-        const T *b = blk + ((int64_t)rb * ncb + cb) * 4096;
+    for (int i = rb0; i < rb1; ++i) {
+        const int64_t rb = (int64_t)(i / seg) * stride + (int64_t)blockIdx.z * seg + i % seg;
+        const T *b = blk + (rb * ncb + cb) * 4096;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const u32x4 raw = *reinterpret_cast<const u32x4 *>(b + (rs + 32 * h) * 64 + c8);
@@ -210,7 +215,7 @@ __global__ __launch_bounds__(256) void colsum_blocked_partial_kernel(const T *bl
 #pragma unroll
         for (int r = 0; r < 32; ++r) t += red[r][threadIdx.x];
         const int c = cb * 64 + threadIdx.x;
-        if (c < C) partial[(int64_t)blockIdx.y * C + c] = t;
+        if (c < C) partial[((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * C + c] = t;
     }
 }
 template <typename T>
@@ -546,20 +551,25 @@ int colsum(int dtype, const void *in, int64_t ld, int R, int C, const float *row
 
 int colsum_blocked_chunks(int R) { return R <= 0 ? 1 : ((R + 63) / 64 + CSB_BLOCKS - 1) / CSB_BLOCKS; }
 
-int colsum_blocked(int dtype, const void *blk, int ncb, int R, int C, float *partial, void *out_lp, hipStream_t s) {
+int colsum_blocked(int dtype, const void *blk, int ncb, int R, int C, float *partial, void *out_lp, hipStream_t s, int workers,
+                   int seg_rows, int64_t out_stride) {
     KernelTimer timer(KC_AUX, s, 0.0, 0.0);
     if (C <= 0) return LSTM_OK;
+    // R rows per worker; with several workers every time step holds `workers` segments of seg_rows rows
     const int nrb = (R + 63) / 64, chunks = colsum_blocked_chunks(R);
-    if (dtype == LSTM_DTYPE_FP32 || chunks > 65535 || (C + 63) / 64 > ncb) {
-        set_error("colsum_blocked: unsupported (dtype %d, R=%d, C=%d, ncb=%d)", dtype, R, C, ncb);
+    if (dtype == LSTM_DTYPE_FP32 || chunks > 65535 || (C + 63) / 64 > ncb || workers < 1 || workers > 65535 ||
+        (workers > 1 && (seg_rows < 64 || seg_rows % 64 != 0 || R % seg_rows != 0))) {
+        set_error("colsum_blocked: unsupported (dtype %d, R=%d, C=%d, ncb=%d, workers=%d, segment %d)", dtype, R, C, ncb, workers,
+                  seg_rows);
         return LSTM_ERR_UNSUPPORTED;
     }
+    const int seg = workers > 1 ? seg_rows / 64 : (nrb > 0 ? nrb : 1), stride = seg * workers;
     LSTM_DISPATCH(dtype, T, {
         if constexpr (sizeof(T) == 2)
-            hipLaunchKernelGGL(colsum_blocked_partial_kernel<T>, dim3((C + 63) / 64, chunks), dim3(256), 0, s, (const T *)blk, ncb, nrb,
-                               C, partial);
-        hipLaunchKernelGGL(colsum_final_kernel<T>, dim3((C + 255) / 256, 1), dim3(256), 0, s, partial, chunks, C, (const float *)nullptr,
-                           (T *)out_lp, (int64_t)0);
+            hipLaunchKernelGGL(colsum_blocked_partial_kernel<T>, dim3((C + 63) / 64, chunks, workers), dim3(256), 0, s, (const T *)blk,
+                               ncb, nrb, C, partial, seg, stride);
+        hipLaunchKernelGGL(colsum_final_kernel<T>, dim3((C + 255) / 256, workers), dim3(256), 0, s, partial, chunks, C,
+                           (const float *)nullptr, (T *)out_lp, out_stride);
     });
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
