@@ -968,9 +968,12 @@ RecurrentDims recurrent_dims(int B, int H) {
 // against the two-launch form: ahead or level for H <= 768 up to batch 4096 at H = 200..256, 1.6x behind
 // at H = 2048, 12 % behind at H = 200 with 8192 rows).
 static bool narrow_cells(const RecurrentDims &d, int H) { return H % 8 == 0 && H <= 768 && d.n_mt * d.n_hb <= 512; }
-// Tile edge of the narrow-layer kernels: 16 while that keeps a cell within a few hundred workgroups
-// (the smaller the tile, the fewer bytes each compute unit pulls in), else 32.
-static int narrow_tile(int B, int H) { return ((B + 15) / 16) * ((H + 15) / 16) <= 512 ? 16 : 32; }
+// Tile edge of the narrow-layer kernels: 16 while that keeps a launch (all its cells) within about 512
+// workgroups: the smaller the tile, the fewer bytes each compute unit pulls in and the shorter the launch;
+// with more cells per launch (deep stacks along the diagonals) the launch is bound by throughput and the
+// 32x32 tile's lower operand traffic wins (measured, 200 units, batch 256: 2 layers 1.73 vs 1.90 ms per
+// step with 16 vs 32, 12 layers 9.3 vs 7.8 ms, 29 layers 22.1 vs 18.7 ms).
+static int narrow_tile(int B, int H, int n_cells) { return (int64_t)((B + 15) / 16) * ((H + 15) / 16) * n_cells <= 512 ? 16 : 32; }
 // Slices of the backward contraction over the 4H gate rows: split by gate over four workgroups (four
 // fp32 partial results that the gate kernel adds) unless the tiles alone fill the chip: then one
 // workgroup contracts over all of it and 12 bytes per unit less are written and read back.
@@ -1159,7 +1162,7 @@ int backward_fused_wave(int dtype, const FusedBackwardCell *c, int n_cells, int 
         set_error("backward_fused_wave: operands must be 16-byte aligned");
         return LSTM_ERR_INVALID;
     }
-    const int R = narrow_tile(B, H);
+    const int R = narrow_tile(B, H, n_cells);
     const dim3 grid((B + R - 1) / R, (H + R - 1) / R, n_cells);
     w.blk_ncb = blk_ncb; w.B = B; w.H = H; w.nkc = d.nkc;
     const double n = (double)B * H;
@@ -1210,7 +1213,7 @@ int step_forward_wave(int dtype, const WaveCell *cells, int n_cells, int blk_ncb
     }
     KernelTimer timer(KC_GEMM_STEP, s, flops, bytes);
     if (narrow_cells(d, H) && all % 16 == 0) {
-        const int R = narrow_tile(B, H);
+        const int R = narrow_tile(B, H, n_cells);
         const dim3 grid((B + R - 1) / R, (H + R - 1) / R, n_cells);
         if (R == 16) {
             LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_narrow_forward_kernel<T, 16>), grid, dim3(256), 0, s, w));
