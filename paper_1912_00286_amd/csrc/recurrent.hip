@@ -553,16 +553,21 @@ __global__ __launch_bounds__(256) void wave_gates_backward_kernel(WaveGateArgs w
 //             add up), the four gates meet through LDS.
 // Operands are the packed ones of the other kernels; an R-row slice of a chunk is a few
 // contiguous pieces of it.
-constexpr int FUSED_MAX_CELLS = 8;
+constexpr int FUSED_MAX_CELLS = 16;         // cells per launch; the argument block comes in three sizes (NC = 2, 4, 16):
+                                           // a launch pays for the size of its arguments (measured: 16 slots instead
+                                           // of 8 cost a two-cell launch 7 %)
 struct FusedBwdCell {
     const void *dApk_next, *UTpk, *dApk_above, *WTpk, *dh_above, *gates, *c_t, *c_prev;
     float *dc_state;
     void *dA, *dApk, *dAblk;
     int first;
 };
-struct FusedBwdArgs {
-    FusedBwdCell cell[FUSED_MAX_CELLS];
+template <int NC> struct FusedBwdArgs {
+    FusedBwdCell cell[NC];
     int blk_ncb, B, H, nkc;
+};
+template <int NC> struct NarrowFwdArgs {
+    FwdArgs cell[NC];
 };
 
 // The cell's argument block is copied into registers in one go: cell = blockIdx.z, tile = (blockIdx.x,
@@ -721,8 +726,8 @@ template <typename T, int IW> struct BackwardItem {
     }
 };
 
-template <typename T, int R>
-__global__ __launch_bounds__(256) void lstm_fused_backward_kernel(FusedBwdArgs w) {
+template <typename T, int R, int NC>
+__global__ __launch_bounds__(256) void lstm_fused_backward_kernel(FusedBwdArgs<NC> w) {
     typedef NarrowGeo<T, R> Geo;
     constexpr int IW = R * R / 256;                              // units per thread: every thread gets an item
     constexpr int UG = R / IW, LD = R + 4, NR = Geo::NR;         // items per row, LDS row pitch, accumulator registers
@@ -811,8 +816,8 @@ template <typename T, int IW> struct ForwardItem {
     }
 };
 
-template <typename T, int R>
-__global__ __launch_bounds__(256) void lstm_narrow_forward_kernel(WaveFwdArgs w) {
+template <typename T, int R, int NC>
+__global__ __launch_bounds__(256) void lstm_narrow_forward_kernel(NarrowFwdArgs<NC> w) {
     typedef NarrowGeo<T, R> Geo;
     constexpr int IW = R * R / 256;                              // units per thread: every thread gets an item
     constexpr int UG = R / IW, LD = R + 4, NR = Geo::NR;
@@ -1133,17 +1138,32 @@ bool fused_backward_supported(int dtype, int B, int H) {
     return narrow_cells(recurrent_dims(B, H), H);
 }
 
+template <int NC>
+static int launch_fused_backward(int dtype, const FusedBwdCell *cells, int n_cells, int blk_ncb, int B, int H, int nkc, hipStream_t s) {
+    FusedBwdArgs<NC> w;
+    for (int i = 0; i < NC; ++i) w.cell[i] = cells[i < n_cells ? i : 0];
+    w.blk_ncb = blk_ncb; w.B = B; w.H = H; w.nkc = nkc;
+    const int R = narrow_tile(B, H, n_cells);
+    const dim3 grid((B + R - 1) / R, (H + R - 1) / R, n_cells);
+    if (R == 16) {
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_fused_backward_kernel<T, 16, NC>), grid, dim3(256), 0, s, w));
+    } else {
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_fused_backward_kernel<T, 32, NC>), grid, dim3(256), 0, s, w));
+    }
+    return LSTM_OK;
+}
+
 int backward_fused_wave(int dtype, const FusedBackwardCell *c, int n_cells, int blk_ncb, int B, int H, hipStream_t s) {
     const RecurrentDims d = recurrent_dims(B, H);
     if (n_cells < 1 || n_cells > FUSED_MAX_CELLS || H % 8 != 0) {
         set_error("backward_fused_wave: %d cells (1..%d), H = %d (multiple of 8)", n_cells, FUSED_MAX_CELLS, H);
         return LSTM_ERR_INVALID;
     }
-    FusedBwdArgs w;
+    FusedBwdCell cells[FUSED_MAX_CELLS];
     uintptr_t all = 0;
     double chunks = 0.0;
-    for (int i = 0; i < FUSED_MAX_CELLS; ++i) {
-        const FusedBackwardCell &x = c[i < n_cells ? i : 0];
+    for (int i = 0; i < n_cells; ++i) {
+        const FusedBackwardCell &x = c[i];
         if (!x.gates || !x.c_t || !x.c_prev || !x.dc_state || !x.dApk || (!x.dA && !x.dAblk) || (!x.dApk_next != !x.UTpk) ||
             (!x.dApk_above != !x.WTpk) || (!x.dApk_above && !x.dh_above) || (!x.first && !x.dApk_next)) {
             set_error("backward_fused_wave: inconsistent operands in cell %d", i);
@@ -1152,78 +1172,97 @@ int backward_fused_wave(int dtype, const FusedBackwardCell *c, int n_cells, int 
         all |= (uintptr_t)x.dApk_next | (uintptr_t)x.UTpk | (uintptr_t)x.dApk_above | (uintptr_t)x.WTpk | (uintptr_t)x.dh_above |
                (uintptr_t)x.gates | (uintptr_t)x.c_t | (uintptr_t)x.c_prev | (uintptr_t)x.dc_state | (uintptr_t)x.dA |
                (uintptr_t)x.dApk | (uintptr_t)x.dAblk;
-        FusedBwdCell &o = w.cell[i];
+        FusedBwdCell &o = cells[i];
         o.dApk_next = x.dApk_next; o.UTpk = x.UTpk; o.dApk_above = x.dApk_above; o.WTpk = x.WTpk; o.dh_above = x.dh_above;
         o.gates = x.gates; o.c_t = x.c_t; o.c_prev = x.c_prev; o.dc_state = x.dc_state; o.dA = x.dA; o.dApk = x.dApk;
         o.dAblk = x.dAblk; o.first = x.first;
-        if (i < n_cells) chunks += (x.dApk_next ? 1.0 : 0.0) + (x.dApk_above ? 1.0 : 0.0);
+        chunks += (x.dApk_next ? 1.0 : 0.0) + (x.dApk_above ? 1.0 : 0.0);
     }
     if (all % 16 != 0) {
         set_error("backward_fused_wave: operands must be 16-byte aligned");
         return LSTM_ERR_INVALID;
     }
-    const int R = narrow_tile(B, H, n_cells);
-    const dim3 grid((B + R - 1) / R, (H + R - 1) / R, n_cells);
-    w.blk_ncb = blk_ncb; w.B = B; w.H = H; w.nkc = d.nkc;
     const double n = (double)B * H;
     // products: 2 B H 4H flops, operands once; gate arithmetic: as in the stand-alone kernel without the partials
     KernelTimer timer(KC_GEMM_STEP, s, chunks * 2.0 * n * 4.0 * H, chunks * 2.0 * (4.0 * H * H + 4.0 * n) + n_cells * n * (8.0 + 15.0 * 2.0));
-    if (R == 16) {
-        LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_fused_backward_kernel<T, 16>), grid, dim3(256), 0, s, w));
-    } else {
-        LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_fused_backward_kernel<T, 32>), grid, dim3(256), 0, s, w));
-    }
+    if (n_cells <= 2) { LSTM_TRY(launch_fused_backward<2>(dtype, cells, n_cells, blk_ncb, B, H, d.nkc, s)); }
+    else if (n_cells <= 4) { LSTM_TRY(launch_fused_backward<4>(dtype, cells, n_cells, blk_ncb, B, H, d.nkc, s)); }
+    else { LSTM_TRY(launch_fused_backward<FUSED_MAX_CELLS>(dtype, cells, n_cells, blk_ncb, B, H, d.nkc, s)); }
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
 
-int wave_forward_max_cells() { return WAVE_MAX_CELLS; }
+int wave_forward_max_cells() { return FUSED_MAX_CELLS; }   // step_forward_wave splits for the general kernel itself
+
+template <int NC>
+static int launch_narrow_forward(int dtype, const FwdArgs *cells, int n_cells, int B, int H, hipStream_t s) {
+    NarrowFwdArgs<NC> w;
+    for (int i = 0; i < NC; ++i) w.cell[i] = cells[i < n_cells ? i : 0];
+    const int R = narrow_tile(B, H, n_cells);
+    const dim3 grid((B + R - 1) / R, (H + R - 1) / R, n_cells);
+    if (R == 16) {
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_narrow_forward_kernel<T, 16, NC>), grid, dim3(256), 0, s, w));
+    } else {
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_narrow_forward_kernel<T, 32, NC>), grid, dim3(256), 0, s, w));
+    }
+    return LSTM_OK;
+}
 
 int step_forward_wave(int dtype, const WaveCell *cells, int n_cells, int blk_ncb, int B, int H, hipStream_t s) {
     const RecurrentDims d = recurrent_dims(B, H);
-    if (n_cells < 1 || n_cells > WAVE_MAX_CELLS) {
-        set_error("step_forward_wave: %d cells (1..%d)", n_cells, WAVE_MAX_CELLS);
+    if (n_cells < 1 || n_cells > FUSED_MAX_CELLS) {
+        set_error("step_forward_wave: %d cells (1..%d)", n_cells, FUSED_MAX_CELLS);
         return LSTM_ERR_INVALID;
     }
-    WaveFwdArgs w;
-    w.wgs_per_cell = d.n_mt * d.n_hb;
+    FwdArgs args[FUSED_MAX_CELLS];
     uintptr_t all = 0;
-    for (int i = 0; i < WAVE_MAX_CELLS; ++i) {
-        const WaveCell &c = cells[i < n_cells ? i : 0];
+    for (int i = 0; i < n_cells; ++i) {
+        const WaveCell &c = cells[i];
         if (!c.hpk_prev || !c.Upk || !c.c_state || !c.gates || !c.c_out || !c.h_out || !c.hpk_next || (!c.Ax && (!c.xpk || !c.Wpk || !c.bias))) {
             set_error("step_forward_wave: null operand in cell %d", i);
             return LSTM_ERR_INVALID;
         }
         all |= (uintptr_t)c.hpk_prev | (uintptr_t)c.Upk | (uintptr_t)c.Ax | (uintptr_t)c.xpk | (uintptr_t)c.Wpk | (uintptr_t)c.bias |
                (uintptr_t)c.c_state | (uintptr_t)c.gates | (uintptr_t)c.c_out | (uintptr_t)c.h_out | (uintptr_t)c.hpk_next | (uintptr_t)c.h_blk;
-        FwdArgs &a = w.cell[i];
+        FwdArgs &a = args[i];
         a.hpk_prev = c.hpk_prev; a.Upk = c.Upk; a.Ax = c.Ax; a.xpk = c.xpk; a.Wpk = c.Wpk; a.bias = c.bias;
         a.c_state = c.c_state; a.gates = c.gates; a.c_out = c.c_out; a.h_out = c.h_out; a.hpk_next = c.hpk_next; a.h_blk = c.h_blk;
         a.blk_ncb = blk_ncb; a.B = B; a.H = H; a.n_mt = d.n_mt; a.nkc = d.nkc;
     }
     // per cell as in step_forward_fused; a cell that projects its input reads W and the packed
     // input instead of a ready-made projection
-    double flops = 0.0, bytes = 0.0;
-    const double bh = (double)B * H;
-    for (int i = 0; i < n_cells; ++i) {
-        const bool proj = !cells[i].Ax;
-        flops += 2.0 * B * 4.0 * H * H * (proj ? 2.0 : 1.0);
-        bytes += 2.0 * (4.0 * H * H * (proj ? 2.0 : 1.0) + bh + (proj ? bh : 4.0 * bh)) + 4.0 * bh +
-                 2.0 * (4.0 * bh + bh + (cells[i].h_blk ? 3.0 : 2.0) * bh) + 4.0 * bh;
-    }
-    KernelTimer timer(KC_GEMM_STEP, s, flops, bytes);
-    if (narrow_cells(d, H) && all % 16 == 0) {
-        const int R = narrow_tile(B, H, n_cells);
-        const dim3 grid((B + R - 1) / R, (H + R - 1) / R, n_cells);
-        if (R == 16) {
-            LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_narrow_forward_kernel<T, 16>), grid, dim3(256), 0, s, w));
-        } else {
-            LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_narrow_forward_kernel<T, 32>), grid, dim3(256), 0, s, w));
+    auto work = [&](int first, int n, double &flops, double &bytes) {
+        const double bh = (double)B * H;
+        flops = bytes = 0.0;
+        for (int i = first; i < first + n; ++i) {
+            const bool proj = !cells[i].Ax;
+            flops += 2.0 * B * 4.0 * H * H * (proj ? 2.0 : 1.0);
+            bytes += 2.0 * (4.0 * H * H * (proj ? 2.0 : 1.0) + bh + (proj ? bh : 4.0 * bh)) + 4.0 * bh +
+                     2.0 * (4.0 * bh + bh + (cells[i].h_blk ? 3.0 : 2.0) * bh) + 4.0 * bh;
         }
-    } else {
-        LP_ONLY(dtype, T, hipLaunchKernelGGL(lstm_wave_forward_kernel<T>, dim3(w.wgs_per_cell * n_cells), dim3(256), 0, s, w));
+    };
+    if (narrow_cells(d, H) && all % 16 == 0) {
+        double flops, bytes;
+        work(0, n_cells, flops, bytes);
+        KernelTimer timer(KC_GEMM_STEP, s, flops, bytes);
+        if (n_cells <= 2) { LSTM_TRY(launch_narrow_forward<2>(dtype, args, n_cells, B, H, s)); }
+        else if (n_cells <= 4) { LSTM_TRY(launch_narrow_forward<4>(dtype, args, n_cells, B, H, s)); }
+        else { LSTM_TRY(launch_narrow_forward<FUSED_MAX_CELLS>(dtype, args, n_cells, B, H, s)); }
+        LSTM_LAUNCH_CHECK();
+        return LSTM_OK;
     }
-    LSTM_LAUNCH_CHECK();
+    // the general multi-cell kernel takes up to WAVE_MAX_CELLS cells per launch
+    for (int first = 0; first < n_cells; first += WAVE_MAX_CELLS) {
+        const int n = n_cells - first < WAVE_MAX_CELLS ? n_cells - first : WAVE_MAX_CELLS;
+        WaveFwdArgs w;
+        w.wgs_per_cell = d.n_mt * d.n_hb;
+        for (int i = 0; i < WAVE_MAX_CELLS; ++i) w.cell[i] = args[first + (i < n ? i : 0)];
+        double flops, bytes;
+        work(first, n, flops, bytes);
+        KernelTimer timer(KC_GEMM_STEP, s, flops, bytes);
+        LP_ONLY(dtype, T, hipLaunchKernelGGL(lstm_wave_forward_kernel<T>, dim3(w.wgs_per_cell * n), dim3(256), 0, s, w));
+        LSTM_LAUNCH_CHECK();
+    }
     return LSTM_OK;
 }
 
