@@ -753,8 +753,26 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             LSTM_TRY(setup.flush(p.dtype, p.B, p.H, s));
         }
         char *dablk = p.blk ? at(scratch, p.wb ? p.s_wb_dablk[l] : p.s_dablk) : nullptr;
+        const bool fused_step = fused && !p.wb && step_backward_fused_supported(p.dtype, p.B, p.H) && (dA_rm || dablk);
         for (int t = p.wb ? -1 : p.T - 1; t >= 0; --t) {      // along the diagonals the steps are already done
             const bool last = t == p.T - 1;
+            if (fused && fused_step) {
+                // thousands of rows per step: product and gate arithmetic in one launch, no partial sums in memory
+                FusedBackwardCell c{};
+                c.dApk_next = last ? nullptr : dapk[(t + 1) & 1];
+                c.UTpk = last ? nullptr : utpk;
+                c.dh_above = dh_above + (size_t)t * BH * es;
+                c.gates = gates + (size_t)t * p.B * p.G * es;
+                c.c_t = cs + (size_t)(t + 1) * BH * es;
+                c.c_prev = cs + (size_t)t * BH * es;
+                c.dc_state = dc_state;
+                c.dA = dA_rm ? dA + (size_t)t * p.B * p.G * es : nullptr;
+                c.dApk = dapk[t & 1];
+                c.dAblk = dablk ? dablk + (size_t)t * (p.B / 64) * p.g_ncb * 4096 * es : nullptr;
+                c.first = last ? 1 : 0;
+                LSTM_TRY(step_backward_fused(p.dtype, c, p.g_ncb, p.B, p.H, s));
+                continue;
+            }
             if (fused) {
                 // dA_{t+1} U as four per-gate K-slices, summed by the gate kernel
                 float *part = (float *)at(scratch, p.s_part);

@@ -141,6 +141,9 @@ struct FusedBackwardCell {
     void *dA, *dApk, *dAblk;  // dA row-major (nullable), packed (the next step's operand), blocked (nullable)
     int first;
 };
+// one BPTT step of one layer in a single launch on the large-batch tiles (dApk_above / WTpk must be null)
+bool step_backward_fused_supported(int dtype, int B, int H);
+int step_backward_fused(int dtype, const FusedBackwardCell &c, int blk_ncb, int B, int H, hipStream_t s);
 int fused_backward_max_cells();
 bool fused_backward_supported(int dtype, int B, int H);
 int backward_fused_wave(int dtype, const FusedBackwardCell *c, int n_cells, int blk_ncb, int B, int H, hipStream_t s);

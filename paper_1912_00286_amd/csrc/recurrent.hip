@@ -853,6 +853,65 @@ __global__ __launch_bounds__(256) void lstm_narrow_forward_kernel(NarrowFwdArgs<
     item.finish(a, pz, b, j0);
 }
 
+// ---------------------------------------------------------------- fused backward step, large batches
+// With thousands of rows per step the 64x128 tiles alone fill the chip, the contraction over the 4H gate rows
+// is not split over workgroups (backward_slices), and the workgroup that owns a tile has the complete
+// gradient of its 64 rows x 128 units: the gate arithmetic follows in its epilogue instead of in a second
+// kernel, and the fp32 partial sums never go to memory.  Main loop and reduction are those of
+// lstm_step_backward_gemm_kernel, the epilogue is BackwardItem's (four items of 8 units per thread).
+struct FusedStepArgs {
+    FusedBwdCell c;        // dApk_above / WTpk unused (the gradient from above arrives in dh_above)
+    int blk_ncb, B, H, n_mt, nkc;
+};
+template <typename T>
+__global__ __launch_bounds__(256) void lstm_step_backward_fused_kernel(FusedStepArgs a) {
+    constexpr int LD = TN + 4;
+    __shared__ __attribute__((aligned(16))) float smem[4 * RED_FLOATS];
+    const FusedBwdCell c = a.c;
+    const int lin = xcd_swizzle(blockIdx.x, gridDim.x);
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int mt = lin % a.n_mt, nt = lin / a.n_mt;
+    const int m0 = mt * TM, n0 = nt * TN;
+    const int H = a.H;
+    const int nch = c.dApk_next ? 4 * a.nkc : 0;
+    const int cpw = (nch + 3) / 4;
+    const int c0 = min(nch, wave * cpw), c1 = min(nch, c0 + cpw);
+    v16f acc[2][NBLK];
+    zero_acc(acc);
+    packed_mainloop<T>(reinterpret_cast<const uint16_t *>(c.dApk_next) + (int64_t)mt * 4 * a.nkc * A_CHUNK,
+                       reinterpret_cast<const uint16_t *>(c.UTpk) + (int64_t)nt * 4 * a.nkc * B_CHUNK, c0, c1, (int)blockIdx.x, lane, acc);
+    // the epilogue's operands: item i of this thread is batch row (i * 256 + tid) / 16 of the tile, units 8 ((i * 256 + tid) % 16) ..
+    BackwardItem<T, 8> item[4];
+    bool valid[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int idx = i * 256 + tid, b = m0 + (idx >> 4), j0 = n0 + (idx & 15) * 8;
+        valid[i] = b < a.B && j0 < H;
+        if (valid[i]) item[i].request(c, b, j0, H);
+    }
+    float sum[8][NBLK];
+    reduce_waves(smem, wave, lane, acc, sum);
+    __syncthreads();                                   // every wavefront has read the partial sums
+    {
+        const int mb = wave >> 1, rh = (wave & 1) * 8;
+#pragma unroll
+        for (int rr = 0; rr < 8; ++rr) {
+            const int r = rh + rr, trow = mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+#pragma unroll
+            for (int nb = 0; nb < NBLK; ++nb) smem[trow * LD + nb * 32 + (lane & 31)] = sum[rr][nb];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (!valid[i]) continue;
+        const int idx = i * 256 + tid, row = idx >> 4, ug = idx & 15;
+        __attribute__((aligned(16))) float rec[8];
+        copy_bytes<32>(rec, smem + row * LD + ug * 8);
+        item[i].finish(c, rec, m0 + row, n0 + ug * 8, H, a.nkc, a.blk_ncb);
+    }
+}
+
 // ---------------------------------------------------------------- packing
 // chunk (hb, kc) of Upk, row g*32 + r, column kk = U[g*H + hb*32 + r][kc*64 + kk], zero outside
 template <typename T>
@@ -1095,6 +1154,33 @@ int step_backward_gemm(int dtype, const void *dApk, const void *UTpk, float *par
     } else {
         LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_step_backward_gemm_kernel<T, false>), dim3(grid), dim3(256), 0, s, a));
     }
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+bool step_backward_fused_supported(int dtype, int B, int H) {
+    if (dtype != LSTM_DTYPE_FP16 && dtype != LSTM_DTYPE_BF16) return false;
+    return H % 8 == 0 && backward_slices(recurrent_dims(B, H)) == 1;
+}
+
+int step_backward_fused(int dtype, const FusedBackwardCell &x, int blk_ncb, int B, int H, hipStream_t s) {
+    const RecurrentDims d = recurrent_dims(B, H);
+    const uintptr_t all = (uintptr_t)x.dApk_next | (uintptr_t)x.UTpk | (uintptr_t)x.dh_above | (uintptr_t)x.gates | (uintptr_t)x.c_t |
+                          (uintptr_t)x.c_prev | (uintptr_t)x.dc_state | (uintptr_t)x.dA | (uintptr_t)x.dApk | (uintptr_t)x.dAblk;
+    if (!step_backward_fused_supported(dtype, B, H) || !x.gates || !x.c_t || !x.c_prev || !x.dc_state || !x.dApk || (!x.dA && !x.dAblk) ||
+        (!x.dApk_next != !x.UTpk) || x.dApk_above || x.WTpk || !x.dh_above || (!x.first && !x.dApk_next) || all % 16 != 0) {
+        set_error("step_backward_fused: unsupported shape or inconsistent / misaligned operands (B=%d H=%d)", B, H);
+        return LSTM_ERR_INVALID;
+    }
+    FusedStepArgs a;
+    a.c.dApk_next = x.dApk_next; a.c.UTpk = x.UTpk; a.c.dApk_above = nullptr; a.c.WTpk = nullptr; a.c.dh_above = x.dh_above;
+    a.c.gates = x.gates; a.c.c_t = x.c_t; a.c.c_prev = x.c_prev; a.c.dc_state = x.dc_state; a.c.dA = x.dA; a.c.dApk = x.dApk;
+    a.c.dAblk = x.dAblk; a.c.first = x.first;
+    a.blk_ncb = blk_ncb; a.B = B; a.H = H; a.n_mt = d.n_mt; a.nkc = d.nkc;
+    const double n = (double)B * H;
+    KernelTimer timer(KC_GEMM_STEP, s, x.dApk_next ? 2.0 * n * 4.0 * H : 0.0,
+                      (x.dApk_next ? 2.0 * (4.0 * H * H + 4.0 * n) : 0.0) + n * (8.0 + 2.0 * (7.0 + 4.0 * (1 + (x.dA ? 1 : 0) + (x.dAblk ? 1 : 0)))));
+    LP_ONLY(dtype, T, hipLaunchKernelGGL(lstm_step_backward_fused_kernel<T>, dim3(d.n_mt * d.n_nt), dim3(256), 0, s, a));
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
