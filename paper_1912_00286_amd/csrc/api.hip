@@ -50,6 +50,8 @@ struct Plan {
            s_colpart = 0, s_dE32 = 0, s_part = 0, s_upk = 0, s_apk[2] = {0, 0}, scratch_bytes = 0;
     // forward along anti-diagonals (cells of several layers per launch): per-layer operands and state
     bool wf = false, wb = false;   // wb: the backward pass too (costs one dA per layer, see make_plan)
+    bool proj = false;             // large batches of narrow layers: the input projection runs inside the step kernels
+    size_t s_pj_wpk = 0, s_pj_xseq = 0, s_pj_hseq[2] = {0, 0}, pj_slot_h = 0, pj_slot_x = 0;   // bytes
     bool fb = false;               // wb with each cell's products and gate arithmetic in one launch (narrow layers)
     std::vector<size_t> s_wb_dapk1; // second packed dA per layer (fb: a cell reads one step's while writing the next)
     std::vector<size_t> s_wf_upk, s_wf_wpk, s_wf_c, s_wf_hpk0, s_wf_hpk1;
@@ -229,6 +231,20 @@ int make_plan(const lstm_config *c, Plan &p) {
                 p.s_wf_hpk1[l] = s; s += align_up(rd.hpk_elems * p.es);
                 p.s_wf_c[l] = s; s += align_up((size_t)p.B * p.H * 4);
             }
+        }
+        // Thousands of rows per step on narrow layers: a whole-sequence input projection is bound by writing and
+        // re-reading its [T*B, 4H] result, so the step kernels project their own input (W packed like U, the
+        // layer's input sequence packed step by step; a layer's packed h_t sequence is the next layer's input).
+        p.proj = !p.wf && recurrent_wide_shape(p.B, p.H) && !fused_backward_supported(p.dtype, p.B, p.H);   // beyond the narrow-layer kernels' range
+        if (p.proj) {
+            int max_in = 1;
+            for (int l = 0; l < p.L; ++l) max_in = p.in_dim[l] > max_in ? p.in_dim[l] : max_in;
+            const size_t b_chunk = rd.upk_elems / ((size_t)rd.n_hb * rd.nkc), a_chunk = rd.hpk_elems / ((size_t)rd.n_mt * rd.nkc);
+            p.s_pj_wpk = s; s += align_up((size_t)rd.n_hb * ((max_in + 63) / 64) * b_chunk * p.es);
+            p.pj_slot_h = align_up(rd.hpk_elems * p.es);
+            p.pj_slot_x = align_up((size_t)rd.n_mt * ((p.in_dim[0] + 63) / 64) * a_chunk * p.es);
+            p.s_pj_xseq = s; s += (size_t)p.T * p.pj_slot_x;
+            for (int k = 0; k < 2; ++k) { p.s_pj_hseq[k] = s; s += (size_t)(p.T + 1) * p.pj_slot_h; }
         }
         // Narrow layers of any depth: each BPTT cell in one launch instead of two.
         const bool fb_ok = fused_backward_supported(p.dtype, p.B, p.H);
@@ -426,6 +442,15 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
         // layer 0 has its input ahead of time; the layers above project inside their step kernels)
         if (p.wf && l > 0) {
             setup.pack_u_forward(W, at(scratch, p.s_wf_wpk[l]));
+        } else if (p.proj) {
+            // the step kernels project their own input: W packed like U; layer 0's input sequence packed step by
+            // step (the layers above read the packed h_t sequence of the layer below)
+            LSTM_TRY(pack_w_forward(p.dtype, W, at(scratch, p.s_pj_wpk), p.H, p.in_dim[l], s));
+            if (l == 0) {
+                if (p.blk)   // the weight-gradient GEMM of layer 0 reads the blocked copy
+                    LSTM_TRY(pack_blocked(p.dtype, layer_in, p.in_dim[0], TB, p.in_dim[0], at(reserve, p.r_xblk), s));
+                LSTM_TRY(pack_rows_seq(p.dtype, layer_in, at(scratch, p.s_pj_xseq), p.T, p.B, p.in_dim[0], (int64_t)(p.pj_slot_x / es), s));
+            }
         } else if (p.blk) {
             // operands in 64x64 blocks: layer 0 packs the input once, upper layers read the blocked
             // hidden sequence the step kernels of the layer below wrote
@@ -456,12 +481,14 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
                             c_state, BH, s));
         char *upk = at(scratch, p.wf ? p.s_wf_upk[l] : p.s_upk);
         char *hpk[2] = {at(scratch, p.wf ? p.s_wf_hpk0[l] : p.s_apk[0]), at(scratch, p.wf ? p.s_wf_hpk1[l] : p.s_apk[1])};
+        char *hseq = p.proj ? at(scratch, p.s_pj_hseq[l & 1]) : nullptr;    // packed h_0 .. h_T of this layer, one slot per step
         if (fused) {
             // recurrent weights and the initial hidden state in packed tile order; the second
-            // packed-h buffer only needs its zero padding
+            // packed-h buffer only needs its zero padding (the per-step slots of the projection mode get
+            // theirs from the step kernels)
             setup.pack_u_forward(U, upk);
-            setup.pack_rows(h0 ? at(h0, (size_t)l * BH * es) : nullptr, hpk[0]);
-            setup.pack_rows(nullptr, hpk[1]);
+            setup.pack_rows(h0 ? at(h0, (size_t)l * BH * es) : nullptr, p.proj ? hseq : hpk[0]);
+            if (!p.proj) setup.pack_rows(nullptr, hpk[1]);
         }
         char *hblk = p.blk ? at(reserve, p.r_hblk[l]) : nullptr;
         const size_t slot = (size_t)(p.B / 64) * p.h_ncb * 4096 * es;      // bytes of one time slot of the blocked sequence
@@ -478,6 +505,15 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
         LSTM_TRY(setup.flush(p.dtype, p.B, p.H, s));
         for (int t = 0; t < p.T; ++t) {
             char *a_t = ax + (size_t)t * p.B * p.G * axs;
+            if (fused && p.proj) {
+                const char *xin = l == 0 ? at(scratch, p.s_pj_xseq) + (size_t)t * p.pj_slot_x
+                                         : at(scratch, p.s_pj_hseq[(l - 1) & 1]) + (size_t)(t + 1) * p.pj_slot_h;
+                LSTM_TRY(step_forward_proj(p.dtype, hseq + (size_t)t * p.pj_slot_h, upk, xin, at(scratch, p.s_pj_wpk), b, p.in_dim[l],
+                                           c_state, gates + (size_t)t * p.B * p.G * es, cs + (size_t)(t + 1) * BH * es,
+                                           hs + (size_t)(t + 1) * BH * es, hseq + (size_t)(t + 1) * p.pj_slot_h,
+                                           hblk ? hblk + (size_t)(t + 1) * slot : nullptr, p.h_ncb, p.B, p.H, s));
+                continue;
+            }
             if (fused) {
                 // recurrent projection, gates, cell and hidden update in one launch
                 LSTM_TRY(step_forward_fused(p.dtype, hpk[t & 1], upk, a_t, c_state, gates + (size_t)t * p.B * p.G * es,

@@ -96,6 +96,15 @@ int setup_jobs(int dtype, const SetupJob *jobs, int n_jobs, int B, int H, hipStr
 // h_blk (nullable): first block row of this time slot in a 64x64-blocked copy of the hidden sequence
 int step_forward_fused(int dtype, const void *hpk_prev, const void *Upk, const void *Ax, float *c_state, void *gates,
                        void *c_out, void *h_out, void *hpk_next, void *h_blk, int blk_ncb, int B, int H, hipStream_t s);
+// The same with the step's input projection done in the kernel (large batches of narrow layers, where a
+// whole-sequence projection is bound by writing and re-reading its [T*B, 4H] result): W packed for an
+// input width K, a sequence [T, B, K] packed step by step (slot stride in elements).
+bool recurrent_wide_shape(int B, int H);
+int pack_w_forward(int dtype, const void *W, void *Wpk, int H, int K, hipStream_t s);
+int pack_rows_seq(int dtype, const void *x, void *xpk, int T_steps, int B, int K, int64_t dst_stride, hipStream_t s);
+int step_forward_proj(int dtype, const void *hpk_prev, const void *Upk, const void *xpk, const void *Wpk, const void *bias, int in_width,
+                      float *c_state, void *gates, void *c_out, void *h_out, void *hpk_next, void *h_blk, int blk_ncb, int B, int H,
+                      hipStream_t s);
 // backward: partials[q][B,H] = dA_next[:, gate q rows] * U[gate q rows, :] for q = 0..3
 int step_backward_gemm(int dtype, const void *dApk, const void *UTpk, float *partials, int B, int H, hipStream_t s);
 // BPTT through the gates; dA written row-major, packed, and (dAblk non-null: first block row of the time slot) 64x64-blocked

@@ -183,6 +183,7 @@ struct FwdArgs {
     void *h_blk;           // h_t out in 64x64 blocks (first block row of this time slot), or null
     int blk_ncb;           // column blocks per row block of h_blk
     int B, H, n_mt, nkc;
+    int nkc2;              // K chunks of the input projection done here (xpk / Wpk), when Ax is null
 };
 
 // WIDE = false: the four wavefronts split the K range of one 64-row tile and their partial
@@ -199,21 +200,21 @@ __device__ __forceinline__ void forward_cell(const FwdArgs &a, int tile, int rot
     const int H = a.H, G = 4 * a.H;
     // K chunks of this cell: the recurrent product, then (a cell that projects its own input) the
     // layer below's h_t times W^T; the wavefronts split the whole list
-    const int nch = a.Ax ? a.nkc : 2 * a.nkc;
+    const int nch = a.Ax ? a.nkc : a.nkc + a.nkc2;
     const int cpw = (nch + 3) / 4;                         // chunks per wavefront
     const int c0 = WIDE ? 0 : min(nch, wave * cpw), c1 = WIDE ? nch : min(nch, c0 + cpw);
     v16f acc[2][NBLK];
     zero_acc(acc);
     packed_mainloop<T>(reinterpret_cast<const uint16_t *>(a.hpk_prev) + (int64_t)mt * a.nkc * A_CHUNK,
                        reinterpret_cast<const uint16_t *>(a.Upk) + (int64_t)hb * a.nkc * B_CHUNK, c0, c1, rot, lane, acc,
-                       a.Ax ? nullptr : reinterpret_cast<const uint16_t *>(a.xpk) + (int64_t)mt * a.nkc * A_CHUNK,
-                       a.Ax ? nullptr : reinterpret_cast<const uint16_t *>(a.Wpk) + (int64_t)hb * a.nkc * B_CHUNK, a.nkc);
+                       a.Ax ? nullptr : reinterpret_cast<const uint16_t *>(a.xpk) + (int64_t)mt * a.nkc2 * A_CHUNK,
+                       a.Ax ? nullptr : reinterpret_cast<const uint16_t *>(a.Wpk) + (int64_t)hb * a.nkc2 * B_CHUNK, a.nkc);
     const int j = j0 + (lane & 31);
     const int jc = min(j, H - 1);
     T *gates = reinterpret_cast<T *>(a.gates);
     T *c_out = reinterpret_cast<T *>(a.c_out);
     T *h_out = reinterpret_cast<T *>(a.h_out);
-    T *hpk = reinterpret_cast<T *>(a.hpk_next) + ((int64_t)mt * a.nkc + (min(j, H - 1) >> 6)) * A_CHUNK;
+    T *hpk = reinterpret_cast<T *>(a.hpk_next) + ((int64_t)mt * a.nkc + (min(j, a.nkc * SK - 1) >> 6)) * A_CHUNK;
     // The step's input projection and the previous cell state do not depend on the GEMM: a
     // group of 8 accumulator rows requests them first (addresses clamped into the tensors;
     // out-of-range lanes never store) and consumes them after the pre-activations are ready.
@@ -230,7 +231,19 @@ __device__ __forceinline__ void forward_cell(const FwdArgs &a, int tile, int rot
         }
     };
     auto finish_group = [&](int mb, int rh, const float (&pre)[8][NBLK], const float (&axv)[8][4], const float (&cprev)[8]) {
-        if (j >= H) return;
+        if (j >= H) {
+            // padding columns of the packed h_t (up to the next multiple of 64) are written as zeros, so
+            // that a slot never touched before can serve as the next step's operand
+            if (j < a.nkc * SK) {
+#pragma unroll
+                for (int rr = 0; rr < 8; ++rr) {
+                    const int r = rh + rr;
+                    const int rl = mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                    if (m0 + rl < a.B) hpk[frag_offset(rl, j & 63, 2)] = Lp<T>::from_f(0.0f);
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int rr = 0; rr < 8; ++rr) {
             const int r = rh + rr;
@@ -832,7 +845,7 @@ __global__ __launch_bounds__(256) void lstm_narrow_forward_kernel(NarrowFwdArgs<
     const bool valid = b < a.B && j0 < a.H;
     ForwardItem<T, IW> item;
     if (valid) item.request(a, b, j0);
-    const int nch = a.Ax ? a.nkc : 2 * a.nkc;
+    const int nch = a.Ax ? a.nkc : a.nkc + a.nkc2;       // nkc2 = nkc here: the input of these cells is H wide
     // rows of U (and W): hidden block u0 / 32, inside it gate `wave`'s 32 rows, of those the tile's R
     const int64_t a_off = (int64_t)(b0 >> 6) * a.nkc * (A_CHUNK / 8) + Geo::slice_a(b0) + Geo::lane_a(lane);
     const int64_t b_off = (int64_t)(u0 >> 5) * a.nkc * (B_CHUNK / 8) + Geo::slice_b(wave * 32 + (u0 & 31)) + Geo::lane_b(lane);
@@ -913,15 +926,16 @@ __global__ __launch_bounds__(256) void lstm_step_backward_fused_kernel(FusedStep
 }
 
 // ---------------------------------------------------------------- packing
-// chunk (hb, kc) of Upk, row g*32 + r, column kk = U[g*H + hb*32 + r][kc*64 + kk], zero outside
+// chunk (hb, kc) of Upk, row g*32 + r, column kk = U[g*H + hb*32 + r][kc*64 + kk], zero outside;
+// U is [4H, K] (K = H for the recurrent matrix, the layer's input width for W), nkc = ceil(K / 64)
 template <typename T>
-__device__ __forceinline__ void pack_u_forward_block(const T *U, T *Upk, int H, int nkc, int kc, int hb) {
+__device__ __forceinline__ void pack_u_forward_block(const T *U, T *Upk, int H, int nkc, int kc, int hb, int K) {
     T *dst = Upk + ((int64_t)hb * nkc + kc) * B_CHUNK;
     for (int v = threadIdx.x; v < B_CHUNK; v += 256) {
         const int row = v >> 6, kk = v & 63;
         const int g = row >> 5, r = row & 31;
         const int unit = hb * 32 + r, k = kc * 64 + kk;
-        dst[frag_offset(row, kk, NBLK)] = (unit < H && k < H) ? U[((int64_t)g * H + unit) * H + k] : Lp<T>::from_f(0.0f);
+        dst[frag_offset(row, kk, NBLK)] = (unit < H && k < K) ? U[((int64_t)g * H + unit) * K + k] : Lp<T>::from_f(0.0f);
     }
 }
 // chunk (nt, q, kc) of UTpk, row r, column kk = U[q*H + kc*64 + kk][nt*128 + r], zero outside
@@ -937,7 +951,7 @@ __device__ __forceinline__ void pack_u_backward_block(const T *U, T *UTpk, int H
     T *dst = UTpk + (((int64_t)nt * 4 + q) * nkc + kc) * B_CHUNK;
     for (int v = threadIdx.x; v < B_CHUNK; v += 256) dst[frag_offset(v >> 6, v & 63, NBLK)] = tile[v & 63][v >> 6];
 }
-// chunk (mt, kc) of hpk, row, column kk = h[mt*64 + row][kc*64 + kk] (null h = 0), zero outside
+// chunk (mt, kc) of hpk, row, column kk = h[mt*64 + row][kc*64 + kk] (null h = 0), zero outside; h is [B, H]
 template <typename T>
 __device__ __forceinline__ void pack_rows_block(const T *h, T *hpk, int B, int H, int nkc, int kc, int mt) {
     T *dst = hpk + ((int64_t)mt * nkc + kc) * A_CHUNK;
@@ -946,9 +960,18 @@ __device__ __forceinline__ void pack_rows_block(const T *h, T *hpk, int B, int H
         dst[frag_offset(v >> 6, v & 63, 2)] = (h && row < B && k < H) ? h[(int64_t)row * H + k] : Lp<T>::from_f(0.0f);
     }
 }
+// a whole sequence [T, B, K] packed step by step: blockIdx.z = time step
+template <typename T>
+__global__ __launch_bounds__(256) void pack_rows_seq_kernel(const T *x, T *xpk, int B, int K, int nkc, int64_t dst_stride) {
+    pack_rows_block<T>(x + (int64_t)blockIdx.z * B * K, xpk + (int64_t)blockIdx.z * dst_stride, B, K, nkc, blockIdx.x, blockIdx.y);
+}
 template <typename T>
 __global__ __launch_bounds__(256) void pack_u_forward_kernel(const T *U, T *Upk, int H, int nkc) {
-    pack_u_forward_block<T>(U, Upk, H, nkc, blockIdx.x, blockIdx.y);
+    pack_u_forward_block<T>(U, Upk, H, nkc, blockIdx.x, blockIdx.y, H);
+}
+template <typename T>
+__global__ __launch_bounds__(256) void pack_w_forward_kernel(const T *W, T *Wpk, int H, int K, int nkc) {
+    pack_u_forward_block<T>(W, Wpk, H, nkc, blockIdx.x, blockIdx.y, K);
 }
 template <typename T>
 __global__ __launch_bounds__(256) void pack_u_backward_kernel(const T *U, T *UTpk, int H, int nkc) {
@@ -980,7 +1003,7 @@ __global__ __launch_bounds__(256) void setup_jobs_kernel(SetupArgs a) {
     const int x = blockIdx.x;
     switch (j.kind) {                                    // uniform over the workgroup
         case SETUP_PACK_U_FORWARD:
-            if (x < a.nkc * a.n_hb) pack_u_forward_block<T>((const T *)j.src, (T *)j.dst, a.H, a.nkc, x % a.nkc, x / a.nkc);
+            if (x < a.nkc * a.n_hb) pack_u_forward_block<T>((const T *)j.src, (T *)j.dst, a.H, a.nkc, x % a.nkc, x / a.nkc, a.H);
             break;
         case SETUP_PACK_U_BACKWARD:
             if (x < a.nkc * 4 * a.n_nt)
@@ -1115,7 +1138,7 @@ int step_forward_fused(int dtype, const void *hpk_prev, const void *Upk, const v
     const RecurrentDims d = recurrent_dims(B, H);
     FwdArgs a;
     a.hpk_prev = hpk_prev; a.Upk = Upk; a.Ax = Ax; a.c_state = c_state; a.gates = gates; a.c_out = c_out; a.h_out = h_out;
-    a.xpk = nullptr; a.Wpk = nullptr; a.bias = nullptr;
+    a.xpk = nullptr; a.Wpk = nullptr; a.bias = nullptr; a.nkc2 = 0;
     a.hpk_next = hpk_next; a.h_blk = h_blk; a.blk_ncb = blk_ncb;
     a.B = B; a.H = H; a.n_mt = d.n_mt; a.nkc = d.nkc;
     if (narrow_cells(d, H)) {                                  // a few dozen workgroups: the latency-lean kernel
@@ -1131,6 +1154,59 @@ int step_forward_fused(int dtype, const void *hpk_prev, const void *Upk, const v
     KernelTimer timer(KC_GEMM_STEP, s, 2.0 * B * 4.0 * H * H,
                       2.0 * (4.0 * H * H + bh + 4.0 * bh) + 4.0 * bh + 2.0 * (4.0 * bh + bh + (h_blk ? 3.0 : 2.0) * bh) + 4.0 * bh);
     if (wide) {
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_step_forward_kernel<T, true>), dim3(grid), dim3(64), 0, s, a));
+    } else {
+        LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_step_forward_kernel<T, false>), dim3(grid), dim3(256), 0, s, a));
+    }
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+bool recurrent_wide_shape(int B, int H) { return recurrent_wide(recurrent_dims(B, H)); }
+
+int pack_w_forward(int dtype, const void *W, void *Wpk, int H, int K, hipStream_t s) {
+    const RecurrentDims d = recurrent_dims(1, H);
+    const int nkc = (K + SK - 1) / SK;
+    KernelTimer timer(KC_AUX, s, 0.0, 0.0);
+    LP_ONLY(dtype, T, hipLaunchKernelGGL(pack_w_forward_kernel<T>, dim3(nkc, d.n_hb), dim3(256), 0, s, (const T *)W, (T *)Wpk, H, K, nkc));
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+int pack_rows_seq(int dtype, const void *x, void *xpk, int T_steps, int B, int K, int64_t dst_stride, hipStream_t s) {
+    const int nkc = (K + SK - 1) / SK, n_mt = (B + TM - 1) / TM;
+    if (T_steps < 1 || T_steps > 65535 || dst_stride < (int64_t)n_mt * nkc * A_CHUNK) {
+        set_error("pack_rows_seq: bad sequence length %d or slot stride", T_steps);
+        return LSTM_ERR_INVALID;
+    }
+    KernelTimer timer(KC_AUX, s, 0.0, 0.0);
+    LP_ONLY(dtype, T, hipLaunchKernelGGL(pack_rows_seq_kernel<T>, dim3(nkc, n_mt, T_steps), dim3(256), 0, s, (const T *)x, (T *)xpk, B, K, nkc,
+                                         dst_stride));
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+// as step_forward_fused, with the step's input projection done here: xpk = the step's input packed like h
+// (in_width columns), Wpk = W packed by pack_w_forward, bias added in the epilogue
+int step_forward_proj(int dtype, const void *hpk_prev, const void *Upk, const void *xpk, const void *Wpk, const void *bias, int in_width,
+                      float *c_state, void *gates, void *c_out, void *h_out, void *hpk_next, void *h_blk, int blk_ncb, int B, int H,
+                      hipStream_t s) {
+    const RecurrentDims d = recurrent_dims(B, H);
+    if (!xpk || !Wpk || !bias || in_width < 1) {
+        set_error("step_forward_proj: null operand");
+        return LSTM_ERR_INVALID;
+    }
+    FwdArgs a;
+    a.hpk_prev = hpk_prev; a.Upk = Upk; a.Ax = nullptr; a.c_state = c_state; a.gates = gates; a.c_out = c_out; a.h_out = h_out;
+    a.xpk = xpk; a.Wpk = Wpk; a.bias = bias; a.nkc2 = (in_width + SK - 1) / SK;
+    a.hpk_next = hpk_next; a.h_blk = h_blk; a.blk_ncb = blk_ncb;
+    a.B = B; a.H = H; a.n_mt = d.n_mt; a.nkc = d.nkc;
+    const int grid = d.n_mt * d.n_hb;
+    const double bh = (double)B * H;
+    KernelTimer timer(KC_GEMM_STEP, s, 2.0 * B * 4.0 * H * ((double)H + in_width),
+                      2.0 * (4.0 * H * ((double)H + in_width) + bh + (double)B * in_width) + 4.0 * bh +
+                          2.0 * (4.0 * bh + bh + (h_blk ? 3.0 : 2.0) * bh) + 4.0 * bh);
+    if (recurrent_wide(d)) {
         LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_step_forward_kernel<T, true>), dim3(grid), dim3(64), 0, s, a));
     } else {
         LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_step_forward_kernel<T, false>), dim3(grid), dim3(256), 0, s, a));
@@ -1313,7 +1389,7 @@ int step_forward_wave(int dtype, const WaveCell *cells, int n_cells, int blk_ncb
         FwdArgs &a = args[i];
         a.hpk_prev = c.hpk_prev; a.Upk = c.Upk; a.Ax = c.Ax; a.xpk = c.xpk; a.Wpk = c.Wpk; a.bias = c.bias;
         a.c_state = c.c_state; a.gates = c.gates; a.c_out = c.c_out; a.h_out = c.h_out; a.hpk_next = c.hpk_next; a.h_blk = c.h_blk;
-        a.blk_ncb = blk_ncb; a.B = B; a.H = H; a.n_mt = d.n_mt; a.nkc = d.nkc;
+        a.blk_ncb = blk_ncb; a.B = B; a.H = H; a.n_mt = d.n_mt; a.nkc = d.nkc; a.nkc2 = d.nkc;
     }
     // per cell as in step_forward_fused; a cell that projects its input reads W and the packed
     // input instead of a ready-made projection
