@@ -124,8 +124,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="large")
-    ap.add_argument("--dtype", default=None, choices=["fp16", "bf16"],
-                    help="storage type override (bf16: no loss scaling needed, static scale 1)")
+    ap.add_argument("--dtype", default=None, choices=["fp16", "bf16", "fp32"],
+                    help="storage type override (bf16: no loss scaling needed, static scale 1; fp32: the paper's "
+                         "all-single-precision baseline mode, no loss scaling)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streams", type=int, default=0,
                     help="streams the simulated workers are spread over (0: 4 when there are several workers, else 1)")
@@ -160,7 +161,7 @@ def main():
         return
     w = wl.CONFIGS[args.workload] if args.workload in wl.CONFIGS else wl.EXTRA[args.workload]
     if args.dtype and args.dtype != w.dtype:
-        w = w.with_(dtype=args.dtype, **({"loss_scale": 1.0, "dynamic_scale": False} if args.dtype == "bf16" else {}))
+        w = w.with_(dtype=args.dtype, **({"loss_scale": 1.0, "dynamic_scale": False} if args.dtype in ("bf16", "fp32") else {}))
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     log(f"[bench] workload {w.name}: L={w.num_layers} H={w.hidden} T={w.seq_len} B={w.batch} N={w.n_workers} {w.dtype}")

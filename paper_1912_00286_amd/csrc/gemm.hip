@@ -3,7 +3,8 @@
 //  * half / bfloat16: LDS-staged tiles feeding v_mfma_f32_32x32x16 (fp32
 //    accumulate), 4 wavefronts of 64 lanes per workgroup, each owning a 64x64
 //    sub-tile as 2x2 MFMA blocks.
-//  * fp32 (the all-single-precision baseline mode): LDS-tiled FMA kernel.
+//  * fp32 (the all-single-precision baseline mode): LDS-staged 64x64 tiles on
+//    v_mfma_f32_32x32x2_f32.
 //
 // Optional bias add, fp32 accumulate-into-C, low-precision output, and a
 // split-K form writing fp32 partials that a second kernel sums in a fixed
@@ -535,59 +536,201 @@ __global__ __launch_bounds__(256) void pack_blocked_kernel(const U *src, int64_t
     }
 }
 
-// fp32 baseline-mode GEMM: 64x64 tile, 16-deep K slices, 4x4 outputs per thread.
-constexpr int SBM = 64, SBN = 64, SBK = 16;
+// fp32 baseline-mode GEMM: 64x64 tile, 32-deep K slices, four wavefronts with one 32x32 block each on
+// v_mfma_f32_32x32x2_f32 (fp32 products, fp32 accumulate).  That instruction takes k = 0 from lanes
+// 0..31 and k = 1 from lanes 32..63; the order of k inside a slice is free as long as both operands
+// agree, so lane half q contracts k = 16 q + j in MFMA j and a lane's operands are 16 consecutive
+// floats of its row (four 16-byte LDS reads per operand and slice).
+constexpr int SBM = 64, SBN = 64, SBK = 32;
+constexpr int SLD = SBK + 4;             // floats per LDS row: 16-byte reads of 8 rows cover all banks
+
+// 4 consecutive floats of row `row` at column k; zero outside the operand
+template <bool VEC>
+__device__ inline v4f load4(const float *base, int64_t ld, int row, int nrows, int k, int ksafe, int kend) {
+    if constexpr (VEC) {
+        const bool ok = row < nrows && k < kend;
+        const int rr = row < nrows ? row : 0;
+        const int kk = k < kend ? k : ksafe;
+        v4f v = *reinterpret_cast<const v4f *>(base + (int64_t)rr * ld + kk);
+        if (!ok) v = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+        return v;
+    } else {
+        v4f v = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+        if (row >= nrows) return v;
+        const float *p = base + (int64_t)row * ld + k;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (k + j < kend) v[j] = p[j];
+        return v;
+    }
+}
+
+template <bool VEC>
 __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(KernArgs a) {
-    __shared__ float As[SBK][SBM + 1];
-    __shared__ float Bs[SBK][SBN + 1];
+    __shared__ __attribute__((aligned(16))) float As[2][SBM * SLD];
+    __shared__ __attribute__((aligned(16))) float Bs[2][SBN * SLD];
     const float *A = reinterpret_cast<const float *>(a.A);
     const float *B = reinterpret_cast<const float *>(a.B);
     const int tid = threadIdx.x;
-    const int tx = tid & 15, ty = tid >> 4;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
     const int m0 = blockIdx.y * SBM, n0 = blockIdx.x * SBN;
     const int kbeg = blockIdx.z * a.k_chunk;
     const int kend = min(a.K, kbeg + a.k_chunk);
-    float acc[4][4] = {};
-    for (int k0 = kbeg; k0 < kend; k0 += SBK) {
+
+    v16f acc;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int e = tid + 256 * i;          // 0..1023 over a 64 x 16 slice
-            int row = e >> 4, kk = e & 15;
-            int k = k0 + kk;
-            As[kk][row] = (m0 + row < a.M && k < kend) ? A[(int64_t)(m0 + row) * a.lda + k] : 0.0f;
-            Bs[kk][row] = (n0 + row < a.N && k < kend) ? B[(int64_t)(n0 + row) * a.ldb + k] : 0.0f;
+    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+
+    // each thread moves 2 + 2 vectors of 4 floats per K slice
+    v4f ra[2], rb[2];
+    auto gload = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int v = tid + 256 * i;
+            const int row = v >> 3, kv = (v & 7) * 4;
+            ra[i] = load4<VEC>(A, a.lda, m0 + row, a.M, k0 + kv, kbeg, kend);
+            rb[i] = load4<VEC>(B, a.ldb, n0 + row, a.N, k0 + kv, kbeg, kend);
         }
-        __syncthreads();
+    };
+    auto sstore = [&](int buf) {
 #pragma unroll
-        for (int kk = 0; kk < SBK; ++kk) {
-            float av[4], bv[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) av[i] = As[kk][ty * 4 + i];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) bv[j] = Bs[kk][tx * 4 + j];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
+        for (int i = 0; i < 2; ++i) {
+            const int v = tid + 256 * i;
+            const int row = v >> 3, kv = (v & 7) * 4;
+            *reinterpret_cast<v4f *>(&As[buf][row * SLD + kv]) = ra[i];
+            *reinterpret_cast<v4f *>(&Bs[buf][row * SLD + kv]) = rb[i];
         }
+    };
+
+    const int ntiles = (kend > kbeg) ? (kend - kbeg + SBK - 1) / SBK : 0;
+    if (ntiles > 0) {
+        gload(kbeg);
+        sstore(0);
+    }
+    __syncthreads();
+    const int lrow = lane & 31, lk = (lane >> 5) * 16;
+    for (int t = 0; t < ntiles; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < ntiles) gload(kbeg + (t + 1) * SBK);
+        v4f fa[4], fb[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            fa[q] = *reinterpret_cast<const v4f *>(&As[buf][(wm * 32 + lrow) * SLD + lk + q * 4]);
+            fb[q] = *reinterpret_cast<const v4f *>(&Bs[buf][(wn * 32 + lrow) * SLD + lk + q * 4]);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[q][j], fb[q][j], acc, 0, 0, 0);
+        if (t + 1 < ntiles) sstore(buf ^ 1);
         __syncthreads();
     }
+
+    // lane holds column lane % 32 and rows 8*(r/4) + 4*(lane/32) + r%4, r = 0..15, of its block
+    const float *bias = reinterpret_cast<const float *>(a.bias);
+    const int col = n0 + wn * 32 + lrow;
+    if (col >= a.N) return;
+    const float bv = (bias && blockIdx.z == 0) ? bias[col] : 0.0f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        if (row >= a.M) continue;
+        const float v = acc[r] + bv;
+        if (a.ws) {
+            a.ws[((int64_t)blockIdx.z * a.M + row) * a.N + col] = v;
+        } else {
+            float *c = reinterpret_cast<float *>(a.C) + (int64_t)row * a.ldc + col;
+            *c = a.accumulate ? (*c + v) : v;
+        }
+    }
+}
+
+// The same contraction for results of few tiles (the per-time-step products of the fp32 mode): a
+// 32x32 tile per workgroup and 128-deep K slices (few workgroups, so what a launch costs is the
+// chain of load latencies: four vectors per thread and operand are in flight at a time); the four
+// wavefronts each contract a quarter of every slice (k = 32 w + 16 q + j for wavefront w, lane
+// half q, MFMA j) and their partial blocks are added through LDS.
+constexpr int SSK = 128, SSLD = SSK + 4;
+template <bool VEC>
+__global__ __launch_bounds__(256) void gemm_nt_f32_small_kernel(KernArgs a) {
+    __shared__ __attribute__((aligned(16))) float As[2][32 * SSLD];
+    __shared__ __attribute__((aligned(16))) float Bs[2][32 * SSLD];
+    __shared__ float red[4][16 * 64];
+    const float *A = reinterpret_cast<const float *>(a.A);
+    const float *B = reinterpret_cast<const float *>(a.B);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+    const int kbeg = blockIdx.z * a.k_chunk;
+    const int kend = min(a.K, kbeg + a.k_chunk);
+
+    v16f acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+
+    v4f ra[4], rb[4];
+    auto gload = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int v = tid + 256 * i;
+            const int row = v >> 5, kv = (v & 31) * 4;
+            ra[i] = load4<VEC>(A, a.lda, m0 + row, a.M, k0 + kv, kbeg, kend);
+            rb[i] = load4<VEC>(B, a.ldb, n0 + row, a.N, k0 + kv, kbeg, kend);
+        }
+    };
+    auto sstore = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int v = tid + 256 * i;
+            const int row = v >> 5, kv = (v & 31) * 4;
+            *reinterpret_cast<v4f *>(&As[buf][row * SSLD + kv]) = ra[i];
+            *reinterpret_cast<v4f *>(&Bs[buf][row * SSLD + kv]) = rb[i];
+        }
+    };
+
+    const int ntiles = (kend > kbeg) ? (kend - kbeg + SSK - 1) / SSK : 0;
+    if (ntiles > 0) {
+        gload(kbeg);
+        sstore(0);
+    }
+    __syncthreads();
+    const int lrow = lane & 31, lk = wave * 32 + (lane >> 5) * 16;
+    for (int t = 0; t < ntiles; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < ntiles) gload(kbeg + (t + 1) * SSK);
+        v4f fa[4], fb[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            fa[q] = *reinterpret_cast<const v4f *>(&As[buf][lrow * SSLD + lk + q * 4]);
+            fb[q] = *reinterpret_cast<const v4f *>(&Bs[buf][lrow * SSLD + lk + q * 4]);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[q][j], fb[q][j], acc, 0, 0, 0);
+        if (t + 1 < ntiles) sstore(buf ^ 1);
+        __syncthreads();
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) red[wave][r * 64 + lane] = acc[r];
+    __syncthreads();
+
+    // element (r, l) of a block: column l % 32, row 8*(r/4) + 4*(l/32) + r%4
     const float *bias = reinterpret_cast<const float *>(a.bias);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int row = m0 + ty * 4 + i;
-        if (row >= a.M) continue;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int col = n0 + tx * 4 + j;
-            if (col >= a.N) continue;
-            float v = acc[i][j] + ((bias && blockIdx.z == 0) ? bias[col] : 0.0f);
-            if (a.ws) {
-                a.ws[((int64_t)blockIdx.z * a.M + row) * a.N + col] = v;
-            } else {
-                float *c = reinterpret_cast<float *>(a.C) + (int64_t)row * a.ldc + col;
-                *c = a.accumulate ? (*c + v) : v;
-            }
+        const int e = tid + 256 * i;
+        const int r = e >> 6, l = e & 63;
+        const int row = m0 + (r >> 2) * 8 + (l >> 5) * 4 + (r & 3), col = n0 + (l & 31);
+        if (row >= a.M || col >= a.N) continue;
+        float v = (red[0][e] + red[1][e]) + (red[2][e] + red[3][e]);
+        if (bias && blockIdx.z == 0) v += bias[col];
+        if (a.ws) {
+            a.ws[((int64_t)blockIdx.z * a.M + row) * a.N + col] = v;
+        } else {
+            float *c = reinterpret_cast<float *>(a.C) + (int64_t)row * a.ldc + col;
+            *c = a.accumulate ? (*c + v) : v;
         }
     }
 }
@@ -638,11 +781,16 @@ static double gemm_algorithmic_bytes(const Args &g) {
 template <typename T>
 int launch(const GemmArgs &g, hipStream_t stream) {
     constexpr bool is_f32 = sizeof(T) == 4;
-    const bool aligned = !is_f32 && g.K % 8 == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 && ((uintptr_t)g.A % 16 == 0) &&
+    constexpr int vec = 16 / (int)sizeof(T);     // elements per 16-byte load
+    const bool aligned = g.K % vec == 0 && g.lda % vec == 0 && g.ldb % vec == 0 && ((uintptr_t)g.A % 16 == 0) &&
                          ((uintptr_t)g.B % 16 == 0);
-    const bool big = aligned && fits_32bit(g.M, g.lda, g.N, g.ldb) &&
+    const bool big = !is_f32 && aligned && fits_32bit(g.M, g.lda, g.N, g.ldb) &&
                      use_big_tiles(is_f32 ? LSTM_DTYPE_FP32 : LSTM_DTYPE_FP16, g.M, g.N);
-    const int bm = is_f32 ? SBM : (big ? GBM : BM), bn = is_f32 ? SBN : (big ? GBN : BN), bk = is_f32 ? SBK : BK;
+    // fp32: 32x32 tiles while 64x64 ones would leave compute units without a workgroup
+    const int asked = (g.splitk_ws && g.splits > 1) ? g.splits : 1;
+    const bool small32 = is_f32 && (int64_t)((g.M + SBM - 1) / SBM) * ((g.N + SBN - 1) / SBN) * asked < 256;
+    const int bm = is_f32 ? (small32 ? 32 : SBM) : (big ? GBM : BM), bn = is_f32 ? (small32 ? 32 : SBN) : (big ? GBN : BN);
+    const int bk = is_f32 ? SBK : BK;
     KernArgs a{};
     a.A = g.A; a.B = g.B; a.C = g.C; a.bias = g.bias;
     a.M = g.M; a.N = g.N; a.K = g.K;
@@ -665,7 +813,15 @@ int launch(const GemmArgs &g, hipStream_t stream) {
     }
     KernelTimer timer(g.kclass, stream, 2.0 * g.M * g.N * g.K, gemm_algorithmic_bytes<T>(g));
     if constexpr (is_f32) {
-        hipLaunchKernelGGL(gemm_nt_f32_kernel, dim3(tiles_n, tiles_m, splits), dim3(256), 0, stream, a);
+        if (small32 && a.vec_ok) {
+            hipLaunchKernelGGL(gemm_nt_f32_small_kernel<true>, dim3(tiles_n, tiles_m, splits), dim3(256), 0, stream, a);
+        } else if (small32) {
+            hipLaunchKernelGGL(gemm_nt_f32_small_kernel<false>, dim3(tiles_n, tiles_m, splits), dim3(256), 0, stream, a);
+        } else if (a.vec_ok) {
+            hipLaunchKernelGGL(gemm_nt_f32_kernel<true>, dim3(tiles_n, tiles_m, splits), dim3(256), 0, stream, a);
+        } else {
+            hipLaunchKernelGGL(gemm_nt_f32_kernel<false>, dim3(tiles_n, tiles_m, splits), dim3(256), 0, stream, a);
+        }
     } else {
         if (big) {
             hipLaunchKernelGGL((gemm_mfma_big_kernel<T, false, false, false, false>), dim3(tiles_m * tiles_n, 1, splits), dim3(GTHREADS), 0,
