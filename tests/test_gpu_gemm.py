@@ -1,7 +1,8 @@
 """The whole-sequence GEMM kernels on their own, through the C ABI's diagnostic entry point,
 against a float64 matmul on the same fp16/bf16-rounded operands: every operand layout the
 training step uses (row-major K-contiguous, row-major transposed, 64x64-blocked in three role
-combinations), shapes with several tiles and ragged edges, and split-K."""
+combinations), shapes with several tiles and ragged edges, and split-K; the fp32
+mode's kernel against the same matmul."""
 import numpy as np
 import pytest
 
@@ -52,6 +53,32 @@ def test_gemm_layouts_match_matmul(hip, layout, dtype):
             tol = (2.0 ** -8 if dtype == "bf16" else 2.0 ** -11) * np.abs(ref) + 1e-3 * np.sqrt(K) * 2.0 ** -9
             assert np.all(np.isfinite(got))
             assert np.all(np.abs(got - ref) <= tol + 1e-6), float(np.max(np.abs(got - ref) - tol))
+
+
+F32_SHAPES = [(128, 800, 200), (100, 37, 9), (1100, 1030, 77), (320, 200, 4096), (2048, 1024, 64), (64, 64, 3), (33, 65, 132)]
+
+
+def test_gemm_fp32_matches_matmul(hip):
+    """The all-fp32 baseline mode's GEMM (fp32 MFMA): both tile sizes, 16-byte and element-wise loads
+    (K % 4 != 0), ragged edges, split-K; error within the fp32 summation bound K u sum|a||b|."""
+    import torch
+    dev = torch.device("cuda:0")
+    for (M, N, K) in F32_SHAPES:
+        for splits in (1, 3):
+            print(f"[case] gemm fp32 M={M} N={N} K={K} splits={splits}", flush=True)
+            gen = torch.Generator(device="cuda").manual_seed(M + N + K)
+            A = torch.randn((M, K), device=dev, generator=gen)
+            B = torch.randn((N, K), device=dev, generator=gen)
+            A64 = A.double().cpu().numpy(); B64 = B.double().cpu().numpy()
+            ref = A64 @ B64.T
+            C = torch.full((M, N), float("nan"), dtype=torch.float32, device=dev)
+            ws = torch.empty(splits * M * N, device=dev) if splits > 1 else None
+            hip.lstm_debug_gemm(0, 0, M, N, K, A, B, C, ws, splits)
+            torch.cuda.synchronize()
+            got = C.double().cpu().numpy()
+            tol = 2.0 * (K + 4) * 2.0 ** -24 * (np.abs(A64) @ np.abs(B64).T)
+            assert np.all(np.isfinite(got))
+            assert np.all(np.abs(got - ref) <= tol), float(np.max(np.abs(got - ref) - tol))
 
 
 def test_blocked_packing_layout(hip):
