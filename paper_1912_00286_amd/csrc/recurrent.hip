@@ -231,9 +231,20 @@ __device__ __forceinline__ void forward_cell(const FwdArgs &a, int tile, int rot
         }
     };
     auto finish_group = [&](int mb, int rh, const float (&pre)[8][NBLK], const float (&axv)[8][4], const float (&cprev)[8]) {
+        if (j0 + 32 >= H && j0 + 32 < a.nkc * SK) {
+            // the last block of 32 units ends in the first half of a 64-column chunk: nobody owns the second
+            // half, so this workgroup clears it (column j + 32 lies in the same chunk as column j)
+#pragma unroll
+            for (int rr = 0; rr < 8; ++rr) {
+                const int r = rh + rr;
+                const int rl = mb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                if (m0 + rl < a.B) hpk[frag_offset(rl, (j & 63) + 32, 2)] = Lp<T>::from_f(0.0f);
+            }
+        }
         if (j >= H) {
-            // padding columns of the packed h_t (up to the next multiple of 64) are written as zeros, so
-            // that a slot never touched before can serve as the next step's operand
+            // padding columns of the packed h_t inside this block of 32 are written as zeros (with the half
+            // chunk above: every column up to the next multiple of 64), so that a slot never touched before can
+            // serve as the next step's operand
             if (j < a.nkc * SK) {
 #pragma unroll
                 for (int rr = 0; rr < 8; ++rr) {
