@@ -84,3 +84,53 @@ def test_deep_stack(hip, dtype, L):
     got = pu.run_gpu_step(w)
     want = pu.run_oracle_step(w)
     pu.assert_step_close(w, got, want)
+
+
+STATE_CASES = [
+    ("narrow", 2, 24, 200, 4, 128, "fp16"),
+    ("narrow_ragged_bf16", 3, 9, 104, 4, 100, "bf16"),
+    ("wide", 1, 40, 1024, 3, 128, "fp16"),
+    ("rows2048", 2, 64, 200, 3, 2048, "fp16"),
+    ("rows1024_h520", 1, 8, 520, 3, 1024, "fp16"),
+    ("odd_sizes", 2, 5, 33, 4, 17, "fp16"),
+    ("fp32", 2, 5, 72, 4, 70, "fp32"),
+]
+
+
+@pytest.mark.parametrize("spec", STATE_CASES, ids=[c[0] for c in STATE_CASES])
+def test_nonzero_initial_state(hip, spec):
+    """A chunk that starts from a given (h_0, c_0) on every kernel family: loss, gradients and the state handed
+    on, (h_T, c_T), against the oracle started from the same state.  The workspaces hold NaN bytes before the call."""
+    import torch
+    name, L, I, H, T, B, dtype = spec
+    w = wl.Workload(f"state_{name}", L, I, H, T, B, dtype, wl.HEAD_STEP_BCE, loss_scale=1.0 if dtype != "fp16" else 512.0,
+                    target_p=0.4, data_seed=41, weight_seed=42)
+    print(f"[case] {w.name}: L={L} I={I} H={H} T={T} B={B} {dtype}", flush=True)
+    master0, xs, ys = pu.inputs_for(w)
+    dev = torch.device("cuda:0")
+    ts = pu.make_step(w, master0, dev)
+    for buf in list(ts.reserves) + list(ts.scratches):
+        buf.fill_(255)
+    rng = np.random.default_rng(43)
+    h0 = torch.from_numpy(rng.uniform(-0.9, 0.9, (L, B, H)).astype(np.float32)).to(ts.lp_dtype).to(dev)   # storage-rounded
+    c0 = torch.from_numpy(rng.normal(0.0, 1.0, (L, B, H)).astype(np.float32)).to(dev)
+    hT = torch.full((L, B, H), float("nan"), dtype=ts.lp_dtype, device=dev)
+    cT = torch.full((L, B, H), float("nan"), device=dev)
+    x = torch.from_numpy(xs[0]).to(ts.lp_dtype).to(dev)
+    y = torch.from_numpy(ys[0]).to(dev)
+    hip.lstm_forward(ts.cfg, ts.params_lp, x, y, h0, c0, ts.reserve, ts.scratch, ts.losses[0:1], hT, cT)
+    hip.lstm_backward(ts.cfg, ts.params_lp, x, y, ts.reserve, ts.scratch, ts.loss_scale, ts.grads[0])
+    torch.cuda.synchronize()
+    shapes = pu.oracle_shapes(w)
+    params = orc.unflatten(ts.params_lp.double().cpu().numpy(), shapes)
+    loss, cache = orc.forward(params, L, x.double().cpu().numpy(), ys[0], w.head, h0.double().cpu().numpy(), c0.double().cpu().numpy())
+    g = orc.flatten(orc.backward(params, L, cache, 1.0), shapes)
+    assert abs(float(ts.losses[0].item()) - loss) <= pu.LOSS_RTOL * abs(loss)
+    got = ts.grads[0].double().cpu().numpy() / w.loss_scale
+    assert np.all(np.isfinite(got))
+    pu.assert_grads_close(got, g, shapes, pu.GRAD_RTOL[dtype], "chunk with initial state")
+    h_ref = np.stack([cache["layers"][l]["h"][-1] for l in range(L)])
+    c_ref = np.stack([cache["layers"][l]["c"][-1] for l in range(L)])
+    atol = {"fp16": 6e-3, "bf16": 4e-2, "fp32": 1e-5}[dtype]
+    np.testing.assert_allclose(hT.double().cpu().numpy(), h_ref, atol=atol)
+    np.testing.assert_allclose(cT.double().cpu().numpy(), c_ref, atol=atol * 4)
