@@ -25,27 +25,37 @@ def _assert_same(a, b, what):
         assert torch.equal(a[k], b[k]), f"{what}: {k} differs between eager and graph replay"
 
 
-@pytest.mark.parametrize("name", ["jet", "text"])
+@pytest.mark.parametrize("name", ["jet", "text", "rows2048", "wide1024", "stacked"])
 def test_graph_replay_matches_eager(name):
     import torch
-    w = wl.CONFIGS[name]
+    batched = False
     if name == "jet":
-        w = w.with_(seq_len=24, n_workers=2, dynamic_scale=True, loss_scale=4096.0)
-    else:
-        w = w.with_(seq_len=40)
+        w = wl.CONFIGS[name].with_(seq_len=24, n_workers=2, dynamic_scale=True, loss_scale=4096.0)
+    elif name == "text":
+        w = wl.CONFIGS[name].with_(seq_len=40)
+    elif name == "rows2048":        # thousands of rows per step: self-projecting forward cells, one-launch BPTT steps
+        w = wl.Workload(name, 2, 64, 200, 6, 2048, "fp16", wl.HEAD_STEP_BCE, loss_scale=1024.0, target_p=0.4, data_seed=51, weight_seed=52)
+    elif name == "wide1024":        # wide layers: two launches per BPTT step
+        w = wl.Workload(name, 2, 40, 1024, 5, 128, "bf16", wl.HEAD_STEP_MSE, target_kind="normal", data_seed=53, weight_seed=54)
+    else:                           # several workers stacked into one call per direction
+        w = wl.Workload(name, 2, 64, 200, 6, 128, "fp16", wl.HEAD_STEP_BCE, n_workers=4, loss_scale=1024.0, target_p=0.4,
+                        data_seed=55, weight_seed=56)
+        batched = True
     master0, xs, ys = pu.inputs_for(w)
     n_steps = 4
 
-    eager = pu.make_step(w, master0)
+    eager = pu.make_step(w, master0, batched=batched)
     dx, dy = pu.device_batches(w, xs, ys, eager.lp_dtype, eager.dev)
+    if batched:
+        dx, dy = eager.stack_workers(dx, dy)
     ref = []
     for k in range(n_steps):
         eager.step(dx, dy, pu.lr_for(w, k))
         ref.append(_snapshot(eager))
 
-    graph = pu.make_step(w, master0)
-    gx = [t.clone() for t in dx]
-    gy = [t.clone() for t in dy]
+    graph = pu.make_step(w, master0, batched=batched)
+    gx = dx.clone() if batched else [t.clone() for t in dx]
+    gy = dy.clone() if batched else [t.clone() for t in dy]
     graph.capture(gx, gy)
     # capture runs nothing: the state is still the initial one
     assert torch.equal(graph.master, torch.as_tensor(master0, dtype=torch.float32, device=graph.dev))
