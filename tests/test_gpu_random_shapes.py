@@ -80,3 +80,58 @@ def test_random_narrow_configuration(seed):
     got = pu.run_gpu_step(w)
     want = pu.run_oracle_step(w)
     pu.assert_step_close(w, got, want)
+
+
+def _draw_wide(seed):
+    """Layers too wide for the one-launch cells (H > 768): the per-step kernels with the contraction split by
+    gate over workgroups, ragged widths and batches."""
+    rng = np.random.default_rng(31000 + seed)
+    dtype = ["fp16", "bf16"][int(rng.integers(0, 2))]
+    L = int(rng.integers(1, 3))
+    H = int(rng.choice([776, 800, 1024, 1032, 904]))
+    B = int(rng.choice([1, 17, 64, 100, 128, 200, 256]))
+    T = int(rng.integers(1, 4))
+    I = int(rng.choice([3, 8, 24, 64, 130]))
+    head = int(rng.choice([wl.HEAD_STEP_BCE, wl.HEAD_LAST_BCE, wl.HEAD_STEP_MSE]))
+    kw = dict(target_kind="normal") if head == wl.HEAD_STEP_MSE else dict(target_p=0.4)
+    if dtype == "bf16":
+        L = 1; B = max(B, 64); T = max(T, 3)
+    scale = 1.0 if dtype != "fp16" else float(rng.choice([64.0, 1024.0]))
+    return wl.Workload(f"wide{seed}", L, I, H, T, B, dtype, head, loss_scale=scale, data_seed=2700 + seed, weight_seed=2800 + seed, **kw)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_wide_configuration(seed):
+    w = _draw_wide(seed)
+    print(f"[case] wide{seed}: L={w.num_layers} I={w.input_dim} H={w.hidden} T={w.seq_len} B={w.batch} {w.dtype} head={w.head}", flush=True)
+    got = pu.run_gpu_step(w)
+    want = pu.run_oracle_step(w)
+    pu.assert_step_close(w, got, want)
+
+
+def _draw_many_rows(seed):
+    """A thousand to eight thousand rows per time step (what stacked workers look like to the kernels): the
+    single-wavefront forward cells, cells that project their own input, the one-launch BPTT step, widths whose
+    padding to whole tiles nobody owns, and the fp32 mode at such batches."""
+    rng = np.random.default_rng(32000 + seed)
+    dtype = ["fp16", "bf16", "fp32"][int(rng.integers(0, 3))]
+    L = int(rng.integers(1, 4))
+    H = int(rng.choice([8, 40, 100, 200, 264, 520]))
+    B = int(rng.choice([960, 1000, 1024, 2048, 4100, 8192]))
+    T = int(rng.integers(1, 4))
+    I = int(rng.choice([3, 8, 24, 64, 200]))
+    head = int(rng.choice([wl.HEAD_STEP_BCE, wl.HEAD_LAST_BCE, wl.HEAD_STEP_MSE]))
+    kw = dict(target_kind="normal") if head == wl.HEAD_STEP_MSE else dict(target_p=0.4)
+    if dtype == "bf16":
+        L = min(L, 2); T = max(T, 3); H = max(H, 40)
+    scale = 1.0 if dtype != "fp16" else float(rng.choice([64.0, 1024.0]))
+    return wl.Workload(f"rows{seed}", L, I, H, T, B, dtype, head, loss_scale=scale, data_seed=3700 + seed, weight_seed=3800 + seed, **kw)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_many_rows_configuration(seed):
+    w = _draw_many_rows(seed)
+    print(f"[case] rows{seed}: L={w.num_layers} I={w.input_dim} H={w.hidden} T={w.seq_len} B={w.batch} {w.dtype} head={w.head}", flush=True)
+    got = pu.run_gpu_step(w)
+    want = pu.run_oracle_step(w)
+    pu.assert_step_close(w, got, want)
