@@ -153,6 +153,11 @@ int make_plan(const lstm_config *c, Plan &p) {
     p.r_fc = r; if (p.F > 0) r += align_up(TB * p.F * p.es);
     // 64x64-blocked copies for the large-tile GEMMs: time slots must start on a block row
     p.blk = p.dtype != LSTM_DTYPE_FP32 && p.B % 64 == 0 && gemm_blocked_supported(p.dtype, (int)TB, p.G);
+    // the blocked kernels address an operand with 32-bit element offsets: beyond that the row-major path runs
+    const size_t blk_limit = (size_t)1 << 31;
+    if (p.blk && (blocked_elems((int)TB, p.G) >= blk_limit || blocked_elems((int)(TB + p.B), p.H) >= blk_limit ||
+                  blocked_elems((int)TB, p.in_dim[0]) >= blk_limit))
+        p.blk = false;
     p.r_hblk.assign(p.L, 0);
     if (p.blk) {
         p.h_ncb = (p.H + 63) / 64;
@@ -282,7 +287,7 @@ int make_plan(const lstm_config *c, Plan &p) {
     }
     p.scratch_bytes = s;
     if (p.W > 1 && !p.blk) {
-        set_error("config: workers=%d needs shapes the blocked GEMM path handles (T*W*B >= 192, 4H >= 192)", p.W);
+        set_error("config: workers=%d needs shapes the blocked GEMM path handles (T*W*B >= 192, 4H >= 192, T*W*B*4H < 2^31)", p.W);
         return LSTM_ERR_UNSUPPORTED;
     }
     return LSTM_OK;

@@ -117,3 +117,44 @@ def test_many_steps_schedule_and_trajectory(hip):
         bound = pu.GRAD_RTOL["fp16"] * np.max(np.abs(H_ref)) + 1.2e-7 * np.abs(W_ref) + 1e-12
         assert np.all(np.abs(ts.master.double().cpu().numpy() - W_ref) <= bound), f"step {k}"
     assert int(ts.good_steps.item()) == 8 and float(ts.loss_scale.item()) == 1024.0
+
+
+@pytest.mark.parametrize("spec", [(1, 64, 520, 128, 8192, "fp16"), (1, 24, 1032, 260, 2048, "bf16")], ids=["rows8192_h520", "rows2048_h1032"])
+def test_tensors_beyond_2_31_elements(hip, spec):
+    """T*B*4H above 2^31 elements (the saved gates, dA): offsets must be 64-bit wherever such a tensor is addressed,
+    and the GEMM forms with 32-bit offsets must not be chosen.  No oracle finishes this size; the property used is
+    that batch rows do not interact: loss and gradients of the whole batch are the means of those of its two halves,
+    run as two calls of half the size (same kernels, tensors below 2^31 elements)."""
+    import torch
+    L, I, H, T, B, dtype = spec
+    w = wl.Workload("big", L, I, H, T, B, dtype, wl.HEAD_STEP_BCE, loss_scale=1024.0 if dtype == "fp16" else 1.0, target_p=0.4,
+                    data_seed=61, weight_seed=62)
+    assert T * B * 4 * H > 2 ** 31
+    master0, xs, ys = pu.inputs_for(w)
+
+    def run(wk, x, y):
+        ts = pu.make_step(wk, master0)
+        for buf in list(ts.reserves) + list(ts.scratches):
+            buf.fill_(255)
+        dx = torch.from_numpy(np.ascontiguousarray(x)).to(ts.lp_dtype).to(ts.dev)
+        dy = torch.from_numpy(np.ascontiguousarray(y)).to(ts.dev)
+        hip.lstm_forward(ts.cfg, ts.params_lp, dx, dy, None, None, ts.reserve, ts.scratch, ts.losses[0:1])
+        hip.lstm_backward(ts.cfg, ts.params_lp, dx, dy, ts.reserve, ts.scratch, ts.loss_scale, ts.grads[0])
+        torch.cuda.synchronize()
+        out = float(ts.losses[0].item()), ts.grads[0].double().cpu().numpy() / wk.loss_scale
+        del ts, dx, dy
+        torch.cuda.empty_cache()
+        return out
+
+    print(f"[case] whole batch L={L} H={H} T={T} B={B} {dtype}", flush=True)
+    loss, g = run(w, xs[0], ys[0])
+    half = w.with_(batch=B // 2)
+    print("[case] first half", flush=True)
+    l1, g1 = run(half, xs[0][:, :B // 2], ys[0][:, :B // 2])
+    print("[case] second half", flush=True)
+    l2, g2 = run(half, xs[0][:, B // 2:], ys[0][:, B // 2:])
+    assert abs(loss - 0.5 * (l1 + l2)) <= 1e-5 * abs(loss)
+    assert np.all(np.isfinite(g))
+    # the halves seed their BPTT with twice the per-sample gradient, so fewer of their 16-bit intermediates are
+    # subnormal: the two sides differ by storage rounding, hence the 16-bit tolerance
+    pu.assert_grads_close(g, 0.5 * (g1 + g2), pu.oracle_shapes(w), pu.GRAD_RTOL[dtype], "whole batch against the mean of its halves")
