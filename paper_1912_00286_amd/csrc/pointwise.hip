@@ -176,7 +176,7 @@ __global__ __launch_bounds__(256) void colsum_partial_vec_kernel(const T *in, in
     __syncthreads();
     for (int i = threadIdx.x; i < 512; i += 256) {
         const int l = i >> 3, e = i & 7;
-        if (blockIdx.x * 512 + i < C)
+        if ((int)blockIdx.x * 512 + i < C)
             partial[((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * C + blockIdx.x * 512 + i] =
                 (red[0][l][e] + red[1][l][e]) + (red[2][l][e] + red[3][l][e]);
     }
