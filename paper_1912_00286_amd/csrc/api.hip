@@ -508,7 +508,19 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
         }
         if (p.wf) continue;                                   // the time steps follow below, diagonal by diagonal
         LSTM_TRY(setup.flush(p.dtype, p.B, p.H, s));
-        for (int t = 0; t < p.T; ++t) {
+        const bool rows = fused && p.proj && rows_forward_supported(p.dtype, p.B, p.H, p.in_dim[l]);
+        if (rows) {
+            // every workgroup walks its 32 rows through all T steps: one launch for the layer
+            RowsForward r{};
+            r.hseq = hseq; r.slot_h = (int64_t)(p.pj_slot_h / es);
+            r.xseq = l == 0 ? at(scratch, p.s_pj_xseq) : at(scratch, p.s_pj_hseq[(l - 1) & 1]) + p.pj_slot_h;
+            r.slot_x = (int64_t)((l == 0 ? p.pj_slot_x : p.pj_slot_h) / es);
+            r.Upk = upk; r.Wpk = at(scratch, p.s_pj_wpk); r.bias = b;
+            r.c_state = c_state; r.gates = gates; r.c_out = cs + (size_t)BH * es; r.h_out = hs + (size_t)BH * es;
+            r.h_blk = hblk ? hblk + slot : nullptr; r.slot_blk = (int64_t)(slot / es); r.blk_ncb = p.h_ncb;
+            LSTM_TRY(rows_forward(p.dtype, r, p.in_dim[l], p.T, p.B, p.H, s));
+        }
+        for (int t = rows ? p.T : 0; t < p.T; ++t) {
             char *a_t = ax + (size_t)t * p.B * p.G * axs;
             if (fused && p.proj) {
                 const char *xin = l == 0 ? at(scratch, p.s_pj_xseq) + (size_t)t * p.pj_slot_x

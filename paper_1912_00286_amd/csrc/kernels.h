@@ -100,6 +100,21 @@ int step_forward_fused(int dtype, const void *hpk_prev, const void *Upk, const v
 // whole-sequence projection is bound by writing and re-reading its [T*B, 4H] result): W packed for an
 // input width K, a sequence [T, B, K] packed step by step (slot stride in elements).
 bool recurrent_wide_shape(int B, int H);
+// a layer's whole forward recurrence in one launch; operands as step_forward_proj takes them, per time slot
+struct RowsForward {
+    const void *hseq;          // packed h slots: slot 0 = h_0 (in), slot t + 1 = h_t (out)
+    const void *xseq;          // packed input slots
+    int64_t slot_h, slot_x;    // elements per slot
+    const void *Upk, *Wpk, *bias;
+    float *c_state;            // [B,H]: c_0 in, c_T out
+    void *gates;               // [T][B,4H]
+    void *c_out, *h_out;       // step 0's [B,H] (slot 1 of the saved sequences)
+    void *h_blk;               // step 0's blocked slot, or null
+    int64_t slot_blk;
+    int blk_ncb;
+};
+bool rows_forward_supported(int dtype, int B, int H, int in_width);
+int rows_forward(int dtype, const RowsForward &x, int in_width, int T, int B, int H, hipStream_t s);
 int pack_w_forward(int dtype, const void *W, void *Wpk, int H, int K, hipStream_t s);
 int pack_rows_seq(int dtype, const void *x, void *xpk, int T_steps, int B, int K, int64_t dst_stride, hipStream_t s);
 int step_forward_proj(int dtype, const void *hpk_prev, const void *Upk, const void *xpk, const void *Wpk, const void *bias, int in_width,

@@ -327,6 +327,153 @@ __global__ __launch_bounds__(256) void lstm_wave_forward_kernel(WaveFwdArgs w) {
     forward_cell<T, false>(w.cell[c], (int)blockIdx.x - c * w.wgs_per_cell, (int)blockIdx.x);
 }
 
+// ---------------------------------------------------------------- a layer's whole forward recurrence in one launch
+// Batch rows never interact, so a workgroup that owns 32 rows and ALL hidden units can walk them through the T
+// time steps on its own: no launch per step and nothing crosses workgroups.  Per step it contracts its rows of
+// h_{t-1} (kept in LDS in fragment order, written by its own epilogue one step earlier) with the packed U and its
+// rows of x_t (packed input sequence, from memory) with the packed W, one block of 32 units x 4 gates at a time
+// (eight wavefronts, one per block), keeps c_t in registers in the accumulator layout, and writes the saved
+// gates, c_t, h_t (row-major, packed for the layer above, blocked for the weight-gradient GEMMs) as it goes.
+// Workgroups drift apart in time, so the products of one run under the stores of another, which the lock-step
+// grid of a per-step launch cannot do.  Used with thousands of rows per step (stacked workers) and H <= 256.
+struct RowsFwdArgs {
+    const void *hseq;      // packed h slots [T+1][n_mt][nkc][64][64]: slot 0 = h_0 (in), slot t + 1 = h_t (out)
+    const void *xseq;      // packed input slots [T][n_mt][nkc2][64][64]
+    int64_t slot_h, slot_x;   // elements per slot
+    const void *Upk, *Wpk, *bias;
+    float *c_state;        // fp32 [B,H]: c_0 in, c_T out
+    void *gates;           // lp [T][B,4H] out
+    void *c_out, *h_out;   // lp [B,H] of step 0 (slot 1 of the saved sequences), the steps follow at B*H
+    void *h_blk;           // blocked h of step 0 (slot 1), or null
+    int64_t slot_blk;      // elements per time slot of h_blk
+    int blk_ncb, T, B, H, nkc, nkc2;
+};
+template <typename T>
+__global__ __launch_bounds__(512) void lstm_rows_forward_kernel(RowsFwdArgs a) {
+    constexpr int HCH = 32 * SK;                       // elements of a 32-row chunk in LDS: [ks][lane][8]
+    __shared__ __attribute__((aligned(16))) uint16_t hbuf[2][4 * HCH];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int hb = __builtin_amdgcn_readfirstlane(tid >> 6);      // wavefront = block of 32 units x 4 gates
+    const int mt = blockIdx.x >> 1, mb = blockIdx.x & 1;
+    const int r0 = mt * TM + mb * 32;
+    if (r0 >= a.B) return;                             // the second half of a ragged last tile
+    const int H = a.H, G = 4 * a.H, n_hb = (H + 31) / 32;
+    const int nq = 2 * (a.nkc + a.nkc2);               // half chunks (two k-steps of 16) of the step's two products
+    // h_0 of these rows: chunk c, k-step ks of the packed 64-row tile is fragment (c*8 + ks*2 + mb)
+    {
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(a.hseq) + (int64_t)mt * a.nkc * A_CHUNK);
+        u32x4 *dst = reinterpret_cast<u32x4 *>(hbuf[0]);
+        for (int v = tid; v < a.nkc * 256; v += 512) dst[v] = src[((v >> 8) * 8 + ((v >> 6) & 3) * 2 + mb) * 64 + (v & 63)];
+    }
+    const bool active = hb < n_hb;                     // uniform over the wavefront
+    const int col = lane & 31, rsub = (lane >> 5) * 4;
+    const int j = hb * 32 + col, jc = min(j, H - 1);
+    float creg[16], breg[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) breg[g] = Lp<T>::to_f(reinterpret_cast<const T *>(a.bias)[g * H + jc]);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int row = min(r0 + (r >> 2) * 8 + rsub + (r & 3), a.B - 1);
+        creg[r] = a.c_state[(int64_t)row * H + jc];
+    }
+    __syncthreads();
+    const int hbc = min(hb, n_hb - 1);
+    const uint16_t *Upk = reinterpret_cast<const uint16_t *>(a.Upk) + (int64_t)hbc * a.nkc * B_CHUNK;
+    const uint16_t *Wpk = reinterpret_cast<const uint16_t *>(a.Wpk) + (int64_t)hbc * a.nkc2 * B_CHUNK;
+    const bool unit = j < H;
+    const bool pad_half = hb * 32 + 32 >= H && hb * 32 + 32 < a.nkc * SK;   // nobody owns the chunk's second half
+    const int kc = min(j, a.nkc * SK - 1) >> 6, kk = j & 63;
+    for (int t = 0; t < a.T; ++t) {
+        if (active) {
+            const u32x4 *hA = reinterpret_cast<const u32x4 *>(hbuf[t & 1]);
+            T *hN = reinterpret_cast<T *>(hbuf[(t + 1) & 1]);
+            const u32x4 *xA = reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(a.xseq) + (int64_t)t * a.slot_x + (int64_t)mt * a.nkc2 * A_CHUNK);
+            v16f acc[NBLK];
+#pragma unroll
+            for (int nb = 0; nb < NBLK; ++nb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[nb][r] = 0.0f;
+            // half-chunk list: the recurrent product (h from LDS, U), then the input projection (x from memory, W)
+            auto load = [&](u32x4 (&ra)[2], u32x4 (&rb)[8], int q) {
+                const int c = q >> 1, hf = q & 1;
+                const bool rec = c < a.nkc;
+                const u32x4 *b = reinterpret_cast<const u32x4 *>(rec ? Upk + (int64_t)c * B_CHUNK : Wpk + (int64_t)(c - a.nkc) * B_CHUNK) + hf * 512;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) rb[i] = b[lane + 64 * i];
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2)
+                    ra[k2] = rec ? hA[(c * 4 + hf * 2 + k2) * 64 + lane] : xA[((c - a.nkc) * 8 + (hf * 2 + k2) * 2 + mb) * 64 + lane];
+            };
+            auto mm = [&](const u32x4 (&ra)[2], const u32x4 (&rb)[8]) {
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+                    for (int nb = 0; nb < NBLK; ++nb) acc[nb] = Lp<T>::mfma(ra[k2], rb[k2 * NBLK + nb], acc[nb]);
+            };
+            u32x4 ra0[2], ra1[2], rb0[8], rb1[8];
+            load(ra0, rb0, 0);
+            load(ra1, rb1, 1);                         // nq >= 4: at least one chunk per product
+            int s = 0;
+            for (; s + 4 <= nq; s += 2) {
+                mm(ra0, rb0);
+                load(ra0, rb0, s + 2);
+                mm(ra1, rb1);
+                load(ra1, rb1, s + 3);
+            }
+            mm(ra0, rb0);                              // nq is even: two half chunks are left
+            mm(ra1, rb1);
+            // gate arithmetic in the accumulator layout: this lane has the four gates of unit j for 16 rows.
+            // Row r of the accumulator is tile row rsub + crow(r), crow a compile-time constant: every address
+            // below is one per-lane base plus a constant (or uniform) multiple of crow, so that sixteen rows'
+            // worth of addresses need not be kept in registers across the time loop.
+            const int row0 = r0 + rsub;
+            T *hpk = const_cast<T *>(reinterpret_cast<const T *>(a.hseq)) + (int64_t)(t + 1) * a.slot_h + ((int64_t)mt * a.nkc + kc) * A_CHUNK +
+                     frag_offset(mb * 32 + rsub, kk, 2);
+            T *gates = reinterpret_cast<T *>(a.gates) + (int64_t)t * a.B * G + (int64_t)row0 * G + j;
+            T *c_out = reinterpret_cast<T *>(a.c_out) + (int64_t)t * a.B * H + (int64_t)row0 * H + j;
+            T *h_out = reinterpret_cast<T *>(a.h_out) + (int64_t)t * a.B * H + (int64_t)row0 * H + j;
+            T *h_blk = a.h_blk ? reinterpret_cast<T *>(a.h_blk) + (int64_t)t * a.slot_blk + ((int64_t)mt * a.blk_ncb + (j >> 6)) * 4096 +
+                                     (mb * 32 + rsub) * 64 + kk
+                               : nullptr;
+            T *hl = hN + (kc * 4 + (kk >> 4)) * 512 + (((kk >> 3) & 1) * 32 + rsub) * 8 + (kk & 7);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int crow = (r >> 2) * 8 + (r & 3);
+                const float gi = sigmoidf_dev(acc[0][r] + breg[0]);
+                const float gf = sigmoidf_dev(acc[1][r] + breg[1]);
+                const float gg = tanhf_dev(acc[2][r] + breg[2]);
+                const float go = sigmoidf_dev(acc[3][r] + breg[3]);
+                const float c = gf * creg[r] + gi * gg;
+                creg[r] = c;
+                const T h = unit ? Lp<T>::from_f(go * tanhf_dev(c)) : Lp<T>::from_f(0.0f);
+                // next step's operand (zero in the padding columns up to the next multiple of 64)
+                hl[crow * 8] = h;
+                if (pad_half) hl[crow * 8 + 2 * 512] = Lp<T>::from_f(0.0f);         // column j + 32: two k-steps of 16 further
+                if (row0 + crow >= a.B) continue;
+                hpk[crow * 8] = h;
+                if (pad_half) hpk[crow * 8 + 2 * 2 * 512] = Lp<T>::from_f(0.0f);    // same, in the 64-row chunk (two blocks per k-step)
+                if (!unit) continue;
+                T *gr = gates + crow * G;
+                gr[0] = Lp<T>::from_f(gi);
+                gr[H] = Lp<T>::from_f(gf);
+                gr[2 * H] = Lp<T>::from_f(gg);
+                gr[3 * H] = Lp<T>::from_f(go);
+                c_out[crow * H] = Lp<T>::from_f(c);
+                h_out[crow * H] = h;
+                if (h_blk) h_blk[crow * 64] = h;
+            }
+        }
+        __syncthreads();                               // h_t of every unit block is in LDS before the next step reads it
+    }
+    if (active && unit) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = r0 + (r >> 2) * 8 + rsub + (r & 3);
+            if (row < a.B) a.c_state[(int64_t)row * H + j] = creg[r];
+        }
+    }
+}
+
 // ---------------------------------------------------------------- backward
 struct BwdArgs {
     const void *dApk;      // packed dA_{t+1}: [n_mt][4][nkc][64][64]
@@ -1222,6 +1369,33 @@ int step_forward_proj(int dtype, const void *hpk_prev, const void *Upk, const vo
     } else {
         LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_step_forward_kernel<T, false>), dim3(grid), dim3(256), 0, s, a));
     }
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+// the whole recurrence of a layer in one launch (lstm_rows_forward_kernel): thousands of rows, H <= 256
+bool rows_forward_supported(int dtype, int B, int H, int in_width) {
+    if (dtype != LSTM_DTYPE_FP16 && dtype != LSTM_DTYPE_BF16) return false;
+    const RecurrentDims d = recurrent_dims(B, H);
+    return recurrent_wide(d) && d.n_hb <= 8 && d.nkc <= 4 && in_width >= 1 && in_width <= 512;
+}
+
+int rows_forward(int dtype, const RowsForward &x, int in_width, int T, int B, int H, hipStream_t s) {
+    const RecurrentDims d = recurrent_dims(B, H);
+    if (!rows_forward_supported(dtype, B, H, in_width) || !x.hseq || !x.xseq || !x.Upk || !x.Wpk || !x.bias || !x.c_state || !x.gates ||
+        !x.c_out || !x.h_out || T < 1) {
+        set_error("rows_forward: unsupported shape or null operand (B=%d H=%d)", B, H);
+        return LSTM_ERR_INVALID;
+    }
+    RowsFwdArgs a;
+    a.hseq = x.hseq; a.xseq = x.xseq; a.slot_h = x.slot_h; a.slot_x = x.slot_x; a.Upk = x.Upk; a.Wpk = x.Wpk; a.bias = x.bias;
+    a.c_state = x.c_state; a.gates = x.gates; a.c_out = x.c_out; a.h_out = x.h_out; a.h_blk = x.h_blk; a.slot_blk = x.slot_blk;
+    a.blk_ncb = x.blk_ncb; a.T = T; a.B = B; a.H = H; a.nkc = d.nkc; a.nkc2 = (in_width + SK - 1) / SK;
+    const double bh = (double)B * H;
+    KernelTimer timer(KC_GEMM_STEP, s, (double)T * 2.0 * B * 4.0 * H * ((double)H + in_width),
+                      (double)T * (2.0 * (4.0 * H * ((double)H + in_width) + bh + (double)B * in_width) +
+                                   2.0 * (4.0 * bh + bh + (x.h_blk ? 3.0 : 2.0) * bh)));
+    LP_ONLY(dtype, T_, hipLaunchKernelGGL(lstm_rows_forward_kernel<T_>, dim3(2 * d.n_mt), dim3(512), 0, s, a));
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
