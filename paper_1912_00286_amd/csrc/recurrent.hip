@@ -351,7 +351,9 @@ struct RowsFwdArgs {
 template <typename T>
 __global__ __launch_bounds__(512) void lstm_rows_forward_kernel(RowsFwdArgs a) {
     constexpr int HCH = 32 * SK;                       // elements of a 32-row chunk in LDS: [ks][lane][8]
+    constexpr int STAGE_LD = 40;                       // elements per row of a staging tile (80 bytes: 16-byte aligned, off the bank stride)
     __shared__ __attribute__((aligned(16))) uint16_t hbuf[2][4 * HCH];
+    __shared__ __attribute__((aligned(16))) T stage[8][32 * STAGE_LD];
     const int tid = threadIdx.x, lane = tid & 63;
     const int hb = __builtin_amdgcn_readfirstlane(tid >> 6);      // wavefront = block of 32 units x 4 gates
     const int mt = blockIdx.x >> 1, mb = blockIdx.x & 1;
@@ -380,9 +382,7 @@ __global__ __launch_bounds__(512) void lstm_rows_forward_kernel(RowsFwdArgs a) {
     const int hbc = min(hb, n_hb - 1);
     const uint16_t *Upk = reinterpret_cast<const uint16_t *>(a.Upk) + (int64_t)hbc * a.nkc * B_CHUNK;
     const uint16_t *Wpk = reinterpret_cast<const uint16_t *>(a.Wpk) + (int64_t)hbc * a.nkc2 * B_CHUNK;
-    const bool unit = j < H;
     const bool pad_half = hb * 32 + 32 >= H && hb * 32 + 32 < a.nkc * SK;   // nobody owns the chunk's second half
-    const int kc = min(j, a.nkc * SK - 1) >> 6, kk = j & 63;
     for (int t = 0; t < a.T; ++t) {
         if (active) {
             const u32x4 *hA = reinterpret_cast<const u32x4 *>(hbuf[t & 1]);
@@ -422,50 +422,79 @@ __global__ __launch_bounds__(512) void lstm_rows_forward_kernel(RowsFwdArgs a) {
             }
             mm(ra0, rb0);                              // nq is even: two half chunks are left
             mm(ra1, rb1);
-            // gate arithmetic in the accumulator layout: this lane has the four gates of unit j for 16 rows.
-            // Row r of the accumulator is tile row rsub + crow(r), crow a compile-time constant: every address
-            // below is one per-lane base plus a constant (or uniform) multiple of crow, so that sixteen rows'
-            // worth of addresses need not be kept in registers across the time loop.
-            const int row0 = r0 + rsub;
-            T *hpk = const_cast<T *>(reinterpret_cast<const T *>(a.hseq)) + (int64_t)(t + 1) * a.slot_h + ((int64_t)mt * a.nkc + kc) * A_CHUNK +
-                     frag_offset(mb * 32 + rsub, kk, 2);
-            T *gates = reinterpret_cast<T *>(a.gates) + (int64_t)t * a.B * G + (int64_t)row0 * G + j;
-            T *c_out = reinterpret_cast<T *>(a.c_out) + (int64_t)t * a.B * H + (int64_t)row0 * H + j;
-            T *h_out = reinterpret_cast<T *>(a.h_out) + (int64_t)t * a.B * H + (int64_t)row0 * H + j;
-            T *h_blk = a.h_blk ? reinterpret_cast<T *>(a.h_blk) + (int64_t)t * a.slot_blk + ((int64_t)mt * a.blk_ncb + (j >> 6)) * 4096 +
-                                     (mb * 32 + rsub) * 64 + kk
-                               : nullptr;
-            T *hl = hN + (kc * 4 + (kk >> 4)) * 512 + (((kk >> 3) & 1) * 32 + rsub) * 8 + (kk & 7);
+            // Gate arithmetic in the accumulator layout (this lane: the four gates of unit j for 16 rows), then
+            // every output goes through the wavefront's 32 x 32 staging tile in LDS, so that a lane stores 8
+            // consecutive units of one row (16 bytes) instead of one unit of sixteen rows: a sixteenth of the
+            // store instructions.  The tile is private to the wavefront, whose LDS accesses execute in
+            // program order: no barrier between writing it in one layout and reading it in the other.
+            T *tile = stage[hb];
+            T *tw = tile + rsub * STAGE_LD + col;                  // + crow * STAGE_LD: element (row, unit) of the tile
+            const int irow = lane >> 2, igrp = (lane & 3) * 8;     // item k of this lane: row irow + 16 k, units igrp..
+            const int j8 = hb * 32 + igrp;
+            const bool units8 = j8 < H;                            // H % 8 == 0: a group of 8 is inside or outside
+            const bool pad8 = !units8 && j8 < a.nkc * SK;          // padding columns of the packed operand
+            float gv[4][16];
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int crow = (r >> 2) * 8 + (r & 3);
-                const float gi = sigmoidf_dev(acc[0][r] + breg[0]);
-                const float gf = sigmoidf_dev(acc[1][r] + breg[1]);
-                const float gg = tanhf_dev(acc[2][r] + breg[2]);
-                const float go = sigmoidf_dev(acc[3][r] + breg[3]);
-                const float c = gf * creg[r] + gi * gg;
-                creg[r] = c;
-                const T h = unit ? Lp<T>::from_f(go * tanhf_dev(c)) : Lp<T>::from_f(0.0f);
-                // next step's operand (zero in the padding columns up to the next multiple of 64)
-                hl[crow * 8] = h;
-                if (pad_half) hl[crow * 8 + 2 * 512] = Lp<T>::from_f(0.0f);         // column j + 32: two k-steps of 16 further
-                if (row0 + crow >= a.B) continue;
-                hpk[crow * 8] = h;
-                if (pad_half) hpk[crow * 8 + 2 * 2 * 512] = Lp<T>::from_f(0.0f);    // same, in the 64-row chunk (two blocks per k-step)
-                if (!unit) continue;
-                T *gr = gates + crow * G;
-                gr[0] = Lp<T>::from_f(gi);
-                gr[H] = Lp<T>::from_f(gf);
-                gr[2 * H] = Lp<T>::from_f(gg);
-                gr[3 * H] = Lp<T>::from_f(go);
-                c_out[crow * H] = Lp<T>::from_f(c);
-                h_out[crow * H] = h;
-                if (h_blk) h_blk[crow * 64] = h;
+                gv[0][r] = sigmoidf_dev(acc[0][r] + breg[0]);
+                gv[1][r] = sigmoidf_dev(acc[1][r] + breg[1]);
+                gv[2][r] = tanhf_dev(acc[2][r] + breg[2]);
+                gv[3][r] = sigmoidf_dev(acc[3][r] + breg[3]);
+                creg[r] = gv[1][r] * creg[r] + gv[0][r] * gv[2][r];
+            }
+            auto exchange = [&](const float (&v)[16], u32x4 (&out)[2]) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) tw[((r >> 2) * 8 + (r & 3)) * STAGE_LD] = Lp<T>::from_f(v[r]);
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int k = 0; k < 2; ++k) out[k] = *reinterpret_cast<const u32x4 *>(tile + (irow + 16 * k) * STAGE_LD + igrp);
+                __builtin_amdgcn_wave_barrier();
+            };
+            u32x4 o8[2];
+            const int kc8 = j8 >> 6, kk8 = j8 & 63;
+            T *gates = reinterpret_cast<T *>(a.gates) + (int64_t)t * a.B * G + j8;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                exchange(gv[g], o8);
+#pragma unroll
+                for (int k = 0; k < 2; ++k) {
+                    const int row = r0 + irow + 16 * k;
+                    if (units8 && row < a.B) *reinterpret_cast<u32x4 *>(gates + (int64_t)row * G + g * H) = o8[k];
+                }
+            }
+            float hv[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) hv[r] = gv[3][r] * tanhf_dev(creg[r]);
+            exchange(creg, o8);
+            T *c_out = reinterpret_cast<T *>(a.c_out) + (int64_t)t * a.B * H + j8;
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int row = r0 + irow + 16 * k;
+                if (units8 && row < a.B) *reinterpret_cast<u32x4 *>(c_out + (int64_t)row * H) = o8[k];
+            }
+            exchange(hv, o8);
+            T *h_out = reinterpret_cast<T *>(a.h_out) + (int64_t)t * a.B * H + j8;
+            T *hpk = const_cast<T *>(reinterpret_cast<const T *>(a.hseq)) + (int64_t)(t + 1) * a.slot_h + ((int64_t)mt * a.nkc + kc8) * A_CHUNK;
+            T *h_blk = a.h_blk ? reinterpret_cast<T *>(a.h_blk) + (int64_t)t * a.slot_blk + ((int64_t)mt * a.blk_ncb + kc8) * 4096 + kk8 : nullptr;
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int rl = irow + 16 * k, row = r0 + rl;
+                const u32x4 h8 = units8 ? o8[k] : u32x4{0u, 0u, 0u, 0u};
+                // next step's operand: 8 units of a row are one 16-byte slot of the fragment order (zero in the padding)
+                const int slot32 = ((kc8 * 4 + (kk8 >> 4)) * 64 + ((kk8 >> 3) & 1) * 32 + rl) * 8;
+                if (units8 || pad8) *reinterpret_cast<u32x4 *>(hN + slot32) = h8;
+                if (pad_half) *reinterpret_cast<u32x4 *>(hN + slot32 + 2 * 512) = u32x4{0u, 0u, 0u, 0u};   // columns + 32: nobody owns them
+                if (row >= a.B) continue;
+                if (units8 || pad8) *reinterpret_cast<u32x4 *>(hpk + frag_offset(mb * 32 + rl, kk8, 2)) = h8;
+                if (pad_half) *reinterpret_cast<u32x4 *>(hpk + frag_offset(mb * 32 + rl, kk8 + 32, 2)) = u32x4{0u, 0u, 0u, 0u};
+                if (!units8) continue;
+                *reinterpret_cast<u32x4 *>(h_out + (int64_t)row * H) = h8;
+                if (h_blk) *reinterpret_cast<u32x4 *>(h_blk + (mb * 32 + rl) * 64) = h8;
             }
         }
         __syncthreads();                               // h_t of every unit block is in LDS before the next step reads it
     }
-    if (active && unit) {
+    if (active && j < H) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int row = r0 + (r >> 2) * 8 + rsub + (r & 3);
@@ -1377,7 +1406,7 @@ int step_forward_proj(int dtype, const void *hpk_prev, const void *Upk, const vo
 bool rows_forward_supported(int dtype, int B, int H, int in_width) {
     if (dtype != LSTM_DTYPE_FP16 && dtype != LSTM_DTYPE_BF16) return false;
     const RecurrentDims d = recurrent_dims(B, H);
-    return recurrent_wide(d) && d.n_hb <= 8 && d.nkc <= 4 && in_width >= 1 && in_width <= 512;
+    return H % 8 == 0 && recurrent_wide(d) && d.n_hb <= 8 && d.nkc <= 4 && in_width >= 1 && in_width <= 512;
 }
 
 int rows_forward(int dtype, const RowsForward &x, int in_width, int T, int B, int H, hipStream_t s) {
