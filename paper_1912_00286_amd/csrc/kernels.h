@@ -112,6 +112,8 @@ struct RowsForward {
     void *h_blk;               // step 0's blocked slot, or null
     int64_t slot_blk;
     int blk_ncb;
+    int all_h_out;             // 0: only h_T is written to h_out
+    int write_hpk;             // 0: the packed h_t slots (a layer above reads them as its input) are not written
 };
 bool rows_forward_supported(int dtype, int B, int H, int in_width);
 int rows_forward(int dtype, const RowsForward &x, int in_width, int T, int B, int H, hipStream_t s);

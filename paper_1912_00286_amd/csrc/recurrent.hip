@@ -347,12 +347,16 @@ struct RowsFwdArgs {
     void *h_blk;           // blocked h of step 0 (slot 1), or null
     int64_t slot_blk;      // elements per time slot of h_blk
     int blk_ncb, T, B, H, nkc, nkc2;
+    int in_width;          // columns of x (the rest of its last chunk is zero padding and is skipped)
+    int all_h_out;         // 0: only h_T goes to h_out (a layer whose row-major h_t nobody reads)
+    int write_hpk;         // 0: the packed h_t slots are not written (no layer above reads them)
 };
 template <typename T>
 __global__ __launch_bounds__(512) void lstm_rows_forward_kernel(RowsFwdArgs a) {
     constexpr int HCH = 32 * SK;                       // elements of a 32-row chunk in LDS: [ks][lane][8]
     constexpr int STAGE_LD = 40;                       // elements per row of a staging tile (80 bytes: 16-byte aligned, off the bank stride)
-    __shared__ __attribute__((aligned(16))) uint16_t hbuf[2][4 * HCH];
+    // both operands' rows for one step, in fragment order: chunks [0, nkc) = h_{t-1}, [nkc, nkc + nkc2) = x_t
+    __shared__ __attribute__((aligned(16))) uint16_t abuf[2][8 * HCH];
     __shared__ __attribute__((aligned(16))) T stage[8][32 * STAGE_LD];
     const int tid = threadIdx.x, lane = tid & 63;
     const int hb = __builtin_amdgcn_readfirstlane(tid >> 6);      // wavefront = block of 32 units x 4 gates
@@ -360,12 +364,17 @@ __global__ __launch_bounds__(512) void lstm_rows_forward_kernel(RowsFwdArgs a) {
     const int r0 = mt * TM + mb * 32;
     if (r0 >= a.B) return;                             // the second half of a ragged last tile
     const int H = a.H, G = 4 * a.H, n_hb = (H + 31) / 32;
-    const int nq = 2 * (a.nkc + a.nkc2);               // half chunks (two k-steps of 16) of the step's two products
-    // h_0 of these rows: chunk c, k-step ks of the packed 64-row tile is fragment (c*8 + ks*2 + mb)
+    // half chunks (two k-steps of 16) of the step's two products; all-padding halves at the end of K are left out
+    const int nqh = (H + 31) / 32, nq = nqh + (a.in_width + 31) / 32;
+    // chunk c, k-step ks of these rows is fragment (c*8 + ks*2 + mb) of the packed 64-row tile
+    auto tile_frag = [&](int v) { return ((v >> 8) * 8 + ((v >> 6) & 3) * 2 + mb) * 64 + (v & 63); };
+    const u32x4 *xsrc = reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(a.xseq) + (int64_t)mt * a.nkc2 * A_CHUNK);
+    const int64_t xstep = a.slot_x / 8;                // 16-byte units per input slot
     {
         const u32x4 *src = reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(a.hseq) + (int64_t)mt * a.nkc * A_CHUNK);
-        u32x4 *dst = reinterpret_cast<u32x4 *>(hbuf[0]);
-        for (int v = tid; v < a.nkc * 256; v += 512) dst[v] = src[((v >> 8) * 8 + ((v >> 6) & 3) * 2 + mb) * 64 + (v & 63)];
+        u32x4 *dst = reinterpret_cast<u32x4 *>(abuf[0]);
+        for (int v = tid; v < a.nkc * 256; v += 512) dst[v] = src[tile_frag(v)];
+        for (int v = tid; v < a.nkc2 * 256; v += 512) dst[a.nkc * 256 + v] = xsrc[tile_frag(v)];
     }
     const bool active = hb < n_hb;                     // uniform over the wavefront
     const int col = lane & 31, rsub = (lane >> 5) * 4;
@@ -384,25 +393,34 @@ __global__ __launch_bounds__(512) void lstm_rows_forward_kernel(RowsFwdArgs a) {
     const uint16_t *Wpk = reinterpret_cast<const uint16_t *>(a.Wpk) + (int64_t)hbc * a.nkc2 * B_CHUNK;
     const bool pad_half = hb * 32 + 32 >= H && hb * 32 + 32 < a.nkc * SK;   // nobody owns the chunk's second half
     for (int t = 0; t < a.T; ++t) {
+        // x_{t+1} of these rows is requested now and put into the other buffer at the end of the step
+        u32x4 xnext[2];
+        const bool more = t + 1 < a.T;
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int v = tid + 512 * i;
+                if (v < a.nkc2 * 256) xnext[i] = xsrc[(int64_t)(t + 1) * xstep + tile_frag(v)];
+            }
+        }
+        T *hN = reinterpret_cast<T *>(abuf[(t + 1) & 1]);
         if (active) {
-            const u32x4 *hA = reinterpret_cast<const u32x4 *>(hbuf[t & 1]);
-            T *hN = reinterpret_cast<T *>(hbuf[(t + 1) & 1]);
-            const u32x4 *xA = reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(a.xseq) + (int64_t)t * a.slot_x + (int64_t)mt * a.nkc2 * A_CHUNK);
+            const u32x4 *A = reinterpret_cast<const u32x4 *>(abuf[t & 1]);
             v16f acc[NBLK];
 #pragma unroll
             for (int nb = 0; nb < NBLK; ++nb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[nb][r] = 0.0f;
-            // half-chunk list: the recurrent product (h from LDS, U), then the input projection (x from memory, W)
+            // half-chunk list: the recurrent product (h, U), then the input projection (x, W)
             auto load = [&](u32x4 (&ra)[2], u32x4 (&rb)[8], int q) {
-                const int c = q >> 1, hf = q & 1;
-                const bool rec = c < a.nkc;
-                const u32x4 *b = reinterpret_cast<const u32x4 *>(rec ? Upk + (int64_t)c * B_CHUNK : Wpk + (int64_t)(c - a.nkc) * B_CHUNK) + hf * 512;
+                const bool rec = q < nqh;
+                const int q2 = rec ? q : q - nqh, c = q2 >> 1, hf = q2 & 1;
+                const u32x4 *b = reinterpret_cast<const u32x4 *>(rec ? Upk + (int64_t)c * B_CHUNK : Wpk + (int64_t)c * B_CHUNK) + hf * 512;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) rb[i] = b[lane + 64 * i];
+                const int ca = rec ? c : a.nkc + c;
 #pragma unroll
-                for (int k2 = 0; k2 < 2; ++k2)
-                    ra[k2] = rec ? hA[(c * 4 + hf * 2 + k2) * 64 + lane] : xA[((c - a.nkc) * 8 + (hf * 2 + k2) * 2 + mb) * 64 + lane];
+                for (int k2 = 0; k2 < 2; ++k2) ra[k2] = A[(ca * 4 + hf * 2 + k2) * 64 + lane];
             };
             auto mm = [&](const u32x4 (&ra)[2], const u32x4 (&rb)[8]) {
 #pragma unroll
@@ -412,16 +430,19 @@ __global__ __launch_bounds__(512) void lstm_rows_forward_kernel(RowsFwdArgs a) {
             };
             u32x4 ra0[2], ra1[2], rb0[8], rb1[8];
             load(ra0, rb0, 0);
-            load(ra1, rb1, 1);                         // nq >= 4: at least one chunk per product
+            load(ra1, rb1, 1);                         // nq >= 2: at least one half chunk per product
             int s = 0;
-            for (; s + 4 <= nq; s += 2) {
+            for (; s + 4 <= nq; s += 2) {              // branch-free body: both refills are in range
                 mm(ra0, rb0);
                 load(ra0, rb0, s + 2);
                 mm(ra1, rb1);
                 load(ra1, rb1, s + 3);
             }
-            mm(ra0, rb0);                              // nq is even: two half chunks are left
+            // tail: two or three half chunks left, set 0 holds s, set 1 holds s + 1
+            mm(ra0, rb0);
+            if (s + 2 < nq) load(ra0, rb0, s + 2);
             mm(ra1, rb1);
+            if (s + 2 < nq) mm(ra0, rb0);
             // Gate arithmetic in the accumulator layout (this lane: the four gates of unit j for 16 rows), then
             // every output goes through the wavefront's 32 x 32 staging tile in LDS, so that a lane stores 8
             // consecutive units of one row (16 bytes) instead of one unit of sixteen rows: a sixteenth of the
@@ -485,14 +506,23 @@ __global__ __launch_bounds__(512) void lstm_rows_forward_kernel(RowsFwdArgs a) {
                 if (units8 || pad8) *reinterpret_cast<u32x4 *>(hN + slot32) = h8;
                 if (pad_half) *reinterpret_cast<u32x4 *>(hN + slot32 + 2 * 512) = u32x4{0u, 0u, 0u, 0u};   // columns + 32: nobody owns them
                 if (row >= a.B) continue;
-                if (units8 || pad8) *reinterpret_cast<u32x4 *>(hpk + frag_offset(mb * 32 + rl, kk8, 2)) = h8;
-                if (pad_half) *reinterpret_cast<u32x4 *>(hpk + frag_offset(mb * 32 + rl, kk8 + 32, 2)) = u32x4{0u, 0u, 0u, 0u};
+                if (a.write_hpk) {
+                    if (units8 || pad8) *reinterpret_cast<u32x4 *>(hpk + frag_offset(mb * 32 + rl, kk8, 2)) = h8;
+                    if (pad_half) *reinterpret_cast<u32x4 *>(hpk + frag_offset(mb * 32 + rl, kk8 + 32, 2)) = u32x4{0u, 0u, 0u, 0u};
+                }
                 if (!units8) continue;
-                *reinterpret_cast<u32x4 *>(h_out + (int64_t)row * H) = h8;
+                if (a.all_h_out || !more) *reinterpret_cast<u32x4 *>(h_out + (int64_t)row * H) = h8;
                 if (h_blk) *reinterpret_cast<u32x4 *>(h_blk + (mb * 32 + rl) * 64) = h8;
             }
         }
-        __syncthreads();                               // h_t of every unit block is in LDS before the next step reads it
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int v = tid + 512 * i;
+                if (v < a.nkc2 * 256) reinterpret_cast<u32x4 *>(hN)[a.nkc * 256 + v] = xnext[i];
+            }
+        }
+        __syncthreads();                               // h_t of every unit block and x_{t+1} are in LDS before the next step reads them
     }
     if (active && j < H) {
 #pragma unroll
@@ -1406,7 +1436,7 @@ int step_forward_proj(int dtype, const void *hpk_prev, const void *Upk, const vo
 bool rows_forward_supported(int dtype, int B, int H, int in_width) {
     if (dtype != LSTM_DTYPE_FP16 && dtype != LSTM_DTYPE_BF16) return false;
     const RecurrentDims d = recurrent_dims(B, H);
-    return H % 8 == 0 && recurrent_wide(d) && d.n_hb <= 8 && d.nkc <= 4 && in_width >= 1 && in_width <= 512;
+    return H % 8 == 0 && recurrent_wide(d) && d.n_hb <= 8 && d.nkc <= 4 && in_width >= 1 && in_width <= 256;
 }
 
 int rows_forward(int dtype, const RowsForward &x, int in_width, int T, int B, int H, hipStream_t s) {
@@ -1420,6 +1450,7 @@ int rows_forward(int dtype, const RowsForward &x, int in_width, int T, int B, in
     a.hseq = x.hseq; a.xseq = x.xseq; a.slot_h = x.slot_h; a.slot_x = x.slot_x; a.Upk = x.Upk; a.Wpk = x.Wpk; a.bias = x.bias;
     a.c_state = x.c_state; a.gates = x.gates; a.c_out = x.c_out; a.h_out = x.h_out; a.h_blk = x.h_blk; a.slot_blk = x.slot_blk;
     a.blk_ncb = x.blk_ncb; a.T = T; a.B = B; a.H = H; a.nkc = d.nkc; a.nkc2 = (in_width + SK - 1) / SK;
+    a.in_width = in_width; a.all_h_out = x.all_h_out; a.write_hpk = x.write_hpk;
     const double bh = (double)B * H;
     KernelTimer timer(KC_GEMM_STEP, s, (double)T * 2.0 * B * 4.0 * H * ((double)H + in_width),
                       (double)T * (2.0 * (4.0 * H * ((double)H + in_width) + bh + (double)B * in_width) +
