@@ -811,7 +811,16 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
         }
         char *dablk = p.blk ? at(scratch, p.wb ? p.s_wb_dablk[l] : p.s_dablk) : nullptr;
         const bool fused_step = fused && !p.wb && step_backward_fused_supported(p.dtype, p.B, p.H) && (dA_rm || dablk);
-        for (int t = p.wb ? -1 : p.T - 1; t >= 0; --t) {      // along the diagonals the steps are already done
+        const bool rows_bwd = fused_step && rows_backward_supported(p.dtype, p.B, p.H);
+        if (rows_bwd) {
+            // every workgroup walks its 32 rows back through all T steps: one launch for the layer
+            RowsBackward r{};
+            r.UTpk = utpk; r.dh_above = dh_above; r.gates = gates; r.cs = cs;
+            r.dA = dA_rm ? dA : nullptr; r.dAblk = dablk;
+            r.slot_blk = (int64_t)(p.B / 64) * p.g_ncb * 4096; r.blk_ncb = p.g_ncb;
+            LSTM_TRY(rows_backward(p.dtype, r, p.T, p.B, p.H, s));
+        }
+        for (int t = (p.wb || rows_bwd) ? -1 : p.T - 1; t >= 0; --t) {      // along the diagonals the steps are already done
             const bool last = t == p.T - 1;
             if (fused && fused_step) {
                 // thousands of rows per step: product and gate arithmetic in one launch, no partial sums in memory

@@ -115,6 +115,19 @@ struct RowsForward {
     int all_h_out;             // 0: only h_T is written to h_out
     int write_hpk;             // 0: the packed h_t slots (a layer above reads them as its input) are not written
 };
+// a layer's whole BPTT recurrence in one launch: dA_t for every step from the saved activations and dh from above
+struct RowsBackward {
+    const void *UTpk;          // packed U^T (pack_u_backward)
+    const void *dh_above;      // lp [T][B,H]
+    const void *gates;         // lp [T][B,4H]
+    const void *cs;            // lp [T+1][B,H] saved cell states (slot 0 = c_0)
+    void *dA;                  // lp [T][B,4H] row-major out, or null
+    void *dAblk;               // blocked out (slot_blk elements per time step), or null
+    int64_t slot_blk;
+    int blk_ncb;
+};
+bool rows_backward_supported(int dtype, int B, int H);
+int rows_backward(int dtype, const RowsBackward &x, int T, int B, int H, hipStream_t s);
 bool rows_forward_supported(int dtype, int B, int H, int in_width);
 int rows_forward(int dtype, const RowsForward &x, int in_width, int T, int B, int H, hipStream_t s);
 int pack_w_forward(int dtype, const void *W, void *Wpk, int H, int K, hipStream_t s);

@@ -533,6 +533,165 @@ __global__ __launch_bounds__(512) void lstm_rows_forward_kernel(RowsFwdArgs a) {
     }
 }
 
+// ---------------------------------------------------------------- a layer's whole BPTT recurrence in one launch
+// The same ownership backwards: a workgroup walks its 32 rows from t = T-1 down to 0.  dA_{t+1} of its rows (all
+// four gates) sits in LDS in fragment order; wavefront w contracts it with the packed U^T for its block of 32
+// units (all 4H gate rows: nothing to add up across wavefronts), turns the 32 x 32 result round through its
+// staging tile so that a lane holds 8 consecutive units of two rows, and does the gate arithmetic there: the saved
+// gates, c_t, c_{t-1} and the gradient from above arrive as 16-byte loads requested before the product, dA_t
+// leaves as 16-byte stores (LDS for the next step, the blocked and / or row-major copy for the whole-sequence
+// GEMMs), the cell-state gradient never leaves the registers.
+struct RowsBwdArgs {
+    const void *UTpk;      // packed U^T: [n_nt][4][nkc][128][64]
+    const void *dh_above;  // lp [T][B,H]
+    const void *gates;     // lp [T][B,4H]
+    const void *cs;        // lp [T+1][B,H]: c_{t-1} is slot t, c_t slot t + 1
+    void *dA;              // lp [T][B,4H] row-major, or null
+    void *dAblk;           // dA in 64x64 blocks, slot_blk elements per time step, or null
+    int64_t slot_blk;
+    int blk_ncb, T, B, H, nkc;
+};
+template <typename T>
+__global__ __launch_bounds__(512) void lstm_rows_backward_kernel(RowsBwdArgs a) {
+    constexpr int HCH = 32 * SK;                       // elements of a 32-row chunk in LDS: [ks][lane][8]
+    constexpr int SLD = 36;                            // floats per row of a staging tile
+    __shared__ __attribute__((aligned(16))) uint16_t dabuf[16 * HCH];      // [gate][nkc <= 4] chunks
+    __shared__ __attribute__((aligned(16))) float stage[8][32 * SLD];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int hb = __builtin_amdgcn_readfirstlane(tid >> 6);      // wavefront = block of 32 units
+    const int mt = blockIdx.x >> 1, mb = blockIdx.x & 1;
+    const int r0 = mt * TM + mb * 32;
+    if (r0 >= a.B) return;
+    const int H = a.H, G = 4 * a.H, n_hb = (H + 31) / 32;
+    const int nq = 4 * n_hb;                           // half chunks of the contraction: gate = q % 4, half chunk q / 4
+    for (int v = tid; v < 16 * 256; v += 512) reinterpret_cast<u32x4 *>(dabuf)[v] = u32x4{0u, 0u, 0u, 0u};   // padding stays zero
+    const bool active = hb < n_hb;                     // uniform over the wavefront
+    const int col = lane & 31, rsub = (lane >> 5) * 4;
+    const int irow = lane >> 2, igrp = (lane & 3) * 8; // item k of this lane: row irow + 16 k, units igrp..igrp + 7 of the block
+    const int j8 = hb * 32 + igrp;
+    const bool units8 = active && j8 < H;              // H % 8 == 0: a group of 8 is inside or outside
+    const int kc8 = j8 >> 6, kk8 = j8 & 63;
+    float dc[2][8];
+#pragma unroll
+    for (int k = 0; k < 2; ++k)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dc[k][e] = 0.0f;
+    const int hbc = min(hb, n_hb - 1);
+    // B fragments of this wavefront: chunk (nt, gate, c), k-step ks, unit block hbc % 4
+    const u32x4 *UT = reinterpret_cast<const u32x4 *>(a.UTpk) + (int64_t)(hbc >> 2) * 4 * a.nkc * (B_CHUNK / 8) + (hbc & 3) * 64 + lane;
+    const u32x4 *Ad = reinterpret_cast<const u32x4 *>(dabuf) + lane;
+    float *tile = stage[hb];
+    __syncthreads();
+    for (int t = a.T - 1; t >= 0; --t) {
+        const bool first = t == a.T - 1;
+        // this step's saved activations and the gradient from above do not depend on the recurrence: requested first
+        u32x4 vi[2], vf[2], vg[2], vo[2], vct[2], vcp[2], vdh[2];
+        bool ok[2];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int row = r0 + irow + 16 * k;
+            ok[k] = units8 && row < a.B;
+            if (ok[k]) {
+                const T *gr = reinterpret_cast<const T *>(a.gates) + (int64_t)t * a.B * G + (int64_t)row * G + j8;
+                const int64_t e = (int64_t)row * H + j8;
+                vi[k] = *reinterpret_cast<const u32x4 *>(gr);
+                vf[k] = *reinterpret_cast<const u32x4 *>(gr + H);
+                vg[k] = *reinterpret_cast<const u32x4 *>(gr + 2 * H);
+                vo[k] = *reinterpret_cast<const u32x4 *>(gr + 3 * H);
+                vcp[k] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(a.cs) + (int64_t)t * a.B * H + e);
+                vct[k] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(a.cs) + (int64_t)(t + 1) * a.B * H + e);
+                vdh[k] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(a.dh_above) + (int64_t)t * a.B * H + e);
+            }
+        }
+        v16f acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+        if (active && !first) {
+            // dh_rec = dA_{t+1} U for this block of units: four register sets of one half chunk each
+            auto load = [&](u32x4 (&ra)[2], u32x4 (&rb)[2], int q) {
+                const int g = q & 3, hq = q >> 2, c = hq >> 1, hf = hq & 1;
+                const int chunk = g * a.nkc + c;
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2) {
+                    rb[k2] = UT[(int64_t)chunk * (B_CHUNK / 8) + (hf * 2 + k2) * 256];
+                    ra[k2] = Ad[(chunk * 4 + hf * 2 + k2) * 64];
+                }
+            };
+            auto mm = [&](const u32x4 (&ra)[2], const u32x4 (&rb)[2]) {
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2) acc = Lp<T>::mfma(ra[k2], rb[k2], acc);
+            };
+            u32x4 ra0[2], ra1[2], ra2[2], ra3[2], rb0[2], rb1[2], rb2[2], rb3[2];
+            load(ra0, rb0, 0); load(ra1, rb1, 1); load(ra2, rb2, 2); load(ra3, rb3, 3);
+            int s = 0;
+            for (; s + 8 <= nq; s += 4) {              // nq is a multiple of four; branch-free body
+                mm(ra0, rb0); load(ra0, rb0, s + 4);
+                mm(ra1, rb1); load(ra1, rb1, s + 5);
+                mm(ra2, rb2); load(ra2, rb2, s + 6);
+                mm(ra3, rb3); load(ra3, rb3, s + 7);
+            }
+            mm(ra0, rb0); mm(ra1, rb1); mm(ra2, rb2); mm(ra3, rb3);
+        }
+        __syncthreads();                               // every wavefront has read dA_{t+1}: the buffer may take dA_t
+        if (active) {
+            // accumulator layout (lane = unit, 16 rows) -> item layout (lane = 8 units of rows irow, irow + 16)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) tile[(rsub + (r >> 2) * 8 + (r & 3)) * SLD + col] = acc[r];
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                if (!ok[k]) continue;
+                const int rl = irow + 16 * k, row = r0 + rl;
+                __attribute__((aligned(16))) float rec[8];
+                *reinterpret_cast<v4f *>(rec) = *reinterpret_cast<const v4f *>(tile + rl * SLD + igrp);
+                *reinterpret_cast<v4f *>(rec + 4) = *reinterpret_cast<const v4f *>(tile + rl * SLD + igrp + 4);
+                __attribute__((aligned(16))) T ti[8], tf[8], tg[8], to[8], tct[8], tcp[8], tdh[8], o0[8], o1[8], o2[8], o3[8];
+                *reinterpret_cast<u32x4 *>(ti) = vi[k]; *reinterpret_cast<u32x4 *>(tf) = vf[k]; *reinterpret_cast<u32x4 *>(tg) = vg[k];
+                *reinterpret_cast<u32x4 *>(to) = vo[k]; *reinterpret_cast<u32x4 *>(tct) = vct[k]; *reinterpret_cast<u32x4 *>(tcp) = vcp[k];
+                *reinterpret_cast<u32x4 *>(tdh) = vdh[k];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float i = Lp<T>::to_f(ti[e]), f = Lp<T>::to_f(tf[e]), g = Lp<T>::to_f(tg[e]), o = Lp<T>::to_f(to[e]);
+                    const float tc = tanhf_dev(Lp<T>::to_f(tct[e]));
+                    const float dh = Lp<T>::to_f(tdh[e]) + rec[e];
+                    const float d_o = dh * tc;
+                    const float dcv = dc[k][e] + dh * o * (1.0f - tc * tc);
+                    const float di = dcv * g, dg = dcv * i, df = dcv * Lp<T>::to_f(tcp[e]);
+                    dc[k][e] = dcv * f;
+                    o0[e] = Lp<T>::from_f(di * i * (1.0f - i));
+                    o1[e] = Lp<T>::from_f(df * f * (1.0f - f));
+                    o2[e] = Lp<T>::from_f(dg * (1.0f - g * g));
+                    o3[e] = Lp<T>::from_f(d_o * o * (1.0f - o));
+                }
+                // the next step's operand: 8 units of a row and gate are one 16-byte slot of the fragment order
+                u32x4 *slot = reinterpret_cast<u32x4 *>(dabuf) + (kc8 * 4 + (kk8 >> 4)) * 64 + ((kk8 >> 3) & 1) * 32 + rl;
+                const int gs = a.nkc * 256;                // 16-byte slots per gate
+                slot[0] = *reinterpret_cast<const u32x4 *>(o0);
+                slot[gs] = *reinterpret_cast<const u32x4 *>(o1);
+                slot[2 * gs] = *reinterpret_cast<const u32x4 *>(o2);
+                slot[3 * gs] = *reinterpret_cast<const u32x4 *>(o3);
+                if (a.dA) {
+                    T *da = reinterpret_cast<T *>(a.dA) + (int64_t)t * a.B * G + (int64_t)row * G + j8;
+                    *reinterpret_cast<u32x4 *>(da) = *reinterpret_cast<const u32x4 *>(o0);
+                    *reinterpret_cast<u32x4 *>(da + H) = *reinterpret_cast<const u32x4 *>(o1);
+                    *reinterpret_cast<u32x4 *>(da + 2 * H) = *reinterpret_cast<const u32x4 *>(o2);
+                    *reinterpret_cast<u32x4 *>(da + 3 * H) = *reinterpret_cast<const u32x4 *>(o3);
+                }
+                if (a.dAblk) {
+                    T *rowp = reinterpret_cast<T *>(a.dAblk) + (int64_t)t * a.slot_blk + (int64_t)mt * a.blk_ncb * 4096 + (mb * 32 + rl) * 64;
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int cg = g * H + j8;
+                        const T *src = g == 0 ? o0 : (g == 1 ? o1 : (g == 2 ? o2 : o3));
+                        *reinterpret_cast<u32x4 *>(rowp + (int64_t)(cg >> 6) * 4096 + (cg & 63)) = *reinterpret_cast<const u32x4 *>(src);
+                    }
+                }
+            }
+        }
+        __syncthreads();                               // dA_t of every unit block is in LDS
+    }
+}
+
 // ---------------------------------------------------------------- backward
 struct BwdArgs {
     const void *dApk;      // packed dA_{t+1}: [n_mt][4][nkc][64][64]
@@ -1456,6 +1615,31 @@ int rows_forward(int dtype, const RowsForward &x, int in_width, int T, int B, in
                       (double)T * (2.0 * (4.0 * H * ((double)H + in_width) + bh + (double)B * in_width) +
                                    2.0 * (4.0 * bh + bh + (x.h_blk ? 3.0 : 2.0) * bh)));
     LP_ONLY(dtype, T_, hipLaunchKernelGGL(lstm_rows_forward_kernel<T_>, dim3(2 * d.n_mt), dim3(512), 0, s, a));
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+// the whole BPTT recurrence of a layer in one launch (lstm_rows_backward_kernel): thousands of rows, H <= 256
+bool rows_backward_supported(int dtype, int B, int H) {
+    if (dtype != LSTM_DTYPE_FP16 && dtype != LSTM_DTYPE_BF16) return false;
+    const RecurrentDims d = recurrent_dims(B, H);
+    return H % 8 == 0 && recurrent_wide(d) && d.n_hb <= 8 && d.nkc <= 4;
+}
+
+int rows_backward(int dtype, const RowsBackward &x, int T, int B, int H, hipStream_t s) {
+    const RecurrentDims d = recurrent_dims(B, H);
+    const uintptr_t all = (uintptr_t)x.UTpk | (uintptr_t)x.dh_above | (uintptr_t)x.gates | (uintptr_t)x.cs | (uintptr_t)x.dA | (uintptr_t)x.dAblk;
+    if (!rows_backward_supported(dtype, B, H) || !x.UTpk || !x.dh_above || !x.gates || !x.cs || (!x.dA && !x.dAblk) || T < 1 || all % 16 != 0) {
+        set_error("rows_backward: unsupported shape, null or misaligned operand (B=%d H=%d)", B, H);
+        return LSTM_ERR_INVALID;
+    }
+    RowsBwdArgs a;
+    a.UTpk = x.UTpk; a.dh_above = x.dh_above; a.gates = x.gates; a.cs = x.cs; a.dA = x.dA; a.dAblk = x.dAblk; a.slot_blk = x.slot_blk;
+    a.blk_ncb = x.blk_ncb; a.T = T; a.B = B; a.H = H; a.nkc = d.nkc;
+    const double n = (double)B * H;
+    KernelTimer timer(KC_GEMM_STEP, s, (double)(T - 1) * 2.0 * n * 4.0 * H,
+                      (double)T * (2.0 * 4.0 * H * H + n * 2.0 * (7.0 + 4.0 * ((x.dA ? 1 : 0) + (x.dAblk ? 1 : 0)))));
+    LP_ONLY(dtype, T_, hipLaunchKernelGGL(lstm_rows_backward_kernel<T_>, dim3(2 * d.n_mt), dim3(512), 0, s, a));
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
