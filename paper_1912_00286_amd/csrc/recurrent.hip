@@ -1611,9 +1611,11 @@ int rows_forward(int dtype, const RowsForward &x, int in_width, int T, int B, in
     a.blk_ncb = x.blk_ncb; a.T = T; a.B = B; a.H = H; a.nkc = d.nkc; a.nkc2 = (in_width + SK - 1) / SK;
     a.in_width = in_width; a.all_h_out = x.all_h_out; a.write_hpk = x.write_hpk;
     const double bh = (double)B * H;
+    // operands once: the weights per launch; per step x_t read, the gates, c_t and the copies of h_t written; c_0 / c_T in fp32
+    const double h_copies = (x.all_h_out ? 1.0 : 0.0) + (x.write_hpk ? 1.0 : 0.0) + (x.h_blk ? 1.0 : 0.0);
     KernelTimer timer(KC_GEMM_STEP, s, (double)T * 2.0 * B * 4.0 * H * ((double)H + in_width),
-                      (double)T * (2.0 * (4.0 * H * ((double)H + in_width) + bh + (double)B * in_width) +
-                                   2.0 * (4.0 * bh + bh + (x.h_blk ? 3.0 : 2.0) * bh)));
+                      2.0 * 4.0 * H * ((double)H + in_width) + 8.0 * bh +
+                          (double)T * 2.0 * ((double)B * in_width + 4.0 * bh + bh + h_copies * bh));
     LP_ONLY(dtype, T_, hipLaunchKernelGGL(lstm_rows_forward_kernel<T_>, dim3(2 * d.n_mt), dim3(512), 0, s, a));
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
@@ -1637,8 +1639,9 @@ int rows_backward(int dtype, const RowsBackward &x, int T, int B, int H, hipStre
     a.UTpk = x.UTpk; a.dh_above = x.dh_above; a.gates = x.gates; a.cs = x.cs; a.dA = x.dA; a.dAblk = x.dAblk; a.slot_blk = x.slot_blk;
     a.blk_ncb = x.blk_ncb; a.T = T; a.B = B; a.H = H; a.nkc = d.nkc;
     const double n = (double)B * H;
+    // operands once: U per launch; per step the saved gates, c_t and the gradient from above read, dA written once per copy
     KernelTimer timer(KC_GEMM_STEP, s, (double)(T - 1) * 2.0 * n * 4.0 * H,
-                      (double)T * (2.0 * 4.0 * H * H + n * 2.0 * (7.0 + 4.0 * ((x.dA ? 1 : 0) + (x.dAblk ? 1 : 0)))));
+                      2.0 * 4.0 * H * H + (double)T * n * 2.0 * (6.0 + 4.0 * ((x.dA ? 1 : 0) + (x.dAblk ? 1 : 0))));
     LP_ONLY(dtype, T_, hipLaunchKernelGGL(lstm_rows_backward_kernel<T_>, dim3(2 * d.n_mt), dim3(512), 0, s, a));
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
