@@ -392,6 +392,17 @@ __global__ __launch_bounds__(512) void lstm_rows_forward_kernel(RowsFwdArgs a) {
     const uint16_t *Upk = reinterpret_cast<const uint16_t *>(a.Upk) + (int64_t)hbc * a.nkc * B_CHUNK;
     const uint16_t *Wpk = reinterpret_cast<const uint16_t *>(a.Wpk) + (int64_t)hbc * a.nkc2 * B_CHUNK;
     const bool pad_half = hb * 32 + 32 >= H && hb * 32 + 32 < a.nkc * SK;   // nobody owns the chunk's second half
+    // the weights of a half chunk: eight 16-byte fragments per lane (two k-steps x four gates)
+    auto loadB = [&](u32x4 (&rb)[8], int q) {
+        const bool rec = q < nqh;
+        const int q2 = rec ? q : q - nqh;
+        const u32x4 *b = reinterpret_cast<const u32x4 *>((rec ? Upk : Wpk) + (int64_t)(q2 >> 1) * B_CHUNK) + (q2 & 1) * 512;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) rb[i] = b[lane + 64 * i];
+    };
+    u32x4 rb0[8], rb1[8];
+    loadB(rb0, 0);
+    loadB(rb1, 1);                                     // nq >= 2: at least one half chunk per product
     for (int t = 0; t < a.T; ++t) {
         // x_{t+1} of these rows is requested now and put into the other buffer at the end of the step
         u32x4 xnext[2];
@@ -412,13 +423,9 @@ __global__ __launch_bounds__(512) void lstm_rows_forward_kernel(RowsFwdArgs a) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[nb][r] = 0.0f;
             // half-chunk list: the recurrent product (h, U), then the input projection (x, W)
-            auto load = [&](u32x4 (&ra)[2], u32x4 (&rb)[8], int q) {
+            auto loadA = [&](u32x4 (&ra)[2], int q) {
                 const bool rec = q < nqh;
-                const int q2 = rec ? q : q - nqh, c = q2 >> 1, hf = q2 & 1;
-                const u32x4 *b = reinterpret_cast<const u32x4 *>(rec ? Upk + (int64_t)c * B_CHUNK : Wpk + (int64_t)c * B_CHUNK) + hf * 512;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) rb[i] = b[lane + 64 * i];
-                const int ca = rec ? c : a.nkc + c;
+                const int q2 = rec ? q : q - nqh, ca = (rec ? 0 : a.nkc) + (q2 >> 1), hf = q2 & 1;
 #pragma unroll
                 for (int k2 = 0; k2 < 2; ++k2) ra[k2] = A[(ca * 4 + hf * 2 + k2) * 64 + lane];
             };
@@ -428,21 +435,23 @@ __global__ __launch_bounds__(512) void lstm_rows_forward_kernel(RowsFwdArgs a) {
 #pragma unroll
                     for (int nb = 0; nb < NBLK; ++nb) acc[nb] = Lp<T>::mfma(ra[k2], rb[k2 * NBLK + nb], acc[nb]);
             };
-            u32x4 ra0[2], ra1[2], rb0[8], rb1[8];
-            load(ra0, rb0, 0);
-            load(ra1, rb1, 1);                         // nq >= 2: at least one half chunk per product
+            u32x4 ra0[2], ra1[2];
+            loadA(ra0, 0);                             // the weights of half chunks 0 and 1 are already in rb0 / rb1
+            loadA(ra1, 1);
             int s = 0;
             for (; s + 4 <= nq; s += 2) {              // branch-free body: both refills are in range
                 mm(ra0, rb0);
-                load(ra0, rb0, s + 2);
+                loadB(rb0, s + 2); loadA(ra0, s + 2);
                 mm(ra1, rb1);
-                load(ra1, rb1, s + 3);
+                loadB(rb1, s + 3); loadA(ra1, s + 3);
             }
             // tail: two or three half chunks left, set 0 holds s, set 1 holds s + 1
             mm(ra0, rb0);
-            if (s + 2 < nq) load(ra0, rb0, s + 2);
+            if (s + 2 < nq) { loadB(rb0, s + 2); loadA(ra0, s + 2); }
             mm(ra1, rb1);
+            loadB(rb1, 1);                             // the next step's first weights travel during this step's epilogue
             if (s + 2 < nq) mm(ra0, rb0);
+            loadB(rb0, 0);
             // Gate arithmetic in the accumulator layout (this lane: the four gates of unit j for 16 rows), then
             // every output goes through the wavefront's 32 x 32 staging tile in LDS, so that a lane stores 8
             // consecutive units of one row (16 bytes) instead of one unit of sixteen rows: a sixteenth of the
@@ -581,6 +590,15 @@ __global__ __launch_bounds__(512) void lstm_rows_backward_kernel(RowsBwdArgs a) 
     const u32x4 *UT = reinterpret_cast<const u32x4 *>(a.UTpk) + (int64_t)(hbc >> 2) * 4 * a.nkc * (B_CHUNK / 8) + (hbc & 3) * 64 + lane;
     const u32x4 *Ad = reinterpret_cast<const u32x4 *>(dabuf) + lane;
     float *tile = stage[hb];
+    // U^T fragments of a half chunk (gate q % 4, half chunk q / 4): two per lane
+    auto loadB = [&](u32x4 (&rb)[2], int q) {
+        const int chunk = (q & 3) * a.nkc + (q >> 3), hf = (q >> 2) & 1;
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) rb[k2] = UT[(int64_t)chunk * (B_CHUNK / 8) + (hf * 2 + k2) * 256];
+    };
+    u32x4 rb0[2], rb1[2], rb2[2], rb3[2];
+    loadB(rb0, 0); loadB(rb1, 1); loadB(rb2, 2); loadB(rb3, 3);
+    u32x4 vct_next[2] = {};                            // c_{t-1} of step t is c_t of step t - 1
     __syncthreads();
     for (int t = a.T - 1; t >= 0; --t) {
         const bool first = t == a.T - 1;
@@ -599,7 +617,8 @@ __global__ __launch_bounds__(512) void lstm_rows_backward_kernel(RowsBwdArgs a) 
                 vg[k] = *reinterpret_cast<const u32x4 *>(gr + 2 * H);
                 vo[k] = *reinterpret_cast<const u32x4 *>(gr + 3 * H);
                 vcp[k] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(a.cs) + (int64_t)t * a.B * H + e);
-                vct[k] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(a.cs) + (int64_t)(t + 1) * a.B * H + e);
+                vct[k] = first ? *reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(a.cs) + (int64_t)(t + 1) * a.B * H + e) : vct_next[k];
+                vct_next[k] = vcp[k];
                 vdh[k] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(a.dh_above) + (int64_t)t * a.B * H + e);
             }
         }
@@ -608,29 +627,28 @@ __global__ __launch_bounds__(512) void lstm_rows_backward_kernel(RowsBwdArgs a) 
         for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
         if (active && !first) {
             // dh_rec = dA_{t+1} U for this block of units: four register sets of one half chunk each
-            auto load = [&](u32x4 (&ra)[2], u32x4 (&rb)[2], int q) {
-                const int g = q & 3, hq = q >> 2, c = hq >> 1, hf = hq & 1;
-                const int chunk = g * a.nkc + c;
+            auto loadA = [&](u32x4 (&ra)[2], int q) {
+                const int chunk = (q & 3) * a.nkc + (q >> 3), hf = (q >> 2) & 1;
 #pragma unroll
-                for (int k2 = 0; k2 < 2; ++k2) {
-                    rb[k2] = UT[(int64_t)chunk * (B_CHUNK / 8) + (hf * 2 + k2) * 256];
-                    ra[k2] = Ad[(chunk * 4 + hf * 2 + k2) * 64];
-                }
+                for (int k2 = 0; k2 < 2; ++k2) ra[k2] = Ad[(chunk * 4 + hf * 2 + k2) * 64];
             };
             auto mm = [&](const u32x4 (&ra)[2], const u32x4 (&rb)[2]) {
 #pragma unroll
                 for (int k2 = 0; k2 < 2; ++k2) acc = Lp<T>::mfma(ra[k2], rb[k2], acc);
             };
-            u32x4 ra0[2], ra1[2], ra2[2], ra3[2], rb0[2], rb1[2], rb2[2], rb3[2];
-            load(ra0, rb0, 0); load(ra1, rb1, 1); load(ra2, rb2, 2); load(ra3, rb3, 3);
+            u32x4 ra0[2], ra1[2], ra2[2], ra3[2];
+            loadA(ra0, 0); loadA(ra1, 1); loadA(ra2, 2); loadA(ra3, 3);      // their weights are already in rb0 .. rb3
             int s = 0;
             for (; s + 8 <= nq; s += 4) {              // nq is a multiple of four; branch-free body
-                mm(ra0, rb0); load(ra0, rb0, s + 4);
-                mm(ra1, rb1); load(ra1, rb1, s + 5);
-                mm(ra2, rb2); load(ra2, rb2, s + 6);
-                mm(ra3, rb3); load(ra3, rb3, s + 7);
+                mm(ra0, rb0); loadB(rb0, s + 4); loadA(ra0, s + 4);
+                mm(ra1, rb1); loadB(rb1, s + 5); loadA(ra1, s + 5);
+                mm(ra2, rb2); loadB(rb2, s + 6); loadA(ra2, s + 6);
+                mm(ra3, rb3); loadB(rb3, s + 7); loadA(ra3, s + 7);
             }
-            mm(ra0, rb0); mm(ra1, rb1); mm(ra2, rb2); mm(ra3, rb3);
+            mm(ra0, rb0); loadB(rb0, 0);               // the next step's first weights travel during this step's epilogue
+            mm(ra1, rb1); loadB(rb1, 1);
+            mm(ra2, rb2); loadB(rb2, 2);
+            mm(ra3, rb3); loadB(rb3, 3);
         }
         __syncthreads();                               // every wavefront has read dA_{t+1}: the buffer may take dA_t
         if (active) {
