@@ -811,7 +811,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
         }
         char *dablk = p.blk ? at(scratch, p.wb ? p.s_wb_dablk[l] : p.s_dablk) : nullptr;
         const bool fused_step = fused && !p.wb && step_backward_fused_supported(p.dtype, p.B, p.H) && (dA_rm || dablk);
-        const bool rows_bwd = fused_step && rows_backward_supported(p.dtype, p.B, p.H);
+        const bool rows_bwd = fused && !p.wb && rows_backward_supported(p.dtype, p.B, p.H) && (dA_rm || dablk);
         if (rows_bwd) {
             // every workgroup walks its 32 rows back through all T steps: one launch for the layer
             RowsBackward r{};

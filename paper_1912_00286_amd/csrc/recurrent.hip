@@ -1448,7 +1448,14 @@ RecurrentDims recurrent_dims(int B, int H) {
 // and their small tiles re-read the operands too often once the batch is in the thousands (measured
 // against the two-launch form: ahead or level for H <= 768 up to batch 4096 at H = 200..256, 1.6x behind
 // at H = 2048, 12 % behind at H = 200 with 8192 rows).
-static bool narrow_cells(const RecurrentDims &d, int H) { return H % 8 == 0 && H <= 768 && d.n_mt * d.n_hb <= 512; }
+// Shapes whose recurrences run as one launch per layer and direction (lstm_rows_*_kernel): at most eight blocks of
+// 32 units, and enough 32-row groups to occupy the chip (measured against one launch per cell, 2 x 200 units,
+// T = 128: 1024 rows 5.5 vs 3.4 ms per step, 2048 rows 6.4 vs 6.2, 4096 rows 8.4 vs 11.5, 6144 rows 10.7 vs 15.5).
+// (Stacks of very narrow layers with at most 128 workgroups per cell keep the anti-diagonal schedule.)
+static bool rows_shape(const RecurrentDims &d, int H) {
+    return H % 8 == 0 && d.n_hb <= 8 && d.nkc <= 4 && d.n_mt >= 48 && d.n_mt * d.n_hb > 128;
+}
+static bool narrow_cells(const RecurrentDims &d, int H) { return H % 8 == 0 && H <= 768 && d.n_mt * d.n_hb <= 512 && !rows_shape(d, H); }
 // Tile edge of the narrow-layer kernels: 16 while that keeps a launch (all its cells) within about 512
 // workgroups: the smaller the tile, the fewer bytes each compute unit pulls in and the shorter the launch;
 // with more cells per launch (deep stacks along the diagonals) the launch is bound by throughput and the
@@ -1643,7 +1650,7 @@ int rows_forward(int dtype, const RowsForward &x, int in_width, int T, int B, in
 bool rows_backward_supported(int dtype, int B, int H) {
     if (dtype != LSTM_DTYPE_FP16 && dtype != LSTM_DTYPE_BF16) return false;
     const RecurrentDims d = recurrent_dims(B, H);
-    return H % 8 == 0 && recurrent_wide(d) && d.n_hb <= 8 && d.nkc <= 4;
+    return H % 8 == 0 && recurrent_wide(d) && d.n_hb <= 8 && d.nkc <= 4 && (rows_shape(d, H) || backward_slices(d) == 1);
 }
 
 int rows_backward(int dtype, const RowsBackward &x, int T, int B, int H, hipStream_t s) {
