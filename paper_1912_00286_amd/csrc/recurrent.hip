@@ -29,12 +29,14 @@
 // The epilogues write the next step's A operand directly in packed order (and
 // in row-major / 64x64-blocked order for the whole-sequence GEMMs).
 //
-// Three families share those operands:
+// Four families share those operands:
 //   * the kernels above (any H; a second form, WIDE, for H <= 512 with >= 1024 rows);
 //   * their multi-cell forms (several independent (layer, time) cells per launch) for the
 //     anti-diagonal schedule of stacks of narrow layers;
 //   * the narrow-layer kernels (H <= 768, H % 8 == 0): a whole cell per launch on 16x16 or 32x32
-//     tiles, the BPTT cell with its products and gate arithmetic in ONE launch.
+//     tiles, the BPTT cell with its products and gate arithmetic in ONE launch;
+//   * the row-ownership kernels (H <= 256, from 3072 rows per step: stacked workers): a layer's whole
+//     recurrence in ONE launch per direction, a workgroup walking its 32 rows through all time steps.
 // The host wrappers at the end of the file pick the family from the shape.
 #include "kernels.h"
 
