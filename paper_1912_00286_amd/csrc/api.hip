@@ -518,9 +518,10 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
             r.Upk = upk; r.Wpk = at(scratch, p.s_pj_wpk); r.bias = b;
             r.c_state = c_state; r.gates = gates; r.c_out = cs + (size_t)BH * es; r.h_out = hs + (size_t)BH * es;
             r.h_blk = hblk ? hblk + slot : nullptr; r.slot_blk = (int64_t)(slot / es); r.blk_ncb = p.h_ncb;
-            // row-major h_t: the head reads the top layer's, the GEMMs of a plan without blocked copies every layer's;
-            // packed h_t: the layer above's input
-            r.all_h_out = (l == p.L - 1 || !p.blk) ? 1 : 0;
+            // row-major h_t: the head reads the top layer's, and this layer's dU product reads it unless it takes the
+            // blocked copy (same condition as in lstm_backward); packed h_t: the layer above's input
+            const bool u_blk = p.blk && (p.W > 1 || gemm_blocked_supported(p.dtype, p.G, p.H));
+            r.all_h_out = (l == p.L - 1 || !u_blk) ? 1 : 0;
             r.write_hpk = l + 1 < p.L ? 1 : 0;
             LSTM_TRY(rows_forward(p.dtype, r, p.in_dim[l], p.T, p.B, p.H, s));
         }

@@ -20,6 +20,8 @@ CASES = [
     ("h104_rows16384", 1, 200, 104, 3, 16384, "fp16", wl.HEAD_LAST_BCE),
     ("h200_three_layers_in40", 3, 40, 200, 4, 8192, "fp16", wl.HEAD_STEP_BCE),
     ("h232_bf16", 1, 130, 232, 3, 8192, "bf16", wl.HEAD_STEP_BCE),
+    ("h96_two_layers", 2, 8, 96, 3, 4096, "fp16", wl.HEAD_STEP_BCE),          # 4H too narrow for the blocked dU product
+    ("h136_three_layers_bf16", 3, 33, 136, 3, 6144, "bf16", wl.HEAD_STEP_BCE),
     ("rows3072_smallest_batch", 2, 64, 200, 3, 3072, "fp16", wl.HEAD_STEP_BCE),
     ("rows4100_ragged", 2, 8, 200, 2, 4100, "fp16", wl.HEAD_LAST_BCE),
 ]
