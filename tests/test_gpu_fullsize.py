@@ -91,6 +91,7 @@ TRAJECTORIES = [
     # name, L, I, H, T, B, workers, stacked into one call, steps
     ("narrow_4workers", 2, 16, 40, 10, 8, 4, False, 8),
     ("rows2048", 2, 24, 200, 4, 2048, 1, False, 4),
+    ("rows3072_one_launch_per_layer", 2, 24, 200, 4, 3072, 1, False, 4),
     ("wide_h1024", 1, 40, 1024, 3, 128, 1, False, 4),
     ("stacked_4workers", 2, 64, 200, 4, 128, 4, True, 4),
 ]

@@ -25,7 +25,7 @@ def _assert_same(a, b, what):
         assert torch.equal(a[k], b[k]), f"{what}: {k} differs between eager and graph replay"
 
 
-@pytest.mark.parametrize("name", ["jet", "text", "rows2048", "wide1024", "stacked"])
+@pytest.mark.parametrize("name", ["jet", "text", "rows2048", "rows4096", "wide1024", "stacked"])
 def test_graph_replay_matches_eager(name):
     import torch
     batched = False
@@ -33,8 +33,10 @@ def test_graph_replay_matches_eager(name):
         w = wl.CONFIGS[name].with_(seq_len=24, n_workers=2, dynamic_scale=True, loss_scale=4096.0)
     elif name == "text":
         w = wl.CONFIGS[name].with_(seq_len=40)
-    elif name == "rows2048":        # thousands of rows per step: self-projecting forward cells, one-launch BPTT steps
+    elif name == "rows2048":        # two thousand rows per step: one launch per cell on 32x32 tiles
         w = wl.Workload(name, 2, 64, 200, 6, 2048, "fp16", wl.HEAD_STEP_BCE, loss_scale=1024.0, target_p=0.4, data_seed=51, weight_seed=52)
+    elif name == "rows4096":        # a layer's whole recurrence in one launch per direction
+        w = wl.Workload(name, 2, 64, 200, 6, 4096, "fp16", wl.HEAD_STEP_BCE, loss_scale=1024.0, target_p=0.4, data_seed=57, weight_seed=58)
     elif name == "wide1024":        # wide layers: two launches per BPTT step
         w = wl.Workload(name, 2, 40, 1024, 5, 128, "bf16", wl.HEAD_STEP_MSE, target_kind="normal", data_seed=53, weight_seed=54)
     else:                           # several workers stacked into one call per direction
