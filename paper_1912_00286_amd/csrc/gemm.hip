@@ -536,6 +536,18 @@ __global__ __launch_bounds__(256) void pack_blocked_kernel(const U *src, int64_t
     }
 }
 
+// the same for 16-bit elements in 16-byte pieces (rows 16-byte aligned, C a multiple of 8): two pieces per thread
+__global__ __launch_bounds__(256) void pack_blocked_vec_kernel(const uint16_t *src, int64_t ld, int R, int C, uint16_t *dst, int ncb) {
+    const int rb = blockIdx.y, cb = blockIdx.x;
+    u32x4 *d = reinterpret_cast<u32x4 *>(dst + ((int64_t)rb * ncb + cb) * 4096);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int v = threadIdx.x + 256 * i;
+        const int r = rb * 64 + (v >> 3), c = cb * 64 + (v & 7) * 8;
+        d[v] = (r < R && c < C) ? *reinterpret_cast<const u32x4 *>(src + (int64_t)r * ld + c) : u32x4{0u, 0u, 0u, 0u};
+    }
+}
+
 // fp32 baseline-mode GEMM: 64x64 tile, 32-deep K slices, four wavefronts with one 32x32 block each on
 // v_mfma_f32_32x32x2_f32 (fp32 products, fp32 accumulate).  That instruction takes k = 0 from lanes
 // 0..31 and k = 1 from lanes 32..63; the order of k inside a slice is free as long as both operands
@@ -956,6 +968,8 @@ int pack_blocked(int dtype, const void *src, int64_t ld, int rows, int cols, voi
     KernelTimer timer(KC_AUX, stream, 0.0, 0.0);
     if (dtype == LSTM_DTYPE_FP32)
         hipLaunchKernelGGL(pack_blocked_kernel<uint32_t>, dim3(ncb, nrb), dim3(256), 0, stream, (const uint32_t *)src, ld, rows, cols, (uint32_t *)dst, ncb);
+    else if (ld % 8 == 0 && cols % 8 == 0 && ((uintptr_t)src | (uintptr_t)dst) % 16 == 0)
+        hipLaunchKernelGGL(pack_blocked_vec_kernel, dim3(ncb, nrb), dim3(256), 0, stream, (const uint16_t *)src, ld, rows, cols, (uint16_t *)dst, ncb);
     else
         hipLaunchKernelGGL(pack_blocked_kernel<uint16_t>, dim3(ncb, nrb), dim3(256), 0, stream, (const uint16_t *)src, ld, rows, cols, (uint16_t *)dst, ncb);
     LSTM_LAUNCH_CHECK();

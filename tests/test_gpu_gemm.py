@@ -81,15 +81,17 @@ def test_gemm_fp32_matches_matmul(hip):
             assert np.all(np.abs(got - ref) <= tol), float(np.max(np.abs(got - ref) - tol))
 
 
-def test_blocked_packing_layout(hip):
+@pytest.mark.parametrize("shape", [(130, 70), (130, 72), (64, 200), (1, 8)], ids=["element_wise", "vector_ragged_rows", "vector_one_row_block", "vector_tiny"])
+def test_blocked_packing_layout(hip, shape):
     import torch
     dev = torch.device("cuda:0")
-    R, C = 130, 70
-    src = torch.arange(R * C, device=dev, dtype=torch.float32).reshape(R, C).to(torch.float16)
-    dst = _blocked(hip, torch, src, 1).cpu().numpy().astype(np.float64).reshape(3, 2, 64, 64)
+    R, C = shape
+    nrb, ncb = (R + 63) // 64, (C + 63) // 64
+    src = (torch.arange(R * C, device=dev, dtype=torch.float32).reshape(R, C) % 2039).to(torch.float16)
+    dst = _blocked(hip, torch, src, 1).cpu().numpy().astype(np.float64).reshape(nrb, ncb, 64, 64)
     s = src.cpu().numpy().astype(np.float64)
-    want = np.zeros((192, 128)); want[:R, :C] = s
-    want = want.reshape(3, 64, 2, 64).transpose(0, 2, 1, 3)
+    want = np.zeros((nrb * 64, ncb * 64)); want[:R, :C] = s
+    want = want.reshape(nrb, 64, ncb, 64).transpose(0, 2, 1, 3)
     assert np.array_equal(dst, want)
 
 
