@@ -333,11 +333,13 @@ __global__ __launch_bounds__(256) void lstm_wave_forward_kernel(WaveFwdArgs w) {
 // Batch rows never interact, so a workgroup that owns 32 rows and ALL hidden units can walk them through the T
 // time steps on its own: no launch per step and nothing crosses workgroups.  Per step it contracts its rows of
 // h_{t-1} (kept in LDS in fragment order, written by its own epilogue one step earlier) with the packed U and its
-// rows of x_t (packed input sequence, from memory) with the packed W, one block of 32 units x 4 gates at a time
-// (eight wavefronts, one per block), keeps c_t in registers in the accumulator layout, and writes the saved
+// rows of x_t (packed input sequence, fetched into LDS one step ahead) with the packed W, one block of 32 units x
+// 4 gates per wavefront (eight wavefronts), keeps c_t in registers in the accumulator layout, and writes the saved
 // gates, c_t, h_t (row-major, packed for the layer above, blocked for the weight-gradient GEMMs) as it goes.
 // Workgroups drift apart in time, so the products of one run under the stores of another, which the lock-step
-// grid of a per-step launch cannot do.  Used with thousands of rows per step (stacked workers) and H <= 256.
+// grid of a per-step launch cannot do.  U and W stream from L2 every step (the half chunks of K that are all
+// padding are skipped; the first fragments of the next step are requested before the epilogue).  Used with
+// thousands of rows per step (stacked workers) and H <= 256.
 struct RowsFwdArgs {
     const void *hseq;      // packed h slots [T+1][n_mt][nkc][64][64]: slot 0 = h_0 (in), slot t + 1 = h_t (out)
     const void *xseq;      // packed input slots [T][n_mt][nkc2][64][64]
