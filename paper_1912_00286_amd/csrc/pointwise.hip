@@ -346,8 +346,14 @@ __global__ __launch_bounds__(256) void head_forward_vec_kernel(int head, const T
 __global__ __launch_bounds__(256) void loss_final_kernel(const float *partial, int n, float inv_M, float *loss, RowSeg rs) {
     __shared__ double red[256];
     double s = 0.0;
-    for (int i = threadIdx.x; i < n; i += 256)
-        if (rs.workers == 1 || (4 * i % (rs.workers * rs.seg)) / rs.seg == (int)blockIdx.x) s += (double)partial[i];
+    if (rs.workers == 1) {
+        for (int i = threadIdx.x; i < n; i += 256) s += (double)partial[i];
+    } else {
+        // this worker's rows are seg consecutive rows of every time step: seg / 4 consecutive partial sums per step
+        const int per_step = rs.seg / 4, stride = rs.workers * per_step, steps = n / stride;
+        for (int k = threadIdx.x; k < steps * per_step; k += 256)
+            s += (double)partial[(int64_t)(k / per_step) * stride + (int)blockIdx.x * per_step + k % per_step];
+    }
     red[threadIdx.x] = s;
     __syncthreads();
     for (int o = 128; o > 0; o >>= 1) {
