@@ -298,10 +298,19 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a_in, 
     KernArgs a = a_in;
     const T *A = reinterpret_cast<const T *>(a.A);
     const T *B = reinterpret_cast<const T *>(a.B);
+    int bx = blockIdx.x;
     if constexpr (SEG) {
-        // batch entry blockIdx.y: its K rows start seg_len block rows further on in both operands
+        // batch entry y: its K rows start seg_len block rows further on in both operands.  The tiles of one
+        // entry all stream the same B panel, so they should share an L2: workgroup id -> (XCD = id % 8, slot =
+        // id / 8), and an XCD's slots walk the tiles of the entries 8 k + XCD one entry after the other (plain
+        // (x, y) order puts the tiles of an entry on neighbouring XCDs and every one of them fetches the panel).
         static_assert(!SEG || (BLK && TA && TB_), "segmented K only for blocked operands in the rows-are-K role");
-        const int64_t y = blockIdx.y;
+        int64_t y = blockIdx.y;
+        if (gridDim.y % 8 == 0) {
+            const int id = (int)blockIdx.y * (int)gridDim.x + (int)blockIdx.x, slot = id >> 3;
+            bx = slot % (int)gridDim.x;
+            y = (int64_t)(slot / (int)gridDim.x) * 8 + (id & 7);
+        }
         A += y * a.seg_len * a.lda * 4096;
         B += y * a.seg_len * a.ldb * 4096;
         a.C = reinterpret_cast<char *>(a.C) + y * a.batch_c * (a.out_lp ? (int64_t)sizeof(T) : 4);
@@ -318,8 +327,8 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a_in, 
     // tile order: workgroups of one XCD (id % 8) take neighbouring tiles, and tiles
     // are walked in bands of 8 tile rows so that a band's A and B panels stay in L2
     const int total = tiles_m * tiles_n;
-    int lin = blockIdx.x;
-    if (total % 8 == 0) lin = (lin % 8) * (total / 8) + lin / 8;
+    int lin = bx;
+    if (!SEG && total % 8 == 0) lin = (lin % 8) * (total / 8) + lin / 8;
     const int band = 8 * tiles_n;
     const int b0 = (lin / band) * 8;
     const int bh = min(8, tiles_m - b0);
