@@ -1414,6 +1414,15 @@ __global__ __launch_bounds__(256) void setup_jobs_kernel(SetupArgs a) {
             const int c0 = j.cols & 63, npad = 64 - c0;
             const int64_t n = j.n_words * 64 * npad;     // row blocks x 64 rows x padding columns
             uint16_t *d = (uint16_t *)j.dst;
+            if (c0 % 8 == 0) {                           // 16-byte pieces
+                const int nv = npad / 8;
+                for (int64_t i = (int64_t)x * 256 + threadIdx.x; i < n / 8; i += (int64_t)gridDim.x * 256) {
+                    const int64_t r = i / nv;
+                    const int c = c0 + (int)(i - r * nv) * 8;
+                    *reinterpret_cast<u32x4 *>(d + ((r >> 6) * j.ncb + (j.ncb - 1)) * 4096 + (r & 63) * 64 + c) = u32x4{0u, 0u, 0u, 0u};
+                }
+                break;
+            }
             for (int64_t i = (int64_t)x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
                 const int64_t r = i / npad;              // row index over all row blocks
                 const int c = c0 + (int)(i - r * npad);
