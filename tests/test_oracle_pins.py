@@ -57,18 +57,105 @@ def test_backward_matches_central_differences(L, head, vocab):
             assert abs(fd - an) <= 1e-6 * max(1.0, abs(fd)) + 2e-8, (name, k, fd, an)
 
 
-def test_backward_fd_with_initial_state():
-    rng = np.random.default_rng(5)
-    L, T, B, I, H = 2, 3, 2, 3, 3
+@pytest.mark.parametrize("L,head", [(1, 1), (2, 3), (3, 2)])
+def test_backward_fd_with_initial_state(L, head):
+    """Central differences of S * loss over EVERY element of every tensor with a non-zero initial state:
+    the t = 0 contributions (dU from h_prev = h0, the forget-gate term dc * c0, the upper layers' own
+    h0 / c0) are part of every difference, so a wrong or dropped one fails here."""
+    rng = np.random.default_rng(50 + L)
+    T, B, I, H = 3, 2, 3, 3
     p, shapes = _rand_params(rng, L, I, H)
-    x = rng.standard_normal((T, B, I)); y = _targets(rng, 1, T, B)
-    h0 = rng.uniform(-0.5, 0.5, (L, B, H)); c0 = rng.uniform(-0.5, 0.5, (L, B, H))
-    # gradient machinery is the same; what must differ is the forward value
-    l0, _ = orc.forward(p, L, x, y, 1)
-    l1, cache = orc.forward(p, L, x, y, 1, h0, c0)
+    x = rng.standard_normal((T, B, I)); y = _targets(rng, head, T, B)
+    h0 = rng.uniform(-0.9, 0.9, (L, B, H)); c0 = rng.uniform(-1.5, 1.5, (L, B, H))
+    S = 4.0
+    l0, _ = orc.forward(p, L, x, y, head)
+    l1, cache = orc.forward(p, L, x, y, head, h0, c0)
     assert abs(l0 - l1) > 1e-6
     assert np.array_equal(cache["layers"][0]["h"][0], h0[0])
-    assert np.array_equal(cache["layers"][1]["c"][0], c0[1])
+    assert np.array_equal(cache["layers"][L - 1]["c"][0], c0[L - 1])
+    g = orc.backward(p, L, cache, S)
+    g_zero = orc.backward(p, L, orc.forward(p, L, x, y, head)[1], S)
+    eps = 1e-6
+    for name, _ in shapes:
+        flat = p[name].reshape(-1)
+        for k in range(flat.size):
+            old = flat[k]
+            flat[k] = old + eps
+            lp, _ = orc.forward(p, L, x, y, head, h0, c0)
+            flat[k] = old - eps
+            lm, _ = orc.forward(p, L, x, y, head, h0, c0)
+            flat[k] = old
+            fd = S * (lp - lm) / (2 * eps)
+            an = g[name].reshape(-1)[k]
+            assert abs(fd - an) <= 1e-6 * max(1.0, abs(fd)) + 2e-8, (name, k, fd, an)
+    # the state really enters the gradients (the pin above is not the zero-state pin in disguise)
+    for l in range(L):
+        assert np.max(np.abs(g[f"U{l}"] - g_zero[f"U{l}"])) > 1e-4
+
+
+def test_single_step_gradients_come_from_the_initial_state_only():
+    """T = 1: dU = dA^T h0 exists only because of h0, and the forget-gate rows of every gradient only
+    because of c0 (df = dc * c0).  With c0 = 0 those rows vanish exactly; with h0 = 0, dU does."""
+    rng = np.random.default_rng(61)
+    L, T, B, I, H = 1, 1, 3, 2, 4
+    p, shapes = _rand_params(rng, L, I, H)
+    x = rng.standard_normal((T, B, I)); y = _targets(rng, 3, T, B)
+    h0 = rng.uniform(-0.9, 0.9, (L, B, H)); c0 = rng.uniform(-1.5, 1.5, (L, B, H))
+    _, ca = orc.forward(p, L, x, y, 3, h0, np.zeros_like(c0))
+    ga = orc.backward(p, L, ca, 1.0)
+    assert np.all(ga["b0"][H:2 * H] == 0.0) and np.all(ga["W0"][H:2 * H] == 0.0) and np.all(ga["U0"][H:2 * H] == 0.0)
+    assert np.max(np.abs(ga["U0"][:H])) > 1e-6
+    _, cb = orc.forward(p, L, x, y, 3, np.zeros_like(h0), c0)
+    gb = orc.backward(p, L, cb, 1.0)
+    assert np.all(gb["U0"] == 0.0)
+    assert np.max(np.abs(gb["b0"][H:2 * H])) > 1e-6
+    # hand-written single cell, one sample, against the oracle's df row: df = dc * c0, da_f = df f (1 - f)
+    b = 1
+    a = p["W0"] @ x[0, b] + p["U0"] @ h0[0, b] + p["b0"]
+    i = 1 / (1 + np.exp(-a[:H])); f = 1 / (1 + np.exp(-a[H:2 * H])); gg = np.tanh(a[2 * H:3 * H]); o = 1 / (1 + np.exp(-a[3 * H:]))
+    c = f * c0[0, b] + i * gg
+    h = o * np.tanh(c)
+    z = h @ p["w_head"] + p["b_head"][0]
+    dz = 2.0 * (z - y[0, b, 0]) / (T * B)
+    dc = dz * p["w_head"] * o * (1 - np.tanh(c) ** 2)
+    da_f = dc * c0[0, b] * f * (1 - f)
+    _, cc = orc.forward(p, L, x[:, b:b + 1], y[:, b:b + 1], 3, h0[:, b:b + 1], c0[:, b:b + 1])
+    gc = orc.backward(p, L, cc, 1.0)
+    np.testing.assert_allclose(gc["b0"][H:2 * H] / B, da_f, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(gc["U0"][H:2 * H] / B, np.outer(da_f, h0[0, b]), rtol=1e-12, atol=1e-15)
+
+
+@pytest.mark.parametrize("L", [1, 2, 3])
+def test_initial_state_matches_torch_lstm_autograd(L):
+    """torch.nn.LSTM with (h0, c0) passed in, fp64, bias_hh = 0: loss, final states and every gradient."""
+    rng = np.random.default_rng(70 + L)
+    T, B, I, H = 5, 4, 3, 6
+    p, shapes = _rand_params(rng, L, I, H, scale=0.4)
+    x = rng.standard_normal((T, B, I)); y = _targets(rng, 3, T, B)
+    h0 = rng.uniform(-0.9, 0.9, (L, B, H)); c0 = rng.uniform(-1.5, 1.5, (L, B, H))
+    loss, cache = orc.forward(p, L, x, y, orc.HEAD_STEP_MSE, h0, c0)
+    g = orc.backward(p, L, cache, 2.0)
+    lstm = torch.nn.LSTM(I, H, num_layers=L, bias=True).double()
+    with torch.no_grad():
+        for l in range(L):
+            getattr(lstm, f"weight_ih_l{l}").copy_(torch.from_numpy(p[f"W{l}"]))
+            getattr(lstm, f"weight_hh_l{l}").copy_(torch.from_numpy(p[f"U{l}"]))
+            getattr(lstm, f"bias_ih_l{l}").copy_(torch.from_numpy(p[f"b{l}"]))
+            getattr(lstm, f"bias_hh_l{l}").zero_()
+    wh = torch.from_numpy(p["w_head"]).requires_grad_()
+    bh = torch.from_numpy(p["b_head"]).requires_grad_()
+    out, (hT, cT) = lstm(torch.from_numpy(x), (torch.from_numpy(h0), torch.from_numpy(c0)))
+    z = out @ wh + bh
+    tl = torch.nn.functional.mse_loss(z, torch.from_numpy(y[..., 0]))
+    (2.0 * tl).backward()
+    assert abs(loss - tl.item()) < 1e-12
+    for l in range(L):
+        np.testing.assert_allclose(cache["layers"][l]["h"][-1], hT[l].detach().numpy(), atol=1e-13)
+        np.testing.assert_allclose(cache["layers"][l]["c"][-1], cT[l].detach().numpy(), atol=1e-13)
+        np.testing.assert_allclose(g[f"W{l}"], getattr(lstm, f"weight_ih_l{l}").grad.numpy(), atol=1e-12)
+        np.testing.assert_allclose(g[f"U{l}"], getattr(lstm, f"weight_hh_l{l}").grad.numpy(), atol=1e-12)
+        np.testing.assert_allclose(g[f"b{l}"], getattr(lstm, f"bias_ih_l{l}").grad.numpy(), atol=1e-12)
+    np.testing.assert_allclose(g["w_head"], wh.grad.numpy(), atol=1e-12)
 
 
 # ---------------------------------------------------------------- library special case
