@@ -38,13 +38,13 @@
 extern "C" {
 #endif
 
-#define LSTM_ABI_VERSION 3
+#define LSTM_ABI_VERSION 4
 
 enum {
     LSTM_OK = 0,
     LSTM_ERR_INVALID = -1,      /* null pointer, misaligned buffer, bad enum or size */
     LSTM_ERR_UNSUPPORTED = -2,  /* shape or dtype this build has no kernel for */
-    LSTM_ERR_WORKSPACE = -3,    /* reserved */
+    LSTM_ERR_WORKSPACE = -3,    /* reserve_bytes / scratch_bytes below what lstm_workspace_bytes reports for the config */
     LSTM_ERR_HIP = -4           /* a HIP runtime call failed */
 };
 
@@ -136,26 +136,32 @@ int lstm_workspace_bytes(const lstm_config *cfg, size_t *reserve_bytes, size_t *
  *               (ids must lie in [0,vocab); out-of-range ids are clamped).
  *   targets   : device, fp32 [T,B,1] (per-step heads) or [B,1] (last-step).
  *   h0, c0    : device or NULL (= zeros). h0: lp[L,B,H]; c0: fp32[L,B,H].
- *   reserve   : device, out, reserve_bytes; consumed by lstm_backward.
- *   scratch   : device, scratch_bytes, contents undefined afterwards.
+ *   reserve   : device, out; consumed by lstm_backward.
+ *   scratch   : device, contents undefined afterwards.
+ *   reserve_bytes, scratch_bytes : sizes of the two buffers as allocated by the caller; when either is
+ *               below what lstm_workspace_bytes reports for cfg the call returns LSTM_ERR_WORKSPACE and
+ *               enqueues nothing (a config edited after sizing the buffers selects other kernels and
+ *               another layout).
  *   loss      : device, out, one fp32: mean of the per-output loss (unscaled).
  *   hT, cT    : device or NULL, out; final states, same shapes/types as h0, c0.
  * Per layer and step: a = W x_t + U h_{t-1} + b; i,f,o = logistic, g = tanh;
  * c_t = f c_{t-1} + i g; h_t = o tanh(c_t). */
 int lstm_forward(const lstm_config *cfg, const void *params_lp, const void *x, const float *targets,
-                 const void *h0, const float *c0, void *reserve, void *scratch, float *loss,
-                 void *hT, float *cT, void *stream);
+                 const void *h0, const float *c0, void *reserve, size_t reserve_bytes, void *scratch,
+                 size_t scratch_bytes, float *loss, void *hT, float *cT, void *stream);
 
 /* bprop by BPTT of (loss_scale * loss) (Section "Performance evaluation",
  * Eq. 6: the scalar multiplies the loss before the partial derivatives).
  *   params_lp, x, targets, reserve : as given to / produced by lstm_forward.
+ *   reserve_bytes, scratch_bytes   : as for lstm_forward (LSTM_ERR_WORKSPACE when too small).
  *   loss_scale : device, one fp32 (read on the device, no host sync).
  *   grads_lp   : device, out, lp[n_params] = loss_scale * dloss/dtheta in the
  *                parameter layout; half-precision overflow shows up as Inf.
  * Weight gradients are accumulated over all time steps in fp32 and rounded to
  * lp once. */
 int lstm_backward(const lstm_config *cfg, const void *params_lp, const void *x, const float *targets,
-                  const void *reserve, void *scratch, const float *loss_scale, void *grads_lp, void *stream);
+                  const void *reserve, size_t reserve_bytes, void *scratch, size_t scratch_bytes,
+                  const float *loss_scale, void *grads_lp, void *stream);
 
 /* Step 4 of the framework list: sum the workers' raw gradients, divide by the
  * number of workers, and undo the loss scale; also report Inf/NaN.
@@ -200,6 +206,13 @@ int master_update(int64_t n_params, const optimizer_config *opt, float lr, int64
                   float *state1, float *state2, const float *avg_grad, const int32_t *found_inf,
                   float *loss_scale, int32_t *good_steps, void *params_lp_out, int32_t dtype, void *stream);
 
+/* The last action of step 5 taken on its own: params_lp_out = round-to-nearest-even cast of the fp32
+ * master weights to the working type, which is what master_update leaves behind after every
+ * iteration.  For the first iteration, before any update has run.
+ *   master        : device, fp32[n_params].
+ *   params_lp_out : device, out, lp[n_params] (dtype = LSTM_DTYPE_*). */
+int lstm_cast_params(int64_t n_params, const float *master, void *params_lp_out, int32_t dtype, void *stream);
+
 /* Section "Learning rate schedule" (host, pure function).
  *   base = lr0 / (1 + n_workers / n_half)                      (Eq. 4)
  *   if base * n_workers > eff_lr_max: base = eff_lr_max / n_workers
@@ -209,43 +222,6 @@ int master_update(int64_t n_params, const optimizer_config *opt, float lr, int64
  * Returns 0 for invalid arguments (n_workers < 1, n_half <= 0). */
 float lr_schedule(float lr0, int32_t n_workers, float n_half, float eff_lr_max, int32_t warmup_steps,
                   float gamma, int64_t index);
-
-/* ---- diagnostics (not part of the training step) ----------------------------
- * Per-kernel-class launch timing for benchmarks.  When enabled, every launch
- * the library enqueues is bracketed by two HIP events recorded on the caller's
- * stream (events are created on first use and reused).  lstm_timing_enable
- * also clears the accumulated numbers.  lstm_timing_read waits for the
- * recorded work, then returns for one class the number of timed launches, the
- * summed event-to-event duration in ms, and the summed algorithmic flops
- * (GEMM classes: 2*M*N*K) and bytes (streaming classes) of those launches.
- * Classes: 0 whole-sequence GEMMs, 1 per-time-step recurrent GEMMs, 2 gate
- * pointwise kernels, 3 auxiliary kernels, 4 grad_average, 5 master_update.
- * All out-pointers are host memory.  Not thread-safe with respect to
- * concurrently running entry points on other threads' streams. */
-int lstm_timing_enable(int32_t on);
-int lstm_timing_read(int32_t kernel_class, int64_t *launches, double *total_ms, double *flops, double *bytes);
-
-/* One whole-sequence GEMM through the dispatch the training step uses, for kernel tests and
- * micro-benchmarks.  All pointers device.  C: lp [M,N] row-major, out.
- *   layout 0: C = A B^T, row-major A[M,K], B[N,K]
- *   layout 1: C = A^T B, row-major A[K,M], B[K,N]   (16-bit types, M, N >= 192, multiples of 8)
- *   layout 2/3/4: operands in 64x64 blocks as written by lstm_debug_pack_blocked, with
- *                 (A rows, B rows) indexing (M, N) / (M, K) / (K, K)   (16-bit types, M, N >= 192)
- * splitk_ws: fp32 [splits, M, N] or NULL with splits <= 1. */
-int lstm_debug_gemm(int32_t dtype, int32_t layout, int32_t M, int32_t N, int32_t K, const void *A, const void *B, void *C,
-                    float *splitk_ws, int32_t splits, void *stream);
-/* dst (64x64 blocks, zero padded to whole blocks: ceil(rows/64)*ceil(cols/64)*4096 elements) =
- * src (row-major [rows, cols]).  Both device. */
-/* Enqueues a loop of `iters` x 8 independent 32x32x16 MFMAs per wavefront (256 workgroups of 8
- * wavefronts) whose operands stay in registers: the rate the matrix pipes sustain on the given
- * operand values, which depends on the values through the chip's power management.
- *   operands: device, 256*512*2 fragments of 16 bytes (8 lp values each), read once
- *   sink:     device, 1 float (never written in practice)
- *   flops:    host, out (may be NULL): floating-point operations the launch performs
- * 16-bit types only; 1 <= iters <= 2^22.  The caller times the launch. */
-int lstm_debug_mfma_rate(int32_t dtype, const void *operands, int32_t iters, float *sink, double *flops, void *stream);
-
-int lstm_debug_pack_blocked(int32_t dtype, const void *src, int32_t rows, int32_t cols, void *dst, void *stream);
 
 #ifdef __cplusplus
 }

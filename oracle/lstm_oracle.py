@@ -185,11 +185,16 @@ def forward(params, num_layers, x, targets, head, h0=None, c0=None):
 # --------------------------------------------------------------------------
 # backward pass (bprop = BPTT), loss multiplied by the scale first
 # --------------------------------------------------------------------------
-def backward(params, num_layers, cache, loss_scale=1.0):
+def backward(params, num_layers, cache, loss_scale=1.0, trace=None):
     """Gradients of (loss_scale * loss) w.r.t. every parameter tensor.
 
     Returns dict name -> float64 array holding S * dloss/dtheta (the *scaled*
     raw gradient a worker would hand to the exchange step).
+
+    trace: optional dict that receives intermediates of the pass (no effect on
+    the result): "dz" [T,B] or [B], "d_top" [T,B,H] (gradient entering the top
+    layer), and per layer "da{l}" [T,B,4H], the gradient of the gate
+    pre-activations whose sums over (t, b) are the weight gradients.
     """
     T, B = cache["T"], cache["B"]
     S = float(loss_scale)
@@ -216,6 +221,11 @@ def backward(params, num_layers, cache, loss_scale=1.0):
         grads["w_head"] = np.einsum("tb,tbh->h", dz, top)
         grads["b_head"] = np.array([dz.sum()])
         d_above = dz[:, :, None] * w_head[None, None, :]
+    if trace is not None:
+        trace["dz"] = dz
+        trace["d_top"] = d_above
+        if cache["head"] == HEAD_FC_HINGE:
+            trace["d_pre"] = d_pre
     for l in range(num_layers - 1, -1, -1):
         lay = cache["layers"][l]
         W, U = params[f"W{l}"], params[f"U{l}"]
@@ -240,6 +250,8 @@ def backward(params, num_layers, cache, loss_scale=1.0):
                                  df * f * (1.0 - f),
                                  dg * (1.0 - g * g),
                                  do * o * (1.0 - o)], axis=1)   # [B,4H]
+            if trace is not None:
+                trace.setdefault(f"da{l}", np.empty((T, B, 4 * Hl)))[t] = da
             d_inp[t] = da @ W
             dh_rec = da @ U
             dW += da.T @ inp[t]
@@ -247,6 +259,8 @@ def backward(params, num_layers, cache, loss_scale=1.0):
             db += da.sum(axis=0)
         grads[f"W{l}"], grads[f"U{l}"], grads[f"b{l}"] = dW, dU, db
         d_above = d_inp
+    if trace is not None:
+        trace["d_input"] = d_above
     if cache["ids"] is not None:
         dE = np.zeros_like(params["E"])
         np.add.at(dE, cache["ids"].reshape(-1), d_above.reshape(T * B, -1))

@@ -60,8 +60,11 @@ def load_library():
     lib.lstm_param_count.argtypes = [cfgp, C.POINTER(i64)]
     lib.lstm_param_offset.argtypes = [cfgp, i32, i32, C.POINTER(i64), C.POINTER(i64)]
     lib.lstm_workspace_bytes.argtypes = [cfgp, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
-    lib.lstm_forward.argtypes = [cfgp] + [vp] * 11
-    lib.lstm_backward.argtypes = [cfgp] + [vp] * 8
+    sz = C.c_size_t
+    lib.lstm_forward.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, sz, vp, sz, vp, vp, vp, vp]
+    lib.lstm_backward.argtypes = [cfgp, vp, vp, vp, vp, sz, vp, sz, vp, vp, vp]
+    lib.lstm_cast_params.argtypes = [i64, vp, vp, i32, vp]
+    lib.lstm_debug_plan_regions.argtypes = [cfgp, i32, C.POINTER(i32), C.POINTER(sz), C.POINTER(sz), C.POINTER(i32)]
     lib.grad_average.argtypes = [i64, i32, vp, i32, vp, vp, vp, vp]
     lib.grad_average_masked.argtypes = [i64, i32, vp, i32, vp, vp, vp, vp, vp, vp]
     lib.master_update.argtypes = [i64, optp, f32, i64, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
@@ -73,8 +76,8 @@ def load_library():
     lib.lstm_timing_enable.argtypes = [i32]
     lib.lstm_timing_read.argtypes = [i32, C.POINTER(i64), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double)]
     for name in ("lstm_param_count", "lstm_param_offset", "lstm_workspace_bytes", "lstm_forward", "lstm_backward",
-                 "grad_average", "grad_average_masked", "master_update", "lstm_timing_enable", "lstm_timing_read", "lstm_debug_gemm",
-                 "lstm_debug_pack_blocked", "lstm_debug_mfma_rate"):
+                 "grad_average", "grad_average_masked", "master_update", "lstm_cast_params", "lstm_timing_enable", "lstm_timing_read",
+                 "lstm_debug_gemm", "lstm_debug_pack_blocked", "lstm_debug_mfma_rate", "lstm_debug_plan_regions"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -129,14 +132,31 @@ def lstm_workspace_bytes(cfg: LstmConfig):
     return r.value, s.value
 
 
-def lstm_forward(cfg, params_lp, x, targets, h0, c0, reserve, scratch, loss, hT=None, cT=None, stream=None):
+def _nbytes(t, given) -> int:
+    """Size in bytes of a workspace tensor; a raw address needs the size spelled out."""
+    if given is not None:
+        return int(given)
+    if t is None or isinstance(t, int):
+        return 0
+    return t.numel() * t.element_size()
+
+
+def lstm_forward(cfg, params_lp, x, targets, h0, c0, reserve, scratch, loss, hT=None, cT=None, stream=None,
+                 reserve_bytes=None, scratch_bytes=None):
     _check(load_library().lstm_forward(C.byref(cfg), _ptr(params_lp), _ptr(x), _ptr(targets), _ptr(h0), _ptr(c0),
-                                       _ptr(reserve), _ptr(scratch), _ptr(loss), _ptr(hT), _ptr(cT), _stream(stream)))
+                                       _ptr(reserve), _nbytes(reserve, reserve_bytes), _ptr(scratch),
+                                       _nbytes(scratch, scratch_bytes), _ptr(loss), _ptr(hT), _ptr(cT), _stream(stream)))
 
 
-def lstm_backward(cfg, params_lp, x, targets, reserve, scratch, loss_scale, grads_lp, stream=None):
+def lstm_backward(cfg, params_lp, x, targets, reserve, scratch, loss_scale, grads_lp, stream=None, reserve_bytes=None,
+                  scratch_bytes=None):
     _check(load_library().lstm_backward(C.byref(cfg), _ptr(params_lp), _ptr(x), _ptr(targets), _ptr(reserve),
-                                        _ptr(scratch), _ptr(loss_scale), _ptr(grads_lp), _stream(stream)))
+                                        _nbytes(reserve, reserve_bytes), _ptr(scratch), _nbytes(scratch, scratch_bytes),
+                                        _ptr(loss_scale), _ptr(grads_lp), _stream(stream)))
+
+
+def lstm_cast_params(n_params, master, params_lp_out, dtype, stream=None):
+    _check(load_library().lstm_cast_params(n_params, _ptr(master), _ptr(params_lp_out), dtype, _stream(stream)))
 
 
 def grad_average(n_params, n_workers, grads_lp, dtype, loss_scale, avg_grad, found_inf, stream=None):
@@ -191,6 +211,16 @@ def lstm_debug_pack_blocked(dtype, src, rows, cols, dst, stream=None):
     _check(load_library().lstm_debug_pack_blocked(dtype, _ptr(src), rows, cols, _ptr(dst), _stream(stream)))
 
 
+def lstm_debug_plan_regions(cfg):
+    """[(which, offset, bytes)] of the workspace plan: which = 0 reserve, 1 scratch."""
+    lib = load_library()
+    n = C.c_int32()
+    _check(lib.lstm_debug_plan_regions(C.byref(cfg), 0, None, None, None, C.byref(n)))
+    which, off, size = (C.c_int32 * n.value)(), (C.c_size_t * n.value)(), (C.c_size_t * n.value)()
+    _check(lib.lstm_debug_plan_regions(C.byref(cfg), n.value, which, off, size, C.byref(n)))
+    return [(which[i], off[i], size[i]) for i in range(n.value)]
+
+
 # --------------------------------------------------------------------------
 # buffer plumbing for a whole training step (no arithmetic here)
 # --------------------------------------------------------------------------
@@ -220,7 +250,8 @@ class TrainingStep:
         rb, sb = lstm_workspace_bytes(self.call_cfg)
         self.master = torch.as_tensor(master_fp32, dtype=torch.float32).to(self.dev).contiguous()
         assert self.master.numel() == self.P
-        self.params_lp = self.master.to(self.lp_dtype)          # storage cast only
+        self.params_lp = torch.empty(self.P, dtype=self.lp_dtype, device=self.dev)
+        lstm_cast_params(self.P, self.master, self.params_lp, cfg.dtype)      # the library's own rounding
         self.state1 = torch.zeros(self.P, dtype=torch.float32, device=self.dev)
         self.state2 = torch.zeros(self.P, dtype=torch.float32, device=self.dev) if opt.kind == OPT_ADAM else None
         self.grads = torch.zeros((self.N, self.P), dtype=self.lp_dtype, device=self.dev)

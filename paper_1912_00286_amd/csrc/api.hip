@@ -26,7 +26,13 @@ inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 // Everything derived from a config: parameter offsets (elements) and the byte
 // offsets of each region inside the caller's reserve and scratch buffers.
+struct PlanRegion {
+    int which;           // 0: reserve, 1: scratch
+    size_t offset, bytes;
+};
+
 struct Plan {
+    std::vector<PlanRegion> regions;     // every region make_plan handed out
     int L, H, T, B, G, dtype, head, V, D;   // B: rows per time step = workers * per-worker batch
     int W = 1, Bw = 0;                       // simulated workers processed together, batch of each
     size_t es;                           // bytes per lp element
@@ -141,16 +147,26 @@ int make_plan(const lstm_config *c, Plan &p) {
     p.head_rows = p.head == LSTM_HEAD_LAST_BCE ? p.B : p.T * p.B;
     // ---- reserve
     const size_t TB = (size_t)p.T * p.B;
-    size_t r = 0;
+    size_t r = 0, s = 0;
+    // every region of the two workspaces is handed out here, 256-byte aligned, and remembered, so
+    // that the plan can be checked for overlaps from the host (lstm_debug_plan_regions)
+    p.regions.clear();
+    auto take = [&](int which, size_t bytes) {
+        size_t &cur = which == 0 ? r : s;
+        const size_t off = cur;
+        if (bytes > 0) p.regions.push_back(PlanRegion{which, off, bytes});
+        cur += align_up(bytes);
+        return off;
+    };
     p.r_gates.resize(p.L); p.r_c.resize(p.L); p.r_h.resize(p.L);
     for (int l = 0; l < p.L; ++l) {
-        p.r_gates[l] = r; r += align_up(TB * p.G * p.es);
-        p.r_c[l] = r; r += align_up((TB + p.B) * p.H * p.es);
-        p.r_h[l] = r; r += align_up((TB + p.B) * p.H * p.es);
+        p.r_gates[l] = take(0, TB * p.G * p.es);
+        p.r_c[l] = take(0, (TB + p.B) * p.H * p.es);
+        p.r_h[l] = take(0, (TB + p.B) * p.H * p.es);
     }
-    p.r_xemb = r; if (p.V > 0) r += align_up(TB * p.D * p.es);
-    p.r_dzu = r; r += align_up((size_t)p.head_rows * 4);
-    p.r_fc = r; if (p.F > 0) r += align_up(TB * p.F * p.es);
+    p.r_xemb = r; if (p.V > 0) take(0, TB * p.D * p.es);
+    p.r_dzu = take(0, (size_t)p.head_rows * 4);
+    p.r_fc = r; if (p.F > 0) take(0, TB * p.F * p.es);
     // 64x64-blocked copies for the large-tile GEMMs: time slots must start on a block row
     p.blk = p.dtype != LSTM_DTYPE_FP32 && p.B % 64 == 0 && gemm_blocked_supported(p.dtype, (int)TB, p.G);
     // the blocked kernels address an operand with 32-bit element offsets: beyond that the row-major path runs
@@ -162,31 +178,30 @@ int make_plan(const lstm_config *c, Plan &p) {
     if (p.blk) {
         p.h_ncb = (p.H + 63) / 64;
         p.g_ncb = (p.G + 63) / 64;
-        for (int l = 0; l < p.L; ++l) { p.r_hblk[l] = r; r += align_up(blocked_elems((int)(TB + p.B), p.H) * p.es); }
-        p.r_xblk = r; r += align_up(blocked_elems((int)TB, p.in_dim[0]) * p.es);
+        for (int l = 0; l < p.L; ++l) { p.r_hblk[l] = take(0, blocked_elems((int)(TB + p.B), p.H) * p.es); }
+        p.r_xblk = take(0, blocked_elems((int)TB, p.in_dim[0]) * p.es);
     }
     p.reserve_bytes = r;
     // ---- scratch
-    size_t s = 0;
     int max_in = 0;
     for (int l = 0; l < p.L; ++l) max_in = p.in_dim[l] > max_in ? p.in_dim[l] : max_in;
     const int max_dim = max_in > p.H ? max_in : p.H;
-    p.s_ax = s; s += align_up(TB * p.G * 4);
-    p.s_cstate = s; s += align_up((size_t)p.B * p.H * 4);
-    p.s_losspart = s; s += align_up((size_t)head_loss_blocks(p.head_rows) * 4);
+    p.s_ax = take(1, TB * p.G * 4);
+    p.s_cstate = take(1, (size_t)p.B * p.H * 4);
+    p.s_losspart = take(1, (size_t)head_loss_blocks(p.head_rows) * 4);
     p.s_wT = s;
     p.wT_off.resize(p.L); p.uT_off.resize(p.L);
     for (int l = 0; l < p.L; ++l) {
-        p.wT_off[l] = s - p.s_wT; s += align_up((size_t)p.G * p.in_dim[l] * p.es);
-        p.uT_off[l] = s - p.s_wT; s += align_up((size_t)p.G * p.H * p.es);
+        p.wT_off[l] = take(1, (size_t)p.G * p.in_dim[l] * p.es) - p.s_wT;
+        p.uT_off[l] = take(1, (size_t)p.G * p.H * p.es) - p.s_wT;
     }
-    p.s_dA = s; s += align_up(TB * p.G * p.es);
-    p.s_dAT = s; s += align_up(TB * p.G * p.es);
-    p.s_xT = s; s += align_up(TB * max_dim * p.es);
-    p.s_dh[0] = s; s += align_up(TB * max_dim * p.es);
-    p.s_dh[1] = s; s += align_up(TB * max_dim * p.es);
-    p.s_dhrec = s; s += align_up((size_t)p.B * p.H * 4);
-    p.s_dcstate = s; s += align_up((size_t)p.B * p.H * 4);
+    p.s_dA = take(1, TB * p.G * p.es);
+    p.s_dAT = take(1, TB * p.G * p.es);
+    p.s_xT = take(1, TB * max_dim * p.es);
+    p.s_dh[0] = take(1, TB * max_dim * p.es);
+    p.s_dh[1] = take(1, TB * max_dim * p.es);
+    p.s_dhrec = take(1, (size_t)p.B * p.H * 4);
+    p.s_dcstate = take(1, (size_t)p.B * p.H * 4);
     size_t splitk = 0;
     p.split_w.resize(p.L); p.split_u.resize(p.L);
     for (int l = 0; l < p.L; ++l) {
@@ -202,25 +217,25 @@ int make_plan(const lstm_config *c, Plan &p) {
         const size_t a = p.split_fc > 1 ? (size_t)p.split_fc * p.F * p.H * 4 : 0;
         splitk = a > splitk ? a : splitk;
     }
-    p.s_splitk = s; s += align_up(splitk);
+    p.s_splitk = take(1, splitk);
     if (p.F > 0) {
-        p.s_fcd = s; s += align_up(TB * p.F * p.es);
-        p.s_fcdT = s; s += align_up(TB * p.F * p.es);
-        p.s_fcwT = s; s += align_up((size_t)p.F * p.H * p.es);
+        p.s_fcd = take(1, TB * p.F * p.es);
+        p.s_fcdT = take(1, TB * p.F * p.es);
+        p.s_fcwT = take(1, (size_t)p.F * p.H * p.es);
     }
     const int colw = (p.G > p.H ? p.G : p.H) > p.F ? (p.G > p.H ? p.G : p.H) : p.F;
-    p.s_colpart = s; s += align_up((size_t)colsum_chunks((int)(TB / p.W)) * p.W * colw * 4);
-    p.s_dE32 = s; if (p.V > 0) s += align_up((size_t)p.V * p.D * 4);
+    p.s_colpart = take(1, (size_t)colsum_chunks((int)(TB / p.W)) * p.W * colw * 4);
+    p.s_dE32 = s; if (p.V > 0) take(1, (size_t)p.V * p.D * 4);
     if (p.dtype != LSTM_DTYPE_FP32) {
         // packed operands of the fused recurrent kernels
         const RecurrentDims rd = recurrent_dims(p.B, p.H);
-        p.s_part = s; s += align_up(rd.partial_bytes);
-        p.s_upk = s; s += align_up((rd.utpk_elems > rd.upk_elems ? rd.utpk_elems : rd.upk_elems) * p.es);
-        for (int k = 0; k < 2; ++k) { p.s_apk[k] = s; s += align_up(rd.dapk_elems * p.es); }
+        p.s_part = take(1, rd.partial_bytes);
+        p.s_upk = take(1, (rd.utpk_elems > rd.upk_elems ? rd.utpk_elems : rd.upk_elems) * p.es);
+        for (int k = 0; k < 2; ++k) { p.s_apk[k] = take(1, rd.dapk_elems * p.es); }
     }
     if (p.blk) {
-        p.s_wblk = s; s += align_up(blocked_elems(p.G, max_dim) * p.es);
-        p.s_dablk = s; s += align_up(blocked_elems((int)TB, p.G) * p.es);
+        p.s_wblk = take(1, blocked_elems(p.G, max_dim) * p.es);
+        p.s_dablk = take(1, blocked_elems((int)TB, p.G) * p.es);
     }
     if (p.dtype != LSTM_DTYPE_FP32) {
         const RecurrentDims rd = recurrent_dims(p.B, p.H);
@@ -230,11 +245,11 @@ int make_plan(const lstm_config *c, Plan &p) {
         if (p.wf) {
             p.s_wf_upk.resize(p.L); p.s_wf_wpk.assign(p.L, 0); p.s_wf_c.resize(p.L); p.s_wf_hpk0.resize(p.L); p.s_wf_hpk1.resize(p.L);
             for (int l = 0; l < p.L; ++l) {
-                p.s_wf_upk[l] = s; s += align_up(rd.upk_elems * p.es);
-                if (l > 0) { p.s_wf_wpk[l] = s; s += align_up(rd.upk_elems * p.es); }
-                p.s_wf_hpk0[l] = s; s += align_up(rd.hpk_elems * p.es);
-                p.s_wf_hpk1[l] = s; s += align_up(rd.hpk_elems * p.es);
-                p.s_wf_c[l] = s; s += align_up((size_t)p.B * p.H * 4);
+                p.s_wf_upk[l] = take(1, rd.upk_elems * p.es);
+                if (l > 0) { p.s_wf_wpk[l] = take(1, rd.upk_elems * p.es); }
+                p.s_wf_hpk0[l] = take(1, rd.hpk_elems * p.es);
+                p.s_wf_hpk1[l] = take(1, rd.hpk_elems * p.es);
+                p.s_wf_c[l] = take(1, (size_t)p.B * p.H * 4);
             }
         }
         // Thousands of rows per step on narrow layers: a whole-sequence input projection is bound by writing and
@@ -245,11 +260,11 @@ int make_plan(const lstm_config *c, Plan &p) {
             int max_in = 1;
             for (int l = 0; l < p.L; ++l) max_in = p.in_dim[l] > max_in ? p.in_dim[l] : max_in;
             const size_t b_chunk = rd.upk_elems / ((size_t)rd.n_hb * rd.nkc), a_chunk = rd.hpk_elems / ((size_t)rd.n_mt * rd.nkc);
-            p.s_pj_wpk = s; s += align_up((size_t)rd.n_hb * ((max_in + 63) / 64) * b_chunk * p.es);
+            p.s_pj_wpk = take(1, (size_t)rd.n_hb * ((max_in + 63) / 64) * b_chunk * p.es);
             p.pj_slot_h = align_up(rd.hpk_elems * p.es);
             p.pj_slot_x = align_up((size_t)rd.n_mt * ((p.in_dim[0] + 63) / 64) * a_chunk * p.es);
-            p.s_pj_xseq = s; s += (size_t)p.T * p.pj_slot_x;
-            for (int k = 0; k < 2; ++k) { p.s_pj_hseq[k] = s; s += (size_t)(p.T + 1) * p.pj_slot_h; }
+            p.s_pj_xseq = take(1, (size_t)p.T * p.pj_slot_x);
+            for (int k = 0; k < 2; ++k) p.s_pj_hseq[k] = take(1, (size_t)(p.T + 1) * p.pj_slot_h);
         }
         // Narrow layers of any depth: each BPTT cell in one launch instead of two.
         const bool fb_ok = fused_backward_supported(p.dtype, p.B, p.H);
@@ -273,15 +288,15 @@ int make_plan(const lstm_config *c, Plan &p) {
             p.s_wb_dapk.resize(p.L); p.s_wb_dapk1.assign(p.L, 0); p.s_wb_partU.resize(p.L); p.s_wb_partW.assign(p.L, 0);
             p.s_wb_dc.resize(p.L);
             for (int l = 0; l < p.L; ++l) {
-                p.s_wb_dA[l] = s; if (p.dA_rowmajor_needed(l)) s += align_up(TB * p.G * p.es);
-                if (p.blk) { p.s_wb_dablk[l] = s; s += align_up(blocked_elems((int)TB, p.G) * p.es); }
-                p.s_wb_utpk[l] = s; s += align_up(rd.utpk_elems * p.es);
-                if (l > 0) { p.s_wb_wtpk[l] = s; s += align_up(rd.utpk_elems * p.es); }
-                p.s_wb_dapk[l] = s; s += align_up(rd.dapk_elems * p.es);
-                if (p.fb) { p.s_wb_dapk1[l] = s; s += align_up(rd.dapk_elems * p.es); }
-                p.s_wb_partU[l] = s; if (!p.fb) s += align_up(rd.partial_bytes);
-                if (l > 0 && !p.fb) { p.s_wb_partW[l] = s; s += align_up(rd.partial_bytes); }
-                p.s_wb_dc[l] = s; s += align_up((size_t)p.B * p.H * 4);
+                p.s_wb_dA[l] = s; if (p.dA_rowmajor_needed(l)) take(1, TB * p.G * p.es);
+                if (p.blk) { p.s_wb_dablk[l] = take(1, blocked_elems((int)TB, p.G) * p.es); }
+                p.s_wb_utpk[l] = take(1, rd.utpk_elems * p.es);
+                if (l > 0) { p.s_wb_wtpk[l] = take(1, rd.utpk_elems * p.es); }
+                p.s_wb_dapk[l] = take(1, rd.dapk_elems * p.es);
+                if (p.fb) { p.s_wb_dapk1[l] = take(1, rd.dapk_elems * p.es); }
+                p.s_wb_partU[l] = s; if (!p.fb) take(1, rd.partial_bytes);
+                if (l > 0 && !p.fb) { p.s_wb_partW[l] = take(1, rd.partial_bytes); }
+                p.s_wb_dc[l] = take(1, (size_t)p.B * p.H * 4);
             }
         }
     }
@@ -401,11 +416,22 @@ extern "C" int lstm_workspace_bytes(const lstm_config *cfg, size_t *reserve_byte
     return LSTM_OK;
 }
 
+// the caller's buffers against the plan: an undersized workspace is refused before anything is enqueued
+static int check_workspace(const Plan &p, size_t reserve_bytes, size_t scratch_bytes) {
+    if (reserve_bytes < p.reserve_bytes || scratch_bytes < p.scratch_bytes) {
+        set_error("workspace too small for this config: reserve %zu of %zu bytes, scratch %zu of %zu bytes (see lstm_workspace_bytes)",
+                  reserve_bytes, p.reserve_bytes, scratch_bytes, p.scratch_bytes);
+        return LSTM_ERR_WORKSPACE;
+    }
+    return LSTM_OK;
+}
+
 extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const void *x, const float *targets,
-                            const void *h0, const float *c0, void *reserve, void *scratch, float *loss, void *hT,
-                            float *cT, void *stream) {
+                            const void *h0, const float *c0, void *reserve, size_t reserve_bytes, void *scratch,
+                            size_t scratch_bytes, float *loss, void *hT, float *cT, void *stream) {
     Plan p;
     LSTM_TRY(make_plan(cfg, p));
+    LSTM_TRY(check_workspace(p, reserve_bytes, scratch_bytes));
     LSTM_TRY(check_ptr(params_lp, "params_lp"));
     LSTM_TRY(check_ptr(x, "x"));
     LSTM_TRY(check_ptr(targets, "targets"));
@@ -623,9 +649,11 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
 }
 
 extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, const void *x, const float *targets,
-                             const void *reserve, void *scratch, const float *loss_scale, void *grads_lp, void *stream) {
+                             const void *reserve, size_t reserve_bytes, void *scratch, size_t scratch_bytes,
+                             const float *loss_scale, void *grads_lp, void *stream) {
     Plan p;
     LSTM_TRY(make_plan(cfg, p));
+    LSTM_TRY(check_workspace(p, reserve_bytes, scratch_bytes));
     LSTM_TRY(check_ptr(params_lp, "params_lp"));
     LSTM_TRY(check_ptr(x, "x"));
     LSTM_TRY(check_ptr(reserve, "reserve"));
@@ -960,6 +988,34 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
         LSTM_TRY(fill_u32(dE32, 0, (int64_t)p.V * p.D, s));
         LSTM_TRY(embed_scatter_add(p.dtype, (const int32_t *)x, dh_above, dE32, TB, p.V, p.D, s));
         LSTM_TRY(cast_f32_to_lp(p.dtype, dE32, grd + p.off_E * es, (int64_t)p.V * p.D, s));
+    }
+    return LSTM_OK;
+}
+
+// Step 11 of the iteration taken on its own: the working copy as the round-to-nearest-even cast of the
+// fp32 master weights (what master_update leaves behind after every step), for the first step.
+extern "C" int lstm_cast_params(int64_t n_params, const float *master, void *params_lp_out, int32_t dtype, void *stream) {
+    if (n_params < 1 || dtype < LSTM_DTYPE_FP32 || dtype > LSTM_DTYPE_BF16) {
+        set_error("lstm_cast_params: bad n_params %lld or dtype %d", (long long)n_params, dtype);
+        return LSTM_ERR_INVALID;
+    }
+    LSTM_TRY(check_ptr(master, "master"));
+    LSTM_TRY(check_ptr(params_lp_out, "params_lp_out"));
+    return cast_f32_to_lp(dtype, master, params_lp_out, n_params, (hipStream_t)stream);
+}
+
+// Diagnostic: the regions of the workspace plan, for overlap checks on the host.
+extern "C" int lstm_debug_plan_regions(const lstm_config *cfg, int32_t max_regions, int32_t *which, size_t *offsets,
+                                       size_t *bytes, int32_t *count) {
+    Plan p;
+    LSTM_TRY(make_plan(cfg, p));
+    if (!count || (max_regions > 0 && (!which || !offsets || !bytes))) {
+        set_error("lstm_debug_plan_regions: null output");
+        return LSTM_ERR_INVALID;
+    }
+    *count = (int32_t)p.regions.size();
+    for (int i = 0; i < (int)p.regions.size() && i < max_regions; ++i) {
+        which[i] = p.regions[i].which; offsets[i] = p.regions[i].offset; bytes[i] = p.regions[i].bytes;
     }
     return LSTM_OK;
 }

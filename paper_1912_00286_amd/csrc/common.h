@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "../../include/lstm_mi355.h"
+#include "../../include/lstm_mi355_debug.h"
 
 namespace lstm {
 

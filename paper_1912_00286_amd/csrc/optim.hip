@@ -306,7 +306,8 @@ extern "C" int master_update(int64_t n_params, const optimizer_config *opt, floa
         u.inv_bc2 = (float)(1.0 / (1.0 - pow((double)opt->beta2, (double)step)));
     }
     // algorithmic traffic per parameter: read master, state(s), gradient; write master, state(s), working copy
-    const double per_param = (opt->kind == LSTM_OPT_ADAM ? 5.0 : 3.0) * 4.0 + 4.0 + (double)dtype_size(dtype);
+    // SGD: 3 reads + 2 writes of fp32 (20 B) + the working copy; Adam: 4 reads + 3 writes (28 B) + the working copy
+    const double per_param = (opt->kind == LSTM_OPT_ADAM ? 7.0 : 5.0) * 4.0 + (double)dtype_size(dtype);
     KernelTimer timer(KC_UPDATE, s, 0.0, (double)n_params * per_param);
     if (n_params > 0) {
         const int grid = grid_for(n_params / 4 + 1);

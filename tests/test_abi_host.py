@@ -12,7 +12,7 @@ import workloads as wl
 from oracle import lstm_oracle as orc
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "lstm_mi355.h")
+HEADERS = [os.path.join(ROOT, "include", "lstm_mi355.h"), os.path.join(ROOT, "include", "lstm_mi355_debug.h")]
 
 
 @pytest.fixture(scope="module")
@@ -26,7 +26,7 @@ def hip():
 
 
 def _declared_functions():
-    text = open(HEADER).read()
+    text = "".join(open(h).read() for h in HEADERS)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"^\s*(?:const\s+)?(?:int|float|char)\s*\*?\s*(\w+)\s*\(", text, flags=re.M)
     return sorted(set(names))
@@ -36,12 +36,14 @@ def test_header_symbols_are_exported(hip):
     names = _declared_functions()
     for expected in ("lstm_forward", "lstm_backward", "grad_average", "master_update", "lr_schedule",
                      "lstm_param_count", "lstm_param_offset", "lstm_workspace_bytes", "lstm_abi_version",
-                     "lstm_last_error"):
+                     "lstm_last_error", "lstm_cast_params", "grad_average_masked", "lstm_debug_plan_regions", "lstm_timing_read"):
         assert expected in names
     lib = hip.load_library()
     for n in names:
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
-    assert hip.lstm_abi_version() == 3
+    assert hip.lstm_abi_version() == 4
+    # the product header declares no diagnostic
+    assert "lstm_debug" not in open(HEADERS[0]).read() and "lstm_timing" not in open(HEADERS[0]).read()
 
 
 def _cfg(hip, w):
@@ -125,11 +127,27 @@ def test_invalid_arguments_are_rejected_on_the_host(hip):
     with pytest.raises(hip.LstmError):
         hip.lstm_param_offset(cfg, 0, 0)         # no embedding in this config
     # null / misaligned device pointers are refused before anything is enqueued
+    big = dict(reserve_bytes=1 << 30, scratch_bytes=1 << 30)
     with pytest.raises(hip.LstmError):
-        hip.lstm_forward(cfg, 0, 0, 0, None, None, 0, 0, 0, stream=0)
+        hip.lstm_forward(cfg, 0, 0, 0, None, None, 0, 0, 0, stream=0, **big)
     with pytest.raises(hip.LstmError) as e:
-        hip.lstm_forward(cfg, 4096 + 2, 4096, 4096, None, None, 4096, 4096, 4096, stream=0)
+        hip.lstm_forward(cfg, 4096 + 2, 4096, 4096, None, None, 4096, 4096, 4096, stream=0, **big)
     assert "aligned" in str(e.value)
+    # a workspace one byte short of the plan is refused with its own status, in both directions
+    r, s = hip.lstm_workspace_bytes(cfg)
+    for rb, sb in ((r - 1, s), (r, s - 1), (0, 0)):
+        with pytest.raises(hip.LstmError) as e:
+            hip.lstm_forward(cfg, 4096, 4096, 4096, None, None, 4096, 4096, 4096, stream=0, reserve_bytes=rb, scratch_bytes=sb)
+        assert e.value.status == -3 and "workspace too small" in str(e.value)
+        with pytest.raises(hip.LstmError) as e:
+            hip.lstm_backward(cfg, 4096, 4096, 4096, 4096, 4096, 4096, 4096, stream=0, reserve_bytes=rb, scratch_bytes=sb)
+        assert e.value.status == -3
+    # buffers sized for one config do not serve an edited one that plans a larger workspace
+    bigger = _cfg(hip, w)
+    bigger.batch = 64
+    with pytest.raises(hip.LstmError) as e:
+        hip.lstm_forward(bigger, 4096, 4096, 4096, None, None, 4096, 4096, 4096, stream=0, reserve_bytes=r, scratch_bytes=s)
+    assert e.value.status == -3
     with pytest.raises(hip.LstmError):
         hip.grad_average(10, 0, 4096, 1, 4096, 4096, 4096, stream=0)
     opt = hip.OptimizerConfig(kind=9)
@@ -183,3 +201,43 @@ def test_bench_helpers_do_not_load_the_oracle():
     _, _, tail = bench.partition("def cpu_baseline")
     # the only import of the oracle in bench.py sits inside cpu_baseline()
     assert bench.count("from oracle import") == 1 and "from oracle import" in tail.split("\ndef ")[0]
+
+
+def _plan_grid():
+    """One or more shapes per kernel family and layout the plan chooses between."""
+    out = []
+    for dtype in ("fp32", "fp16", "bf16"):
+        for L in (1, 2, 3, 5):
+            for H in (8, 33, 200, 256, 264, 776, 1032, 2048):
+                for T, B in ((1, 1), (3, 17), (4, 64), (5, 128), (2, 1024), (3, 3072), (2, 8192)):
+                    if H >= 1032 and B > 1024:
+                        continue
+                    for head, I, V in ((wl.HEAD_STEP_BCE, 24, 0), (wl.HEAD_LAST_BCE, 0, 50), (wl.HEAD_FC_HINGE, 9, 0)):
+                        out.append(wl.Workload("grid", L, I, H, T, B, dtype, head, vocab=V, embed_dim=16 if V else 0,
+                                               fc_units=20 if head == wl.HEAD_FC_HINGE else 0))
+    return out
+
+
+def test_workspace_regions_are_disjoint_and_inside_the_reported_sizes(hip):
+    """Every region the plan hands out (saved activations, packed operands, partial sums, per-layer
+    buffers of the diagonal schedules, ...) lies inside the size lstm_workspace_bytes reports and
+    overlaps no other region of the same buffer, over a grid of shapes that reaches every kernel
+    family; with several workers stacked into one call too."""
+    checked = 0
+    cases = [(w, 1) for w in _plan_grid()]
+    cases += [(wl.Workload("stk", L, 24, H, 4, B, "fp16", wl.HEAD_STEP_BCE), W) for L in (1, 2) for H in (56, 200, 520)
+              for B in (64, 128) for W in (2, 16, 64)]
+    cases += [(w, 1) for w in wl.CONFIGS.values()] + [(wl.CONFIGS["workers64"], 64)]
+    for w, workers in cases:
+        cfg = _cfg(hip, w)
+        cfg.workers = workers
+        r, s = hip.lstm_workspace_bytes(cfg)
+        regions = hip.lstm_debug_plan_regions(cfg)
+        assert regions, w
+        for which, total in ((0, r), (1, s)):
+            spans = sorted((off, off + size) for k, off, size in regions if k == which)
+            assert all(a % 256 == 0 for a, _ in spans)
+            assert all(b <= total for _, b in spans), (w, workers, which)
+            assert all(spans[i][1] <= spans[i + 1][0] for i in range(len(spans) - 1)), (w, workers, which)
+        checked += 1
+    assert checked > 1000

@@ -30,27 +30,25 @@ def test_config4_large_fp16_dynamic_scale(hip):
     assert gpu["scales"][0] == 32768.0
 
 
-def test_config4_large_bf16_short_sequence(hip):
-    """The 88 M-parameter model in bfloat16 without loss scaling (the variant the paper's
-    precision study points to), 8 of the 128 time steps so that the fp64 oracle stays short.
-    Criterion: loss within 1e-3, every gradient tensor within 2e-2 in the relative L2 norm.
-    (With an 8-bit significand the largest single-element error of one bias gradient,
-    relative to that tensor's largest element, comes out at 2.4e-2; it is printed, and
-    bounded at twice the tolerance.)"""
-    w = wl.CONFIGS["large"].with_(dtype="bf16", loss_scale=1.0, dynamic_scale=False, seq_len=8, name="large_bf16_T8")
-    print("[case] large bf16 T=8: HIP step", flush=True)
+def test_config4_large_bf16_full_length(hip):
+    """The 88 M-parameter model in bfloat16 without loss scaling (the variant the paper's precision study
+    points to) at the full 128 time steps, against the oracle run in full.  Loss within 1e-3, every gradient
+    tensor within 2e-2 per tensor; a bias gradient (sums of 32768 cancelling terms under the zero-mean
+    squared-error derivative) may exceed that on single elements and must then stay inside the rounding
+    bound derived from the terms of its sums, which is printed."""
+    w = wl.CONFIGS["large"].with_(dtype="bf16", loss_scale=1.0, dynamic_scale=False, name="large_bf16")
+    print("[case] large bf16: HIP step", flush=True)
     gpu = pu.run_gpu_step(w)
-    print("[case] large bf16 T=8: oracle", flush=True)
-    ref = pu.run_oracle_step(w)
-    tol = pu.GRAD_RTOL["bf16"]
+    print("[case] large bf16: oracle", flush=True)
+    ref = pu.run_oracle_step(w, with_terms=True)
     assert gpu["found_inf"] == [0]
-    assert abs(gpu["losses"][0] - ref["losses"][0]) <= pu.LOSS_RTOL * abs(ref["losses"][0])
     errs = pu.tensor_errors(gpu["grads"][0], ref["grads"][0], ref["shapes"])
-    print("[case] large bf16 T=8: (l2 rel, max rel) per tensor:", {k: (round(a, 4), round(b, 4)) for k, (a, b) in errs.items()}, flush=True)
-    assert all(l2 <= tol for l2, _ in errs.values()), errs
-    assert all(mx <= 2 * tol for _, mx in errs.values()), errs
-    dW = ref["master"] - gpu["master0"]
-    assert np.all(np.abs(gpu["master"] - ref["master"]) <= 2 * tol * np.max(np.abs(dW)) + 1.2e-7 * np.abs(ref["master"]) + 1e-12)
+    print("[case] large bf16: (l2 rel, max rel) per tensor:", {k: (round(a, 4), round(b, 4)) for k, (a, b) in errs.items()}, flush=True)
+    used = []
+    pu.assert_step_close(w, gpu, ref, used)
+    print("[case] large bf16: rounding bound needed for", [(what, name, err) for what, name, err, _ in used], flush=True)
+    # only sums over all T*B rows of one column (the bias gradients) may need it
+    assert all(name.startswith("b") for _, name, _, _ in used), used
 
 
 def test_config5_sixty_four_workers(hip):

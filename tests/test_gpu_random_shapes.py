@@ -11,6 +11,20 @@ from tests import parity_util as pu
 pytestmark = pytest.mark.gpu
 
 
+def _check(w):
+    """2e-2 (1e-4 in fp32) per tensor; a 16-bit tensor beyond that must stay inside the rounding bound
+    derived from the terms of its sums, and the same shape must then pass in fp32 at 1e-4."""
+    got = pu.run_gpu_step(w)
+    want = pu.run_oracle_step(w, with_terms=True)
+    used = []
+    pu.assert_step_close(w, got, want, used)
+    if used:
+        print("  rounding bound needed for:", [(what, name, tuple(round(e, 4) for e in err), round(kappa / pu.GRAD_RTOL[w.dtype], 1))
+                                                for what, name, err, kappa in used[:6]], flush=True)
+        w32 = w.with_(dtype="fp32", loss_scale=1.0)
+        pu.assert_step_close(w32, pu.run_gpu_step(w32), pu.run_oracle_step(w32))
+
+
 def _draw(seed):
     rng = np.random.default_rng(9000 + seed)
     dtype = ["fp16", "bf16", "fp32"][int(rng.integers(0, 3))]
@@ -28,16 +42,10 @@ def _draw(seed):
     else:
         kw = dict(target_p=0.4)
     if head == wl.HEAD_FC_HINGE:
-        dtype = "fp32"          # hinge and ReLU have kinks: a sample that 16-bit rounding moves across one changes its whole gradient
-    if dtype == "bf16":
-        # 8-bit significands: measured errors are 8-10x those of fp16 on the same model (0.1-0.5 % there),
-        # so narrow stacks of three or four layers, or bias gradients that sum a few dozen cancelling
-        # terms, pass 2e-2 through the storage rounding alone: keep bf16 draws at one or two layers
-        # and give the sums enough terms
-        L = min(L, 2)
-        B = int(rng.choice([64, 70, 128]))
-        T = max(T, 3)
-        H = max(H, 24)
+        # Hinge and ReLU are decisions: a sample that 16-bit rounding moves across a kink changes a whole
+        # term of every gradient below it, which no rounding bound covers.  The 16-bit runs of this head
+        # are the fixed cases of test_gpu_paper_head.py; the random draws keep it in fp32.
+        dtype = "fp32"
     scale = 1.0 if dtype != "fp16" else float(rng.choice([64.0, 1024.0]))
     return wl.Workload(f"rnd{seed}", L, I, H, T, B, dtype, head, loss_scale=scale, data_seed=700 + seed, weight_seed=800 + seed, **kw)
 
@@ -47,9 +55,7 @@ def test_random_configuration(seed):
     w = _draw(seed)
     print(f"[case] rnd{seed}: L={w.num_layers} I={w.input_dim} H={w.hidden} T={w.seq_len} B={w.batch} {w.dtype} head={w.head} "
           f"F={w.fc_units}", flush=True)
-    got = pu.run_gpu_step(w)
-    want = pu.run_oracle_step(w)
-    pu.assert_step_close(w, got, want)
+    _check(w)
 
 
 def _draw_narrow(seed):
@@ -64,11 +70,6 @@ def _draw_narrow(seed):
     I = int(rng.choice([3, 8, 24, 64]))
     head = int(rng.choice([wl.HEAD_STEP_BCE, wl.HEAD_LAST_BCE, wl.HEAD_STEP_MSE]))
     kw = dict(target_kind="normal") if head == wl.HEAD_STEP_MSE else dict(target_p=0.4)
-    if dtype == "bf16":
-        L = min(L, 2)
-        B = max(B, 64)
-        T = max(T, 3)
-        H = max(H, 40)
     scale = 1.0 if dtype != "fp16" else float(rng.choice([64.0, 1024.0]))
     return wl.Workload(f"nar{seed}", L, I, H, T, B, dtype, head, loss_scale=scale, data_seed=1700 + seed, weight_seed=1800 + seed, **kw)
 
@@ -77,9 +78,7 @@ def _draw_narrow(seed):
 def test_random_narrow_configuration(seed):
     w = _draw_narrow(seed)
     print(f"[case] nar{seed}: L={w.num_layers} I={w.input_dim} H={w.hidden} T={w.seq_len} B={w.batch} {w.dtype} head={w.head}", flush=True)
-    got = pu.run_gpu_step(w)
-    want = pu.run_oracle_step(w)
-    pu.assert_step_close(w, got, want)
+    _check(w)
 
 
 def _draw_wide(seed):
@@ -94,8 +93,6 @@ def _draw_wide(seed):
     I = int(rng.choice([3, 8, 24, 64, 130]))
     head = int(rng.choice([wl.HEAD_STEP_BCE, wl.HEAD_LAST_BCE, wl.HEAD_STEP_MSE]))
     kw = dict(target_kind="normal") if head == wl.HEAD_STEP_MSE else dict(target_p=0.4)
-    if dtype == "bf16":
-        L = 1; B = max(B, 64); T = max(T, 3)
     scale = 1.0 if dtype != "fp16" else float(rng.choice([64.0, 1024.0]))
     return wl.Workload(f"wide{seed}", L, I, H, T, B, dtype, head, loss_scale=scale, data_seed=2700 + seed, weight_seed=2800 + seed, **kw)
 
@@ -104,9 +101,7 @@ def _draw_wide(seed):
 def test_random_wide_configuration(seed):
     w = _draw_wide(seed)
     print(f"[case] wide{seed}: L={w.num_layers} I={w.input_dim} H={w.hidden} T={w.seq_len} B={w.batch} {w.dtype} head={w.head}", flush=True)
-    got = pu.run_gpu_step(w)
-    want = pu.run_oracle_step(w)
-    pu.assert_step_close(w, got, want)
+    _check(w)
 
 
 def _draw_many_rows(seed):
@@ -122,8 +117,6 @@ def _draw_many_rows(seed):
     I = int(rng.choice([3, 8, 24, 64, 200]))
     head = int(rng.choice([wl.HEAD_STEP_BCE, wl.HEAD_LAST_BCE, wl.HEAD_STEP_MSE]))
     kw = dict(target_kind="normal") if head == wl.HEAD_STEP_MSE else dict(target_p=0.4)
-    if dtype == "bf16":
-        L = min(L, 2); T = max(T, 3); H = max(H, 40)
     scale = 1.0 if dtype != "fp16" else float(rng.choice([64.0, 1024.0]))
     return wl.Workload(f"rows{seed}", L, I, H, T, B, dtype, head, loss_scale=scale, data_seed=3700 + seed, weight_seed=3800 + seed, **kw)
 
@@ -132,6 +125,4 @@ def _draw_many_rows(seed):
 def test_random_many_rows_configuration(seed):
     w = _draw_many_rows(seed)
     print(f"[case] rows{seed}: L={w.num_layers} I={w.input_dim} H={w.hidden} T={w.seq_len} B={w.batch} {w.dtype} head={w.head}", flush=True)
-    got = pu.run_gpu_step(w)
-    want = pu.run_oracle_step(w)
-    pu.assert_step_close(w, got, want)
+    _check(w)

@@ -652,3 +652,38 @@ def test_fc_head_parameter_count():
     # Fig. 2: 2 x LSTM(200) on 9 features, FC(200) + ReLU, 1 output
     n = orc.param_count(2, 9, 200, 0, 0, 200)
     assert n == 4 * 200 * (9 + 200) + 800 + 4 * 200 * 400 + 800 + 200 * 200 + 200 + 200 + 1
+
+
+# ---------------------------------------------------------------- the intermediates the rounding bound is built from
+@pytest.mark.parametrize("head,vocab", [(1, 0), (3, 0), (2, 7), (4, 0)])
+def test_trace_terms_add_up_to_the_gradients(head, vocab):
+    """backward(trace=...) hands out da per layer; the weight gradients are its sums over the T*B rows
+    (dW = da^T x, dU = da^T h_prev, db = sum da), and the sums of absolute terms the parity tests derive
+    their rounding bound from can never be smaller than the gradient itself."""
+    import workloads as wl
+    from tests import parity_util as pu
+    rng = np.random.default_rng(90 + head)
+    L, T, B, I, H, F = 2, 4, 3, 5, 4, 3
+    shapes = orc.param_shapes(L, I, H, vocab, 6 if vocab else 0, F if head == 4 else 0)
+    p = {n: rng.uniform(-0.5, 0.5, s) for n, s in shapes}
+    x = rng.integers(0, vocab, (T, B)) if vocab else rng.standard_normal((T, B, I))
+    y = np.where(rng.random((T, B, 1)) < 0.5, 1.0, -1.0) if head == 4 else _targets(rng, head, T, B)
+    _, cache = orc.forward(p, L, x, y, head)
+    trace = {}
+    g = orc.backward(p, L, cache, 3.0, trace)
+    g_plain = orc.backward(p, L, cache, 3.0)
+    for k in g:
+        np.testing.assert_array_equal(g[k], g_plain[k])         # tracing changes nothing
+    for l in range(L):
+        da = trace[f"da{l}"].reshape(T * B, 4 * H)
+        lay = cache["layers"][l]
+        np.testing.assert_allclose(da.T @ lay["inp"].reshape(T * B, -1), g[f"W{l}"], rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(da.T @ lay["h"][:-1].reshape(T * B, -1), g[f"U{l}"], rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(da.sum(axis=0), g[f"b{l}"], rtol=1e-12, atol=1e-14)
+    w = wl.Workload("t", L, I, H, T, B, "bf16", head, vocab=vocab, embed_dim=6 if vocab else 0, fc_units=F if head == 4 else 0)
+    A, X = pu.term_magnitudes(w, p, cache, trace)
+    for name, _ in shapes:
+        assert A[name].shape == g[name].shape
+        assert np.all(A[name] >= np.abs(g[name]) - 1e-12), name
+    bound = pu.rounding_bound(w, orc.flatten(A, shapes), orc.flatten({n: X.get(n, np.zeros(s)) for n, s in shapes}, shapes), 3.0, shapes)
+    assert bound.shape == (sum(int(np.prod(s)) for _, s in shapes),) and np.all(bound >= 0)
