@@ -150,6 +150,20 @@ int lstm_forward(const lstm_config *cfg, const void *params_lp, const void *x, c
                  const void *h0, const float *c0, void *reserve, size_t reserve_bytes, void *scratch,
                  size_t scratch_bytes, float *loss, void *hT, float *cT, void *stream);
 
+/* lstm_forward for callers that cannot allocate device memory or pass a workspace along: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * kernels and results as lstm_forward, except that the scratch workspace is a buffer of
+ * LSTM_STATIC_SCRATCH_BYTES built into the library's device image (one copy per GPU, held until the
+ * process ends); the call allocates and frees nothing.  A config whose scratch requirement
+ * (lstm_workspace_bytes) exceeds that size is refused with LSTM_ERR_WORKSPACE.  All calls on one GPU
+ * share the buffer: calls that overlap in time on the same GPU (different streams or threads) race;
+ * order them on one stream.  The buffer keeps the last call's contents, which never enter a result
+ * (every element a kernel reads was written by the same call first). */
+#define LSTM_STATIC_SCRATCH_BYTES (32u << 20)
+int lstm_forward_static_scratch(const lstm_config *cfg, const void *params_lp, const void *x, const float *targets,
+                                const void *h0, const float *c0, void *reserve, size_t reserve_bytes, float *loss,
+                                void *hT, float *cT, void *stream);
+
 /* bprop by BPTT of (loss_scale * loss) (Section "Performance evaluation",
  * Eq. 6: the scalar multiplies the loss before the partial derivatives).
  *   params_lp, x, targets, reserve : as given to / produced by lstm_forward.

@@ -63,6 +63,8 @@ def load_library():
     sz = C.c_size_t
     lib.lstm_forward.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, sz, vp, sz, vp, vp, vp, vp]
     lib.lstm_backward.argtypes = [cfgp, vp, vp, vp, vp, sz, vp, sz, vp, vp, vp]
+    lib.lstm_forward_static_scratch.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp]
+    lib.lstm_forward_static_scratch.restype = C.c_int
     lib.lstm_cast_params.argtypes = [i64, vp, vp, i32, vp]
     lib.lstm_debug_plan_regions.argtypes = [cfgp, i32, C.POINTER(i32), C.POINTER(sz), C.POINTER(sz), C.POINTER(i32)]
     lib.grad_average.argtypes = [i64, i32, vp, i32, vp, vp, vp, vp]
@@ -146,6 +148,16 @@ def lstm_forward(cfg, params_lp, x, targets, h0, c0, reserve, scratch, loss, hT=
     _check(load_library().lstm_forward(C.byref(cfg), _ptr(params_lp), _ptr(x), _ptr(targets), _ptr(h0), _ptr(c0),
                                        _ptr(reserve), _nbytes(reserve, reserve_bytes), _ptr(scratch),
                                        _nbytes(scratch, scratch_bytes), _ptr(loss), _ptr(hT), _ptr(cT), _stream(stream)))
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def lstm_forward_static_scratch(cfg, params_lp, x, targets, h0, c0, reserve, loss, hT=None, cT=None, stream=None,
+                                reserve_bytes=None):
+    _check(load_library().lstm_forward_static_scratch(C.byref(cfg), _ptr(params_lp), _ptr(x), _ptr(targets), _ptr(h0),
+                                                      _ptr(c0), _ptr(reserve), _nbytes(reserve, reserve_bytes), _ptr(loss),
+                                                      _ptr(hT), _ptr(cT), _stream(stream)))
 
 
 def lstm_backward(cfg, params_lp, x, targets, reserve, scratch, loss_scale, grads_lp, stream=None, reserve_bytes=None,

@@ -5,6 +5,7 @@
 #include <stdio.h>
 
 #include <algorithm>
+#include <mutex>
 #include <vector>
 
 #include "kernels.h"
@@ -990,6 +991,57 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
         LSTM_TRY(cast_f32_to_lp(p.dtype, dE32, grd + p.off_E * es, (int64_t)p.V * p.D, s));
     }
     return LSTM_OK;
+}
+
+// ---- lstm_forward for callers that cannot allocate: the scratch workspace lives in the library's own
+// device image.  Every GPU the library runs on holds its own copy of the array at its own address;
+// the address is looked up once per device and only that pointer is ever handed to kernels.
+static __device__ __align__(256) unsigned char static_scratch[LSTM_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mu;
+void *g_static_ptr[kMaxDevices] = {};
+
+int static_scratch_address(void **out) {
+    int dev = -1;
+    LSTM_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) {
+        set_error("device index %d outside the range this build keeps static scratch addresses for", dev);
+        return LSTM_ERR_UNSUPPORTED;
+    }
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ptr[dev]) {
+        void *ptr = nullptr;
+        LSTM_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(static_scratch)));
+        if (!ptr) {
+            set_error("hipGetSymbolAddress returned a null address for the static scratch array");
+            return LSTM_ERR_HIP;
+        }
+        g_static_ptr[dev] = ptr;
+    }
+    *out = g_static_ptr[dev];
+    return LSTM_OK;
+}
+}  // namespace
+
+extern "C" int lstm_forward_static_scratch(const lstm_config *cfg, const void *params_lp, const void *x, const float *targets,
+                                           const void *h0, const float *c0, void *reserve, size_t reserve_bytes, float *loss,
+                                           void *hT, float *cT, void *stream) {
+    Plan p;
+    LSTM_TRY(make_plan(cfg, p));
+    if (p.scratch_bytes > (size_t)LSTM_STATIC_SCRATCH_BYTES) {
+        set_error("lstm_forward_static_scratch: this config needs %zu bytes of scratch, the built-in buffer holds %zu; "
+                  "use lstm_forward with a caller-provided scratch buffer",
+                  p.scratch_bytes, (size_t)LSTM_STATIC_SCRATCH_BYTES);
+        return LSTM_ERR_WORKSPACE;
+    }
+    void *scratch_ptr = nullptr;
+    LSTM_TRY(static_scratch_address(&scratch_ptr));
+    // same kernels, same order as lstm_forward; every scratch element a kernel reads is written by the
+    // library first, so what an earlier call left behind in the array never enters a result
+    return lstm_forward(cfg, params_lp, x, targets, h0, c0, reserve, reserve_bytes, scratch_ptr, (size_t)LSTM_STATIC_SCRATCH_BYTES,
+                        loss, hT, cT, stream);
 }
 
 // Step 11 of the iteration taken on its own: the working copy as the round-to-nearest-even cast of the
