@@ -60,6 +60,12 @@ struct Plan {
     bool proj = false;             // large batches of narrow layers: the input projection runs inside the step kernels
     size_t s_pj_wpk = 0, s_pj_xseq = 0, s_pj_hseq[2] = {0, 0}, pj_slot_h = 0, pj_slot_x = 0;   // bytes
     bool fb = false;               // wb with each cell's products and gate arithmetic in one launch (narrow layers)
+    // Wide layers (recurrent_tile.hip): the diagonal schedules with layer l running lag_c time steps behind the layer
+    // it depends on, so that the projection that feeds it (forward: Ax of layer l from h of layer l - 1; backward: dh
+    // of layer l from dA of layer l + 1) stays a whole-sequence GEMM over chunks of lag_c time steps
+    bool lag = false;
+    int lag_c = 32;
+    std::vector<size_t> s_lag_ax, s_lag_dx, s_lag_wblk;
     std::vector<size_t> s_wb_dapk1; // second packed dA per layer (fb: a cell reads one step's while writing the next)
     std::vector<size_t> s_wf_upk, s_wf_wpk, s_wf_c, s_wf_hpk0, s_wf_hpk1;
     // backward along anti-diagonals: per-layer dA (row-major and blocked), packed U^T / W^T, packed dA_t,
@@ -243,11 +249,28 @@ int make_plan(const lstm_config *c, Plan &p) {
         // Stacks of narrow layers: a time step of one layer is a handful of workgroups, so the
         // forward pass runs along anti-diagonals (all layers' ready cells in one launch).
         p.wf = p.L >= 2 && rd.n_mt * rd.n_hb <= 128;
+        // wide layers: a cell is hundreds of workgroups and bound by operand traffic; the tile kernels with the
+        // layers' cells sharing launches (any depth: a single layer simply has one cell per launch)
+        p.lag = !p.wf && p.W == 1 && p.blk && p.H >= 1024 && p.B >= 192 && tile_kernels_supported(p.dtype, p.B, p.H);
+        if (p.lag) {
+            p.wf = true;
+            // 32 steps: the chunk GEMMs (32 * B rows) are large enough to run near the whole-sequence rate, and the
+            // ramps at both ends of the schedule (launches with fewer cells than layers) stay short.  Measured on
+            // the 3 x 2048-unit model, T = 128, B = 256: 16 steps 24.9 ms per training step, 24: 23.9, 32: 23.7,
+            // 48: 24.2, 64: 24.7, 128 (no overlap between layers): 26.0
+            p.lag_c = p.T < 32 ? p.T : 32;
+            p.s_lag_ax.assign(p.L, 0); p.s_lag_dx.assign(p.L, 0); p.s_lag_wblk.assign(p.L, 0);
+            for (int l = 1; l < p.L; ++l) {
+                p.s_lag_ax[l] = take(1, (size_t)p.lag_c * p.B * p.G * p.es);
+                p.s_lag_dx[l - 1] = take(1, (size_t)p.lag_c * p.B * p.H * p.es);
+                p.s_lag_wblk[l] = take(1, blocked_elems(p.G, p.H) * p.es);
+            }
+        }
         if (p.wf) {
             p.s_wf_upk.resize(p.L); p.s_wf_wpk.assign(p.L, 0); p.s_wf_c.resize(p.L); p.s_wf_hpk0.resize(p.L); p.s_wf_hpk1.resize(p.L);
             for (int l = 0; l < p.L; ++l) {
                 p.s_wf_upk[l] = take(1, rd.upk_elems * p.es);
-                if (l > 0) { p.s_wf_wpk[l] = take(1, rd.upk_elems * p.es); }
+                if (l > 0 && !p.lag) { p.s_wf_wpk[l] = take(1, rd.upk_elems * p.es); }
                 p.s_wf_hpk0[l] = take(1, rd.hpk_elems * p.es);
                 p.s_wf_hpk1[l] = take(1, rd.hpk_elems * p.es);
                 p.s_wf_c[l] = take(1, (size_t)p.B * p.H * 4);
@@ -292,11 +315,11 @@ int make_plan(const lstm_config *c, Plan &p) {
                 p.s_wb_dA[l] = s; if (p.dA_rowmajor_needed(l)) take(1, TB * p.G * p.es);
                 if (p.blk) { p.s_wb_dablk[l] = take(1, blocked_elems((int)TB, p.G) * p.es); }
                 p.s_wb_utpk[l] = take(1, rd.utpk_elems * p.es);
-                if (l > 0) { p.s_wb_wtpk[l] = take(1, rd.utpk_elems * p.es); }
+                if (l > 0 && !p.lag) { p.s_wb_wtpk[l] = take(1, rd.utpk_elems * p.es); }
                 p.s_wb_dapk[l] = take(1, rd.dapk_elems * p.es);
                 if (p.fb) { p.s_wb_dapk1[l] = take(1, rd.dapk_elems * p.es); }
                 p.s_wb_partU[l] = s; if (!p.fb) take(1, rd.partial_bytes);
-                if (l > 0 && !p.fb) { p.s_wb_partW[l] = take(1, rd.partial_bytes); }
+                if (l > 0 && !p.fb && !p.lag) { p.s_wb_partW[l] = take(1, rd.partial_bytes); }
                 p.s_wb_dc[l] = take(1, (size_t)p.B * p.H * 4);
             }
         }
@@ -472,7 +495,10 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
         float *c_state = (float *)at(scratch, p.wf ? p.s_wf_c[l] : p.s_cstate);
         // input projection of the whole sequence: Ax = X W^T + b  (along the anti-diagonals only
         // layer 0 has its input ahead of time; the layers above project inside their step kernels)
-        if (p.wf && l > 0) {
+        if (p.lag && l > 0) {
+            // projected chunk by chunk between the step launches below: W in 64x64 blocks once
+            LSTM_TRY(pack_blocked(p.dtype, W, p.in_dim[l], p.G, p.in_dim[l], at(scratch, p.s_lag_wblk[l]), s));
+        } else if (p.wf && l > 0) {
             setup.pack_u_forward(W, at(scratch, p.s_wf_wpk[l]));
         } else if (p.proj) {
             // the step kernels project their own input: W packed like U; layer 0's input sequence packed step by
@@ -592,10 +618,25 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
         const int max_cells = wave_forward_max_cells();
         const size_t slot = p.blk ? (size_t)(p.B / 64) * p.h_ncb * 4096 * es : 0;
         std::vector<WaveCell> cells;
-        for (int d = 0; d < p.T + p.L - 1; ++d) {
+        // wide layers: layer l runs lag_c steps behind layer l - 1, and takes its input projection from a
+        // whole-sequence GEMM over the lag_c steps the layer below has just finished
+        const int lag = p.lag ? p.lag_c : 1, max_launch = p.lag ? tile_max_cells() : max_cells;
+        for (int d = 0; d < p.T + (p.L - 1) * lag; ++d) {
             cells.clear();
+            for (int l = 1; p.lag && l < p.L; ++l) {
+                const int t0 = d - l * lag;
+                if (t0 < 0 || t0 >= p.T || t0 % lag != 0) continue;
+                const int nt = p.T - t0 < lag ? p.T - t0 : lag;
+                BlockedGemmArgs g{};
+                g.A = BlockedOperand{at(reserve, p.r_hblk[l - 1]) + (size_t)(t0 + 1) * slot, p.h_ncb, 0};
+                g.B = BlockedOperand{at(scratch, p.s_lag_wblk[l]), (p.in_dim[l] + 63) / 64, 0};
+                g.C = at(scratch, p.s_lag_ax[l]); g.bias = par + p.off_b[l] * es; g.ldc = p.G; g.out_lp = 1;
+                g.M = nt * p.B; g.N = p.G; g.K = p.in_dim[l];
+                g.kclass = KC_GEMM_BATCHED;
+                LSTM_TRY(gemm_blocked(p.dtype, g, s));
+            }
             for (int l = 0; l < p.L; ++l) {
-                const int t = d - l;
+                const int t = d - l * lag;
                 if (t < 0 || t >= p.T) continue;
                 char *hpk[2] = {at(scratch, p.s_wf_hpk0[l]), at(scratch, p.s_wf_hpk1[l])};
                 WaveCell c{};
@@ -603,6 +644,8 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
                 c.Upk = at(scratch, p.s_wf_upk[l]);
                 if (l == 0) {
                     c.Ax = ax + (size_t)t * p.B * p.G * axs;
+                } else if (p.lag) {
+                    c.Ax = at(scratch, p.s_lag_ax[l]) + (size_t)(t % lag) * p.B * p.G * es;
                 } else {
                     // packed h_t of the layer below: written one launch ago into its buffer (t + 1) % 2
                     c.xpk = at(scratch, ((t + 1) & 1) ? p.s_wf_hpk1[l - 1] : p.s_wf_hpk0[l - 1]);
@@ -615,12 +658,13 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
                 c.h_out = at(reserve, p.r_h[l]) + (size_t)(t + 1) * BH * es;
                 c.h_blk = p.blk ? at(reserve, p.r_hblk[l]) + (size_t)(t + 1) * slot : nullptr;
                 cells.push_back(c);
-                if ((int)cells.size() == max_cells) {
-                    LSTM_TRY(step_forward_wave(p.dtype, cells.data(), (int)cells.size(), p.h_ncb, p.B, p.H, s));
+                if ((int)cells.size() == max_launch) {
+                    LSTM_TRY((p.lag ? step_forward_tile : step_forward_wave)(p.dtype, cells.data(), (int)cells.size(), p.h_ncb, p.B, p.H, s));
                     cells.clear();
                 }
             }
-            if (!cells.empty()) LSTM_TRY(step_forward_wave(p.dtype, cells.data(), (int)cells.size(), p.h_ncb, p.B, p.H, s));
+            if (!cells.empty())
+                LSTM_TRY((p.lag ? step_forward_tile : step_forward_wave)(p.dtype, cells.data(), (int)cells.size(), p.h_ncb, p.B, p.H, s));
         }
         for (int l = 0; l < p.L; ++l)
             LSTM_TRY(copy_state(p.dtype, at(reserve, p.r_h[l]) + (size_t)p.T * BH * es, (const float *)at(scratch, p.s_wf_c[l]),
@@ -746,7 +790,9 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
         SetupBatch setup;
         for (int l = 0; l < p.L; ++l) {
             setup.pack_u_backward(par + p.off_U[l] * es, at(scratch, p.s_wb_utpk[l]));
-            if (l > 0) setup.pack_u_backward(par + p.off_W[l] * es, at(scratch, p.s_wb_wtpk[l]));
+            if (l > 0 && !p.lag) setup.pack_u_backward(par + p.off_W[l] * es, at(scratch, p.s_wb_wtpk[l]));
+            if (l > 0 && p.lag)      // the chunked dX GEMMs read W in 64x64 blocks
+                LSTM_TRY(pack_blocked(p.dtype, par + p.off_W[l] * es, p.in_dim[l], p.G, p.in_dim[l], at(scratch, p.s_lag_wblk[l]), s));
             setup.zero(at(scratch, p.s_wb_dapk[l]), (int64_t)((rd.dapk_elems * es + 3) / 4));
             if (p.fb) setup.zero(at(scratch, p.s_wb_dapk1[l]), (int64_t)((rd.dapk_elems * es + 3) / 4));
             if (p.blk) setup.zero_pad(at(scratch, p.s_wb_dablk[l]), TB, p.G);
@@ -784,17 +830,39 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
                                                  p.H, s));
             }
         }
-        const int max_gates = wave_backward_max_gates(), max_gemms = wave_backward_max_gemms();
+        const int max_gates = wave_backward_max_gates(), max_gemms = p.lag ? tile_max_cells() : wave_backward_max_gemms();
         std::vector<WaveGates> gc;
         std::vector<WaveGemm> mm;
-        for (int d = 0; d < (p.fb ? 0 : p.T + p.L - 1); ++d) {
+        // wide layers: layer l runs lag_c steps behind layer l + 1 and takes the gradient from above out of a
+        // whole-sequence dX GEMM over the lag_c steps the layer above has just finished
+        const int lag = p.lag ? p.lag_c : 1;
+        const size_t slotg = p.blk ? (size_t)(p.B / 64) * p.g_ncb * 4096 * es : 0;   // bytes of one time slot of a blocked dA
+        // first time step of the chunk that holds step t of a layer below the top (chunks count from the last step)
+        auto chunk_lo = [&](int t) {
+            const int k = p.T - 1 - t, t_hi = p.T - 1 - (k - k % lag);
+            return t_hi - lag + 1 > 0 ? t_hi - lag + 1 : 0;
+        };
+        for (int d = 0; d < (p.fb ? 0 : p.T + (p.L - 1) * lag); ++d) {
             gc.clear(); mm.clear();
+            for (int l = p.L - 2; p.lag && l >= 0; --l) {
+                const int k = d - (p.L - 1 - l) * lag;
+                if (k < 0 || k >= p.T || k % lag != 0) continue;
+                const int t_hi = p.T - 1 - k, t_lo = chunk_lo(t_hi);
+                BlockedGemmArgs g{};
+                g.A = BlockedOperand{at(scratch, p.s_wb_dablk[l + 1]) + (size_t)t_lo * slotg, p.g_ncb, 0};
+                g.B = BlockedOperand{at(scratch, p.s_lag_wblk[l + 1]), (p.H + 63) / 64, 1};      // rows of W are the contraction index
+                g.C = at(scratch, p.s_lag_dx[l]); g.ldc = p.H; g.out_lp = 1;
+                g.M = (t_hi - t_lo + 1) * p.B; g.N = p.H; g.K = p.G;
+                g.kclass = KC_GEMM_BATCHED;
+                LSTM_TRY(gemm_blocked(p.dtype, g, s));
+            }
             for (int l = p.L - 1; l >= 0; --l) {
-                const int t = p.T - 1 - (d - (p.L - 1 - l));
+                const int t = p.T - 1 - (d - (p.L - 1 - l) * lag);
                 if (t < 0 || t >= p.T) continue;
                 WaveGates c{};
-                c.dh_above = l == p.L - 1 ? dh_above + (size_t)t * BH * es : nullptr;
-                c.above4 = l < p.L - 1 ? (const float *)at(scratch, p.s_wb_partW[l + 1]) : nullptr;
+                c.dh_above = l == p.L - 1 ? dh_above + (size_t)t * BH * es
+                                          : (p.lag ? at(scratch, p.s_lag_dx[l]) + (size_t)(t - chunk_lo(t)) * BH * es : nullptr);
+                c.above4 = (l < p.L - 1 && !p.lag) ? (const float *)at(scratch, p.s_wb_partW[l + 1]) : nullptr;
                 c.partials = (const float *)at(scratch, p.s_wb_partU[l]);
                 c.gates = at(reserve, p.r_gates[l]) + (size_t)t * p.B * p.G * es;
                 c.c_t = at(reserve, p.r_c[l]) + (size_t)(t + 1) * BH * es;
@@ -802,17 +870,18 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
                 c.dc_state = (float *)at(scratch, p.s_wb_dc[l]);
                 c.dA = dA_rowmajor_needed(l) ? at(scratch, p.s_wb_dA[l]) + (size_t)t * p.B * p.G * es : nullptr;
                 c.dApk = at(scratch, p.s_wb_dapk[l]);
-                c.dAblk = p.blk ? at(scratch, p.s_wb_dablk[l]) + (size_t)t * (p.B / 64) * p.g_ncb * 4096 * es : nullptr;
+                c.dAblk = p.blk ? at(scratch, p.s_wb_dablk[l]) + (size_t)t * slotg : nullptr;
                 c.first = t == p.T - 1 ? 1 : 0;
                 gc.push_back(c);
                 if (t > 0) mm.push_back(WaveGemm{c.dApk, at(scratch, p.s_wb_utpk[l]), (float *)at(scratch, p.s_wb_partU[l])});
-                if (l > 0) mm.push_back(WaveGemm{c.dApk, at(scratch, p.s_wb_wtpk[l]), (float *)at(scratch, p.s_wb_partW[l])});
+                if (l > 0 && !p.lag) mm.push_back(WaveGemm{c.dApk, at(scratch, p.s_wb_wtpk[l]), (float *)at(scratch, p.s_wb_partW[l])});
             }
             for (size_t i = 0; i < gc.size(); i += max_gates)
                 LSTM_TRY(gates_backward_wave(p.dtype, gc.data() + i, (int)std::min<size_t>(max_gates, gc.size() - i), p.g_ncb, p.B,
                                              p.H, s));
             for (size_t i = 0; i < mm.size(); i += max_gemms)
-                LSTM_TRY(step_backward_gemm_wave(p.dtype, mm.data() + i, (int)std::min<size_t>(max_gemms, mm.size() - i), p.B, p.H, s));
+                LSTM_TRY((p.lag ? step_backward_gemm_tile : step_backward_gemm_wave)(p.dtype, mm.data() + i,
+                                                                                     (int)std::min<size_t>(max_gemms, mm.size() - i), p.B, p.H, s));
         }
     }
     char *dAT = at(scratch, p.s_dAT);

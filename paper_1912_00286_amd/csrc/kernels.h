@@ -186,6 +186,12 @@ int step_backward_fused(int dtype, const FusedBackwardCell &c, int blk_ncb, int 
 int fused_backward_max_cells();
 bool fused_backward_supported(int dtype, int B, int H);
 int backward_fused_wave(int dtype, const FusedBackwardCell *c, int n_cells, int blk_ncb, int B, int H, hipStream_t s);
+// The same per-cell work on the wide-layer kernels (recurrent_tile.hip): H a multiple of 128, batch a multiple
+// of 64, 16-bit types; every cell takes a ready-made input projection (Ax).  Up to tile_max_cells() per launch.
+bool tile_kernels_supported(int dtype, int B, int H);
+int tile_max_cells();
+int step_forward_tile(int dtype, const WaveCell *cells, int n_cells, int blk_ncb, int B, int H, hipStream_t s);
+int step_backward_gemm_tile(int dtype, const WaveGemm *g, int n, int B, int H, hipStream_t s);
 int wave_forward_max_cells();
 int step_forward_wave(int dtype, const WaveCell *cells, int n_cells, int blk_ncb, int B, int H, hipStream_t s);
 

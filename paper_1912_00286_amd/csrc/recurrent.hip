@@ -39,19 +39,15 @@
 //     recurrence in ONE launch per direction, a workgroup walking its 32 rows through all time steps.
 // The host wrappers at the end of the file pick the family from the shape.
 #include "kernels.h"
+#include "packed.h"
 
 namespace lstm {
 namespace {
 
-constexpr int TM = 64;                 // batch rows per workgroup
-constexpr int NBLK = 4;                // 32-row B blocks per workgroup
-constexpr int TN = NBLK * 32;          // B rows per workgroup
-constexpr int SK = 64;                 // K elements per packed chunk
+// TM, NBLK, TN, SK, A_CHUNK, B_CHUNK, frag_offset, xcd_swizzle: packed.h
 constexpr int NLD_A = TM * SK / 8 / 64;   // 16-byte loads per lane and chunk, A operand (8)
 constexpr int NLD_B = TN * SK / 8 / 64;   // same, B operand (16)
 constexpr int RED_FLOATS = 8 * 16 * 64;   // one wavefront's 8 accumulator blocks
-constexpr int A_CHUNK = TM * SK;       // elements of one packed A block
-constexpr int B_CHUNK = TN * SK;       // elements of one packed B block
 
 // A small kernel in a chain of dependent launches starts with dependent memory round trips (arguments,
 // then operands), and the compiler fetches kernel arguments lazily, next to their first use: up to nine
@@ -59,12 +55,6 @@ constexpr int B_CHUNK = TN * SK;       // elements of one packed B block
 // makes its load issue there, together with its neighbours'.
 template <typename V>
 __device__ __forceinline__ void fetch_now(const V &v) { asm volatile("" ::"s"(v)); }
-
-// offset of element (row, kk) inside a packed chunk whose rows form `nblk` blocks of 32
-__host__ __device__ inline int frag_offset(int row, int kk, int nblk) {
-    const int blk = row >> 5, r = row & 31, ks = kk >> 4, half = (kk >> 3) & 1, j = kk & 7;
-    return (((ks * nblk + blk) * 64) + half * 32 + r) * 8 + j;
-}
 
 __device__ __forceinline__ void load_chunk(u32x4 (&ra)[NLD_A], u32x4 (&rb)[NLD_B], const u32x4 *a, const u32x4 *b, int lane) {
 #pragma unroll
@@ -152,12 +142,6 @@ __device__ __forceinline__ void reduce_waves(float *red, int wave, int lane, v16
 #pragma unroll
             for (int k = 0; k < 4; ++k) out[q * 4 + k][nb] = s[k];
         }
-}
-
-// linear tile index with workgroups of one XCD (id % 8) on neighbouring tiles,
-// so that tiles sharing B rows share that XCD's L2
-__device__ __forceinline__ int xcd_swizzle(int wg, int total) {
-    return (total % 8 == 0) ? (wg % 8) * (total / 8) + wg / 8 : wg;
 }
 
 __device__ __forceinline__ void zero_acc(v16f (&acc)[2][NBLK]) {
@@ -818,7 +802,19 @@ __device__ __forceinline__ void gates_backward_cell(const T *dh_above, const flo
     const int64_t n = (int64_t)B * H;
     const int G = 4 * H;
     const int64_t gs = (int64_t)nkc * A_CHUNK;
-    for (int64_t e0 = thread0 * W; e0 < n; e0 += nthreads * W) {
+    // Which 8 units a thread takes.  Plain: consecutive threads walk along a row.  With whole 8 x 64 patches
+    // (B % 8 == 0, H % 64 == 0) a wavefront takes 8 rows x 64 units instead, lane = row + 8 * group of 8 units:
+    // its loads and row-major stores are still whole 128-byte lines (8 lanes side by side in a row), and so are its
+    // stores into the packed copy, where a line holds one group of 8 units of 8 consecutive rows (with the plain
+    // order those eight 16-byte pieces come from eight workgroups on as many XCDs and reach memory one by one).
+    const bool patches = VEC && W == 8 && B % 8 == 0 && H % 64 == 0;
+    for (int64_t it = thread0; it * W < n; it += nthreads) {
+        int64_t e0 = it * W;
+        if (patches) {
+            const int64_t patch = it >> 6;
+            const int lane = (int)(it & 63), per_row = H >> 6;
+            e0 = ((patch / per_row) * 8 + (lane & 7)) * (int64_t)H + (patch % per_row) * 64 + (lane >> 3) * 8;
+        }
         const int b = (int)(e0 / H), j0 = (int)(e0 % H);
         __attribute__((aligned(16))) T vi[W], vf[W], vg[W], vo[W], vct[W], vcp[W], vdh[W];
         __attribute__((aligned(16))) float p0[W], p1[W], p2[W], p3[W], dcs[W];

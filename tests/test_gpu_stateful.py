@@ -90,6 +90,8 @@ STATE_CASES = [
     ("narrow", 2, 24, 200, 4, 128, "fp16"),
     ("narrow_ragged_bf16", 3, 9, 104, 4, 100, "bf16"),
     ("wide", 1, 40, 1024, 3, 128, "fp16"),
+    ("wide_tiles_two_chunks", 2, 40, 1024, 40, 256, "fp16"),
+    ("wide_tiles_64_rows_bf16", 2, 24, 1152, 3, 192, "bf16"),
     ("rows2048", 2, 64, 200, 3, 2048, "fp16"),
     ("rows1024_h520", 1, 8, 520, 3, 1024, "fp16"),
     ("odd_sizes", 2, 5, 33, 4, 17, "fp16"),

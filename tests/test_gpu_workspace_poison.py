@@ -28,6 +28,8 @@ CASES = [
     (_w("embedding", 1, 0, 256, 4, 128, "fp16", wl.HEAD_LAST_BCE, vocab=300, embed_dim=128), False),
     (_w("wide_h1024", 2, 130, 1024, 3, 256, "fp16", wl.HEAD_STEP_MSE, target_kind="normal"), False),
     (_w("wide_h1032_ragged", 1, 8, 1032, 3, 100, "fp16"), False),
+    (_w("wide_tiles_3layers", 3, 24, 1024, 36, 256, "fp16"), False),
+    (_w("wide_tiles_h1280_b192", 2, 8, 1280, 5, 192, "bf16", wl.HEAD_LAST_BCE), False),
     (_w("rows1024_h520", 2, 24, 520, 3, 1024, "fp16"), False),
     (_w("odd_sizes", 2, 5, 33, 4, 17, "fp16"), False),
     (_w("fp32_odd_sizes", 2, 5, 33, 4, 17, "fp32"), False),
