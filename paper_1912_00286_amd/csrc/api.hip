@@ -878,7 +878,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             }
             for (size_t i = 0; i < gc.size(); i += max_gates)
                 LSTM_TRY(gates_backward_wave(p.dtype, gc.data() + i, (int)std::min<size_t>(max_gates, gc.size() - i), p.g_ncb, p.B,
-                                             p.H, s));
+                                             p.H, s, p.lag ? tile_backward_slices() : 4));
             for (size_t i = 0; i < mm.size(); i += max_gemms)
                 LSTM_TRY((p.lag ? step_backward_gemm_tile : step_backward_gemm_wave)(p.dtype, mm.data() + i,
                                                                                      (int)std::min<size_t>(max_gemms, mm.size() - i), p.B, p.H, s));

@@ -167,7 +167,8 @@ struct WaveGates {
 int wave_backward_max_gemms();
 int wave_backward_max_gates();
 int step_backward_gemm_wave(int dtype, const WaveGemm *g, int n, int B, int H, hipStream_t s);
-int gates_backward_wave(int dtype, const WaveGates *c, int n_cells, int blk_ncb, int B, int H, hipStream_t s);
+// n_part: K-slice partials per cell behind WaveGates::partials (4: one per gate; 2: step_backward_gemm_tile's)
+int gates_backward_wave(int dtype, const WaveGates *c, int n_cells, int blk_ncb, int B, int H, hipStream_t s, int n_part = 4);
 // One BPTT cell done in a single launch (narrow layers): the recurrent products and the gate
 // arithmetic together.  dApk_next / UTpk: packed dA_{t+1} and U^T of the cell's layer (null at the
 // last time step); dApk_above / WTpk: packed dA_t and W^T of the layer above (null for the top
@@ -191,6 +192,8 @@ int backward_fused_wave(int dtype, const FusedBackwardCell *c, int n_cells, int 
 bool tile_kernels_supported(int dtype, int B, int H);
 int tile_max_cells();
 int step_forward_tile(int dtype, const WaveCell *cells, int n_cells, int blk_ncb, int B, int H, hipStream_t s);
+// partials[q][B,H], q < tile_backward_slices(): the contraction over the rows of the gates of slice q
+int tile_backward_slices();
 int step_backward_gemm_tile(int dtype, const WaveGemm *g, int n, int B, int H, hipStream_t s);
 int wave_forward_max_cells();
 int step_forward_wave(int dtype, const WaveCell *cells, int n_cells, int blk_ncb, int B, int H, hipStream_t s);

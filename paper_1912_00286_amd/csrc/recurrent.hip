@@ -831,8 +831,8 @@ __device__ __forceinline__ void gates_backward_cell(const T *dh_above, const flo
 #pragma unroll
                 for (int h = 0; h < W / 4; ++h) {
                     *reinterpret_cast<u32x4 *>(p0 + 4 * h) = *reinterpret_cast<const u32x4 *>(partials + e0 + 4 * h);
+                    if (n_part >= 2) *reinterpret_cast<u32x4 *>(p1 + 4 * h) = *reinterpret_cast<const u32x4 *>(partials + n + e0 + 4 * h);
                     if (n_part == 4) {
-                        *reinterpret_cast<u32x4 *>(p1 + 4 * h) = *reinterpret_cast<const u32x4 *>(partials + n + e0 + 4 * h);
                         *reinterpret_cast<u32x4 *>(p2 + 4 * h) = *reinterpret_cast<const u32x4 *>(partials + 2 * n + e0 + 4 * h);
                         *reinterpret_cast<u32x4 *>(p3 + 4 * h) = *reinterpret_cast<const u32x4 *>(partials + 3 * n + e0 + 4 * h);
                     }
@@ -845,7 +845,8 @@ __device__ __forceinline__ void gates_backward_cell(const T *dh_above, const flo
             if (dh_above) vdh[0] = dh_above[e0];
             if (!first) {
                 p0[0] = partials[e0];
-                if (n_part == 4) { p1[0] = partials[n + e0]; p2[0] = partials[2 * n + e0]; p3[0] = partials[3 * n + e0]; }
+                if (n_part >= 2) p1[0] = partials[n + e0];
+                if (n_part == 4) { p2[0] = partials[2 * n + e0]; p3[0] = partials[3 * n + e0]; }
                 dcs[0] = dc_state[e0];
             }
         }
@@ -859,7 +860,7 @@ __device__ __forceinline__ void gates_backward_cell(const T *dh_above, const flo
             if (above4) dh += (above4[e0 + k] + above4[n + e0 + k]) + (above4[2 * n + e0 + k] + above4[3 * n + e0 + k]);
             float dcr = 0.0f;
             if (!first) {
-                dh += n_part == 4 ? (p0[k] + p1[k]) + (p2[k] + p3[k]) : p0[k];
+                dh += n_part == 4 ? (p0[k] + p1[k]) + (p2[k] + p3[k]) : (n_part == 2 ? p0[k] + p1[k] : p0[k]);
                 dcr = dcs[k];
             }
             const float d_o = dh * tc;
@@ -933,6 +934,7 @@ struct WaveGateCell {
 struct WaveGateArgs {
     WaveGateCell cell[WAVE_MAX_GATES];
     int blk_ncb, B, H, nkc, blocks_per_cell;
+    int n_part;               // K-slice partials per cell: 4 (one per gate) or 2 (the wide-layer tile kernels)
 };
 template <typename T, int W>
 __global__ __launch_bounds__(256) void wave_gates_backward_kernel(WaveGateArgs w) {
@@ -941,7 +943,7 @@ __global__ __launch_bounds__(256) void wave_gates_backward_kernel(WaveGateArgs w
     const int blk = (int)blockIdx.x - ci * w.blocks_per_cell;
     gates_backward_cell<T, W>((const T *)c.dh_above, c.above4, c.partials, (const T *)c.gates, (const T *)c.c_t, (const T *)c.c_prev,
                                 c.dc_state, (T *)c.dA, (T *)c.dApk, (T *)c.dAblk, w.blk_ncb, w.B, w.H, w.nkc, c.first,
-                                blk * (int64_t)blockDim.x + threadIdx.x, (int64_t)w.blocks_per_cell * blockDim.x);
+                                blk * (int64_t)blockDim.x + threadIdx.x, (int64_t)w.blocks_per_cell * blockDim.x, w.n_part);
 }
 
 // ---------------------------------------------------------------- narrow layers
@@ -1559,10 +1561,11 @@ int step_forward_fused(int dtype, const void *hpk_prev, const void *Upk, const v
     }
     const bool wide = recurrent_wide(d);
     const int grid = d.n_mt * d.n_hb;
-    // operands once: U, h, Ax read, gates, c, h (row-major + packed [+ blocked]) written in storage, cell state fp32 both ways
+    // what the fused step has to move whatever the layout: U once; per unit the four pre-activations and c read, the four
+    // gates, c and h written (26 bytes in a 16-bit type).  The extra copies of h_t this build writes for its own
+    // consumers (packed, blocked) and the fp32 cell state are layout choices and are not counted.
     const double bh = (double)B * H;
-    KernelTimer timer(KC_GEMM_STEP, s, 2.0 * B * 4.0 * H * H,
-                      2.0 * (4.0 * H * H + bh + 4.0 * bh) + 4.0 * bh + 2.0 * (4.0 * bh + bh + (h_blk ? 3.0 : 2.0) * bh) + 4.0 * bh);
+    KernelTimer timer(KC_GEMM_STEP, s, 2.0 * B * 4.0 * H * H, 2.0 * 4.0 * H * H + 26.0 * bh);
     if (wide) {
         LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_step_forward_kernel<T, true>), dim3(grid), dim3(64), 0, s, a));
     } else {
@@ -1688,9 +1691,8 @@ int step_backward_gemm(int dtype, const void *dApk, const void *UTpk, float *par
     a.B = B; a.H = H; a.n_mt = d.n_mt; a.nkc = d.nkc; a.slices = backward_slices(d);
     const bool wide = recurrent_wide(d) && a.slices == 4;      // unsplit: the four wavefronts share the longer K range
     const int grid = d.n_mt * d.n_nt * a.slices;
-    // operands once: U^T and dA read in storage, the fp32 partial sums [slices][B,H] written
-    KernelTimer timer(KC_GEMM_STEP, s, 2.0 * B * 4.0 * H * H,
-                      2.0 * (4.0 * H * H + 4.0 * (double)B * H) + 4.0 * a.slices * (double)B * H);
+    // U and dA read once, one fp32 dh written (the K-slice partials this build writes instead are a layout choice)
+    KernelTimer timer(KC_GEMM_STEP, s, 2.0 * B * 4.0 * H * H, 2.0 * 4.0 * H * H + 12.0 * (double)B * H);
     if (wide) {
         LP_ONLY(dtype, T, hipLaunchKernelGGL((lstm_step_backward_gemm_kernel<T, true>), dim3(grid), dim3(64), 0, s, a));
     } else {
@@ -1865,8 +1867,7 @@ int step_forward_wave(int dtype, const WaveCell *cells, int n_cells, int blk_ncb
         for (int i = first; i < first + n; ++i) {
             const bool proj = !cells[i].Ax;
             flops += 2.0 * B * 4.0 * H * H * (proj ? 2.0 : 1.0);
-            bytes += 2.0 * (4.0 * H * H * (proj ? 2.0 : 1.0) + bh + (proj ? bh : 4.0 * bh)) + 4.0 * bh +
-                     2.0 * (4.0 * bh + bh + (cells[i].h_blk ? 3.0 : 2.0) * bh) + 4.0 * bh;
+            bytes += 2.0 * 4.0 * H * H * (proj ? 2.0 : 1.0) + (proj ? 20.0 : 26.0) * bh;
         }
     };
     if (narrow_cells(d, H) && all % 16 == 0) {
@@ -1913,13 +1914,13 @@ int step_backward_gemm_wave(int dtype, const WaveGemm *g, int n, int B, int H, h
         w.dApk[i] = c.dApk; w.Bpk[i] = c.Bpk; w.partials[i] = c.partials;
     }
     w.B = B; w.H = H; w.n_mt = d.n_mt; w.nkc = d.nkc; w.wgs_per_cell = d.n_mt * d.n_nt * 4;
-    KernelTimer timer(KC_GEMM_STEP, s, n * 2.0 * B * 4.0 * H * H, n * (2.0 * (4.0 * H * H + 4.0 * (double)B * H) + 16.0 * (double)B * H));
+    KernelTimer timer(KC_GEMM_STEP, s, n * 2.0 * B * 4.0 * H * H, n * (2.0 * 4.0 * H * H + 12.0 * (double)B * H));
     LP_ONLY(dtype, T, hipLaunchKernelGGL(lstm_wave_backward_gemm_kernel<T>, dim3(w.wgs_per_cell * n), dim3(256), 0, s, w));
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
 
-int gates_backward_wave(int dtype, const WaveGates *c, int n_cells, int blk_ncb, int B, int H, hipStream_t s) {
+int gates_backward_wave(int dtype, const WaveGates *c, int n_cells, int blk_ncb, int B, int H, hipStream_t s, int n_part) {
     const RecurrentDims d = recurrent_dims(B, H);
     if (n_cells < 1 || n_cells > WAVE_MAX_GATES) {
         set_error("gates_backward_wave: %d cells (1..%d)", n_cells, WAVE_MAX_GATES);
@@ -1945,8 +1946,8 @@ int gates_backward_wave(int dtype, const WaveGates *c, int n_cells, int blk_ncb,
     int blocks = (int)((items + 255) / 256);
     if (blocks > 2048) blocks = 2048;
     if (blocks < 1) blocks = 1;
-    w.blk_ncb = blk_ncb; w.B = B; w.H = H; w.nkc = d.nkc; w.blocks_per_cell = blocks;
-    KernelTimer timer(KC_POINTWISE, s, 0.0, n_cells * (double)n * (16.0 + 8.0 + 15.0 * 2.0));
+    w.blk_ncb = blk_ncb; w.B = B; w.H = H; w.nkc = d.nkc; w.blocks_per_cell = blocks; w.n_part = n_part;
+    KernelTimer timer(KC_POINTWISE, s, 0.0, n_cells * (double)n * (4.0 * n_part + 8.0 + 15.0 * 2.0));
     if (vec) {
         LP_ONLY(dtype, T, hipLaunchKernelGGL((wave_gates_backward_kernel<T, 8>), dim3(blocks * n_cells), dim3(256), 0, s, w));
     } else {

@@ -242,17 +242,22 @@ __global__ __launch_bounds__(256, 2) void lstm_tile_forward_kernel(TileFwdArgs a
 }
 
 // ---------------------------------------------------------------- backward product
+constexpr int TILE_SLICES = 4;   // K-slices of the backward product: one gate each.  Two gates each (8 bytes of partial sums
+                                 // per unit and direction instead of 16, half as many workgroups of twice the length) was
+                                 // measured on the 3 x 2048-unit model: gate kernels 2.62 -> 2.46 ms per training step, step
+                                 // kernels 10.3 -> 11.05 ms: slower in all
 struct TileBwdCell {
     const void *dApk;      // packed dA_{t+1}: [n_mt][4][nkc] chunks of 64 x 64
     const void *UTpk;      // packed U^T: [n_nt][4][nkc] chunks of 128 x 64
-    float *partials;       // fp32 [4][B,H] out: one K-slice (gate) each
+    float *partials;       // fp32 [TILE_SLICES][B,H] out: one K-slice each
 };
 struct TileBwdArgs {
     TileBwdCell cell[TILE_MAX_CELLS];
     int B, H, nkc, wgs_per_cell;
 };
 
-// partial[q][b, j] = sum over the rows k of gate q of dA_next[b, k] * U[k, j]
+// partial[q][b, j] = sum over the rows k of the gates of slice q of dA_next[b, k] * U[k, j]; the chunks of consecutive
+// gates follow each other in both packed operands, so a slice is one run of NCH = (4 / TILE_SLICES) nkc chunks
 template <typename T, int MB, int NCH>
 __global__ __launch_bounds__(256, 2) void lstm_tile_backward_kernel(TileBwdArgs a) {
     typedef TileGeo<MB> G;
@@ -261,18 +266,19 @@ __global__ __launch_bounds__(256, 2) void lstm_tile_backward_kernel(TileBwdArgs 
     const int ci = blockIdx.x / a.wgs_per_cell;
     const TileBwdCell &c = a.cell[ci];
     const int lin = xcd_swizzle((int)blockIdx.x - ci * a.wgs_per_cell, a.wgs_per_cell);
-    // gate-slice major: the workgroups of one XCD share one K slice, so that XCD's L2 pulls only that
-    // quarter of dA over the fabric
-    const int per_q = a.wgs_per_cell / 4;
+    // slice major: the workgroups of one XCD share one K slice, so that XCD's L2 pulls only that
+    // part of dA over the fabric
+    constexpr int GPS = 4 / TILE_SLICES;                            // gates per slice
+    const int per_q = a.wgs_per_cell / TILE_SLICES;
     const int q = lin / per_q, tile = lin - q * per_q;
     const int n_m2 = a.B / G::ROWS;
     const int mt2 = tile % n_m2, nt = tile / n_m2;
     v16f acc[MB];
     zero_acc<MB>(acc);
-    tile_mainloop<T, MB, NCH>(reinterpret_cast<const uint16_t *>(c.dApk) + ((int64_t)mt2 * G::TILES * 4 + q) * a.nkc * A_CHUNK,
+    tile_mainloop<T, MB, NCH>(reinterpret_cast<const uint16_t *>(c.dApk) + ((int64_t)mt2 * G::TILES * 4 + q * GPS) * a.nkc * A_CHUNK,
                          (int64_t)4 * a.nkc * A_CHUNK,
-                         reinterpret_cast<const uint16_t *>(c.UTpk) + ((int64_t)nt * 4 + q) * a.nkc * B_CHUNK + wave * 64 * 8, a.nkc, ring,
-                         wave, lane, acc);
+                         reinterpret_cast<const uint16_t *>(c.UTpk) + ((int64_t)nt * 4 + q * GPS) * a.nkc * B_CHUNK + wave * 64 * 8,
+                         GPS * a.nkc, ring, wave, lane, acc);
     float *part = c.partials + (int64_t)q * a.B * a.H + (int64_t)mt2 * G::ROWS * a.H + nt * TN + wave * 32 + (lane & 31);
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
@@ -285,14 +291,15 @@ __global__ __launch_bounds__(256, 2) void lstm_tile_backward_kernel(TileBwdArgs 
     else if (dtype == LSTM_DTYPE_BF16) { using T = bf16_t; __VA_ARGS__; }            \
     else { set_error("recurrent kernels: dtype %d is not a 16-bit type", dtype); return LSTM_ERR_UNSUPPORTED; }
 
-// Kernel instance by K chunks: the widths 1024 and 2048 get completely unrolled loops.
-#define TILE_LAUNCH(T, MB_, kernel, grid, s, a)                                                                   \
+// Kernel instance by K chunks of a workgroup's product (`mult` runs of nkc chunks): the widths 1024 and 2048 get
+// completely unrolled loops.
+#define TILE_LAUNCH(T, MB_, kernel, mult, grid, s, a)                                                             \
     do {                                                                                                          \
-        if ((a).nkc == 32) hipLaunchKernelGGL((kernel<T, MB_, 32>), grid, dim3(256), 0, s, a);                     \
-        else if ((a).nkc == 16) hipLaunchKernelGGL((kernel<T, MB_, 16>), grid, dim3(256), 0, s, a);                \
+        if ((a).nkc == 32) hipLaunchKernelGGL((kernel<T, MB_, 32 * (mult)>), grid, dim3(256), 0, s, a);            \
+        else if ((a).nkc == 16) hipLaunchKernelGGL((kernel<T, MB_, 16 * (mult)>), grid, dim3(256), 0, s, a);       \
         else hipLaunchKernelGGL((kernel<T, MB_, 0>), grid, dim3(256), 0, s, a);                                    \
     } while (0)
-#define TILE_DISPATCH(dtype, kernel, grid, s, a) LP_ONLY(dtype, T, TILE_LAUNCH(T, TILE_MB, kernel, grid, s, a))
+#define TILE_DISPATCH(dtype, kernel, mult, grid, s, a) LP_ONLY(dtype, T, TILE_LAUNCH(T, TILE_MB, kernel, mult, grid, s, a))
 
 // Rows per workgroup tile, in blocks of 32.  Measured on the 3 x 2048-unit model at batch 256 (three cells per
 // launch): 64-row tiles 10.2 ms of step kernels per training step, 128-row tiles (a third fewer bytes into the
@@ -306,6 +313,7 @@ bool tile_kernels_supported(int dtype, int B, int H) {
     return dtype != LSTM_DTYPE_FP32 && H % 128 == 0 && B % 64 == 0 && B >= 64;
 }
 int tile_max_cells() { return TILE_MAX_CELLS; }
+int tile_backward_slices() { return TILE_SLICES; }
 
 int step_forward_tile(int dtype, const WaveCell *cells, int n_cells, int blk_ncb, int B, int H, hipStream_t s) {
     if (!tile_kernels_supported(dtype, B, H) || n_cells < 1 || n_cells > TILE_MAX_CELLS) {
@@ -334,7 +342,7 @@ int step_forward_tile(int dtype, const WaveCell *cells, int n_cells, int blk_ncb
     const double bh = (double)B * H;
     KernelTimer timer(KC_GEMM_STEP, s, n_cells * 2.0 * B * 4.0 * H * H, n_cells * (2.0 * 4.0 * H * H + 26.0 * bh));
     const dim3 grid(a.wgs_per_cell * n_cells);
-    TILE_DISPATCH(dtype, lstm_tile_forward_kernel, grid, s, a);
+    TILE_DISPATCH(dtype, lstm_tile_forward_kernel, 1, grid, s, a);
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
@@ -354,11 +362,11 @@ int step_backward_gemm_tile(int dtype, const WaveGemm *g, int n, int B, int H, h
         a.cell[i] = TileBwdCell{c.dApk, c.Bpk, c.partials};
     }
     constexpr int mb = TILE_MB;
-    a.B = B; a.H = H; a.nkc = H / SK; a.wgs_per_cell = (B / (32 * mb)) * (H / TN) * 4;
+    a.B = B; a.H = H; a.nkc = H / SK; a.wgs_per_cell = (B / (32 * mb)) * (H / TN) * TILE_SLICES;
     // per product: U and dA read once, one fp32 dh written
     KernelTimer timer(KC_GEMM_STEP, s, n * 2.0 * B * 4.0 * H * H, n * (2.0 * 4.0 * H * H + 12.0 * (double)B * H));
     const dim3 grid(a.wgs_per_cell * n);
-    TILE_DISPATCH(dtype, lstm_tile_backward_kernel, grid, s, a);
+    TILE_DISPATCH(dtype, lstm_tile_backward_kernel, 4 / TILE_SLICES, grid, s, a);
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }
