@@ -44,18 +44,23 @@ def gemm_flops_per_step(w) -> float:
 def measured_traffic(workload: str, kernel_class: str):
     """HBM bytes per launch of one kernel class as measured with rocprofv3's
     FETCH_SIZE and WRITE_SIZE counters (scaled by the copy-kernel calibration);
-    read from the committed counter summary of this workload, None if there is
-    no summary for it.  Counters cannot be collected from inside this process."""
-    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.txt")
+    read from the committed counter summary of this workload, (None, None) if
+    there is no summary for it.  Counters cannot be collected from inside this
+    process: the second value says which file and which build the figure is
+    from, so that it can be told apart from what this run measured itself."""
+    rel = os.path.join("profiles", f"{workload}_hbm_traffic.txt")
+    value, build = None, "unknown build"
     try:
-        with open(path) as f:
+        with open(os.path.join(ROOT, rel)) as f:
             for line in f:
                 p = line.split()
                 if len(p) == 3 and p[0] == "class" and p[1] == kernel_class:
-                    return float(p[2])
+                    value = float(p[2])
+                if len(p) >= 3 and p[0] == "#" and p[1] == "build:":
+                    build = p[2]
     except OSError:
-        pass
-    return None
+        return None, None
+    return value, (f"{rel} (rocprofv3 counters of build {build}; not measured in this run)" if value is not None else None)
 
 
 def measured_peaks(hip, torch, dtype: str):
@@ -249,7 +254,7 @@ def main():
     if dom.startswith("gemm"):
         roof.update({"flops_per_byte": intensity, "ridge_flops_per_byte": ridge,
                      "tflops": c["flops"] / secs / 1e12, "mfma_frac": c["flops"] / secs / 1e12 / peak_fl})
-    roof["traffic"] = measured_traffic(w.name, dom)
+    roof["traffic"], roof["traffic_source"] = measured_traffic(w.name, dom)
     roof.update({"kernel_class": dom, "algorithmic_bytes_per_launch": c["bytes"] / max(c["launches"], 1), "launches_per_step": c["launches"] / args.steps, "avg_launch_us": c["avg_us"]})
     gemm_ms = classes["gemm_batched"]["total_ms"] + classes["gemm_step"]["total_ms"]
     gemm_fl = classes["gemm_batched"]["flops"] + classes["gemm_step"]["flops"]
