@@ -657,6 +657,9 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
                 c.c_out = at(reserve, p.r_c[l]) + (size_t)(t + 1) * BH * es;
                 c.h_out = at(reserve, p.r_h[l]) + (size_t)(t + 1) * BH * es;
                 c.h_blk = p.blk ? at(reserve, p.r_hblk[l]) + (size_t)(t + 1) * slot : nullptr;
+                // row-major h_t: the head reads the top layer's and the final state is copied out of the last step's;
+                // everything else on the wide-layer path reads the packed or the blocked copy
+                if (p.lag && l < p.L - 1 && t < p.T - 1 && gemm_blocked_supported(p.dtype, p.G, p.H)) c.h_out = nullptr;
                 cells.push_back(c);
                 if ((int)cells.size() == max_launch) {
                     LSTM_TRY((p.lag ? step_forward_tile : step_forward_wave)(p.dtype, cells.data(), (int)cells.size(), p.h_ncb, p.B, p.H, s));

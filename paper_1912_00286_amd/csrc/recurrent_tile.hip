@@ -151,7 +151,7 @@ struct TileFwdCell {
     const void *Ax;        // lp [B,4H]: input projection + bias of this step
     float *c_state;        // fp32 [B,H] in/out
     void *gates;           // lp [B,4H] out
-    void *c_out, *h_out;   // lp [B,H] out (row-major)
+    void *c_out, *h_out;   // lp [B,H] out (row-major); h_out may be null when only the packed / blocked copies are read
     void *hpk_next;        // packed h_t out
     void *h_blk;           // h_t out in 64x64 blocks (first block row of the time slot), or null
 };
@@ -232,7 +232,7 @@ __global__ __launch_bounds__(256, 2) void lstm_tile_forward_kernel(TileFwdArgs a
         *reinterpret_cast<v4f *>(c.c_state + row * H + j8 + 4) = *reinterpret_cast<const v4f *>(cn + 4);
         *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(c.c_out) + row * H + j8) = *reinterpret_cast<const u32x4 *>(oc);
         const u32x4 h8 = *reinterpret_cast<const u32x4 *>(oh);
-        *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(c.h_out) + row * H + j8) = h8;
+        if (c.h_out) *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(c.h_out) + row * H + j8) = h8;
         // the next step's A operand: 8 units of a row are one 16-byte slot of the fragment order
         *reinterpret_cast<u32x4 *>(reinterpret_cast<T *>(c.hpk_next) + ((row >> 6) * a.nkc + (j8 >> 6)) * A_CHUNK +
                                    frag_offset((int)(row & 63), j8 & 63, 2)) = h8;
@@ -324,7 +324,7 @@ int step_forward_tile(int dtype, const WaveCell *cells, int n_cells, int blk_ncb
     uintptr_t all = 0;
     for (int i = 0; i < TILE_MAX_CELLS; ++i) {
         const WaveCell &c = cells[i < n_cells ? i : 0];
-        if (!c.hpk_prev || !c.Upk || !c.Ax || !c.c_state || !c.gates || !c.c_out || !c.h_out || !c.hpk_next) {
+        if (!c.hpk_prev || !c.Upk || !c.Ax || !c.c_state || !c.gates || !c.c_out || !c.hpk_next || (!c.h_out && !c.h_blk)) {
             set_error("step_forward_tile: null operand in cell %d", i);
             return LSTM_ERR_INVALID;
         }
