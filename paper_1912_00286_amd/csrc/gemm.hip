@@ -214,6 +214,18 @@ __device__ __forceinline__ u32x4 read_frag_tr(const uint16_t *tile, int m0, int 
     return __builtin_bit_cast(u32x4, both);
 }
 
+// The same for the 16x16x32 MFMA (lane = 16 * (k / 8) + row): rows m0 .. m0 + 15 of the [k][m] tile, 32-deep step q.
+// Each 16-lane group reads 4 k-rows x 16 columns per instruction and receives column (lane % 16) of them.
+__device__ __forceinline__ u32x4 read_frag_tr16(const uint16_t *tile, int m0, int q, int lane) {
+    const int g = lane >> 4, i = lane & 15;
+    const uint16_t *p = tile + (q * 32 + 8 * g + (i >> 2)) * GLDT + m0 + 4 * (i & 3);
+    typedef __attribute__((address_space(3))) v4s *lds_v4s;
+    const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)p);
+    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(p + 4 * GLDT));
+    struct { v4s l, h; } both = {lo, hi};
+    return __builtin_bit_cast(u32x4, both);
+}
+
 // Result tile of the large-tile kernels: bias, then split-K partials, 16-bit or fp32 result.
 // MI: 32-row MFMA blocks per wavefront; wavefront (wm, wn) owns rows (wm MI + i) 32.., columns wn 128...
 template <typename T, int MI, int GTHREADS>
@@ -283,6 +295,68 @@ __device__ __forceinline__ void big_epilogue(const KernArgs &a, BigSmem &sm, v16
     }
 }
 
+// The same for the 16x16x32 accumulators: block (i, j) of a wavefront's 64 x 128 = rows 16 i + 4 (lane / 16) + r,
+// column 16 j + lane % 16.
+template <typename T, int GTHREADS>
+__device__ __forceinline__ void big_epilogue16(const KernArgs &a, BigSmem &sm, v4f (&acc)[4][8], int m0, int n0, int wm, int wn,
+                                               int lane, int tid) {
+    const int col_l = lane & 15, rgrp = (lane >> 4) * 4;
+    const T *bias = reinterpret_cast<const T *>(a.bias);
+    if (a.out_lp && !a.ws && a.vec_out) {
+        constexpr int OLD = GBN + 8;                       // staging row pitch (elements)
+        T *stage = reinterpret_cast<T *>(&sm);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int cl = wn * 128 + j * 16 + col_l;
+            const int col = n0 + cl;
+            const float bv = (bias && col < a.N) ? Lp<T>::to_f(bias[col]) : 0.0f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) stage[(wm * 64 + i * 16 + rgrp + r) * OLD + cl] = Lp<T>::from_f(acc[i][j][r] + bv);
+        }
+        __syncthreads();
+        T *C = reinterpret_cast<T *>(a.C);
+#pragma unroll 4
+        for (int v = tid; v < GBM * (GBN / 8); v += GTHREADS) {
+            const int rl = v / (GBN / 8), cl = (v % (GBN / 8)) * 8;
+            const int row = m0 + rl, col = n0 + cl;
+            if (row >= a.M || col >= a.N) continue;
+            const u32x4 val = *reinterpret_cast<const u32x4 *>(&stage[rl * OLD + cl]);
+            if (col + 8 <= a.N) {
+                *reinterpret_cast<u32x4 *>(&C[(int64_t)row * a.ldc + col]) = val;
+            } else {
+                T e[8];
+                __builtin_memcpy(e, &val, 16);
+                for (int q = 0; q < a.N - col; ++q) C[(int64_t)row * a.ldc + col + q] = e[q];
+            }
+        }
+        return;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int col = n0 + wn * 128 + j * 16 + col_l;
+        if (col >= a.N) continue;
+        const float bv = (bias && blockIdx.z == 0) ? Lp<T>::to_f(bias[col]) : 0.0f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = m0 + wm * 64 + i * 16 + rgrp + r;
+                if (row >= a.M) continue;
+                const float v = acc[i][j][r] + bv;
+                if (a.ws) {
+                    a.ws[((int64_t)blockIdx.z * a.M + row) * a.N + col] = v;
+                } else if (a.out_lp) {
+                    reinterpret_cast<T *>(a.C)[(int64_t)row * a.ldc + col] = Lp<T>::from_f(v);
+                } else {
+                    float *c = reinterpret_cast<float *>(a.C) + (int64_t)row * a.ldc + col;
+                    *c = a.accumulate ? (*c + v) : v;
+                }
+            }
+    }
+}
+
 // TA / TB_: operand A / B is in the transposed role (its rows are the contraction index).
 // BLK: operands are stored in 64x64 blocks ([row block][column block][64][64], zero padded to
 //      whole blocks; lda / ldb then hold the number of column blocks per row block and K is a
@@ -337,13 +411,16 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a_in, 
     const int kbeg = blockIdx.z * a.k_chunk;
     const int kend = min(a.K, kbeg + a.k_chunk);
 
-    v16f acc[MI][4];
+    // 16x16x32 MFMAs: block (i, j) of the wavefront's 64 x 128.  Per flop this form moves half as many accumulator
+    // registers as the 32x32x16 one, and on real (non-constant) operands, where the clock is set by the power cap,
+    // that is worth more than anything the schedule can win (register-resident loops: 2.03 against 1.70 PFLOP/s).
+    v4f acc[4][8];
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 8; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
 
     // Per-thread element offsets of the vectors this thread copies for K tile 0 (32-bit: the
     // host checks that both operands span less than 2^31 elements) and the step to the next
@@ -360,8 +437,10 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a_in, 
                 const int xb = x0 / 64 + v / 512, nxb = (extent + 63) / 64;
                 const int xbc = xb < nxb ? xb : 0;
                 const int ncb = (int)ld;
-                o[i] = trans ? (uint32_t)(((kbeg / 64) * ncb + xbc) * 4096 + (v % 512) * 8)
-                             : (uint32_t)((xbc * ncb + kbeg / 64) * 4096 + (v % 512) * 8);
+                // block offset only (the same for the whole workgroup: it stays in scalar registers); the thread's
+                // vector inside the block, tid * 8 elements, is added at the access
+                static_assert(!BLK || GTHREADS == 512, "vector v % 512 of a block is the thread's own");
+                o[i] = (uint32_t)__builtin_amdgcn_readfirstlane(trans ? ((kbeg / 64) * ncb + xbc) * 4096 : (xbc * ncb + kbeg / 64) * 4096);
             } else if (trans) {
                 const int krow = v / GVPK, xv = (v % GVPK) * 8;
                 o[i] = (uint32_t)((kbeg + krow) * ld + (x0 + xv < extent ? x0 + xv : 0));
@@ -379,12 +458,15 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a_in, 
     const int ntiles = (klen + GBK - 1) / GBK;
     const int nfull = klen / GBK;                  // tiles that lie wholly inside the K range
 
+    const uint32_t lane_el = BLK ? (uint32_t)tid * 8u : 0u;
+    auto src_a = [&](int i, uint32_t add) { return reinterpret_cast<const u32x4 *>(A + (oa[i] + add) + lane_el); };
+    auto src_b = [&](int i, uint32_t add) { return reinterpret_cast<const u32x4 *>(B + (ob[i] + add) + lane_el); };
     u32x4 a0[GNV], b0r[GNV], a1[GNV], b1r[GNV];    // register set 0 and 1
     auto gload_full = [&](u32x4 (&ra)[GNV], u32x4 (&rb)[GNV], int tile) {
 #pragma unroll
         for (int i = 0; i < GNV; ++i) {
-            ra[i] = *reinterpret_cast<const u32x4 *>(A + (oa[i] + (TA ? krow(tile) : (uint32_t)tile) * step_a));
-            rb[i] = *reinterpret_cast<const u32x4 *>(B + (ob[i] + (TB_ ? krow(tile) : (uint32_t)tile) * step_b));
+            ra[i] = *src_a(i, (TA ? krow(tile) : (uint32_t)tile) * step_a);
+            rb[i] = *src_b(i, (TB_ ? krow(tile) : (uint32_t)tile) * step_b);
         }
     };
     auto gload_any = [&](u32x4 (&ra)[GNV], u32x4 (&rb)[GNV], int tile) {   // also the last, partial tile
@@ -394,9 +476,9 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a_in, 
             // first k of this vector inside the tile (blocked operands are padded: always inside)
             const int ka = BLK ? 0 : (TA ? v / GVPK : (v % GVPR) * 8);
             const int kb = BLK ? 0 : (TB_ ? v / GVPK : (v % GVPR) * 8);
-            ra[i] = tile * GBK + ka < klen ? *reinterpret_cast<const u32x4 *>(A + (oa[i] + (TA ? krow(tile) : (uint32_t)tile) * step_a))
+            ra[i] = tile * GBK + ka < klen ? *src_a(i, (TA ? krow(tile) : (uint32_t)tile) * step_a)
                                            : u32x4{0u, 0u, 0u, 0u};
-            rb[i] = tile * GBK + kb < klen ? *reinterpret_cast<const u32x4 *>(B + (ob[i] + (TB_ ? krow(tile) : (uint32_t)tile) * step_b))
+            rb[i] = tile * GBK + kb < klen ? *src_b(i, (TB_ ? krow(tile) : (uint32_t)tile) * step_b)
                                            : u32x4{0u, 0u, 0u, 0u};
         }
     };
@@ -415,29 +497,36 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a_in, 
             *reinterpret_cast<u32x4 *>(&sm.b[buf][lds_off(TB_, i)]) = rb[i];
         }
     };
-    const int lrow = lane & 31, lk = (lane >> 5) * 8;
-    // k-steps [ks0, ks1) of the tile in LDS buffer `buf`
-    auto compute = [&](int buf, int ks0, int ks1) {
+    const int lrow = lane & 15, lk = (lane >> 4) * 8;
+    // fragments of 32-deep step q: A rows (wm 64 + 16 i ..), B rows (wn 128 + 16 j ..)
+    auto frag_a = [&](int buf, int i, int q) -> u32x4 {
+        if constexpr (TA) return read_frag_tr16(sm.a[buf], wm * 64 + i * 16, q, lane);
+        else return *reinterpret_cast<const u32x4 *>(&sm.a[buf][(wm * 64 + i * 16 + lrow) * GLD + lk + q * 32]);
+    };
+    auto frag_b = [&](int buf, int j, int q) -> u32x4 {
+        if constexpr (TB_) return read_frag_tr16(sm.b[buf], wn * 128 + j * 16, q, lane);
+        else return *reinterpret_cast<const u32x4 *>(&sm.b[buf][(wn * 128 + j * 16 + lrow) * GLD + lk + q * 32]);
+    };
+    // half steps [h0, h1) of the tile in LDS buffer `buf`: half step h = 32-deep step h / 2, column blocks 4 (h % 2) ..
+    auto compute = [&](int buf, int h0, int h1) {
+        u32x4 fa[4];
 #pragma unroll
-        for (int ks = ks0; ks < ks1; ++ks) {
-            u32x4 fa[MI], fb[4];
+        for (int h = h0; h < h1; ++h) {
+            const int q = h >> 1, nh = h & 1;
+            u32x4 fb[4];
+            if (nh == 0 || h == h0) {
 #pragma unroll
-            for (int i = 0; i < MI; ++i) {
-                if constexpr (TA) fa[i] = read_frag_tr(sm.a[buf], (wm * MI + i) * 32, ks, lane);
-                else fa[i] = *reinterpret_cast<const u32x4 *>(&sm.a[buf][((wm * MI + i) * 32 + lrow) * GLD + lk + ks * 16]);
+                for (int i = 0; i < 4; ++i) fa[i] = frag_a(buf, i, q);
             }
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if constexpr (TB_) fb[j] = read_frag_tr(sm.b[buf], wn * 128 + j * 32, ks, lane);
-                else fb[j] = *reinterpret_cast<const u32x4 *>(&sm.b[buf][(wn * 128 + j * 32 + lrow) * GLD + lk + ks * 16]);
-            }
+            for (int j = 0; j < 4; ++j) fb[j] = frag_b(buf, nh * 4 + j, q);
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
+            for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = Lp<T>::mfma(fa[i], fb[j], acc[i][j]);
+                for (int j = 0; j < 4; ++j) acc[i][nh * 4 + j] = Lp<T>::mfma16(fa[i], fb[j], acc[i][nh * 4 + j]);
         }
     };
-    constexpr int KS = GBK / 16;
+    constexpr int KS = GBK / 16;                  // half steps per tile (16 MFMAs per wavefront each)
 
     if (ntiles > 0) {
         // prologue: tile 0 -> LDS buffer 0, tile 1 -> set 1, tile 2 -> set 0
@@ -466,28 +555,26 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a_in, 
             auto pp_tile = [&](int buf, u32x4 (&ra)[GNV], u32x4 (&rb)[GNV], int tile_next) {
                 const uint32_t next_a = (TA ? krow(tile_next) : (uint32_t)tile_next) * step_a;
                 const uint32_t next_b = (TB_ ? krow(tile_next) : (uint32_t)tile_next) * step_b;
+                u32x4 fa[4];
 #pragma unroll
                 for (int ks = 0; ks < GBK / 16; ++ks) {
-                    u32x4 fa[MI], fb[4];
+                    const int q = ks >> 1, nh = ks & 1;
+                    u32x4 fb[4];
+                    if (nh == 0) {
 #pragma unroll
-                    for (int i = 0; i < MI; ++i) {
-                        if constexpr (TA) fa[i] = read_frag_tr(sm.a[buf], (wm * MI + i) * 32, ks, lane);
-                        else fa[i] = *reinterpret_cast<const u32x4 *>(&sm.a[buf][((wm * MI + i) * 32 + lrow) * GLD + lk + ks * 16]);
+                        for (int i = 0; i < 4; ++i) fa[i] = frag_a(buf, i, q);
                     }
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        if constexpr (TB_) fb[j] = read_frag_tr(sm.b[buf], wn * 128 + j * 32, ks, lane);
-                        else fb[j] = *reinterpret_cast<const u32x4 *>(&sm.b[buf][(wn * 128 + j * 32 + lrow) * GLD + lk + ks * 16]);
-                    }
+                    for (int j = 0; j < 4; ++j) fb[j] = frag_b(buf, nh * 4 + j, q);
                     *reinterpret_cast<u32x4 *>(&sm.a[buf ^ 1][lds_off(TA, ks)]) = ra[ks];
                     *reinterpret_cast<u32x4 *>(&sm.b[buf ^ 1][lds_off(TB_, ks)]) = rb[ks];
-                    ra[ks] = *reinterpret_cast<const u32x4 *>(A + (oa[ks] + next_a));
-                    rb[ks] = *reinterpret_cast<const u32x4 *>(B + (ob[ks] + next_b));
+                    ra[ks] = *src_a(ks, next_a);
+                    rb[ks] = *src_b(ks, next_b);
                     slot_barrier();
 #pragma unroll
-                    for (int i = 0; i < MI; ++i)
+                    for (int i = 0; i < 4; ++i)
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) acc[i][j] = Lp<T>::mfma(fa[i], fb[j], acc[i][j]);
+                        for (int j = 0; j < 4; ++j) acc[i][nh * 4 + j] = Lp<T>::mfma16(fa[i], fb[j], acc[i][nh * 4 + j]);
                     slot_barrier();
                 }
             };
@@ -531,7 +618,7 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a_in, 
         }
     }
 
-    big_epilogue<T, MI, GTHREADS>(a, sm, acc, m0, n0, wm, wn, lane, tid);
+    big_epilogue16<T, GTHREADS>(a, sm, acc, m0, n0, wm, wn, lane, tid);
 }
 
 // row-major [R, C] (leading dimension ld) -> 64x64 blocks, zero padded
