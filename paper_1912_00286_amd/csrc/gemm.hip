@@ -168,8 +168,8 @@ __global__ __launch_bounds__(THREADS) void gemm_nt_mfma_kernel(KernArgs a) {
 
 // Large-tile variant for the whole-sequence GEMMs: 256x256 workgroup tile, eight
 // wavefronts (two per SIMD, so one can issue MFMAs while the other waits on LDS
-// or the barrier) in a 4x2 arrangement, each owning 64x128 (2x4 MFMA blocks,
-// 128 accumulator registers).  K tile 64, two LDS buffers (2 x 72 KB with
+// or the barrier) in a 4x2 arrangement, each owning 64x128 (4x8 blocks of the
+// 16x16x32 MFMA, 128 accumulator registers).  K tile 64, two LDS buffers (2 x 72 KB with
 // padding) and two register sets: while tile t is multiplied out of LDS, tile
 // t+1 sits in (or is arriving into) one register set and tile t+2 is in flight
 // into the other, which covers the L2/HBM latency of about two tile times.
@@ -179,7 +179,7 @@ __global__ __launch_bounds__(THREADS) void gemm_nt_mfma_kernel(KernArgs a) {
 // Two operand layouts:
 //   TRANS = false: C = A B^T with A[M,K], B[N,K], K contiguous (forward
 //                  projection, data gradient).  LDS rows are operand rows; one
-//                  16-byte LDS read is one MFMA fragment.
+//                  16-byte LDS read per lane is one MFMA fragment.
 //   TRANS = true : C = A^T B with A[K,M], B[K,N], M / N contiguous (weight
 //                  gradients dA^T X, contraction over all T*B rows).  The tile
 //                  is kept as it lies in memory ([k][m]) and the fragments are
@@ -202,20 +202,9 @@ struct BigSmem {
 
 typedef short v4s __attribute__((ext_vector_type(4)));
 
-// MFMA fragment (row = lane % 32 of the 32-row block starting at column m0 of the
-// [k][m] tile, k = 8 * (lane / 32) + 0..7 of k-step ks) via two transpose reads.
-__device__ __forceinline__ u32x4 read_frag_tr(const uint16_t *tile, int m0, int ks, int lane) {
-    const int g = lane >> 4, i = lane & 15;
-    const uint16_t *p = tile + (ks * 16 + 8 * (g >> 1) + (i >> 2)) * GLDT + m0 + 16 * (g & 1) + 4 * (i & 3);
-    typedef __attribute__((address_space(3))) v4s *lds_v4s;
-    const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)p);
-    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(p + 4 * GLDT));
-    struct { v4s l, h; } both = {lo, hi};
-    return __builtin_bit_cast(u32x4, both);
-}
-
-// The same for the 16x16x32 MFMA (lane = 16 * (k / 8) + row): rows m0 .. m0 + 15 of the [k][m] tile, 32-deep step q.
-// Each 16-lane group reads 4 k-rows x 16 columns per instruction and receives column (lane % 16) of them.
+// Fragment of the 16x16x32 MFMA (lane = 16 * (k / 8) + row) out of a [k][m] tile: columns m0 .. m0 + 15, 32-deep step
+// q, via two transpose reads: each 16-lane group reads 4 k-rows x 16 columns per instruction and every lane receives
+// the 4 k-values of column (lane % 16).
 __device__ __forceinline__ u32x4 read_frag_tr16(const uint16_t *tile, int m0, int q, int lane) {
     const int g = lane >> 4, i = lane & 15;
     const uint16_t *p = tile + (q * 32 + 8 * g + (i >> 2)) * GLDT + m0 + 4 * (i & 3);
@@ -226,12 +215,12 @@ __device__ __forceinline__ u32x4 read_frag_tr16(const uint16_t *tile, int m0, in
     return __builtin_bit_cast(u32x4, both);
 }
 
-// Result tile of the large-tile kernels: bias, then split-K partials, 16-bit or fp32 result.
-// MI: 32-row MFMA blocks per wavefront; wavefront (wm, wn) owns rows (wm MI + i) 32.., columns wn 128...
-template <typename T, int MI, int GTHREADS>
-__device__ __forceinline__ void big_epilogue(const KernArgs &a, BigSmem &sm, v16f (&acc)[MI][4], int m0, int n0, int wm, int wn,
-                                             int lane, int tid) {
-    const int col_l = lane & 31, rgrp = (lane >> 5) * 4;
+// Result tile of the large-tile kernel: bias, then split-K partials, 16-bit or fp32 result.  Accumulator block
+// (i, j) of a wavefront's 64 x 128 holds rows 16 i + 4 (lane / 16) + r, column 16 j + lane % 16.
+template <typename T, int GTHREADS>
+__device__ __forceinline__ void big_epilogue16(const KernArgs &a, BigSmem &sm, v4f (&acc)[4][8], int m0, int n0, int wm, int wn,
+                                               int lane, int tid) {
+    const int col_l = lane & 15, rgrp = (lane >> 4) * 4;
     const T *bias = reinterpret_cast<const T *>(a.bias);
     if (a.out_lp && !a.ws && a.vec_out) {
         // 16-bit result: the accumulators hold one column per lane, which would go out as 2-byte
@@ -239,71 +228,6 @@ __device__ __forceinline__ void big_epilogue(const KernArgs &a, BigSmem &sm, v16
         // write it as whole 512-byte row segments instead.
         constexpr int OLD = GBN + 8;                       // staging row pitch (elements)
         static_assert(GBM * OLD * 2 <= (int)sizeof(BigSmem), "staged tile must fit the operand buffers");
-        T *stage = reinterpret_cast<T *>(&sm);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int cl = wn * 128 + j * 32 + col_l;
-            const int col = n0 + cl;
-            const float bv = (bias && col < a.N) ? Lp<T>::to_f(bias[col]) : 0.0f;
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int rl = (wm * MI + i) * 32 + (r >> 2) * 8 + rgrp + (r & 3);
-                    stage[rl * OLD + cl] = Lp<T>::from_f(acc[i][j][r] + bv);
-                }
-        }
-        __syncthreads();
-        T *C = reinterpret_cast<T *>(a.C);
-#pragma unroll 4
-        for (int v = tid; v < GBM * (GBN / 8); v += GTHREADS) {
-            const int rl = v / (GBN / 8), cl = (v % (GBN / 8)) * 8;
-            const int row = m0 + rl, col = n0 + cl;
-            if (row >= a.M || col >= a.N) continue;
-            const u32x4 val = *reinterpret_cast<const u32x4 *>(&stage[rl * OLD + cl]);
-            if (col + 8 <= a.N) {
-                *reinterpret_cast<u32x4 *>(&C[(int64_t)row * a.ldc + col]) = val;
-            } else {
-                T e[8];
-                __builtin_memcpy(e, &val, 16);
-                for (int q = 0; q < a.N - col; ++q) C[(int64_t)row * a.ldc + col + q] = e[q];
-            }
-        }
-        return;
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int col = n0 + wn * 128 + j * 32 + col_l;
-        if (col >= a.N) continue;
-        const float bv = (bias && blockIdx.z == 0) ? Lp<T>::to_f(bias[col]) : 0.0f;
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + (wm * MI + i) * 32 + (r >> 2) * 8 + rgrp + (r & 3);
-                if (row >= a.M) continue;
-                const float v = acc[i][j][r] + bv;
-                if (a.ws) {
-                    a.ws[((int64_t)blockIdx.z * a.M + row) * a.N + col] = v;
-                } else if (a.out_lp) {
-                    reinterpret_cast<T *>(a.C)[(int64_t)row * a.ldc + col] = Lp<T>::from_f(v);
-                } else {
-                    float *c = reinterpret_cast<float *>(a.C) + (int64_t)row * a.ldc + col;
-                    *c = a.accumulate ? (*c + v) : v;
-                }
-            }
-    }
-}
-
-// The same for the 16x16x32 accumulators: block (i, j) of a wavefront's 64 x 128 = rows 16 i + 4 (lane / 16) + r,
-// column 16 j + lane % 16.
-template <typename T, int GTHREADS>
-__device__ __forceinline__ void big_epilogue16(const KernArgs &a, BigSmem &sm, v4f (&acc)[4][8], int m0, int n0, int wm, int wn,
-                                               int lane, int tid) {
-    const int col_l = lane & 15, rgrp = (lane >> 4) * 4;
-    const T *bias = reinterpret_cast<const T *>(a.bias);
-    if (a.out_lp && !a.ws && a.vec_out) {
-        constexpr int OLD = GBN + 8;                       // staging row pitch (elements)
         T *stage = reinterpret_cast<T *>(&sm);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -367,7 +291,6 @@ __device__ __forceinline__ void big_epilogue16(const KernArgs &a, BigSmem &sm, v
 template <typename T, bool TA, bool TB_, bool BLK, bool PP, bool SEG = false>
 __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a_in, int tiles_m, int tiles_n) {
     constexpr int GNV = GBM * GBK / 8 / GTHREADS;  // 16-byte vectors per thread, operand and K tile (4)
-    constexpr int MI = 2;                          // 32-row MFMA blocks per wavefront
     __shared__ __attribute__((aligned(16))) BigSmem sm;
     KernArgs a = a_in;
     const T *A = reinterpret_cast<const T *>(a.A);
