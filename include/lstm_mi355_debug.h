@@ -35,6 +35,19 @@ int lstm_timing_read(int32_t kernel_class, int64_t *launches, double *total_ms, 
  * splitk_ws: fp32 [splits, M, N] or NULL with splits <= 1. */
 int lstm_debug_gemm(int32_t dtype, int32_t layout, int32_t M, int32_t N, int32_t K, const void *A, const void *B, void *C,
                     float *splitk_ws, int32_t splits, void *stream);
+
+/* The whole-sequence GEMM on operands in packed (MFMA-fragment) order, C = A B^T (+ bias): 16-bit types, M and
+ * rows_per_step multiples of 64 (M a multiple of rows_per_step), K a multiple of 256, N a multiple of 8.
+ * All pointers device.  Element (row, k) of a 64-row tile's 64-wide K chunk lies at
+ * ((k/16 * nblk + row/32) * 64 + 32 * (k/8 % 2) + row % 32) * 8 + k % 8 inside the chunk, nblk = 2 for A, 4 for B.
+ *   A: the rows of one time step (rows_per_step of them) as [64-row tile][K/64][chunk of 64 x 64]; consecutive
+ *      time steps a_step_stride elements apart.
+ *   B: [128-row tile][K/64][chunk of 128 x 64].  gate_h = 0: row n of B produces column n of C.  gate_h = H
+ *      (N = 4H): row 32 g + r of tile j produces column g H + 32 j + r (the order the recurrent kernels keep
+ *      their weights in).
+ *   bias: lp [N] or NULL.  C: lp [M, N] row-major, out. */
+int lstm_debug_gemm_stream(int32_t dtype, int32_t M, int32_t N, int32_t K, int32_t rows_per_step, int64_t a_step_stride,
+                           int32_t gate_h, const void *A, const void *B, const void *bias, void *C, void *stream);
 /* Enqueues a loop of `iters` x 8 independent 32x32x16 MFMAs per wavefront (256 workgroups of 8
  * wavefronts) whose operands stay in registers: the rate the matrix pipes sustain on the given
  * operand values, which depends on the values through the chip's power management.

@@ -74,12 +74,13 @@ def load_library():
     lib.lr_schedule.restype = f32
     lib.lstm_debug_gemm.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, i32, vp]
     lib.lstm_debug_pack_blocked.argtypes = [i32, vp, i32, i32, vp, vp]
+    lib.lstm_debug_gemm_stream.argtypes = [i32, i32, i32, i32, i32, i64, i32, vp, vp, vp, vp, vp]
     lib.lstm_debug_mfma_rate.argtypes = [i32, vp, i32, vp, C.POINTER(C.c_double), vp]
     lib.lstm_timing_enable.argtypes = [i32]
     lib.lstm_timing_read.argtypes = [i32, C.POINTER(i64), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double)]
     for name in ("lstm_param_count", "lstm_param_offset", "lstm_workspace_bytes", "lstm_forward", "lstm_backward",
                  "grad_average", "grad_average_masked", "master_update", "lstm_cast_params", "lstm_timing_enable", "lstm_timing_read",
-                 "lstm_debug_gemm", "lstm_debug_pack_blocked", "lstm_debug_mfma_rate", "lstm_debug_plan_regions"):
+                 "lstm_debug_gemm", "lstm_debug_gemm_stream", "lstm_debug_pack_blocked", "lstm_debug_mfma_rate", "lstm_debug_plan_regions"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -210,6 +211,11 @@ def lstm_timing_read(kernel_class: int):
 def lstm_debug_gemm(dtype, layout, M, N, K, A, B, Cout, splitk_ws=None, splits=1, stream=None):
     _check(load_library().lstm_debug_gemm(dtype, layout, M, N, K, _ptr(A), _ptr(B), _ptr(Cout), _ptr(splitk_ws), splits,
                                           _stream(stream)))
+
+
+def lstm_debug_gemm_stream(dtype, M, N, K, rows_per_step, a_step_stride, gate_h, A, B, bias, Cout, stream=None):
+    _check(load_library().lstm_debug_gemm_stream(dtype, M, N, K, rows_per_step, a_step_stride, gate_h, _ptr(A), _ptr(B),
+                                                 _ptr(bias), _ptr(Cout), _stream(stream)))
 
 
 def lstm_debug_mfma_rate(dtype, operands, iters, sink, stream=None) -> float:

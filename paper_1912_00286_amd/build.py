@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblstm_mi355.so")
 
-SOURCES = ["api.hip", "gemm.hip", "pointwise.hip", "optim.hip", "timing.hip", "recurrent.hip", "recurrent_tile.hip"]
+SOURCES = ["api.hip", "gemm.hip", "pointwise.hip", "optim.hip", "timing.hip", "recurrent.hip", "recurrent_tile.hip", "gemm_stream.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -66,6 +66,12 @@ struct Plan {
     bool lag = false;
     int lag_c = 32;
     std::vector<size_t> s_lag_ax, s_lag_dx, s_lag_wblk;
+    // The chunk GEMMs on the packed-operand kernel (gemm_stream.hip): its A operand is the packed per-step copy the
+    // recurrence writes anyway, kept for every time step instead of in two alternating buffers (s_lag_hseq: h_0 .. h_T
+    // of the layers below the top, s_lag_daseq: dA_0 .. dA_{T-1} of the layers above the first); its B operand is W
+    // packed like the recurrent matrix.  Projection: needs H % 256 == 0; data gradient: always.
+    bool lag_sax = false, lag_sdx = false;
+    std::vector<size_t> s_lag_hseq, s_lag_daseq;
     std::vector<size_t> s_wb_dapk1; // second packed dA per layer (fb: a cell reads one step's while writing the next)
     std::vector<size_t> s_wf_upk, s_wf_wpk, s_wf_c, s_wf_hpk0, s_wf_hpk1;
     // backward along anti-diagonals: per-layer dA (row-major and blocked), packed U^T / W^T, packed dA_t,
@@ -260,17 +266,21 @@ int make_plan(const lstm_config *c, Plan &p) {
             // 48: 24.2, 64: 24.7, 128 (no overlap between layers): 26.0
             p.lag_c = p.T < 32 ? p.T : 32;
             p.s_lag_ax.assign(p.L, 0); p.s_lag_dx.assign(p.L, 0); p.s_lag_wblk.assign(p.L, 0);
+            p.s_lag_hseq.assign(p.L, 0); p.s_lag_daseq.assign(p.L, 0);
+            p.lag_sax = p.H % 256 == 0;
+            p.lag_sdx = true;
             for (int l = 1; l < p.L; ++l) {
                 p.s_lag_ax[l] = take(1, (size_t)p.lag_c * p.B * p.G * p.es);
                 p.s_lag_dx[l - 1] = take(1, (size_t)p.lag_c * p.B * p.H * p.es);
-                p.s_lag_wblk[l] = take(1, blocked_elems(p.G, p.H) * p.es);
+                if (!p.lag_sax) p.s_lag_wblk[l] = take(1, blocked_elems(p.G, p.H) * p.es);
+                if (p.lag_sax) p.s_lag_hseq[l - 1] = take(1, (size_t)(p.T + 1) * rd.hpk_elems * p.es);
             }
         }
         if (p.wf) {
             p.s_wf_upk.resize(p.L); p.s_wf_wpk.assign(p.L, 0); p.s_wf_c.resize(p.L); p.s_wf_hpk0.resize(p.L); p.s_wf_hpk1.resize(p.L);
             for (int l = 0; l < p.L; ++l) {
                 p.s_wf_upk[l] = take(1, rd.upk_elems * p.es);
-                if (l > 0 && !p.lag) { p.s_wf_wpk[l] = take(1, rd.upk_elems * p.es); }
+                if (l > 0 && (!p.lag || p.lag_sax)) { p.s_wf_wpk[l] = take(1, rd.upk_elems * p.es); }
                 p.s_wf_hpk0[l] = take(1, rd.hpk_elems * p.es);
                 p.s_wf_hpk1[l] = take(1, rd.hpk_elems * p.es);
                 p.s_wf_c[l] = take(1, (size_t)p.B * p.H * 4);
@@ -303,7 +313,8 @@ int make_plan(const lstm_config *c, Plan &p) {
             for (int l = 0; l < p.L; ++l)
                 extra += (p.dA_rowmajor_needed(l) ? align_up(TB * p.G * p.es) : 0) +
                          (p.blk ? align_up(blocked_elems((int)TB, p.G) * p.es) : 0) + 2 * align_up(rd.utpk_elems * p.es) +
-                         2 * align_up(rd.dapk_elems * p.es) + 2 * align_up(rd.partial_bytes) + align_up((size_t)p.B * p.H * 4);
+                         2 * align_up(rd.dapk_elems * p.es) + 2 * align_up(rd.partial_bytes) + align_up((size_t)p.B * p.H * 4) +
+                         (p.lag && l > 0 ? align_up((size_t)p.T * rd.dapk_elems * p.es) : 0);
             p.wb = extra <= kDiagonalBackwardBudget;
         }
         p.fb = p.wb && fb_ok;
@@ -315,7 +326,8 @@ int make_plan(const lstm_config *c, Plan &p) {
                 p.s_wb_dA[l] = s; if (p.dA_rowmajor_needed(l)) take(1, TB * p.G * p.es);
                 if (p.blk) { p.s_wb_dablk[l] = take(1, blocked_elems((int)TB, p.G) * p.es); }
                 p.s_wb_utpk[l] = take(1, rd.utpk_elems * p.es);
-                if (l > 0 && !p.lag) { p.s_wb_wtpk[l] = take(1, rd.utpk_elems * p.es); }
+                if (l > 0 && (!p.lag || p.lag_sdx)) { p.s_wb_wtpk[l] = take(1, rd.utpk_elems * p.es); }
+                if (l > 0 && p.lag && p.lag_sdx) { p.s_lag_daseq[l] = take(1, (size_t)p.T * rd.dapk_elems * p.es); }
                 p.s_wb_dapk[l] = take(1, rd.dapk_elems * p.es);
                 if (p.fb) { p.s_wb_dapk1[l] = take(1, rd.dapk_elems * p.es); }
                 p.s_wb_partU[l] = s; if (!p.fb) take(1, rd.partial_bytes);
@@ -495,10 +507,11 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
         float *c_state = (float *)at(scratch, p.wf ? p.s_wf_c[l] : p.s_cstate);
         // input projection of the whole sequence: Ax = X W^T + b  (along the anti-diagonals only
         // layer 0 has its input ahead of time; the layers above project inside their step kernels)
-        if (p.lag && l > 0) {
+        if (p.lag && l > 0 && !p.lag_sax) {
             // projected chunk by chunk between the step launches below: W in 64x64 blocks once
             LSTM_TRY(pack_blocked(p.dtype, W, p.in_dim[l], p.G, p.in_dim[l], at(scratch, p.s_lag_wblk[l]), s));
         } else if (p.wf && l > 0) {
+            // (wide layers: the B operand of the chunked projection on the packed-operand kernel)
             setup.pack_u_forward(W, at(scratch, p.s_wf_wpk[l]));
         } else if (p.proj) {
             // the step kernels project their own input: W packed like U; layer 0's input sequence packed step by
@@ -539,6 +552,7 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
                             c_state, BH, s));
         char *upk = at(scratch, p.wf ? p.s_wf_upk[l] : p.s_upk);
         char *hpk[2] = {at(scratch, p.wf ? p.s_wf_hpk0[l] : p.s_apk[0]), at(scratch, p.wf ? p.s_wf_hpk1[l] : p.s_apk[1])};
+        if (p.lag && p.lag_sax && l < p.L - 1) hpk[0] = at(scratch, p.s_lag_hseq[l]);   // slot 0 of the kept sequence
         char *hseq = p.proj ? at(scratch, p.s_pj_hseq[l & 1]) : nullptr;    // packed h_0 .. h_T of this layer, one slot per step
         if (fused) {
             // recurrent weights and the initial hidden state in packed tile order; the second
@@ -627,6 +641,18 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
                 const int t0 = d - l * lag;
                 if (t0 < 0 || t0 >= p.T || t0 % lag != 0) continue;
                 const int nt = p.T - t0 < lag ? p.T - t0 : lag;
+                if (p.lag_sax) {
+                    const RecurrentDims rd = recurrent_dims(p.B, p.H);
+                    StreamGemmArgs g{};
+                    g.A = at(scratch, p.s_lag_hseq[l - 1]) + (size_t)(t0 + 1) * rd.hpk_elems * es;
+                    g.a_step_stride = (int64_t)rd.hpk_elems; g.rows_per_step = p.B;
+                    g.B = at(scratch, p.s_wf_wpk[l]); g.gate_h = p.H;
+                    g.C = at(scratch, p.s_lag_ax[l]); g.bias = par + p.off_b[l] * es; g.ldc = p.G;
+                    g.M = nt * p.B; g.N = p.G; g.K = p.in_dim[l];
+                    g.kclass = KC_GEMM_BATCHED;
+                    LSTM_TRY(gemm_stream(p.dtype, g, s));
+                    continue;
+                }
                 BlockedGemmArgs g{};
                 g.A = BlockedOperand{at(reserve, p.r_hblk[l - 1]) + (size_t)(t0 + 1) * slot, p.h_ncb, 0};
                 g.B = BlockedOperand{at(scratch, p.s_lag_wblk[l]), (p.in_dim[l] + 63) / 64, 0};
@@ -641,6 +667,11 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
                 char *hpk[2] = {at(scratch, p.s_wf_hpk0[l]), at(scratch, p.s_wf_hpk1[l])};
                 WaveCell c{};
                 c.hpk_prev = hpk[t & 1]; c.hpk_next = hpk[(t + 1) & 1];
+                if (p.lag && p.lag_sax && l < p.L - 1) {
+                    const size_t hpk_bytes = recurrent_dims(p.B, p.H).hpk_elems * es;
+                    c.hpk_prev = at(scratch, p.s_lag_hseq[l]) + (size_t)t * hpk_bytes;
+                    c.hpk_next = at(scratch, p.s_lag_hseq[l]) + (size_t)(t + 1) * hpk_bytes;
+                }
                 c.Upk = at(scratch, p.s_wf_upk[l]);
                 if (l == 0) {
                     c.Ax = ax + (size_t)t * p.B * p.G * axs;
@@ -793,8 +824,8 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
         SetupBatch setup;
         for (int l = 0; l < p.L; ++l) {
             setup.pack_u_backward(par + p.off_U[l] * es, at(scratch, p.s_wb_utpk[l]));
-            if (l > 0 && !p.lag) setup.pack_u_backward(par + p.off_W[l] * es, at(scratch, p.s_wb_wtpk[l]));
-            if (l > 0 && p.lag)      // the chunked dX GEMMs read W in 64x64 blocks
+            if (l > 0 && (!p.lag || p.lag_sdx)) setup.pack_u_backward(par + p.off_W[l] * es, at(scratch, p.s_wb_wtpk[l]));
+            if (l > 0 && p.lag && !p.lag_sdx)      // the chunked dX GEMMs read W in 64x64 blocks
                 LSTM_TRY(pack_blocked(p.dtype, par + p.off_W[l] * es, p.in_dim[l], p.G, p.in_dim[l], at(scratch, p.s_lag_wblk[l]), s));
             setup.zero(at(scratch, p.s_wb_dapk[l]), (int64_t)((rd.dapk_elems * es + 3) / 4));
             if (p.fb) setup.zero(at(scratch, p.s_wb_dapk1[l]), (int64_t)((rd.dapk_elems * es + 3) / 4));
@@ -851,6 +882,17 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
                 const int k = d - (p.L - 1 - l) * lag;
                 if (k < 0 || k >= p.T || k % lag != 0) continue;
                 const int t_hi = p.T - 1 - k, t_lo = chunk_lo(t_hi);
+                if (p.lag_sdx) {
+                    StreamGemmArgs g{};
+                    g.A = at(scratch, p.s_lag_daseq[l + 1]) + (size_t)t_lo * rd.dapk_elems * es;
+                    g.a_step_stride = (int64_t)rd.dapk_elems; g.rows_per_step = p.B;
+                    g.B = at(scratch, p.s_wb_wtpk[l + 1]); g.gate_h = 0;
+                    g.C = at(scratch, p.s_lag_dx[l]); g.ldc = p.H;
+                    g.M = (t_hi - t_lo + 1) * p.B; g.N = p.H; g.K = p.G;
+                    g.kclass = KC_GEMM_BATCHED;
+                    LSTM_TRY(gemm_stream(p.dtype, g, s));
+                    continue;
+                }
                 BlockedGemmArgs g{};
                 g.A = BlockedOperand{at(scratch, p.s_wb_dablk[l + 1]) + (size_t)t_lo * slotg, p.g_ncb, 0};
                 g.B = BlockedOperand{at(scratch, p.s_lag_wblk[l + 1]), (p.H + 63) / 64, 1};      // rows of W are the contraction index
@@ -873,6 +915,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
                 c.dc_state = (float *)at(scratch, p.s_wb_dc[l]);
                 c.dA = dA_rowmajor_needed(l) ? at(scratch, p.s_wb_dA[l]) + (size_t)t * p.B * p.G * es : nullptr;
                 c.dApk = at(scratch, p.s_wb_dapk[l]);
+                if (p.lag && p.lag_sdx && l > 0) c.dApk = at(scratch, p.s_lag_daseq[l]) + (size_t)t * rd.dapk_elems * es;
                 c.dAblk = p.blk ? at(scratch, p.s_wb_dablk[l]) + (size_t)t * slotg : nullptr;
                 c.first = t == p.T - 1 ? 1 : 0;
                 gc.push_back(c);
@@ -1165,6 +1208,15 @@ extern "C" int lstm_debug_gemm(int32_t dtype, int32_t layout, int32_t M, int32_t
     g.C = C; g.ldc = N; g.out_lp = 1; g.M = M; g.N = N; g.K = K;
     g.splitk_ws = splitk_ws; g.splits = splits; g.kclass = KC_GEMM_BATCHED;
     return gemm_blocked(dtype, g, s);
+}
+
+// Diagnostic: the whole-sequence GEMM on operands in packed (MFMA-fragment) order.
+extern "C" int lstm_debug_gemm_stream(int32_t dtype, int32_t M, int32_t N, int32_t K, int32_t rows_per_step, int64_t a_step_stride,
+                                      int32_t gate_h, const void *A, const void *B, const void *bias, void *C, void *stream) {
+    StreamGemmArgs g{};
+    g.A = A; g.a_step_stride = a_step_stride; g.rows_per_step = rows_per_step; g.B = B; g.C = C; g.ldc = N; g.bias = bias;
+    g.M = M; g.N = N; g.K = K; g.gate_h = gate_h; g.kclass = KC_GEMM_BATCHED;
+    return gemm_stream(dtype, g, (hipStream_t)stream);
 }
 
 // Diagnostic: register-resident MFMA loop on caller-provided operand values.

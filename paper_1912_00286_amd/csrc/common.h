@@ -191,6 +191,23 @@ bool gemm_blocked_supported(int dtype, int M, int N);
 // C = op(A) op(B)^T-style product of blocked operands (roles per BlockedOperand::trans);
 // supported role pairs: (0,0), (0,1), (1,1).
 int gemm_blocked(int dtype, const BlockedGemmArgs &g, hipStream_t stream);
+// ---- operands in packed (MFMA-fragment) order (packed.h): C[M,N] (+ bias) = A B^T, 16-bit row-major result.
+// A: the rows of `rows_per_step` consecutive rows form one time step, stored as [64-row tile][K/64][A chunk],
+//    consecutive time steps a_step_stride elements apart.  B: [128-row tile][K/64][B chunk].
+struct StreamGemmArgs {
+    const void *A;
+    int64_t a_step_stride;
+    int rows_per_step;
+    const void *B;
+    void *C;
+    int64_t ldc;
+    const void *bias;    // [N] or null
+    int M, N, K;
+    int gate_h;          // 0: row n of B is column n of C.  H: row 32 g + r of B tile j is column g H + 32 j + r (N = 4H)
+    int kclass;
+};
+bool gemm_stream_supported(int dtype, const StreamGemmArgs &g);
+int gemm_stream(int dtype, const StreamGemmArgs &g, hipStream_t stream);
 // number of K splits gemm_nt / gemm_tn would like for this shape (>= 1)
 // Diagnostic MFMA loop: operands = 256*512*2 16-byte fragments (device), sink = 1 float (device).
 int mfma_rate(int dtype, const void *operands, int iters, float *sink, double *flops, hipStream_t stream);

@@ -1,0 +1,79 @@
+"""The whole-sequence GEMM on packed (MFMA-fragment order) operands against torch's fp32 matmul.
+
+The operands are packed here, on the host, from the layout formula the header states, so the test also pins the
+layout itself; the products the training step sends through this kernel are covered by the parity tests of the
+wide-layer schedule."""
+import numpy as np
+import pytest
+import torch
+
+import paper_1912_00286_amd as hip
+
+pytestmark = pytest.mark.gpu
+
+DT = {"fp16": (hip.DTYPE_FP16, torch.float16, 2e-3), "bf16": (hip.DTYPE_BF16, torch.bfloat16, 1.6e-2)}
+
+
+def pack_tiles(x: torch.Tensor, tile_rows: int) -> torch.Tensor:
+    """[R, K] -> [R / tile_rows][K / 64][chunk], element (row, k) of a chunk at
+    ((k/16 * nblk + row/32) * 64 + 32 * (k/8 % 2) + row % 32) * 8 + k % 8."""
+    R, K = x.shape
+    assert R % tile_rows == 0 and K % 64 == 0
+    nblk = tile_rows // 32
+    row = torch.arange(tile_rows).view(-1, 1).expand(tile_rows, 64)
+    k = torch.arange(64).view(1, -1).expand(tile_rows, 64)
+    off = ((k // 16 * nblk + row // 32) * 64 + 32 * (k // 8 % 2) + row % 32) * 8 + k % 8
+    chunks = x.view(R // tile_rows, tile_rows, K // 64, 64).permute(0, 2, 1, 3).reshape(-1, tile_rows * 64)
+    out = torch.empty_like(chunks)
+    out[:, off.reshape(-1)] = chunks
+    return out.reshape(-1)
+
+
+CASES = [
+    # M, N, K, rows_per_step, gated, bias
+    (512, 512, 256, 256, False, False),
+    (768, 384, 512, 192, False, True),      # steps of three row tiles, N not a multiple of the 256-column tile
+    (448, 1024, 256, 64, True, True),       # M not a multiple of the 256-row tile, gate-interleaved columns
+    (2048, 2560, 1024, 256, True, True),    # H = 640: the last column tile is half empty
+    (1024, 2048, 2048, 512, False, False),
+]
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+@pytest.mark.parametrize("M,N,K,rps,gated,with_bias", CASES)
+def test_gemm_stream_matches_fp32_matmul(dtype, M, N, K, rps, gated, with_bias):
+    code, tdt, tol = DT[dtype]
+    g = torch.Generator().manual_seed(M * 7 + N * 3 + K)
+    A = (torch.randn(M, K, generator=g) * 0.5).to(tdt)
+    B = (torch.randn(N, K, generator=g) * 0.5).to(tdt)
+    bias = torch.randn(N, generator=g).to(tdt) if with_bias else None
+    ref = A.float() @ B.float().T + (bias.float() if with_bias else 0.0)
+    # A: every time step's rows packed on their own, steps a padded stride apart
+    steps = M // rps
+    per_step = rps * K
+    stride = per_step + 4096
+    Apk = torch.zeros(steps * stride, dtype=tdt)
+    for s in range(steps):
+        Apk[s * stride: s * stride + per_step] = pack_tiles(A[s * rps:(s + 1) * rps], 64)
+    if gated:
+        H = N // 4
+        assert H % 32 == 0
+        # B tile j holds, for each gate g, the rows g H + 32 j .. g H + 32 j + 31
+        idx = torch.arange(N).view(4, H // 32, 32).permute(1, 0, 2).reshape(-1)
+        Bt = B[idx]
+        gate_h = H
+    else:
+        pad = (-N) % 128
+        Bt = torch.cat([B, torch.zeros(pad, K, dtype=tdt)]) if pad else B
+        gate_h = 0
+    Bpk = pack_tiles(Bt, 128)
+    dev = torch.device("cuda:0")
+    C = torch.full((M, N), float("nan"), dtype=tdt, device=dev)
+    hip.lstm_debug_gemm_stream(code, M, N, K, rps, stride, gate_h, Apk.to(dev), Bpk.to(dev),
+                               bias.to(dev) if with_bias else None, C)
+    torch.cuda.synchronize()
+    got = C.float().cpu()
+    assert torch.isfinite(got).all()
+    err = (got - ref).abs().max().item()
+    scale = ref.abs().max().item()
+    assert err <= tol * scale, f"max error {err:.3e} against scale {scale:.3e}"
