@@ -1074,6 +1074,8 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
                 g.batch = p.W; g.seg_len = p.Bw / 64; g.seg_stride = p.B / 64; g.batch_c = p.P;
                 g.splitk_ws = nullptr; g.splits = 1;
             }
+            // large single products: the hand-scheduled kernel
+            if (p.W == 1 && gemm_stream_tn_supported(p.dtype, g)) return gemm_stream_tn(p.dtype, g, s);
             return gemm_blocked(p.dtype, g, s);
         };
         if (w_blk) {
@@ -1190,7 +1192,7 @@ extern "C" int lstm_debug_plan_regions(const lstm_config *cfg, int32_t max_regio
 // Diagnostic: one whole-sequence GEMM through the same dispatch the training step uses.
 // layout 0: C = A B^T, row-major A[M,K], B[N,K];  1: C = A^T B, row-major A[K,M], B[K,N];
 // 2/3/4: operands in 64x64 blocks (see pack_blocked), roles (A,B) = (rows M, rows N) /
-// (rows M, rows K) / (rows K, rows K).  C is row-major lp [M,N].
+// (rows M, rows K) / (rows K, rows K); 5: as 4 on the kernel of gemm_stream.hip.  C is row-major lp [M,N].
 extern "C" int lstm_debug_gemm(int32_t dtype, int32_t layout, int32_t M, int32_t N, int32_t K, const void *A, const void *B,
                                void *C, float *splitk_ws, int32_t splits, void *stream) {
     hipStream_t s = (hipStream_t)stream;
@@ -1202,12 +1204,12 @@ extern "C" int lstm_debug_gemm(int32_t dtype, int32_t layout, int32_t M, int32_t
         return layout == 0 ? gemm_nt(dtype, g, s) : gemm_tn(dtype, g, s);
     }
     BlockedGemmArgs g{};
-    const int ta = layout == 4, tb = layout >= 3;
+    const int ta = layout >= 4, tb = layout >= 3;
     g.A = BlockedOperand{A, ((ta ? M : K) + 63) / 64, ta};
     g.B = BlockedOperand{B, ((tb ? N : K) + 63) / 64, tb};
     g.C = C; g.ldc = N; g.out_lp = 1; g.M = M; g.N = N; g.K = K;
     g.splitk_ws = splitk_ws; g.splits = splits; g.kclass = KC_GEMM_BATCHED;
-    return gemm_blocked(dtype, g, s);
+    return layout == 5 ? gemm_stream_tn(dtype, g, s) : gemm_blocked(dtype, g, s);
 }
 
 // Diagnostic: the whole-sequence GEMM on operands in packed (MFMA-fragment) order.

@@ -208,6 +208,10 @@ struct StreamGemmArgs {
 };
 bool gemm_stream_supported(int dtype, const StreamGemmArgs &g);
 int gemm_stream(int dtype, const StreamGemmArgs &g, hipStream_t stream);
+// The (1,1) role pair of gemm_blocked (C = A^T B, 16-bit result, no bias, one product, no split) on the kernel of
+// gemm_stream.hip; K a multiple of 128.
+bool gemm_stream_tn_supported(int dtype, const BlockedGemmArgs &g);
+int gemm_stream_tn(int dtype, const BlockedGemmArgs &g, hipStream_t stream);
 // number of K splits gemm_nt / gemm_tn would like for this shape (>= 1)
 // Diagnostic MFMA loop: operands = 256*512*2 16-byte fragments (device), sink = 1 float (device).
 int mfma_rate(int dtype, const void *operands, int iters, float *sink, double *flops, hipStream_t stream);

@@ -248,6 +248,177 @@ __global__ __launch_bounds__(SG_THREADS) void gemm_stream_kernel(StreamArgs a) {
     }
 }
 
+// ---------------------------------------------------------------- C = A^T B, both operands with the contraction index as rows
+// The weight gradients dW = dA^T X, dU = dA^T H: both operands are 64x64-blocked activations whose rows are the
+// contraction index (all T*B rows), so the fragments have to be transposed on the way into the MFMA, which the LDS
+// transpose read does: both operands go through LDS.  Same loop as above (16x16x32 MFMAs pinned to the accumulator
+// registers, one other instruction between two MFMAs, four stages, fragments of the next step read ahead of the
+// barrier), with these differences:
+//   * a stage is 32 contraction rows x (256 m + 256 n): 32 KB, so that four of them fit; the rows of a blocked
+//     operand are whole 128-byte lines, so half a 64x64 block is still fetched in whole lines;
+//   * both operands arrive by direct-to-LDS loads, 1 KB (8 rows of one block) per wavefront instruction;
+//   * four wavefronts of 128 x 128 each (2 x 2): 8 A and 8 B fragments per 32-deep step, two 8-byte transpose
+//     reads each;
+//   * the LDS image keeps the rows at their 128-byte pitch and swaps 32-byte groups inside a row, group' = group ^
+//     f(row), f = bit 1 of the row | bit 3 of the row << 1: the sixteen rows one transpose-read instruction touches
+//     (rows 8 g .. 8 g + 3 of its four 16-lane groups g) then spread evenly over the banks.  The swap is applied by
+//     choosing which 16 bytes each lane of a direct-to-LDS load fetches.
+struct StreamTnArgs {
+    const uint16_t *A;        // blocked [K / 64][ncb_a][64][64], rows = contraction index, columns = m (first m block at column block 0)
+    const uint16_t *B;        // blocked [K / 64][ncb_b][64][64], columns = n
+    int ncb_a, ncb_b;
+    void *C;                  // 16-bit, row-major [M, ldc]
+    int64_t ldc;
+    int M, N, K;
+    int tiles_m, tiles_n;
+};
+
+typedef short sg_v4s __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) sg_v4s *sg_lds_v4s;
+
+// Direct-to-LDS load of 16 bytes per lane: global address = base (scalar) + offset (per lane) + j KB, LDS address =
+// lds + 16 lane + j KB.  Written as assembly because the compiler, once it has seen a direct-to-LDS load, waits for
+// ALL outstanding loads before every LDS transpose read that follows (it cannot tell the two apart), which would
+// serialise the whole pipeline; the waits these loads need are the explicit ones of the loop.  M0 carries the LDS
+// address (nothing else in the kernel uses it).
+__device__ __forceinline__ void sg_dma_piece4(const void *base, unsigned offset, unsigned lds, int j) {
+    switch (j) {
+        case 0: asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" :: "v"(offset), "s"(base), "s"(lds) : "memory"); break;
+        case 1: asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 offset:1024" :: "v"(offset), "s"(base), "s"(lds) : "memory"); break;
+        case 2: asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 offset:2048" :: "v"(offset), "s"(base), "s"(lds) : "memory"); break;
+        default: asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 offset:3072" :: "v"(offset), "s"(base), "s"(lds) : "memory"); break;
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(SG_THREADS) void gemm_stream_tn_kernel(StreamTnArgs a) {
+    __shared__ __attribute__((aligned(1024))) unsigned char ring[SG_LDS];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int total = a.tiles_m * a.tiles_n;
+    int lin = blockIdx.x;
+    if (total % 8 == 0) lin = (lin % 8) * (total / 8) + lin / 8;
+    const int band = 8 * a.tiles_n;
+    const int b0 = (lin / band) * 8;
+    const int bh = min(8, a.tiles_m - b0);
+    const int tm = b0 + (lin % band) % bh, tn = (lin % band) / bh;
+
+    // Loads.  Piece p of a stage's 32: operand p / 16 (A, B), block (p / 4) % 4 of the tile's four, rows 8 (p % 4) ..
+    // of the stage's 32.  Wavefront w takes pieces 8 w .. 8 w + 7: two blocks of one operand, four pieces each.
+    // Lane i of a piece holds row i / 8 and the 16 bytes at position i % 8 of that row, and fetches the 16 bytes that
+    // belong there under the swap: chunk (i % 8) ^ 2 f, f from the row 8 (p % 4) + i / 8 (two cases: p % 4 even, odd).
+    const bool opB = wave >= 2;
+    const uint16_t *Op = opB ? a.B : a.A;
+    const int ncb = opB ? a.ncb_b : a.ncb_a, nblk = ((opB ? a.N : a.M) + 63) / 64;
+    const int blk0 = (opB ? tn : tm) * 4 + (wave & 1) * 2;
+    const int blkc0 = blk0 < nblk ? blk0 : 0, blkc1 = blk0 + 1 < nblk ? blk0 + 1 : 0;      // blocks past the edge: read block 0, never stored
+    const int lrow = lane >> 3, lpos = lane & 7;
+    const unsigned lsrc0 = (lrow * 64 + ((lpos ^ ((((lrow >> 1) & 1) | 0) << 1)) * 8)) * 2;   // bytes, pieces with p % 4 even
+    const unsigned lsrc1 = (lrow * 64 + ((lpos ^ ((((lrow >> 1) & 1) | 2) << 1)) * 8)) * 2;   // pieces with p % 4 odd
+    const char *src0 = reinterpret_cast<const char *>(Op + (int64_t)blkc0 * 4096);            // + block row * ncb * 8 KB + half * 4 KB
+    const char *src1 = reinterpret_cast<const char *>(Op + (int64_t)blkc1 * 4096);
+    unsigned char *my_pieces = ring + wave * 8192;
+    const int64_t row_bytes = (int64_t)ncb * 8192;                                             // one block row of the operand
+    // pieces q = 0 .. 7 of step c into stage st
+    auto dma = [&](int c, int st, int q) {
+        const char *s = (q < 4 ? src0 : src1) + (int64_t)(c >> 1) * row_bytes + (c & 1) * 4096;
+        const unsigned lds = (unsigned)(uintptr_t)(lds_ptr)(my_pieces + st * SG_STAGE + (q >> 2) * 4096);
+        sg_dma_piece4(s, (q & 1) ? lsrc1 : lsrc0, lds, q & 3);
+    };
+
+    // Fragments.  Lane (i = lane % 16, g = lane / 16) of a transpose read supplies the address of 4 columns of row
+    // 8 g + i / 4 (+ 4 for the second read) and receives the four rows' values of column i: contraction values 8 g ..
+    // 8 g + 7 of column i, the 16x16x32 operand layout.  f of those rows is the same for both reads.
+    const int ti = lane & 15, tg = lane >> 4;
+    const int tf = ((ti >> 3) & 1) | ((tg & 1) << 1);
+    unsigned tr_off[4];                                   // 16-column group cp of a block: byte offset of this lane's first read
+#pragma unroll
+    for (int cp = 0; cp < 4; ++cp) tr_off[cp] = (8 * tg + (ti >> 2)) * 128 + ((cp ^ tf) << 5) + (ti & 3) * 8;
+    auto read_frag = [&](const unsigned char *blk, int cp) -> u32x4 {
+        const sg_v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((sg_lds_v4s)(blk + tr_off[cp]));
+        const sg_v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((sg_lds_v4s)(blk + tr_off[cp] + 512));
+        struct { sg_v4s l, h; } both = {lo, hi};
+        return __builtin_bit_cast(u32x4, both);
+    };
+
+    v4f acc[8][8];                                        // block (ia, jb) of the wavefront's 128 x 128
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
+    u32x4 fa[2][8], fb[2][8];                             // fragments of step c in set c % 2
+    // fragment x of a stage: x < 8: B fragment x, else A fragment x - 8 (B first: the MFMAs walk along jb)
+    auto read_one = [&](int set, int st, int x) {
+        if (x < 8) fb[set][x] = read_frag(ring + st * SG_STAGE + 16384 + (wn * 2 + (x >> 2)) * 4096, x & 3);
+        else fa[set][x - 8] = read_frag(ring + st * SG_STAGE + (wm * 2 + ((x - 8) >> 2)) * 4096, x & 3);
+    };
+
+    // Step c multiplies the 32 contraction rows of stage c % 4 and requests step c + 3 into the stage step c - 1
+    // occupied; it ends with [wait until at most its own 8 requests are outstanding] [barrier: step c + 2 is complete
+    // in LDS, everybody is done with step c].  Requests past the last step are clamped to it (never read).
+    const int last = a.K / 32 - 1;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) dma(0, 0, q);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) dma(1, 1, q);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) dma(2, 2, q);
+    __builtin_amdgcn_sched_barrier(0);
+    sg_wait_vm<8>();
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int x = 0; x < 16; ++x) read_one(0, 0, x);
+    for (int g = 0; g <= last; g += SG_GRP) {
+#pragma unroll
+        for (int i = 0; i < SG_GRP; ++i) {
+            const int c = g + i, cn = c + 3 < last ? c + 3 : last;
+            const int set = i & 1;
+            // 64 MFMAs; after every second one half a fragment (one transpose read) of step c + 1, after every
+            // eighth one load piece of step c + 3
+#pragma unroll
+            for (int x = 0; x < 16; ++x) {
+#pragma unroll
+                for (int n = 0; n < 4; ++n) {
+                    const int m = x * 4 + n, ia = m >> 3, jb = m & 7;
+                    mfma_acc<T>(acc[ia][jb], fa[set][ia], fb[set][jb]);
+                }
+                read_one(set ^ 1, (i + 1) % SG_NS, x);
+                if (x & 1) dma(cn, (i + 3) % SG_NS, x >> 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            sg_wait_vm<8>();
+            __builtin_amdgcn_s_barrier();
+        }
+    }
+    sg_wait_vm<0>();
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // the last MFMAs leave the pipe before their accumulators are read
+    __syncthreads();
+
+    // 16-bit result through LDS, written as whole 512-byte row segments
+    T *stage = reinterpret_cast<T *>(ring);
+    const int col_l = lane & 15, rgrp = (lane >> 4) * 4;
+#pragma unroll
+    for (int ia = 0; ia < 8; ++ia)
+#pragma unroll
+        for (int jb = 0; jb < 8; ++jb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                stage[(wm * 128 + ia * 16 + rgrp + r) * SG_OLD + wn * 128 + jb * 16 + col_l] = Lp<T>::from_f(acc[ia][jb][r]);
+    __syncthreads();
+    T *C = reinterpret_cast<T *>(a.C);
+#pragma unroll 4
+    for (int v = tid; v < 256 * 32; v += SG_THREADS) {
+        const int rl = v >> 5, cv = v & 31;
+        const int row = tm * 256 + rl, col = tn * 256 + cv * 8;
+        if (row >= a.M || col >= a.N) continue;
+        *reinterpret_cast<u32x4 *>(&C[(int64_t)row * a.ldc + col]) = *reinterpret_cast<const u32x4 *>(&stage[rl * SG_OLD + cv * 8]);
+    }
+}
+
 }  // namespace
 
 bool gemm_stream_supported(int dtype, const StreamGemmArgs &g) {
@@ -283,6 +454,38 @@ int gemm_stream(int dtype, const StreamGemmArgs &g, hipStream_t stream) {
     const dim3 grid(a.tiles_m * a.tiles_n);
     if (dtype == LSTM_DTYPE_FP16) hipLaunchKernelGGL(gemm_stream_kernel<_Float16>, grid, dim3(SG_THREADS), 0, stream, a);
     else hipLaunchKernelGGL(gemm_stream_kernel<bf16_t>, grid, dim3(SG_THREADS), 0, stream, a);
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
+bool gemm_stream_tn_supported(int dtype, const BlockedGemmArgs &g) {
+    if (dtype == LSTM_DTYPE_FP32) return false;
+    if (!g.A.trans || !g.B.trans || !g.out_lp || g.accumulate || g.bias || g.batch > 1 || g.splits > 1) return false;
+    if (g.M <= 0 || g.N <= 0 || g.K < 32 * SG_GRP || g.K % (32 * SG_GRP) != 0) return false;
+    if (g.M % 8 != 0 || g.N % 8 != 0 || g.ldc % 8 != 0) return false;
+    return g.A.ncb >= (g.M + 63) / 64 && g.B.ncb >= (g.N + 63) / 64;
+}
+
+int gemm_stream_tn(int dtype, const BlockedGemmArgs &g, hipStream_t stream) {
+    if (!gemm_stream_tn_supported(dtype, g)) {
+        set_error("gemm_stream_tn: unsupported product M=%d N=%d K=%d (16-bit result of blocked operands whose rows are the "
+                  "contraction index, K a multiple of %d)", g.M, g.N, g.K, 32 * SG_GRP);
+        return LSTM_ERR_INVALID;
+    }
+    if (!g.A.ptr || !g.B.ptr || !g.C || (uintptr_t)g.A.ptr % 16 || (uintptr_t)g.B.ptr % 16 || (uintptr_t)g.C % 16) {
+        set_error("gemm_stream_tn: null or misaligned operand");
+        return LSTM_ERR_INVALID;
+    }
+    StreamTnArgs a{};
+    a.A = (const uint16_t *)g.A.ptr; a.B = (const uint16_t *)g.B.ptr; a.ncb_a = g.A.ncb; a.ncb_b = g.B.ncb;
+    a.C = g.C; a.ldc = g.ldc; a.M = g.M; a.N = g.N; a.K = g.K;
+    a.tiles_m = (g.M + 255) / 256; a.tiles_n = (g.N + 255) / 256;
+    const double flops = 2.0 * g.M * g.N * g.K;
+    const double bytes = 2.0 * ((double)g.M * g.K + (double)g.N * g.K + (double)g.M * g.N);
+    KernelTimer timer(g.kclass, stream, flops, bytes);
+    const dim3 grid(a.tiles_m * a.tiles_n);
+    if (dtype == LSTM_DTYPE_FP16) hipLaunchKernelGGL(gemm_stream_tn_kernel<_Float16>, grid, dim3(SG_THREADS), 0, stream, a);
+    else hipLaunchKernelGGL(gemm_stream_tn_kernel<bf16_t>, grid, dim3(SG_THREADS), 0, stream, a);
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }

@@ -77,3 +77,40 @@ def test_gemm_stream_matches_fp32_matmul(dtype, M, N, K, rps, gated, with_bias):
     err = (got - ref).abs().max().item()
     scale = ref.abs().max().item()
     assert err <= tol * scale, f"max error {err:.3e} against scale {scale:.3e}"
+
+
+TN_CASES = [
+    # M, N, K
+    (512, 512, 256),
+    (768, 320, 384),        # N not a multiple of the 256-column tile, nor of 64
+    (264, 1024, 1152),      # M not a multiple of 64
+    (2048, 2048, 4096),
+]
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+@pytest.mark.parametrize("M,N,K", TN_CASES)
+def test_gemm_stream_tn_matches_fp32_matmul(dtype, M, N, K):
+    """C = A^T B with both operands 64x64-blocked and the contraction index as their rows (the weight-gradient
+    products), on the second kernel (layout 5 of the diagnostic GEMM call)."""
+    code, tdt, tol = DT[dtype]
+    g = torch.Generator().manual_seed(M + 3 * N + 7 * K)
+    A = (torch.randn(K, M, generator=g) * 0.5).to(tdt)
+    B = (torch.randn(K, N, generator=g) * 0.5).to(tdt)
+    ref = A.float().T @ B.float()
+    dev = torch.device("cuda:0")
+
+    def blocked(x):
+        r, c = x.shape
+        out = torch.empty(((r + 63) // 64) * ((c + 63) // 64) * 4096, dtype=tdt, device=dev)
+        hip.lstm_debug_pack_blocked(code, x.to(dev).contiguous(), r, c, out)
+        return out
+
+    C = torch.full((M, N), float("nan"), dtype=tdt, device=dev)
+    hip.lstm_debug_gemm(code, 5, M, N, K, blocked(A), blocked(B), C)
+    torch.cuda.synchronize()
+    got = C.float().cpu()
+    assert torch.isfinite(got).all()
+    err = (got - ref).abs().max().item()
+    scale = ref.abs().max().item()
+    assert err <= tol * scale, f"max error {err:.3e} against scale {scale:.3e}"
