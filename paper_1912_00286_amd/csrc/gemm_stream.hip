@@ -463,17 +463,15 @@ bool gemm_stream_tn_supported(int dtype, const BlockedGemmArgs &g) {
     if (!g.A.trans || !g.B.trans || !g.out_lp || g.accumulate || g.bias || g.batch > 1 || g.splits > 1) return false;
     if (g.M <= 0 || g.N <= 0 || g.K < 32 * SG_GRP || g.K % (32 * SG_GRP) != 0) return false;
     if (g.M % 8 != 0 || g.N % 8 != 0 || g.ldc % 8 != 0) return false;
+    // 16-byte stores into C (a worker's row of a gradient matrix may start at any element: then the other kernel)
+    if (!g.A.ptr || !g.B.ptr || !g.C || (uintptr_t)g.A.ptr % 16 || (uintptr_t)g.B.ptr % 16 || (uintptr_t)g.C % 16) return false;
     return g.A.ncb >= (g.M + 63) / 64 && g.B.ncb >= (g.N + 63) / 64;
 }
 
 int gemm_stream_tn(int dtype, const BlockedGemmArgs &g, hipStream_t stream) {
     if (!gemm_stream_tn_supported(dtype, g)) {
-        set_error("gemm_stream_tn: unsupported product M=%d N=%d K=%d (16-bit result of blocked operands whose rows are the "
-                  "contraction index, K a multiple of %d)", g.M, g.N, g.K, 32 * SG_GRP);
-        return LSTM_ERR_INVALID;
-    }
-    if (!g.A.ptr || !g.B.ptr || !g.C || (uintptr_t)g.A.ptr % 16 || (uintptr_t)g.B.ptr % 16 || (uintptr_t)g.C % 16) {
-        set_error("gemm_stream_tn: null or misaligned operand");
+        set_error("gemm_stream_tn: unsupported product M=%d N=%d K=%d (16-bit result of 16-byte aligned blocked operands whose "
+                  "rows are the contraction index, K a multiple of %d)", g.M, g.N, g.K, 32 * SG_GRP);
         return LSTM_ERR_INVALID;
     }
     StreamTnArgs a{};
