@@ -190,10 +190,10 @@ __global__ __launch_bounds__(THREADS) void gemm_nt_mfma_kernel(KernArgs a) {
 constexpr int GBM = 256, GBN = 256, GBK = 64;
 constexpr int GTHREADS = 512;
 constexpr int GLD = GBK + LDS_PAD;               // row pitch, rows = operand rows
-constexpr int GLDT = GBM + 32;                   // row pitch, rows = k (transposed form)
+constexpr int GLDT = GBM + 16;                   // row pitch, rows = k (transposed form): 8 consecutive rows x 32 bytes cover all banks once
 constexpr int GVPR = GBK / 8;                    // 16-byte vectors per operand row of a K tile
 constexpr int GVPK = GBM / 8;                    // 16-byte vectors per k row (transposed form)
-static_assert(GBM * GLD == GBK * GLDT, "both layouts use the same LDS footprint");
+static_assert(GBK * GLDT <= GBM * GLD, "the transposed layout fits the buffers of the other one");
 
 struct BigSmem {
     uint16_t a[2][GBM * GLD];
@@ -205,12 +205,16 @@ typedef short v4s __attribute__((ext_vector_type(4)));
 // Fragment of the 16x16x32 MFMA (lane = 16 * (k / 8) + row) out of a [k][m] tile: columns m0 .. m0 + 15, 32-deep step
 // q, via two transpose reads: each 16-lane group reads 4 k-rows x 16 columns per instruction and every lane receives
 // the 4 k-values of column (lane % 16).
+// PERM (both operands of the product are read this way): k-group g of the MFMA takes tile rows 4 g .. 4 g + 3 and
+// 16 + 4 g .. 16 + 4 g + 3 of the step instead of 8 g .. 8 g + 7 (any assignment of tile rows to the MFMA's
+// contraction slots is right as long as both operands use it), so that one instruction touches 16 consecutive rows.
+template <bool PERM>
 __device__ __forceinline__ u32x4 read_frag_tr16(const uint16_t *tile, int m0, int q, int lane) {
     const int g = lane >> 4, i = lane & 15;
-    const uint16_t *p = tile + (q * 32 + 8 * g + (i >> 2)) * GLDT + m0 + 4 * (i & 3);
+    const uint16_t *p = tile + (q * 32 + (PERM ? 4 : 8) * g + (i >> 2)) * GLDT + m0 + 4 * (i & 3);
     typedef __attribute__((address_space(3))) v4s *lds_v4s;
     const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)p);
-    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(p + 4 * GLDT));
+    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(p + (PERM ? 16 : 4) * GLDT));
     struct { v4s l, h; } both = {lo, hi};
     return __builtin_bit_cast(u32x4, both);
 }
@@ -423,11 +427,11 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a_in, 
     const int lrow = lane & 15, lk = (lane >> 4) * 8;
     // fragments of 32-deep step q: A rows (wm 64 + 16 i ..), B rows (wn 128 + 16 j ..)
     auto frag_a = [&](int buf, int i, int q) -> u32x4 {
-        if constexpr (TA) return read_frag_tr16(sm.a[buf], wm * 64 + i * 16, q, lane);
+        if constexpr (TA) return read_frag_tr16<TA && TB_>(sm.a[buf], wm * 64 + i * 16, q, lane);
         else return *reinterpret_cast<const u32x4 *>(&sm.a[buf][(wm * 64 + i * 16 + lrow) * GLD + lk + q * 32]);
     };
     auto frag_b = [&](int buf, int j, int q) -> u32x4 {
-        if constexpr (TB_) return read_frag_tr16(sm.b[buf], wn * 128 + j * 16, q, lane);
+        if constexpr (TB_) return read_frag_tr16<TA && TB_>(sm.b[buf], wn * 128 + j * 16, q, lane);
         else return *reinterpret_cast<const u32x4 *>(&sm.b[buf][(wn * 128 + j * 16 + lrow) * GLD + lk + q * 32]);
     };
     // half steps [h0, h1) of the tile in LDS buffer `buf`: half step h = 32-deep step h / 2, column blocks 4 (h % 2) ..
