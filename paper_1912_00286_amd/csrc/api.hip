@@ -1192,7 +1192,7 @@ extern "C" int lstm_debug_plan_regions(const lstm_config *cfg, int32_t max_regio
 // Diagnostic: one whole-sequence GEMM through the same dispatch the training step uses.
 // layout 0: C = A B^T, row-major A[M,K], B[N,K];  1: C = A^T B, row-major A[K,M], B[K,N];
 // 2/3/4: operands in 64x64 blocks (see pack_blocked), roles (A,B) = (rows M, rows N) /
-// (rows M, rows K) / (rows K, rows K); 5: as 4 on the kernel of gemm_stream.hip.  C is row-major lp [M,N].
+// (rows M, rows K) / (rows K, rows K); 5: as 4 on the kernel of gemm_stream.hip; 6: as 5 with every block in fragment order.  C is row-major lp [M,N].
 extern "C" int lstm_debug_gemm(int32_t dtype, int32_t layout, int32_t M, int32_t N, int32_t K, const void *A, const void *B,
                                void *C, float *splitk_ws, int32_t splits, void *stream) {
     hipStream_t s = (hipStream_t)stream;
@@ -1209,7 +1209,8 @@ extern "C" int lstm_debug_gemm(int32_t dtype, int32_t layout, int32_t M, int32_t
     g.B = BlockedOperand{B, ((tb ? N : K) + 63) / 64, tb};
     g.C = C; g.ldc = N; g.out_lp = 1; g.M = M; g.N = N; g.K = K;
     g.splitk_ws = splitk_ws; g.splits = splits; g.kclass = KC_GEMM_BATCHED;
-    return layout == 5 ? gemm_stream_tn(dtype, g, s) : gemm_blocked(dtype, g, s);
+    if (layout == 6) g.A.packed = g.B.packed = 1;
+    return layout >= 5 ? gemm_stream_tn(dtype, g, s) : gemm_blocked(dtype, g, s);
 }
 
 // Diagnostic: the whole-sequence GEMM on operands in packed (MFMA-fragment) order.

@@ -167,6 +167,8 @@ struct BlockedOperand {
     const void *ptr;
     int ncb;      // column blocks per row block (>= ceil(C/64))
     int trans;    // 0: rows index M (resp. N), columns index K; 1: rows index K, columns index M (resp. N)
+    int packed = 0;   // 1: every 64x64 block in MFMA-fragment order (packed.h, two 32-row blocks) instead of row-major:
+                      //    the per-time-step copies the recurrent kernels write, one after the other.  gemm_stream_tn only
 };
 struct BlockedGemmArgs {
     BlockedOperand A, B;

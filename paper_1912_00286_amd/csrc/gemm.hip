@@ -1002,7 +1002,7 @@ int pack_blocked(int dtype, const void *src, int64_t ld, int rows, int cols, voi
 bool gemm_blocked_supported(int dtype, int M, int N) { return dtype != LSTM_DTYPE_FP32 && M >= 192 && N >= 192; }
 
 int gemm_blocked(int dtype, const BlockedGemmArgs &g, hipStream_t stream) {
-    if (!g.A.ptr || !g.B.ptr || !g.C || g.M < 1 || g.N < 1 || g.K < 1 || dtype == LSTM_DTYPE_FP32) {
+    if (!g.A.ptr || !g.B.ptr || !g.C || g.M < 1 || g.N < 1 || g.K < 1 || dtype == LSTM_DTYPE_FP32 || g.A.packed || g.B.packed) {
         set_error("gemm_blocked: invalid argument");
         return LSTM_ERR_INVALID;
     }

@@ -263,9 +263,13 @@ __global__ __launch_bounds__(SG_THREADS) void gemm_stream_kernel(StreamArgs a) {
 //     f(row), f = bit 1 of the row | bit 3 of the row << 1: the sixteen rows one transpose-read instruction touches
 //     (rows 8 g .. 8 g + 3 of its four 16-lane groups g) then spread evenly over the banks.  The swap is applied by
 //     choosing which 16 bytes each lane of a direct-to-LDS load fetches.
+// Operand formats: 64x64 blocks [K / 64][ncb][64][64] (row-major inside a block), or (PK) the packed copies the
+// recurrent kernels write, kept for all time steps one after the other: [K / 64][ncb][64 x 64 in fragment order,
+// packed.h].  Either way 64 contraction rows x 64 columns are 8 KB and a row's 8 columns are 16 contiguous bytes;
+// only the place of those 16 bytes inside the 8 KB differs, i.e. which address each lane of a load fetches.
 struct StreamTnArgs {
-    const uint16_t *A;        // blocked [K / 64][ncb_a][64][64], rows = contraction index, columns = m (first m block at column block 0)
-    const uint16_t *B;        // blocked [K / 64][ncb_b][64][64], columns = n
+    const uint16_t *A;        // rows = contraction index, columns = m (first m block at column block 0)
+    const uint16_t *B;        // columns = n
     int ncb_a, ncb_b;
     void *C;                  // 16-bit, row-major [M, ldc]
     int64_t ldc;
@@ -281,7 +285,18 @@ typedef __attribute__((address_space(3))) sg_v4s *sg_lds_v4s;
 // ALL outstanding loads before every LDS transpose read that follows (it cannot tell the two apart), which would
 // serialise the whole pipeline; the waits these loads need are the explicit ones of the loop.  M0 carries the LDS
 // address (nothing else in the kernel uses it).
+template <bool PK>
 __device__ __forceinline__ void sg_dma_piece4(const void *base, unsigned offset, unsigned lds, int j) {
+    if constexpr (PK) {
+        // packed source: 8 rows further on are 128 bytes further on in memory (and 1 KB in LDS, which goes into M0)
+        switch (j) {
+            case 0: asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" :: "v"(offset), "s"(base), "s"(lds) : "memory"); break;
+            case 1: asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" :: "v"(offset + 128u), "s"(base), "s"(lds + 1024u) : "memory"); break;
+            case 2: asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" :: "v"(offset + 256u), "s"(base), "s"(lds + 2048u) : "memory"); break;
+            default: asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" :: "v"(offset + 384u), "s"(base), "s"(lds + 3072u) : "memory"); break;
+        }
+        return;
+    }
     switch (j) {
         case 0: asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" :: "v"(offset), "s"(base), "s"(lds) : "memory"); break;
         case 1: asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 offset:1024" :: "v"(offset), "s"(base), "s"(lds) : "memory"); break;
@@ -290,7 +305,7 @@ __device__ __forceinline__ void sg_dma_piece4(const void *base, unsigned offset,
     }
 }
 
-template <typename T>
+template <typename T, bool PK>
 __global__ __launch_bounds__(SG_THREADS) void gemm_stream_tn_kernel(StreamTnArgs a) {
     __shared__ __attribute__((aligned(1024))) unsigned char ring[SG_LDS];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -314,17 +329,21 @@ __global__ __launch_bounds__(SG_THREADS) void gemm_stream_tn_kernel(StreamTnArgs
     const int blk0 = (opB ? tn : tm) * 4 + (wave & 1) * 2;
     const int blkc0 = blk0 < nblk ? blk0 : 0, blkc1 = blk0 + 1 < nblk ? blk0 + 1 : 0;      // blocks past the edge: read block 0, never stored
     const int lrow = lane >> 3, lpos = lane & 7;
-    const unsigned lsrc0 = (lrow * 64 + ((lpos ^ ((((lrow >> 1) & 1) | 0) << 1)) * 8)) * 2;   // bytes, pieces with p % 4 even
-    const unsigned lsrc1 = (lrow * 64 + ((lpos ^ ((((lrow >> 1) & 1) | 2) << 1)) * 8)) * 2;   // pieces with p % 4 odd
+    // byte offset of (row lrow, 16-byte chunk ch) inside the 8 rows a piece covers
+    auto chunk_off = [&](int ch) -> unsigned {
+        return PK ? (unsigned)((ch >> 1) * 2048 + (ch & 1) * 512 + lrow * 16) : (unsigned)(lrow * 128 + ch * 16);
+    };
+    const unsigned lsrc0 = chunk_off(lpos ^ ((((lrow >> 1) & 1) | 0) << 1));   // pieces with p % 4 even
+    const unsigned lsrc1 = chunk_off(lpos ^ ((((lrow >> 1) & 1) | 2) << 1));   // pieces with p % 4 odd
     const char *src0 = reinterpret_cast<const char *>(Op + (int64_t)blkc0 * 4096);            // + block row * ncb * 8 KB + half * 4 KB
     const char *src1 = reinterpret_cast<const char *>(Op + (int64_t)blkc1 * 4096);
     unsigned char *my_pieces = ring + wave * 8192;
     const int64_t row_bytes = (int64_t)ncb * 8192;                                             // one block row of the operand
     // pieces q = 0 .. 7 of step c into stage st
     auto dma = [&](int c, int st, int q) {
-        const char *s = (q < 4 ? src0 : src1) + (int64_t)(c >> 1) * row_bytes + (c & 1) * 4096;
+        const char *s = (q < 4 ? src0 : src1) + (int64_t)(c >> 1) * row_bytes + (c & 1) * (PK ? 1024 : 4096);
         const unsigned lds = (unsigned)(uintptr_t)(lds_ptr)(my_pieces + st * SG_STAGE + (q >> 2) * 4096);
-        sg_dma_piece4(s, (q & 1) ? lsrc1 : lsrc0, lds, q & 3);
+        sg_dma_piece4<PK>(s, (q & 1) ? lsrc1 : lsrc0, lds, q & 3);
     };
 
     // Fragments.  Lane (i = lane % 16, g = lane / 16) of a transpose read supplies the address of 4 columns of row
@@ -461,6 +480,7 @@ int gemm_stream(int dtype, const StreamGemmArgs &g, hipStream_t stream) {
 bool gemm_stream_tn_supported(int dtype, const BlockedGemmArgs &g) {
     if (dtype == LSTM_DTYPE_FP32) return false;
     if (!g.A.trans || !g.B.trans || !g.out_lp || g.accumulate || g.bias || g.batch > 1 || g.splits > 1) return false;
+    if (g.A.packed != g.B.packed) return false;
     if (g.M <= 0 || g.N <= 0 || g.K < 32 * SG_GRP || g.K % (32 * SG_GRP) != 0) return false;
     if (g.M % 8 != 0 || g.N % 8 != 0 || g.ldc % 8 != 0) return false;
     // 16-byte stores into C (a worker's row of a gradient matrix may start at any element: then the other kernel)
@@ -482,8 +502,13 @@ int gemm_stream_tn(int dtype, const BlockedGemmArgs &g, hipStream_t stream) {
     const double bytes = 2.0 * ((double)g.M * g.K + (double)g.N * g.K + (double)g.M * g.N);
     KernelTimer timer(g.kclass, stream, flops, bytes);
     const dim3 grid(a.tiles_m * a.tiles_n);
-    if (dtype == LSTM_DTYPE_FP16) hipLaunchKernelGGL(gemm_stream_tn_kernel<_Float16>, grid, dim3(SG_THREADS), 0, stream, a);
-    else hipLaunchKernelGGL(gemm_stream_tn_kernel<bf16_t>, grid, dim3(SG_THREADS), 0, stream, a);
+    if (g.A.packed) {
+        if (dtype == LSTM_DTYPE_FP16) hipLaunchKernelGGL((gemm_stream_tn_kernel<_Float16, true>), grid, dim3(SG_THREADS), 0, stream, a);
+        else hipLaunchKernelGGL((gemm_stream_tn_kernel<bf16_t, true>), grid, dim3(SG_THREADS), 0, stream, a);
+    } else {
+        if (dtype == LSTM_DTYPE_FP16) hipLaunchKernelGGL((gemm_stream_tn_kernel<_Float16, false>), grid, dim3(SG_THREADS), 0, stream, a);
+        else hipLaunchKernelGGL((gemm_stream_tn_kernel<bf16_t, false>), grid, dim3(SG_THREADS), 0, stream, a);
+    }
     LSTM_LAUNCH_CHECK();
     return LSTM_OK;
 }

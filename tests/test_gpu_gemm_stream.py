@@ -114,3 +114,24 @@ def test_gemm_stream_tn_matches_fp32_matmul(dtype, M, N, K):
     err = (got - ref).abs().max().item()
     scale = ref.abs().max().item()
     assert err <= tol * scale, f"max error {err:.3e} against scale {scale:.3e}"
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+@pytest.mark.parametrize("M,N,K", [(512, 512, 256), (768, 320 + 64, 384), (2048, 2048, 4096)])
+def test_gemm_stream_tn_on_fragment_order_blocks(dtype, M, N, K):
+    """The same product with every 64x64 block of both operands in fragment order (layout 6): the packed h_t / dA_t
+    copies of the recurrence, one time step after the other, serve as the weight-gradient operands as they are."""
+    code, tdt, tol = DT[dtype]
+    g = torch.Generator().manual_seed(5 * M + N + K)
+    A = (torch.randn(K, M, generator=g) * 0.5).to(tdt)
+    B = (torch.randn(K, N, generator=g) * 0.5).to(tdt)
+    ref = A.float().T @ B.float()
+    dev = torch.device("cuda:0")
+    C = torch.full((M, N), float("nan"), dtype=tdt, device=dev)
+    hip.lstm_debug_gemm(code, 6, M, N, K, pack_tiles(A, 64).to(dev), pack_tiles(B, 64).to(dev), C)
+    torch.cuda.synchronize()
+    got = C.float().cpu()
+    assert torch.isfinite(got).all()
+    err = (got - ref).abs().max().item()
+    scale = ref.abs().max().item()
+    assert err <= tol * scale, f"max error {err:.3e} against scale {scale:.3e}"
