@@ -72,6 +72,12 @@ struct Plan {
     // packed like the recurrent matrix.  Projection: needs H % 256 == 0; data gradient: always.
     bool lag_sax = false, lag_sdx = false;
     std::vector<size_t> s_lag_hseq, s_lag_daseq;
+    // lag_pk: nothing on the wide-layer path reads the 64x64-blocked copies of h_t and dA_t any more (the
+    // weight-gradient GEMMs take the packed copies too): h_t is written in packed form only, into the region the
+    // blocked sequence would occupy (same size; slot t = h_t), dA_t of the layers above the first into s_lag_daseq
+    // only.  Layer 0 keeps its blocked dA: its dW (narrow input, split K) stays on the general kernel.  Needs the
+    // diagonal backward form and T*B a multiple of 128 (the weight-gradient kernel's K granularity).
+    bool lag_pk = false;
     std::vector<size_t> s_wb_dapk1; // second packed dA per layer (fb: a cell reads one step's while writing the next)
     std::vector<size_t> s_wf_upk, s_wf_wpk, s_wf_c, s_wf_hpk0, s_wf_hpk1;
     // backward along anti-diagonals: per-layer dA (row-major and blocked), packed U^T / W^T, packed dA_t,
@@ -252,6 +258,23 @@ int make_plan(const lstm_config *c, Plan &p) {
     }
     if (p.dtype != LSTM_DTYPE_FP32) {
         const RecurrentDims rd = recurrent_dims(p.B, p.H);
+        // The backward pass along the diagonals keeps every layer's dA (row-major and blocked) until
+        // the weight-gradient GEMMs at the end, instead of one layer's at a time.  It is used while
+        // that extra storage stays within a fixed budget; stacks deep enough to be bound by device
+        // memory (the capacity experiment of Table 1) keep the layer-by-layer backward pass.
+        auto diagonal_backward_fits = [&]() {
+            constexpr size_t kDiagonalBackwardBudget = (size_t)8 << 30;
+            const bool wb_was = p.wb;
+            p.wb = true;                                       // dA_rowmajor_needed() asks as if the form were on
+            size_t extra = 0;
+            for (int l = 0; l < p.L; ++l)
+                extra += (p.dA_rowmajor_needed(l) ? align_up(TB * p.G * p.es) : 0) +
+                         (p.blk ? align_up(blocked_elems((int)TB, p.G) * p.es) : 0) + 2 * align_up(rd.utpk_elems * p.es) +
+                         2 * align_up(rd.dapk_elems * p.es) + 2 * align_up(rd.partial_bytes) + align_up((size_t)p.B * p.H * 4) +
+                         (p.lag ? align_up((size_t)p.T * rd.dapk_elems * p.es) : 0);
+            p.wb = wb_was;
+            return extra <= kDiagonalBackwardBudget;
+        };
         // Stacks of narrow layers: a time step of one layer is a handful of workgroups, so the
         // forward pass runs along anti-diagonals (all layers' ready cells in one launch).
         p.wf = p.L >= 2 && rd.n_mt * rd.n_hb <= 128;
@@ -269,11 +292,15 @@ int make_plan(const lstm_config *c, Plan &p) {
             p.s_lag_hseq.assign(p.L, 0); p.s_lag_daseq.assign(p.L, 0);
             p.lag_sax = p.H % 256 == 0;
             p.lag_sdx = true;
+            p.lag_pk = p.lag_sax && TB % 128 == 0 && gemm_blocked_supported(p.dtype, p.G, p.H) &&
+                       (size_t)(p.T + 1) * rd.hpk_elems <= blocked_elems((int)(TB + p.B), p.H) && diagonal_backward_fits();
+            // (the kernel that takes packed weight-gradient operands has no split-K form)
+            for (int l = 0; l < p.L; ++l) p.lag_pk = p.lag_pk && p.split_u[l] == 1 && (l == 0 || p.split_w[l] == 1);
             for (int l = 1; l < p.L; ++l) {
                 p.s_lag_ax[l] = take(1, (size_t)p.lag_c * p.B * p.G * p.es);
                 p.s_lag_dx[l - 1] = take(1, (size_t)p.lag_c * p.B * p.H * p.es);
                 if (!p.lag_sax) p.s_lag_wblk[l] = take(1, blocked_elems(p.G, p.H) * p.es);
-                if (p.lag_sax) p.s_lag_hseq[l - 1] = take(1, (size_t)(p.T + 1) * rd.hpk_elems * p.es);
+                if (p.lag_sax && !p.lag_pk) p.s_lag_hseq[l - 1] = take(1, (size_t)(p.T + 1) * rd.hpk_elems * p.es);
             }
         }
         if (p.wf) {
@@ -302,21 +329,7 @@ int make_plan(const lstm_config *c, Plan &p) {
         }
         // Narrow layers of any depth: each BPTT cell in one launch instead of two.
         const bool fb_ok = fused_backward_supported(p.dtype, p.B, p.H);
-        if (p.wf || fb_ok) {
-            // The backward pass along the diagonals keeps every layer's dA (row-major and blocked) until
-            // the weight-gradient GEMMs at the end, instead of one layer's at a time.  It is used while
-            // that extra storage stays within a fixed budget; stacks deep enough to be bound by device
-            // memory (the capacity experiment of Table 1) keep the layer-by-layer backward pass.
-            constexpr size_t kDiagonalBackwardBudget = (size_t)8 << 30;
-            p.wb = true;                                       // dA_rowmajor_needed() asks as if the form were on
-            size_t extra = 0;
-            for (int l = 0; l < p.L; ++l)
-                extra += (p.dA_rowmajor_needed(l) ? align_up(TB * p.G * p.es) : 0) +
-                         (p.blk ? align_up(blocked_elems((int)TB, p.G) * p.es) : 0) + 2 * align_up(rd.utpk_elems * p.es) +
-                         2 * align_up(rd.dapk_elems * p.es) + 2 * align_up(rd.partial_bytes) + align_up((size_t)p.B * p.H * 4) +
-                         (p.lag && l > 0 ? align_up((size_t)p.T * rd.dapk_elems * p.es) : 0);
-            p.wb = extra <= kDiagonalBackwardBudget;
-        }
+        if (p.wf || fb_ok) p.wb = diagonal_backward_fits();
         p.fb = p.wb && fb_ok;
         if (p.wb) {
             p.s_wb_dA.resize(p.L); p.s_wb_dablk.assign(p.L, 0); p.s_wb_utpk.resize(p.L); p.s_wb_wtpk.assign(p.L, 0);
@@ -324,10 +337,10 @@ int make_plan(const lstm_config *c, Plan &p) {
             p.s_wb_dc.resize(p.L);
             for (int l = 0; l < p.L; ++l) {
                 p.s_wb_dA[l] = s; if (p.dA_rowmajor_needed(l)) take(1, TB * p.G * p.es);
-                if (p.blk) { p.s_wb_dablk[l] = take(1, blocked_elems((int)TB, p.G) * p.es); }
+                if (p.blk && !(p.lag_pk && l > 0)) { p.s_wb_dablk[l] = take(1, blocked_elems((int)TB, p.G) * p.es); }
                 p.s_wb_utpk[l] = take(1, rd.utpk_elems * p.es);
                 if (l > 0 && (!p.lag || p.lag_sdx)) { p.s_wb_wtpk[l] = take(1, rd.utpk_elems * p.es); }
-                if (l > 0 && p.lag && p.lag_sdx) { p.s_lag_daseq[l] = take(1, (size_t)p.T * rd.dapk_elems * p.es); }
+                if (p.lag && p.lag_sdx && (l > 0 || p.lag_pk)) { p.s_lag_daseq[l] = take(1, (size_t)p.T * rd.dapk_elems * p.es); }
                 p.s_wb_dapk[l] = take(1, rd.dapk_elems * p.es);
                 if (p.fb) { p.s_wb_dapk1[l] = take(1, rd.dapk_elems * p.es); }
                 p.s_wb_partU[l] = s; if (!p.fb) take(1, rd.partial_bytes);
@@ -498,6 +511,8 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
     char *ax = at(scratch, p.s_ax);
     const bool fused = p.dtype != LSTM_DTYPE_FP32;
     const size_t axs = fused ? es : 4;
+    // wide layers: packed h_0 .. h_T of layer l, one slot per step (in place of the blocked sequence when nothing reads that)
+    auto lag_hseq = [&](int l) { return p.lag_pk ? at(reserve, p.r_hblk[l]) : at(scratch, p.s_lag_hseq[l]); };
     SetupBatch setup;
     for (int l = 0; l < p.L; ++l) {
         const void *W = par + p.off_W[l] * es, *U = par + p.off_U[l] * es, *b = par + p.off_b[l] * es;
@@ -552,7 +567,7 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
                             c_state, BH, s));
         char *upk = at(scratch, p.wf ? p.s_wf_upk[l] : p.s_upk);
         char *hpk[2] = {at(scratch, p.wf ? p.s_wf_hpk0[l] : p.s_apk[0]), at(scratch, p.wf ? p.s_wf_hpk1[l] : p.s_apk[1])};
-        if (p.lag && p.lag_sax && l < p.L - 1) hpk[0] = at(scratch, p.s_lag_hseq[l]);   // slot 0 of the kept sequence
+        if (p.lag && p.lag_sax && (l < p.L - 1 || p.lag_pk)) hpk[0] = lag_hseq(l);   // slot 0 of the kept sequence
         char *hseq = p.proj ? at(scratch, p.s_pj_hseq[l & 1]) : nullptr;    // packed h_0 .. h_T of this layer, one slot per step
         if (fused) {
             // recurrent weights and the initial hidden state in packed tile order; the second
@@ -562,9 +577,9 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
             setup.pack_rows(h0 ? at(h0, (size_t)l * BH * es) : nullptr, p.proj ? hseq : hpk[0]);
             if (!p.proj) setup.pack_rows(nullptr, hpk[1]);
         }
-        char *hblk = p.blk ? at(reserve, p.r_hblk[l]) : nullptr;
+        char *hblk = (p.blk && !p.lag_pk) ? at(reserve, p.r_hblk[l]) : nullptr;
         const size_t slot = (size_t)(p.B / 64) * p.h_ncb * 4096 * es;      // bytes of one time slot of the blocked sequence
-        if (p.blk) {
+        if (hblk) {
             // zero padding columns (H not a multiple of 64) once, then slot 0 = initial hidden state
             setup.zero_pad(hblk, (int64_t)TB + p.B, p.H);
             if (!h0) setup.zero(hblk, (int64_t)(slot / 4));
@@ -644,7 +659,7 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
                 if (p.lag_sax) {
                     const RecurrentDims rd = recurrent_dims(p.B, p.H);
                     StreamGemmArgs g{};
-                    g.A = at(scratch, p.s_lag_hseq[l - 1]) + (size_t)(t0 + 1) * rd.hpk_elems * es;
+                    g.A = lag_hseq(l - 1) + (size_t)(t0 + 1) * rd.hpk_elems * es;
                     g.a_step_stride = (int64_t)rd.hpk_elems; g.rows_per_step = p.B;
                     g.B = at(scratch, p.s_wf_wpk[l]); g.gate_h = p.H;
                     g.C = at(scratch, p.s_lag_ax[l]); g.bias = par + p.off_b[l] * es; g.ldc = p.G;
@@ -667,10 +682,10 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
                 char *hpk[2] = {at(scratch, p.s_wf_hpk0[l]), at(scratch, p.s_wf_hpk1[l])};
                 WaveCell c{};
                 c.hpk_prev = hpk[t & 1]; c.hpk_next = hpk[(t + 1) & 1];
-                if (p.lag && p.lag_sax && l < p.L - 1) {
+                if (p.lag && p.lag_sax && (l < p.L - 1 || p.lag_pk)) {
                     const size_t hpk_bytes = recurrent_dims(p.B, p.H).hpk_elems * es;
-                    c.hpk_prev = at(scratch, p.s_lag_hseq[l]) + (size_t)t * hpk_bytes;
-                    c.hpk_next = at(scratch, p.s_lag_hseq[l]) + (size_t)(t + 1) * hpk_bytes;
+                    c.hpk_prev = lag_hseq(l) + (size_t)t * hpk_bytes;
+                    c.hpk_next = lag_hseq(l) + (size_t)(t + 1) * hpk_bytes;
                 }
                 c.Upk = at(scratch, p.s_wf_upk[l]);
                 if (l == 0) {
@@ -687,7 +702,7 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
                 c.gates = at(reserve, p.r_gates[l]) + (size_t)t * p.B * p.G * es;
                 c.c_out = at(reserve, p.r_c[l]) + (size_t)(t + 1) * BH * es;
                 c.h_out = at(reserve, p.r_h[l]) + (size_t)(t + 1) * BH * es;
-                c.h_blk = p.blk ? at(reserve, p.r_hblk[l]) + (size_t)(t + 1) * slot : nullptr;
+                c.h_blk = (p.blk && !p.lag_pk) ? at(reserve, p.r_hblk[l]) + (size_t)(t + 1) * slot : nullptr;
                 // row-major h_t: the head reads the top layer's and the final state is copied out of the last step's;
                 // everything else on the wide-layer path reads the packed or the blocked copy
                 if (p.lag && l < p.L - 1 && t < p.T - 1 && gemm_blocked_supported(p.dtype, p.G, p.H)) c.h_out = nullptr;
@@ -829,7 +844,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
                 LSTM_TRY(pack_blocked(p.dtype, par + p.off_W[l] * es, p.in_dim[l], p.G, p.in_dim[l], at(scratch, p.s_lag_wblk[l]), s));
             setup.zero(at(scratch, p.s_wb_dapk[l]), (int64_t)((rd.dapk_elems * es + 3) / 4));
             if (p.fb) setup.zero(at(scratch, p.s_wb_dapk1[l]), (int64_t)((rd.dapk_elems * es + 3) / 4));
-            if (p.blk) setup.zero_pad(at(scratch, p.s_wb_dablk[l]), TB, p.G);
+            if (p.blk && !(p.lag_pk && l > 0)) setup.zero_pad(at(scratch, p.s_wb_dablk[l]), TB, p.G);
         }
         LSTM_TRY(setup.flush(p.dtype, p.B, p.H, s));
         if (p.fb) {
@@ -915,8 +930,8 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
                 c.dc_state = (float *)at(scratch, p.s_wb_dc[l]);
                 c.dA = dA_rowmajor_needed(l) ? at(scratch, p.s_wb_dA[l]) + (size_t)t * p.B * p.G * es : nullptr;
                 c.dApk = at(scratch, p.s_wb_dapk[l]);
-                if (p.lag && p.lag_sdx && l > 0) c.dApk = at(scratch, p.s_lag_daseq[l]) + (size_t)t * rd.dapk_elems * es;
-                c.dAblk = p.blk ? at(scratch, p.s_wb_dablk[l]) + (size_t)t * slotg : nullptr;
+                if (p.lag && p.lag_sdx && (l > 0 || p.lag_pk)) c.dApk = at(scratch, p.s_lag_daseq[l]) + (size_t)t * rd.dapk_elems * es;
+                c.dAblk = (p.blk && !(p.lag_pk && l > 0)) ? at(scratch, p.s_wb_dablk[l]) + (size_t)t * slotg : nullptr;
                 c.first = t == p.T - 1 ? 1 : 0;
                 gc.push_back(c);
                 if (t > 0) mm.push_back(WaveGemm{c.dApk, at(scratch, p.s_wb_utpk[l]), (float *)at(scratch, p.s_wb_partU[l])});
@@ -954,7 +969,9 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             if (p.blk) setup.zero_pad(at(scratch, p.s_dablk), TB, p.G);
             LSTM_TRY(setup.flush(p.dtype, p.B, p.H, s));
         }
-        char *dablk = p.blk ? at(scratch, p.wb ? p.s_wb_dablk[l] : p.s_dablk) : nullptr;
+        // wide layers above the first: no blocked copy, every reader takes the packed per-step copies
+        const bool pk_only = p.lag_pk && l > 0;
+        char *dablk = (p.blk && !pk_only) ? at(scratch, p.wb ? p.s_wb_dablk[l] : p.s_dablk) : nullptr;
         const bool fused_step = fused && !p.wb && step_backward_fused_supported(p.dtype, p.B, p.H) && (dA_rm || dablk);
         const bool rows_bwd = fused && !p.wb && rows_backward_supported(p.dtype, p.B, p.H) && (dA_rm || dablk);
         if (rows_bwd) {
@@ -1015,7 +1032,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
         char *wblk = p.blk ? at(scratch, p.s_wblk) : nullptr;
         if (p.blk) {
             if (l == 0) in_blk = BlockedOperand{at(reserve, p.r_xblk), (p.in_dim[0] + 63) / 64, 0};
-            else in_blk = BlockedOperand{at(reserve, p.r_hblk[l - 1]) + (size_t)(p.B / 64) * p.h_ncb * 4096 * es, p.h_ncb, 0};
+            else in_blk = BlockedOperand{at(reserve, p.r_hblk[l - 1]) + (size_t)(p.B / 64) * p.h_ncb * 4096 * es, p.h_ncb, 0, p.lag_pk ? 1 : 0};
         }
         if ((l > 0 && !p.wb) || (l == 0 && p.V > 0)) {
             // dX = dA W  for the layer below (or the embedding rows); along the diagonals the layers
@@ -1063,8 +1080,9 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
         if ((!w_blk && !w_tn) || (!u_blk && !u_tn)) LSTM_TRY(transpose_lp(p.dtype, dA, p.G, dAT, TB, TB, p.G, s));
         auto blocked_wgrad = [&](const GemmArgs &r, const BlockedOperand &bop) {
             BlockedGemmArgs g{};
-            g.A = BlockedOperand{dablk, p.g_ncb, 1};
-            g.B = BlockedOperand{bop.ptr, bop.ncb, 1};
+            // both operands blocked, or both the packed per-step copies
+            g.A = bop.packed ? BlockedOperand{at(scratch, p.s_lag_daseq[l]), p.g_ncb, 1, 1} : BlockedOperand{dablk, p.g_ncb, 1, 0};
+            g.B = BlockedOperand{bop.ptr, bop.ncb, 1, bop.packed};
             g.C = r.C; g.ldc = r.ldc; g.out_lp = 1;
             g.M = r.M; g.N = r.N; g.K = r.K;
             g.splitk_ws = r.splitk_ws; g.splits = r.splits; g.kclass = r.kclass;
@@ -1088,7 +1106,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             LSTM_TRY(gemm_nt(p.dtype, w, s));
         }
         if (u_blk) {
-            LSTM_TRY(blocked_wgrad(u, BlockedOperand{at(reserve, p.r_hblk[l]), p.h_ncb, 1}));
+            LSTM_TRY(blocked_wgrad(u, BlockedOperand{at(reserve, p.r_hblk[l]), p.h_ncb, 1, p.lag_pk ? 1 : 0}));
         } else if (u_tn) {
             LSTM_TRY(gemm_tn(p.dtype, ut, s));
         } else {
@@ -1097,6 +1115,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             LSTM_TRY(gemm_nt(p.dtype, u, s));
         }
         if (dA_rm) LSTM_TRY(colsum(p.dtype, dA, p.G, TB / p.W, p.G, nullptr, nullptr, colpart, grd + p.off_b[l] * es, s, p.W, p.Bw, p.P));
+        else if (pk_only) LSTM_TRY(colsum_blocked(p.dtype, at(scratch, p.s_lag_daseq[l]), p.g_ncb, TB, p.G, colpart, grd + p.off_b[l] * es, s, 1, 0, 0, 1));
         else LSTM_TRY(colsum_blocked(p.dtype, dablk, p.g_ncb, TB / p.W, p.G, colpart, grd + p.off_b[l] * es, s, p.W, p.Bw, p.P));
         cur ^= 1;
         dh_above = d_below;

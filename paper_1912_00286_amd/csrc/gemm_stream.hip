@@ -266,7 +266,8 @@ __global__ __launch_bounds__(SG_THREADS) void gemm_stream_kernel(StreamArgs a) {
 // Operand formats: 64x64 blocks [K / 64][ncb][64][64] (row-major inside a block), or (PK) the packed copies the
 // recurrent kernels write, kept for all time steps one after the other: [K / 64][ncb][64 x 64 in fragment order,
 // packed.h].  Either way 64 contraction rows x 64 columns are 8 KB and a row's 8 columns are 16 contiguous bytes;
-// only the place of those 16 bytes inside the 8 KB differs, i.e. which address each lane of a load fetches.
+// only the place of those 16 bytes inside the 8 KB differs.  The packed form keeps that order in LDS too (see the
+// loads in the kernel), with the transpose reads addressed accordingly.
 struct StreamTnArgs {
     const uint16_t *A;        // rows = contraction index, columns = m (first m block at column block 0)
     const uint16_t *B;        // columns = n
@@ -288,13 +289,10 @@ typedef __attribute__((address_space(3))) sg_v4s *sg_lds_v4s;
 template <bool PK>
 __device__ __forceinline__ void sg_dma_piece4(const void *base, unsigned offset, unsigned lds, int j) {
     if constexpr (PK) {
-        // packed source: 8 rows further on are 128 bytes further on in memory (and 1 KB in LDS, which goes into M0)
-        switch (j) {
-            case 0: asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" :: "v"(offset), "s"(base), "s"(lds) : "memory"); break;
-            case 1: asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" :: "v"(offset + 128u), "s"(base), "s"(lds + 1024u) : "memory"); break;
-            case 2: asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" :: "v"(offset + 256u), "s"(base), "s"(lds + 2048u) : "memory"); break;
-            default: asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" :: "v"(offset + 384u), "s"(base), "s"(lds + 3072u) : "memory"); break;
-        }
+        // packed source: a piece is the kilobyte of one 16-column group (32 rows x 2 halves of 8 columns); the next
+        // group lies 2 KB further on in memory (scalar base) and 1 KB further on in LDS (M0)
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     :: "v"(offset), "s"(reinterpret_cast<const char *>(base) + 2048 * j), "s"(lds + 1024u * j) : "memory");
         return;
     }
     switch (j) {
@@ -328,13 +326,17 @@ __global__ __launch_bounds__(SG_THREADS) void gemm_stream_tn_kernel(StreamTnArgs
     const int ncb = opB ? a.ncb_b : a.ncb_a, nblk = ((opB ? a.N : a.M) + 63) / 64;
     const int blk0 = (opB ? tn : tm) * 4 + (wave & 1) * 2;
     const int blkc0 = blk0 < nblk ? blk0 : 0, blkc1 = blk0 + 1 < nblk ? blk0 + 1 : 0;      // blocks past the edge: read block 0, never stored
+    // Packed operands (PK) keep their own order in LDS instead: a piece is one 16-column group of a block, the
+    // contiguous kilobyte [8-column half][row 0 .. 31][16 bytes], so that neighbouring lanes fetch neighbouring
+    // memory (fetching the row-major image out of it would send the eight lanes of a row to eight different lines).
+    // Only the rows of the second half are stored with bit 2 flipped (again by the choice of what a lane fetches):
+    // the two halves one transpose read touches then fall on different banks.
     const int lrow = lane >> 3, lpos = lane & 7;
     // byte offset of (row lrow, 16-byte chunk ch) inside the 8 rows a piece covers
-    auto chunk_off = [&](int ch) -> unsigned {
-        return PK ? (unsigned)((ch >> 1) * 2048 + (ch & 1) * 512 + lrow * 16) : (unsigned)(lrow * 128 + ch * 16);
-    };
-    const unsigned lsrc0 = chunk_off(lpos ^ ((((lrow >> 1) & 1) | 0) << 1));   // pieces with p % 4 even
-    const unsigned lsrc1 = chunk_off(lpos ^ ((((lrow >> 1) & 1) | 2) << 1));   // pieces with p % 4 odd
+    auto chunk_off = [&](int ch) -> unsigned { return (unsigned)(lrow * 128 + ch * 16); };
+    const unsigned lsrc_pk = (unsigned)(((lane & 32) + ((lane & 31) ^ ((lane >> 5) << 2))) * 16);
+    const unsigned lsrc0 = PK ? lsrc_pk : chunk_off(lpos ^ ((((lrow >> 1) & 1) | 0) << 1));   // pieces with p % 4 even
+    const unsigned lsrc1 = PK ? lsrc_pk : chunk_off(lpos ^ ((((lrow >> 1) & 1) | 2) << 1));   // pieces with p % 4 odd
     const char *src0 = reinterpret_cast<const char *>(Op + (int64_t)blkc0 * 4096);            // + block row * ncb * 8 KB + half * 4 KB
     const char *src1 = reinterpret_cast<const char *>(Op + (int64_t)blkc1 * 4096);
     unsigned char *my_pieces = ring + wave * 8192;
@@ -354,9 +356,14 @@ __global__ __launch_bounds__(SG_THREADS) void gemm_stream_tn_kernel(StreamTnArgs
     unsigned tr_off[4];                                   // 16-column group cp of a block: byte offset of this lane's first read
 #pragma unroll
     for (int cp = 0; cp < 4; ++cp) tr_off[cp] = (8 * tg + (ti >> 2)) * 128 + ((cp ^ tf) << 5) + (ti & 3) * 8;
+    // PK: group cp is the kilobyte cp; inside it [half = bit 1 of ti][row, bit 2 flipped in the second half][16 bytes],
+    // and the second read (4 rows further on) is the same address with that row bit the other way round
+    const int th = (ti >> 1) & 1;
+    const unsigned tr_pk = (unsigned)(th * 512 + ((8 * tg + (ti >> 2)) ^ (th << 2)) * 16 + (ti & 1) * 8);
+    const unsigned tr_pk2 = tr_pk ^ 64u;
     auto read_frag = [&](const unsigned char *blk, int cp) -> u32x4 {
-        const sg_v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((sg_lds_v4s)(blk + tr_off[cp]));
-        const sg_v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((sg_lds_v4s)(blk + tr_off[cp] + 512));
+        const sg_v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((sg_lds_v4s)(blk + (PK ? tr_pk + cp * 1024 : tr_off[cp])));
+        const sg_v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((sg_lds_v4s)(blk + (PK ? tr_pk2 + cp * 1024 : tr_off[cp] + 512)));
         struct { sg_v4s l, h; } both = {lo, hi};
         return __builtin_bit_cast(u32x4, both);
     };

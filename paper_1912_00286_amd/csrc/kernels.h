@@ -44,9 +44,10 @@ int colsum(int dtype, const void *in, int64_t ld, int R, int C, const float *row
 // blocks per row block; partial holds workers * colsum_blocked_chunks(R) * C floats.  Several workers:
 // R rows each, laid out as consecutive segments of seg_rows rows (a multiple of 64) per worker that
 // repeat every workers * seg_rows rows; worker w's sums go to out_lp + w * out_stride.
+// packed = 1: every 64x64 block holds its elements in MFMA-fragment order (packed.h, two 32-row blocks).
 int colsum_blocked_chunks(int R);
 int colsum_blocked(int dtype, const void *blk, int ncb, int R, int C, float *partial, void *out_lp, hipStream_t s, int workers = 1,
-                   int seg_rows = 0, int64_t out_stride = 0);
+                   int seg_rows = 0, int64_t out_stride = 0, int packed = 0);
 
 // head forward: z = h.w + b per row; loss partial sums; dzu = dloss/dz (unscaled, already / M)
 int head_loss_blocks(int rows);

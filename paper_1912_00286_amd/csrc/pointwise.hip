@@ -2,6 +2,7 @@
 // gate non-linearities forward/backward, transposes, column sums, the output
 // head with its loss, embedding gather / scatter-add, casts and fills.
 #include "kernels.h"
+#include "packed.h"
 
 namespace lstm {
 
@@ -185,14 +186,17 @@ __global__ __launch_bounds__(256) void colsum_partial_vec_kernel(const T *in, in
 // workgroup owns one column block and up to CSB_BLOCKS row blocks, reads them as whole 8 KB
 // blocks (thread = 8 columns of one of 32 row slots) and writes one partial row.
 constexpr int CSB_BLOCKS = 8;
+// packed: every block is in MFMA-fragment order instead (16 bytes = 8 columns of one row, the rows of a 32-row half one
+// after the other); the threads then take consecutive rows, so that a wavefront still reads whole lines.
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_blocked_partial_kernel(const T *blk, int ncb, int nrb, int C, float *partial, int seg,
-                                                                     int stride) {
+                                                                     int stride, int packed) {
     // Several workers (blockIdx.z): worker z owns `seg` consecutive row blocks out of every `stride`
     // (its rows of one time step); its i-th row block is (i / seg) * stride + z * seg + i % seg.
     // One worker: seg = stride, which makes that i.
     __shared__ float red[32][65];
-    const int cb = blockIdx.x, c8 = (threadIdx.x & 7) * 8, rs = threadIdx.x >> 3;
+    const int cb = blockIdx.x;
+    const int c8 = (packed ? threadIdx.x >> 5 : threadIdx.x & 7) * 8, rs = packed ? threadIdx.x & 31 : threadIdx.x >> 3;
     const int rb0 = blockIdx.y * CSB_BLOCKS, rb1 = min(nrb, rb0 + CSB_BLOCKS);
     float s[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
     for (int i = rb0; i < rb1; ++i) {
@@ -200,7 +204,7 @@ __global__ __launch_bounds__(256) void colsum_blocked_partial_kernel(const T *bl
         const T *b = blk + (rb * ncb + cb) * 4096;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const u32x4 raw = *reinterpret_cast<const u32x4 *>(b + (rs + 32 * h) * 64 + c8);
+            const u32x4 raw = *reinterpret_cast<const u32x4 *>(b + (packed ? frag_offset(rs + 32 * h, c8, 2) : (rs + 32 * h) * 64 + c8));
             T v[8];
             __builtin_memcpy(v, &raw, 16);
 #pragma unroll
@@ -558,7 +562,7 @@ int colsum(int dtype, const void *in, int64_t ld, int R, int C, const float *row
 int colsum_blocked_chunks(int R) { return R <= 0 ? 1 : ((R + 63) / 64 + CSB_BLOCKS - 1) / CSB_BLOCKS; }
 
 int colsum_blocked(int dtype, const void *blk, int ncb, int R, int C, float *partial, void *out_lp, hipStream_t s, int workers,
-                   int seg_rows, int64_t out_stride) {
+                   int seg_rows, int64_t out_stride, int packed) {
     KernelTimer timer(KC_AUX, s, 0.0, 0.0);
     if (C <= 0) return LSTM_OK;
     // R rows per worker; with several workers every time step holds `workers` segments of seg_rows rows
@@ -573,7 +577,7 @@ int colsum_blocked(int dtype, const void *blk, int ncb, int R, int C, float *par
     LSTM_DISPATCH(dtype, T, {
         if constexpr (sizeof(T) == 2)
             hipLaunchKernelGGL(colsum_blocked_partial_kernel<T>, dim3((C + 63) / 64, chunks, workers), dim3(256), 0, s, (const T *)blk,
-                               ncb, nrb, C, partial, seg, stride);
+                               ncb, nrb, C, partial, seg, stride, packed);
         hipLaunchKernelGGL(colsum_final_kernel<T>, dim3((C + 255) / 256, workers), dim3(256), 0, s, partial, chunks, C,
                            (const float *)nullptr, (T *)out_lp, out_stride);
     });

@@ -1931,7 +1931,7 @@ int gates_backward_wave(int dtype, const WaveGates *c, int n_cells, int blk_ncb,
     WaveGateArgs w;
     for (int i = 0; i < WAVE_MAX_GATES; ++i) {
         const WaveGates &x = c[i < n_cells ? i : 0];
-        if (!x.gates || !x.c_t || !x.c_prev || !x.dc_state || (!x.dA && !x.dAblk) || !x.dApk || (!x.first && !x.partials) || (!x.dh_above && !x.above4)) {
+        if (!x.gates || !x.c_t || !x.c_prev || !x.dc_state || !x.dApk || (!x.first && !x.partials) || (!x.dh_above && !x.above4)) {
             set_error("gates_backward_wave: null operand in cell %d", i);
             return LSTM_ERR_INVALID;
         }

@@ -324,7 +324,7 @@ int step_forward_tile(int dtype, const WaveCell *cells, int n_cells, int blk_ncb
     uintptr_t all = 0;
     for (int i = 0; i < TILE_MAX_CELLS; ++i) {
         const WaveCell &c = cells[i < n_cells ? i : 0];
-        if (!c.hpk_prev || !c.Upk || !c.Ax || !c.c_state || !c.gates || !c.c_out || !c.hpk_next || (!c.h_out && !c.h_blk)) {
+        if (!c.hpk_prev || !c.Upk || !c.Ax || !c.c_state || !c.gates || !c.c_out || !c.hpk_next) {
             set_error("step_forward_tile: null operand in cell %d", i);
             return LSTM_ERR_INVALID;
         }
