@@ -78,6 +78,10 @@ struct Plan {
     // only.  Layer 0 keeps its blocked dA: its dW (narrow input, split K) stays on the general kernel.  Needs the
     // diagonal backward form and T*B a multiple of 128 (the weight-gradient kernel's K granularity).
     bool lag_pk = false;
+    // lag_x0: layer 0 as well (input width a multiple of 256): the input sequence is kept packed, in the region its
+    // blocked copy would occupy, its projection runs on the packed-operand kernel and its dW on the weight-gradient
+    // kernel with split K.  dA_0 then keeps a blocked copy only where the embedding's data gradient reads it.
+    bool lag_x0 = false;
     std::vector<size_t> s_wb_dapk1; // second packed dA per layer (fb: a cell reads one step's while writing the next)
     std::vector<size_t> s_wf_upk, s_wf_wpk, s_wf_c, s_wf_hpk0, s_wf_hpk1;
     // backward along anti-diagonals: per-layer dA (row-major and blocked), packed U^T / W^T, packed dA_t,
@@ -86,6 +90,8 @@ struct Plan {
     std::vector<size_t> wT_off, uT_off;  // byte offsets inside the s_wT region
     // The row-major copy of dA is only kept where something reads it: with every consumer (dX, dW,
     // dU, the bias gradient) on the blocked copy it is left out.
+    // wide layers whose dA has no blocked copy: every reader takes the packed per-step copies
+    bool dA_packed_only(int l) const { return lag_pk && (l > 0 || (lag_x0 && V == 0)); }
     bool dA_rowmajor_needed(int l) const {
         if (!blk) return true;
         const int TB = T * B, I = in_dim[l];
@@ -296,6 +302,7 @@ int make_plan(const lstm_config *c, Plan &p) {
                        (size_t)(p.T + 1) * rd.hpk_elems <= blocked_elems((int)(TB + p.B), p.H) && diagonal_backward_fits();
             // (the kernel that takes packed weight-gradient operands has no split-K form)
             for (int l = 0; l < p.L; ++l) p.lag_pk = p.lag_pk && p.split_u[l] == 1 && (l == 0 || p.split_w[l] == 1);
+            p.lag_x0 = p.lag_pk && p.in_dim[0] % 256 == 0 && TB % (128 * (size_t)p.split_w[0]) == 0;
             for (int l = 1; l < p.L; ++l) {
                 p.s_lag_ax[l] = take(1, (size_t)p.lag_c * p.B * p.G * p.es);
                 p.s_lag_dx[l - 1] = take(1, (size_t)p.lag_c * p.B * p.H * p.es);
@@ -308,6 +315,7 @@ int make_plan(const lstm_config *c, Plan &p) {
             for (int l = 0; l < p.L; ++l) {
                 p.s_wf_upk[l] = take(1, rd.upk_elems * p.es);
                 if (l > 0 && (!p.lag || p.lag_sax)) { p.s_wf_wpk[l] = take(1, rd.upk_elems * p.es); }
+                if (l == 0 && p.lag_x0) { p.s_wf_wpk[0] = take(1, (size_t)p.G * p.in_dim[0] * p.es); }
                 p.s_wf_hpk0[l] = take(1, rd.hpk_elems * p.es);
                 p.s_wf_hpk1[l] = take(1, rd.hpk_elems * p.es);
                 p.s_wf_c[l] = take(1, (size_t)p.B * p.H * 4);
@@ -337,7 +345,7 @@ int make_plan(const lstm_config *c, Plan &p) {
             p.s_wb_dc.resize(p.L);
             for (int l = 0; l < p.L; ++l) {
                 p.s_wb_dA[l] = s; if (p.dA_rowmajor_needed(l)) take(1, TB * p.G * p.es);
-                if (p.blk && !(p.lag_pk && l > 0)) { p.s_wb_dablk[l] = take(1, blocked_elems((int)TB, p.G) * p.es); }
+                if (p.blk && !p.dA_packed_only(l)) { p.s_wb_dablk[l] = take(1, blocked_elems((int)TB, p.G) * p.es); }
                 p.s_wb_utpk[l] = take(1, rd.utpk_elems * p.es);
                 if (l > 0 && (!p.lag || p.lag_sdx)) { p.s_wb_wtpk[l] = take(1, rd.utpk_elems * p.es); }
                 if (p.lag && p.lag_sdx && (l > 0 || p.lag_pk)) { p.s_lag_daseq[l] = take(1, (size_t)p.T * rd.dapk_elems * p.es); }
@@ -522,7 +530,19 @@ extern "C" int lstm_forward(const lstm_config *cfg, const void *params_lp, const
         float *c_state = (float *)at(scratch, p.wf ? p.s_wf_c[l] : p.s_cstate);
         // input projection of the whole sequence: Ax = X W^T + b  (along the anti-diagonals only
         // layer 0 has its input ahead of time; the layers above project inside their step kernels)
-        if (p.lag && l > 0 && !p.lag_sax) {
+        if (l == 0 && p.lag_x0) {
+            // the packed-operand kernel: x packed step by step like the h_t sequences, W like the recurrent matrix
+            const int I = p.in_dim[0];
+            LSTM_TRY(pack_w_forward(p.dtype, W, at(scratch, p.s_wf_wpk[0]), p.H, I, s));
+            LSTM_TRY(pack_rows_seq(p.dtype, layer_in, at(reserve, p.r_xblk), p.T, p.B, I, (int64_t)p.B * I, s));
+            StreamGemmArgs g{};
+            g.A = at(reserve, p.r_xblk); g.a_step_stride = (int64_t)p.B * I; g.rows_per_step = p.B;
+            g.B = at(scratch, p.s_wf_wpk[0]); g.gate_h = p.H;
+            g.C = ax; g.bias = b; g.ldc = p.G;
+            g.M = (int)TB; g.N = p.G; g.K = I;
+            g.kclass = KC_GEMM_BATCHED;
+            LSTM_TRY(gemm_stream(p.dtype, g, s));
+        } else if (p.lag && l > 0 && !p.lag_sax) {
             // projected chunk by chunk between the step launches below: W in 64x64 blocks once
             LSTM_TRY(pack_blocked(p.dtype, W, p.in_dim[l], p.G, p.in_dim[l], at(scratch, p.s_lag_wblk[l]), s));
         } else if (p.wf && l > 0) {
@@ -844,7 +864,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
                 LSTM_TRY(pack_blocked(p.dtype, par + p.off_W[l] * es, p.in_dim[l], p.G, p.in_dim[l], at(scratch, p.s_lag_wblk[l]), s));
             setup.zero(at(scratch, p.s_wb_dapk[l]), (int64_t)((rd.dapk_elems * es + 3) / 4));
             if (p.fb) setup.zero(at(scratch, p.s_wb_dapk1[l]), (int64_t)((rd.dapk_elems * es + 3) / 4));
-            if (p.blk && !(p.lag_pk && l > 0)) setup.zero_pad(at(scratch, p.s_wb_dablk[l]), TB, p.G);
+            if (p.blk && !p.dA_packed_only(l)) setup.zero_pad(at(scratch, p.s_wb_dablk[l]), TB, p.G);
         }
         LSTM_TRY(setup.flush(p.dtype, p.B, p.H, s));
         if (p.fb) {
@@ -931,7 +951,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
                 c.dA = dA_rowmajor_needed(l) ? at(scratch, p.s_wb_dA[l]) + (size_t)t * p.B * p.G * es : nullptr;
                 c.dApk = at(scratch, p.s_wb_dapk[l]);
                 if (p.lag && p.lag_sdx && (l > 0 || p.lag_pk)) c.dApk = at(scratch, p.s_lag_daseq[l]) + (size_t)t * rd.dapk_elems * es;
-                c.dAblk = (p.blk && !(p.lag_pk && l > 0)) ? at(scratch, p.s_wb_dablk[l]) + (size_t)t * slotg : nullptr;
+                c.dAblk = (p.blk && !p.dA_packed_only(l)) ? at(scratch, p.s_wb_dablk[l]) + (size_t)t * slotg : nullptr;
                 c.first = t == p.T - 1 ? 1 : 0;
                 gc.push_back(c);
                 if (t > 0) mm.push_back(WaveGemm{c.dApk, at(scratch, p.s_wb_utpk[l]), (float *)at(scratch, p.s_wb_partU[l])});
@@ -969,8 +989,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             if (p.blk) setup.zero_pad(at(scratch, p.s_dablk), TB, p.G);
             LSTM_TRY(setup.flush(p.dtype, p.B, p.H, s));
         }
-        // wide layers above the first: no blocked copy, every reader takes the packed per-step copies
-        const bool pk_only = p.lag_pk && l > 0;
+        const bool pk_only = p.dA_packed_only(l);
         char *dablk = (p.blk && !pk_only) ? at(scratch, p.wb ? p.s_wb_dablk[l] : p.s_dablk) : nullptr;
         const bool fused_step = fused && !p.wb && step_backward_fused_supported(p.dtype, p.B, p.H) && (dA_rm || dablk);
         const bool rows_bwd = fused && !p.wb && rows_backward_supported(p.dtype, p.B, p.H) && (dA_rm || dablk);
@@ -1031,7 +1050,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
         BlockedOperand in_blk{nullptr, 0, 0};
         char *wblk = p.blk ? at(scratch, p.s_wblk) : nullptr;
         if (p.blk) {
-            if (l == 0) in_blk = BlockedOperand{at(reserve, p.r_xblk), (p.in_dim[0] + 63) / 64, 0};
+            if (l == 0) in_blk = BlockedOperand{at(reserve, p.r_xblk), (p.in_dim[0] + 63) / 64, 0, p.lag_x0 ? 1 : 0};
             else in_blk = BlockedOperand{at(reserve, p.r_hblk[l - 1]) + (size_t)(p.B / 64) * p.h_ncb * 4096 * es, p.h_ncb, 0, p.lag_pk ? 1 : 0};
         }
         if ((l > 0 && !p.wb) || (l == 0 && p.V > 0)) {

@@ -190,6 +190,8 @@ size_t blocked_elems(int rows, int cols);
 // dst (blocked, zero padded) = src (row-major [rows, cols], leading dimension ld)
 int pack_blocked(int dtype, const void *src, int64_t ld, int rows, int cols, void *dst, hipStream_t stream);
 bool gemm_blocked_supported(int dtype, int M, int N);
+// 16-bit C [M, ldc] = sum of `splits` fp32 partial results ws [split][M][N], added up in index order
+int splitk_reduce(int dtype, const float *ws, int splits, int M, int N, void *C, int64_t ldc, hipStream_t stream);
 // C = op(A) op(B)^T-style product of blocked operands (roles per BlockedOperand::trans);
 // supported role pairs: (0,0), (0,1), (1,1).
 int gemm_blocked(int dtype, const BlockedGemmArgs &g, hipStream_t stream);

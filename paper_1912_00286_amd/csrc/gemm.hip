@@ -805,6 +805,17 @@ int finish_splitk(const GemmArgs &g, int splits, hipStream_t stream) {
     return LSTM_OK;
 }
 
+}  // namespace
+// 16-bit C = sum of `splits` fp32 partial results [split][M][N], added up in index order
+int splitk_reduce(int dtype, const float *ws, int splits, int M, int N, void *C, int64_t ldc, hipStream_t stream) {
+    GemmArgs g{};
+    g.splitk_ws = const_cast<float *>(ws); g.M = M; g.N = N; g.C = C; g.ldc = ldc; g.out_lp = 1;
+    if (dtype == LSTM_DTYPE_FP16) return finish_splitk<_Float16>(g, splits, stream);
+    if (dtype == LSTM_DTYPE_BF16) return finish_splitk<bf16_t>(g, splits, stream);
+    set_error("splitk_reduce: 16-bit types only");
+    return LSTM_ERR_UNSUPPORTED;
+}
+namespace {
 // Bytes a GEMM moves if every operand is read once and the result written once
 // (read too when accumulating): what the event timer accounts the launch with.
 template <typename T, typename Args>

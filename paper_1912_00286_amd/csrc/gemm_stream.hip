@@ -21,6 +21,8 @@
 //     are read ahead of it.
 // The K loop is unrolled over groups of four chunks with a branch-free body (ring slots and outstanding-load
 // counts are compile-time constants); K must be a multiple of 256.
+#include <type_traits>
+
 #include "kernels.h"
 #include "packed.h"
 
@@ -100,7 +102,13 @@ __global__ __launch_bounds__(SG_THREADS) void gemm_stream_kernel(StreamArgs a) {
     // lets a load take its address from scalar registers + one vector register + an immediate)
     const char *Aw = reinterpret_cast<const char *>(a.A + (int64_t)(rtc / a.tiles_per_step) * a.a_step_stride +
                                                     (int64_t)(rtc % a.tiles_per_step) * a.nkc * A_CHUNK);
-    const unsigned lane16 = lane * 16;
+    // A lane's 16 bytes of a 1 KB piece of a B stage.  The piece is [k half][row 0 .. 31 of a 32-row block]; the LDS
+    // image keeps that shape but holds row 8 (i / 4) + 4 s + i % 4 of the block in slot 16 s + i (s = 0, 1; i = 0 .. 15),
+    // by letting the lane of that slot fetch that row: the 16-row fragment s of the block then holds, at MFMA index
+    // 4 g + r, column 8 g + 4 s + r of the block's 32, so that the two fragments' accumulators of a lane are 8
+    // consecutive columns of C (see the result stores below).
+    const int slot = lane & 31;
+    const unsigned lane16 = (unsigned)(((lane & 32) + 8 * ((slot & 15) >> 2) + 4 * (slot >> 4) + (slot & 3)) * 16);
     // its eight 1 KB pieces of every B stage: pieces 8 w .. 8 w + 7 of 32 (the first 16 belong to B tile 2 tn)
     const int bt = 2 * tn + (wave >> 1), btc = bt < a.n_btiles ? bt : 0;
     const char *Bw = reinterpret_cast<const char *>(a.Bpk + (int64_t)btc * a.nkc * B_CHUNK + (wave & 1) * 8 * 64 * 8);
@@ -134,8 +142,9 @@ __global__ __launch_bounds__(SG_THREADS) void gemm_stream_kernel(StreamArgs a) {
     auto half32 = [&](const u32x4 (&ar)[8], int q, int tile, int stn, int qn, const char *srcB, unsigned char *dstB, int pb,
                       u32x4 (&arl)[8], int ql, const char *srcA) {
         const unsigned char *pn = ring + stn * SG_STAGE + (tile ^ 1) * 16384 + qn * 8192 + laneB;
-        // MFMA n of the half: column block tile * 8 + n / 4, row block n % 4
-        auto mm = [&](int n) { mfma_acc<T>(acc[n & 3][tile * 8 + (n >> 2)], ar[q * 4 + (n & 3)], bf[tile][n >> 2]); };
+        // MFMA n of the half: column block tile * 8 + n / 4, row block n % 4.  The B fragment is the first operand: a
+        // lane's four accumulator values are then four columns of one row of C
+        auto mm = [&](int n) { mfma_acc<T>(acc[n & 3][tile * 8 + (n >> 2)], bf[tile][n >> 2], ar[q * 4 + (n & 3)]); };
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             mm(2 * j);
@@ -203,48 +212,67 @@ __global__ __launch_bounds__(SG_THREADS) void gemm_stream_kernel(StreamArgs a) {
     }
     sg_wait_vm<0>();
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // the last MFMAs leave the pipe before their accumulators are read
-    __syncthreads();                                     // every stage is free: the ring becomes the staged result tile
-
-    // 16-bit result: stage the tile (bias added) and write whole 128-byte row segments
-    T *stage = reinterpret_cast<T *>(ring);
+    // 16-bit result (bias added) straight from the accumulators.  Lane (m = lane % 16, g = lane / 16) holds, of the
+    // 32-column group p = (B tile p / 4, 32-row block p % 4) and row block i, columns 8 g .. 8 g + 3 in the group's
+    // first fragment and 8 g + 4 .. 8 g + 7 in its second, all of row 16 i + m: 16 bytes, and the four lanes of a row
+    // 64 consecutive bytes.  Stores want whole 128-byte lines (half lines were measured at a third of the rate), so
+    // two groups that are neighbours in C are written together: lanes m < 8 and m >= 8 swap one group's values
+    // (lane m with lane m ^ 8, a rotation by 8 inside the row of 16 lanes), after which one store instruction covers
+    // rows 0 .. 7 of the block and the next rows 8 .. 15, 128 bytes each.
+    T *C = reinterpret_cast<T *>(a.C);
     const T *bias = reinterpret_cast<const T *>(a.bias);
-    const int col_l = lane & 15, rgrp = (lane >> 4) * 4;
+    const int ml = lane & 15, g8 = (lane >> 4) * 8;
+    const bool lo = ml < 8;
+    const int row0 = tm * 256 + wave * 64 + (ml & 7);
+    // groups pa and pb = pa's right-hand neighbour; col: first column of the lane's 8 in group pa
+    auto store_pair = [&](auto pa_c, auto pb_c, int col, int colb, bool oka, bool okb) {
+        constexpr int pa = decltype(pa_c)::value, pb = decltype(pb_c)::value;
+        __attribute__((aligned(16))) T bla[8], blb[8];
+        if (bias && oka) *reinterpret_cast<u32x4 *>(bla) = *reinterpret_cast<const u32x4 *>(bias + col);
+        if (bias && okb) *reinterpret_cast<u32x4 *>(blb) = *reinterpret_cast<const u32x4 *>(bias + colb);
+        float bva[8], bvb[8];
 #pragma unroll
-    for (int f = 0; f < 16; ++f) {
-        // B row of column block f: tile f / 8, 32-row block (f % 8) / 2, half f % 2.  Staged column order: gate-major
-        // when the B rows interleave gates, so that a row's segments are contiguous in C
-        const int tile = f >> 3, blk = (f & 7) >> 1, sub = f & 1;
-        const int sc = a.gate_h ? (blk * 2 + tile) * 32 + sub * 16 + col_l : f * 16 + col_l;
-        const int unit = (2 * tn + tile) * 32 + sub * 16 + col_l;
-        const int col = a.gate_h ? blk * a.gate_h + unit : tn * 256 + f * 16 + col_l;
-        const bool col_ok = a.gate_h ? unit < a.gate_h : col < a.N;
-        const float bv = (bias && col_ok) ? Lp<T>::to_f(bias[col]) : 0.0f;
+        for (int e = 0; e < 8; ++e) {
+            bva[e] = (bias && oka) ? Lp<T>::to_f(bla[e]) : 0.0f;
+            bvb[e] = (bias && okb) ? Lp<T>::to_f(blb[e]) : 0.0f;
+        }
+        const bool ok = lo ? oka : okb;                  // of the group this lane stores
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4; ++i) {
+            __attribute__((aligned(16))) T oa[8], ob[8];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int rl = wave * 64 + i * 16 + rgrp + r;
-                stage[rl * SG_OLD + sc] = Lp<T>::from_f(acc[i][f][r] + bv);
+                oa[r] = Lp<T>::from_f(acc[i][2 * pa][r] + bva[r]);
+                oa[4 + r] = Lp<T>::from_f(acc[i][2 * pa + 1][r] + bva[4 + r]);
+                ob[r] = Lp<T>::from_f(acc[i][2 * pb][r] + bvb[r]);
+                ob[4 + r] = Lp<T>::from_f(acc[i][2 * pb + 1][r] + bvb[4 + r]);
             }
-    }
-    __syncthreads();
-    T *C = reinterpret_cast<T *>(a.C);
-#pragma unroll 4
-    for (int v = tid; v < 256 * 32; v += SG_THREADS) {
-        const int rl = v >> 5, cv = v & 31;
-        const int row = tm * 256 + rl;
-        int col;
-        bool ok;
-        if (a.gate_h) {
-            const int unit = tn * 64 + (cv & 7) * 8;
-            col = (cv >> 3) * a.gate_h + unit;
-            ok = unit < a.gate_h;
-        } else {
-            col = tn * 256 + cv * 8;
-            ok = col < a.N;
+            const u32x4 va = *reinterpret_cast<const u32x4 *>(oa), vb = *reinterpret_cast<const u32x4 *>(ob);
+            u32x4 got;
+#pragma unroll
+            for (int d = 0; d < 4; ++d)
+                got[d] = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(lo ? vb[d] : va[d]), 0x128, 0xf, 0xf, false);   // row_ror:8
+            // rows 0 .. 7: own group pa (m < 8) | the partner's group pb; rows 8 .. 15: the partner's pa | own pb
+            const int c = lo ? col : colb;
+            const int r0 = row0 + i * 16;
+            if (ok && r0 < a.M) *reinterpret_cast<u32x4 *>(&C[(int64_t)r0 * a.ldc + c]) = lo ? va : got;
+            if (ok && r0 + 8 < a.M) *reinterpret_cast<u32x4 *>(&C[(int64_t)(r0 + 8) * a.ldc + c]) = lo ? got : vb;
         }
-        if (row >= a.M || !ok) continue;
-        *reinterpret_cast<u32x4 *>(&C[(int64_t)row * a.ldc + col]) = *reinterpret_cast<const u32x4 *>(&stage[rl * SG_OLD + cv * 8]);
+    };
+    if (a.gate_h) {
+        // B tile j, row 32 g + r is column g H + 32 j + r: the neighbour of (tile 0, block b) is (tile 1, block b)
+        const int unit = 2 * tn * 32 + g8;
+        const bool oka = unit < a.gate_h, okb = unit + 32 < a.gate_h;
+        store_pair(std::integral_constant<int, 0>{}, std::integral_constant<int, 4>{}, unit, unit + 32, oka, okb);
+        store_pair(std::integral_constant<int, 1>{}, std::integral_constant<int, 5>{}, a.gate_h + unit, a.gate_h + unit + 32, oka, okb);
+        store_pair(std::integral_constant<int, 2>{}, std::integral_constant<int, 6>{}, 2 * a.gate_h + unit, 2 * a.gate_h + unit + 32, oka, okb);
+        store_pair(std::integral_constant<int, 3>{}, std::integral_constant<int, 7>{}, 3 * a.gate_h + unit, 3 * a.gate_h + unit + 32, oka, okb);
+    } else {
+        const int col = tn * 256 + g8;
+        store_pair(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{}, col, col + 32, col < a.N, col + 32 < a.N);
+        store_pair(std::integral_constant<int, 2>{}, std::integral_constant<int, 3>{}, col + 64, col + 96, col + 64 < a.N, col + 96 < a.N);
+        store_pair(std::integral_constant<int, 4>{}, std::integral_constant<int, 5>{}, col + 128, col + 160, col + 128 < a.N, col + 160 < a.N);
+        store_pair(std::integral_constant<int, 6>{}, std::integral_constant<int, 7>{}, col + 192, col + 224, col + 192 < a.N, col + 224 < a.N);
     }
 }
 
@@ -276,6 +304,8 @@ struct StreamTnArgs {
     int64_t ldc;
     int M, N, K;
     int tiles_m, tiles_n;
+    float *ws;                // split K: fp32 partial results [split][M][N] (the caller adds them up), else null
+    int split_steps;          // 32-row steps per split (K / 32 without split K)
 };
 
 typedef short sg_v4s __attribute__((ext_vector_type(4)));
@@ -310,7 +340,8 @@ __global__ __launch_bounds__(SG_THREADS) void gemm_stream_tn_kernel(StreamTnArgs
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int total = a.tiles_m * a.tiles_n;
-    int lin = blockIdx.x;
+    const int split = (int)blockIdx.x / total;            // split K: the workgroups of one split follow each other
+    int lin = (int)blockIdx.x - split * total;
     if (total % 8 == 0) lin = (lin % 8) * (total / 8) + lin / 8;
     const int band = 8 * a.tiles_n;
     const int b0 = (lin / band) * 8;
@@ -337,10 +368,11 @@ __global__ __launch_bounds__(SG_THREADS) void gemm_stream_tn_kernel(StreamTnArgs
     const unsigned lsrc_pk = (unsigned)(((lane & 32) + ((lane & 31) ^ ((lane >> 5) << 2))) * 16);
     const unsigned lsrc0 = PK ? lsrc_pk : chunk_off(lpos ^ ((((lrow >> 1) & 1) | 0) << 1));   // pieces with p % 4 even
     const unsigned lsrc1 = PK ? lsrc_pk : chunk_off(lpos ^ ((((lrow >> 1) & 1) | 2) << 1));   // pieces with p % 4 odd
-    const char *src0 = reinterpret_cast<const char *>(Op + (int64_t)blkc0 * 4096);            // + block row * ncb * 8 KB + half * 4 KB
-    const char *src1 = reinterpret_cast<const char *>(Op + (int64_t)blkc1 * 4096);
-    unsigned char *my_pieces = ring + wave * 8192;
     const int64_t row_bytes = (int64_t)ncb * 8192;                                             // one block row of the operand
+    const int64_t split_off = (int64_t)split * (a.split_steps >> 1) * row_bytes;               // (a split is whole block rows)
+    const char *src0 = reinterpret_cast<const char *>(Op + (int64_t)blkc0 * 4096) + split_off;  // + block row * ncb * 8 KB + half * 4 KB
+    const char *src1 = reinterpret_cast<const char *>(Op + (int64_t)blkc1 * 4096) + split_off;
+    unsigned char *my_pieces = ring + wave * 8192;
     // pieces q = 0 .. 7 of step c into stage st
     auto dma = [&](int c, int st, int q) {
         const char *s = (q < 4 ? src0 : src1) + (int64_t)(c >> 1) * row_bytes + (c & 1) * (PK ? 1024 : 4096);
@@ -385,7 +417,7 @@ __global__ __launch_bounds__(SG_THREADS) void gemm_stream_tn_kernel(StreamTnArgs
     // Step c multiplies the 32 contraction rows of stage c % 4 and requests step c + 3 into the stage step c - 1
     // occupied; it ends with [wait until at most its own 8 requests are outstanding] [barrier: step c + 2 is complete
     // in LDS, everybody is done with step c].  Requests past the last step are clamped to it (never read).
-    const int last = a.K / 32 - 1;
+    const int last = a.split_steps - 1;
 #pragma unroll
     for (int q = 0; q < 8; ++q) dma(0, 0, q);
 #pragma unroll
@@ -424,9 +456,36 @@ __global__ __launch_bounds__(SG_THREADS) void gemm_stream_tn_kernel(StreamTnArgs
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // the last MFMAs leave the pipe before their accumulators are read
     __syncthreads();
 
+    const int col_l = lane & 15, rgrp = (lane >> 4) * 4;
+    if (a.ws) {
+        // split K: the fp32 partial tile, 64 rows at a time through LDS (whole kilobyte row segments)
+        constexpr int PITCH = 256 + 4;
+        float *stage32 = reinterpret_cast<float *>(ring);
+        float *W = a.ws + (int64_t)split * a.M * a.N;
+#pragma unroll
+        for (int slab = 0; slab < 4; ++slab) {               // rows 64 slab .. 64 slab + 63 of the tile
+            if (wm == (slab >> 1)) {
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4)
+#pragma unroll
+                    for (int jb = 0; jb < 8; ++jb)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            stage32[(i4 * 16 + rgrp + r) * PITCH + wn * 128 + jb * 16 + col_l] = acc[(slab & 1) * 4 + i4][jb][r];
+            }
+            __syncthreads();
+            for (int v = tid; v < 64 * 64; v += SG_THREADS) {
+                const int rl = v >> 6, cv = v & 63;
+                const int row = tm * 256 + slab * 64 + rl, col = tn * 256 + cv * 4;
+                if (row < a.M && col < a.N)
+                    *reinterpret_cast<v4f *>(&W[(int64_t)row * a.N + col]) = *reinterpret_cast<const v4f *>(&stage32[rl * PITCH + cv * 4]);
+            }
+            __syncthreads();
+        }
+        return;
+    }
     // 16-bit result through LDS, written as whole 512-byte row segments
     T *stage = reinterpret_cast<T *>(ring);
-    const int col_l = lane & 15, rgrp = (lane >> 4) * 4;
 #pragma unroll
     for (int ia = 0; ia < 8; ++ia)
 #pragma unroll
@@ -486,10 +545,12 @@ int gemm_stream(int dtype, const StreamGemmArgs &g, hipStream_t stream) {
 
 bool gemm_stream_tn_supported(int dtype, const BlockedGemmArgs &g) {
     if (dtype == LSTM_DTYPE_FP32) return false;
-    if (!g.A.trans || !g.B.trans || !g.out_lp || g.accumulate || g.bias || g.batch > 1 || g.splits > 1) return false;
+    if (!g.A.trans || !g.B.trans || !g.out_lp || g.accumulate || g.bias || g.batch > 1) return false;
     if (g.A.packed != g.B.packed) return false;
     if (g.M <= 0 || g.N <= 0 || g.K < 32 * SG_GRP || g.K % (32 * SG_GRP) != 0) return false;
     if (g.M % 8 != 0 || g.N % 8 != 0 || g.ldc % 8 != 0) return false;
+    // split K: equal splits of whole groups of steps, partial sums in the caller's fp32 workspace
+    if (g.splits > 1 && (!g.splitk_ws || (uintptr_t)g.splitk_ws % 16 || g.K % (32 * SG_GRP * g.splits) != 0)) return false;
     // 16-byte stores into C (a worker's row of a gradient matrix may start at any element: then the other kernel)
     if (!g.A.ptr || !g.B.ptr || !g.C || (uintptr_t)g.A.ptr % 16 || (uintptr_t)g.B.ptr % 16 || (uintptr_t)g.C % 16) return false;
     return g.A.ncb >= (g.M + 63) / 64 && g.B.ncb >= (g.N + 63) / 64;
@@ -505,10 +566,13 @@ int gemm_stream_tn(int dtype, const BlockedGemmArgs &g, hipStream_t stream) {
     a.A = (const uint16_t *)g.A.ptr; a.B = (const uint16_t *)g.B.ptr; a.ncb_a = g.A.ncb; a.ncb_b = g.B.ncb;
     a.C = g.C; a.ldc = g.ldc; a.M = g.M; a.N = g.N; a.K = g.K;
     a.tiles_m = (g.M + 255) / 256; a.tiles_n = (g.N + 255) / 256;
+    const int splits = g.splits > 1 ? g.splits : 1;
+    a.ws = splits > 1 ? g.splitk_ws : nullptr;
+    a.split_steps = g.K / 32 / splits;
     const double flops = 2.0 * g.M * g.N * g.K;
     const double bytes = 2.0 * ((double)g.M * g.K + (double)g.N * g.K + (double)g.M * g.N);
     KernelTimer timer(g.kclass, stream, flops, bytes);
-    const dim3 grid(a.tiles_m * a.tiles_n);
+    const dim3 grid(a.tiles_m * a.tiles_n * splits);
     if (g.A.packed) {
         if (dtype == LSTM_DTYPE_FP16) hipLaunchKernelGGL((gemm_stream_tn_kernel<_Float16, true>), grid, dim3(SG_THREADS), 0, stream, a);
         else hipLaunchKernelGGL((gemm_stream_tn_kernel<bf16_t, true>), grid, dim3(SG_THREADS), 0, stream, a);
@@ -517,6 +581,7 @@ int gemm_stream_tn(int dtype, const BlockedGemmArgs &g, hipStream_t stream) {
         else hipLaunchKernelGGL((gemm_stream_tn_kernel<bf16_t, false>), grid, dim3(SG_THREADS), 0, stream, a);
     }
     LSTM_LAUNCH_CHECK();
+    if (splits > 1) return splitk_reduce(dtype, g.splitk_ws, splits, g.M, g.N, g.C, g.ldc, stream);
     return LSTM_OK;
 }
 

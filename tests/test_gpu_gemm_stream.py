@@ -135,3 +135,34 @@ def test_gemm_stream_tn_on_fragment_order_blocks(dtype, M, N, K):
     err = (got - ref).abs().max().item()
     scale = ref.abs().max().item()
     assert err <= tol * scale, f"max error {err:.3e} against scale {scale:.3e}"
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+@pytest.mark.parametrize("layout", [5, 6])
+@pytest.mark.parametrize("M,N,K,splits", [(512, 256, 1024, 4), (768, 320, 768, 2), (2048, 512, 8192, 4)])
+def test_gemm_stream_tn_split_k(dtype, layout, M, N, K, splits):
+    """A narrow result (few tiles) with the contraction cut into equal splits: fp32 partial tiles in the caller's
+    workspace, added up in split order."""
+    code, tdt, tol = DT[dtype]
+    g = torch.Generator().manual_seed(7 * M + N + K + splits)
+    A = (torch.randn(K, M, generator=g) * 0.5).to(tdt)
+    B = (torch.randn(K, N, generator=g) * 0.5).to(tdt)
+    ref = A.float().T @ B.float()
+    dev = torch.device("cuda:0")
+    C = torch.full((M, N), float("nan"), dtype=tdt, device=dev)
+    ws = torch.full((splits, M, N), float("nan"), dtype=torch.float32, device=dev)
+
+    def blocked(x):
+        r, c = x.shape
+        out = torch.empty(((r + 63) // 64) * ((c + 63) // 64) * 4096, dtype=tdt, device=dev)
+        hip.lstm_debug_pack_blocked(code, x.to(dev).contiguous(), r, c, out)
+        return out
+
+    form = blocked if layout == 5 else (lambda x: pack_tiles(x, 64).to(dev))
+    hip.lstm_debug_gemm(code, layout, M, N, K, form(A), form(B), C, ws, splits)
+    torch.cuda.synchronize()
+    got = C.float().cpu()
+    assert torch.isfinite(got).all()
+    err = (got - ref).abs().max().item()
+    scale = ref.abs().max().item()
+    assert err <= tol * scale, f"max error {err:.3e} against scale {scale:.3e}"
