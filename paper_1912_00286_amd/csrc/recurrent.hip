@@ -1327,6 +1327,15 @@ __global__ __launch_bounds__(256) void lstm_step_backward_fused_kernel(FusedStep
 template <typename T>
 __device__ __forceinline__ void pack_u_forward_block(const T *U, T *Upk, int H, int nkc, int kc, int hb, int K) {
     T *dst = Upk + ((int64_t)hb * nkc + kc) * B_CHUNK;
+    if (hb * 32 + 32 <= H && kc * 64 + 64 <= K && K % 8 == 0 && ((uintptr_t)U | (uintptr_t)Upk) % 16 == 0) {
+        // whole chunk inside the matrix: 16-byte slots (8 consecutive k of one row), written in slot order
+        for (int s = threadIdx.x; s < B_CHUNK / 8; s += 256) {
+            const int r = s & 31, half = (s >> 5) & 1, g = (s >> 6) & (NBLK - 1), ks = s >> 8;
+            const T *src = U + ((int64_t)g * H + hb * 32 + r) * K + kc * 64 + ks * 16 + half * 8;
+            *reinterpret_cast<u32x4 *>(dst + s * 8) = *reinterpret_cast<const u32x4 *>(src);
+        }
+        return;
+    }
     for (int v = threadIdx.x; v < B_CHUNK; v += 256) {
         const int row = v >> 6, kk = v & 63;
         const int g = row >> 5, r = row & 31;
@@ -1338,19 +1347,47 @@ __device__ __forceinline__ void pack_u_forward_block(const T *U, T *Upk, int H, 
 template <typename T>
 __device__ __forceinline__ void pack_u_backward_block(const T *U, T *UTpk, int H, int nkc, int kc, int q, int nt, T (*tile)[TN + 2]) {
     // read U rows (k) x columns (units) coalesced along units, write transposed
+    T *dst = UTpk + (((int64_t)nt * 4 + q) * nkc + kc) * B_CHUNK;
+    if (kc * 64 + 64 <= H && nt * TN + TN <= H && H % 8 == 0 && ((uintptr_t)U | (uintptr_t)UTpk) % 16 == 0) {
+        // whole chunk inside the matrix: 16 bytes (8 units of one k) per load, 16-byte slots (8 k of one unit) per store
+        for (int v = threadIdx.x; v < 64 * TN / 8; v += 256) {
+            const int kk = v / (TN / 8), r8 = (v % (TN / 8)) * 8;
+            const u32x4 raw = *reinterpret_cast<const u32x4 *>(U + ((int64_t)q * H + kc * 64 + kk) * H + nt * TN + r8);
+            unsigned *t32 = reinterpret_cast<unsigned *>(&tile[kk][r8]);       // rows of the tile are 4-byte aligned
+            t32[0] = raw[0]; t32[1] = raw[1]; t32[2] = raw[2]; t32[3] = raw[3];
+        }
+        __syncthreads();
+        for (int s = threadIdx.x; s < B_CHUNK / 8; s += 256) {
+            const int r = s & 31, half = (s >> 5) & 1, blk = (s >> 6) & (NBLK - 1), ks = s >> 8;
+            const int row = blk * 32 + r, kk0 = ks * 16 + half * 8;
+            __attribute__((aligned(16))) T o[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) o[j] = tile[kk0 + j][row];
+            *reinterpret_cast<u32x4 *>(dst + s * 8) = *reinterpret_cast<const u32x4 *>(o);
+        }
+        return;
+    }
     for (int v = threadIdx.x; v < 64 * TN; v += 256) {
         const int kk = v / TN, r = v % TN;
         const int k = kc * 64 + kk, unit = nt * TN + r;
         tile[kk][r] = (k < H && unit < H) ? U[((int64_t)q * H + k) * H + unit] : Lp<T>::from_f(0.0f);
     }
     __syncthreads();
-    T *dst = UTpk + (((int64_t)nt * 4 + q) * nkc + kc) * B_CHUNK;
     for (int v = threadIdx.x; v < B_CHUNK; v += 256) dst[frag_offset(v >> 6, v & 63, NBLK)] = tile[v & 63][v >> 6];
 }
 // chunk (mt, kc) of hpk, row, column kk = h[mt*64 + row][kc*64 + kk] (null h = 0), zero outside; h is [B, H]
 template <typename T>
 __device__ __forceinline__ void pack_rows_block(const T *h, T *hpk, int B, int H, int nkc, int kc, int mt) {
     T *dst = hpk + ((int64_t)mt * nkc + kc) * A_CHUNK;
+    if (h && mt * 64 + 64 <= B && kc * 64 + 64 <= H && H % 8 == 0 && ((uintptr_t)h | (uintptr_t)hpk) % 16 == 0) {
+        // whole chunk inside the matrix: 16-byte slots (8 consecutive k of one row), written in slot order
+        for (int s = threadIdx.x; s < A_CHUNK / 8; s += 256) {
+            const int r = s & 31, half = (s >> 5) & 1, blk = (s >> 6) & 1, ks = s >> 7;
+            const T *src = h + (int64_t)(mt * 64 + blk * 32 + r) * H + kc * 64 + ks * 16 + half * 8;
+            *reinterpret_cast<u32x4 *>(dst + s * 8) = *reinterpret_cast<const u32x4 *>(src);
+        }
+        return;
+    }
     for (int v = threadIdx.x; v < A_CHUNK; v += 256) {
         const int row = mt * 64 + (v >> 6), k = kc * 64 + (v & 63);
         dst[frag_offset(v >> 6, v & 63, 2)] = (h && row < B && k < H) ? h[(int64_t)row * H + k] : Lp<T>::from_f(0.0f);
