@@ -249,7 +249,12 @@ int make_plan(const lstm_config *c, Plan &p) {
         p.s_fcwT = take(1, (size_t)p.F * p.H * p.es);
     }
     const int colw = (p.G > p.H ? p.G : p.H) > p.F ? (p.G > p.H ? p.G : p.H) : p.F;
-    p.s_colpart = take(1, (size_t)colsum_chunks((int)(TB / p.W)) * p.W * colw * 4);
+    {
+        // partial column sums: the column-sum kernels' chunks, or the row groups of the one-launch backward recurrence
+        size_t parts = (size_t)colsum_chunks((int)(TB / p.W)) * p.W;
+        if (parts < (size_t)rows_backward_groups(p.B)) parts = (size_t)rows_backward_groups(p.B);
+        p.s_colpart = take(1, parts * colw * 4);
+    }
     p.s_dE32 = s; if (p.V > 0) take(1, (size_t)p.V * p.D * 4);
     if (p.dtype != LSTM_DTYPE_FP32) {
         // packed operands of the fused recurrent kernels
@@ -993,11 +998,14 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
         char *dablk = (p.blk && !pk_only) ? at(scratch, p.wb ? p.s_wb_dablk[l] : p.s_dablk) : nullptr;
         const bool fused_step = fused && !p.wb && step_backward_fused_supported(p.dtype, p.B, p.H) && (dA_rm || dablk);
         const bool rows_bwd = fused && !p.wb && rows_backward_supported(p.dtype, p.B, p.H) && (dA_rm || dablk);
+        // ... and adds up the bias gradient's parts on the way (each worker's rows are whole groups of 32)
+        const bool rows_bias = rows_bwd && !dA_rm && (p.W == 1 || p.Bw % 32 == 0);
         if (rows_bwd) {
             // every workgroup walks its 32 rows back through all T steps: one launch for the layer
             RowsBackward r{};
             r.UTpk = utpk; r.dh_above = dh_above; r.gates = gates; r.cs = cs;
             r.dA = dA_rm ? dA : nullptr; r.dAblk = dablk;
+            r.bias_partial = rows_bias ? colpart : nullptr;
             r.slot_blk = (int64_t)(p.B / 64) * p.g_ncb * 4096; r.blk_ncb = p.g_ncb;
             LSTM_TRY(rows_backward(p.dtype, r, p.T, p.B, p.H, s));
         }
@@ -1134,6 +1142,7 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             LSTM_TRY(gemm_nt(p.dtype, u, s));
         }
         if (dA_rm) LSTM_TRY(colsum(p.dtype, dA, p.G, TB / p.W, p.G, nullptr, nullptr, colpart, grd + p.off_b[l] * es, s, p.W, p.Bw, p.P));
+        else if (rows_bias) LSTM_TRY(colsum_finish(p.dtype, colpart, p.W == 1 ? rows_backward_groups(p.B) : p.Bw / 32, p.G, grd + p.off_b[l] * es, s, p.W, p.P));
         else if (pk_only) LSTM_TRY(colsum_blocked(p.dtype, at(scratch, p.s_lag_daseq[l]), p.g_ncb, TB, p.G, colpart, grd + p.off_b[l] * es, s, 1, 0, 0, 1));
         else LSTM_TRY(colsum_blocked(p.dtype, dablk, p.g_ncb, TB / p.W, p.G, colpart, grd + p.off_b[l] * es, s, p.W, p.Bw, p.P));
         cur ^= 1;

@@ -46,6 +46,8 @@ int colsum(int dtype, const void *in, int64_t ld, int R, int C, const float *row
 // repeat every workers * seg_rows rows; worker w's sums go to out_lp + w * out_stride.
 // packed = 1: every 64x64 block holds its elements in MFMA-fragment order (packed.h, two 32-row blocks).
 int colsum_blocked_chunks(int R);
+// out_lp[w * out_stride + c] = sum over k < chunks of partial[(w * chunks + k) * C + c], w < workers (16-bit types)
+int colsum_finish(int dtype, const float *partial, int chunks, int C, void *out_lp, hipStream_t s, int workers, int64_t out_stride);
 int colsum_blocked(int dtype, const void *blk, int ncb, int R, int C, float *partial, void *out_lp, hipStream_t s, int workers = 1,
                    int seg_rows = 0, int64_t out_stride = 0, int packed = 0);
 
@@ -126,7 +128,11 @@ struct RowsBackward {
     void *dAblk;               // blocked out (slot_blk elements per time step), or null
     int64_t slot_blk;
     int blk_ncb;
+    float *bias_partial;       // out or null: [rows_backward_groups(B)][4H] column sums of dA (fp32, before its rounding to
+                               // 16 bits) over all T steps and the 32 rows of group i = rows 32 i .. 32 i + 31: the bias
+                               // gradient's parts
 };
+int rows_backward_groups(int B);
 bool rows_backward_supported(int dtype, int B, int H);
 int rows_backward(int dtype, const RowsBackward &x, int T, int B, int H, hipStream_t s);
 bool rows_forward_supported(int dtype, int B, int H, int in_width);

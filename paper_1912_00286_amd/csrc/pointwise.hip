@@ -585,6 +585,21 @@ int colsum_blocked(int dtype, const void *blk, int ncb, int R, int C, float *par
     return LSTM_OK;
 }
 
+int colsum_finish(int dtype, const float *partial, int chunks, int C, void *out_lp, hipStream_t s, int workers, int64_t out_stride) {
+    KernelTimer timer(KC_AUX, s, 0.0, 0.0);
+    if (C <= 0) return LSTM_OK;
+    if (dtype == LSTM_DTYPE_FP32 || chunks < 1 || workers < 1 || workers > 65535 || !partial || !out_lp) {
+        set_error("colsum_finish: unsupported (dtype %d, %d chunks, %d workers)", dtype, chunks, workers);
+        return LSTM_ERR_UNSUPPORTED;
+    }
+    LSTM_DISPATCH(dtype, T, {
+        hipLaunchKernelGGL(colsum_final_kernel<T>, dim3((C + 255) / 256, workers), dim3(256), 0, s, partial, chunks, C,
+                           (const float *)nullptr, (T *)out_lp, out_stride);
+    });
+    LSTM_LAUNCH_CHECK();
+    return LSTM_OK;
+}
+
 int head_loss_blocks(int rows) { return rows <= 0 ? 1 : (rows + 3) / 4; }
 
 int head_forward(int dtype, int head, const void *h_top, const void *w, const void *b, const float *targets, int rows,

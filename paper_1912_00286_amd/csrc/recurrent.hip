@@ -546,6 +546,7 @@ struct RowsBwdArgs {
     void *dA;              // lp [T][B,4H] row-major, or null
     void *dAblk;           // dA in 64x64 blocks, slot_blk elements per time step, or null
     int64_t slot_blk;
+    float *bias_partial;   // [gridDim.x][4H] out or null: column sums of this workgroup's dA rows over all steps
     int blk_ncb, T, B, H, nkc;
 };
 template <typename T>
@@ -554,13 +555,25 @@ __global__ __launch_bounds__(512) void lstm_rows_backward_kernel(RowsBwdArgs a) 
     constexpr int SLD = 36;                            // floats per row of a staging tile
     __shared__ __attribute__((aligned(16))) uint16_t dabuf[16 * HCH];      // [gate][nkc <= 4] chunks
     __shared__ __attribute__((aligned(16))) float stage[8][32 * SLD];
+    // the cell-state gradient of a lane's 2 x 8 units: private, but kept in LDS (four 16-byte slots per lane) so that
+    // the registers can hold the bias gradient's running sums instead
+    __shared__ __attribute__((aligned(16))) v4f dcl[4][512];
     const int tid = threadIdx.x, lane = tid & 63;
     const int hb = __builtin_amdgcn_readfirstlane(tid >> 6);      // wavefront = block of 32 units
     const int mt = blockIdx.x >> 1, mb = blockIdx.x & 1;
     const int r0 = mt * TM + mb * 32;
-    if (r0 >= a.B) return;
+    if (r0 >= a.B) {                                   // (an odd group past the last row: its sums are zero)
+        if (a.bias_partial)
+            for (int c = tid; c < 4 * a.H; c += 512) a.bias_partial[(int64_t)blockIdx.x * 4 * a.H + c] = 0.0f;
+        return;
+    }
     const int H = a.H, G = 4 * a.H, n_hb = (H + 31) / 32;
     const int nq = 4 * n_hb;                           // half chunks of the contraction: gate = q % 4, half chunk q / 4
+    float bsum[4][8];                                  // bias gradient: this lane's units, summed over its rows and all steps
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bsum[g][e] = 0.0f;
     for (int v = tid; v < 16 * 256; v += 512) reinterpret_cast<u32x4 *>(dabuf)[v] = u32x4{0u, 0u, 0u, 0u};   // padding stays zero
     const bool active = hb < n_hb;                     // uniform over the wavefront
     const int col = lane & 31, rsub = (lane >> 5) * 4;
@@ -568,11 +581,8 @@ __global__ __launch_bounds__(512) void lstm_rows_backward_kernel(RowsBwdArgs a) 
     const int j8 = hb * 32 + igrp;
     const bool units8 = active && j8 < H;              // H % 8 == 0: a group of 8 is inside or outside
     const int kc8 = j8 >> 6, kk8 = j8 & 63;
-    float dc[2][8];
 #pragma unroll
-    for (int k = 0; k < 2; ++k)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) dc[k][e] = 0.0f;
+    for (int k = 0; k < 4; ++k) dcl[k][tid] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
     const int hbc = min(hb, n_hb - 1);
     // B fragments of this wavefront: chunk (nt, gate, c), k-step ks, unit block hbc % 4
     const u32x4 *UT = reinterpret_cast<const u32x4 *>(a.UTpk) + (int64_t)(hbc >> 2) * 4 * a.nkc * (B_CHUNK / 8) + (hbc & 3) * 64 + lane;
@@ -655,20 +665,24 @@ __global__ __launch_bounds__(512) void lstm_rows_backward_kernel(RowsBwdArgs a) 
                 *reinterpret_cast<u32x4 *>(ti) = vi[k]; *reinterpret_cast<u32x4 *>(tf) = vf[k]; *reinterpret_cast<u32x4 *>(tg) = vg[k];
                 *reinterpret_cast<u32x4 *>(to) = vo[k]; *reinterpret_cast<u32x4 *>(tct) = vct[k]; *reinterpret_cast<u32x4 *>(tcp) = vcp[k];
                 *reinterpret_cast<u32x4 *>(tdh) = vdh[k];
+                __attribute__((aligned(16))) float dck[8];
+                *reinterpret_cast<v4f *>(dck) = dcl[2 * k][tid];
+                *reinterpret_cast<v4f *>(dck + 4) = dcl[2 * k + 1][tid];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const float i = Lp<T>::to_f(ti[e]), f = Lp<T>::to_f(tf[e]), g = Lp<T>::to_f(tg[e]), o = Lp<T>::to_f(to[e]);
                     const float tc = tanhf_dev(Lp<T>::to_f(tct[e]));
                     const float dh = Lp<T>::to_f(tdh[e]) + rec[e];
                     const float d_o = dh * tc;
-                    const float dcv = dc[k][e] + dh * o * (1.0f - tc * tc);
+                    const float dcv = dck[e] + dh * o * (1.0f - tc * tc);
                     const float di = dcv * g, dg = dcv * i, df = dcv * Lp<T>::to_f(tcp[e]);
-                    dc[k][e] = dcv * f;
-                    o0[e] = Lp<T>::from_f(di * i * (1.0f - i));
-                    o1[e] = Lp<T>::from_f(df * f * (1.0f - f));
-                    o2[e] = Lp<T>::from_f(dg * (1.0f - g * g));
-                    o3[e] = Lp<T>::from_f(d_o * o * (1.0f - o));
+                    dck[e] = dcv * f;
+                    const float a0 = di * i * (1.0f - i), a1 = df * f * (1.0f - f), a2 = dg * (1.0f - g * g), a3 = d_o * o * (1.0f - o);
+                    o0[e] = Lp<T>::from_f(a0); o1[e] = Lp<T>::from_f(a1); o2[e] = Lp<T>::from_f(a2); o3[e] = Lp<T>::from_f(a3);
+                    bsum[0][e] += a0; bsum[1][e] += a1; bsum[2][e] += a2; bsum[3][e] += a3;      // (before the rounding to 16 bits)
                 }
+                dcl[2 * k][tid] = *reinterpret_cast<const v4f *>(dck);
+                dcl[2 * k + 1][tid] = *reinterpret_cast<const v4f *>(dck + 4);
                 // the next step's operand: 8 units of a row and gate are one 16-byte slot of the fragment order
                 u32x4 *slot = reinterpret_cast<u32x4 *>(dabuf) + (kc8 * 4 + (kk8 >> 4)) * 64 + ((kk8 >> 3) & 1) * 32 + rl;
                 const int gs = a.nkc * 256;                // 16-byte slots per gate
@@ -695,6 +709,26 @@ __global__ __launch_bounds__(512) void lstm_rows_backward_kernel(RowsBwdArgs a) 
             }
         }
         __syncthreads();                               // dA_t of every unit block is in LDS
+    }
+    if (a.bias_partial) {
+        // the sixteen lanes that share a group of 8 units (lane % 4) hold different rows: add them up
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float v = bsum[g][e];
+#pragma unroll
+                for (int off = 4; off < 64; off <<= 1) v += __shfl_xor(v, off, 64);
+                bsum[g][e] = v;
+            }
+        if (units8 && lane < 4) {
+            float *dst = a.bias_partial + (int64_t)blockIdx.x * G + j8;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                *reinterpret_cast<v4f *>(dst + g * H) = v4f{bsum[g][0], bsum[g][1], bsum[g][2], bsum[g][3]};
+                *reinterpret_cast<v4f *>(dst + g * H + 4) = v4f{bsum[g][4], bsum[g][5], bsum[g][6], bsum[g][7]};
+            }
+        }
     }
 }
 
@@ -1696,6 +1730,8 @@ int rows_forward(int dtype, const RowsForward &x, int in_width, int T, int B, in
 }
 
 // the whole BPTT recurrence of a layer in one launch (lstm_rows_backward_kernel): thousands of rows, H <= 256
+int rows_backward_groups(int B) { return 2 * ((B + TM - 1) / TM); }
+
 bool rows_backward_supported(int dtype, int B, int H) {
     if (dtype != LSTM_DTYPE_FP16 && dtype != LSTM_DTYPE_BF16) return false;
     const RecurrentDims d = recurrent_dims(B, H);
@@ -1704,13 +1740,15 @@ bool rows_backward_supported(int dtype, int B, int H) {
 
 int rows_backward(int dtype, const RowsBackward &x, int T, int B, int H, hipStream_t s) {
     const RecurrentDims d = recurrent_dims(B, H);
-    const uintptr_t all = (uintptr_t)x.UTpk | (uintptr_t)x.dh_above | (uintptr_t)x.gates | (uintptr_t)x.cs | (uintptr_t)x.dA | (uintptr_t)x.dAblk;
+    const uintptr_t all = (uintptr_t)x.UTpk | (uintptr_t)x.dh_above | (uintptr_t)x.gates | (uintptr_t)x.cs | (uintptr_t)x.dA | (uintptr_t)x.dAblk |
+                          (uintptr_t)x.bias_partial;
     if (!rows_backward_supported(dtype, B, H) || !x.UTpk || !x.dh_above || !x.gates || !x.cs || (!x.dA && !x.dAblk) || T < 1 || all % 16 != 0) {
         set_error("rows_backward: unsupported shape, null or misaligned operand (B=%d H=%d)", B, H);
         return LSTM_ERR_INVALID;
     }
     RowsBwdArgs a;
     a.UTpk = x.UTpk; a.dh_above = x.dh_above; a.gates = x.gates; a.cs = x.cs; a.dA = x.dA; a.dAblk = x.dAblk; a.slot_blk = x.slot_blk;
+    a.bias_partial = x.bias_partial;
     a.blk_ncb = x.blk_ncb; a.T = T; a.B = B; a.H = H; a.nkc = d.nkc;
     const double n = (double)B * H;
     // operands once: U per launch; per step the saved gates, c_t and the gradient from above read, dA written once per copy
