@@ -1123,7 +1123,20 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             if (p.W == 1 && gemm_stream_tn_supported(p.dtype, g)) return gemm_stream_tn(p.dtype, g, s);
             return gemm_blocked(p.dtype, g, s);
         };
-        if (w_blk) {
+        // several workers: dW and dU of a layer in one launch (they share dA, which then comes from memory once)
+        const bool wu_together = p.W > 1 && w_blk && u_blk && (p.G + 255) / 256 <= 8;
+        if (wu_together) {
+            BlockedGemmArgs g{};
+            g.A = BlockedOperand{dablk, p.g_ncb, 1, 0};
+            g.B = BlockedOperand{in_blk.ptr, in_blk.ncb, 1, 0};
+            g.C = w.C; g.ldc = w.ldc; g.out_lp = 1;
+            g.M = w.M; g.N = w.N; g.K = w.K / p.W;
+            g.B2 = BlockedOperand{at(reserve, p.r_hblk[l]), p.h_ncb, 1, 0};
+            g.C2 = u.C; g.ldc2 = u.ldc; g.N2 = u.N;
+            g.batch = p.W; g.seg_len = p.Bw / 64; g.seg_stride = p.B / 64; g.batch_c = p.P;
+            g.kclass = w.kclass;
+            LSTM_TRY(gemm_blocked(p.dtype, g, s));
+        } else if (w_blk) {
             LSTM_TRY(blocked_wgrad(w, in_blk));
         } else if (w_tn) {
             LSTM_TRY(gemm_tn(p.dtype, wt, s));
@@ -1132,7 +1145,9 @@ extern "C" int lstm_backward(const lstm_config *cfg, const void *params_lp, cons
             w.A = dAT; w.B = xT; w.lda = TB; w.ldb = TB;
             LSTM_TRY(gemm_nt(p.dtype, w, s));
         }
-        if (u_blk) {
+        if (wu_together) {
+            // (done above)
+        } else if (u_blk) {
             LSTM_TRY(blocked_wgrad(u, BlockedOperand{at(reserve, p.r_hblk[l]), p.h_ncb, 1, p.lag_pk ? 1 : 0}));
         } else if (u_tn) {
             LSTM_TRY(gemm_tn(p.dtype, ut, s));

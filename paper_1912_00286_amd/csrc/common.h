@@ -185,6 +185,13 @@ struct BlockedGemmArgs {
     // (t / seg_len) * seg_stride + t % seg_len + y * seg_len; results batch_c elements apart.
     int batch = 1, seg_len = 0, seg_stride = 0;
     int64_t batch_c = 0;
+    // batch > 1 only: a second product with the same A in the same launch, C2 [M, ldc2] = A^T B2 with N2 columns (same
+    // roles, batch layout and batch_c as B / C).  dW and dU of a layer share dA: issued together, the tiles of both
+    // run side by side on one XCD and dA comes from memory once.  B2.ptr null: none.
+    BlockedOperand B2{nullptr, 0, 1, 0};
+    void *C2 = nullptr;
+    int64_t ldc2 = 0;
+    int N2 = 0;
 };
 size_t blocked_elems(int rows, int cols);
 // dst (blocked, zero padded) = src (row-major [rows, cols], leading dimension ld)

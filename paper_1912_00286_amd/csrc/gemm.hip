@@ -37,6 +37,11 @@ struct KernArgs {
     //   (t / seg_len) * seg_stride + t % seg_len + y * seg_len      (seg_len = 0: plain, one GEMM)
     int seg_len, seg_stride;
     int64_t batch_c;    // elements between the results of consecutive batch entries
+    // second product of the launch (segmented form only): tile columns tiles_n1 .. take B2 / C2 / N2 / ldb2 / ldc2
+    const void *B2;
+    void *C2;
+    int N2, tiles_n1;
+    int64_t ldb2, ldc2;
 };
 
 // 8 consecutive lp elements of row `row` at column k; zero outside the operand.
@@ -313,6 +318,16 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a_in, 
             y = (int64_t)(slot / (int)gridDim.x) * 8 + (id & 7);
         }
         A += y * a.seg_len * a.lda * 4096;
+        if (a.B2) {
+            // two products share the launch: which one this tile column belongs to (same order as below: the tiles of
+            // an entry are walked tile column by tile column)
+            const int bh_ = min(8, tiles_m);
+            const int tn_ = (bx % (8 * tiles_n)) / bh_;
+            if (tn_ >= a.tiles_n1) {
+                B = reinterpret_cast<const T *>(a.B2);
+                a.C = a.C2; a.N = a.N2; a.ldb = a.ldb2; a.ldc = a.ldc2;
+            }
+        }
         B += y * a.seg_len * a.ldb * 4096;
         a.C = reinterpret_cast<char *>(a.C) + y * a.batch_c * (a.out_lp ? (int64_t)sizeof(T) : 4);
     }
@@ -333,7 +348,11 @@ __global__ __launch_bounds__(GTHREADS) void gemm_mfma_big_kernel(KernArgs a_in, 
     const int band = 8 * tiles_n;
     const int b0 = (lin / band) * 8;
     const int bh = min(8, tiles_m - b0);
-    const int tm = b0 + (lin % band) % bh, tn = (lin % band) / bh;
+    const int tm = b0 + (lin % band) % bh;
+    int tn = (lin % band) / bh;
+    if constexpr (SEG) {
+        if (a.B2 && tn >= a.tiles_n1) tn -= a.tiles_n1;   // (operands switched above)
+    }
     const int m0 = tm * GBM, n0 = tn * GBN;
     const int kbeg = blockIdx.z * a.k_chunk;
     const int kend = min(a.K, kbeg + a.k_chunk);
@@ -965,12 +984,28 @@ int launch_blocked(const BlockedGemmArgs &g, hipStream_t stream) {
     a.k_chunk = k_chunk;
     a.vec_ok = 1;
     a.vec_out = (g.out_lp && g.ldc % 8 == 0 && (uintptr_t)g.C % 16 == 0) ? 1 : 0;
-    const int tiles_m = (g.M + GBM - 1) / GBM, tiles_n = (g.N + GBN - 1) / GBN;
+    const int tiles_m = (g.M + GBM - 1) / GBM;
+    int tiles_n = (g.N + GBN - 1) / GBN;
     a.seg_len = g.batch > 1 ? g.seg_len : 0;
     a.seg_stride = g.seg_stride;
     a.batch_c = g.batch_c;
+    double flops = 2.0 * g.M * g.N * g.K, bytes = gemm_algorithmic_bytes<T>(g);
+    if (g.B2.ptr) {
+        // the second product of a segmented launch; the tile order below must keep an entry's tiles within one band
+        if (a.seg_len <= 0 || !g.A.trans || !g.B.trans || !g.B2.trans || g.B2.packed || !g.C2 || g.N2 <= 0 || splits > 1 || g.bias ||
+            tiles_m > 8) {
+            set_error("gemm_blocked: a second product needs the batched rows-are-K form without split K, at most %d rows", 8 * GBM);
+            return LSTM_ERR_UNSUPPORTED;
+        }
+        a.B2 = g.B2.ptr; a.C2 = g.C2; a.N2 = g.N2; a.ldb2 = g.B2.ncb; a.ldc2 = g.ldc2;
+        a.tiles_n1 = tiles_n;
+        tiles_n += (g.N2 + GBN - 1) / GBN;
+        if (!(g.ldc2 % 8 == 0 && (uintptr_t)g.C2 % 16 == 0)) a.vec_out = 0;
+        flops += 2.0 * g.M * g.N2 * g.K;
+        bytes += (double)g.N2 * g.K * sizeof(T) + (double)g.M * g.N2 * (g.out_lp ? sizeof(T) : 4.0);
+    }
     const dim3 grid(tiles_m * tiles_n, g.batch > 1 ? g.batch : 1, splits);
-    KernelTimer timer(g.kclass, stream, 2.0 * g.M * g.N * g.K, gemm_algorithmic_bytes<T>(g));
+    KernelTimer timer(g.kclass, stream, flops, bytes);
     if (!g.A.trans && !g.B.trans)
         hipLaunchKernelGGL((gemm_mfma_big_kernel<T, false, false, true, true>), grid, dim3(GTHREADS), 0, stream, a, tiles_m, tiles_n);
     else if (!g.A.trans && g.B.trans)
@@ -1031,7 +1066,8 @@ int gemm_blocked(int dtype, const BlockedGemmArgs &g, hipStream_t stream) {
     // operand extents in elements must fit the kernel's 32-bit offsets
     const int64_t ea = (g.A.trans ? kb : (int64_t)(g.M + 63) / 64) * g.A.ncb * 4096;
     const int64_t eb = (g.B.trans ? kb : (int64_t)(g.N + 63) / 64) * g.B.ncb * 4096;
-    if (ea >= (int64_t)1 << 31 || eb >= (int64_t)1 << 31) {
+    const int64_t eb2 = g.B2.ptr ? kb * g.B2.ncb * 4096 : 0;
+    if (ea >= (int64_t)1 << 31 || eb >= (int64_t)1 << 31 || eb2 >= (int64_t)1 << 31) {
         set_error("gemm_blocked: operand too large for 32-bit offsets");
         return LSTM_ERR_UNSUPPORTED;
     }
