@@ -92,6 +92,7 @@ STATE_CASES = [
     ("wide", 1, 40, 1024, 3, 128, "fp16"),
     ("wide_tiles_two_chunks", 2, 40, 1024, 40, 256, "fp16"),
     ("wide_tiles_64_rows_bf16", 2, 24, 1152, 3, 192, "bf16"),
+    ("wide_tiles_2048_packed_copies_only", 2, 256, 2048, 4, 256, "fp16"),
     ("rows2048", 2, 64, 200, 3, 2048, "fp16"),
     ("rows1024_h520", 1, 8, 520, 3, 1024, "fp16"),
     ("odd_sizes", 2, 5, 33, 4, 17, "fp16"),

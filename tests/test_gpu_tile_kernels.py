@@ -18,6 +18,8 @@ CASES = [
     ("four_layers_short_sequence", 4, 130, 1024, 5, 384, "bf16", wl.HEAD_STEP_BCE),
     ("two_layers_one_step", 2, 16, 1280, 1, 256, "fp16", wl.HEAD_STEP_MSE),
     ("width_2048_two_layers", 2, 64, 2048, 33, 256, "fp16", wl.HEAD_STEP_MSE),
+    # every tensor in packed form only, layer 0 included (input width a multiple of 256)
+    ("width_2048_packed_input", 2, 256, 2048, 8, 256, "bf16", wl.HEAD_STEP_BCE),
 ]
 
 

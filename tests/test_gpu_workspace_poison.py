@@ -30,6 +30,8 @@ CASES = [
     (_w("wide_h1032_ragged", 1, 8, 1032, 3, 100, "fp16"), False),
     (_w("wide_tiles_3layers", 3, 24, 1024, 36, 256, "fp16"), False),
     (_w("wide_tiles_h1280_b192", 2, 8, 1280, 5, 192, "bf16", wl.HEAD_LAST_BCE), False),
+    (_w("wide_tiles_h2048_packed_copies_only", 2, 256, 2048, 3, 256, "fp16"), False),
+    (_w("wide_tiles_h2048_embedding", 1, 0, 2048, 2, 256, "fp16", wl.HEAD_LAST_BCE, vocab=300, embed_dim=256), False),
     (_w("rows1024_h520", 2, 24, 520, 3, 1024, "fp16"), False),
     (_w("odd_sizes", 2, 5, 33, 4, 17, "fp16"), False),
     (_w("fp32_odd_sizes", 2, 5, 33, 4, 17, "fp32"), False),
