@@ -2022,7 +2022,11 @@ int gates_backward_wave(int dtype, const WaveGates *c, int n_cells, int blk_ncb,
     if (blocks > 2048) blocks = 2048;
     if (blocks < 1) blocks = 1;
     w.blk_ncb = blk_ncb; w.B = B; w.H = H; w.nkc = d.nkc; w.blocks_per_cell = blocks; w.n_part = n_part;
-    KernelTimer timer(KC_POINTWISE, s, 0.0, n_cells * (double)n * (4.0 * n_part + 8.0 + 15.0 * 2.0));
+    // per unit and cell: the fp32 partial sums and the cell gradient read, the cell gradient written, seven 16-bit values
+    // read, four gate gradients written once per copy that exists (packed always; row-major, blocked)
+    double copies = 0.0;
+    for (int i = 0; i < n_cells; ++i) copies += 1.0 + (c[i].dA ? 1.0 : 0.0) + (c[i].dAblk ? 1.0 : 0.0);
+    KernelTimer timer(KC_POINTWISE, s, 0.0, (double)n * (n_cells * (4.0 * n_part + 8.0 + 7.0 * 2.0) + copies * 4.0 * 2.0));
     if (vec) {
         LP_ONLY(dtype, T, hipLaunchKernelGGL((wave_gates_backward_kernel<T, 8>), dim3(blocks * n_cells), dim3(256), 0, s, w));
     } else {
