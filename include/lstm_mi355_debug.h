@@ -32,7 +32,8 @@ int lstm_timing_read(int32_t kernel_class, int64_t *launches, double *total_ms, 
  *   layout 1: C = A^T B, row-major A[K,M], B[K,N]   (16-bit types, M, N >= 192, multiples of 8)
  *   layout 2/3/4: operands in 64x64 blocks as written by lstm_debug_pack_blocked, with
  *                 (A rows, B rows) indexing (M, N) / (M, K) / (K, K)   (16-bit types, M, N >= 192)
- *   layout 5: as 4 on the second (K,K) kernel   (K a multiple of 128, splits <= 1)
+ *   layout 5: as 4 on the second (K,K) kernel   (K a multiple of 128; with splits > 1 the contraction is cut
+ *             into that many equal parts, K a multiple of 128 * splits)
  *   layout 6: as 5, every 64x64 block of both operands in the fragment order given below for a 64-row tile
  * splitk_ws: fp32 [splits, M, N] or NULL with splits <= 1. */
 int lstm_debug_gemm(int32_t dtype, int32_t layout, int32_t M, int32_t N, int32_t K, const void *A, const void *B, void *C,
