@@ -36,6 +36,8 @@ CASES = [
     (448, 1024, 256, 64, True, True),       # M not a multiple of the 256-row tile, gate-interleaved columns
     (2048, 2560, 1024, 256, True, True),    # H = 640: the last column tile is half empty
     (1024, 2048, 2048, 512, False, False),
+    (320, 328, 256, 64, False, True),       # N a multiple of 8 only: a lane pair of the result stores straddles the edge
+    (256, 384, 512, 128, True, True),       # H = 96: the second B tile of the last column tile is empty
 ]
 
 
