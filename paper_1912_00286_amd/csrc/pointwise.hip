@@ -222,6 +222,8 @@ __global__ __launch_bounds__(256) void colsum_blocked_partial_kernel(const T *bl
         if (c < C) partial[((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * C + c] = t;
     }
 }
+// (one-wavefront workgroups: a thread adds up a whole column of partial sums, so the columns should spread over as
+// many compute units as possible)
 template <typename T>
 __global__ void colsum_final_kernel(const float *partial, int chunks, int C, const float *scale_dev, T *out, int64_t out_stride) {
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
@@ -552,7 +554,7 @@ int colsum(int dtype, const void *in, int64_t ld, int R, int C, const float *row
                                    (const T *)in, ld, R, C, row_w, partial, rs);
         }
         if (!vec) hipLaunchKernelGGL(colsum_partial_kernel<T>, grid, dim3(256), 0, s, (const T *)in, ld, R, C, row_w, partial, rs);
-        hipLaunchKernelGGL(colsum_final_kernel<T>, dim3((C + 255) / 256, workers), dim3(256), 0, s, partial, chunks, C, scale_dev,
+        hipLaunchKernelGGL(colsum_final_kernel<T>, dim3((C + 63) / 64, workers), dim3(64), 0, s, partial, chunks, C, scale_dev,
                            (T *)out_lp, out_stride);
     });
     LSTM_LAUNCH_CHECK();
@@ -578,7 +580,7 @@ int colsum_blocked(int dtype, const void *blk, int ncb, int R, int C, float *par
         if constexpr (sizeof(T) == 2)
             hipLaunchKernelGGL(colsum_blocked_partial_kernel<T>, dim3((C + 63) / 64, chunks, workers), dim3(256), 0, s, (const T *)blk,
                                ncb, nrb, C, partial, seg, stride, packed);
-        hipLaunchKernelGGL(colsum_final_kernel<T>, dim3((C + 255) / 256, workers), dim3(256), 0, s, partial, chunks, C,
+        hipLaunchKernelGGL(colsum_final_kernel<T>, dim3((C + 63) / 64, workers), dim3(64), 0, s, partial, chunks, C,
                            (const float *)nullptr, (T *)out_lp, out_stride);
     });
     LSTM_LAUNCH_CHECK();
@@ -593,7 +595,7 @@ int colsum_finish(int dtype, const float *partial, int chunks, int C, void *out_
         return LSTM_ERR_UNSUPPORTED;
     }
     LSTM_DISPATCH(dtype, T, {
-        hipLaunchKernelGGL(colsum_final_kernel<T>, dim3((C + 255) / 256, workers), dim3(256), 0, s, partial, chunks, C,
+        hipLaunchKernelGGL(colsum_final_kernel<T>, dim3((C + 63) / 64, workers), dim3(64), 0, s, partial, chunks, C,
                            (const float *)nullptr, (T *)out_lp, out_stride);
     });
     LSTM_LAUNCH_CHECK();
