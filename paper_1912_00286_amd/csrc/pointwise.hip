@@ -228,8 +228,15 @@ template <typename T>
 __global__ void colsum_final_kernel(const float *partial, int chunks, int C, const float *scale_dev, T *out, int64_t out_stride) {
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= C) return;
-    float s = 0.0f;
-    for (int k = 0; k < chunks; ++k) s += partial[((int64_t)blockIdx.y * chunks + k) * C + c];
+    // four running sums, so that the loads of consecutive chunks do not wait for each other's additions
+    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+    const float *p = partial + (int64_t)blockIdx.y * chunks * C + c;
+    int k = 0;
+    for (; k + 4 <= chunks; k += 4) {
+        s0 += p[(int64_t)k * C]; s1 += p[(int64_t)(k + 1) * C]; s2 += p[(int64_t)(k + 2) * C]; s3 += p[(int64_t)(k + 3) * C];
+    }
+    for (; k < chunks; ++k) s0 += p[(int64_t)k * C];
+    float s = (s0 + s1) + (s2 + s3);
     if (scale_dev) s *= *scale_dev;
     out[blockIdx.y * out_stride + c] = Lp<T>::from_f(s);
 }

@@ -116,9 +116,16 @@ __device__ __forceinline__ void tile_mainloop(const uint16_t *A0, int64_t a_tile
         multiply(b, st);
         if (c + PF < nch) issueB(b, c + PF);
     };
+    // The waits count loads from the youngest backwards, so the requests of one chunk have to be issued together, in
+    // chunk order.  Between two barriers the steps below guarantee that; here, before the first barrier, the compiler
+    // would interleave the loads of the PF chunks as it likes (it did: the second A piece of chunk 0 was issued
+    // behind register loads of chunks 1 and 2, so the first step's wait did not cover it and a workgroup now and then
+    // multiplied 32 rows of stale LDS bytes).  A scheduling fence after every chunk keeps the order.
 #pragma unroll
-    for (int i = 0; i < PF; ++i)
+    for (int i = 0; i < PF; ++i) {
         if (i < nch) { issueA(i, i); issueB(breg[i], i); }
+        __builtin_amdgcn_sched_barrier(0);
+    }
     if constexpr (NCH > 0) {
 #pragma unroll
         for (int c = 0; c < NCH; ++c) step(c, breg[c % PF], c % NS, (c + PF) % NS);

@@ -54,3 +54,32 @@ def test_wide_layers_run_to_run_identical():
     b = pu.run_gpu_step(w)
     np.testing.assert_array_equal(a["grads"], b["grads"])
     np.testing.assert_array_equal(a["losses"], b["losses"])
+
+
+def test_wide_layers_identical_over_many_runs_with_refilled_workspaces():
+    """One 2048-wide layer, two time steps, thirty forward + backward passes on the same inputs with the scratch
+    buffer refilled before each (0xFF bytes and zeros in turn): every pass must give the first pass's gradients bit
+    for bit.  (The step kernels count their outstanding loads from the youngest backwards; a load issued out of its
+    chunk's turn before the first barrier once left a workgroup, now and then, multiplying LDS bytes that had not
+    arrived yet, and only back-to-back passes on refilled buffers showed it.)"""
+    import torch
+    import paper_1912_00286_amd as hip
+    w = wl.Workload("tile_repeat", 1, 256, 2048, 2, 256, "fp16", wl.HEAD_LAST_BCE, loss_scale=1024.0, target_p=0.4,
+                    data_seed=11, weight_seed=12)
+    master0, xs, ys = pu.inputs_for(w)
+    ts = pu.make_step(w, master0)
+    dx, dy = pu.device_batches(w, xs, ys, ts.lp_dtype, ts.dev)
+    x, y = dx[0], dy[0]
+    first = None
+    for i in range(30):
+        ts.scratch.fill_(255 if i % 2 == 0 else 0)
+        ts.grads.view(torch.uint8).fill_(255)
+        hip.lstm_forward(ts.cfg, ts.params_lp, x, y, None, None, ts.reserve, ts.scratch, ts.losses[0:1])
+        hip.lstm_backward(ts.cfg, ts.params_lp, x, y, ts.reserve, ts.scratch, ts.loss_scale, ts.grads[0])
+        torch.cuda.synchronize()
+        g = ts.grads[0].cpu().view(torch.int16).numpy()
+        if first is None:
+            first = g
+            assert np.isfinite(ts.grads[0].float().cpu().numpy()).all()
+        else:
+            assert np.array_equal(g, first), f"pass {i} differs from the first pass in {int((g != first).sum())} elements"
