@@ -3,7 +3,8 @@ buffers are caller-owned and arrive uninitialised; here they (and the gradient o
 0xFF bytes, a NaN in every storage type, before the step, on one shape per kernel family (narrow layers,
 wide layers, thousands of rows per step with the step kernels projecting their own input, embeddings,
 the fp32 mode, stacked workers), widths whose padding to whole tiles is owned by no workgroup included.
-A kernel that reads a padding element it never wrote turns the loss or a gradient into NaN."""
+A kernel that reads a padding element it never wrote turns the loss or a gradient into NaN.  Each shape runs
+twice, first on zero-filled workspaces: the two passes must agree bit for bit."""
 import numpy as np
 import pytest
 
@@ -48,12 +49,20 @@ def test_results_do_not_depend_on_workspace_contents(case):
     master0, xs, ys = pu.inputs_for(w)
     ts = pu.make_step(w, master0, batched=batched)
     dx, dy = pu.device_batches(w, xs, ys, ts.lp_dtype, ts.dev)
+    # a first pass on zeroed workspaces, then the checked one on workspaces full of 0xFF bytes: the same bits
+    for buf in list(ts.reserves) + list(ts.scratches):
+        buf.fill_(0)
+    ts.grads.view(torch.uint8).fill_(255)
+    ts.forward_backward(dx, dy)
+    torch.cuda.synchronize()
+    on_zeros = ts.grads.clone()
     for buf in list(ts.reserves) + list(ts.scratches):
         buf.fill_(255)
     ts.grads.view(torch.uint8).fill_(255)
     ts.step(dx, dy, pu.lr_for(w, 0))
     torch.cuda.synchronize()
     assert int(ts.found_inf.item()) == 0, "a non-finite gradient came out of finite inputs"
+    assert torch.equal(ts.grads.view(torch.uint8), on_zeros.view(torch.uint8)), "the gradients depend on what the workspaces held"
     want = pu.run_oracle_step(w)
     losses = ts.losses.double().cpu().numpy()
     assert np.all(np.abs(losses - want["losses"]) <= pu.LOSS_RTOL * np.abs(want["losses"])), (losses, want["losses"])
