@@ -25,7 +25,7 @@ def _assert_same(a, b, what):
         assert torch.equal(a[k], b[k]), f"{what}: {k} differs between eager and graph replay"
 
 
-@pytest.mark.parametrize("name", ["jet", "text", "rows2048", "rows4096", "wide1024", "tile1024", "stacked"])
+@pytest.mark.parametrize("name", ["jet", "text", "rows2048", "rows4096", "wide1024", "tile1024", "tile2048", "stacked"])
 def test_graph_replay_matches_eager(name):
     import torch
     batched = False
@@ -42,6 +42,9 @@ def test_graph_replay_matches_eager(name):
     elif name == "tile1024":        # the benchmark's path: tile kernels on the lagged diagonals, chunked projection GEMMs
         w = wl.Workload(name, 3, 64, 1024, 40, 192, "fp16", wl.HEAD_STEP_MSE, target_kind="normal", loss_scale=256.0,
                         data_seed=59, weight_seed=60)
+    elif name == "tile2048":        # the same with every tensor in packed form only and layer 0 on the packed-operand GEMMs
+        w = wl.Workload(name, 2, 256, 2048, 34, 256, "fp16", wl.HEAD_STEP_MSE, target_kind="normal", loss_scale=256.0,
+                        data_seed=61, weight_seed=62)
     else:                           # several workers stacked into one call per direction
         w = wl.Workload(name, 2, 64, 200, 6, 128, "fp16", wl.HEAD_STEP_BCE, n_workers=4, loss_scale=1024.0, target_p=0.4,
                         data_seed=55, weight_seed=56)
